@@ -1,0 +1,21 @@
+"""fp64 CPU oracle for the hybrid attention of Hybrid Forcing (test infrastructure).
+
+This package is a checker, not a product path: only tests, the smoke check and the
+benchmark's cpu_baseline leg may import it. It shares no code with the HIP library.
+"""
+from .hybrid_attention import (  # noqa: F401
+    PHI_RELU,
+    PHI_ELU1,
+    phi,
+    rope_rotate,
+    state_zero,
+    state_absorb,
+    pool_blocks,
+    block_scores,
+    select_k,
+    select_blocks,
+    sparse_attention,
+    dense_attention,
+    history_readout,
+    hybrid_attention,
+)
