@@ -1,0 +1,145 @@
+/*
+ * hf.h — C ABI of the MI355X (gfx950) hybrid-attention library.
+ *
+ * One per-chunk hybrid attention of the Hybrid Forcing streaming video transformer
+ * (Sec. 3.2 of the paper): block-sparse softmax attention of the chunk's queries over
+ * the sliding-window KV cache (Eq. 4, 5), a linear-attention readout from a compact
+ * per-head state (Eq. 3), their sum (Eq. 6), and the absorption of tokens evicted from
+ * the window into that state (Eq. 2; the eviction step of the rolling-KV-cache
+ * inference algorithm in the supplement).
+ *
+ * Conventions shared by every call
+ * --------------------------------
+ *  - Every data pointer is a DEVICE pointer on the current HIP device unless it says
+ *    "host".  `cfg`, `bytes_out`, `k_out` are HOST pointers.
+ *  - The caller owns every buffer (inputs, outputs, state, workspace).  The library
+ *    allocates nothing on the device and keeps no global state except a thread-local
+ *    error string.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every call
+ *    only enqueues kernels on that stream: no call synchronises, none allocates.
+ *  - Tensors are contiguous, head-major [batch, heads, tokens, head_dim] with head_dim
+ *    innermost; dtype of Q, K, V, O is cfg->dtype (bf16 or fp32).  The linear state is
+ *    ALWAYS fp32.  Data pointers must be 16-byte aligned.
+ *  - Blocks are consecutive runs of block_q / block_kv tokens counted from token 0 of the
+ *    buffer; the last block may be short (it is pooled over its real length and only its
+ *    real keys take part).  T_m = ceil(n_q / block_q), T_n = ceil(n_kv / block_kv).
+ *  - The window buffer holds [older cached tokens ... | current chunk]; sink frames are
+ *    ordinary leading tokens.  There is no causal mask inside the window.
+ *  - Return value: HF_OK (0) or a negative HF_ERR_* code; on error nothing was enqueued
+ *    and hf_last_error() describes the problem.  No C++ exception crosses this boundary.
+ *
+ * State layout (fp32), for batch b and head h, with d = head_dim:
+ *     L[b][h][i][j]   i = key feature, j = value feature     B*H*d*d floats
+ *     z[b][h][i]      normaliser (the paper's H)             B*H*d floats, after all of L
+ */
+#ifndef HF_H_
+#define HF_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#if defined(__GNUC__)
+#define HF_API __attribute__((visibility("default")))
+#else
+#define HF_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { HF_BF16 = 0, HF_F32 = 1 };            /* hf_config.dtype */
+enum { HF_PHI_RELU = 0, HF_PHI_ELU1 = 1 };   /* hf_config.phi: max(x,0) | elu(x)+1 */
+
+enum {
+  HF_OK = 0,
+  HF_ERR_NULL = -1,       /* a required pointer is NULL */
+  HF_ERR_SHAPE = -2,      /* unsupported or inconsistent sizes */
+  HF_ERR_DTYPE = -3,      /* unknown dtype / phi */
+  HF_ERR_ALIGN = -4,      /* a data pointer is not 16-byte aligned */
+  HF_ERR_WORKSPACE = -5,  /* workspace missing or too small */
+  HF_ERR_HIP = -6         /* a kernel launch failed; text from the HIP runtime */
+};
+
+/* Problem statement of the paper's hybrid-attention algorithm: per-head Q, K, V in
+ * R^{N x d}, state L in R^{d x d} and H in R^{1 x d}, block sizes b_q, b_kv, sparse Top K. */
+typedef struct hf_config {
+  int32_t batch;          /* >= 1 */
+  int32_t heads;          /* >= 1 */
+  int32_t head_dim;       /* 64 or 128 */
+  int32_t dtype;          /* HF_BF16 | HF_F32: storage type of Q, K, V, O */
+  int32_t block_q;        /* b_q  >= 1 */
+  int32_t block_kv;       /* b_kv >= 1 */
+  float   keep_ratio;     /* in (0, 1]; 1.0 keeps every block (dense window attention) */
+  int32_t keep_k;         /* > 0 overrides keep_ratio; 0: k = clamp(ceil(keep_ratio*T_n - 1e-9), 1, T_n) */
+  int32_t phi;            /* HF_PHI_RELU (default) | HF_PHI_ELU1 */
+  float   eps;            /* added to the readout denominator (Eq. 3); e.g. 1e-6 */
+  float   z_scale;        /* multiplies phi(q).z at readout; 1.0 = plain sum normaliser */
+  float   softmax_scale;  /* 0 means 1/sqrt(head_dim) (Eq. 5) */
+} hf_config;
+
+/* Size in bytes of the linear state: batch*heads*(d*d + d)*4.  Host-only. */
+HF_API int hf_state_bytes(const hf_config* cfg, size_t* bytes_out);
+
+/* "Initialize Linear State cache" of the inference algorithm: L = 0, z = 0.
+ * Uses a fill kernel (not a memset node), so it is safe to capture in a HIP graph. */
+HF_API int hf_state_init(const hf_config* cfg, void* state, void* stream);
+
+/* Eq. 2, incremental form used at cache eviction: for every (b, h)
+ *     L += sum_t R_t(phi(k_t))^T v_t      z += sum_t phi(k_t)
+ * over the n_tokens evicted tokens K_ev, V_ev [B, H, n_tokens, d] (read-only).
+ * rope_cos / rope_sin: fp32 [n_tokens, d/2] per-token rotation of adjacent feature pairs
+ * (2p, 2p+1), shared by heads and batch, applied after phi to the L term only; both NULL =
+ * identity.  The state is updated in place (fp32 accumulation; concurrent calls on the same
+ * state from different streams are allowed only if the caller orders them). */
+HF_API int hf_absorb_evicted(const hf_config* cfg, void* state,
+                      const void* K_ev, const void* V_ev, int32_t n_tokens,
+                      const float* rope_cos, const float* rope_sin, void* stream);
+
+/* k of "sparse Top K" for a window of n_kv tokens (see keep_k / keep_ratio).  Host-only. */
+HF_API int hf_select_k(const hf_config* cfg, int32_t n_kv, int32_t* k_out);
+
+/* Bytes of scratch hf_block_select and hf_hybrid_attn_fwd need for these sizes.  Host-only. */
+HF_API int hf_workspace_bytes(const hf_config* cfg, int32_t n_q, int32_t n_kv, size_t* bytes_out);
+
+/* Eq. 4 and the Top-K mask: per (b, h) mean-pool Q and K_win per block,
+ * A[i][j] = mean(q_i) . mean(k_j) (raw dot product), and for each query-block row i keep
+ * the k largest A[i][:] (ties: lower j).  Row-wise softmax and the 1/sqrt(d) factor of the
+ * algorithm listing are monotone per row and do not change the kept set.
+ *   Q      [B, H, n_q, d], K_win [B, H, n_kv, d]                      read-only
+ *   block_idx   out int32 [B, H, T_m, k], ascending within a row
+ *   scores_or_null   out fp32 [B, H, T_m, T_n] raw scores, or NULL
+ *   workspace   >= hf_workspace_bytes(...) bytes, 256-byte aligned */
+HF_API int hf_block_select(const hf_config* cfg, const void* Q, int32_t n_q,
+                    const void* K_win, int32_t n_kv,
+                    int32_t* block_idx, float* scores_or_null,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/* Eq. 5 + Eq. 3 + Eq. 6 for one chunk:
+ *   O_local = softmax over the keys of the selected blocks of (Q K^T * scale) times V
+ *             (online softmax, fp32 statistics and accumulation);
+ *   O_hist  = R_q(phi(q)) L / (z_scale * phi(q).z + eps)          (no Linear map);
+ *   O       = O_local + O_hist.
+ *   block_idx  int32 [B, H, T_m, k] from hf_block_select (entries in [0, T_n), distinct
+ *              within a row); NULL = every block (dense sliding-window attention), k ignored.
+ *   state_or_null   the fp32 state, or NULL for O_hist = 0.
+ *   rope_cos_q / rope_sin_q  fp32 [n_q, d/2] for the numerator of Eq. 3, or both NULL.
+ *   O          out [B, H, n_q, d], must not alias an input.
+ *   workspace  >= hf_workspace_bytes(...) bytes, 256-byte aligned. */
+HF_API int hf_hybrid_attn_fwd(const hf_config* cfg, const void* Q, int32_t n_q,
+                       const void* K_win, const void* V_win, int32_t n_kv,
+                       const int32_t* block_idx, int32_t k,
+                       const void* state_or_null,
+                       const float* rope_cos_q, const float* rope_sin_q,
+                       void* O, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Last error message of the calling thread (static storage, never NULL). */
+HF_API const char* hf_last_error(void);
+
+/* Library version string, e.g. "hf-gfx950 0.1". */
+HF_API const char* hf_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HF_H_ */

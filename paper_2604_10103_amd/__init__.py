@@ -1,0 +1,24 @@
+"""MI355X-native hybrid attention of Hybrid Forcing: HIP kernels behind a C ABI, plus a thin binding.
+
+The shared library is loaded on first use (``binding.load()``); importing the package does
+not need a GPU.
+"""
+from .binding import (  # noqa: F401
+    HF_BF16,
+    HF_F32,
+    HF_PHI_RELU,
+    HF_PHI_ELU1,
+    HFError,
+    hf_config,
+    make_config,
+    load,
+    lib_path,
+    hf_version,
+    hf_state_bytes,
+    hf_state_init,
+    hf_absorb_evicted,
+    hf_select_k,
+    hf_workspace_bytes,
+    hf_block_select,
+    hf_hybrid_attn_fwd,
+)

@@ -1,0 +1,200 @@
+"""ctypes binding of libhf.so: same names as the C ABI, argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU, checks dtype / shape /
+contiguity, and passes raw device pointers plus the current HIP stream.  No step of the
+method runs in Python or in torch; torch is used for device memory and streams.
+There is no fallback: a missing library or a failed call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+HF_BF16, HF_F32 = 0, 1
+HF_PHI_RELU, HF_PHI_ELU1 = 0, 1
+HF_OK = 0
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libhf.so")
+_lib = None
+
+
+class HFError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"hf error {code}: {msg}")
+        self.code = code
+
+
+class hf_config(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32),
+        ("heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32),
+        ("dtype", ctypes.c_int32),
+        ("block_q", ctypes.c_int32),
+        ("block_kv", ctypes.c_int32),
+        ("keep_ratio", ctypes.c_float),
+        ("keep_k", ctypes.c_int32),
+        ("phi", ctypes.c_int32),
+        ("eps", ctypes.c_float),
+        ("z_scale", ctypes.c_float),
+        ("softmax_scale", ctypes.c_float),
+    ]
+
+
+def make_config(batch, heads, head_dim, dtype, block_q, block_kv, keep_ratio=1.0, keep_k=0,
+                phi=HF_PHI_RELU, eps=1e-6, z_scale=1.0, softmax_scale=0.0) -> hf_config:
+    if isinstance(dtype, str):
+        dtype = {"bf16": HF_BF16, "f32": HF_F32}[dtype]
+    elif isinstance(dtype, torch.dtype):
+        dtype = {torch.bfloat16: HF_BF16, torch.float32: HF_F32}[dtype]
+    return hf_config(batch, heads, head_dim, dtype, block_q, block_kv, keep_ratio, keep_k, phi, eps,
+                     z_scale, softmax_scale)
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load():
+    """Load libhf.so (built in-tree by ``python -m paper_2604_10103_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2604_10103_amd.build`")
+    lib = ctypes.CDLL(_LIB_PATH)
+    P, I, SZ = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    CP = ctypes.POINTER(hf_config)
+    lib.hf_last_error.restype = ctypes.c_char_p
+    lib.hf_last_error.argtypes = []
+    lib.hf_version.restype = ctypes.c_char_p
+    lib.hf_version.argtypes = []
+    lib.hf_state_bytes.argtypes = [CP, ctypes.POINTER(SZ)]
+    lib.hf_state_init.argtypes = [CP, P, P]
+    lib.hf_absorb_evicted.argtypes = [CP, P, P, P, I, P, P, P]
+    lib.hf_select_k.argtypes = [CP, I, ctypes.POINTER(I)]
+    lib.hf_workspace_bytes.argtypes = [CP, I, I, ctypes.POINTER(SZ)]
+    lib.hf_block_select.argtypes = [CP, P, I, P, I, P, P, P, SZ, P]
+    lib.hf_hybrid_attn_fwd.argtypes = [CP, P, I, P, P, I, P, I, P, P, P, P, P, SZ, P]
+    for name in ("hf_state_bytes", "hf_state_init", "hf_absorb_evicted", "hf_select_k", "hf_workspace_bytes",
+                 "hf_block_select", "hf_hybrid_attn_fwd"):
+        getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _check(code: int):
+    if code != HF_OK:
+        raise HFError(code, load().hf_last_error().decode())
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t, name, dtype=None, shape=None):
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a GPU tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name} must have shape {tuple(shape)}, got {tuple(t.shape)}")
+    return t.data_ptr()
+
+
+def _tdtype(cfg: hf_config):
+    return torch.bfloat16 if cfg.dtype == HF_BF16 else torch.float32
+
+
+def _cdiv(a, b):
+    return -(-a // b)
+
+
+# ------------------------------------------------------------------------------ host helpers
+def hf_version() -> str:
+    return load().hf_version().decode()
+
+
+def hf_state_bytes(cfg: hf_config) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().hf_state_bytes(ctypes.byref(cfg), ctypes.byref(out)))
+    return out.value
+
+
+def hf_select_k(cfg: hf_config, n_kv: int) -> int:
+    out = ctypes.c_int32(0)
+    _check(load().hf_select_k(ctypes.byref(cfg), n_kv, ctypes.byref(out)))
+    return out.value
+
+
+def hf_workspace_bytes(cfg: hf_config, n_q: int, n_kv: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().hf_workspace_bytes(ctypes.byref(cfg), n_q, n_kv, ctypes.byref(out)))
+    return out.value
+
+
+# ------------------------------------------------------------------------------ device calls
+def hf_state_init(cfg: hf_config, state: torch.Tensor) -> None:
+    """state: fp32 GPU tensor of hf_state_bytes(cfg)/4 elements, zeroed in place."""
+    n = hf_state_bytes(cfg) // 4
+    _check(load().hf_state_init(ctypes.byref(cfg), _dev(state, "state", torch.float32, (n,)), _stream()))
+
+
+def hf_absorb_evicted(cfg: hf_config, state, K_ev, V_ev, rope_cos=None, rope_sin=None) -> None:
+    n = hf_state_bytes(cfg) // 4
+    B, H, d = cfg.batch, cfg.heads, cfg.head_dim
+    if K_ev.dim() != 4:
+        raise ValueError("K_ev must be [B, H, n, d]")
+    nt = K_ev.shape[2]
+    shp = (B, H, nt, d)
+    tab = (nt, d // 2)
+    _check(load().hf_absorb_evicted(
+        ctypes.byref(cfg), _dev(state, "state", torch.float32, (n,)),
+        _dev(K_ev, "K_ev", _tdtype(cfg), shp), _dev(V_ev, "V_ev", _tdtype(cfg), shp), nt,
+        _dev(rope_cos, "rope_cos", torch.float32, tab), _dev(rope_sin, "rope_sin", torch.float32, tab),
+        _stream()))
+
+
+def hf_block_select(cfg: hf_config, Q, K_win, block_idx, scores=None, workspace=None) -> None:
+    """block_idx: int32 [B,H,T_m,k] out; scores: optional fp32 [B,H,T_m,T_n] out; workspace: uint8 buffer."""
+    B, H, d = cfg.batch, cfg.heads, cfg.head_dim
+    n_q, n_kv = Q.shape[2], K_win.shape[2]
+    t_m, t_n = _cdiv(n_q, cfg.block_q), _cdiv(n_kv, cfg.block_kv)
+    k = hf_select_k(cfg, n_kv)
+    ws_ptr = _dev(workspace, "workspace", torch.uint8)
+    _check(load().hf_block_select(
+        ctypes.byref(cfg), _dev(Q, "Q", _tdtype(cfg), (B, H, n_q, d)), n_q,
+        _dev(K_win, "K_win", _tdtype(cfg), (B, H, n_kv, d)), n_kv,
+        _dev(block_idx, "block_idx", torch.int32, (B, H, t_m, k)),
+        _dev(scores, "scores", torch.float32, (B, H, t_m, t_n)),
+        ws_ptr, 0 if workspace is None else workspace.numel(), _stream()))
+
+
+def hf_hybrid_attn_fwd(cfg: hf_config, Q, K_win, V_win, block_idx, state, O, workspace=None,
+                       rope_cos_q=None, rope_sin_q=None) -> None:
+    """block_idx None = dense window attention; state None = no history term."""
+    B, H, d = cfg.batch, cfg.heads, cfg.head_dim
+    n_q, n_kv = Q.shape[2], K_win.shape[2]
+    t_m = _cdiv(n_q, cfg.block_q)
+    k = 0
+    if block_idx is not None:
+        if block_idx.dim() != 4:
+            raise ValueError("block_idx must be [B, H, T_m, k]")
+        k = block_idx.shape[3]
+    tab = (n_q, d // 2)
+    ns = hf_state_bytes(cfg) // 4
+    _check(load().hf_hybrid_attn_fwd(
+        ctypes.byref(cfg), _dev(Q, "Q", _tdtype(cfg), (B, H, n_q, d)), n_q,
+        _dev(K_win, "K_win", _tdtype(cfg), (B, H, n_kv, d)),
+        _dev(V_win, "V_win", _tdtype(cfg), (B, H, n_kv, d)), n_kv,
+        _dev(block_idx, "block_idx", torch.int32, (B, H, t_m, k)), k,
+        _dev(state, "state", torch.float32, (ns,)),
+        _dev(rope_cos_q, "rope_cos_q", torch.float32, tab), _dev(rope_sin_q, "rope_sin_q", torch.float32, tab),
+        _dev(O, "O", _tdtype(cfg), (B, H, n_q, d)),
+        _dev(workspace, "workspace", torch.uint8), 0 if workspace is None else workspace.numel(), _stream()))

@@ -1,0 +1,231 @@
+// C-ABI entry points: host-side argument checks and kernel dispatch.  No device allocation,
+// no synchronisation; everything is enqueued on the caller's stream.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "hf_common.h"
+
+namespace hf {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+int check_launch(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    set_error("%s: %s", what, hipGetErrorString(e));
+    return HF_ERR_HIP;
+  }
+  return HF_OK;
+}
+
+static int check_cfg(const hf_config* c) {
+  if (!c) { set_error("cfg is NULL"); return HF_ERR_NULL; }
+  if (c->batch < 1 || c->heads < 1) { set_error("batch and heads must be >= 1"); return HF_ERR_SHAPE; }
+  if ((int64_t)c->batch * c->heads > 65535) { set_error("batch*heads must be <= 65535"); return HF_ERR_SHAPE; }
+  if (c->head_dim != 64 && c->head_dim != 128) { set_error("head_dim must be 64 or 128, got %d", c->head_dim); return HF_ERR_SHAPE; }
+  if (c->dtype != HF_BF16 && c->dtype != HF_F32) { set_error("unknown dtype %d", c->dtype); return HF_ERR_DTYPE; }
+  if (c->phi != HF_PHI_RELU && c->phi != HF_PHI_ELU1) { set_error("unknown phi %d", c->phi); return HF_ERR_DTYPE; }
+  if (c->block_q < 1 || c->block_kv < 1) { set_error("block sizes must be >= 1"); return HF_ERR_SHAPE; }
+  if (c->block_q > 1024 || c->block_kv > 1024) { set_error("block sizes must be <= 1024"); return HF_ERR_SHAPE; }
+  if (c->keep_k < 0) { set_error("keep_k must be >= 0"); return HF_ERR_SHAPE; }
+  if (c->keep_k == 0 && !(c->keep_ratio > 0.0f && c->keep_ratio <= 1.0f)) {
+    set_error("keep_ratio must be in (0, 1]"); return HF_ERR_SHAPE;
+  }
+  if (!(c->eps >= 0.0f) || !isfinite(c->z_scale) || !(c->softmax_scale >= 0.0f)) {
+    set_error("eps, z_scale or softmax_scale is invalid"); return HF_ERR_SHAPE;
+  }
+  return HF_OK;
+}
+
+static int check_ptr(const void* p, const char* name, bool required) {
+  if (!p) {
+    if (!required) return HF_OK;
+    set_error("%s is NULL", name);
+    return HF_ERR_NULL;
+  }
+  if (reinterpret_cast<uintptr_t>(p) & 15u) { set_error("%s is not 16-byte aligned", name); return HF_ERR_ALIGN; }
+  return HF_OK;
+}
+
+static int check_tokens(int32_t n, const char* name) {
+  // 2^24 tokens keeps every element offset within one head below 2^31
+  if (n < 1 || n > (1 << 24)) { set_error("%s must be in [1, 2^24], got %d", name, n); return HF_ERR_SHAPE; }
+  return HF_OK;
+}
+
+static inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+static int select_k_of(const hf_config* c, int t_n) {
+  if (c->keep_k > 0) return c->keep_k;
+  int k = (int)ceil((double)c->keep_ratio * (double)t_n - 1e-9);
+  if (k < 1) k = 1;
+  if (k > t_n) k = t_n;
+  return k;
+}
+
+static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+static inline size_t esize(const hf_config* c) { return c->dtype == HF_BF16 ? 2 : 4; }
+
+struct WorkspaceLayout {
+  size_t qbar, kbar, olocal, total;  // byte offsets
+};
+
+static WorkspaceLayout workspace_layout(const hf_config* c, int n_q, int n_kv) {
+  const size_t bh = (size_t)c->batch * c->heads, d = c->head_dim;
+  const size_t t_m = cdiv(n_q, c->block_q), t_n = cdiv(n_kv, c->block_kv);
+  WorkspaceLayout w;
+  w.qbar = 0;
+  w.kbar = align256(bh * t_m * d * 4);
+  w.olocal = w.kbar + align256(bh * t_n * d * 4);
+  w.total = w.olocal + align256(bh * (size_t)n_q * d * esize(c));
+  return w;
+}
+
+}  // namespace hf
+
+using namespace hf;
+
+#define HF_TRY(expr) do { int _r = (expr); if (_r != HF_OK) return _r; } while (0)
+
+extern "C" {
+
+const char* hf_last_error(void) { return g_err; }
+const char* hf_version(void) { return "hf-gfx950 0.1"; }
+
+int hf_state_bytes(const hf_config* cfg, size_t* bytes_out) {
+  HF_TRY(check_cfg(cfg));
+  if (!bytes_out) { set_error("bytes_out is NULL"); return HF_ERR_NULL; }
+  const size_t d = cfg->head_dim;
+  *bytes_out = (size_t)cfg->batch * cfg->heads * (d * d + d) * sizeof(float);
+  return HF_OK;
+}
+
+int hf_state_init(const hf_config* cfg, void* state, void* stream) {
+  HF_TRY(check_cfg(cfg));
+  HF_TRY(check_ptr(state, "state", true));
+  const size_t d = cfg->head_dim;
+  return launch_fill_zero(static_cast<float*>(state), (size_t)cfg->batch * cfg->heads * (d * d + d),
+                          static_cast<hipStream_t>(stream));
+}
+
+int hf_absorb_evicted(const hf_config* cfg, void* state, const void* K_ev, const void* V_ev,
+                      int32_t n_tokens, const float* rope_cos, const float* rope_sin, void* stream) {
+  HF_TRY(check_cfg(cfg));
+  HF_TRY(check_ptr(state, "state", true));
+  HF_TRY(check_ptr(K_ev, "K_ev", true));
+  HF_TRY(check_ptr(V_ev, "V_ev", true));
+  HF_TRY(check_tokens(n_tokens, "n_tokens"));
+  if ((rope_cos == nullptr) != (rope_sin == nullptr)) {
+    set_error("rope_cos and rope_sin must both be given or both be NULL");
+    return HF_ERR_NULL;
+  }
+  HF_TRY(check_ptr(rope_cos, "rope_cos", false));
+  HF_TRY(check_ptr(rope_sin, "rope_sin", false));
+  return launch_absorb(*cfg, static_cast<float*>(state), K_ev, V_ev, n_tokens, rope_cos, rope_sin,
+                       static_cast<hipStream_t>(stream));
+}
+
+int hf_select_k(const hf_config* cfg, int32_t n_kv, int32_t* k_out) {
+  HF_TRY(check_cfg(cfg));
+  if (!k_out) { set_error("k_out is NULL"); return HF_ERR_NULL; }
+  HF_TRY(check_tokens(n_kv, "n_kv"));
+  const int t_n = cdiv(n_kv, cfg->block_kv);
+  const int k = select_k_of(cfg, t_n);
+  if (k > t_n) { set_error("keep_k=%d exceeds the %d KV blocks of the window", k, t_n); return HF_ERR_SHAPE; }
+  *k_out = k;
+  return HF_OK;
+}
+
+int hf_workspace_bytes(const hf_config* cfg, int32_t n_q, int32_t n_kv, size_t* bytes_out) {
+  HF_TRY(check_cfg(cfg));
+  if (!bytes_out) { set_error("bytes_out is NULL"); return HF_ERR_NULL; }
+  HF_TRY(check_tokens(n_q, "n_q"));
+  HF_TRY(check_tokens(n_kv, "n_kv"));
+  *bytes_out = workspace_layout(cfg, n_q, n_kv).total;
+  return HF_OK;
+}
+
+int hf_block_select(const hf_config* cfg, const void* Q, int32_t n_q, const void* K_win, int32_t n_kv,
+                    int32_t* block_idx, float* scores_or_null, void* workspace, size_t workspace_bytes,
+                    void* stream) {
+  HF_TRY(check_cfg(cfg));
+  HF_TRY(check_ptr(Q, "Q", true));
+  HF_TRY(check_ptr(K_win, "K_win", true));
+  HF_TRY(check_ptr(block_idx, "block_idx", true));
+  HF_TRY(check_ptr(scores_or_null, "scores", false));
+  HF_TRY(check_tokens(n_q, "n_q"));
+  HF_TRY(check_tokens(n_kv, "n_kv"));
+  const int t_m = cdiv(n_q, cfg->block_q), t_n = cdiv(n_kv, cfg->block_kv);
+  if (t_n > kMaxSelectBlocks) {
+    set_error("window has %d KV blocks; the selection kernel ranks at most %d", t_n, kMaxSelectBlocks);
+    return HF_ERR_SHAPE;
+  }
+  const int k = select_k_of(cfg, t_n);
+  if (k > t_n) { set_error("keep_k=%d exceeds the %d KV blocks of the window", k, t_n); return HF_ERR_SHAPE; }
+  const WorkspaceLayout w = workspace_layout(cfg, n_q, n_kv);
+  if (!workspace || workspace_bytes < w.total) {
+    set_error("workspace of %zu bytes needed, %zu given", w.total, workspace ? workspace_bytes : (size_t)0);
+    return HF_ERR_WORKSPACE;
+  }
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) { set_error("workspace is not 256-byte aligned"); return HF_ERR_ALIGN; }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  float* qbar = reinterpret_cast<float*>(ws + w.qbar);
+  float* kbar = reinterpret_cast<float*>(ws + w.kbar);
+  HF_TRY(launch_pool(*cfg, Q, n_q, cfg->block_q, t_m, qbar, s));
+  HF_TRY(launch_pool(*cfg, K_win, n_kv, cfg->block_kv, t_n, kbar, s));
+  return launch_score_select(*cfg, qbar, kbar, t_m, t_n, k, block_idx, scores_or_null, s);
+}
+
+int hf_hybrid_attn_fwd(const hf_config* cfg, const void* Q, int32_t n_q, const void* K_win,
+                       const void* V_win, int32_t n_kv, const int32_t* block_idx, int32_t k,
+                       const void* state_or_null, const float* rope_cos_q, const float* rope_sin_q,
+                       void* O, void* workspace, size_t workspace_bytes, void* stream) {
+  HF_TRY(check_cfg(cfg));
+  HF_TRY(check_ptr(Q, "Q", true));
+  HF_TRY(check_ptr(K_win, "K_win", true));
+  HF_TRY(check_ptr(V_win, "V_win", true));
+  HF_TRY(check_ptr(O, "O", true));
+  HF_TRY(check_ptr(block_idx, "block_idx", false));
+  HF_TRY(check_ptr(state_or_null, "state", false));
+  HF_TRY(check_tokens(n_q, "n_q"));
+  HF_TRY(check_tokens(n_kv, "n_kv"));
+  if (O == Q || O == K_win || O == V_win) { set_error("O must not alias an input"); return HF_ERR_SHAPE; }
+  if ((rope_cos_q == nullptr) != (rope_sin_q == nullptr)) {
+    set_error("rope_cos_q and rope_sin_q must both be given or both be NULL");
+    return HF_ERR_NULL;
+  }
+  HF_TRY(check_ptr(rope_cos_q, "rope_cos_q", false));
+  HF_TRY(check_ptr(rope_sin_q, "rope_sin_q", false));
+  const int t_n = cdiv(n_kv, cfg->block_kv);
+  if (block_idx) {
+    if (k < 1 || k > t_n) { set_error("k=%d must be in [1, %d]", k, t_n); return HF_ERR_SHAPE; }
+  } else {
+    k = t_n;
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (!state_or_null) {
+    // no history yet: O = O_local, written directly
+    return launch_attn(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, O, s);
+  }
+  const WorkspaceLayout w = workspace_layout(cfg, n_q, n_kv);
+  if (!workspace || workspace_bytes < w.total) {
+    set_error("workspace of %zu bytes needed, %zu given", w.total, workspace ? workspace_bytes : (size_t)0);
+    return HF_ERR_WORKSPACE;
+  }
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) { set_error("workspace is not 256-byte aligned"); return HF_ERR_ALIGN; }
+  void* o_local = static_cast<char*>(workspace) + w.olocal;
+  HF_TRY(launch_attn(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, o_local, s));
+  return launch_readout(*cfg, Q, n_q, o_local, static_cast<const float*>(state_or_null), rope_cos_q,
+                        rope_sin_q, O, s);
+}
+
+}  // extern "C"

@@ -1,0 +1,92 @@
+// Shared host/device helpers of the gfx950 hybrid-attention library (internal).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "hf.h"
+
+namespace hf {
+
+constexpr int kWave = 64;            // CDNA wavefront width
+constexpr int kMaxSelectBlocks = 2048;  // largest T_n the selection kernel ranks in LDS
+
+typedef uint16_t bf16_t;  // storage type of a bfloat16 value
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t x) {
+  return __uint_as_float(static_cast<uint32_t>(x) << 16);
+}
+
+// round-to-nearest-even; maps to v_cvt_pk_bf16_f32 on gfx950
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  __bf16 b = static_cast<__bf16>(f);
+  return __builtin_bit_cast(bf16_t, b);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static constexpr int kPer16B = 4;
+  __device__ static __forceinline__ float load(const float* p) { return *p; }
+  __device__ static __forceinline__ void store(float* p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+  static constexpr int kPer16B = 8;
+  __device__ static __forceinline__ float load(const bf16_t* p) { return bf16_to_f32(*p); }
+  __device__ static __forceinline__ void store(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+};
+
+// 16-byte vector load of consecutive elements into fp32 registers
+template <typename T> __device__ __forceinline__ void load16B(const T* p, float* out);
+template <> __device__ __forceinline__ void load16B<float>(const float* p, float* out) {
+  const float4 v = *reinterpret_cast<const float4*>(p);
+  out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+}
+template <> __device__ __forceinline__ void load16B<bf16_t>(const bf16_t* p, float* out) {
+  const uint4 v = *reinterpret_cast<const uint4*>(p);
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    out[2 * i] = __uint_as_float(w[i] << 16);
+    out[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+  }
+}
+
+// feature map of the linear branch (Eq. 2, 3): ReLU or elu(x)+1
+__device__ __forceinline__ float phi_apply(float x, int kind) {
+  if (kind == HF_PHI_RELU) return fmaxf(x, 0.0f);
+  return x > 0.0f ? x + 1.0f : __expf(x);
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+
+// ---- host side -------------------------------------------------------------------------
+void set_error(const char* fmt, ...);
+int check_launch(const char* what);
+
+struct Dims {
+  int B, H, D, BH;
+  int n_q, n_kv, bq, bkv, t_m, t_n;
+};
+
+// Launchers implemented in the .hip files.  All pointers are device pointers.
+int launch_fill_zero(float* p, size_t n, hipStream_t s);
+int launch_absorb(const hf_config& c, float* state, const void* K, const void* V, int n,
+                  const float* cosv, const float* sinv, hipStream_t s);
+int launch_pool(const hf_config& c, const void* X, int n, int b, int t, float* pooled, hipStream_t s);
+int launch_score_select(const hf_config& c, const float* qbar, const float* kbar, int t_m, int t_n,
+                        int k, int32_t* idx, float* scores, hipStream_t s);
+int launch_attn(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
+                const int32_t* idx, int k, void* O_local, hipStream_t s);
+int launch_readout(const hf_config& c, const void* Q, int n_q, const void* O_local,
+                   const float* state, const float* cosq, const float* sinq, void* O, hipStream_t s);
+
+}  // namespace hf

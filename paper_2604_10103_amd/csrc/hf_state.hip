@@ -1,0 +1,129 @@
+// Linear state of the history branch: zero fill and absorption of evicted tokens (Eq. 2).
+//
+//   L[i][j] += sum_t R_t(phi(k_t))[i] * v_t[j]        z[i] += sum_t phi(k_t)[i]
+//
+// The evicted tokens of one (batch, head) are cut into slices; a workgroup reduces one slice to
+// a d x d partial in registers and adds it to the fp32 state with device-scope float atomics
+// (the 0.8 MB state stays cache resident; no partials go to HBM).
+#include "hf_common.h"
+
+namespace hf {
+
+__global__ void fill_zero_kernel(float* __restrict__ p, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) p[i] = 0.0f;
+}
+
+int launch_fill_zero(float* p, size_t n, hipStream_t s) {
+  const int threads = 256;
+  size_t blocks = (n + threads - 1) / threads;
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(threads), 0, s, p, n);
+  return check_launch("hf_state_init");
+}
+
+// ---------------------------------------------------------------------------------------------
+// fp32 FMA path (any storage dtype, fp32 arithmetic): used for fp32 inputs.
+// 256 threads own a D x D register tile grid: thread (ti, tj) holds an E x E tile, E = D / 16.
+// Tokens are staged TT at a time in LDS as fp32 (rotated phi(k) and v).
+template <typename T, int D>
+__global__ __launch_bounds__(256) void absorb_fma_kernel(float* __restrict__ state, const T* __restrict__ K,
+                                                         const T* __restrict__ V, int n, int tokens_per_slice,
+                                                         const float* __restrict__ cosv,
+                                                         const float* __restrict__ sinv, int phi_kind, int BH) {
+  constexpr int E = D / 16;
+  constexpr int TT = 32;
+  __shared__ float sk[TT][D + 4];
+  __shared__ float sv[TT][D + 4];
+  const int bh = blockIdx.y;
+  const int t0 = blockIdx.x * tokens_per_slice;
+  const int t1 = min(n, t0 + tokens_per_slice);
+  if (t0 >= t1) return;
+  const int tid = threadIdx.x;
+  const int ti = tid / 16, tj = tid % 16;
+  const T* Kh = K + (size_t)bh * n * D;
+  const T* Vh = V + (size_t)bh * n * D;
+  float acc[E][E];
+#pragma unroll
+  for (int a = 0; a < E; ++a)
+#pragma unroll
+    for (int b = 0; b < E; ++b) acc[a][b] = 0.0f;
+  float zsum = 0.0f;  // thread tid < D sums feature tid
+
+  for (int tb = t0; tb < t1; tb += TT) {
+    const int cnt = min(TT, t1 - tb);
+    // stage: one feature pair per work item so the rotation has both partners
+    for (int w = tid; w < TT * (D / 2); w += 256) {
+      const int r = w / (D / 2), p = w % (D / 2);
+      float k0 = 0.f, k1 = 0.f, v0 = 0.f, v1 = 0.f;
+      if (r < cnt) {
+        const size_t off = (size_t)(tb + r) * D + 2 * p;
+        k0 = phi_apply(Elem<T>::load(Kh + off), phi_kind);
+        k1 = phi_apply(Elem<T>::load(Kh + off + 1), phi_kind);
+        v0 = Elem<T>::load(Vh + off);
+        v1 = Elem<T>::load(Vh + off + 1);
+        if (cosv) {
+          const float c = cosv[(size_t)(tb + r) * (D / 2) + p], s = sinv[(size_t)(tb + r) * (D / 2) + p];
+          const float r0 = k0 * c - k1 * s, r1 = k0 * s + k1 * c;
+          k0 = r0; k1 = r1;
+        }
+      }
+      sk[r][2 * p] = k0; sk[r][2 * p + 1] = k1;
+      sv[r][2 * p] = v0; sv[r][2 * p + 1] = v1;
+    }
+    if (tid < D) {  // normaliser: un-rotated phi(k), straight from memory
+      for (int r = 0; r < cnt; ++r) zsum += phi_apply(Elem<T>::load(Kh + (size_t)(tb + r) * D + tid), phi_kind);
+    }
+    __syncthreads();
+    for (int r = 0; r < TT; ++r) {
+      float kk[E], vv[E];
+#pragma unroll
+      for (int a = 0; a < E; ++a) kk[a] = sk[r][ti * E + a];
+#pragma unroll
+      for (int b = 0; b < E; ++b) vv[b] = sv[r][tj * E + b];
+#pragma unroll
+      for (int a = 0; a < E; ++a)
+#pragma unroll
+        for (int b = 0; b < E; ++b) acc[a][b] = fmaf(kk[a], vv[b], acc[a][b]);
+    }
+    __syncthreads();
+  }
+  float* L = state + (size_t)bh * D * D;
+  float* z = state + (size_t)BH * D * D + (size_t)bh * D;
+#pragma unroll
+  for (int a = 0; a < E; ++a)
+#pragma unroll
+    for (int b = 0; b < E; ++b) atomicAdd(L + (size_t)(ti * E + a) * D + tj * E + b, acc[a][b]);
+  if (tid < D) atomicAdd(z + tid, zsum);
+}
+
+template <typename T, int D>
+static int launch_absorb_fma(const hf_config& c, float* state, const void* K, const void* V, int n,
+                             const float* cosv, const float* sinv, hipStream_t s) {
+  const int BH = c.batch * c.heads;
+  // aim at ~4 workgroups per compute unit, at least 64 tokens per slice
+  int slices = (1024 + BH - 1) / BH;
+  int per = (n + slices - 1) / slices;
+  if (per < 64) per = 64;
+  per = (per + 31) / 32 * 32;
+  slices = (n + per - 1) / per;
+  hipLaunchKernelGGL((absorb_fma_kernel<T, D>), dim3(slices, BH), dim3(256), 0, s, state,
+                     static_cast<const T*>(K), static_cast<const T*>(V), n, per, cosv, sinv, c.phi, BH);
+  return check_launch("hf_absorb_evicted");
+}
+
+int launch_absorb_mfma(const hf_config& c, float* state, const void* K, const void* V, int n,
+                       const float* cosv, const float* sinv, hipStream_t s);  // hf_state_mfma.hip
+
+int launch_absorb(const hf_config& c, float* state, const void* K, const void* V, int n,
+                  const float* cosv, const float* sinv, hipStream_t s) {
+  if (c.dtype == HF_F32) {
+    return c.head_dim == 128 ? launch_absorb_fma<float, 128>(c, state, K, V, n, cosv, sinv, s)
+                             : launch_absorb_fma<float, 64>(c, state, K, V, n, cosv, sinv, s);
+  }
+  if (c.head_dim == 128) return launch_absorb_mfma(c, state, K, V, n, cosv, sinv, s);
+  return launch_absorb_fma<bf16_t, 64>(c, state, K, V, n, cosv, sinv, s);
+}
+
+}  // namespace hf

@@ -1,0 +1,105 @@
+"""Host-side checks of the C-ABI library: it loads, exports what the header declares, and its
+host-only helpers and argument checks behave.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import oracle as orc
+import paper_2604_10103_amd as hf
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(hf.lib_path()):
+        from paper_2604_10103_amd import build
+        build.build()
+    return hf.load()
+
+
+def _declared():
+    src = open(os.path.join(ROOT, "include", "hf.h")).read()
+    return re.findall(r"HF_API\s+[\w\s\*]+?\b(hf_\w+)\s*\(", src)
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared()
+    assert set(names) >= {"hf_state_bytes", "hf_state_init", "hf_absorb_evicted", "hf_select_k",
+                          "hf_workspace_bytes", "hf_block_select", "hf_hybrid_attn_fwd", "hf_last_error",
+                          "hf_version"}
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in hf.h but not exported"
+
+
+def test_config_struct_layout():
+    assert ctypes.sizeof(hf.hf_config) == 12 * 4
+    assert hf.hf_config.keep_ratio.offset == 24 and hf.hf_config.softmax_scale.offset == 44
+
+
+def test_version_and_state_bytes(lib):
+    assert hf.hf_version().startswith("hf-gfx950")
+    cfg = hf.make_config(1, 12, 128, "bf16", 64, 64, 0.25)
+    assert hf.hf_state_bytes(cfg) == 12 * (128 * 128 + 128) * 4 == 792576
+    cfg = hf.make_config(2, 3, 64, "f32", 16, 16, 0.25)
+    assert hf.hf_state_bytes(cfg) == 6 * (64 * 64 + 64) * 4
+
+
+@pytest.mark.parametrize("ratio,n_kv,b", [(0.25, 256, 16), (0.25, 9360, 64), (0.125, 21600, 128), (0.25, 21600, 128),
+                                          (0.5, 21600, 128), (1.0, 21600, 128), (0.3, 500, 32), (1e-6, 100, 10)])
+def test_select_k_matches_oracle(lib, ratio, n_kv, b):
+    cfg = hf.make_config(1, 1, 128, "bf16", b, b, ratio)
+    t_n = -(-n_kv // b)
+    assert hf.hf_select_k(cfg, n_kv) == orc.select_k(ratio, t_n)
+
+
+def test_keep_k_override_and_bounds(lib):
+    cfg = hf.make_config(1, 1, 128, "bf16", 64, 64, 0.25, keep_k=5)
+    assert hf.hf_select_k(cfg, 9360) == 5
+    cfg = hf.make_config(1, 1, 128, "bf16", 64, 64, 0.25, keep_k=148)
+    with pytest.raises(hf.HFError) as e:
+        hf.hf_select_k(cfg, 9360)
+    assert e.value.code == -2
+
+
+def test_workspace_covers_pooled_means_and_local_output(lib):
+    cfg = hf.make_config(1, 12, 128, "bf16", 64, 64, 0.25)
+    need = 12 * (74 + 147) * 128 * 4 + 12 * 4680 * 128 * 2
+    got = hf.hf_workspace_bytes(cfg, 4680, 9360)
+    assert need <= got <= need + 3 * 256
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(head_dim=96), -2), (dict(dtype=7), -3), (dict(phi=9), -3), (dict(block_q=0), -2),
+    (dict(keep_ratio=0.0), -2), (dict(keep_ratio=1.5), -2), (dict(batch=0), -2), (dict(eps=-1.0), -2),
+])
+def test_bad_config_is_rejected(lib, kw, code):
+    base = dict(batch=1, heads=2, head_dim=128, dtype=hf.HF_BF16, block_q=64, block_kv=64, keep_ratio=0.25)
+    base.update(kw)
+    cfg = hf.make_config(**base)
+    with pytest.raises(hf.HFError) as e:
+        hf.hf_state_bytes(cfg)
+    assert e.value.code == code
+    assert hf.load().hf_last_error()
+
+
+def test_null_and_misaligned_pointers_are_rejected_before_any_launch(lib):
+    cfg = hf.make_config(1, 2, 128, "bf16", 64, 64, 0.25)
+    c = ctypes.byref(cfg)
+    assert lib.hf_state_init(c, None, None) == -1
+    assert lib.hf_state_init(None, None, None) == -1
+    assert lib.hf_absorb_evicted(c, 4096, None, 4096, 10, None, None, None) == -1
+    assert lib.hf_absorb_evicted(c, 4096, 4096, 4100, 10, None, None, None) == -4
+    assert lib.hf_absorb_evicted(c, 4096, 4096, 4096, 0, None, None, None) == -2
+    assert lib.hf_absorb_evicted(c, 4096, 4096, 4096, 10, 4096, None, None) == -1   # cos without sin
+    assert lib.hf_block_select(c, 4096, 100, 4096, 200, 4096, None, None, 0, None) == -5
+    assert lib.hf_block_select(c, 4096, 100, 4096, 200, 4096, None, 4096 + 16, 1 << 30, None) == -4
+    # O aliases Q
+    assert lib.hf_hybrid_attn_fwd(c, 4096, 100, 8192, 8192, 200, None, 0, None, None, None, 4096, None, 0, None) == -2
+    # k out of range with an index list
+    assert lib.hf_hybrid_attn_fwd(c, 4096, 100, 8192, 8192, 200, 4096, 9, None, None, None, 16384, None, 0, None) == -2
+    # state given but no workspace
+    assert lib.hf_hybrid_attn_fwd(c, 4096, 100, 8192, 8192, 200, None, 0, 4096, None, None, 16384, None, 0, None) == -5
+    assert b"workspace" in lib.hf_last_error()

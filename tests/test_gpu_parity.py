@@ -1,0 +1,263 @@
+"""GPU parity: every stage of the HIP path, through the C ABI, against the fp64 oracle on the
+same seeded inputs.  Bounds: block indices exact as sets except boundary ties closer than
+1e-6 in the oracle; outputs rel-L2 <= 1e-2 and max-abs <= 2e-2 for bf16, rel-L2 <= 1e-5 for
+fp32; fp32 state rel-L2 <= 1e-5 (bf16-exact products, fp32 accumulation) and <= 5e-3 when
+rotated keys are rounded to bf16 for the matrix cores."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+import paper_2604_10103_amd as hf
+import workloads as wl
+from parity import (BF16_MAX_ABS, BF16_REL_L2, F32_REL_L2, check_block_idx, heads_of, max_abs, oracle_state,
+                    rel_l2, split_state)
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def cfg_of(w, **kw):
+    args = dict(batch=w.batch, heads=w.heads, head_dim=w.head_dim, dtype=w.dtype, block_q=w.block,
+                block_kv=w.block, keep_ratio=w.keep_ratio)
+    args.update(kw)
+    return hf.make_config(**args)
+
+
+def new_state(cfg):
+    st = torch.empty(hf.hf_state_bytes(cfg) // 4, dtype=torch.float32, device=DEV)
+    st.fill_(float("nan"))          # init must overwrite everything
+    hf.hf_state_init(cfg, st)
+    return st
+
+
+def new_workspace(cfg, n_q, n_kv):
+    return torch.empty(hf.hf_workspace_bytes(cfg, n_q, n_kv), dtype=torch.uint8, device=DEV)
+
+
+def out_bounds(w):
+    return (BF16_REL_L2, BF16_MAX_ABS) if w.dtype == "bf16" else (F32_REL_L2, 1e-4)
+
+
+def gpu_select(cfg, w, Q, K, want_scores=True):
+    k = hf.hf_select_k(cfg, K.shape[2])
+    t_m, t_n = -(-Q.shape[2] // cfg.block_q), -(-K.shape[2] // cfg.block_kv)
+    idx = torch.full((w.batch, w.heads, t_m, k), -1, dtype=torch.int32, device=DEV)
+    scores = torch.empty((w.batch, w.heads, t_m, t_n), dtype=torch.float32, device=DEV) if want_scores else None
+    ws = new_workspace(cfg, Q.shape[2], K.shape[2])
+    hf.hf_block_select(cfg, Q, K, idx, scores, ws)
+    torch.cuda.synchronize()
+    return idx, scores, k
+
+
+# ------------------------------------------------------------------------------- state (Eq. 2)
+@pytest.mark.parametrize("name", ["tiny_f32", "small_bf16", "small_f32_d128"])
+def test_state_init_and_absorb_match_direct_sum(name):
+    w = wl.get(name)
+    cfg = cfg_of(w)
+    st = new_state(cfg)
+    assert not st.isnan().any() and float(st.abs().max()) == 0.0
+    Ks, Vs = [], []
+    for c in range(w.evicted_frames):       # one call per evicted frame
+        K, V = wl.make_evicted(w, c, w.tokens_per_frame)
+        Ks.append(K); Vs.append(V)
+        hf.hf_absorb_evicted(cfg, st, K.to(DEV), V.to(DEV))
+    torch.cuda.synchronize()
+    ref = oracle_state(Ks, Vs, w.head_dim)
+    L, z = split_state(st, w.batch * w.heads, w.head_dim)
+    assert rel_l2(L, np.stack([r[0] for r in ref])) <= 1e-5
+    assert rel_l2(z, np.stack([r[1] for r in ref])) <= 1e-5
+    # order / chunking invariance on the GPU: one call with all tokens
+    st2 = new_state(cfg)
+    hf.hf_absorb_evicted(cfg, st2, torch.cat(Ks, 2).to(DEV), torch.cat(Vs, 2).to(DEV))
+    torch.cuda.synchronize()
+    L2, z2 = split_state(st2, w.batch * w.heads, w.head_dim)
+    assert rel_l2(L2, L) <= 2e-6 and rel_l2(z2, z) <= 2e-6
+
+
+@pytest.mark.parametrize("name", ["tiny_f32", "small_bf16"])
+@pytest.mark.parametrize("phi", [hf.HF_PHI_RELU, hf.HF_PHI_ELU1])
+def test_absorb_with_rope_and_elu(name, phi):
+    w = wl.get(name)
+    cfg = cfg_of(w, phi=phi)
+    st = new_state(cfg)
+    n = 3 * w.tokens_per_frame + 5   # ragged
+    K, V = wl.make_evicted(w, 40, n)
+    cos, sin = wl.rope_tables(n, w.head_dim, first_position=3.0, tokens_per_position=w.tokens_per_frame)
+    hf.hf_absorb_evicted(cfg, st, K.to(DEV), V.to(DEV), cos.to(DEV), sin.to(DEV))
+    torch.cuda.synchronize()
+    ref = oracle_state([K], [V], w.head_dim, phi, [(cos, sin)])
+    L, z = split_state(st, w.batch * w.heads, w.head_dim)
+    tol = 5e-3 if w.dtype == "bf16" else 1e-5
+    assert rel_l2(L, np.stack([r[0] for r in ref])) <= tol
+    assert rel_l2(z, np.stack([r[1] for r in ref])) <= 1e-5
+
+
+def test_absorb_single_token_and_accumulation():
+    w = wl.get("small_bf16")
+    cfg = cfg_of(w)
+    st = new_state(cfg)
+    K, V = wl.make_evicted(w, 41, 1)
+    hf.hf_absorb_evicted(cfg, st, K.to(DEV), V.to(DEV))
+    hf.hf_absorb_evicted(cfg, st, K.to(DEV), V.to(DEV))     # twice: the state accumulates
+    torch.cuda.synchronize()
+    ref = oracle_state([K, K], [V, V], w.head_dim)
+    L, z = split_state(st, w.batch * w.heads, w.head_dim)
+    assert rel_l2(L, np.stack([r[0] for r in ref])) <= 1e-6
+    assert rel_l2(z, np.stack([r[1] for r in ref])) <= 1e-6
+
+
+# ------------------------------------------------------------------------------- selection (Eq. 4)
+@pytest.mark.parametrize("name", ["tiny_f32", "small_bf16", "small_b128", "small_f32_d128"])
+def test_block_scores_and_indices(name):
+    w = wl.get(name)
+    cfg = cfg_of(w)
+    Q, K, _ = wl.make_qkv(w)
+    idx, scores, k = gpu_select(cfg, w, Q.to(DEV), K.to(DEV))
+    assert k == orc.select_k(w.keep_ratio, w.t_n)
+    idx, scores = idx.cpu().numpy(), wl.to_f64(scores)
+    for h, (q, kk) in enumerate(zip(heads_of(Q), heads_of(K))):
+        A = orc.block_scores(q, kk, w.block, w.block)
+        assert np.abs(scores[0, h] - A).max() <= 1e-5 * max(1.0, np.abs(A).max())
+        check_block_idx(idx[0, h], A, k)
+
+
+def test_selection_ties_and_keep_all():
+    # identical key blocks give exactly tied scores: the lower index must win
+    w = wl.get("small_bf16")
+    cfg = cfg_of(w, keep_k=3)
+    Q, K, _ = wl.make_qkv(w)
+    K[:, :, 64:128] = K[:, :, 0:64]
+    K[:, :, 128:192] = K[:, :, 0:64]
+    idx, scores, k = gpu_select(cfg, w, Q.to(DEV), K.to(DEV))
+    idx = idx.cpu().numpy()
+    for h, (q, kk) in enumerate(zip(heads_of(Q), heads_of(K))):
+        A = orc.block_scores(q, kk, w.block, w.block)
+        ref, _ = orc.select_blocks(A, 3)
+        # ties are exact in fp32 as well (same pooled vectors), so the sets must agree outright
+        assert np.array_equal(idx[0, h], ref)
+    cfg = cfg_of(w, keep_ratio=1.0)
+    idx, _, k = gpu_select(cfg, w, Q.to(DEV), K.to(DEV), want_scores=False)
+    assert k == w.t_n
+    assert np.array_equal(idx.cpu().numpy(), np.broadcast_to(np.arange(k, dtype=np.int32), idx.shape))
+
+
+# ------------------------------------------------------------------------------- attention (Eq. 5, 3, 6)
+def run_hybrid(cfg, w, Q, K, V, idx, st, tables=None):
+    O = torch.full(Q.shape, float("nan"), dtype=Q.dtype, device=DEV)
+    ws = new_workspace(cfg, Q.shape[2], K.shape[2])
+    cos, sin = (None, None) if tables is None else (tables[0].to(DEV), tables[1].to(DEV))
+    hf.hf_hybrid_attn_fwd(cfg, Q.to(DEV), K.to(DEV), V.to(DEV), idx, st, O, ws, cos, sin)
+    torch.cuda.synchronize()
+    return O
+
+
+@pytest.mark.parametrize("name,q_gain", [("tiny_f32", 1.0), ("tiny_f32", 6.0), ("small_bf16", 1.0),
+                                         ("small_bf16", 8.0), ("small_b128", 1.0), ("small_f32_d128", 3.0)])
+def test_sparse_attention_alone_matches_oracle(name, q_gain):
+    w = wl.get(name)
+    cfg = cfg_of(w)
+    Q, K, V = wl.make_qkv(w, q_gain=q_gain)
+    idx, _, k = gpu_select(cfg, w, Q.to(DEV), K.to(DEV), want_scores=False)
+    O = run_hybrid(cfg, w, Q, K, V, idx, None)
+    assert not O.isnan().any()
+    Og, idxc = wl.to_f64(O), idx.cpu().numpy()
+    rl, ma = out_bounds(w)
+    for h, (q, kk, v) in enumerate(zip(heads_of(Q), heads_of(K), heads_of(V))):
+        ref = orc.sparse_attention(q, kk, v, idxc[0, h], w.block, w.block)   # the GPU's own index list
+        assert rel_l2(Og[0, h], ref) <= rl, (name, h)
+        assert max_abs(Og[0, h], ref) <= ma
+
+
+@pytest.mark.parametrize("name", ["tiny_f32", "small_bf16", "small_b128"])
+def test_dense_window_attention_matches_bruteforce(name):
+    w = wl.get(name)
+    cfg = cfg_of(w, keep_ratio=1.0)
+    Q, K, V = wl.make_qkv(w, q_gain=2.0)
+    O = wl.to_f64(run_hybrid(cfg, w, Q, K, V, None, None))
+    rl, ma = out_bounds(w)
+    for h, (q, kk, v) in enumerate(zip(heads_of(Q), heads_of(K), heads_of(V))):
+        ref = orc.dense_attention(q, kk, v)
+        assert rel_l2(O[0, h], ref) <= rl and max_abs(O[0, h], ref) <= ma
+
+
+@pytest.mark.parametrize("name,phi,rope", [("tiny_f32", hf.HF_PHI_RELU, False), ("tiny_f32", hf.HF_PHI_ELU1, True),
+                                           ("small_bf16", hf.HF_PHI_RELU, False), ("small_bf16", hf.HF_PHI_RELU, True),
+                                           ("small_b128", hf.HF_PHI_ELU1, False), ("small_f32_d128", hf.HF_PHI_RELU, True)])
+def test_full_hybrid_path_matches_oracle(name, phi, rope):
+    w = wl.get(name)
+    cfg = cfg_of(w, phi=phi)
+    st = new_state(cfg)
+    Ks, Vs, tabs = [], [], []
+    for c in range(w.evicted_frames):
+        K, V = wl.make_evicted(w, c, w.tokens_per_frame)
+        tab = wl.rope_tables(w.tokens_per_frame, w.head_dim, first_position=float(c)) if rope else (None, None)
+        Ks.append(K); Vs.append(V); tabs.append(tab)
+        hf.hf_absorb_evicted(cfg, st, K.to(DEV), V.to(DEV), *(t.to(DEV) if t is not None else None for t in tab))
+    Q, K, V = wl.make_qkv(w)
+    qtab = wl.rope_tables(w.n_q, w.head_dim, first_position=float(w.evicted_frames + 2),
+                          tokens_per_position=w.tokens_per_frame) if rope else None
+    idx, _, k = gpu_select(cfg, w, Q.to(DEV), K.to(DEV), want_scores=False)
+    O = wl.to_f64(run_hybrid(cfg, w, Q, K, V, idx, st, qtab))
+    idxc = idx.cpu().numpy()
+    ref_states = oracle_state(Ks, Vs, w.head_dim, phi, tabs if rope else None)
+    rl, ma = out_bounds(w)
+    cq = None if qtab is None else wl.to_f64(qtab[0])
+    sq = None if qtab is None else wl.to_f64(qtab[1])
+    for h, (q, kk, v) in enumerate(zip(heads_of(Q), heads_of(K), heads_of(V))):
+        ref, ref_local, ref_hist, _, _ = orc.hybrid_attention(q, kk, v, ref_states[h], w.block, w.block, k, phi,
+                                                             cq, sq, cfg.eps, cfg.z_scale, block_idx=idxc[0, h])
+        assert np.abs(ref_hist).max() > 1e-4   # the history term is really there
+        assert rel_l2(O[0, h], ref) <= rl, (name, h, rel_l2(O[0, h], ref))
+        assert max_abs(O[0, h], ref) <= ma
+
+
+def test_empty_state_gives_local_attention_only():
+    w = wl.get("small_bf16")
+    cfg = cfg_of(w)
+    Q, K, V = wl.make_qkv(w)
+    idx, _, _ = gpu_select(cfg, w, Q.to(DEV), K.to(DEV), want_scores=False)
+    a = run_hybrid(cfg, w, Q, K, V, idx, None)
+    b = run_hybrid(cfg, w, Q, K, V, idx, new_state(cfg))     # zero state: 0 / (0 + eps) = 0
+    assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("n_q,n_kv,b", [(1, 1, 64), (5, 70, 64), (64, 64, 64), (129, 257, 128), (33, 100, 16)])
+def test_ragged_and_degenerate_sizes(n_q, n_kv, b):
+    dtype = torch.bfloat16
+    cfg = hf.make_config(1, 2, 128, "bf16", b, b, 0.5)
+    Q = wl.randn((1, 2, n_q, 128), 901, 0.7, dtype)
+    K = wl.randn((1, 2, n_kv, 128), 902, 0.7, dtype)
+    V = wl.randn((1, 2, n_kv, 128), 903, 0.7, dtype)
+    Ke, Ve = wl.randn((1, 2, 37, 128), 904, 0.7, dtype), wl.randn((1, 2, 37, 128), 905, 0.7, dtype)
+    st = new_state(cfg)
+    hf.hf_absorb_evicted(cfg, st, Ke.to(DEV), Ve.to(DEV))
+    k = hf.hf_select_k(cfg, n_kv)
+    t_m = -(-n_q // b)
+    idx = torch.empty((1, 2, t_m, k), dtype=torch.int32, device=DEV)
+    ws = new_workspace(cfg, n_q, n_kv)
+    hf.hf_block_select(cfg, Q.to(DEV), K.to(DEV), idx, None, ws)
+    guard = torch.full((1, 2, n_q + 4, 128), 7.0, dtype=dtype, device=DEV)   # rows past n_q must stay untouched
+    O = guard[:, :, :n_q].contiguous()
+    hf.hf_hybrid_attn_fwd(cfg, Q.to(DEV), K.to(DEV), V.to(DEV), idx, st, O, ws)
+    torch.cuda.synchronize()
+    states = oracle_state([Ke], [Ve], 128)
+    idxc = idx.cpu().numpy()
+    for h, (q, kk, v) in enumerate(zip(heads_of(Q), heads_of(K), heads_of(V))):
+        A = orc.block_scores(q, kk, b, b)
+        check_block_idx(idxc[0, h], A, k)
+        ref, *_ = orc.hybrid_attention(q, kk, v, states[h], b, b, k, block_idx=idxc[0, h])
+        assert rel_l2(wl.to_f64(O)[0, h], ref) <= BF16_REL_L2
+        assert max_abs(wl.to_f64(O)[0, h], ref) <= BF16_MAX_ABS
+
+
+def test_out_of_range_block_index_is_ignored_not_read():
+    w = wl.get("small_bf16")
+    cfg = cfg_of(w)
+    Q, K, V = wl.make_qkv(w)
+    idx, _, k = gpu_select(cfg, w, Q.to(DEV), K.to(DEV), want_scores=False)
+    bad = torch.cat([idx, torch.full_like(idx[..., :1], 1 << 20)], dim=-1).contiguous()
+    a = run_hybrid(cfg, w, Q, K, V, idx, None)
+    b = run_hybrid(cfg, w, Q, K, V, bad[..., : k + 1].contiguous() if k + 1 <= w.t_n else idx, None)
+    assert torch.equal(a, b)
