@@ -25,6 +25,7 @@ SOURCES = [
     "hf_select.hip",
     "hf_attn_generic.hip",
     "hf_attn_mfma.hip",
+    "hf_attn_w64.hip",
     "hf_readout.hip",
     "hf_readout_mfma.hip",
 ]
@@ -45,6 +46,13 @@ FLAGS = [
 ]
 
 
+# per-source additions: the ILP-driven machine scheduler keeps several LDS fragment reads in
+# flight ahead of the MFMAs of the flash-attention loops (the default one serialises them)
+EXTRA_FLAGS = {
+    "hf_attn_w64.hip": ["-mllvm", "-amdgpu-sched-strategy=iterative-ilp"],
+}
+
+
 def hipcc() -> str:
     exe = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
     if not os.path.exists(exe):
@@ -60,7 +68,7 @@ def build(verbose: bool = False, jobs: int = 8) -> str:
 
     def compile_one(src):
         obj = os.path.join(out_dir, src.replace(".hip", ".o"))
-        cmd = [cc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [cc, *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         r = subprocess.run(cmd, capture_output=True, text=True)

@@ -75,7 +75,7 @@ static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 static inline size_t esize(const hf_config* c) { return c->dtype == HF_BF16 ? 2 : 4; }
 
 struct WorkspaceLayout {
-  size_t qbar, kbar, olocal, total;  // byte offsets
+  size_t qbar, kbar, olocal, planes, total;  // byte offsets
 };
 
 static WorkspaceLayout workspace_layout(const hf_config* c, int n_q, int n_kv) {
@@ -85,7 +85,8 @@ static WorkspaceLayout workspace_layout(const hf_config* c, int n_q, int n_kv) {
   w.qbar = 0;
   w.kbar = align256(bh * t_m * d * 4);
   w.olocal = w.kbar + align256(bh * t_n * d * 4);
-  w.total = w.olocal + align256(bh * (size_t)n_q * d * esize(c));
+  w.planes = w.olocal + align256(bh * (size_t)n_q * d * esize(c));
+  w.total = w.planes + align256(readout_planes_bytes(*c));
   return w;
 }
 
@@ -180,8 +181,7 @@ int hf_block_select(const hf_config* cfg, const void* Q, int32_t n_q, const void
   char* ws = static_cast<char*>(workspace);
   float* qbar = reinterpret_cast<float*>(ws + w.qbar);
   float* kbar = reinterpret_cast<float*>(ws + w.kbar);
-  HF_TRY(launch_pool(*cfg, Q, n_q, cfg->block_q, t_m, qbar, s));
-  HF_TRY(launch_pool(*cfg, K_win, n_kv, cfg->block_kv, t_n, kbar, s));
+  HF_TRY(launch_pool_both(*cfg, Q, n_q, t_m, K_win, n_kv, t_n, qbar, kbar, s));
   return launch_score_select(*cfg, qbar, kbar, t_m, t_n, k, block_idx, scores_or_null, s);
 }
 
@@ -225,7 +225,7 @@ int hf_hybrid_attn_fwd(const hf_config* cfg, const void* Q, int32_t n_q, const v
   void* o_local = static_cast<char*>(workspace) + w.olocal;
   HF_TRY(launch_attn(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, o_local, s));
   return launch_readout(*cfg, Q, n_q, o_local, static_cast<const float*>(state_or_null), rope_cos_q,
-                        rope_sin_q, O, s);
+                        rope_sin_q, static_cast<char*>(workspace) + w.planes, O, s);
 }
 
 }  // extern "C"

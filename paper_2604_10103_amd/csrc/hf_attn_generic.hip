@@ -6,6 +6,8 @@
 //   scores : lane = key (64 keys per step), q broadcast from LDS, K row read by its lane
 //   softmax: online (running max m, running sum l) in the exp2 domain, wave reductions
 //   P V    : lanes = value features, p broadcast with a lane read, V row read coalesced
+#include <stdlib.h>
+
 #include "hf_common.h"
 
 namespace hf {
@@ -137,6 +139,9 @@ int launch_attn_generic(const hf_config& c, const void* Q, int n_q, const void* 
 int launch_attn_mfma(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
                      const int32_t* idx, int k, void* O_local, hipStream_t s);  // hf_attn_mfma.hip
 bool attn_mfma_supported(const hf_config& c);
+int launch_attn_w64(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
+                    const int32_t* idx, int k, void* O_local, hipStream_t s);  // hf_attn_w64.hip
+bool attn_w64_supported(const hf_config& c);
 
 int launch_attn(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
                 const int32_t* idx, int k, void* O_local, hipStream_t s) {
@@ -144,6 +149,9 @@ int launch_attn(const hf_config& c, const void* Q, int n_q, const void* K, const
     set_error("grid too large");
     return HF_ERR_SHAPE;
   }
+  const char* pick = getenv("HF_ATTN_KERNEL");  // development switch between the MFMA variants
+  const bool want_wg = pick && pick[0] == 'g';
+  if (attn_w64_supported(c) && !want_wg) return launch_attn_w64(c, Q, n_q, K, V, n_kv, idx, k, O_local, s);
   if (attn_mfma_supported(c)) return launch_attn_mfma(c, Q, n_q, K, V, n_kv, idx, k, O_local, s);
   return launch_attn_generic(c, Q, n_q, K, V, n_kv, idx, k, O_local, s);
 }

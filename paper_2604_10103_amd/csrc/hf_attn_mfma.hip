@@ -1,36 +1,43 @@
 // Block-sparse flash forward (Eq. 5) on bf16 MFMA for gfx950: head_dim 128, block_q 64 or 128.
 //
 // One workgroup owns one query block; each of its wavefronts owns 32 query rows and walks the
-// block's selected KV blocks in tiles of 64 keys.  The products are formed TRANSPOSED so that
+// block's selected KV blocks in tiles of 32 keys.  The products are formed TRANSPOSED so that
 // every softmax statistic is private to a lane:
 //
-//   S^T (keys x queries) = K_tile (A operand, from LDS)  x  Q^T (B operand, registers)
-//   O^T (d x queries)   += V_tile^T (A operand, LDS transpose read)  x  P^T (B operand, registers)
+//   S^T (keys x queries) = K_tile (A operand, from LDS)   x  Q^T (B operand, registers)
+//   O^T (d x queries)   += V_tile^T (A operand, from LDS) x  P^T (B operand, registers)
 //
-// With the 32x32x16 MFMA a lane then holds, for ONE query, 16 keys of each 32-key sub-tile:
-// row max and row sum are in-lane reductions plus one exchange with lane^32, the rescale
-// factor is a per-lane scalar, and the exp'd accumulators of S^T are, after rounding to bf16,
-// already the B operand of the second product (the k index of that MFMA is bound to the keys
-// the lane holds; V^T fragments are fetched with the matching key order by two
-// ds_read_b64_tr_b16 each).  K and V tiles are staged in LDS in their memory layout
-// (key-major), the next tile travels global -> registers while the current one is consumed.
+// With the 32x32x16 MFMA a lane then holds, for ONE query, 16 of the tile's 32 scores: row max
+// and row sum are in-lane reductions plus one exchange with lane^32, the rescale factor is a
+// per-lane scalar, and the exp'd accumulators of S^T are, after rounding to bf16, already the
+// B operand of the second product.  The k index of that MFMA is thereby bound to the order in
+// which a lane holds keys, so V is transposed on its way into LDS with the key pairs stored in
+// that order: a V^T fragment is one conflict-free 16-byte read.
+//
+// The CU's LDS port is what bounds this kernel at block_q 64: every query block stages its own
+// 8 KB of K and 8 KB of V per 32 keys (LDS stores run at 64 B/clk), which at full MFMA rate is
+// exactly that port's throughput, and every wavefront's LDS round trips queue behind it.  LDS
+// holds two tiles (ping-pong): while tile t is consumed, tile t+1 moves registers -> LDS and
+// tile t+2 global -> registers (buffer loads, no branches); one workgroup barrier per tile.
+// Operand fragments are read a phase ahead of the MFMAs that use them, so that the LDS latency
+// of a wavefront overlaps its own softmax and matrix work.
 #include "hf_common.h"
 
 namespace hf {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
 constexpr int D = 128;
-constexpr int TK = 64;      // keys per tile
-constexpr int KSTR = 272;   // bytes per key row of the K tile in LDS (256 + 16: conflict-free 16-byte operand reads)
-constexpr int VSTR = 320;   // bytes per key row of the V tile in LDS (256 + 64: conflict-free transpose reads)
-
-typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+constexpr int TK = 32;      // keys per tile
+constexpr int KSTR = 272;   // bytes per key row of a K tile in LDS (256 + 16: conflict-free 16-byte operand reads)
+constexpr int VSTRD = 36;   // dwords per feature row of the V^T image: 2 tiles x 16 key pairs + 4 (conflict-free reads)
+constexpr int OSTR = 272;   // bytes per query row of the staged output
+constexpr int KTILE = TK * KSTR;
+constexpr float kRescaleThreshold = 8.0f;  // log2 units: rescale only when a row max grew by more than 2^8
 
 template <int NW>
 __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
@@ -39,9 +46,12 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
     int total_items, float c_scale, bf16_t* __restrict__ O) {
   constexpr int NT = 64 * NW;
   constexpr int BQ = 32 * NW;
-  constexpr int CPT = (TK * D * 2 / 16) / NT;  // 16-byte chunks of a tile per thread
-  __shared__ __attribute__((aligned(16))) char sK[TK * KSTR];
-  __shared__ __attribute__((aligned(16))) char sV[TK * VSTR];
+  constexpr int CPT = (TK * D * 2 / 16) / NT;  // 16-byte chunks of a K tile per thread (4 or 2)
+  constexpr int IPT = CPT / 2;                 // (key pair, feature group) items of a V tile per thread
+  __shared__ __attribute__((aligned(16))) char smem[2 * KTILE + D * VSTRD * 4];
+  char* const sK = smem;                                                   // two K tiles
+  uint32_t* const sVt = reinterpret_cast<uint32_t*>(smem + 2 * KTILE);     // V^T, both tiles side by side
+  static_assert(BQ * OSTR <= 2 * KTILE + D * VSTRD * 4, "staged output must fit in the tiles");
 
   // consecutive workgroup ids go to consecutive XCDs: give every XCD one contiguous run of
   // (head, query block) items so that its L2 sees few heads
@@ -75,141 +85,199 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
   for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[dt][r] = 0.0f;
-  float m_run = -INFINITY, l_run = 0.0f;
+  float m_ref = -INFINITY, l_run = 0.0f;
 
-  uint4 kreg[CPT], vreg[CPT];
-  auto gload = [&](int t) -> int {
-    const int s = t / subs, sub = t - s * subs;
-    const int jb = row_idx ? row_idx[s] : s;
-    int start = 0, valid = 0;
-    if ((unsigned)jb < (unsigned)t_n) {  // an out-of-range block index contributes nothing
-      start = jb * bkv + TK * sub;
-      valid = max(0, min(TK, min(n_kv, (jb + 1) * bkv) - start));
-    }
+  // ---- tile list: (selected block, 32-key part).  Tiles past the end of the list and
+  // out-of-range block indices give (0, 0): such a tile reads real rows and is masked entirely.
+  int cur_s = 0, cur_sub = 0;
+  auto next_tile = [&](int& start, int& valid) {
+    const int sc = min(cur_s, nsel - 1);
+    const int jb = row_idx ? row_idx[sc] : sc;
+    const bool ok = (cur_s < nsel) && ((unsigned)jb < (unsigned)t_n);
+    const int st = jb * bkv + TK * cur_sub;
+    start = ok ? st : 0;
+    valid = ok ? max(0, min(TK, min(n_kv, (jb + 1) * bkv) - st)) : 0;
+    if (++cur_sub == subs) { cur_sub = 0; ++cur_s; }
+  };
+
+  // ---- staging.  Loads go through buffer resources that end at the head's last key: rows past
+  // n_kv (the only rows of a tile that can be missing) read as zero without a branch; every
+  // offset sits in the vector operand, which is what the hardware range check looks at.
+  const __amdgpu_buffer_rsrc_t k_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(Kh), 0, n_kv * (D * 2), 0x00020000);
+  const __amdgpu_buffer_rsrc_t v_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(Vh), 0, n_kv * (D * 2), 0x00020000);
+  const int grp = tid & 15;                                  // 16-byte feature group
+  const int k_ld_off = (tid >> 4) * (D * 2) + grp * 16;      // K: row (tid>>4) + (NT/16) i
+  const int sub4 = lane >> 4;                                // V: which of 4 adjacent key pairs
+  const int v_key_lane = 8 * (sub4 >> 1) + 2 * (sub4 & 1);
+  auto gload = [&](int start, u32x4 (&kreg)[CPT], u32x4 (&vreg)[CPT]) {
+    const int kb = k_ld_off + start * (D * 2);
 #pragma unroll
-    for (int i = 0; i < CPT; ++i) {
-      const int c = tid + NT * i, row = c >> 4, col = c & 15;
-      if (row < valid) {
-        const size_t off = (size_t)(start + row) * D + col * 8;
-        kreg[i] = *reinterpret_cast<const uint4*>(Kh + off);
-        vreg[i] = *reinterpret_cast<const uint4*>(Vh + off);
-      } else {
-        kreg[i] = make_uint4(0, 0, 0, 0);
-        vreg[i] = make_uint4(0, 0, 0, 0);
+    for (int i = 0; i < CPT; ++i) kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, kb + i * (NT / 16) * (D * 2), 0, 0);
+#pragma unroll
+    for (int j = 0; j < IPT; ++j) {
+      const int cb = wave * IPT + j;  // = 2 t2 + hh
+      const int key = 16 * (cb >> 1) + 4 * (cb & 1) + v_key_lane;
+      const int vb = (start + key) * (D * 2) + grp * 16;
+      vreg[2 * j] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, vb, 0, 0);
+      vreg[2 * j + 1] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, vb + D * 2, 0, 0);
+    }
+  };
+  // V^T image: row = feature, dword column = 16 (tile parity) + key pair in MFMA order
+  // (8 t2 + 4 hh + 2 x + y), rotated by 4 dwords per 16 features so that the dword stores of a
+  // wavefront hit distinct banks
+  const int vt_rot = 4 * ((grp >> 1) & 7);
+  auto lstore = [&](int par, const u32x4 (&kreg)[CPT], const u32x4 (&vreg)[CPT]) {
+#pragma unroll
+    for (int i = 0; i < CPT; ++i)
+      *reinterpret_cast<u32x4*>(sK + par * KTILE + ((tid >> 4) + (NT / 16) * i) * KSTR + grp * 16) = kreg[i];
+#pragma unroll
+    for (int j = 0; j < IPT; ++j) {
+      const int col = (16 * par + 4 * (wave * IPT + j) + sub4 + vt_rot) & 31;
+      const u32x4 a = vreg[2 * j], b = vreg[2 * j + 1];  // rows key and key + 1
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        const int f = 8 * grp + 2 * p;
+        sVt[f * VSTRD + col] = __builtin_amdgcn_perm(b[p], a[p], 0x05040100u);        // feature f: (key, key + 1)
+        sVt[(f + 1) * VSTRD + col] = __builtin_amdgcn_perm(b[p], a[p], 0x07060302u);  // feature f + 1
       }
     }
-    return valid;
   };
-  auto lstore = [&]() {
+
+  // per-lane LDS read offsets
+  const char* k_rd = sK + l32 * KSTR + 16 * h;  // + par KTILE + 32 s
+  int v_row[4], v_rot[4];
 #pragma unroll
-    for (int i = 0; i < CPT; ++i) {
-      const int c = tid + NT * i, row = c >> 4, col = c & 15;
-      *reinterpret_cast<uint4*>(sK + row * KSTR + col * 16) = kreg[i];
-      *reinterpret_cast<uint4*>(sV + row * VSTR + col * 16) = vreg[i];
-    }
-  };
+  for (int dt = 0; dt < 4; ++dt) {
+    v_row[dt] = (32 * dt + l32) * VSTRD;
+    v_rot[dt] = 4 * ((2 * dt + (l32 >> 4)) & 7) + 4 * h;
+  }
 
-  // per-lane LDS offsets
-  const int k_off = l32 * KSTR + 16 * h;                                   // + 32*kt*KSTR + 32*s
-  const int g = lane >> 4, i16 = lane & 15;
-  // transpose read: lane i of a 16-lane group points at key (i>>2), 4 features from 4*(i&3);
-  // it receives keys 0..3 of feature i.  Group g serves features 16*(g&1).., keys 4*(g>>1)..
-  const int v_off = (4 * (g >> 1) + (i16 >> 2)) * VSTR + (16 * (g & 1) + 4 * (i16 & 3)) * 2;
-
-  int valid_cur = gload(0);
-  lstore();
+  // ---- prologue: tile 0 in LDS, tiles 1 and 2 on their way in two sets of staging registers.
+  // Two tiles in flight per workgroup cover the global-load latency (one iteration is shorter
+  // than a trip to HBM).
+  u32x4 kregA[CPT], vregA[CPT], kregB[CPT], vregB[CPT];
+  int start_t, valid0, valid1, valid2;
+  next_tile(start_t, valid0);
+  gload(start_t, kregA, vregA);
+  lstore(0, kregA, vregA);
+  next_tile(start_t, valid1);
+  gload(start_t, kregA, vregA);   // tile 1
+  next_tile(start_t, valid2);
+  gload(start_t, kregB, vregB);   // tile 2
   __syncthreads();
 
-  for (int t = 0; t < ntiles; ++t) {
-    int valid_next = 0;
-    if (t + 1 < ntiles) valid_next = gload(t + 1);
+  // One tile: consume LDS half `par`, move tile t+1 (staging set `kr`, `vr`) to the other half,
+  // refill that set with tile t+3.  One barrier per tile.
+  auto tile_step = [&](const int par, const int valid_cur, int& valid_new, u32x4 (&kr)[CPT], u32x4 (&vr)[CPT]) {
+    // ---- S^T = K Q^T : 32 keys, 8 steps over d in two independent accumulation chains
+    f32x16 sa, sb;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { sa[r] = 0.0f; sb[r] = 0.0f; }
+#pragma unroll
+    for (int s = 0; s < 8; s += 2) {
+      const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(k_rd + par * KTILE + 32 * s);
+      const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(k_rd + par * KTILE + 32 * s + 32);
+      sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[s], sa, 0, 0, 0);
+      sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[s + 1], sb, 0, 0, 0);
+    }
 
-    // ---- S^T = K Q^T : 2 sub-tiles of 32 keys, 8 steps over d
-    f32x16 sacc[2];
+    // ---- tile t+1: registers -> the other LDS half; tile t+3: global -> the same registers
+    lstore(par ^ 1, kr, vr);
+    next_tile(start_t, valid_new);
+    gload(start_t, kr, vr);
+
+    f32x16 sacc;
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
+    for (int r = 0; r < 16; ++r) sacc[r] = sa[r] + sb[r];
+    if (valid_cur < TK) {  // keys that do not exist never contribute
 #pragma unroll
-      for (int r = 0; r < 16; ++r) sacc[kt][r] = 0.0f;
-#pragma unroll
-    for (int s = 0; s < 8; ++s)
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(sK + k_off + 32 * kt * KSTR + 32 * s);
-        sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[s], sacc[kt], 0, 0, 0);
+      for (int r = 0; r < 16; ++r) {
+        const int key = 8 * (r >> 2) + 4 * h + (r & 3);
+        if (key >= valid_cur) sacc[r] = -INFINITY;
       }
-    if (valid_cur < TK) {  // short last block: keys that do not exist never contribute
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = 32 * kt + 8 * (r >> 2) + 4 * h + (r & 3);
-          if (key >= valid_cur) sacc[kt][r] = -INFINITY;
-        }
     }
 
     // ---- online softmax in the exp2 domain; statistics are per lane (= per query)
-    float mx = sacc[0][0];
+    float mx = fmaxf(sacc[0], sacc[1]);
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
+    for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(sacc[r], sacc[r + 1]));
+    {
+      const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+      mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1])) * c_scale;  // both lanes of a query agree
+    }
+    // lazy rescale: keep the reference max unless some row's max grew by more than the threshold
+    if (__any(mx > m_ref + kRescaleThreshold)) {
+      const float m_new = fmaxf(m_ref, mx);
+      const float m_use = (m_new == -INFINITY) ? 0.0f : m_new;  // nothing seen yet: keep exp2 finite
+      const float alpha = __builtin_amdgcn_exp2f(m_ref - m_use);
+      m_ref = m_new;
+      l_run *= alpha;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kt][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-    const float m_new = fmaxf(m_run, mx * c_scale);
-    const float m_use = (m_new == -INFINITY) ? 0.0f : m_new;  // nothing seen yet: keep exp2 finite
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-    m_run = m_new;
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+    }
+    const float m_use = (m_ref == -INFINITY) ? 0.0f : m_ref;
     float psum = 0.0f;
-    bf16x8 pf[2][2];
+    bf16x8 pf[2];
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float p = __builtin_amdgcn_exp2f(fmaf(sacc[kt][r], c_scale, -m_use));
-        psum += p;
-        pf[kt][r >> 3][r & 7] = static_cast<__bf16>(p);
-      }
-    l_run = l_run * alpha + psum;
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+    for (int r = 0; r < 16; ++r) {
+      const float p = __builtin_amdgcn_exp2f(fmaf(sacc[r], c_scale, -m_use));
+      psum += p;
+      pf[r >> 3][r & 7] = static_cast<__bf16>(p);
+    }
+    l_run += psum;
 
-    // ---- O^T += V^T P^T : 4 steps of 16 keys, 4 tiles of 32 features
+    // ---- O^T += V^T P^T : 2 steps of 16 keys, 4 tiles of 32 features
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
+    for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
-      for (int t2 = 0; t2 < 2; ++t2) {
-        const int key0 = 32 * kt + 16 * t2;
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt) {
-          const char* p0 = sV + v_off + key0 * VSTR + 64 * dt;
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p0));
-          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p0 + 8 * VSTR));
-          const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[kt][t2], o[dt], 0, 0, 0);
-        }
+      for (int dt = 0; dt < 4; ++dt) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&sVt[v_row[dt] + ((16 * par + 8 * t2 + v_rot[dt]) & 31)]);
+        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[t2], o[dt], 0, 0, 0);
       }
 
-    __syncthreads();  // every wavefront is done with this tile
-    if (t + 1 < ntiles) lstore();
-    __syncthreads();
-    valid_cur = valid_next;
+    __syncthreads();  // tile t is consumed everywhere, tile t+1 is complete in LDS
+  };
+
+  // tiles in pairs so that the staging sets alternate with compile-time names; a surplus tile
+  // of an odd list is empty (fully masked) and changes nothing
+  int va = valid0, vb = valid1, vc = valid2;  // real keys of tiles t, t+1, t+2
+  for (int t = 0; t < ntiles; t += 2) {
+    int vd, ve;
+    tile_step(0, va, vd, kregA, vregA);  // consumes tile t,   stores t+1 (set A), fetches t+3 into A
+    tile_step(1, vb, ve, kregB, vregB);  // consumes tile t+1, stores t+2 (set B), fetches t+4 into B
+    va = vc;
+    vb = vd;
+    vc = ve;
   }
 
-  // ---- normalise and store: lane holds query l32, features 32 dt + 8 (r/4) + 4 h + (r%4)
-  const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
+  // ---- normalise, transpose through LDS (the tiles are dead now) and store coalesced rows
+  float l_tot;
+  {
+    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(l_run), __float_as_uint(l_run), false, false);
+    l_tot = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+  }
   const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
-  if (q_row < n_q) {
-    bf16_t* op = Oh + (size_t)q_row * D + 4 * h;
+  char* stage = smem;
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
+  for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-      for (int rq = 0; rq < 4; ++rq) {
-        uint2 w;
-        w.x = (uint32_t)f32_to_bf16(o[dt][4 * rq] * inv) | ((uint32_t)f32_to_bf16(o[dt][4 * rq + 1] * inv) << 16);
-        w.y = (uint32_t)f32_to_bf16(o[dt][4 * rq + 2] * inv) | ((uint32_t)f32_to_bf16(o[dt][4 * rq + 3] * inv) << 16);
-        *reinterpret_cast<uint2*>(op + 32 * dt + 8 * rq) = w;
-      }
+    for (int rq = 0; rq < 4; ++rq) {
+      uint2 w;
+      w.x = (uint32_t)f32_to_bf16(o[dt][4 * rq] * inv) | ((uint32_t)f32_to_bf16(o[dt][4 * rq + 1] * inv) << 16);
+      w.y = (uint32_t)f32_to_bf16(o[dt][4 * rq + 2] * inv) | ((uint32_t)f32_to_bf16(o[dt][4 * rq + 3] * inv) << 16);
+      *reinterpret_cast<uint2*>(stage + (32 * wave + l32) * OSTR + (32 * dt + 8 * rq + 4 * h) * 2) = w;
+    }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < (BQ * 16) / NT; ++i) {
+    const int c = tid + NT * i, row = c >> 4, col = c & 15;
+    if (qb * BQ + row < n_q)
+      *reinterpret_cast<uint4*>(Oh + (size_t)(qb * BQ + row) * D + col * 8) =
+          *reinterpret_cast<const uint4*>(stage + row * OSTR + col * 16);
   }
 }
 
@@ -219,8 +287,12 @@ bool attn_mfma_supported(const hf_config& c) {
   return c.dtype == HF_BF16 && c.head_dim == 128 && (c.block_q == 64 || c.block_q == 128);
 }
 
+// byte offsets inside one head are 32-bit in the buffer loads
+constexpr int kMfmaMaxKeys = 1 << 23;
+
 int launch_attn_mfma(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
                      const int32_t* idx, int k, void* O_local, hipStream_t s) {
+  if (n_kv >= kMfmaMaxKeys) { set_error("window longer than %d keys", kMfmaMaxKeys); return HF_ERR_SHAPE; }
   const int BH = c.batch * c.heads;
   const int t_m = (n_q + c.block_q - 1) / c.block_q, t_n = (n_kv + c.block_kv - 1) / c.block_kv;
   const long long total = (long long)BH * t_m;

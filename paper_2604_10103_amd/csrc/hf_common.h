@@ -81,12 +81,15 @@ struct Dims {
 int launch_fill_zero(float* p, size_t n, hipStream_t s);
 int launch_absorb(const hf_config& c, float* state, const void* K, const void* V, int n,
                   const float* cosv, const float* sinv, hipStream_t s);
-int launch_pool(const hf_config& c, const void* X, int n, int b, int t, float* pooled, hipStream_t s);
-int launch_score_select(const hf_config& c, const float* qbar, const float* kbar, int t_m, int t_n,
+int launch_pool_both(const hf_config& c, const void* Q, int n_q, int t_m, const void* K, int n_kv, int t_n,
+                     float* qbar, float* kbar_t, hipStream_t s);
+int launch_score_select(const hf_config& c, const float* qbar, const float* kbar_t, int t_m, int t_n,
                         int k, int32_t* idx, float* scores, hipStream_t s);
 int launch_attn(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
                 const int32_t* idx, int k, void* O_local, hipStream_t s);
 int launch_readout(const hf_config& c, const void* Q, int n_q, const void* O_local,
-                   const float* state, const float* cosq, const float* sinq, void* O, hipStream_t s);
+                   const float* state, const float* cosq, const float* sinq, void* planes, void* O,
+                   hipStream_t s);
+size_t readout_planes_bytes(const hf_config& c);  // scratch for the bf16 planes of the state
 
 }  // namespace hf

@@ -94,7 +94,8 @@ __global__ __launch_bounds__(256) void readout_fma_kernel(const T* __restrict__ 
 }  // namespace
 
 int launch_readout_mfma(const hf_config& c, const void* Q, int n_q, const void* O_local, const float* state,
-                        const float* cosq, const float* sinq, void* O, hipStream_t s);  // hf_readout_mfma.hip
+                        const float* cosq, const float* sinq, void* planes, void* O,
+                        hipStream_t s);  // hf_readout_mfma.hip
 bool readout_mfma_supported(const hf_config& c);
 
 template <typename T, int D>
@@ -123,8 +124,8 @@ static int launch_readout_fma(const hf_config& c, const void* Q, int n_q, const 
 }
 
 int launch_readout(const hf_config& c, const void* Q, int n_q, const void* O_local, const float* state,
-                   const float* cosq, const float* sinq, void* O, hipStream_t s) {
-  if (readout_mfma_supported(c)) return launch_readout_mfma(c, Q, n_q, O_local, state, cosq, sinq, O, s);
+                   const float* cosq, const float* sinq, void* planes, void* O, hipStream_t s) {
+  if (readout_mfma_supported(c)) return launch_readout_mfma(c, Q, n_q, O_local, state, cosq, sinq, planes, O, s);
   if (c.dtype == HF_F32) {
     return c.head_dim == 128 ? launch_readout_fma<float, 128>(c, Q, n_q, O_local, state, cosq, sinq, O, s)
                              : launch_readout_fma<float, 64>(c, Q, n_q, O_local, state, cosq, sinq, O, s);

@@ -1,27 +1,36 @@
 // Block importance scores and Top-K block selection (Eq. 4 and the mask M of the sparse branch).
 //
-//  pool kernel    : one wavefront per block of b tokens; 16-byte loads, fp32 sums, mean over the
-//                   block's real length (the last block may be short).  HBM-bound streaming read.
-//  select kernel  : one wavefront per query-block row.  Lane j computes A[i][j] = qbar_i . kbar_j
-//                   for its blocks, the row of scores is kept in LDS, every block gets its rank
-//                   (number of blocks that beat it; ties go to the lower index), the k blocks of
-//                   rank < k are written in ascending order with a ballot prefix sum.
+//  pool kernel    : one launch for Q and K_win, one wavefront per block of b tokens; 16-byte
+//                   loads, fp32 sums, mean over the block's real length (the last block may be
+//                   short).  HBM-bound streaming read.
+//  select kernel  : one workgroup per query-block row.  Thread j computes A[i][j] = qbar_i . kbar_j,
+//                   the row of scores is kept in LDS, every block gets its rank (number of blocks
+//                   that beat it; ties go to the lower index), the k blocks of rank < k are
+//                   written in ascending order with a ballot prefix sum.
 #include "hf_common.h"
 
 namespace hf {
 
 namespace {
 
+// Pooled keys are stored feature-group-major, kbar_t[bh][D/4][t_n][4], so that in the scoring
+// kernel consecutive lanes (= consecutive KV blocks) read consecutive 16-byte groups.
+// Pooled queries stay row-major, qbar[bh][t_m][D].
 template <typename T, int D>
-__global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ X, int n, int b, int t,
-                                                   float* __restrict__ pooled) {
+__global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ Q, int n_q, int bq, int t_m,
+                                                   const T* __restrict__ K, int n_kv, int bkv, int t_n,
+                                                   float* __restrict__ qbar, float* __restrict__ kbar_t) {
   constexpr int E = Elem<T>::kPer16B;  // elements per 16-byte load
   constexpr int LPR = D / E;           // lanes covering one row
   constexpr int RPP = kWave / LPR;     // rows per pass of the wavefront
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int blk = blockIdx.x * 4 + wave;
+  int blk = blockIdx.x * 4 + wave;
   const int bh = blockIdx.y;
-  if (blk >= t) return;
+  if (blk >= t_m + t_n) return;
+  const bool is_q = blk < t_m;
+  if (!is_q) blk -= t_m;
+  const T* X = is_q ? Q : K;
+  const int n = is_q ? n_q : n_kv, b = is_q ? bq : bkv;
   const int r0 = blk * b, r1 = min(n, r0 + b);
   const int sub = lane / LPR, col = (lane % LPR) * E;
   const T* base = X + (size_t)bh * n * D + col;
@@ -29,13 +38,13 @@ __global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ X, int 
 #pragma unroll
   for (int e = 0; e < E; ++e) acc[e] = 0.0f;
   int r = r0 + sub;
-  // four independent loads in flight per lane
-  for (; r + 3 * RPP < r1; r += 4 * RPP) {
-    float v[4][E];
+  // eight independent 16-byte loads in flight per lane
+  for (; r + 7 * RPP < r1; r += 8 * RPP) {
+    float v[8][E];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) load16B<T>(base + (size_t)(r + u * RPP) * D, v[u]);
+    for (int u = 0; u < 8; ++u) load16B<T>(base + (size_t)(r + u * RPP) * D, v[u]);
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
+    for (int u = 0; u < 8; ++u)
 #pragma unroll
       for (int e = 0; e < E; ++e) acc[e] += v[u][e];
   }
@@ -51,95 +60,113 @@ __global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ X, int 
     for (int e = 0; e < E; ++e) acc[e] += __shfl_xor(acc[e], o, kWave);
   if (sub == 0) {
     const float inv = 1.0f / (float)(r1 - r0);
-    float* out = pooled + ((size_t)bh * t + blk) * D + col;
 #pragma unroll
-    for (int e = 0; e < E; e += 4)
-      *reinterpret_cast<float4*>(out + e) =
-          make_float4(acc[e] * inv, acc[e + 1] * inv, acc[e + 2] * inv, acc[e + 3] * inv);
+    for (int e = 0; e < E; e += 4) {
+      const float4 v = make_float4(acc[e] * inv, acc[e + 1] * inv, acc[e + 2] * inv, acc[e + 3] * inv);
+      if (is_q)
+        *reinterpret_cast<float4*>(qbar + ((size_t)bh * t_m + blk) * D + col + e) = v;
+      else
+        *reinterpret_cast<float4*>(kbar_t + (((size_t)bh * (D / 4) + (col + e) / 4) * t_n + blk) * 4) = v;
+    }
   }
 }
 
+// One workgroup per query-block row: thread j scores KV block j, ranks it against the row held
+// in LDS and the kept blocks are written in ascending order (ballot + cross-wave prefix).
 template <int D>
 __global__ __launch_bounds__(256) void score_select_kernel(const float* __restrict__ qbar,
-                                                           const float* __restrict__ kbar, int t_m, int t_n,
+                                                           const float* __restrict__ kbar_t, int t_m, int t_n,
                                                            int k, int32_t* __restrict__ idx,
                                                            float* __restrict__ scores) {
-  extern __shared__ float smem[];  // [4][D] pooled query rows, then [4][t_n] scores
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int row = blockIdx.x * 4 + wave;
-  const int bh = blockIdx.y;
-  if (row >= t_m) return;  // whole wavefront leaves; no workgroup barrier is used below
-  float* sq = smem + wave * D;
-  float* sc = smem + 4 * D + (size_t)wave * t_n;
-  const float* q = qbar + ((size_t)bh * t_m + row) * D;
-  for (int c = lane; c < D; c += kWave) sq[c] = q[c];
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): LDS writes of this wavefront are visible
+  extern __shared__ __attribute__((aligned(16))) float smem[];  // [D] pooled query, then scores padded to 4
+  __shared__ int wave_count[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int row = blockIdx.x, bh = blockIdx.y;
+  float* sq = smem;
+  float* sc = smem + D;
+  const int t_pad = (t_n + 3) & ~3;
+  if (tid < D) sq[tid] = qbar[((size_t)bh * t_m + row) * D + tid];
+  for (int j = t_n + tid; j < t_pad; j += 256) sc[j] = -INFINITY;  // padding never outranks a block
+  __syncthreads();
 
-  for (int j = lane; j < t_n; j += kWave) {
-    const float* kr = kbar + ((size_t)bh * t_n + j) * D;
-    float a = 0.0f;
+  const float4* kt = reinterpret_cast<const float4*>(kbar_t) + (size_t)bh * (D / 4) * t_n;
+  for (int j = tid; j < t_n; j += 256) {
+    float a0 = 0.0f, a1 = 0.0f;
 #pragma unroll 8
-    for (int c = 0; c < D; c += 4) {
-      const float4 kv = *reinterpret_cast<const float4*>(kr + c);
-      a = fmaf(sq[c], kv.x, a);
-      a = fmaf(sq[c + 1], kv.y, a);
-      a = fmaf(sq[c + 2], kv.z, a);
-      a = fmaf(sq[c + 3], kv.w, a);
+    for (int c = 0; c < D / 4; c += 2) {
+      const float4 k0 = kt[(size_t)c * t_n + j], k1 = kt[(size_t)(c + 1) * t_n + j];
+      const float4 q0 = *reinterpret_cast<const float4*>(sq + 4 * c);
+      const float4 q1 = *reinterpret_cast<const float4*>(sq + 4 * c + 4);
+      a0 = fmaf(q0.x, k0.x, a0); a0 = fmaf(q0.y, k0.y, a0); a0 = fmaf(q0.z, k0.z, a0); a0 = fmaf(q0.w, k0.w, a0);
+      a1 = fmaf(q1.x, k1.x, a1); a1 = fmaf(q1.y, k1.y, a1); a1 = fmaf(q1.z, k1.z, a1); a1 = fmaf(q1.w, k1.w, a1);
     }
+    const float a = a0 + a1;
     sc[j] = a;
     if (scores) scores[((size_t)bh * t_m + row) * t_n + j] = a;
   }
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_s_waitcnt(0xc07f);
+  __syncthreads();
 
   int32_t* out = idx + ((size_t)bh * t_m + row) * k;
   int base = 0;
-  for (int j0 = 0; j0 < t_n; j0 += kWave) {
-    const int j = j0 + lane;
+  for (int j0 = 0; j0 < t_n; j0 += 256) {  // uniform trip count: barriers inside
+    const int j = j0 + tid;
     bool keep = false;
     if (j < t_n) {
       const float mine = sc[j];
       int rank = 0;
-      for (int o = 0; o < t_n; ++o) {
-        const float other = sc[o];
-        rank += (other > mine || (other == mine && o < j)) ? 1 : 0;
+      for (int o = 0; o < t_pad; o += 4) {
+        const float4 v = *reinterpret_cast<const float4*>(sc + o);
+        rank += (v.x > mine || (v.x == mine && o < j)) ? 1 : 0;
+        rank += (v.y > mine || (v.y == mine && o + 1 < j)) ? 1 : 0;
+        rank += (v.z > mine || (v.z == mine && o + 2 < j)) ? 1 : 0;
+        rank += (v.w > mine || (v.w == mine && o + 3 < j)) ? 1 : 0;
       }
       keep = rank < k;
     }
     const unsigned long long m = __ballot(keep);
-    const int pos = base + __popcll(m & ((1ull << lane) - 1ull));
+    if (lane == 0) wave_count[wave] = __popcll(m);
+    __syncthreads();
+    int pos = base + __popcll(m & ((1ull << lane) - 1ull));
+    int total = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const int cw = wave_count[w];
+      if (w < wave) pos += cw;
+      total += cw;
+    }
     if (keep && pos < k) out[pos] = j;
-    base += __popcll(m);
+    base += total;
+    __syncthreads();
   }
 }
 
 }  // namespace
 
-int launch_pool(const hf_config& c, const void* X, int n, int b, int t, float* pooled, hipStream_t s) {
+int launch_pool_both(const hf_config& c, const void* Q, int n_q, int t_m, const void* K, int n_kv, int t_n,
+                     float* qbar, float* kbar_t, hipStream_t s) {
   const int BH = c.batch * c.heads;
-  const dim3 grid((t + 3) / 4, BH), block(256);
+  const dim3 grid((t_m + t_n + 3) / 4, BH), block(256);
+#define HF_LAUNCH_POOL(T, DD)                                                                                  \
+  hipLaunchKernelGGL((pool_kernel<T, DD>), grid, block, 0, s, static_cast<const T*>(Q), n_q, c.block_q, t_m,   \
+                     static_cast<const T*>(K), n_kv, c.block_kv, t_n, qbar, kbar_t)
   if (c.dtype == HF_BF16) {
-    const bf16_t* x = static_cast<const bf16_t*>(X);
-    if (c.head_dim == 128) hipLaunchKernelGGL((pool_kernel<bf16_t, 128>), grid, block, 0, s, x, n, b, t, pooled);
-    else hipLaunchKernelGGL((pool_kernel<bf16_t, 64>), grid, block, 0, s, x, n, b, t, pooled);
+    if (c.head_dim == 128) HF_LAUNCH_POOL(bf16_t, 128); else HF_LAUNCH_POOL(bf16_t, 64);
   } else {
-    const float* x = static_cast<const float*>(X);
-    if (c.head_dim == 128) hipLaunchKernelGGL((pool_kernel<float, 128>), grid, block, 0, s, x, n, b, t, pooled);
-    else hipLaunchKernelGGL((pool_kernel<float, 64>), grid, block, 0, s, x, n, b, t, pooled);
+    if (c.head_dim == 128) HF_LAUNCH_POOL(float, 128); else HF_LAUNCH_POOL(float, 64);
   }
+#undef HF_LAUNCH_POOL
   return check_launch("hf_block_select(pool)");
 }
 
-int launch_score_select(const hf_config& c, const float* qbar, const float* kbar, int t_m, int t_n, int k,
+int launch_score_select(const hf_config& c, const float* qbar, const float* kbar_t, int t_m, int t_n, int k,
                         int32_t* idx, float* scores, hipStream_t s) {
   const int BH = c.batch * c.heads;
-  const dim3 grid((t_m + 3) / 4, BH), block(256);
-  const size_t smem = (size_t)(4 * c.head_dim + 4 * (size_t)t_n) * sizeof(float);
+  const dim3 grid(t_m, BH), block(256);
+  const size_t smem = (size_t)(c.head_dim + ((t_n + 3) & ~3)) * sizeof(float);
   if (c.head_dim == 128)
-    hipLaunchKernelGGL((score_select_kernel<128>), grid, block, smem, s, qbar, kbar, t_m, t_n, k, idx, scores);
+    hipLaunchKernelGGL((score_select_kernel<128>), grid, block, smem, s, qbar, kbar_t, t_m, t_n, k, idx, scores);
   else
-    hipLaunchKernelGGL((score_select_kernel<64>), grid, block, smem, s, qbar, kbar, t_m, t_n, k, idx, scores);
+    hipLaunchKernelGGL((score_select_kernel<64>), grid, block, smem, s, qbar, kbar_t, t_m, t_n, k, idx, scores);
   return check_launch("hf_block_select(select)");
 }
 

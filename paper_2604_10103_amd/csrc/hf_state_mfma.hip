@@ -46,13 +46,19 @@ template <bool kPlain>
 __global__ __launch_bounds__(256) void absorb_mfma_kernel(float* __restrict__ state, const bf16_t* __restrict__ K,
                                                           const bf16_t* __restrict__ V, int n, int tokens_per_slice,
                                                           const float* __restrict__ cosv,
-                                                          const float* __restrict__ sinv, int phi_kind, int BH) {
+                                                          const float* __restrict__ sinv, int phi_kind, int BH,
+                                                          int slices) {
   __shared__ __attribute__((aligned(16))) uint32_t Kt[D * SP];
   __shared__ __attribute__((aligned(16))) uint32_t Vt[D * SP];
   __shared__ float zs[D];
 
-  const int bh = blockIdx.y;
-  const int t0 = blockIdx.x * tokens_per_slice;
+  // Consecutive workgroup ids land on consecutive XCDs.  All slices of one (batch, head) are
+  // given to ONE XCD (head index mod 8), so the float atomics that add the partials to that
+  // head's state meet in a single L2 instead of bouncing between the XCDs' caches.
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int bh = xcd + 8 * (slot / slices);
+  if (bh >= BH) return;
+  const int t0 = (slot % slices) * tokens_per_slice;
   const int t1 = min(n, t0 + tokens_per_slice);
   if (t0 >= t1) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -201,7 +207,7 @@ int launch_absorb_mfma(const hf_config& c, float* state, const void* K, const vo
                        const float* cosv, const float* sinv, hipStream_t s) {
   const int BH = c.batch * c.heads;
   // slice length: a multiple of the 64-token chunk; default aims at ~2 workgroups per compute unit
-  static const int forced = env_int("HF_ABSORB_SLICE_TOKENS", 0);
+  const int forced = env_int("HF_ABSORB_SLICE_TOKENS", 0);
   int per;
   if (forced > 0) {
     per = (forced + CH - 1) / CH * CH;
@@ -215,12 +221,14 @@ int launch_absorb_mfma(const hf_config& c, float* state, const void* K, const vo
   const bool plain = (c.phi == HF_PHI_RELU) && cosv == nullptr;
   const bf16_t* Kp = static_cast<const bf16_t*>(K);
   const bf16_t* Vp = static_cast<const bf16_t*>(V);
+  const int heads_per_xcd = (BH + 7) / 8;
+  const dim3 grid(8 * heads_per_xcd * slices);
   if (plain) {
-    hipLaunchKernelGGL((absorb_mfma_kernel<true>), dim3(slices, BH), dim3(256), 0, s, state, Kp, Vp, n, per,
-                       cosv, sinv, c.phi, BH);
+    hipLaunchKernelGGL((absorb_mfma_kernel<true>), grid, dim3(256), 0, s, state, Kp, Vp, n, per, cosv, sinv,
+                       c.phi, BH, slices);
   } else {
-    hipLaunchKernelGGL((absorb_mfma_kernel<false>), dim3(slices, BH), dim3(256), 0, s, state, Kp, Vp, n, per,
-                       cosv, sinv, c.phi, BH);
+    hipLaunchKernelGGL((absorb_mfma_kernel<false>), grid, dim3(256), 0, s, state, Kp, Vp, n, per, cosv, sinv,
+                       c.phi, BH, slices);
   }
   return check_launch("hf_absorb_evicted");
 }
