@@ -82,13 +82,15 @@ def main():
     n_prefill_calls = max(1, w.evicted_frames // chunk_frames)
     prefill = [tuple(t.to(dev) for t in wl.make_evicted(w, c)) for c in range(n_prefill_calls)]
     ws_bytes = hf.hf_workspace_bytes(cfg, w.n_q, w.n_kv)
+    aws_bytes = hf.hf_absorb_workspace_bytes(cfg, w.n_q)
+    aws = torch.empty(aws_bytes, dtype=torch.uint8, device=dev) if aws_bytes else None
     for l in range(nl):
         Q, K, V = wl.make_qkv(w, layer=l)
         Ke, Ve = wl.make_evicted(w, 100 + l)
         st = torch.empty(hf.hf_state_bytes(cfg) // 4, dtype=torch.float32, device=dev)
         hf.hf_state_init(cfg, st)
         for (pk, pv) in prefill:
-            hf.hf_absorb_evicted(cfg, st, pk, pv)
+            hf.hf_absorb_evicted(cfg, st, pk, pv, workspace=aws)
         sets.append(dict(
             Q=Q.to(dev), K=K.to(dev), V=V.to(dev), Ke=Ke.to(dev), Ve=Ve.to(dev), st=st,
             idx=torch.empty((w.batch, w.heads, w.t_m, k), dtype=torch.int32, device=dev),
@@ -106,7 +108,7 @@ def main():
         hf.hf_hybrid_attn_fwd(cfg, s["Q"], s["K"], s["V"], s["idx"], s["st"], s["O"], s["ws"])
         if events is not None:
             events[2].record()
-        hf.hf_absorb_evicted(cfg, s["st"], s["Ke"], s["Ve"])
+        hf.hf_absorb_evicted(cfg, s["st"], s["Ke"], s["Ve"], workspace=aws)
         if events is not None:
             events[3].record()
 

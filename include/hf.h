@@ -85,16 +85,25 @@ HF_API int hf_state_bytes(const hf_config* cfg, size_t* bytes_out);
  * Uses a fill kernel (not a memset node), so it is safe to capture in a HIP graph. */
 HF_API int hf_state_init(const hf_config* cfg, void* state, void* stream);
 
+/* Bytes of scratch that let hf_absorb_evicted combine its per-slice partial sums without
+ * atomics (0 when the configuration has no such path).  Host-only. */
+HF_API int hf_absorb_workspace_bytes(const hf_config* cfg, int32_t n_tokens, size_t* bytes_out);
+
 /* Eq. 2, incremental form used at cache eviction: for every (b, h)
  *     L += sum_t R_t(phi(k_t))^T v_t      z += sum_t phi(k_t)
  * over the n_tokens evicted tokens K_ev, V_ev [B, H, n_tokens, d] (read-only).
  * rope_cos / rope_sin: fp32 [n_tokens, d/2] per-token rotation of adjacent feature pairs
  * (2p, 2p+1), shared by heads and batch, applied after phi to the L term only; both NULL =
  * identity.  The state is updated in place (fp32 accumulation; concurrent calls on the same
- * state from different streams are allowed only if the caller orders them). */
+ * state from different streams are allowed only if the caller orders them).
+ * workspace: optional scratch of >= hf_absorb_workspace_bytes(...) bytes, 256-byte aligned;
+ * with it the slices of one head are summed by a second small kernel (fast path), with NULL
+ * (or too small a buffer) they are added to the state with float atomics.  Same result up to
+ * fp32 summation order. */
 HF_API int hf_absorb_evicted(const hf_config* cfg, void* state,
                       const void* K_ev, const void* V_ev, int32_t n_tokens,
-                      const float* rope_cos, const float* rope_sin, void* stream);
+                      const float* rope_cos, const float* rope_sin,
+                      void* workspace, size_t workspace_bytes, void* stream);
 
 /* k of "sparse Top K" for a window of n_kv tokens (see keep_k / keep_ratio).  Host-only. */
 HF_API int hf_select_k(const hf_config* cfg, int32_t n_kv, int32_t* k_out);

@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     hf_state_bytes,
     hf_state_init,
     hf_absorb_evicted,
+    hf_absorb_workspace_bytes,
     hf_select_k,
     hf_workspace_bytes,
     hf_block_select,

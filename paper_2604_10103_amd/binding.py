@@ -73,12 +73,14 @@ def load():
     lib.hf_version.argtypes = []
     lib.hf_state_bytes.argtypes = [CP, ctypes.POINTER(SZ)]
     lib.hf_state_init.argtypes = [CP, P, P]
-    lib.hf_absorb_evicted.argtypes = [CP, P, P, P, I, P, P, P]
+    lib.hf_absorb_evicted.argtypes = [CP, P, P, P, I, P, P, P, SZ, P]
+    lib.hf_absorb_workspace_bytes.argtypes = [CP, I, ctypes.POINTER(SZ)]
     lib.hf_select_k.argtypes = [CP, I, ctypes.POINTER(I)]
     lib.hf_workspace_bytes.argtypes = [CP, I, I, ctypes.POINTER(SZ)]
     lib.hf_block_select.argtypes = [CP, P, I, P, I, P, P, P, SZ, P]
     lib.hf_hybrid_attn_fwd.argtypes = [CP, P, I, P, P, I, P, I, P, P, P, P, P, SZ, P]
-    for name in ("hf_state_bytes", "hf_state_init", "hf_absorb_evicted", "hf_select_k", "hf_workspace_bytes",
+    for name in ("hf_state_bytes", "hf_state_init", "hf_absorb_evicted", "hf_absorb_workspace_bytes", "hf_select_k",
+                 "hf_workspace_bytes",
                  "hf_block_select", "hf_hybrid_attn_fwd"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -133,6 +135,12 @@ def hf_select_k(cfg: hf_config, n_kv: int) -> int:
     return out.value
 
 
+def hf_absorb_workspace_bytes(cfg: hf_config, n_tokens: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().hf_absorb_workspace_bytes(ctypes.byref(cfg), n_tokens, ctypes.byref(out)))
+    return out.value
+
+
 def hf_workspace_bytes(cfg: hf_config, n_q: int, n_kv: int) -> int:
     out = ctypes.c_size_t(0)
     _check(load().hf_workspace_bytes(ctypes.byref(cfg), n_q, n_kv, ctypes.byref(out)))
@@ -146,7 +154,8 @@ def hf_state_init(cfg: hf_config, state: torch.Tensor) -> None:
     _check(load().hf_state_init(ctypes.byref(cfg), _dev(state, "state", torch.float32, (n,)), _stream()))
 
 
-def hf_absorb_evicted(cfg: hf_config, state, K_ev, V_ev, rope_cos=None, rope_sin=None) -> None:
+def hf_absorb_evicted(cfg: hf_config, state, K_ev, V_ev, rope_cos=None, rope_sin=None, workspace=None) -> None:
+    """workspace: optional uint8 GPU buffer of hf_absorb_workspace_bytes(cfg, n) bytes (atomic-free path)."""
     n = hf_state_bytes(cfg) // 4
     B, H, d = cfg.batch, cfg.heads, cfg.head_dim
     if K_ev.dim() != 4:
@@ -158,7 +167,7 @@ def hf_absorb_evicted(cfg: hf_config, state, K_ev, V_ev, rope_cos=None, rope_sin
         ctypes.byref(cfg), _dev(state, "state", torch.float32, (n,)),
         _dev(K_ev, "K_ev", _tdtype(cfg), shp), _dev(V_ev, "V_ev", _tdtype(cfg), shp), nt,
         _dev(rope_cos, "rope_cos", torch.float32, tab), _dev(rope_sin, "rope_sin", torch.float32, tab),
-        _stream()))
+        _dev(workspace, "workspace", torch.uint8), 0 if workspace is None else workspace.numel(), _stream()))
 
 
 def hf_block_select(cfg: hf_config, Q, K_win, block_idx, scores=None, workspace=None) -> None:

@@ -117,8 +117,17 @@ int hf_state_init(const hf_config* cfg, void* state, void* stream) {
                           static_cast<hipStream_t>(stream));
 }
 
+int hf_absorb_workspace_bytes(const hf_config* cfg, int32_t n_tokens, size_t* bytes_out) {
+  HF_TRY(check_cfg(cfg));
+  if (!bytes_out) { set_error("bytes_out is NULL"); return HF_ERR_NULL; }
+  HF_TRY(check_tokens(n_tokens, "n_tokens"));
+  *bytes_out = absorb_workspace_bytes(*cfg, n_tokens);
+  return HF_OK;
+}
+
 int hf_absorb_evicted(const hf_config* cfg, void* state, const void* K_ev, const void* V_ev,
-                      int32_t n_tokens, const float* rope_cos, const float* rope_sin, void* stream) {
+                      int32_t n_tokens, const float* rope_cos, const float* rope_sin, void* workspace,
+                      size_t workspace_bytes, void* stream) {
   HF_TRY(check_cfg(cfg));
   HF_TRY(check_ptr(state, "state", true));
   HF_TRY(check_ptr(K_ev, "K_ev", true));
@@ -130,8 +139,12 @@ int hf_absorb_evicted(const hf_config* cfg, void* state, const void* K_ev, const
   }
   HF_TRY(check_ptr(rope_cos, "rope_cos", false));
   HF_TRY(check_ptr(rope_sin, "rope_sin", false));
-  return launch_absorb(*cfg, static_cast<float*>(state), K_ev, V_ev, n_tokens, rope_cos, rope_sin,
-                       static_cast<hipStream_t>(stream));
+  if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 255u)) {
+    set_error("workspace is not 256-byte aligned");
+    return HF_ERR_ALIGN;
+  }
+  return launch_absorb(*cfg, static_cast<float*>(state), K_ev, V_ev, n_tokens, rope_cos, rope_sin, workspace,
+                       workspace ? workspace_bytes : 0, static_cast<hipStream_t>(stream));
 }
 
 int hf_select_k(const hf_config* cfg, int32_t n_kv, int32_t* k_out) {

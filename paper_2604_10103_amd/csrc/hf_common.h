@@ -80,7 +80,9 @@ struct Dims {
 // Launchers implemented in the .hip files.  All pointers are device pointers.
 int launch_fill_zero(float* p, size_t n, hipStream_t s);
 int launch_absorb(const hf_config& c, float* state, const void* K, const void* V, int n,
-                  const float* cosv, const float* sinv, hipStream_t s);
+                  const float* cosv, const float* sinv, void* workspace, size_t workspace_bytes,
+                  hipStream_t s);
+size_t absorb_workspace_bytes(const hf_config& c, int n);
 int launch_pool_both(const hf_config& c, const void* Q, int n_q, int t_m, const void* K, int n_kv, int t_n,
                      float* qbar, float* kbar_t, hipStream_t s);
 int launch_score_select(const hf_config& c, const float* qbar, const float* kbar_t, int t_m, int t_n,

@@ -2,9 +2,10 @@
 //
 //   L[i][j] += sum_t R_t(phi(k_t))[i] * v_t[j]        z[i] += sum_t phi(k_t)[i]
 //
+// This file: the fill kernel and the fp32-arithmetic absorb kernel (fp32 inputs, or head_dim 64).
 // The evicted tokens of one (batch, head) are cut into slices; a workgroup reduces one slice to
-// a d x d partial in registers and adds it to the fp32 state with device-scope float atomics
-// (the 0.8 MB state stays cache resident; no partials go to HBM).
+// a d x d partial in registers and adds it to the fp32 state with device-scope float atomics.
+// bf16 inputs with head_dim 128 take the MFMA kernel of hf_state_mfma.hip.
 #include "hf_common.h"
 
 namespace hf {
@@ -114,15 +115,24 @@ static int launch_absorb_fma(const hf_config& c, float* state, const void* K, co
 }
 
 int launch_absorb_mfma(const hf_config& c, float* state, const void* K, const void* V, int n,
-                       const float* cosv, const float* sinv, hipStream_t s);  // hf_state_mfma.hip
+                       const float* cosv, const float* sinv, void* workspace, size_t workspace_bytes,
+                       hipStream_t s);  // hf_state_mfma.hip
+size_t absorb_mfma_workspace_bytes(const hf_config& c, int n);
+
+static bool absorb_uses_mfma(const hf_config& c) { return c.dtype == HF_BF16 && c.head_dim == 128; }
+
+size_t absorb_workspace_bytes(const hf_config& c, int n) {
+  return absorb_uses_mfma(c) ? absorb_mfma_workspace_bytes(c, n) : 0;
+}
 
 int launch_absorb(const hf_config& c, float* state, const void* K, const void* V, int n,
-                  const float* cosv, const float* sinv, hipStream_t s) {
+                  const float* cosv, const float* sinv, void* workspace, size_t workspace_bytes,
+                  hipStream_t s) {
   if (c.dtype == HF_F32) {
     return c.head_dim == 128 ? launch_absorb_fma<float, 128>(c, state, K, V, n, cosv, sinv, s)
                              : launch_absorb_fma<float, 64>(c, state, K, V, n, cosv, sinv, s);
   }
-  if (c.head_dim == 128) return launch_absorb_mfma(c, state, K, V, n, cosv, sinv, s);
+  if (absorb_uses_mfma(c)) return launch_absorb_mfma(c, state, K, V, n, cosv, sinv, workspace, workspace_bytes, s);
   return launch_absorb_fma<bf16_t, 64>(c, state, K, V, n, cosv, sinv, s);
 }
 

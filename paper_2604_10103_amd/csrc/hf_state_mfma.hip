@@ -5,8 +5,16 @@
 // contiguous in each lane.  The workgroup therefore transposes on the way into LDS: two
 // consecutive tokens of one feature are packed into one dword and stored at
 // [feature][token pair], so that an operand fragment (8 tokens of one feature) is one 16-byte
-// LDS read.  The kernel is bound by the HBM read of K_ev and V_ev; the next 64-token chunk is
-// fetched into registers while the matrix cores work on the current one.
+// LDS read.
+//
+// The kernel is bound by the HBM read of K_ev and V_ev, which at this size (tens of MB) is a
+// latency problem: a workgroup requests ALL the tokens of its run (up to 320) before it touches
+// the first one, so that a whole run is in flight per compute unit.  The evicted tokens of one
+// head are cut into slices, one workgroup each.  Slice partials are combined either
+//   - through a caller workspace: plain coalesced stores of the d x d + d partial, then a small
+//     reduction kernel adds the slices to the state (the fast path), or
+//   - with device-scope float atomics straight into the state (no workspace; the L2 atomic units
+//     retire one dword per channel and clock, which costs more than the read itself).
 #include <stdlib.h>
 
 #include "hf_common.h"
@@ -19,9 +27,12 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 namespace {
 
 constexpr int D = 128;
-constexpr int CH = 64;        // tokens per chunk
-constexpr int NP = CH / 2;    // token pairs per chunk
-constexpr int SP = NP + 4;    // LDS row stride in dwords: keeps 16-byte operand reads conflict free
+constexpr int CH = 64;              // tokens per chunk (one LDS image)
+constexpr int NP = CH / 2;          // token pairs per chunk
+constexpr int SP = NP + 4;          // LDS row stride in dwords: keeps 16-byte operand reads conflict free
+constexpr int RUN_CHUNKS = 5;       // chunks requested up front
+constexpr int RUN = RUN_CHUNKS * CH;
+constexpr int PART = D * D + D;     // floats of one partial: L then z
 
 // column of token pair `tp` in the row of `feature`: rows are rotated by one 16-byte group per
 // 16 features, which spreads the transposing dword stores of a wave (16 feature groups x 4
@@ -35,32 +46,41 @@ struct Regs {
   uint4 v[2][2];
 };
 
+typedef short s16x2 __attribute__((ext_vector_type(2)));
+
 __device__ __forceinline__ uint32_t relu_pk(uint32_t x) {
-  // bf16 ReLU on two packed values: a set sign bit (also -0) gives +0
-  const uint32_t lo = (x & 0x8000u) ? 0u : (x & 0xffffu);
-  const uint32_t hi = (x & 0x80000000u) ? 0u : (x & 0xffff0000u);
-  return lo | hi;
+  // bf16 ReLU on two packed values: as signed 16-bit integers negative numbers (also -0) are < 0,
+  // so a packed integer max with zero clears them (one v_pk_max_i16)
+  const s16x2 v = __builtin_bit_cast(s16x2, x);
+  const s16x2 zero = {0, 0};
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(v, zero));
 }
 
 template <bool kPlain>
-__global__ __launch_bounds__(256) void absorb_mfma_kernel(float* __restrict__ state, const bf16_t* __restrict__ K,
-                                                          const bf16_t* __restrict__ V, int n, int tokens_per_slice,
-                                                          const float* __restrict__ cosv,
-                                                          const float* __restrict__ sinv, int phi_kind, int BH,
-                                                          int slices) {
+__global__ __launch_bounds__(256, 1) void absorb_mfma_kernel(float* __restrict__ state, float* __restrict__ partials,
+                                                             const bf16_t* __restrict__ K,
+                                                             const bf16_t* __restrict__ V, int n,
+                                                             int tokens_per_slice, const float* __restrict__ cosv,
+                                                             const float* __restrict__ sinv, int phi_kind, int BH,
+                                                             int slices) {
   __shared__ __attribute__((aligned(16))) uint32_t Kt[D * SP];
   __shared__ __attribute__((aligned(16))) uint32_t Vt[D * SP];
   __shared__ float zs[D];
 
-  // Consecutive workgroup ids land on consecutive XCDs.  All slices of one (batch, head) are
-  // given to ONE XCD (head index mod 8), so the float atomics that add the partials to that
-  // head's state meet in a single L2 instead of bouncing between the XCDs' caches.
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int bh = xcd + 8 * (slot / slices);
+  int bh, slice;
+  if (partials) {  // plain (head, slice) order: every XCD streams the same number of bytes
+    bh = blockIdx.x / slices;
+    slice = blockIdx.x - bh * slices;
+  } else {
+    // Consecutive workgroup ids land on consecutive XCDs; all slices of one (batch, head) go to
+    // one XCD (head index mod 8), which keeps that head's atomics in a single L2.
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    bh = xcd + 8 * (slot / slices);
+    slice = slot % slices;
+  }
   if (bh >= BH) return;
-  const int t0 = (slot % slices) * tokens_per_slice;
+  const int t0 = slice * tokens_per_slice;
   const int t1 = min(n, t0 + tokens_per_slice);
-  if (t0 >= t1) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const bf16_t* Kh = K + (size_t)bh * n * D;
   const bf16_t* Vh = V + (size_t)bh * n * D;
@@ -101,10 +121,8 @@ __global__ __launch_bounds__(256) void absorb_mfma_kernel(float* __restrict__ st
   const int mi0 = 2 * (wave >> 1), nj0 = 2 * (wave & 1);  // this wave's 2x2 grid of 32x32 tiles
   const int h = lane >> 5, l32 = lane & 31;
 
-  Regs cur;
-  load(t0, cur);
-  for (int tb = t0; tb < t1; tb += CH) {
-    // ---- transform, pack token pairs, transposing store to LDS
+  // transform one chunk held in registers, pack token pairs, transposing store to LDS
+  auto stage = [&](int tb, Regs& cur) {
 #pragma unroll
     for (int it = 0; it < 2; ++it) {
       const int tp = tp0 + 16 * it;
@@ -144,16 +162,17 @@ __global__ __launch_bounds__(256) void absorb_mfma_kernel(float* __restrict__ st
       for (int q = 0; q < 4; ++q) {
         const int f = 8 * g + 2 * q;
         const int col = pair_col(f, tp);
-        Kt[f * SP + col] = (kw[0][q] & 0xffffu) | (kw[1][q] << 16);
-        Kt[(f + 1) * SP + col] = (kw[0][q] >> 16) | (kw[1][q] & 0xffff0000u);
-        Vt[f * SP + col] = (vw[0][q] & 0xffffu) | (vw[1][q] << 16);
-        Vt[(f + 1) * SP + col] = (vw[0][q] >> 16) | (vw[1][q] & 0xffff0000u);
+        // one byte permute per dword: (token, token + 1) of feature f, then of feature f + 1
+        Kt[f * SP + col] = __builtin_amdgcn_perm(kw[1][q], kw[0][q], 0x05040100u);
+        Kt[(f + 1) * SP + col] = __builtin_amdgcn_perm(kw[1][q], kw[0][q], 0x07060302u);
+        Vt[f * SP + col] = __builtin_amdgcn_perm(vw[1][q], vw[0][q], 0x05040100u);
+        Vt[(f + 1) * SP + col] = __builtin_amdgcn_perm(vw[1][q], vw[0][q], 0x07060302u);
       }
     }
-    __syncthreads();
-    if (tb + CH < t1) load(tb + CH, cur);  // in flight while the matrix cores run
+  };
 
-    // ---- 4 contraction steps of 16 tokens
+  // 4 contraction steps of 16 tokens over the chunk in LDS
+  auto contract = [&]() {
 #pragma unroll
     for (int ks = 0; ks < CH / 16; ++ks) {
       bf16x8 af[2], bf[2];
@@ -173,11 +192,35 @@ __global__ __launch_bounds__(256) void absorb_mfma_kernel(float* __restrict__ st
         for (int b = 0; b < 2; ++b)
           acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[b], acc[a][b], 0, 0, 0);
     }
-    __syncthreads();
+  };
+
+  for (int run0 = t0; run0 < t1; run0 += RUN) {
+    Regs r[RUN_CHUNKS];
+#pragma unroll
+    for (int c = 0; c < RUN_CHUNKS; ++c) load(run0 + c * CH, r[c]);  // the whole run is requested before use
+#pragma unroll
+    for (int c = 0; c < RUN_CHUNKS; ++c) {
+      if (run0 + c * CH < t1) {  // uniform
+        stage(run0 + c * CH, r[c]);
+        __syncthreads();
+        contract();
+        __syncthreads();
+      }
+    }
   }
 
-  // ---- add the partial to the state
-  float* L = state + (size_t)bh * D * D;
+  // ---- hand the partial over
+  float* L;
+  float* z;
+  if (partials) {
+    L = partials + ((size_t)bh * slices + slice) * PART;
+    z = L + D * D;
+  } else {
+    L = state + (size_t)bh * D * D;
+    z = state + (size_t)BH * D * D + (size_t)bh * D;
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) atomicAdd(&zs[8 * g + e], zacc[e]);
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -186,12 +229,43 @@ __global__ __launch_bounds__(256) void absorb_mfma_kernel(float* __restrict__ st
       for (int r = 0; r < 16; ++r) {
         const int i = 32 * (mi0 + a) + 8 * (r >> 2) + 4 * h + (r & 3);
         const int j = 32 * (nj0 + b) + l32;
-        atomicAdd(L + i * D + j, acc[a][b][r]);
+        if (partials) L[i * D + j] = acc[a][b][r];
+        else atomicAdd(L + i * D + j, acc[a][b][r]);
       }
-#pragma unroll
-  for (int e = 0; e < 8; ++e) atomicAdd(&zs[8 * g + e], zacc[e]);
   __syncthreads();
-  if (tid < D) atomicAdd(state + (size_t)BH * D * D + (size_t)bh * D + tid, zs[tid]);
+  if (tid < D) {
+    if (partials) z[tid] = zs[tid];
+    else atomicAdd(z + tid, zs[tid]);
+  }
+}
+
+// state += sum over slices of the partials; one thread per 4 consecutive floats of a partial
+__global__ __launch_bounds__(256) void absorb_reduce_kernel(float* __restrict__ state,
+                                                            const float* __restrict__ partials, int slices,
+                                                            int BH) {
+  const int e4 = blockIdx.x * 256 + threadIdx.x;  // float4 index inside a partial
+  const int bh = blockIdx.y;
+  if (e4 >= PART / 4) return;
+  const float4* p = reinterpret_cast<const float4*>(partials + (size_t)bh * slices * PART) + e4;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  int sl = 0;
+  for (; sl + 3 < slices; sl += 4) {  // four independent loads in flight
+    const float4 a = p[(size_t)sl * (PART / 4)], b = p[(size_t)(sl + 1) * (PART / 4)];
+    const float4 c = p[(size_t)(sl + 2) * (PART / 4)], d = p[(size_t)(sl + 3) * (PART / 4)];
+    s.x += (a.x + b.x) + (c.x + d.x);
+    s.y += (a.y + b.y) + (c.y + d.y);
+    s.z += (a.z + b.z) + (c.z + d.z);
+    s.w += (a.w + b.w) + (c.w + d.w);
+  }
+  for (; sl < slices; ++sl) {
+    const float4 a = p[(size_t)sl * (PART / 4)];
+    s.x += a.x; s.y += a.y; s.z += a.z; s.w += a.w;
+  }
+  const int e = 4 * e4;
+  float* dst = e < D * D ? state + (size_t)bh * D * D + e : state + (size_t)BH * D * D + (size_t)bh * D + (e - D * D);
+  float4 cur = *reinterpret_cast<float4*>(dst);
+  cur.x += s.x; cur.y += s.y; cur.z += s.z; cur.w += s.w;
+  *reinterpret_cast<float4*>(dst) = cur;
 }
 
 int env_int(const char* name, int dflt) {
@@ -201,36 +275,58 @@ int env_int(const char* name, int dflt) {
   return x > 0 ? x : dflt;
 }
 
-}  // namespace
-
-int launch_absorb_mfma(const hf_config& c, float* state, const void* K, const void* V, int n,
-                       const float* cosv, const float* sinv, hipStream_t s) {
-  const int BH = c.batch * c.heads;
-  // slice length: a multiple of the 64-token chunk; default aims at ~2 workgroups per compute unit
-  const int forced = env_int("HF_ABSORB_SLICE_TOKENS", 0);
-  int per;
+// slice length (a multiple of the 64-token chunk) and slice count for n tokens
+void slice_plan(int BH, int n, bool with_workspace, int& per, int& slices) {
+  const int forced = env_int("HF_ABSORB_SLICE_TOKENS", 0);  // development override
   if (forced > 0) {
     per = (forced + CH - 1) / CH * CH;
+  } else if (with_workspace) {
+    // one run (320 tokens) per workgroup until there are ~4 workgroups per compute unit, then longer slices
+    const int max_slices = (1024 + BH - 1) / BH;
+    per = RUN;
+    if ((n + per - 1) / per > max_slices) per = ((n + max_slices - 1) / max_slices + RUN - 1) / RUN * RUN;
   } else {
-    int slices = (512 + BH - 1) / BH;
-    per = (n + slices - 1) / slices;
-    per = (per + CH - 1) / CH * CH;
+    // atomics: fewer, longer slices (the atomic traffic is slices x state size)
+    const int max_slices = (160 + BH - 1) / BH;
+    per = (((n + max_slices - 1) / max_slices) + CH - 1) / CH * CH;
     if (per < 2 * CH) per = 2 * CH;
   }
-  const int slices = (n + per - 1) / per;
+  slices = (n + per - 1) / per;
+}
+
+}  // namespace
+
+size_t absorb_mfma_workspace_bytes(const hf_config& c, int n) {
+  int per, slices;
+  slice_plan(c.batch * c.heads, n, true, per, slices);
+  return (size_t)c.batch * c.heads * slices * PART * sizeof(float);
+}
+
+int launch_absorb_mfma(const hf_config& c, float* state, const void* K, const void* V, int n,
+                       const float* cosv, const float* sinv, void* workspace, size_t workspace_bytes,
+                       hipStream_t s) {
+  const int BH = c.batch * c.heads;
+  const bool use_ws = workspace != nullptr && workspace_bytes >= absorb_mfma_workspace_bytes(c, n);
+  int per, slices;
+  slice_plan(BH, n, use_ws, per, slices);
+  float* partials = use_ws ? static_cast<float*>(workspace) : nullptr;
   const bool plain = (c.phi == HF_PHI_RELU) && cosv == nullptr;
   const bf16_t* Kp = static_cast<const bf16_t*>(K);
   const bf16_t* Vp = static_cast<const bf16_t*>(V);
   const int heads_per_xcd = (BH + 7) / 8;
-  const dim3 grid(8 * heads_per_xcd * slices);
+  const dim3 grid(use_ws ? BH * slices : 8 * heads_per_xcd * slices);
   if (plain) {
-    hipLaunchKernelGGL((absorb_mfma_kernel<true>), grid, dim3(256), 0, s, state, Kp, Vp, n, per, cosv, sinv,
-                       c.phi, BH, slices);
+    hipLaunchKernelGGL((absorb_mfma_kernel<true>), grid, dim3(256), 0, s, state, partials, Kp, Vp, n, per, cosv,
+                       sinv, c.phi, BH, slices);
   } else {
-    hipLaunchKernelGGL((absorb_mfma_kernel<false>), grid, dim3(256), 0, s, state, Kp, Vp, n, per, cosv, sinv,
-                       c.phi, BH, slices);
+    hipLaunchKernelGGL((absorb_mfma_kernel<false>), grid, dim3(256), 0, s, state, partials, Kp, Vp, n, per, cosv,
+                       sinv, c.phi, BH, slices);
   }
-  return check_launch("hf_absorb_evicted");
+  const int rc = check_launch("hf_absorb_evicted");
+  if (rc != HF_OK || !use_ws) return rc;
+  hipLaunchKernelGGL(absorb_reduce_kernel, dim3((PART / 4 + 255) / 256, BH), dim3(256), 0, s, state, partials,
+                     slices, BH);
+  return check_launch("hf_absorb_evicted(reduce)");
 }
 
 }  // namespace hf

@@ -29,7 +29,7 @@ def test_every_declared_symbol_is_exported(lib):
     names = _declared()
     assert set(names) >= {"hf_state_bytes", "hf_state_init", "hf_absorb_evicted", "hf_select_k",
                           "hf_workspace_bytes", "hf_block_select", "hf_hybrid_attn_fwd", "hf_last_error",
-                          "hf_version"}
+                          "hf_version", "hf_absorb_workspace_bytes"}
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in hf.h but not exported"
 
@@ -53,6 +53,14 @@ def test_select_k_matches_oracle(lib, ratio, n_kv, b):
     cfg = hf.make_config(1, 1, 128, "bf16", b, b, ratio)
     t_n = -(-n_kv // b)
     assert hf.hf_select_k(cfg, n_kv) == orc.select_k(ratio, t_n)
+
+
+def test_absorb_workspace_holds_one_partial_per_slice(lib):
+    cfg = hf.make_config(1, 12, 128, "bf16", 64, 64, 0.25)
+    part = (128 * 128 + 128) * 4
+    got = hf.hf_absorb_workspace_bytes(cfg, 4680)
+    assert got % (12 * part) == 0 and 1 <= got // (12 * part) <= 4680 // 64 + 1
+    assert hf.hf_absorb_workspace_bytes(hf.make_config(1, 2, 64, "f32", 16, 16, 0.25), 512) == 0
 
 
 def test_keep_k_override_and_bounds(lib):
@@ -90,10 +98,11 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_launch(lib):
     c = ctypes.byref(cfg)
     assert lib.hf_state_init(c, None, None) == -1
     assert lib.hf_state_init(None, None, None) == -1
-    assert lib.hf_absorb_evicted(c, 4096, None, 4096, 10, None, None, None) == -1
-    assert lib.hf_absorb_evicted(c, 4096, 4096, 4100, 10, None, None, None) == -4
-    assert lib.hf_absorb_evicted(c, 4096, 4096, 4096, 0, None, None, None) == -2
-    assert lib.hf_absorb_evicted(c, 4096, 4096, 4096, 10, 4096, None, None) == -1   # cos without sin
+    assert lib.hf_absorb_evicted(c, 4096, None, 4096, 10, None, None, None, 0, None) == -1
+    assert lib.hf_absorb_evicted(c, 4096, 4096, 4100, 10, None, None, None, 0, None) == -4
+    assert lib.hf_absorb_evicted(c, 4096, 4096, 4096, 0, None, None, None, 0, None) == -2
+    assert lib.hf_absorb_evicted(c, 4096, 4096, 4096, 10, 4096, None, None, 0, None) == -1   # cos without sin
+    assert lib.hf_absorb_evicted(c, 4096, 4096, 4096, 10, None, None, 4096 + 16, 1 << 20, None) == -4   # workspace alignment
     assert lib.hf_block_select(c, 4096, 100, 4096, 200, 4096, None, None, 0, None) == -5
     assert lib.hf_block_select(c, 4096, 100, 4096, 200, 4096, None, 4096 + 16, 1 << 30, None) == -4
     # O aliases Q

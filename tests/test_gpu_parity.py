@@ -32,6 +32,11 @@ def new_state(cfg):
     return st
 
 
+def absorb_ws(cfg, n):
+    nbytes = hf.hf_absorb_workspace_bytes(cfg, n)
+    return torch.empty(nbytes, dtype=torch.uint8, device=DEV) if nbytes else None
+
+
 def new_workspace(cfg, n_q, n_kv):
     return torch.empty(hf.hf_workspace_bytes(cfg, n_q, n_kv), dtype=torch.uint8, device=DEV)
 
@@ -68,9 +73,11 @@ def test_state_init_and_absorb_match_direct_sum(name):
     L, z = split_state(st, w.batch * w.heads, w.head_dim)
     assert rel_l2(L, np.stack([r[0] for r in ref])) <= 1e-5
     assert rel_l2(z, np.stack([r[1] for r in ref])) <= 1e-5
-    # order / chunking invariance on the GPU: one call with all tokens
+    # order / chunking invariance on the GPU: one call with all tokens, partials through a workspace
     st2 = new_state(cfg)
-    hf.hf_absorb_evicted(cfg, st2, torch.cat(Ks, 2).to(DEV), torch.cat(Vs, 2).to(DEV))
+    n_all = w.evicted_frames * w.tokens_per_frame
+    hf.hf_absorb_evicted(cfg, st2, torch.cat(Ks, 2).to(DEV), torch.cat(Vs, 2).to(DEV),
+                         workspace=absorb_ws(cfg, n_all))
     torch.cuda.synchronize()
     L2, z2 = split_state(st2, w.batch * w.heads, w.head_dim)
     assert rel_l2(L2, L) <= 2e-6 and rel_l2(z2, z) <= 2e-6
@@ -78,14 +85,16 @@ def test_state_init_and_absorb_match_direct_sum(name):
 
 @pytest.mark.parametrize("name", ["tiny_f32", "small_bf16"])
 @pytest.mark.parametrize("phi", [hf.HF_PHI_RELU, hf.HF_PHI_ELU1])
-def test_absorb_with_rope_and_elu(name, phi):
+@pytest.mark.parametrize("use_ws", [False, True])
+def test_absorb_with_rope_and_elu(name, phi, use_ws):
     w = wl.get(name)
     cfg = cfg_of(w, phi=phi)
     st = new_state(cfg)
     n = 3 * w.tokens_per_frame + 5   # ragged
     K, V = wl.make_evicted(w, 40, n)
     cos, sin = wl.rope_tables(n, w.head_dim, first_position=3.0, tokens_per_position=w.tokens_per_frame)
-    hf.hf_absorb_evicted(cfg, st, K.to(DEV), V.to(DEV), cos.to(DEV), sin.to(DEV))
+    hf.hf_absorb_evicted(cfg, st, K.to(DEV), V.to(DEV), cos.to(DEV), sin.to(DEV),
+                         workspace=absorb_ws(cfg, n) if use_ws else None)
     torch.cuda.synchronize()
     ref = oracle_state([K], [V], w.head_dim, phi, [(cos, sin)])
     L, z = split_state(st, w.batch * w.heads, w.head_dim)
@@ -94,13 +103,33 @@ def test_absorb_with_rope_and_elu(name, phi):
     assert rel_l2(z, np.stack([r[1] for r in ref])) <= 1e-5
 
 
+def test_absorb_long_run_uses_several_runs_per_slice():
+    # more tokens than one workgroup requests at once, a ragged end, and a dirty workspace
+    w = wl.get("small_bf16")
+    cfg = cfg_of(w)
+    n = 12 * 320 * 9 + 37
+    K, V = wl.make_evicted(w, 42, n)
+    ws = absorb_ws(cfg, n)
+    ws.fill_(0x7f)
+    st = new_state(cfg)
+    hf.hf_absorb_evicted(cfg, st, K.to(DEV), V.to(DEV), workspace=ws)
+    st2 = new_state(cfg)
+    hf.hf_absorb_evicted(cfg, st2, K.to(DEV), V.to(DEV))
+    torch.cuda.synchronize()
+    ref = oracle_state([K], [V], w.head_dim)
+    for s_ in (st, st2):
+        L, z = split_state(s_, w.batch * w.heads, w.head_dim)
+        assert rel_l2(L, np.stack([r[0] for r in ref])) <= 1e-5
+        assert rel_l2(z, np.stack([r[1] for r in ref])) <= 1e-5
+
+
 def test_absorb_single_token_and_accumulation():
     w = wl.get("small_bf16")
     cfg = cfg_of(w)
     st = new_state(cfg)
     K, V = wl.make_evicted(w, 41, 1)
     hf.hf_absorb_evicted(cfg, st, K.to(DEV), V.to(DEV))
-    hf.hf_absorb_evicted(cfg, st, K.to(DEV), V.to(DEV))     # twice: the state accumulates
+    hf.hf_absorb_evicted(cfg, st, K.to(DEV), V.to(DEV), workspace=absorb_ws(cfg, 1))     # twice: the state accumulates
     torch.cuda.synchronize()
     ref = oracle_state([K, K], [V, V], w.head_dim)
     L, z = split_state(st, w.batch * w.heads, w.head_dim)
