@@ -36,7 +36,10 @@ def parse():
     p.add_argument("--layers", type=int, default=6, help="distinct layer tensor sets rotated through")
     p.add_argument("--keep-ratio", type=float, default=None)
     p.add_argument("--no-cpu-baseline", action="store_true")
-    p.add_argument("--cpu-heads", type=int, default=2, help="heads of layer 0 the oracle is timed on")
+    p.add_argument("--cpu-heads", type=int, default=0, help="heads per layer the oracle is timed on (0 = all)")
+    p.add_argument("--cpu-layers", type=int, default=6, help="layer sets the oracle is timed on")
+    p.add_argument("--calibration-copy-mib", type=int, default=0,
+                   help="also run one plain device copy of this size (reference for HBM byte counters)")
     return p.parse_args()
 
 
@@ -111,6 +114,15 @@ def main():
         hf.hf_absorb_evicted(cfg, s["st"], s["Ke"], s["Ve"], workspace=aws)
         if events is not None:
             events[3].record()
+
+    if a.calibration_copy_mib > 0:   # a copy of known size: what FETCH_SIZE / WRITE_SIZE read for it scales the rest
+        src = torch.empty(a.calibration_copy_mib << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        src.fill_(1)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for i in range(a.warmup):
         step(sets[i % nl])
@@ -194,25 +206,27 @@ def main():
 
     if not a.no_cpu_baseline:
         import oracle as orc
-        s0 = sets[0]
-        heads = list(range(min(a.cpu_heads, w.heads)))
+        heads = list(range(w.heads if a.cpu_heads <= 0 else min(a.cpu_heads, w.heads)))
+        layers = list(range(min(max(1, a.cpu_layers), nl)))
         Ke, Ve = wl.make_evicted(w, 0)
         t0 = time.perf_counter()
-        for h in heads:
-            q, kk, v = (wl.to_f64(s0[n][0, h]) for n in ("Qc", "Kc", "Vc"))
-            st = orc.state_absorb(*orc.state_zero(w.head_dim), wl.to_f64(Ke[0, h]), wl.to_f64(Ve[0, h]))
-            orc.hybrid_attention(q, kk, v, st, w.block, w.block, k)
+        for l in layers:
+            s0 = sets[l]
+            for h in heads:
+                q, kk, v = (wl.to_f64(s0[n][0, h]) for n in ("Qc", "Kc", "Vc"))
+                st = orc.state_absorb(*orc.state_zero(w.head_dim), wl.to_f64(Ke[0, h]), wl.to_f64(Ve[0, h]))
+                orc.hybrid_attention(q, kk, v, st, w.block, w.block, k)
         t_cpu = time.perf_counter() - t0
-        per_layer = t_cpu / len(heads) * w.heads * w.batch
+        per_layer = t_cpu / (len(heads) * len(layers)) * w.heads * w.batch
         try:
             cores = len(os.sched_getaffinity(0))
         except AttributeError:
             cores = os.cpu_count()
         out["cpu_baseline"] = {
             "value": w.n_q * w.batch / per_layer, "unit": "query tokens/s", "cores": cores, "kind": "oracle",
-            "sample": f"fp64 NumPy oracle, heads {heads} of layer 0 at the full chunk shape "
-                      f"(scores, top-k, sparse attention, readout, one absorb), {t_cpu:.1f} s, "
-                      f"scaled to {w.heads} heads"}
+            "sample": f"fp64 NumPy oracle, {len(heads)} of {w.heads} heads of {len(layers)} layer steps at the full "
+                      f"chunk shape (scores, top-k, sparse attention, readout, one absorb), {t_cpu:.1f} s of "
+                      f"CPU work, scaled to one {w.heads}-head layer step"}
     print(json.dumps(out))
 
 

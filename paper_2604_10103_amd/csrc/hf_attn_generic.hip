@@ -149,10 +149,12 @@ int launch_attn(const hf_config& c, const void* Q, int n_q, const void* K, const
     set_error("grid too large");
     return HF_ERR_SHAPE;
   }
-  const char* pick = getenv("HF_ATTN_KERNEL");  // development switch between the MFMA variants
-  const bool want_wg = pick && pick[0] == 'g';
-  if (attn_w64_supported(c) && !want_wg) return launch_attn_w64(c, Q, n_q, K, V, n_kv, idx, k, O_local, s);
-  if (attn_mfma_supported(c)) return launch_attn_mfma(c, Q, n_q, K, V, n_kv, idx, k, O_local, s);
+  // bf16, head_dim 128: block_q 64 / 128 take the workgroup-per-query-block MFMA kernel, other
+  // multiples of 64 the wavefront-per-64-rows MFMA kernel; everything else the fp32-arithmetic one
+  const char* pick = getenv("HF_ATTN_KERNEL");  // development switch: "w" forces the second kernel
+  const bool want_w64 = pick && pick[0] == 'w';
+  if (attn_mfma_supported(c) && !want_w64) return launch_attn_mfma(c, Q, n_q, K, V, n_kv, idx, k, O_local, s);
+  if (attn_w64_supported(c)) return launch_attn_w64(c, Q, n_q, K, V, n_kv, idx, k, O_local, s);
   return launch_attn_generic(c, Q, n_q, K, V, n_kv, idx, k, O_local, s);
 }
 
