@@ -25,6 +25,9 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+# HBM-side bytes per launch of the sparse flash forward from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
+# (profiles/bench_step_832x480_hbm_traffic.txt: read 92.4 MB + written 15.3 MB, scaled by a 256 MiB copy)
+MEASURED_TRAFFIC_BYTES = {"step_832x480": 107.7e6}
 
 
 def parse():
@@ -189,7 +192,8 @@ def main():
                    "t_n": w.t_n, "evicted_tokens_in_state": w.n_evicted, "rotated_layer_sets": nl},
         "roofline": {"kernel": "sparse flash forward (Eq. 5)", "bound": "mfma", "achieved": a4_tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": a4_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": None, "flops_per_launch": flops, "avg_ms": a4_ms, "min_ms": a4_min},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if a.keep_ratio is None else None,
+                     "flops_per_launch": flops, "avg_ms": a4_ms, "min_ms": a4_min},
         "kernels_ms": {"block_select": sel_ms, "attn_fwd_total": fwd_ms, "sparse_flash_fwd": a4_ms,
                        "readout_combine": a5_ms, "absorb": abs_ms, "dense_window_fwd": dense_ms},
         "hbm": {"absorb_GBs": absorb_bytes / (abs_ms * 1e-3) / 1e9,
