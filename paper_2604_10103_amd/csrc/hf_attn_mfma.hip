@@ -39,11 +39,19 @@ constexpr int OSTR = 272;   // bytes per query row of the staged output
 constexpr int KTILE = TK * KSTR;
 constexpr float kRescaleThreshold = 8.0f;  // log2 units: rescale only when a row max grew by more than 2^8
 
-template <int NW>
+// History branch fused into the epilogue (kFused): planes = the fp32 state split into two bf16
+// planes, transposed (Lt[plane][j][i], see hf_readout_mfma.hip), zvec = the state's normaliser.
+struct HistArgs {
+  const bf16_t* planes;  // [BH][2][d][d]
+  const float* zvec;     // [BH][d]
+  float eps, z_scale;
+};
+
+template <int NW, bool kFused>
 __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const int32_t* __restrict__ idx, int k, int n_q, int n_kv, int bkv, int t_m, int t_n, int items_per_xcd,
-    int total_items, float c_scale, bf16_t* __restrict__ O) {
+    int total_items, float c_scale, HistArgs hist, bf16_t* __restrict__ O) {
   constexpr int NT = 64 * NW;
   constexpr int BQ = 32 * NW;
   constexpr int CPT = (TK * D * 2 / 16) / NT;  // 16-byte chunks of a K tile per thread (4 or 2)
@@ -261,14 +269,79 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
     l_tot = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
   }
   const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[dt][r] *= inv;
+
+  if (kFused) {
+    // ---- O += R(phi(q)) L / (z_scale phi(q).z + eps) for phi = ReLU without rotation (Eq. 3, 6):
+    // the query fragments already in registers are, after a packed ReLU, the B operand of
+    // O_hist^T = Lt x phi(Q)^T; the A operand streams from the L2-resident planes.
+    const float* zv = hist.zvec + (size_t)bh * D + 8 * h;
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    const s16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+    float den = 0.0f;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      qf[s] = __builtin_bit_cast(bf16x8, __builtin_elementwise_max(__builtin_bit_cast(s16x8, qf[s]), zero8));  // ReLU
+      const float4 z0 = *reinterpret_cast<const float4*>(zv + 16 * s);
+      const float4 z1 = *reinterpret_cast<const float4*>(zv + 16 * s + 4);
+      den += static_cast<float>(qf[s][0]) * z0.x + static_cast<float>(qf[s][1]) * z0.y +
+             static_cast<float>(qf[s][2]) * z0.z + static_cast<float>(qf[s][3]) * z0.w +
+             static_cast<float>(qf[s][4]) * z1.x + static_cast<float>(qf[s][5]) * z1.y +
+             static_cast<float>(qf[s][6]) * z1.z + static_cast<float>(qf[s][7]) * z1.w;
+    }
+    {
+      const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(den), __float_as_uint(den), false, false);
+      den = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+    }
+    // O_local is scaled by the denominator, the matrix cores add the numerator straight into the
+    // same accumulators, and one multiplication by 1/denominator finishes O_local + O_hist
+    const float den_eps = hist.z_scale * den + hist.eps;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[dt][r] *= den_eps;
+    constexpr int PCH = (D * D * 2 / 16) / NT;  // 16-byte chunks of one plane per thread
+    static_assert(D * KSTR <= 2 * KTILE + D * VSTRD * 4, "a state plane must fit in the tiles' space");
+    const u32x4* gp = reinterpret_cast<const u32x4*>(hist.planes + (size_t)bh * 2 * D * D);
+#pragma unroll
+    for (int plane = 0; plane < 2; ++plane) {  // each plane goes through LDS once per workgroup
+      u32x4 preg[PCH];
+#pragma unroll
+      for (int i = 0; i < PCH; ++i) preg[i] = gp[plane * (D * D * 2 / 16) + tid + NT * i];
+      if (plane) __syncthreads();  // everybody is done with the previous plane
+#pragma unroll
+      for (int i = 0; i < PCH; ++i) {
+        const int c = tid + NT * i;
+        *reinterpret_cast<u32x4*>(smem + (c >> 4) * KSTR + (c & 15) * 16) = preg[i];
+      }
+      __syncthreads();
+#pragma unroll
+      for (int s = 0; s < 8; ++s)
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
+          const bf16x8 a = *reinterpret_cast<const bf16x8*>(smem + (32 * dt + l32) * KSTR + 16 * h + 32 * s);
+          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[s], o[dt], 0, 0, 0);
+        }
+    }
+    const float inv_den = 1.0f / den_eps;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[dt][r] *= inv_den;
+    __syncthreads();  // the plane's space becomes the output staging area
+  }
+
   char* stage = smem;
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
     for (int rq = 0; rq < 4; ++rq) {
       uint2 w;
-      w.x = (uint32_t)f32_to_bf16(o[dt][4 * rq] * inv) | ((uint32_t)f32_to_bf16(o[dt][4 * rq + 1] * inv) << 16);
-      w.y = (uint32_t)f32_to_bf16(o[dt][4 * rq + 2] * inv) | ((uint32_t)f32_to_bf16(o[dt][4 * rq + 3] * inv) << 16);
+      w.x = (uint32_t)f32_to_bf16(o[dt][4 * rq]) | ((uint32_t)f32_to_bf16(o[dt][4 * rq + 1]) << 16);
+      w.y = (uint32_t)f32_to_bf16(o[dt][4 * rq + 2]) | ((uint32_t)f32_to_bf16(o[dt][4 * rq + 3]) << 16);
       *reinterpret_cast<uint2*>(stage + (32 * wave + l32) * OSTR + (32 * dt + 8 * rq + 4 * h) * 2) = w;
     }
   __syncthreads();
@@ -290,8 +363,8 @@ bool attn_mfma_supported(const hf_config& c) {
 // byte offsets inside one head are 32-bit in the buffer loads
 constexpr int kMfmaMaxKeys = 1 << 23;
 
-int launch_attn_mfma(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
-                     const int32_t* idx, int k, void* O_local, hipStream_t s) {
+static int launch_attn_mfma_impl(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
+                                 const int32_t* idx, int k, const HistArgs* hist, void* O, hipStream_t s) {
   if (n_kv >= kMfmaMaxKeys) { set_error("window longer than %d keys", kMfmaMaxKeys); return HF_ERR_SHAPE; }
   const int BH = c.batch * c.heads;
   const int t_m = (n_q + c.block_q - 1) / c.block_q, t_n = (n_kv + c.block_kv - 1) / c.block_kv;
@@ -304,15 +377,35 @@ int launch_attn_mfma(const hf_config& c, const void* Q, int n_q, const void* K, 
   const bf16_t* q = static_cast<const bf16_t*>(Q);
   const bf16_t* kk = static_cast<const bf16_t*>(K);
   const bf16_t* v = static_cast<const bf16_t*>(V);
-  bf16_t* o = static_cast<bf16_t*>(O_local);
+  bf16_t* o = static_cast<bf16_t*>(O);
+  const HistArgs h = hist ? *hist : HistArgs{nullptr, nullptr, 0.0f, 0.0f};
+#define HF_LAUNCH_ATTN(NWV, FUSED)                                                                              \
+  hipLaunchKernelGGL((attn_mfma_kernel<NWV, FUSED>), grid, dim3(64 * NWV), 0, s, q, kk, v, idx, k, n_q, n_kv,   \
+                     c.block_kv, t_m, t_n, per_xcd, (int)total, c_scale, h, o)
   if (c.block_q == 64) {
-    hipLaunchKernelGGL((attn_mfma_kernel<2>), grid, dim3(128), 0, s, q, kk, v, idx, k, n_q, n_kv, c.block_kv, t_m,
-                       t_n, per_xcd, (int)total, c_scale, o);
+    if (hist) HF_LAUNCH_ATTN(2, true); else HF_LAUNCH_ATTN(2, false);
   } else {
-    hipLaunchKernelGGL((attn_mfma_kernel<4>), grid, dim3(256), 0, s, q, kk, v, idx, k, n_q, n_kv, c.block_kv, t_m,
-                       t_n, per_xcd, (int)total, c_scale, o);
+    if (hist) HF_LAUNCH_ATTN(4, true); else HF_LAUNCH_ATTN(4, false);
   }
+#undef HF_LAUNCH_ATTN
   return check_launch("hf_hybrid_attn_fwd(attention)");
+}
+
+int launch_attn_mfma(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
+                     const int32_t* idx, int k, void* O_local, hipStream_t s) {
+  return launch_attn_mfma_impl(c, Q, n_q, K, V, n_kv, idx, k, nullptr, O_local, s);
+}
+
+// ReLU feature map without rotation: the history term rides in the attention epilogue
+bool attn_mfma_fused_supported(const hf_config& c, bool has_rope) {
+  return attn_mfma_supported(c) && c.phi == HF_PHI_RELU && !has_rope;
+}
+
+int launch_attn_mfma_fused(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
+                           const int32_t* idx, int k, const void* planes, const float* zvec, void* O,
+                           hipStream_t s) {
+  const HistArgs h = {static_cast<const bf16_t*>(planes), zvec, c.eps, c.z_scale};
+  return launch_attn_mfma_impl(c, Q, n_q, K, V, n_kv, idx, k, &h, O, s);
 }
 
 }  // namespace hf

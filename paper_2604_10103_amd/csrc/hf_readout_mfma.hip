@@ -180,6 +180,12 @@ size_t readout_planes_bytes(const hf_config& c) {
   return readout_mfma_supported(c) ? (size_t)c.batch * c.heads * 2 * D * D * sizeof(bf16_t) : 0;
 }
 
+int launch_state_planes(const hf_config& c, const float* state, void* planes, hipStream_t s) {
+  hipLaunchKernelGGL(state_planes_kernel, dim3(D / 32, D / 32, c.batch * c.heads), dim3(256), 0, s, state,
+                     static_cast<bf16_t*>(planes));
+  return check_launch("hf_hybrid_attn_fwd(state planes)");
+}
+
 int launch_readout_mfma(const hf_config& c, const void* Q, int n_q, const void* O_local, const float* state,
                         const float* cosq, const float* sinq, void* planes, void* O, hipStream_t s) {
   const int BH = c.batch * c.heads;
