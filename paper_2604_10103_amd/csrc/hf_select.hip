@@ -3,10 +3,11 @@
 //  pool kernel    : one launch for Q and K_win, one wavefront per block of b tokens; 16-byte
 //                   loads, fp32 sums, mean over the block's real length (the last block may be
 //                   short).  HBM-bound streaming read.
-//  select kernel  : one workgroup per query-block row.  Thread j computes A[i][j] = qbar_i . kbar_j,
-//                   the row of scores is kept in LDS, every block gets its rank (number of blocks
-//                   that beat it; ties go to the lower index), the k blocks of rank < k are
-//                   written in ascending order with a ballot prefix sum.
+//  select kernel  : one workgroup per query-block row.  The dot products A[i][j] = qbar_i . kbar_j are
+//                   split over the four wavefronts by feature quarter, the row of scores is kept in
+//                   LDS, every block gets its rank (number of blocks that beat it; ties go to the
+//                   lower index), the k blocks of rank < k are written in ascending order with a
+//                   ballot prefix sum.
 #include "hf_common.h"
 
 namespace hf {
@@ -38,7 +39,16 @@ __global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ Q, int 
 #pragma unroll
   for (int e = 0; e < E; ++e) acc[e] = 0.0f;
   int r = r0 + sub;
-  // eight independent 16-byte loads in flight per lane
+  // sixteen, then eight independent 16-byte loads in flight per lane
+  for (; r + 15 * RPP < r1; r += 16 * RPP) {
+    float v[16][E];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) load16B<T>(base + (size_t)(r + u * RPP) * D, v[u]);
+#pragma unroll
+    for (int u = 0; u < 16; ++u)
+#pragma unroll
+      for (int e = 0; e < E; ++e) acc[e] += v[u][e];
+  }
   for (; r + 7 * RPP < r1; r += 8 * RPP) {
     float v[8][E];
 #pragma unroll
@@ -71,72 +81,111 @@ __global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ Q, int 
   }
 }
 
-// One workgroup per query-block row: thread j scores KV block j, ranks it against the row held
-// in LDS and the kept blocks are written in ascending order (ballot + cross-wave prefix).
+// One workgroup (four wavefronts) per query-block row.
+// Scoring: wavefront w takes a quarter of the head dimension and lane l the KV blocks l, l + 64, ...;
+// all of a thread's pooled-key loads are independent and issued together (the kernel is a chain of
+// latencies, not of bytes), the four partial dot products of a block meet in LDS.
+// Selection: thread j ranks block j against the row in LDS (rank = number of blocks that beat it;
+// ties go to the lower index); the blocks of rank < k are written in ascending order with a ballot
+// and a cross-wave prefix sum.
 template <int D>
 __global__ __launch_bounds__(256) void score_select_kernel(const float* __restrict__ qbar,
                                                            const float* __restrict__ kbar_t, int t_m, int t_n,
                                                            int k, int32_t* __restrict__ idx,
                                                            float* __restrict__ scores) {
-  extern __shared__ __attribute__((aligned(16))) float smem[];  // [D] pooled query, then scores padded to 4
+  extern __shared__ __attribute__((aligned(16))) float smem[];  // [D] query, [4][t_pad] partials, [t_pad] scores
   __shared__ int wave_count[4];
+  constexpr int CW = D / 16;  // 16-byte feature groups per wavefront
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int row = blockIdx.x, bh = blockIdx.y;
-  float* sq = smem;
-  float* sc = smem + D;
   const int t_pad = (t_n + 3) & ~3;
+  float* sq = smem;
+  float* part = smem + D;
+  float* sc = part + 4 * t_pad;
   if (tid < D) sq[tid] = qbar[((size_t)bh * t_m + row) * D + tid];
-  for (int j = t_n + tid; j < t_pad; j += 256) sc[j] = -INFINITY;  // padding never outranks a block
+  if (tid < t_pad - t_n) sc[t_n + tid] = -INFINITY;  // padding never outranks a block
   __syncthreads();
 
-  const float4* kt = reinterpret_cast<const float4*>(kbar_t) + (size_t)bh * (D / 4) * t_n;
-  for (int j = tid; j < t_n; j += 256) {
-    float a0 = 0.0f, a1 = 0.0f;
-#pragma unroll 8
-    for (int c = 0; c < D / 4; c += 2) {
-      const float4 k0 = kt[(size_t)c * t_n + j], k1 = kt[(size_t)(c + 1) * t_n + j];
-      const float4 q0 = *reinterpret_cast<const float4*>(sq + 4 * c);
-      const float4 q1 = *reinterpret_cast<const float4*>(sq + 4 * c + 4);
-      a0 = fmaf(q0.x, k0.x, a0); a0 = fmaf(q0.y, k0.y, a0); a0 = fmaf(q0.z, k0.z, a0); a0 = fmaf(q0.w, k0.w, a0);
-      a1 = fmaf(q1.x, k1.x, a1); a1 = fmaf(q1.y, k1.y, a1); a1 = fmaf(q1.z, k1.z, a1); a1 = fmaf(q1.w, k1.w, a1);
+  const float4* kt = reinterpret_cast<const float4*>(kbar_t) + ((size_t)bh * (D / 4) + wave * CW) * t_n;
+  float4 q[CW];
+#pragma unroll
+  for (int c = 0; c < CW; ++c) q[c] = *reinterpret_cast<const float4*>(sq + 4 * (wave * CW + c));
+  for (int j0 = lane; j0 < t_n; j0 += 256) {
+    float4 kv[4][CW];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = min(j0 + 64 * u, t_n - 1);  // clamped: a valid address, the result is dropped
+#pragma unroll
+      for (int c = 0; c < CW; ++c) kv[u][c] = kt[(size_t)c * t_n + j];
     }
-    const float a = a0 + a1;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      float a0 = 0.0f, a1 = 0.0f;
+#pragma unroll
+      for (int c = 0; c < CW; c += 2) {
+        a0 = fmaf(q[c].x, kv[u][c].x, a0); a0 = fmaf(q[c].y, kv[u][c].y, a0);
+        a0 = fmaf(q[c].z, kv[u][c].z, a0); a0 = fmaf(q[c].w, kv[u][c].w, a0);
+        a1 = fmaf(q[c + 1].x, kv[u][c + 1].x, a1); a1 = fmaf(q[c + 1].y, kv[u][c + 1].y, a1);
+        a1 = fmaf(q[c + 1].z, kv[u][c + 1].z, a1); a1 = fmaf(q[c + 1].w, kv[u][c + 1].w, a1);
+      }
+      if (j0 + 64 * u < t_n) part[wave * t_pad + j0 + 64 * u] = a0 + a1;
+    }
+  }
+  __syncthreads();
+  for (int j = tid; j < t_n; j += 256) {
+    const float a = (part[j] + part[t_pad + j]) + (part[2 * t_pad + j] + part[3 * t_pad + j]);
     sc[j] = a;
     if (scores) scores[((size_t)bh * t_m + row) * t_n + j] = a;
   }
   __syncthreads();
 
   int32_t* out = idx + ((size_t)bh * t_m + row) * k;
-  int base = 0;
-  for (int j0 = 0; j0 < t_n; j0 += 256) {  // uniform trip count: barriers inside
-    const int j = j0 + tid;
-    bool keep = false;
-    if (j < t_n) {
-      const float mine = sc[j];
-      int rank = 0;
-      for (int o = 0; o < t_pad; o += 4) {
-        const float4 v = *reinterpret_cast<const float4*>(sc + o);
-        rank += (v.x > mine || (v.x == mine && o < j)) ? 1 : 0;
-        rank += (v.y > mine || (v.y == mine && o + 1 < j)) ? 1 : 0;
-        rank += (v.z > mine || (v.z == mine && o + 2 < j)) ? 1 : 0;
-        rank += (v.w > mine || (v.w == mine && o + 3 < j)) ? 1 : 0;
+  // First pass: rank by strict comparison only (two instructions per element).  Blocks with equal
+  // scores share a rank, so the pass is exact unless a tie straddles the k-th place, which shows
+  // as more than k blocks of rank < k; only then the row is redone with the tie rule.
+  for (int pass = 0; pass < 2; ++pass) {
+    int base = 0;
+    for (int j0 = 0; j0 < t_n; j0 += 256) {  // uniform trip count: barriers inside
+      const int j = j0 + tid;
+      bool keep = false;
+      if (j < t_n) {
+        const float mine = sc[j];
+        int rank = 0;
+        if (pass == 0) {
+          for (int o = 0; o < t_pad; o += 4) {
+            const float4 v = *reinterpret_cast<const float4*>(sc + o);
+            rank += (v.x > mine) ? 1 : 0;
+            rank += (v.y > mine) ? 1 : 0;
+            rank += (v.z > mine) ? 1 : 0;
+            rank += (v.w > mine) ? 1 : 0;
+          }
+        } else {
+          for (int o = 0; o < t_pad; o += 4) {
+            const float4 v = *reinterpret_cast<const float4*>(sc + o);
+            rank += (v.x > mine || (v.x == mine && o < j)) ? 1 : 0;
+            rank += (v.y > mine || (v.y == mine && o + 1 < j)) ? 1 : 0;
+            rank += (v.z > mine || (v.z == mine && o + 2 < j)) ? 1 : 0;
+            rank += (v.w > mine || (v.w == mine && o + 3 < j)) ? 1 : 0;
+          }
+        }
+        keep = rank < k;
       }
-      keep = rank < k;
-    }
-    const unsigned long long m = __ballot(keep);
-    if (lane == 0) wave_count[wave] = __popcll(m);
-    __syncthreads();
-    int pos = base + __popcll(m & ((1ull << lane) - 1ull));
-    int total = 0;
+      const unsigned long long m = __ballot(keep);
+      if (lane == 0) wave_count[wave] = __popcll(m);
+      __syncthreads();
+      int pos = base + __popcll(m & ((1ull << lane) - 1ull));
+      int total = 0;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const int cw = wave_count[w];
-      if (w < wave) pos += cw;
-      total += cw;
+      for (int w = 0; w < 4; ++w) {
+        const int cw = wave_count[w];
+        if (w < wave) pos += cw;
+        total += cw;
+      }
+      if (keep && pos < k) out[pos] = j;
+      base += total;
+      __syncthreads();
     }
-    if (keep && pos < k) out[pos] = j;
-    base += total;
-    __syncthreads();
+    if (base == k) break;  // uniform over the workgroup
   }
 }
 
@@ -162,7 +211,7 @@ int launch_score_select(const hf_config& c, const float* qbar, const float* kbar
                         int32_t* idx, float* scores, hipStream_t s) {
   const int BH = c.batch * c.heads;
   const dim3 grid(t_m, BH), block(256);
-  const size_t smem = (size_t)(c.head_dim + ((t_n + 3) & ~3)) * sizeof(float);
+  const size_t smem = (size_t)(c.head_dim + 5 * ((t_n + 3) & ~3)) * sizeof(float);
   if (c.head_dim == 128)
     hipLaunchKernelGGL((score_select_kernel<128>), grid, block, smem, s, qbar, kbar_t, t_m, t_n, k, idx, scores);
   else

@@ -33,6 +33,9 @@ constexpr int SP = NP + 4;          // LDS row stride in dwords: keeps 16-byte o
 constexpr int RUN_CHUNKS = 5;       // chunks requested up front
 constexpr int RUN = RUN_CHUNKS * CH;
 constexpr int PART = D * D + D;     // floats of one partial: L then z
+constexpr int NT = 512;             // threads per workgroup: 8 wavefronts, two per SIMD
+constexpr int ITEMS = 16 * NP / NT; // (token pair, feature group) items per thread and chunk
+constexpr int TPI = NT / 16;        // token pairs between two items of a thread
 
 // column of token pair `tp` in the row of `feature`: rows are rotated by one 16-byte group per
 // 16 features, which spreads the transposing dword stores of a wave (16 feature groups x 4
@@ -42,8 +45,8 @@ __device__ __forceinline__ int pair_col(int feature, int tp) {
 }
 
 struct Regs {
-  uint4 k[2][2];  // [item][token of the pair]
-  uint4 v[2][2];
+  uint4 k[ITEMS][2];  // [item][token of the pair]
+  uint4 v[ITEMS][2];
 };
 
 typedef short s16x2 __attribute__((ext_vector_type(2)));
@@ -57,7 +60,7 @@ __device__ __forceinline__ uint32_t relu_pk(uint32_t x) {
 }
 
 template <bool kPlain>
-__global__ __launch_bounds__(256, 1) void absorb_mfma_kernel(float* __restrict__ state, float* __restrict__ partials,
+__global__ __launch_bounds__(NT, 1) void absorb_mfma_kernel(float* __restrict__ state, float* __restrict__ partials,
                                                              const bf16_t* __restrict__ K,
                                                              const bf16_t* __restrict__ V, int n,
                                                              int tokens_per_slice, const float* __restrict__ cosv,
@@ -85,14 +88,14 @@ __global__ __launch_bounds__(256, 1) void absorb_mfma_kernel(float* __restrict__
   const bf16_t* Kh = K + (size_t)bh * n * D;
   const bf16_t* Vh = V + (size_t)bh * n * D;
   const int g = tid & 15;   // feature group: features 8g .. 8g+7
-  const int tp0 = tid >> 4; // token pair of item 0; item 1 is 16 pairs further
+  const int tp0 = tid >> 4; // token pair of item 0; further items are TPI pairs apart
 
   if (tid < D) zs[tid] = 0.0f;
 
   auto load = [&](int tb, Regs& r) {
 #pragma unroll
-    for (int it = 0; it < 2; ++it) {
-      const int tok = tb + 2 * (tp0 + 16 * it);
+    for (int it = 0; it < ITEMS; ++it) {
+      const int tok = tb + 2 * (tp0 + TPI * it);
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         if (tok + u < t1) {
@@ -110,22 +113,23 @@ __global__ __launch_bounds__(256, 1) void absorb_mfma_kernel(float* __restrict__
 #pragma unroll
   for (int e = 0; e < 8; ++e) zacc[e] = 0.0f;
 
-  f32x16 acc[2][2];
+  constexpr int TA = 8 / (NT / 64);   // 32x32 tiles per wave along the key features (4x4 tiles in all)
+  f32x16 acc[TA][2];
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < TA; ++a)
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.0f;
 
-  const int mi0 = 2 * (wave >> 1), nj0 = 2 * (wave & 1);  // this wave's 2x2 grid of 32x32 tiles
+  const int mi0 = TA * (wave >> 1), nj0 = 2 * (wave & 1);  // this wave's TA x 2 grid of 32x32 tiles
   const int h = lane >> 5, l32 = lane & 31;
 
   // transform one chunk held in registers, pack token pairs, transposing store to LDS
   auto stage = [&](int tb, Regs& cur) {
 #pragma unroll
-    for (int it = 0; it < 2; ++it) {
-      const int tp = tp0 + 16 * it;
+    for (int it = 0; it < ITEMS; ++it) {
+      const int tp = tp0 + TPI * it;
       uint32_t kw[2][4] = {{cur.k[it][0].x, cur.k[it][0].y, cur.k[it][0].z, cur.k[it][0].w},
                            {cur.k[it][1].x, cur.k[it][1].y, cur.k[it][1].z, cur.k[it][1].w}};
       const uint32_t vw[2][4] = {{cur.v[it][0].x, cur.v[it][0].y, cur.v[it][0].z, cur.v[it][0].w},
@@ -175,9 +179,9 @@ __global__ __launch_bounds__(256, 1) void absorb_mfma_kernel(float* __restrict__
   auto contract = [&]() {
 #pragma unroll
     for (int ks = 0; ks < CH / 16; ++ks) {
-      bf16x8 af[2], bf[2];
+      bf16x8 af[TA], bf[2];
 #pragma unroll
-      for (int a = 0; a < 2; ++a) {
+      for (int a = 0; a < TA; ++a) {
         const int f = 32 * (mi0 + a) + l32;
         af[a] = *reinterpret_cast<const bf16x8*>(&Kt[f * SP + pair_col(f, 8 * ks + 4 * h)]);
       }
@@ -187,7 +191,7 @@ __global__ __launch_bounds__(256, 1) void absorb_mfma_kernel(float* __restrict__
         bf[b] = *reinterpret_cast<const bf16x8*>(&Vt[f * SP + pair_col(f, 8 * ks + 4 * h)]);
       }
 #pragma unroll
-      for (int a = 0; a < 2; ++a)
+      for (int a = 0; a < TA; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b)
           acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[b], acc[a][b], 0, 0, 0);
@@ -222,7 +226,7 @@ __global__ __launch_bounds__(256, 1) void absorb_mfma_kernel(float* __restrict__
 #pragma unroll
   for (int e = 0; e < 8; ++e) atomicAdd(&zs[8 * g + e], zacc[e]);
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < TA; ++a)
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
@@ -316,10 +320,10 @@ int launch_absorb_mfma(const hf_config& c, float* state, const void* K, const vo
   const int heads_per_xcd = (BH + 7) / 8;
   const dim3 grid(use_ws ? BH * slices : 8 * heads_per_xcd * slices);
   if (plain) {
-    hipLaunchKernelGGL((absorb_mfma_kernel<true>), grid, dim3(256), 0, s, state, partials, Kp, Vp, n, per, cosv,
+    hipLaunchKernelGGL((absorb_mfma_kernel<true>), grid, dim3(NT), 0, s, state, partials, Kp, Vp, n, per, cosv,
                        sinv, c.phi, BH, slices);
   } else {
-    hipLaunchKernelGGL((absorb_mfma_kernel<false>), grid, dim3(256), 0, s, state, partials, Kp, Vp, n, per, cosv,
+    hipLaunchKernelGGL((absorb_mfma_kernel<false>), grid, dim3(NT), 0, s, state, partials, Kp, Vp, n, per, cosv,
                        sinv, c.phi, BH, slices);
   }
   const int rc = check_launch("hf_absorb_evicted");
