@@ -41,6 +41,19 @@ constexpr float kRescaleThreshold = 8.0f;  // log2 units: rescale only when a ro
 
 // History branch fused into the epilogue (kFused): planes = the fp32 state split into two bf16
 // planes, transposed (Lt[plane][j][i], see hf_readout_mfma.hip), zvec = the state's normaliser.
+// max without the NaN-quieting canonicalisation the compiler adds around fmaxf (scores are finite
+// or -inf here): one instruction per three inputs
+__device__ __forceinline__ float max3f(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+__device__ __forceinline__ float max2f(float a, float b) {
+  float r;
+  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+
 struct HistArgs {
   const bf16_t* planes;  // [BH][2][d][d]
   const float* zvec;     // [BH][d]
@@ -179,26 +192,28 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
   // One tile: consume LDS half `par`, move tile t+1 (staging set `kr`, `vr`) to the other half,
   // refill that set with tile t+3.  One barrier per tile.
   auto tile_step = [&](const int par, const int valid_cur, int& valid_new, u32x4 (&kr)[CPT], u32x4 (&vr)[CPT]) {
-    // ---- S^T = K Q^T : 32 keys, 8 steps over d in two independent accumulation chains
-    f32x16 sa, sb;
+    // ---- S^T = K Q^T : 32 keys, 8 steps over d
+    f32x16 sacc;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { sa[r] = 0.0f; sb[r] = 0.0f; }
+    for (int r = 0; r < 16; ++r) sacc[r] = 0.0f;
 #pragma unroll
-    for (int s = 0; s < 8; s += 2) {
-      const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(k_rd + par * KTILE + 32 * s);
-      const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(k_rd + par * KTILE + 32 * s + 32);
-      sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[s], sa, 0, 0, 0);
-      sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[s + 1], sb, 0, 0, 0);
+    for (int s = 0; s < 8; ++s) {
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(k_rd + par * KTILE + 32 * s);
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[s], sacc, 0, 0, 0);
     }
+    // the first half of the V^T fragments is requested now: the reads complete under the softmax
+    // (the barrier keeps the compiler from sinking them down to their use)
+    bf16x8 vf[4];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+      vf[dt] = *reinterpret_cast<const bf16x8*>(&sVt[v_row[dt] + ((16 * par + v_rot[dt]) & 31)]);
+    __builtin_amdgcn_sched_barrier(0);
 
     // ---- tile t+1: registers -> the other LDS half; tile t+3: global -> the same registers
     lstore(par ^ 1, kr, vr);
     next_tile(start_t, valid_new);
     gload(start_t, kr, vr);
 
-    f32x16 sacc;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) sacc[r] = sa[r] + sb[r];
     if (valid_cur < TK) {  // keys that do not exist never contribute
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -208,12 +223,14 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
     }
 
     // ---- online softmax in the exp2 domain; statistics are per lane (= per query)
-    float mx = fmaxf(sacc[0], sacc[1]);
-#pragma unroll
-    for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(sacc[r], sacc[r + 1]));
+    float mx;
     {
+      const float m0 = max3f(sacc[0], sacc[1], sacc[2]), m1 = max3f(sacc[3], sacc[4], sacc[5]);
+      const float m2 = max3f(sacc[6], sacc[7], sacc[8]), m3 = max3f(sacc[9], sacc[10], sacc[11]);
+      const float m4 = max3f(sacc[12], sacc[13], sacc[14]);
+      mx = max2f(max3f(m0, m1, m2), max3f(m3, m4, sacc[15]));
       const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-      mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1])) * c_scale;  // both lanes of a query agree
+      mx = max2f(__uint_as_float(sw[0]), __uint_as_float(sw[1])) * c_scale;  // both lanes of a query agree
     }
     // lazy rescale: keep the reference max unless some row's max grew by more than the threshold
     if (__any(mx > m_ref + kRescaleThreshold)) {
@@ -240,12 +257,13 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
 
     // ---- O^T += V^T P^T : 2 steps of 16 keys, 4 tiles of 32 features
 #pragma unroll
-    for (int t2 = 0; t2 < 2; ++t2)
+    for (int dt = 0; dt < 4; ++dt) {
+      const bf16x8 a = vf[dt];
+      vf[dt] = *reinterpret_cast<const bf16x8*>(&sVt[v_row[dt] + ((16 * par + 8 + v_rot[dt]) & 31)]);
+      o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[0], o[dt], 0, 0, 0);
+    }
 #pragma unroll
-      for (int dt = 0; dt < 4; ++dt) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&sVt[v_row[dt] + ((16 * par + 8 * t2 + v_rot[dt]) & 31)]);
-        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[t2], o[dt], 0, 0, 0);
-      }
+    for (int dt = 0; dt < 4; ++dt) o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt], pf[1], o[dt], 0, 0, 0);
 
     __syncthreads();  // tile t is consumed everywhere, tile t+1 is complete in LDS
   };
