@@ -39,6 +39,8 @@ def parse():
     p.add_argument("--layers", type=int, default=6, help="distinct layer tensor sets rotated through")
     p.add_argument("--keep-ratio", type=float, default=None)
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--eager", action="store_true",
+                   help="time eager single-stream launches instead of one captured HIP graph per step")
     p.add_argument("--cpu-heads", type=int, default=0, help="heads per layer the oracle is timed on (0 = all)")
     p.add_argument("--cpu-layers", type=int, default=6, help="layer sets the oracle is timed on")
     p.add_argument("--calibration-copy-mib", type=int, default=0,
@@ -127,21 +129,48 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for i in range(a.warmup):
+    for i in range(max(a.warmup, nl if not a.eager else 0)):
         step(sets[i % nl])
     torch.cuda.synchronize()
 
-    # ---- timed region: exactly `steps` steps; HIP events on the launch stream give per-call times
+    # ---- per-call times: eager launches with HIP events on the launch stream
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(a.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(a.steps):
         step(sets[i % nl], evs[i])
     torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    wall_eager = time.perf_counter() - t0
     sel_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
     fwd_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))
     abs_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in evs]))
+
+    # ---- timed region: exactly `steps` steps, launched as captured HIP graphs (same kernels, same
+    # order, same stream as the eager step; what goes away is the host's launch gap between the six
+    # kernels of a step).  One graph holds one pass over the rotated layer sets; a remainder of
+    # steps runs from single-step graphs.
+    if a.eager:
+        wall, mode = wall_eager, "eager launches"
+    else:
+        def capture(group):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                for s in group:
+                    step(s)
+            return g
+        g_all = capture(sets)
+        g_one = [capture([s]) for s in sets[:a.steps % nl]]
+        def run_steps(n):
+            for _ in range(n // nl):
+                g_all.replay()
+            for g in g_one[:n % nl]:
+                g.replay()
+        run_steps(max(a.warmup, nl))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run_steps(a.steps)
+        torch.cuda.synchronize()
+        wall, mode = time.perf_counter() - t0, f"HIP graphs of {nl} steps"
     ms_per_step = wall * 1e3 / a.steps
 
     # ---- the sparse flash forward alone (no state => only that kernel runs), same inputs
@@ -188,6 +217,8 @@ def main():
         "steps": a.steps,
         "warmup": a.warmup,
         "ms_per_step": ms_per_step,
+        "launch": mode,
+        "ms_per_step_eager": wall_eager * 1e3 / a.steps,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,

@@ -1,0 +1,87 @@
+"""The whole step as a captured HIP graph, the way bench.py launches it, and a two-stream variant
+in which the evicted chunk is absorbed on a second stream while the blocks are selected.
+
+Every replay is compared with the same step run eagerly on one stream on buffers of its own;
+between replays the process does eager work and synchronises, so that a node whose effect
+survived only the first replay would show.  The captured calls hold no memset (buffers are
+cleared by fill kernels) and allocate nothing.
+"""
+import pytest
+import torch
+
+import paper_2604_10103_amd as hf
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+class Buffers:
+    def __init__(self, cfg, w, Q, K, V, Ke, Ve):
+        self.cfg = cfg
+        self.Q, self.K, self.V, self.Ke, self.Ve = (t.to(DEV) for t in (Q, K, V, Ke, Ve))
+        k = hf.hf_select_k(cfg, w.n_kv)
+        self.idx = torch.full((w.batch, w.heads, w.t_m, k), -1, dtype=torch.int32, device=DEV)
+        self.O = torch.zeros(Q.shape, dtype=Q.dtype, device=DEV)
+        self.ws = torch.empty(hf.hf_workspace_bytes(cfg, w.n_q, w.n_kv), dtype=torch.uint8, device=DEV)
+        nb = hf.hf_absorb_workspace_bytes(cfg, Ke.shape[2])
+        self.aws = torch.empty(nb, dtype=torch.uint8, device=DEV) if nb else None
+        self.st = torch.empty(hf.hf_state_bytes(cfg) // 4, dtype=torch.float32, device=DEV)
+        hf.hf_state_init(cfg, self.st)
+        hf.hf_absorb_evicted(cfg, self.st, self.Ke, self.Ve, workspace=self.aws)   # a non-empty history
+
+    def eager_step(self):
+        hf.hf_absorb_evicted(self.cfg, self.st, self.Ke, self.Ve, workspace=self.aws)
+        hf.hf_block_select(self.cfg, self.Q, self.K, self.idx, None, self.ws)
+        hf.hf_hybrid_attn_fwd(self.cfg, self.Q, self.K, self.V, self.idx, self.st, self.O, self.ws)
+
+    def capture(self, two_streams):
+        g = torch.cuda.CUDAGraph()
+        if not two_streams:
+            with torch.cuda.graph(g):
+                self.eager_step()
+            return g
+        side = torch.cuda.Stream()
+        with torch.cuda.graph(g):
+            main = torch.cuda.current_stream()
+            side.wait_stream(main)
+            with torch.cuda.stream(side):
+                hf.hf_absorb_evicted(self.cfg, self.st, self.Ke, self.Ve, workspace=self.aws)
+            hf.hf_block_select(self.cfg, self.Q, self.K, self.idx, None, self.ws)
+            main.wait_stream(side)
+            hf.hf_hybrid_attn_fwd(self.cfg, self.Q, self.K, self.V, self.idx, self.st, self.O, self.ws)
+        return g
+
+
+@pytest.mark.parametrize("name,two_streams", [("small_bf16", False), ("small_bf16", True), ("tiny_f32", False),
+                                              ("step_832x480", False), ("step_832x480", True)])
+def test_captured_step_replays_match_eager(name, two_streams):
+    w = wl.get(name)
+    cfg = hf.make_config(batch=w.batch, heads=w.heads, head_dim=w.head_dim, dtype=w.dtype, block_q=w.block,
+                         block_kv=w.block, keep_ratio=w.keep_ratio)
+    Q, K, V = wl.make_qkv(w)
+    Ke, Ve = wl.make_evicted(w, 0)
+    ref = Buffers(cfg, w, Q, K, V, Ke, Ve)
+    cap = Buffers(cfg, w, Q, K, V, Ke, Ve)
+    torch.cuda.synchronize()
+    before = cap.st.clone()
+    g = cap.capture(two_streams)            # capturing runs nothing: cap.st still holds one absorbed chunk
+    torch.cuda.synchronize()
+    assert torch.equal(before, cap.st)
+    scratch = torch.zeros(1 << 20, device=DEV)
+    for rep in range(4):
+        ref.eager_step()
+        scratch.add_(1.0)        # the program's own eager work between replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(cap.idx, ref.idx), rep
+        # the normaliser z is summed with LDS float atomics, whose order is not fixed: the state agrees
+        # to fp32 rounding, the output to one rounding step of its type
+        torch.testing.assert_close(cap.st, ref.st, rtol=1e-5, atol=1e-6)
+        if w.dtype == "bf16":
+            torch.testing.assert_close(cap.O.float(), ref.O.float(), rtol=1e-2, atol=1e-3)
+        else:
+            torch.testing.assert_close(cap.O, ref.O, rtol=1e-4, atol=1e-5)
+        assert torch.isfinite(cap.O.float()).all()
