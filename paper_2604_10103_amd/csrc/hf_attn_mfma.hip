@@ -14,13 +14,13 @@
 // which a lane holds keys, so V is transposed on its way into LDS with the key pairs stored in
 // that order: a V^T fragment is one conflict-free 16-byte read.
 //
-// The CU's LDS port is what bounds this kernel at block_q 64: every query block stages its own
-// 8 KB of K and 8 KB of V per 32 keys (LDS stores run at 64 B/clk), which at full MFMA rate is
-// exactly that port's throughput, and every wavefront's LDS round trips queue behind it.  LDS
-// holds two tiles (ping-pong): while tile t is consumed, tile t+1 moves registers -> LDS and
-// tile t+2 global -> registers (buffer loads, no branches); one workgroup barrier per tile.
-// Operand fragments are read a phase ahead of the MFMAs that use them, so that the LDS latency
-// of a wavefront overlaps its own softmax and matrix work.
+// What bounds this kernel at block_q 64: the matrix work and the vector work of the softmax do not
+// overlap on a SIMD of this chip (together about two thirds of the run time), and every query
+// block stages its own 8 KB of K and 8 KB of V per 32 keys through the CU's LDS store port
+// (64 B/clk), whose queue delays the other wavefronts' operand reads.  LDS holds two tiles
+// (ping-pong): while tile t is consumed, tile t+1 moves registers -> LDS and tiles t+2, t+3 are on
+// their way global -> registers (buffer loads, no branches); one workgroup barrier per tile.
+// The V^T fragments of a tile are requested before its softmax so that their LDS latency is hidden.
 #include "hf_common.h"
 
 namespace hf {
