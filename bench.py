@@ -195,6 +195,10 @@ def main():
 
     a4_ms, a4_min = time_calls(
         lambda s: hf.hf_hybrid_attn_fwd(cfg, s["Q"], s["K"], s["V"], s["idx"], None, s["O"], s["ws"]), a.steps)
+    # selection on the later denoising steps of a chunk: pooled keys of the unchanged older half reused
+    reuse = (w.n_kv - w.n_q) // w.block
+    selc_ms, _ = time_calls(
+        lambda s: hf.hf_block_select_cached(cfg, s["Q"], s["K"], reuse, s["idx"], None, s["ws"]), a.steps)
     dense_ms = None
     if not a.no_dense:
         dense_ms, _ = time_calls(
@@ -207,6 +211,14 @@ def main():
         lambda s: hf.hf_hybrid_attn_fwd(cfg, s["Q"], s["K"], s["V"], s["idx"], s["st"], s["O"], s["ws"]), a.steps)
     del os.environ["HF_FUSED_EPILOGUE"]
     a5_ms = max(fwd2_ms - a4_ms, 0.0)
+
+    # practical HBM ceiling at this size: a plain device copy of the readout's byte count (read + written)
+    n_copy = (3 * w.batch * w.heads * w.n_q * w.head_dim * esz) // 2
+    cp_src = [torch.empty(n_copy, dtype=torch.uint8, device=dev).fill_(l) for l in range(nl)]
+    cp_dst = torch.empty(n_copy, dtype=torch.uint8, device=dev)
+    it = iter(range(1 << 30))
+    copy_ms, _ = time_calls(lambda s: cp_dst.copy_(cp_src[next(it) % nl]), a.steps)
+    del cp_src, cp_dst
 
     flops = float(np.mean([algorithmic_flops(s["idx"].cpu(), w) for s in sets]))
     dense_flops = 4.0 * w.head_dim * w.n_q * w.n_kv * w.heads * w.batch
@@ -239,7 +251,7 @@ def main():
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": a4_tflops / PEAK_BF16_TFLOPS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if a.keep_ratio is None else None,
                      "flops_per_launch": flops, "avg_ms": a4_ms, "min_ms": a4_min},
-        "kernels_ms": {"block_select": sel_ms, "attn_fwd_total": fwd_ms, "sparse_flash_fwd": a4_ms,
+        "kernels_ms": {"block_select": sel_ms, "block_select_cached_half": selc_ms, "attn_fwd_total": fwd_ms, "sparse_flash_fwd": a4_ms,
                        "readout_combine_unfused": a5_ms, "fused_epilogue_extra": max(fwd_ms - a4_ms, 0.0), "absorb": abs_ms,
                        "dense_window_fwd": dense_ms},
         "hbm": {"absorb_GBs": absorb_bytes / (abs_ms * 1e-3) / 1e9,
@@ -247,6 +259,7 @@ def main():
                 "readout_GBs": (readout_bytes / (a5_ms * 1e-3) / 1e9) if a5_ms > 0 else None,
                 "readout_frac": (readout_bytes / (a5_ms * 1e-3) / 1e9 / PEAK_HBM_GBS) if a5_ms > 0 else None,
                 "select_GBs": select_bytes / (sel_ms * 1e-3) / 1e9,
+                "device_copy_GBs": 2 * n_copy / (copy_ms * 1e-3) / 1e9,
                 "peak_GBs": PEAK_HBM_GBS,
                 "bytes": {"absorb": absorb_bytes, "readout": readout_bytes, "select": select_bytes}},
     }

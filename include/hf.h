@@ -124,6 +124,20 @@ HF_API int hf_block_select(const hf_config* cfg, const void* Q, int32_t n_q,
                     int32_t* block_idx, float* scores_or_null,
                     void* workspace, size_t workspace_bytes, void* stream);
 
+/* hf_block_select for the denoising steps after a chunk's first (inference algorithm of the
+ * supplement: the older part of the window does not change between the steps of a chunk):
+ * the pooled means of the first n_cached_kv_blocks KV blocks are taken from the workspace as
+ * the previous hf_block_select / hf_block_select_cached call on the SAME workspace, cfg, n_q
+ * and n_kv left them; only the remaining blocks of K_win are read and pooled again.  The
+ * caller guarantees that the tokens of the reused blocks are unchanged and that nothing else
+ * wrote the workspace's pooled-key region in between (hf_hybrid_attn_fwd does not).
+ * 0 <= n_cached_kv_blocks <= floor(n_kv / block_kv) (whole blocks only); 0 = hf_block_select.
+ * Same outputs, bit for bit, as hf_block_select on the same K_win. */
+HF_API int hf_block_select_cached(const hf_config* cfg, const void* Q, int32_t n_q,
+                    const void* K_win, int32_t n_kv, int32_t n_cached_kv_blocks,
+                    int32_t* block_idx, float* scores_or_null,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
 /* Eq. 5 + Eq. 3 + Eq. 6 for one chunk:
  *   O_local = softmax over the keys of the selected blocks of (Q K^T * scale) times V
  *             (online softmax, fp32 statistics and accumulation);

@@ -21,5 +21,6 @@ from .binding import (  # noqa: F401
     hf_select_k,
     hf_workspace_bytes,
     hf_block_select,
+    hf_block_select_cached,
     hf_hybrid_attn_fwd,
 )

@@ -78,10 +78,11 @@ def load():
     lib.hf_select_k.argtypes = [CP, I, ctypes.POINTER(I)]
     lib.hf_workspace_bytes.argtypes = [CP, I, I, ctypes.POINTER(SZ)]
     lib.hf_block_select.argtypes = [CP, P, I, P, I, P, P, P, SZ, P]
+    lib.hf_block_select_cached.argtypes = [CP, P, I, P, I, I, P, P, P, SZ, P]
     lib.hf_hybrid_attn_fwd.argtypes = [CP, P, I, P, P, I, P, I, P, P, P, P, P, SZ, P]
     for name in ("hf_state_bytes", "hf_state_init", "hf_absorb_evicted", "hf_absorb_workspace_bytes", "hf_select_k",
                  "hf_workspace_bytes",
-                 "hf_block_select", "hf_hybrid_attn_fwd"):
+                 "hf_block_select", "hf_block_select_cached", "hf_hybrid_attn_fwd"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -172,14 +173,22 @@ def hf_absorb_evicted(cfg: hf_config, state, K_ev, V_ev, rope_cos=None, rope_sin
 
 def hf_block_select(cfg: hf_config, Q, K_win, block_idx, scores=None, workspace=None) -> None:
     """block_idx: int32 [B,H,T_m,k] out; scores: optional fp32 [B,H,T_m,T_n] out; workspace: uint8 buffer."""
+    hf_block_select_cached(cfg, Q, K_win, 0, block_idx, scores, workspace, _entry="hf_block_select")
+
+
+def hf_block_select_cached(cfg: hf_config, Q, K_win, n_cached_kv_blocks: int, block_idx, scores=None,
+                           workspace=None, _entry="hf_block_select_cached") -> None:
+    """As hf_block_select; the pooled means of the first n_cached_kv_blocks KV blocks are reused from the
+    previous call on the same workspace (the caller guarantees those tokens did not change)."""
     B, H, d = cfg.batch, cfg.heads, cfg.head_dim
     n_q, n_kv = Q.shape[2], K_win.shape[2]
     t_m, t_n = _cdiv(n_q, cfg.block_q), _cdiv(n_kv, cfg.block_kv)
     k = hf_select_k(cfg, n_kv)
     ws_ptr = _dev(workspace, "workspace", torch.uint8)
-    _check(load().hf_block_select(
+    extra = () if _entry == "hf_block_select" else (int(n_cached_kv_blocks),)
+    _check(getattr(load(), _entry)(
         ctypes.byref(cfg), _dev(Q, "Q", _tdtype(cfg), (B, H, n_q, d)), n_q,
-        _dev(K_win, "K_win", _tdtype(cfg), (B, H, n_kv, d)), n_kv,
+        _dev(K_win, "K_win", _tdtype(cfg), (B, H, n_kv, d)), n_kv, *extra,
         _dev(block_idx, "block_idx", torch.int32, (B, H, t_m, k)),
         _dev(scores, "scores", torch.float32, (B, H, t_m, t_n)),
         ws_ptr, 0 if workspace is None else workspace.numel(), _stream()))

@@ -171,6 +171,13 @@ int hf_workspace_bytes(const hf_config* cfg, int32_t n_q, int32_t n_kv, size_t* 
 int hf_block_select(const hf_config* cfg, const void* Q, int32_t n_q, const void* K_win, int32_t n_kv,
                     int32_t* block_idx, float* scores_or_null, void* workspace, size_t workspace_bytes,
                     void* stream) {
+  return hf_block_select_cached(cfg, Q, n_q, K_win, n_kv, 0, block_idx, scores_or_null, workspace, workspace_bytes,
+                                stream);
+}
+
+int hf_block_select_cached(const hf_config* cfg, const void* Q, int32_t n_q, const void* K_win, int32_t n_kv,
+                           int32_t n_cached_kv_blocks, int32_t* block_idx, float* scores_or_null, void* workspace,
+                           size_t workspace_bytes, void* stream) {
   HF_TRY(check_cfg(cfg));
   HF_TRY(check_ptr(Q, "Q", true));
   HF_TRY(check_ptr(K_win, "K_win", true));
@@ -181,6 +188,11 @@ int hf_block_select(const hf_config* cfg, const void* Q, int32_t n_q, const void
   const int t_m = cdiv(n_q, cfg->block_q), t_n = cdiv(n_kv, cfg->block_kv);
   if (t_n > kMaxSelectBlocks) {
     set_error("window has %d KV blocks; the selection kernel ranks at most %d", t_n, kMaxSelectBlocks);
+    return HF_ERR_SHAPE;
+  }
+  if (n_cached_kv_blocks < 0 || n_cached_kv_blocks > n_kv / cfg->block_kv) {
+    set_error("n_cached_kv_blocks=%d outside [0, %d] (whole KV blocks of the window)", n_cached_kv_blocks,
+              n_kv / cfg->block_kv);
     return HF_ERR_SHAPE;
   }
   const int k = select_k_of(cfg, t_n);
@@ -195,7 +207,7 @@ int hf_block_select(const hf_config* cfg, const void* Q, int32_t n_q, const void
   char* ws = static_cast<char*>(workspace);
   float* qbar = reinterpret_cast<float*>(ws + w.qbar);
   float* kbar = reinterpret_cast<float*>(ws + w.kbar);
-  HF_TRY(launch_pool_both(*cfg, Q, n_q, t_m, K_win, n_kv, t_n, qbar, kbar, s));
+  HF_TRY(launch_pool_both(*cfg, Q, n_q, t_m, K_win, n_kv, t_n, n_cached_kv_blocks, qbar, kbar, s));
   return launch_score_select(*cfg, qbar, kbar, t_m, t_n, k, block_idx, scores_or_null, s);
 }
 

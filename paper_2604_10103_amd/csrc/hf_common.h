@@ -84,7 +84,7 @@ int launch_absorb(const hf_config& c, float* state, const void* K, const void* V
                   hipStream_t s);
 size_t absorb_workspace_bytes(const hf_config& c, int n);
 int launch_pool_both(const hf_config& c, const void* Q, int n_q, int t_m, const void* K, int n_kv, int t_n,
-                     float* qbar, float* kbar_t, hipStream_t s);
+                     int kv_first, float* qbar, float* kbar_t, hipStream_t s);
 int launch_score_select(const hf_config& c, const float* qbar, const float* kbar_t, int t_m, int t_n,
                         int k, int32_t* idx, float* scores, hipStream_t s);
 int launch_attn(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,

@@ -105,6 +105,10 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_launch(lib):
     assert lib.hf_absorb_evicted(c, 4096, 4096, 4096, 10, None, None, 4096 + 16, 1 << 20, None) == -4   # workspace alignment
     assert lib.hf_block_select(c, 4096, 100, 4096, 200, 4096, None, None, 0, None) == -5
     assert lib.hf_block_select(c, 4096, 100, 4096, 200, 4096, None, 4096 + 16, 1 << 30, None) == -4
+    # reused pooled keys: whole blocks of the window only (200 tokens = 3 whole blocks of 64)
+    assert lib.hf_block_select_cached(c, 4096, 100, 4096, 200, 4, 4096, None, 4096, 1 << 30, None) == -2
+    assert lib.hf_block_select_cached(c, 4096, 100, 4096, 200, -1, 4096, None, 4096, 1 << 30, None) == -2
+    assert lib.hf_block_select_cached(c, 4096, 100, 4096, 200, 3, 4096, None, None, 0, None) == -5
     # O aliases Q
     assert lib.hf_hybrid_attn_fwd(c, 4096, 100, 8192, 8192, 200, None, 0, None, None, None, 4096, None, 0, None) == -2
     # k out of range with an index list

@@ -172,6 +172,41 @@ def test_selection_ties_and_keep_all():
     assert np.array_equal(idx.cpu().numpy(), np.broadcast_to(np.arange(k, dtype=np.int32), idx.shape))
 
 
+@pytest.mark.parametrize("name", ["small_bf16", "tiny_f32", "small_b128"])
+def test_selection_with_reused_pooled_keys(name):
+    # denoising steps of one chunk: the older half of the window is fixed, the chunk's own K changes;
+    # the pooled means of the unchanged whole blocks are reused from the previous call's workspace
+    w = wl.get(name)
+    cfg = cfg_of(w)
+    k = hf.hf_select_k(cfg, w.n_kv)
+    ws = new_workspace(cfg, w.n_q, w.n_kv)
+    idx = torch.full((w.batch, w.heads, w.t_m, k), -1, dtype=torch.int32, device=DEV)
+    scores = torch.empty((w.batch, w.heads, w.t_m, w.t_n), dtype=torch.float32, device=DEV)
+    Q0, K0, _ = wl.make_qkv(w, step=0)
+    hf.hf_block_select(cfg, Q0.to(DEV), K0.to(DEV), idx, scores, ws)
+    half = w.n_kv - w.n_q                      # tokens of the cached part
+    reuse = half // w.block                    # its whole blocks (a straddling block is pooled again)
+    assert 0 < reuse < w.t_n
+    for step in (1, 2):
+        Q, Kn, _ = wl.make_qkv(w, step=step)
+        K = torch.cat([K0[:, :, :half], Kn[:, :, half:]], dim=2).contiguous()
+        hf.hf_block_select_cached(cfg, Q.to(DEV), K.to(DEV), reuse, idx, scores, ws)
+        torch.cuda.synchronize()
+        got_idx, got_sc = idx.cpu().numpy().copy(), scores.cpu().numpy().copy()
+        for h, (q, kk) in enumerate(zip(heads_of(Q), heads_of(K))):
+            A = orc.block_scores(q, kk, w.block, w.block)
+            assert np.abs(got_sc[0, h] - A).max() <= 1e-5 * max(1.0, np.abs(A).max())
+            check_block_idx(got_idx[0, h], A, k)
+        # bit for bit what the full pooling gives on the same window (in a fresh workspace)
+        idx2, sc2, _ = gpu_select(cfg, w, Q.to(DEV), K.to(DEV))
+        assert np.array_equal(got_idx, idx2.cpu().numpy())
+        assert np.array_equal(got_sc, sc2.cpu().numpy())
+    # reusing everything that is whole, with nothing changed, is the identity
+    hf.hf_block_select_cached(cfg, Q.to(DEV), K.to(DEV), w.n_kv // w.block, idx, scores, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy(), got_idx) and np.array_equal(scores.cpu().numpy(), got_sc)
+
+
 # ------------------------------------------------------------------------------- attention (Eq. 5, 3, 6)
 def run_hybrid(cfg, w, Q, K, V, idx, st, tables=None):
     O = torch.full(Q.shape, float("nan"), dtype=Q.dtype, device=DEV)
