@@ -194,7 +194,7 @@ __global__ __launch_bounds__(NT, 1) void absorb_mfma_kernel(float* __restrict__ 
       for (int a = 0; a < TA; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b)
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[b], acc[a][b], 0, 0, 0);
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[b], af[a], acc[a][b], 0, 0, 0);  // L^T tile
     }
   };
 
@@ -223,19 +223,43 @@ __global__ __launch_bounds__(NT, 1) void absorb_mfma_kernel(float* __restrict__ 
     L = state + (size_t)bh * D * D;
     z = state + (size_t)BH * D * D + (size_t)bh * D;
   }
+  // lanes l, l + 16, l + 32, l + 48 of a wavefront hold the same feature group: sum them first
 #pragma unroll
-  for (int e = 0; e < 8; ++e) atomicAdd(&zs[8 * g + e], zacc[e]);
+  for (int e = 0; e < 8; ++e) {
+    zacc[e] += __shfl_xor(zacc[e], 16, kWave);
+    zacc[e] += __shfl_xor(zacc[e], 32, kWave);
+  }
+  if (lane < 16) {
 #pragma unroll
-  for (int a = 0; a < TA; ++a)
+    for (int e = 0; e < 8; ++e) atomicAdd(&zs[8 * g + e], zacc[e]);
+  }
+  // The tiles were accumulated transposed (V fragment as the A operand): a lane holds, for ONE key
+  // feature i, four consecutive value features j per register group, i.e. 16 contiguous bytes of
+  // row i of L.  Two straight-line epilogues (a choice per element costs a branch each).
+  if (partials) {
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int a = 0; a < TA; ++a)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int i = 32 * (mi0 + a) + 8 * (r >> 2) + 4 * h + (r & 3);
-        const int j = 32 * (nj0 + b) + l32;
-        if (partials) L[i * D + j] = acc[a][b][r];
-        else atomicAdd(L + i * D + j, acc[a][b][r]);
-      }
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+          const int i = 32 * (mi0 + a) + l32;
+          const int j = 32 * (nj0 + b) + 8 * rq + 4 * h;
+          *reinterpret_cast<float4*>(L + i * D + j) =
+              make_float4(acc[a][b][4 * rq], acc[a][b][4 * rq + 1], acc[a][b][4 * rq + 2], acc[a][b][4 * rq + 3]);
+        }
+  } else {
+#pragma unroll
+    for (int a = 0; a < TA; ++a)
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int i = 32 * (mi0 + a) + l32;
+          const int j = 32 * (nj0 + b) + 8 * (r >> 2) + 4 * h + (r & 3);
+          atomicAdd(L + i * D + j, acc[a][b][r]);
+        }
+  }
   __syncthreads();
   if (tid < D) {
     if (partials) z[tid] = zs[tid];
