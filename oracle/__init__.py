@@ -17,5 +17,6 @@ from .hybrid_attention import (  # noqa: F401
     sparse_attention,
     dense_attention,
     history_readout,
+    state_fold_linear,
     hybrid_attention,
 )

@@ -16,7 +16,8 @@ Readings of the paper taken where it is silent or ambiguous (each is a conventio
 * H of Eq. 2 is read as z = sum over evicted tokens of phi(k_t) (a d-vector); a
   constant ``z_scale`` at readout reproduces the per-frame-mean reading.
 * ``phi(Q) H`` in Eq. 3 is the inner product phi(q).z, one scalar per query row.
-* The ``Linear`` map around Eq. 3 is the identity here (its weights are model state).
+* The ``Linear`` map around Eq. 3 is the identity by default; when a weight is given it is read as a
+  per-head d x d matrix without bias acting on the value features (``x -> x W``).
 * RoPE is given by caller-built per-token cos/sin tables ``[tokens, d/2]`` acting on
   adjacent feature pairs (2i, 2i+1); it is applied after phi, on the numerator only.
 * The readout divides by ``z_scale * phi(q).z + eps``.
@@ -200,20 +201,30 @@ def dense_attention(Q, K, V, scale=None) -> np.ndarray:
 
 # --------------------------------------------------------------------------- history readout, Eq. 3
 def history_readout(Q, L, z, phi_kind: int = PHI_RELU, cos=None, sin=None,
-                    eps: float = 1e-6, z_scale: float = 1.0) -> np.ndarray:
-    """Eq. 3 without the Linear map: R_q(phi(q)) L / (z_scale * phi(q).z + eps)."""
+                    eps: float = 1e-6, z_scale: float = 1.0, W=None) -> np.ndarray:
+    """Eq. 3: Linear( R_q(phi(q)) L / (z_scale * phi(q).z + eps) ); Linear = identity when W is None,
+    else right-multiplication of every output row by the d x d matrix W."""
     Q = _as2d(Q)
     fq = phi(Q, phi_kind)
     num = rope_rotate(fq, cos, sin) @ np.asarray(L, dtype=_F)
     den = z_scale * (fq @ np.asarray(z, dtype=_F)) + eps
-    return num / den[:, None]
+    out = num / den[:, None]
+    if W is not None:
+        out = out @ np.asarray(W, dtype=_F)
+    return out
+
+
+def state_fold_linear(L, W) -> np.ndarray:
+    """The state whose plain readout equals Linear(readout of L): the row-wise division of Eq. 3
+    commutes with a right-multiplication, so the map can be applied to L once: L W."""
+    return np.asarray(L, dtype=_F) @ np.asarray(W, dtype=_F)
 
 
 # --------------------------------------------------------------------------- Eq. 6
 def hybrid_attention(Q, K_win, V_win, state, b_q: int, b_kv: int, k: int,
                      phi_kind: int = PHI_RELU, cos_q=None, sin_q=None,
                      eps: float = 1e-6, z_scale: float = 1.0, scale=None,
-                     block_idx=None):
+                     block_idx=None, W=None):
     """The whole per-chunk path for one head: score, select, sparse attention,
     history readout, sum (Eq. 4, 5, 3, 6).
 
@@ -230,5 +241,5 @@ def hybrid_attention(Q, K_win, V_win, state, b_q: int, b_kv: int, k: int,
     if state is None:
         O_hist = np.zeros_like(O_local)
     else:
-        O_hist = history_readout(Q, state[0], state[1], phi_kind, cos_q, sin_q, eps, z_scale)
+        O_hist = history_readout(Q, state[0], state[1], phi_kind, cos_q, sin_q, eps, z_scale, W)
     return O_local + O_hist, O_local, O_hist, np.asarray(block_idx), gap

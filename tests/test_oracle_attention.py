@@ -179,6 +179,47 @@ def test_readout_empty_state_and_dead_queries_give_zero():
     np.testing.assert_array_equal(orc.history_readout(-np.abs(Q), L, z), np.zeros((5, d)))
 
 
+def test_linear_map_of_the_history_branch_and_its_fold_into_the_state():
+    # Eq. 3 with a per-head d x d Linear (no bias): pinned by the quadratic form with projected values,
+    # by the direct-sum state of projected values, and by special matrices
+    r = _rng(34)
+    n_q, n_ev, d, eps = 7, 19, 8, 1e-6
+    Q, K, V = r.normal(size=(n_q, d)), r.normal(size=(n_ev, d)), r.normal(size=(n_ev, d))
+    W = r.normal(size=(d, d))
+    aq, ak = r.uniform(-3, 3, size=(n_q, d // 2)), r.uniform(-3, 3, size=(n_ev, d // 2))
+    L, z = orc.state_absorb(*orc.state_zero(d), K, V, cos=np.cos(ak), sin=np.sin(ak))
+    O = orc.history_readout(Q, L, z, cos=np.cos(aq), sin=np.sin(aq), eps=eps, W=W)
+    # (a) the map acts on what the branch returns: weights of Eq. 3 times the PROJECTED value rows
+    plain = orc.history_readout(Q, L, z, cos=np.cos(aq), sin=np.sin(aq), eps=eps)
+    for i in range(n_q):
+        np.testing.assert_allclose(O[i], sum(plain[i, j] * W[j] for j in range(d)), atol=1e-12)
+    # (b) the same state as absorbing the projected values v_t W by direct sum (Eq. 2)
+    Lp, zp = orc.state_absorb(*orc.state_zero(d), K, V @ W, cos=np.cos(ak), sin=np.sin(ak))
+    np.testing.assert_allclose(orc.state_fold_linear(L, W), Lp, atol=1e-12)
+    np.testing.assert_array_equal(z, zp)
+    # (c) folding: the plain readout of the folded state is the mapped readout
+    np.testing.assert_allclose(orc.history_readout(Q, orc.state_fold_linear(L, W), z, cos=np.cos(aq), sin=np.sin(aq), eps=eps),
+                               O, atol=1e-12)
+    # (d) identity, a feature permutation and a diagonal scaling
+    np.testing.assert_array_equal(orc.history_readout(Q, L, z, eps=eps, W=np.eye(d)), orc.history_readout(Q, L, z, eps=eps))
+    perm = r.permutation(d)
+    np.testing.assert_allclose(orc.history_readout(Q, L, z, eps=eps, W=np.eye(d)[:, perm]),
+                               orc.history_readout(Q, L, z, eps=eps)[:, perm], atol=1e-15)
+    s = r.uniform(0.5, 2.0, size=d)
+    np.testing.assert_allclose(orc.history_readout(Q, L, z, eps=eps, W=np.diag(s)),
+                               orc.history_readout(Q, L, z, eps=eps) * s[None], rtol=1e-13)
+    # (e) a transposed W is a different map (guards the operand order)
+    assert not np.allclose(orc.history_readout(Q, L, z, eps=eps, W=W.T), O)
+    # (f) the whole path: only the history term is mapped
+    Kw, Vw = r.normal(size=(64, d)), r.normal(size=(64, d))
+    Qw = r.normal(size=(16, d))
+    Ow, Ol, Oh, _, _ = orc.hybrid_attention(Qw, Kw, Vw, (L, z), 16, 16, 2, W=W)
+    O0, Ol0, Oh0, _, _ = orc.hybrid_attention(Qw, Kw, Vw, (L, z), 16, 16, 2)
+    np.testing.assert_array_equal(Ol, Ol0)
+    np.testing.assert_allclose(Oh, Oh0 @ W, atol=1e-13)
+    np.testing.assert_allclose(Ow, Ol + Oh, atol=0)
+
+
 # ----------------------------------------------------------------------------- Eq. 6
 def test_hybrid_sum_and_null_state():
     r = _rng(41)
