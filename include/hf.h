@@ -85,6 +85,17 @@ HF_API int hf_state_bytes(const hf_config* cfg, size_t* bytes_out);
  * Uses a fill kernel (not a memset node), so it is safe to capture in a HIP graph. */
 HF_API int hf_state_init(const hf_config* cfg, void* state, void* stream);
 
+/* Linear map of the history branch (Eq. 3), read as a per-head d x d matrix W without bias acting
+ * on the value features (out = x W).  The row-wise division of Eq. 3 commutes with it, so it is
+ * folded into a copy of the state once per chunk:
+ *     L'[b,h] = L[b,h] W[h]      z' = z
+ * and hf_hybrid_attn_fwd on state_out then returns O_local + Linear(history term) at no cost on
+ * the per-step path.  fp32 arithmetic.
+ *   state_in   fp32 state (read-only)        state_out  fp32 state, must not alias state_in
+ *   W          fp32 [H, d, d] device, row = input feature, column = output feature, shared by batch */
+HF_API int hf_state_fold_linear(const hf_config* cfg, const void* state_in, const float* W,
+                         void* state_out, void* stream);
+
 /* Bytes of scratch that let hf_absorb_evicted combine its per-slice partial sums without
  * atomics (0 when the configuration has no such path).  Host-only. */
 HF_API int hf_absorb_workspace_bytes(const hf_config* cfg, int32_t n_tokens, size_t* bytes_out);

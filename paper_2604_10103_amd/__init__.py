@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     hf_version,
     hf_state_bytes,
     hf_state_init,
+    hf_state_fold_linear,
     hf_absorb_evicted,
     hf_absorb_workspace_bytes,
     hf_select_k,

@@ -73,6 +73,7 @@ def load():
     lib.hf_version.argtypes = []
     lib.hf_state_bytes.argtypes = [CP, ctypes.POINTER(SZ)]
     lib.hf_state_init.argtypes = [CP, P, P]
+    lib.hf_state_fold_linear.argtypes = [CP, P, P, P, P]
     lib.hf_absorb_evicted.argtypes = [CP, P, P, P, I, P, P, P, SZ, P]
     lib.hf_absorb_workspace_bytes.argtypes = [CP, I, ctypes.POINTER(SZ)]
     lib.hf_select_k.argtypes = [CP, I, ctypes.POINTER(I)]
@@ -80,7 +81,7 @@ def load():
     lib.hf_block_select.argtypes = [CP, P, I, P, I, P, P, P, SZ, P]
     lib.hf_block_select_cached.argtypes = [CP, P, I, P, I, I, P, P, P, SZ, P]
     lib.hf_hybrid_attn_fwd.argtypes = [CP, P, I, P, P, I, P, I, P, P, P, P, P, SZ, P]
-    for name in ("hf_state_bytes", "hf_state_init", "hf_absorb_evicted", "hf_absorb_workspace_bytes", "hf_select_k",
+    for name in ("hf_state_bytes", "hf_state_init", "hf_state_fold_linear", "hf_absorb_evicted", "hf_absorb_workspace_bytes", "hf_select_k",
                  "hf_workspace_bytes",
                  "hf_block_select", "hf_block_select_cached", "hf_hybrid_attn_fwd"):
         getattr(lib, name).restype = ctypes.c_int
@@ -153,6 +154,15 @@ def hf_state_init(cfg: hf_config, state: torch.Tensor) -> None:
     """state: fp32 GPU tensor of hf_state_bytes(cfg)/4 elements, zeroed in place."""
     n = hf_state_bytes(cfg) // 4
     _check(load().hf_state_init(ctypes.byref(cfg), _dev(state, "state", torch.float32, (n,)), _stream()))
+
+
+def hf_state_fold_linear(cfg: hf_config, state_in, W, state_out) -> None:
+    """state_out = state_in with L[b,h] replaced by L[b,h] @ W[h]; W: fp32 GPU tensor [H, d, d]."""
+    n = hf_state_bytes(cfg) // 4
+    d = cfg.head_dim
+    _check(load().hf_state_fold_linear(
+        ctypes.byref(cfg), _dev(state_in, "state_in", torch.float32, (n,)),
+        _dev(W, "W", torch.float32, (cfg.heads, d, d)), _dev(state_out, "state_out", torch.float32, (n,)), _stream()))
 
 
 def hf_absorb_evicted(cfg: hf_config, state, K_ev, V_ev, rope_cos=None, rope_sin=None, workspace=None) -> None:

@@ -118,6 +118,21 @@ int hf_state_init(const hf_config* cfg, void* state, void* stream) {
                           static_cast<hipStream_t>(stream));
 }
 
+int hf_state_fold_linear(const hf_config* cfg, const void* state_in, const float* W, void* state_out,
+                         void* stream) {
+  HF_TRY(check_cfg(cfg));
+  HF_TRY(check_ptr(state_in, "state_in", true));
+  HF_TRY(check_ptr(W, "W", true));
+  HF_TRY(check_ptr(state_out, "state_out", true));
+  const size_t d = cfg->head_dim;
+  const size_t bytes = (size_t)cfg->batch * cfg->heads * (d * d + d) * sizeof(float);
+  const char* a = static_cast<const char*>(state_in);
+  const char* b = static_cast<const char*>(state_out);
+  if (a < b + bytes && b < a + bytes) { set_error("state_out overlaps state_in"); return HF_ERR_SHAPE; }
+  return launch_fold_linear(*cfg, static_cast<const float*>(state_in), W, static_cast<float*>(state_out),
+                            static_cast<hipStream_t>(stream));
+}
+
 int hf_absorb_workspace_bytes(const hf_config* cfg, int32_t n_tokens, size_t* bytes_out) {
   HF_TRY(check_cfg(cfg));
   if (!bytes_out) { set_error("bytes_out is NULL"); return HF_ERR_NULL; }

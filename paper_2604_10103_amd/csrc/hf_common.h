@@ -79,6 +79,7 @@ struct Dims {
 
 // Launchers implemented in the .hip files.  All pointers are device pointers.
 int launch_fill_zero(float* p, size_t n, hipStream_t s);
+int launch_fold_linear(const hf_config& c, const float* state_in, const float* W, float* state_out, hipStream_t s);
 int launch_absorb(const hf_config& c, float* state, const void* K, const void* V, int n,
                   const float* cosv, const float* sinv, void* workspace, size_t workspace_bytes,
                   hipStream_t s);

@@ -25,6 +25,55 @@ int launch_fill_zero(float* p, size_t n, hipStream_t s) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Linear map of Eq. 3 folded into the state: L'[bh] = L[bh] W[h], z' = z.  Runs once per chunk on
+// 0.8 MB, fp32 FMA: one workgroup per 16 rows of one head's L; thread (row, column group) forms 8
+// (or 4) output columns; the 16 rows of L sit in LDS (broadcast reads), W streams from L2 with
+// the 16 column groups of a row reading 512 (256) contiguous bytes.
+template <int D>
+__global__ __launch_bounds__(256) void fold_linear_kernel(const float* __restrict__ state_in,
+                                                          const float* __restrict__ W,
+                                                          float* __restrict__ state_out, int H, int BH) {
+  constexpr int C = D / 16;  // output columns per thread
+  __shared__ float sL[16][D];
+  const int tid = threadIdx.x, row = tid >> 4, cg = tid & 15;
+  const int bh = blockIdx.y, h = bh % H, i0 = blockIdx.x * 16;
+  const float* Lin = state_in + (size_t)bh * D * D + (size_t)i0 * D;
+  for (int e = tid; e < 16 * D; e += 256) sL[e / D][e % D] = Lin[e];
+  if (blockIdx.x == 0 && tid < D)  // the normaliser is copied unchanged
+    state_out[(size_t)BH * D * D + (size_t)bh * D + tid] = state_in[(size_t)BH * D * D + (size_t)bh * D + tid];
+  __syncthreads();
+  const float* Wh = W + (size_t)h * D * D + cg * C;
+  float acc[C];
+#pragma unroll
+  for (int c = 0; c < C; ++c) acc[c] = 0.0f;
+#pragma unroll 4
+  for (int j = 0; j < D; ++j) {
+    const float l = sL[row][j];
+    float w[C];
+#pragma unroll
+    for (int c = 0; c < C; c += 4) {
+      const float4 v = *reinterpret_cast<const float4*>(Wh + (size_t)j * D + c);
+      w[c] = v.x; w[c + 1] = v.y; w[c + 2] = v.z; w[c + 3] = v.w;
+    }
+#pragma unroll
+    for (int c = 0; c < C; ++c) acc[c] = fmaf(l, w[c], acc[c]);
+  }
+  float* out = state_out + (size_t)bh * D * D + (size_t)(i0 + row) * D + cg * C;
+#pragma unroll
+  for (int c = 0; c < C; c += 4) *reinterpret_cast<float4*>(out + c) = make_float4(acc[c], acc[c + 1], acc[c + 2], acc[c + 3]);
+}
+
+int launch_fold_linear(const hf_config& c, const float* state_in, const float* W, float* state_out, hipStream_t s) {
+  const int BH = c.batch * c.heads;
+  const dim3 grid(c.head_dim / 16, BH), block(256);
+  if (c.head_dim == 128)
+    hipLaunchKernelGGL((fold_linear_kernel<128>), grid, block, 0, s, state_in, W, state_out, c.heads, BH);
+  else
+    hipLaunchKernelGGL((fold_linear_kernel<64>), grid, block, 0, s, state_in, W, state_out, c.heads, BH);
+  return check_launch("hf_state_fold_linear");
+}
+
+// ---------------------------------------------------------------------------------------------
 // fp32 FMA path (any storage dtype, fp32 arithmetic): used for fp32 inputs.
 // 256 threads own a D x D register tile grid: thread (ti, tj) holds an E x E tile, E = D / 16.
 // Tokens are staged TT at a time in LDS as fp32 (rotated phi(k) and v).

@@ -98,6 +98,8 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_launch(lib):
     c = ctypes.byref(cfg)
     assert lib.hf_state_init(c, None, None) == -1
     assert lib.hf_state_init(None, None, None) == -1
+    assert lib.hf_state_fold_linear(c, 4096, None, 1 << 24, None) == -1
+    assert lib.hf_state_fold_linear(c, 4096, 1 << 20, 4096 + 256, None) == -2      # state_out overlaps state_in
     assert lib.hf_absorb_evicted(c, 4096, None, 4096, 10, None, None, None, 0, None) == -1
     assert lib.hf_absorb_evicted(c, 4096, 4096, 4100, 10, None, None, None, 0, None) == -4
     assert lib.hf_absorb_evicted(c, 4096, 4096, 4096, 0, None, None, None, 0, None) == -2

@@ -95,6 +95,33 @@ def test_one_layer_step_832x480_all_heads():
     check_heads(w, cfg, L.k, Q, K, V, L.O, L.idx, states, range(w.heads))
 
 
+def test_linear_map_folded_into_the_state_at_full_size():
+    w = wl.get("step_832x480")
+    cfg = cfg_of(w)
+    L = Layer(cfg, w)
+    Ke, Ve = wl.make_evicted(w, 7)
+    L.absorb(Ke.to(DEV), Ve.to(DEV))
+    W = wl.randn((w.heads, w.head_dim, w.head_dim), 91_000 + w.cfg, w.head_dim ** -0.5, torch.float32)
+    folded = torch.empty_like(L.state)
+    hf.hf_state_fold_linear(cfg, L.state, W.to(DEV), folded)
+    plain, L.state = L.state, folded
+    Q, K, V = wl.make_qkv(w, layer=2)
+    L.attend(Q.to(DEV), K.to(DEV), V.to(DEV))
+    torch.cuda.synchronize()
+    Lg, _ = split_state(plain, w.heads, w.head_dim)
+    Lf, _ = split_state(folded, w.heads, w.head_dim)
+    W64 = W.double().numpy()
+    for h in range(w.heads):
+        assert rel_l2(Lf[h], orc.state_fold_linear(Lg[h], W64[h])) <= 1e-6
+    Og, idxc = wl.to_f64(L.O), L.idx.cpu().numpy()
+    for h in (3, 10):
+        st = orc.state_absorb(*orc.state_zero(w.head_dim), wl.to_f64(Ke[0, h]), wl.to_f64(Ve[0, h]))
+        ref, *_ = orc.hybrid_attention(wl.to_f64(Q[0, h]), wl.to_f64(K[0, h]), wl.to_f64(V[0, h]), st, w.block, w.block,
+                                       L.k, eps=cfg.eps, block_idx=idxc[0, h], W=W64[h])
+        assert rel_l2(Og[0, h], ref) <= BF16_REL_L2
+        assert max_abs(Og[0, h], ref) <= BF16_MAX_ABS
+
+
 def test_peaky_logits_at_full_size_sampled_heads():
     # queries scaled x8: the running max moves and the online-softmax rescale is exercised
     w = wl.get("step_832x480")

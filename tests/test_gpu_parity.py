@@ -207,6 +207,41 @@ def test_selection_with_reused_pooled_keys(name):
     assert np.array_equal(idx.cpu().numpy(), got_idx) and np.array_equal(scores.cpu().numpy(), got_sc)
 
 
+# ------------------------------------------------------------------------------- Linear of Eq. 3
+@pytest.mark.parametrize("name", ["small_bf16", "tiny_f32"])
+def test_linear_map_folded_into_the_state(name):
+    w = wl.get(name)
+    cfg = cfg_of(w)
+    d = w.head_dim
+    Ke, Ve = wl.make_evicted(w, 0)
+    st = new_state(cfg)
+    hf.hf_absorb_evicted(cfg, st, Ke.to(DEV), Ve.to(DEV))
+    W = wl.randn((w.heads, d, d), 91_000 + w.cfg, 1.0 / np.sqrt(d), torch.float32)
+    st2 = torch.full_like(st, float("nan"))
+    hf.hf_state_fold_linear(cfg, st, W.to(DEV), st2)
+    torch.cuda.synchronize()
+    Lg, zg = split_state(st, w.heads, d)
+    L2, z2 = split_state(st2, w.heads, d)
+    assert np.array_equal(z2, zg)                               # the normaliser is copied
+    W64 = W.double().numpy()
+    for h in range(w.heads):
+        ref = orc.state_fold_linear(Lg[0, h] if Lg.ndim == 4 else Lg[h], W64[h])
+        got = L2[0, h] if L2.ndim == 4 else L2[h]
+        assert rel_l2(got, ref) <= 1e-6                         # fp32 FMA over d terms
+    # the whole path on the folded state = oracle with the map applied to the history term
+    Q, K, V = wl.make_qkv(w)
+    idx, _, k = gpu_select(cfg, w, Q.to(DEV), K.to(DEV), want_scores=False)
+    O = run_hybrid(cfg, w, Q, K, V, idx, st2)
+    Og, idxc = wl.to_f64(O), idx.cpu().numpy()
+    states = oracle_state([Ke], [Ve], d)
+    bound_l2, bound_abs = out_bounds(w)
+    for h in range(w.heads):
+        ref, *_ = orc.hybrid_attention(wl.to_f64(Q[0, h]), wl.to_f64(K[0, h]), wl.to_f64(V[0, h]), states[h],
+                                       w.block, w.block, k, eps=cfg.eps, block_idx=idxc[0, h], W=W64[h])
+        assert rel_l2(Og[0, h], ref) <= bound_l2
+        assert max_abs(Og[0, h], ref) <= bound_abs
+
+
 # ------------------------------------------------------------------------------- attention (Eq. 5, 3, 6)
 def run_hybrid(cfg, w, Q, K, V, idx, st, tables=None):
     O = torch.full(Q.shape, float("nan"), dtype=Q.dtype, device=DEV)
