@@ -21,6 +21,8 @@
 // (ping-pong): while tile t is consumed, tile t+1 moves registers -> LDS and tiles t+2, t+3 are on
 // their way global -> registers (buffer loads, no branches); one workgroup barrier per tile.
 // The V^T fragments of a tile are requested before its softmax so that their LDS latency is hidden.
+#include <stdlib.h>
+
 #include "hf_common.h"
 
 namespace hf {
@@ -40,7 +42,8 @@ constexpr int KTILE = TK * KSTR;
 constexpr float kRescaleThreshold = 8.0f;  // log2 units: rescale only when a row max grew by more than 2^8
 
 // History branch fused into the epilogue (kFused): planes = the fp32 state split into two bf16
-// planes, transposed (Lt[plane][j][i], see hf_readout_mfma.hip), zvec = the state's normaliser.
+// planes (hi, lo), transposed (Lt[plane][j][i], see hf_readout_mfma.hip), of which the first
+// n_planes are used; zvec = the state's normaliser.
 // max without the NaN-quieting canonicalisation the compiler adds around fmaxf (scores are finite
 // or -inf here): one instruction per three inputs
 __device__ __forceinline__ float max3f(float a, float b, float c) {
@@ -58,6 +61,7 @@ struct HistArgs {
   const bf16_t* planes;  // [BH][2][d][d]
   const float* zvec;     // [BH][d]
   float eps, z_scale;
+  int n_planes;          // 2 = hi + lo, 1 = hi only
 };
 
 template <int NW, bool kFused>
@@ -324,8 +328,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
     constexpr int PCH = (D * D * 2 / 16) / NT;  // 16-byte chunks of one plane per thread
     static_assert(D * KSTR <= 2 * KTILE + D * VSTRD * 4, "a state plane must fit in the tiles' space");
     const u32x4* gp = reinterpret_cast<const u32x4*>(hist.planes + (size_t)bh * 2 * D * D);
-#pragma unroll
-    for (int plane = 0; plane < 2; ++plane) {  // each plane goes through LDS once per workgroup
+    for (int plane = 0; plane < hist.n_planes; ++plane) {  // each plane goes through LDS once per workgroup
       u32x4 preg[PCH];
 #pragma unroll
       for (int i = 0; i < PCH; ++i) preg[i] = gp[plane * (D * D * 2 / 16) + tid + NT * i];
@@ -396,7 +399,7 @@ static int launch_attn_mfma_impl(const hf_config& c, const void* Q, int n_q, con
   const bf16_t* kk = static_cast<const bf16_t*>(K);
   const bf16_t* v = static_cast<const bf16_t*>(V);
   bf16_t* o = static_cast<bf16_t*>(O);
-  const HistArgs h = hist ? *hist : HistArgs{nullptr, nullptr, 0.0f, 0.0f};
+  const HistArgs h = hist ? *hist : HistArgs{nullptr, nullptr, 0.0f, 0.0f, 0};
 #define HF_LAUNCH_ATTN(NWV, FUSED)                                                                              \
   hipLaunchKernelGGL((attn_mfma_kernel<NWV, FUSED>), grid, dim3(64 * NWV), 0, s, q, kk, v, idx, k, n_q, n_kv,   \
                      c.block_kv, t_m, t_n, per_xcd, (int)total, c_scale, h, o)
@@ -422,7 +425,11 @@ bool attn_mfma_fused_supported(const hf_config& c, bool has_rope) {
 int launch_attn_mfma_fused(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
                            const int32_t* idx, int k, const void* planes, const float* zvec, void* O,
                            hipStream_t s) {
-  const HistArgs h = {static_cast<const bf16_t*>(planes), zvec, c.eps, c.z_scale};
+  // One bf16 plane of L (2^-9 per element, errors of the d terms of a readout average out) costs the
+  // output nothing measurable next to the bf16 rounding of P and O; HF_FUSED_PLANES=2 in the
+  // environment adds the low plane (development switch).
+  const char* np = getenv("HF_FUSED_PLANES");
+  const HistArgs h = {static_cast<const bf16_t*>(planes), zvec, c.eps, c.z_scale, (np && np[0] == '2') ? 2 : 1};
   return launch_attn_mfma_impl(c, Q, n_q, K, V, n_kv, idx, k, &h, O, s);
 }
 
