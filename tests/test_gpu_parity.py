@@ -3,6 +3,8 @@ same seeded inputs.  Bounds: block indices exact as sets except boundary ties cl
 1e-6 in the oracle; outputs rel-L2 <= 1e-2 and max-abs <= 2e-2 for bf16, rel-L2 <= 1e-5 for
 fp32; fp32 state rel-L2 <= 1e-5 (bf16-exact products, fp32 accumulation) and <= 5e-3 when
 rotated keys are rounded to bf16 for the matrix cores."""
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -360,3 +362,38 @@ def test_out_of_range_block_index_is_ignored_not_read():
     a = run_hybrid(cfg, w, Q, K, V, idx, None)
     b = run_hybrid(cfg, w, Q, K, V, bad[..., : k + 1].contiguous() if k + 1 <= w.t_n else idx, None)
     assert torch.equal(a, b)
+
+
+# ------------------------------------------------------------------------------- batch > 1
+@pytest.mark.parametrize("name", ["small_bf16", "tiny_f32"])
+def test_batch_of_two_every_stage(name):
+    # (batch, head) pairs are independent: layouts [B, H, ...] with B = 2, the Linear weight shared by the batch
+    w = dataclasses.replace(wl.get(name), batch=2, heads=3)
+    cfg = cfg_of(w)
+    d, B, H = w.head_dim, w.batch, w.heads
+    Ke, Ve = wl.make_evicted(w, 1)
+    st = new_state(cfg)
+    hf.hf_absorb_evicted(cfg, st, Ke.to(DEV), Ve.to(DEV), workspace=absorb_ws(cfg, Ke.shape[2]))
+    torch.cuda.synchronize()
+    states = oracle_state([Ke], [Ve], d)                      # (b, h) order
+    L, z = split_state(st, B * H, d)
+    assert rel_l2(L, np.stack([s_[0] for s_ in states])) <= 1e-5
+    assert rel_l2(z, np.stack([s_[1] for s_ in states])) <= 1e-5
+    W = wl.randn((H, d, d), 92_000 + w.cfg, d ** -0.5, torch.float32)
+    st2 = torch.empty_like(st)
+    hf.hf_state_fold_linear(cfg, st, W.to(DEV), st2)
+    Q, K, V = wl.make_qkv(w)
+    idx, scores, k = gpu_select(cfg, w, Q.to(DEV), K.to(DEV))
+    O = run_hybrid(cfg, w, Q, K, V, idx, st2)
+    Og, idxc, sc = wl.to_f64(O), idx.cpu().numpy(), scores.cpu().numpy()
+    rl, ma = out_bounds(w)
+    W64 = W.double().numpy()
+    for n, (q, kk, v) in enumerate(zip(heads_of(Q), heads_of(K), heads_of(V))):
+        b, h = divmod(n, H)
+        A = orc.block_scores(q, kk, w.block, w.block)
+        assert np.abs(sc[b, h] - A).max() <= 1e-5 * max(1.0, np.abs(A).max())
+        check_block_idx(idxc[b, h], A, k)
+        ref, *_ = orc.hybrid_attention(q, kk, v, states[n], w.block, w.block, k, eps=cfg.eps,
+                                       block_idx=idxc[b, h], W=W64[h])
+        assert rel_l2(Og[b, h], ref) <= rl, (b, h)
+        assert max_abs(Og[b, h], ref) <= ma
