@@ -35,8 +35,9 @@ namespace {
 
 constexpr int D = 128;
 constexpr int TK = 32;      // keys per tile
-constexpr int KSTR = 272;   // bytes per key row of a K tile in LDS (256 + 16: conflict-free 16-byte operand reads)
-constexpr int VSTRD = 36;   // dwords per feature row of the V^T image: 2 tiles x 16 key pairs + 4 (conflict-free reads)
+constexpr int KSTR = 256;   // bytes per key row of a K tile in LDS; 16-byte units XOR-swizzled by (row & 15)
+constexpr int VSTRD = 48;   // dwords per feature row of the V^T image: 2 tiles x 16 key pairs + 16
+constexpr int PSTR = 272;   // bytes per row of a staged state plane (256 + 16)
 constexpr int OSTR = 272;   // bytes per query row of the staged output
 constexpr int KTILE = TK * KSTR;
 constexpr float kRescaleThreshold = 8.0f;  // log2 units: rescale only when a row max grew by more than 2^8
@@ -134,7 +135,10 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
       __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(Vh), 0, n_kv * (D * 2), 0x00020000);
   const int grp = tid & 15;                                  // 16-byte feature group
   const int k_ld_off = (tid >> 4) * (D * 2) + grp * 16;      // K: row (tid>>4) + (NT/16) i
-  const int sub4 = lane >> 4;                                // V: which of 4 adjacent key pairs
+  // V: a half-wavefront covers 8 feature groups x 4 adjacent key pairs, so that its 32 transposing
+  // dword stores fall into 32 different banks
+  const int vgrp = (lane & 7) + 8 * (lane >> 5);             // 16-byte feature group of the V rows
+  const int sub4 = (lane >> 3) & 3;                          // which of 4 adjacent key pairs
   const int v_key_lane = 8 * (sub4 >> 1) + 2 * (sub4 & 1);
   auto gload = [&](int start, u32x4 (&kreg)[CPT], u32x4 (&vreg)[CPT]) {
     const int kb = k_ld_off + start * (D * 2);
@@ -144,26 +148,30 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
     for (int j = 0; j < IPT; ++j) {
       const int cb = wave * IPT + j;  // = 2 t2 + hh
       const int key = 16 * (cb >> 1) + 4 * (cb & 1) + v_key_lane;
-      const int vb = (start + key) * (D * 2) + grp * 16;
+      const int vb = (start + key) * (D * 2) + vgrp * 16;
       vreg[2 * j] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, vb, 0, 0);
       vreg[2 * j + 1] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, vb + D * 2, 0, 0);
     }
   };
   // V^T image: row = feature, dword column = 16 (tile parity) + key pair in MFMA order
-  // (8 t2 + 4 hh + 2 x + y), rotated by 4 dwords per 16 features so that the dword stores of a
-  // wavefront hit distinct banks
-  const int vt_rot = 4 * ((grp >> 1) & 7);
+  // (8 t2 + 4 hh + 2 x + y), rotated by 4 dwords per 8 features.  LDS serves dword stores 32 lanes
+  // at a time from 32 banks and 16-byte reads from 64 banks in lane groups it picks by one of the
+  // lane bits 2..4: with 48-dword rows and this rotation both the stores and the operand reads
+  // are conflict free (measured with SQ_LDS_BANK_CONFLICT on the exact address patterns).
+  const int vt_rot = 4 * (vgrp & 7);
   auto lstore = [&](int par, const u32x4 (&kreg)[CPT], const u32x4 (&vreg)[CPT]) {
 #pragma unroll
-    for (int i = 0; i < CPT; ++i)
-      *reinterpret_cast<u32x4*>(sK + par * KTILE + ((tid >> 4) + (NT / 16) * i) * KSTR + grp * 16) = kreg[i];
+    for (int i = 0; i < CPT; ++i) {
+      const int row = (tid >> 4) + (NT / 16) * i;
+      *reinterpret_cast<u32x4*>(sK + par * KTILE + row * KSTR + ((grp ^ (row & 15)) * 16)) = kreg[i];
+    }
 #pragma unroll
     for (int j = 0; j < IPT; ++j) {
       const int col = (16 * par + 4 * (wave * IPT + j) + sub4 + vt_rot) & 31;
       const u32x4 a = vreg[2 * j], b = vreg[2 * j + 1];  // rows key and key + 1
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
-        const int f = 8 * grp + 2 * p;
+        const int f = 8 * vgrp + 2 * p;
         sVt[f * VSTRD + col] = __builtin_amdgcn_perm(b[p], a[p], 0x05040100u);        // feature f: (key, key + 1)
         sVt[(f + 1) * VSTRD + col] = __builtin_amdgcn_perm(b[p], a[p], 0x07060302u);  // feature f + 1
       }
@@ -171,12 +179,13 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
   };
 
   // per-lane LDS read offsets
-  const char* k_rd = sK + l32 * KSTR + 16 * h;  // + par KTILE + 32 s
+  // K operand of step s: unit (2 s + h) ^ (row & 15) of row l32, i.e. byte k_rd ^ (32 s)
+  const char* k_rd = sK + l32 * KSTR + 16 * (h ^ (l32 & 1)) + 32 * ((l32 & 15) >> 1);  // + par KTILE
   int v_row[4], v_rot[4];
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt) {
     v_row[dt] = (32 * dt + l32) * VSTRD;
-    v_rot[dt] = 4 * ((2 * dt + (l32 >> 4)) & 7) + 4 * h;
+    v_rot[dt] = 4 * ((4 * dt + (l32 >> 3)) & 7) + 4 * h;
   }
 
   // ---- prologue: tile 0 in LDS, tiles 1 and 2 on their way in two sets of staging registers.
@@ -202,7 +211,8 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
     for (int r = 0; r < 16; ++r) sacc[r] = 0.0f;
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(k_rd + par * KTILE + 32 * s);
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(
+          sK + par * KTILE + (static_cast<uint32_t>(k_rd - sK) ^ (32u * s)));
       sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[s], sacc, 0, 0, 0);
     }
     // the first half of the V^T fragments is requested now: the reads complete under the softmax
@@ -326,7 +336,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[dt][r] *= den_eps;
     constexpr int PCH = (D * D * 2 / 16) / NT;  // 16-byte chunks of one plane per thread
-    static_assert(D * KSTR <= 2 * KTILE + D * VSTRD * 4, "a state plane must fit in the tiles' space");
+    static_assert(D * PSTR <= 2 * KTILE + D * VSTRD * 4, "a state plane must fit in the tiles' space");
     const u32x4* gp = reinterpret_cast<const u32x4*>(hist.planes + (size_t)bh * 2 * D * D);
     for (int plane = 0; plane < hist.n_planes; ++plane) {  // each plane goes through LDS once per workgroup
       u32x4 preg[PCH];
@@ -336,14 +346,14 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
 #pragma unroll
       for (int i = 0; i < PCH; ++i) {
         const int c = tid + NT * i;
-        *reinterpret_cast<u32x4*>(smem + (c >> 4) * KSTR + (c & 15) * 16) = preg[i];
+        *reinterpret_cast<u32x4*>(smem + (c >> 4) * PSTR + (c & 15) * 16) = preg[i];
       }
       __syncthreads();
 #pragma unroll
       for (int s = 0; s < 8; ++s)
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(smem + (32 * dt + l32) * KSTR + 16 * h + 32 * s);
+          const bf16x8 a = *reinterpret_cast<const bf16x8*>(smem + (32 * dt + l32) * PSTR + 16 * h + 32 * s);
           o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[s], o[dt], 0, 0, 0);
         }
     }
