@@ -29,7 +29,7 @@ namespace {
 constexpr int D = 128;
 constexpr int CH = 64;              // tokens per chunk (one LDS image)
 constexpr int NP = CH / 2;          // token pairs per chunk
-constexpr int SP = NP + 4;          // LDS row stride in dwords: keeps 16-byte operand reads conflict free
+constexpr int SP = NP + 16;         // LDS row stride in dwords (see pair_col)
 constexpr int RUN_CHUNKS = 5;       // chunks requested up front
 constexpr int RUN = RUN_CHUNKS * CH;
 constexpr int PART = D * D + D;     // floats of one partial: L then z
@@ -37,11 +37,13 @@ constexpr int NT = 512;             // threads per workgroup: 8 wavefronts, two 
 constexpr int ITEMS = 16 * NP / NT; // (token pair, feature group) items per thread and chunk
 constexpr int TPI = NT / 16;        // token pairs between two items of a thread
 
-// column of token pair `tp` in the row of `feature`: rows are rotated by one 16-byte group per
-// 16 features, which spreads the transposing dword stores of a wave (16 feature groups x 4
-// token pairs) over all 64 banks and keeps the 4-pair groups of an operand read intact
+// column of token pair `tp` in the row of `feature`: rows are rotated by one 16-byte group per 8
+// features.  LDS serves dword stores 32 lanes at a time from 32 banks: a half-wavefront holds 8
+// feature groups x 4 adjacent token pairs, which the rotation spreads over all 32; with 48-dword
+// rows the 16-byte operand reads are conflict free as well (both measured on the exact patterns
+// with SQ_LDS_BANK_CONFLICT), and the 4-pair groups of an operand read stay intact.
 __device__ __forceinline__ int pair_col(int feature, int tp) {
-  return (tp + (((feature >> 4) & 7) << 2)) & (NP - 1);
+  return (tp + (((feature >> 3) & 7) << 2)) & (NP - 1);
 }
 
 struct Regs {
@@ -87,8 +89,8 @@ __global__ __launch_bounds__(NT, 1) void absorb_mfma_kernel(float* __restrict__ 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const bf16_t* Kh = K + (size_t)bh * n * D;
   const bf16_t* Vh = V + (size_t)bh * n * D;
-  const int g = tid & 15;   // feature group: features 8g .. 8g+7
-  const int tp0 = tid >> 4; // token pair of item 0; further items are TPI pairs apart
+  const int g = (lane & 7) + 8 * (lane >> 5);      // feature group: features 8g .. 8g+7
+  const int tp0 = 4 * wave + ((lane >> 3) & 3);    // token pair of item 0; further items are TPI pairs apart
 
   if (tid < D) zs[tid] = 0.0f;
 
@@ -223,13 +225,13 @@ __global__ __launch_bounds__(NT, 1) void absorb_mfma_kernel(float* __restrict__ 
     L = state + (size_t)bh * D * D;
     z = state + (size_t)BH * D * D + (size_t)bh * D;
   }
-  // lanes l, l + 16, l + 32, l + 48 of a wavefront hold the same feature group: sum them first
+  // lanes l, l + 8, l + 16, l + 24 of a half-wavefront hold the same feature group: sum them first
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
+    zacc[e] += __shfl_xor(zacc[e], 8, kWave);
     zacc[e] += __shfl_xor(zacc[e], 16, kWave);
-    zacc[e] += __shfl_xor(zacc[e], 32, kWave);
   }
-  if (lane < 16) {
+  if ((lane & 24) == 0) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) atomicAdd(&zs[8 * g + e], zacc[e]);
   }
