@@ -16,8 +16,8 @@
 //
 // What bounds this kernel at block_q 64: the matrix work and the vector work of the softmax do not
 // overlap on a SIMD of this chip (together about two thirds of the run time), and every query
-// block stages its own 8 KB of K and 8 KB of V per 32 keys through the CU's LDS store port
-// (64 B/clk), whose queue delays the other wavefronts' operand reads.  LDS holds two tiles
+// block stages its own 8 KB of K and 8 KB of V per 32 keys through the CU's vector-memory path
+// (64 B/clk) and LDS (128 B per cycle for stores), whose queues delay the operand reads.  LDS holds two tiles
 // (ping-pong): while tile t is consumed, tile t+1 moves registers -> LDS and tiles t+2, t+3 are on
 // their way global -> registers (buffer loads, no branches); one workgroup barrier per tile.
 // The V^T fragments of a tile are requested before its softmax so that their LDS latency is hidden.

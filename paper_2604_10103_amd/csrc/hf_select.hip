@@ -190,6 +190,134 @@ __global__ __launch_bounds__(256) void score_select_kernel(const float* __restri
   }
 }
 
+// Three query-block rows per workgroup of eight wavefronts: every row of a head reads that head's
+// pooled keys from L2 (the launch is bound by that traffic: T_m x 75 KB per head at the 832x480
+// shape), so sharing one read between three rows cuts it threefold.
+// Scoring: wavefront w takes an eighth of the head dimension, lane l the KV blocks l, l + 64, ...,
+// each loaded pooled key meets the three pooled queries (held in registers); the eight partial dot
+// products of a (row, block) meet in LDS and are added in a fixed order.
+// Selection: the 3 x T_n (row, block) pairs are ranked one per thread (441 or 507 of the 512
+// threads at the two workloads' shapes) by strict comparison; wavefront r then turns row r's keep
+// flags into the ascending list with a ballot prefix sum and, if a tie straddles the k-th place
+// (more than k kept), redoes that row with the tie rule.
+constexpr int kRows = 3;
+
+template <int D>
+__global__ __launch_bounds__(512) void score_select3_kernel(const float* __restrict__ qbar,
+                                                            const float* __restrict__ kbar_t, int t_m, int t_n,
+                                                            int k, int32_t* __restrict__ idx,
+                                                            float* __restrict__ scores) {
+  // LDS: [kRows][D] queries | [8][kRows][t_pad] partials (later: keep flags) | [kRows][t_pad] scores
+  extern __shared__ __attribute__((aligned(16))) float smem[];
+  constexpr int CW = D / 32;  // 16-byte feature groups per wavefront
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int row0 = blockIdx.x * kRows, bh = blockIdx.y;
+  const int t_pad = (t_n + 3) & ~3;
+  float* sq = smem;
+  float* part = smem + kRows * D;
+  float* sc = part + 8 * kRows * t_pad;
+  if (tid < kRows * D) {
+    const int r = min(row0 + tid / D, t_m - 1);  // rows past the end repeat the last one; never written
+    sq[tid] = qbar[((size_t)bh * t_m + r) * D + (tid % D)];
+  }
+  const int pad = t_pad - t_n;  // at most 3
+  if (pad > 0 && tid < kRows * pad) sc[(tid / pad) * t_pad + t_n + tid % pad] = -INFINITY;  // never outranks a block
+  __syncthreads();
+
+  const float4* kt = reinterpret_cast<const float4*>(kbar_t) + ((size_t)bh * (D / 4) + wave * CW) * t_n;
+  float4 q[kRows][CW];
+#pragma unroll
+  for (int r = 0; r < kRows; ++r)
+#pragma unroll
+    for (int c = 0; c < CW; ++c) q[r][c] = *reinterpret_cast<const float4*>(sq + r * D + 4 * (wave * CW + c));
+  for (int j0 = lane; j0 < t_n; j0 += 256) {
+    float4 kv[4][CW];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = min(j0 + 64 * u, t_n - 1);  // clamped: a valid address, the result is dropped
+#pragma unroll
+      for (int c = 0; c < CW; ++c) kv[u][c] = kt[(size_t)c * t_n + j];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int r = 0; r < kRows; ++r) {
+        float a = 0.0f;
+#pragma unroll
+        for (int c = 0; c < CW; ++c) {
+          a = fmaf(q[r][c].x, kv[u][c].x, a); a = fmaf(q[r][c].y, kv[u][c].y, a);
+          a = fmaf(q[r][c].z, kv[u][c].z, a); a = fmaf(q[r][c].w, kv[u][c].w, a);
+        }
+        if (j0 + 64 * u < t_n) part[(wave * kRows + r) * t_pad + j0 + 64 * u] = a;
+      }
+  }
+  __syncthreads();
+  for (int it = tid; it < kRows * t_n; it += 512) {
+    const int r = it / t_n, j = it - r * t_n;
+    const float* p = part + r * t_pad + j;
+    const int ws = kRows * t_pad;  // stride between wavefronts' partials
+    const float a = ((p[0] + p[ws]) + (p[2 * ws] + p[3 * ws])) + ((p[4 * ws] + p[5 * ws]) + (p[6 * ws] + p[7 * ws]));
+    sc[r * t_pad + j] = a;
+    if (scores && row0 + r < t_m) scores[((size_t)bh * t_m + row0 + r) * t_n + j] = a;
+  }
+  __syncthreads();
+
+  // rank every (row, block) pair by strict comparison: blocks with equal scores share a rank
+  int* flags = reinterpret_cast<int*>(part);  // the partials are dead
+  for (int it = tid; it < kRows * t_n; it += 512) {
+    const int r = it / t_n, j = it - r * t_n;
+    const float* my = sc + r * t_pad;
+    const float mine = my[j];
+    int rank = 0;
+    for (int o = 0; o < t_pad; o += 4) {
+      const float4 v = *reinterpret_cast<const float4*>(my + o);
+      rank += (v.x > mine) ? 1 : 0;
+      rank += (v.y > mine) ? 1 : 0;
+      rank += (v.z > mine) ? 1 : 0;
+      rank += (v.w > mine) ? 1 : 0;
+    }
+    flags[r * t_pad + j] = rank < k ? 1 : 0;
+  }
+  __syncthreads();
+
+  if (wave >= kRows || row0 + wave >= t_m) return;
+  const float* my = sc + wave * t_pad;
+  const int* fl = flags + wave * t_pad;
+  int32_t* out = idx + ((size_t)bh * t_m + row0 + wave) * k;
+  int base = 0;
+  for (int j0 = 0; j0 < t_n; j0 += 64) {  // wave-uniform
+    const int j = j0 + lane;
+    const bool keep = j < t_n && fl[j] != 0;
+    const unsigned long long m = __ballot(keep);
+    const int pos = base + __popcll(m & ((1ull << lane) - 1ull));
+    if (keep && pos < k) out[pos] = j;
+    base += __popcll(m);
+  }
+  if (base == k) return;
+  // a tie straddles the k-th place: exact ranks with the tie rule (lower index wins), this row only
+  base = 0;
+  for (int j0 = 0; j0 < t_n && base < k; j0 += 64) {
+    const int j = j0 + lane;
+    bool keep = false;
+    if (j < t_n) {
+      const float mine = my[j];
+      int rank = 0;
+      for (int o = 0; o < t_pad; o += 4) {
+        const float4 v = *reinterpret_cast<const float4*>(my + o);
+        rank += (v.x > mine || (v.x == mine && o < j)) ? 1 : 0;
+        rank += (v.y > mine || (v.y == mine && o + 1 < j)) ? 1 : 0;
+        rank += (v.z > mine || (v.z == mine && o + 2 < j)) ? 1 : 0;
+        rank += (v.w > mine || (v.w == mine && o + 3 < j)) ? 1 : 0;
+      }
+      keep = rank < k;
+    }
+    const unsigned long long m = __ballot(keep);
+    const int pos = base + __popcll(m & ((1ull << lane) - 1ull));
+    if (keep && pos < k) out[pos] = j;
+    base += __popcll(m);
+  }
+}
+
 }  // namespace
 
 int launch_pool_both(const hf_config& c, const void* Q, int n_q, int t_m, const void* K, int n_kv, int t_n,
@@ -211,8 +339,19 @@ int launch_pool_both(const hf_config& c, const void* Q, int n_q, int t_m, const 
 int launch_score_select(const hf_config& c, const float* qbar, const float* kbar_t, int t_m, int t_n, int k,
                         int32_t* idx, float* scores, hipStream_t s) {
   const int BH = c.batch * c.heads;
+  const int t_pad = (t_n + 3) & ~3;
+  // three rows per workgroup while its LDS need stays within the default 64 KB
+  const size_t smem3 = (size_t)(kRows * c.head_dim + 9 * kRows * t_pad) * sizeof(float);
+  if (smem3 <= 64 * 1024) {
+    const dim3 grid((t_m + kRows - 1) / kRows, BH), block(512);
+    if (c.head_dim == 128)
+      hipLaunchKernelGGL((score_select3_kernel<128>), grid, block, smem3, s, qbar, kbar_t, t_m, t_n, k, idx, scores);
+    else
+      hipLaunchKernelGGL((score_select3_kernel<64>), grid, block, smem3, s, qbar, kbar_t, t_m, t_n, k, idx, scores);
+    return check_launch("hf_block_select(select)");
+  }
   const dim3 grid(t_m, BH), block(256);
-  const size_t smem = (size_t)(c.head_dim + 5 * ((t_n + 3) & ~3)) * sizeof(float);
+  const size_t smem = (size_t)(c.head_dim + 5 * t_pad) * sizeof(float);
   if (c.head_dim == 128)
     hipLaunchKernelGGL((score_select_kernel<128>), grid, block, smem, s, qbar, kbar_t, t_m, t_n, k, idx, scores);
   else

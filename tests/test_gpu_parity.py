@@ -154,6 +154,19 @@ def test_block_scores_and_indices(name):
         check_block_idx(idx[0, h], A, k)
 
 
+def test_selection_over_many_blocks_takes_the_one_row_kernel():
+    # 640 KV blocks: the three-rows-per-workgroup kernel's LDS need exceeds 64 KB, the one-row kernel serves
+    w = dataclasses.replace(wl.get("tiny_f32"), heads=1, tokens_per_frame=16 * 64, chunk_frames=1, window_frames=10)
+    assert w.t_n == 640 and w.t_m == 64
+    cfg = cfg_of(w, keep_k=64)
+    Q, K, _ = wl.make_qkv(w)
+    idx, scores, k = gpu_select(cfg, w, Q.to(DEV), K.to(DEV))
+    assert k == 64
+    A = orc.block_scores(wl.to_f64(Q[0, 0]), wl.to_f64(K[0, 0]), w.block, w.block)
+    assert np.abs(scores.cpu().numpy()[0, 0] - A).max() <= 1e-5 * max(1.0, np.abs(A).max())
+    check_block_idx(idx.cpu().numpy()[0, 0], A, k)
+
+
 def test_selection_ties_and_keep_all():
     # identical key blocks give exactly tied scores: the lower index must win
     w = wl.get("small_bf16")
