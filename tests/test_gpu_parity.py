@@ -410,3 +410,59 @@ def test_batch_of_two_every_stage(name):
                                        block_idx=idxc[b, h], W=W64[h])
         assert rel_l2(Og[b, h], ref) <= rl, (b, h)
         assert max_abs(Og[b, h], ref) <= ma
+
+
+# ------------------------------------------------------------------------------- seeded random shapes
+@pytest.mark.parametrize("seed", range(16))
+def test_seeded_random_shapes_whole_path(seed):
+    # every dispatch path (MFMA / generic attention, fused / stand-alone readout, MFMA / FMA absorb with and
+    # without workspace, both selection kernels) on shapes drawn from a seeded generator
+    r = np.random.default_rng(7_000 + seed)
+    dtype = ["bf16", "f32"][int(r.integers(0, 2))]
+    d = [64, 128][int(r.integers(0, 2))]
+    b = [16, 32, 64, 128][int(r.integers(0, 4))]
+    B, H = int(r.integers(1, 3)), int(r.integers(1, 4))
+    n_q, n_kv, n_ev = int(r.integers(1, 300)), int(r.integers(1, 700)), int(r.integers(1, 200))
+    phi = [hf.HF_PHI_RELU, hf.HF_PHI_ELU1][int(r.integers(0, 2))]
+    rope = bool(r.integers(0, 2))
+    keep = float(r.uniform(0.1, 1.0))
+    use_ws = bool(r.integers(0, 2))
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    cfg = hf.make_config(B, H, d, dtype, b, b, keep, phi=phi)
+    mk = lambda n, s_: wl.randn((B, H, n, d), 8_000 + 10 * seed + s_, 0.6, tdt)
+    Q, K, V, Ke, Ve = mk(n_q, 0), mk(n_kv, 1), mk(n_kv, 2), mk(n_ev, 3), mk(n_ev, 4)
+    etab = wl.rope_tables(n_ev, d, first_position=3.0, tokens_per_position=7) if rope else (None, None)
+    qtab = wl.rope_tables(n_q, d, first_position=40.0, tokens_per_position=5) if rope else None
+    st = new_state(cfg)
+    hf.hf_absorb_evicted(cfg, st, Ke.to(DEV), Ve.to(DEV), *(t.to(DEV) if t is not None else None for t in etab),
+                         workspace=absorb_ws(cfg, n_ev) if use_ws else None)
+    k = hf.hf_select_k(cfg, n_kv)
+    t_m, t_n = -(-n_q // b), -(-n_kv // b)
+    idx = torch.full((B, H, t_m, k), -1, dtype=torch.int32, device=DEV)
+    scores = torch.empty((B, H, t_m, t_n), dtype=torch.float32, device=DEV)
+    ws = new_workspace(cfg, n_q, n_kv)
+    hf.hf_block_select(cfg, Q.to(DEV), K.to(DEV), idx, scores, ws)
+    O = torch.full(Q.shape, float("nan"), dtype=tdt, device=DEV)
+    hf.hf_hybrid_attn_fwd(cfg, Q.to(DEV), K.to(DEV), V.to(DEV), idx, st, O, ws,
+                          *(() if qtab is None else (qtab[0].to(DEV), qtab[1].to(DEV))))
+    torch.cuda.synchronize()
+    assert not O.isnan().any()
+    states = oracle_state([Ke], [Ve], d, phi, [etab] if rope else None)
+    L, z = split_state(st, B * H, d)
+    # rotated / ELU keys are rounded to bf16 before the matrix cores on the bf16 d = 128 path
+    sb = 5e-3 if (dtype == "bf16" and d == 128 and (rope or phi != hf.HF_PHI_RELU)) else 1e-5
+    assert rel_l2(L, np.stack([s_[0] for s_ in states])) <= sb
+    assert rel_l2(z, np.stack([s_[1] for s_ in states])) <= 1e-5
+    Og, idxc, sc = wl.to_f64(O), idx.cpu().numpy(), scores.cpu().numpy()
+    rl, ma = (BF16_REL_L2, BF16_MAX_ABS) if dtype == "bf16" else (F32_REL_L2, 1e-4)
+    cq = None if qtab is None else wl.to_f64(qtab[0])
+    sq = None if qtab is None else wl.to_f64(qtab[1])
+    for n, (q, kk, v) in enumerate(zip(heads_of(Q), heads_of(K), heads_of(V))):
+        bi, h = divmod(n, H)
+        A = orc.block_scores(q, kk, b, b)
+        assert np.abs(sc[bi, h] - A).max() <= 1e-5 * max(1.0, np.abs(A).max())
+        check_block_idx(idxc[bi, h], A, k)
+        ref, *_ = orc.hybrid_attention(q, kk, v, states[n], b, b, k, phi, cq, sq, cfg.eps, cfg.z_scale,
+                                       block_idx=idxc[bi, h])
+        assert rel_l2(Og[bi, h], ref) <= rl, (seed, bi, h, rel_l2(Og[bi, h], ref))
+        assert max_abs(Og[bi, h], ref) <= ma
