@@ -268,7 +268,8 @@ def run_hybrid(cfg, w, Q, K, V, idx, st, tables=None):
 
 
 @pytest.mark.parametrize("name,q_gain", [("tiny_f32", 1.0), ("tiny_f32", 6.0), ("small_bf16", 1.0),
-                                         ("small_bf16", 8.0), ("small_b128", 1.0), ("small_f32_d128", 3.0)])
+                                         ("small_bf16", 8.0), ("small_bf16", 64.0), ("small_b128", 1.0),
+                                         ("small_b128", 48.0), ("small_f32_d128", 3.0)])
 def test_sparse_attention_alone_matches_oracle(name, q_gain):
     w = wl.get(name)
     cfg = cfg_of(w)
