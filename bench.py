@@ -39,6 +39,8 @@ def parse():
     p.add_argument("--layers", type=int, default=6, help="distinct layer tensor sets rotated through")
     p.add_argument("--keep-ratio", type=float, default=None)
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--rope", action="store_true",
+                   help="rotate phi(k) / phi(q) of the history branch with synthetic per-token tables (default: none)")
     p.add_argument("--no-dense", action="store_true",
                    help="skip the dense comparator launches (they share the sparse kernel's name in a profile)")
     p.add_argument("--eager", action="store_true",
@@ -109,16 +111,23 @@ def main():
     del prefill
     torch.cuda.synchronize()
 
+    rq = re_ = (None, None)
+    if a.rope:   # caller-side tables (positions in frames); shared by heads and layer sets
+        rq = tuple(t.to(dev) for t in wl.rope_tables(w.n_q, w.head_dim, first_position=21.0,
+                                                     tokens_per_position=w.tokens_per_frame))
+        re_ = tuple(t.to(dev) for t in wl.rope_tables(w.n_q, w.head_dim, first_position=3.0,
+                                                      tokens_per_position=w.tokens_per_frame))
+
     def step(s, events=None):
         if events is not None:
             events[0].record()
         hf.hf_block_select(cfg, s["Q"], s["K"], s["idx"], None, s["ws"])
         if events is not None:
             events[1].record()
-        hf.hf_hybrid_attn_fwd(cfg, s["Q"], s["K"], s["V"], s["idx"], s["st"], s["O"], s["ws"])
+        hf.hf_hybrid_attn_fwd(cfg, s["Q"], s["K"], s["V"], s["idx"], s["st"], s["O"], s["ws"], rq[0], rq[1])
         if events is not None:
             events[2].record()
-        hf.hf_absorb_evicted(cfg, s["st"], s["Ke"], s["Ve"], workspace=aws)
+        hf.hf_absorb_evicted(cfg, s["st"], s["Ke"], s["Ve"], re_[0], re_[1], workspace=aws)
         if events is not None:
             events[3].record()
 
@@ -208,7 +217,8 @@ def main():
     # the default path adds the history term in the attention epilogue
     os.environ["HF_FUSED_EPILOGUE"] = "0"
     fwd2_ms, _ = time_calls(
-        lambda s: hf.hf_hybrid_attn_fwd(cfg, s["Q"], s["K"], s["V"], s["idx"], s["st"], s["O"], s["ws"]), a.steps)
+        lambda s: hf.hf_hybrid_attn_fwd(cfg, s["Q"], s["K"], s["V"], s["idx"], s["st"], s["O"], s["ws"], rq[0], rq[1]),
+        a.steps)
     del os.environ["HF_FUSED_EPILOGUE"]
     a5_ms = max(fwd2_ms - a4_ms, 0.0)
 
@@ -246,7 +256,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "heads": w.heads, "head_dim": w.head_dim,
                    "n_q": w.n_q, "n_kv": w.n_kv, "block": w.block, "keep_ratio": keep, "k": k,
-                   "t_n": w.t_n, "evicted_tokens_in_state": w.n_evicted, "rotated_layer_sets": nl},
+                   "t_n": w.t_n, "evicted_tokens_in_state": w.n_evicted, "rotated_layer_sets": nl,
+                   "history_rope": bool(a.rope)},
         "roofline": {"kernel": "sparse flash forward (Eq. 5)", "bound": "mfma", "achieved": a4_tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": a4_tflops / PEAK_BF16_TFLOPS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if a.keep_ratio is None else None,

@@ -264,14 +264,14 @@ int hf_hybrid_attn_fwd(const hf_config* cfg, const void* Q, int32_t n_q, const v
   }
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) { set_error("workspace is not 256-byte aligned"); return HF_ERR_ALIGN; }
   const char* fuse_env = getenv("HF_FUSED_EPILOGUE");  // "0" keeps the two-kernel path (to time the readout alone)
-  if (attn_mfma_fused_supported(*cfg, rope_cos_q != nullptr) && !(fuse_env && fuse_env[0] == '0')) {
-    // ReLU, no rotation, MFMA shapes: the history term is added in the attention kernel's epilogue
+  if (attn_mfma_fused_supported(*cfg) && !(fuse_env && fuse_env[0] == '0')) {
+    // MFMA shapes: the history term is added in the attention kernel's epilogue
     char* planes = static_cast<char*>(workspace) + w.planes;
     const float* st = static_cast<const float*>(state_or_null);
     const size_t d = cfg->head_dim;
     HF_TRY(launch_state_planes(*cfg, st, planes, s));
     return launch_attn_mfma_fused(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, planes,
-                                  st + (size_t)cfg->batch * cfg->heads * d * d, O, s);
+                                  st + (size_t)cfg->batch * cfg->heads * d * d, rope_cos_q, rope_sin_q, O, s);
   }
   void* o_local = static_cast<char*>(workspace) + w.olocal;
   HF_TRY(launch_attn(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, o_local, s));

@@ -63,9 +63,13 @@ struct HistArgs {
   const float* zvec;     // [BH][d]
   float eps, z_scale;
   int n_planes;          // 2 = hi + lo, 1 = hi only
+  int phi_kind;          // feature map of the history branch
+  const float* cosq;     // [n_q][d/2] rotation of phi(q) in the numerator, or NULL
+  const float* sinq;
 };
 
-template <int NW, bool kFused>
+// kFused: 0 = attention only, 1 = + history term for ReLU without rotation, 2 = + history term, general
+template <int NW, int kFused>
 __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const int32_t* __restrict__ idx, int k, int n_q, int n_kv, int bkv, int t_m, int t_n, int items_per_xcd,
@@ -307,22 +311,52 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
     for (int r = 0; r < 16; ++r) o[dt][r] *= inv;
 
   if (kFused) {
-    // ---- O += R(phi(q)) L / (z_scale phi(q).z + eps) for phi = ReLU without rotation (Eq. 3, 6):
-    // the query fragments already in registers are, after a packed ReLU, the B operand of
-    // O_hist^T = Lt x phi(Q)^T; the A operand streams from the L2-resident planes.
+    // ---- O += R(phi(q)) L / (z_scale phi(q).z + eps) (Eq. 3, 6): the query fragments already in
+    // registers become the B operand of O_hist^T = Lt x R(phi(Q))^T; the A operand comes from the
+    // L2-resident plane(s) through LDS.
     const float* zv = hist.zvec + (size_t)bh * D + 8 * h;
-    typedef short s16x8 __attribute__((ext_vector_type(8)));
-    const s16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
     float den = 0.0f;
+    if (kFused == 1) {
+      // ReLU of a bf16 value as a packed integer max: the fragments stay exact
+      typedef short s16x8 __attribute__((ext_vector_type(8)));
+      const s16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      qf[s] = __builtin_bit_cast(bf16x8, __builtin_elementwise_max(__builtin_bit_cast(s16x8, qf[s]), zero8));  // ReLU
-      const float4 z0 = *reinterpret_cast<const float4*>(zv + 16 * s);
-      const float4 z1 = *reinterpret_cast<const float4*>(zv + 16 * s + 4);
-      den += static_cast<float>(qf[s][0]) * z0.x + static_cast<float>(qf[s][1]) * z0.y +
-             static_cast<float>(qf[s][2]) * z0.z + static_cast<float>(qf[s][3]) * z0.w +
-             static_cast<float>(qf[s][4]) * z1.x + static_cast<float>(qf[s][5]) * z1.y +
-             static_cast<float>(qf[s][6]) * z1.z + static_cast<float>(qf[s][7]) * z1.w;
+      for (int s = 0; s < 8; ++s) {
+        qf[s] = __builtin_bit_cast(bf16x8, __builtin_elementwise_max(__builtin_bit_cast(s16x8, qf[s]), zero8));
+        const float4 z0 = *reinterpret_cast<const float4*>(zv + 16 * s);
+        const float4 z1 = *reinterpret_cast<const float4*>(zv + 16 * s + 4);
+        den += static_cast<float>(qf[s][0]) * z0.x + static_cast<float>(qf[s][1]) * z0.y +
+               static_cast<float>(qf[s][2]) * z0.z + static_cast<float>(qf[s][3]) * z0.w +
+               static_cast<float>(qf[s][4]) * z1.x + static_cast<float>(qf[s][5]) * z1.y +
+               static_cast<float>(qf[s][6]) * z1.z + static_cast<float>(qf[s][7]) * z1.w;
+      }
+    } else {
+      // any feature map, optional rotation of adjacent feature pairs: phi in fp32, the denominator from
+      // the unrotated phi(q), the rotated numerator operand rounded to bf16 (2^-9, like P)
+      const size_t trow = (size_t)min(q_row, n_q - 1) * (D / 2) + 4 * h;
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        float f[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] = phi_apply(static_cast<float>(qf[s][e]), hist.phi_kind);
+        const float4 z0 = *reinterpret_cast<const float4*>(zv + 16 * s);
+        const float4 z1 = *reinterpret_cast<const float4*>(zv + 16 * s + 4);
+        den += f[0] * z0.x + f[1] * z0.y + f[2] * z0.z + f[3] * z0.w + f[4] * z1.x + f[5] * z1.y + f[6] * z1.z +
+               f[7] * z1.w;
+        if (hist.cosq) {
+          const float4 c4 = *reinterpret_cast<const float4*>(hist.cosq + trow + 8 * s);
+          const float4 s4 = *reinterpret_cast<const float4*>(hist.sinq + trow + 8 * s);
+          const float cc[4] = {c4.x, c4.y, c4.z, c4.w}, ss[4] = {s4.x, s4.y, s4.z, s4.w};
+#pragma unroll
+          for (int p2 = 0; p2 < 4; ++p2) {
+            const float a = f[2 * p2], b = f[2 * p2 + 1];
+            f[2 * p2] = a * cc[p2] - b * ss[p2];
+            f[2 * p2 + 1] = a * ss[p2] + b * cc[p2];
+          }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[s][e] = static_cast<__bf16>(f[e]);
+      }
     }
     {
       const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(den), __float_as_uint(den), false, false);
@@ -409,14 +443,15 @@ static int launch_attn_mfma_impl(const hf_config& c, const void* Q, int n_q, con
   const bf16_t* kk = static_cast<const bf16_t*>(K);
   const bf16_t* v = static_cast<const bf16_t*>(V);
   bf16_t* o = static_cast<bf16_t*>(O);
-  const HistArgs h = hist ? *hist : HistArgs{nullptr, nullptr, 0.0f, 0.0f, 0};
+  const HistArgs h = hist ? *hist : HistArgs{nullptr, nullptr, 0.0f, 0.0f, 0, 0, nullptr, nullptr};
 #define HF_LAUNCH_ATTN(NWV, FUSED)                                                                              \
   hipLaunchKernelGGL((attn_mfma_kernel<NWV, FUSED>), grid, dim3(64 * NWV), 0, s, q, kk, v, idx, k, n_q, n_kv,   \
                      c.block_kv, t_m, t_n, per_xcd, (int)total, c_scale, h, o)
+  const int fused = !hist ? 0 : ((h.phi_kind == HF_PHI_RELU && h.cosq == nullptr) ? 1 : 2);
   if (c.block_q == 64) {
-    if (hist) HF_LAUNCH_ATTN(2, true); else HF_LAUNCH_ATTN(2, false);
+    if (fused == 0) HF_LAUNCH_ATTN(2, 0); else if (fused == 1) HF_LAUNCH_ATTN(2, 1); else HF_LAUNCH_ATTN(2, 2);
   } else {
-    if (hist) HF_LAUNCH_ATTN(4, true); else HF_LAUNCH_ATTN(4, false);
+    if (fused == 0) HF_LAUNCH_ATTN(4, 0); else if (fused == 1) HF_LAUNCH_ATTN(4, 1); else HF_LAUNCH_ATTN(4, 2);
   }
 #undef HF_LAUNCH_ATTN
   return check_launch("hf_hybrid_attn_fwd(attention)");
@@ -427,19 +462,18 @@ int launch_attn_mfma(const hf_config& c, const void* Q, int n_q, const void* K, 
   return launch_attn_mfma_impl(c, Q, n_q, K, V, n_kv, idx, k, nullptr, O_local, s);
 }
 
-// ReLU feature map without rotation: the history term rides in the attention epilogue
-bool attn_mfma_fused_supported(const hf_config& c, bool has_rope) {
-  return attn_mfma_supported(c) && c.phi == HF_PHI_RELU && !has_rope;
-}
+// the history term rides in the attention epilogue (any feature map, with or without rotation)
+bool attn_mfma_fused_supported(const hf_config& c) { return attn_mfma_supported(c); }
 
 int launch_attn_mfma_fused(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
-                           const int32_t* idx, int k, const void* planes, const float* zvec, void* O,
-                           hipStream_t s) {
+                           const int32_t* idx, int k, const void* planes, const float* zvec, const float* cosq,
+                           const float* sinq, void* O, hipStream_t s) {
   // One bf16 plane of L (2^-9 per element, errors of the d terms of a readout average out) costs the
   // output nothing measurable next to the bf16 rounding of P and O; HF_FUSED_PLANES=2 in the
   // environment adds the low plane (development switch).
   const char* np = getenv("HF_FUSED_PLANES");
-  const HistArgs h = {static_cast<const bf16_t*>(planes), zvec, c.eps, c.z_scale, (np && np[0] == '2') ? 2 : 1};
+  const HistArgs h = {static_cast<const bf16_t*>(planes), zvec, c.eps, c.z_scale, (np && np[0] == '2') ? 2 : 1,
+                      c.phi, cosq, sinq};
   return launch_attn_mfma_impl(c, Q, n_q, K, V, n_kv, idx, k, &h, O, s);
 }
 

@@ -95,9 +95,9 @@ int launch_readout(const hf_config& c, const void* Q, int n_q, const void* O_loc
                    hipStream_t s);
 size_t readout_planes_bytes(const hf_config& c);  // scratch for the bf16 planes of the state
 int launch_state_planes(const hf_config& c, const float* state, void* planes, hipStream_t s);
-bool attn_mfma_fused_supported(const hf_config& c, bool has_rope);
+bool attn_mfma_fused_supported(const hf_config& c);
 int launch_attn_mfma_fused(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
-                           const int32_t* idx, int k, const void* planes, const float* zvec, void* O,
-                           hipStream_t s);
+                           const int32_t* idx, int k, const void* planes, const float* zvec, const float* cosq,
+                           const float* sinq, void* O, hipStream_t s);
 
 }  // namespace hf
