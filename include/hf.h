@@ -116,6 +116,17 @@ HF_API int hf_absorb_evicted(const hf_config* cfg, void* state,
                       const float* rope_cos, const float* rope_sin,
                       void* workspace, size_t workspace_bytes, void* stream);
 
+/* Cache eviction of the inference algorithm of the supplement ("pop(0)" of the KV cache followed by
+ * the update of the linear state) on the window buffers themselves: the oldest n_evict tokens of
+ * K_win, V_win [B, H, n_kv, d] are absorbed into the state exactly as hf_absorb_evicted does
+ * (rope tables [n_evict, d/2] or both NULL; workspace as for hf_absorb_evicted with n_evict
+ * tokens), then tokens [n_evict, n_kv) of every head move to [0, n_kv - n_evict), in place.  The
+ * last n_evict token slots keep stale data: the caller writes the next chunk's K, V there.
+ * Both steps are enqueued on the stream; 0 < n_evict <= n_kv. */
+HF_API int hf_window_advance(const hf_config* cfg, void* K_win, void* V_win, int32_t n_kv, int32_t n_evict,
+                      void* state, const float* rope_cos, const float* rope_sin,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
 /* k of "sparse Top K" for a window of n_kv tokens (see keep_k / keep_ratio).  Host-only. */
 HF_API int hf_select_k(const hf_config* cfg, int32_t n_kv, int32_t* k_out);
 

@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     hf_state_fold_linear,
     hf_absorb_evicted,
     hf_absorb_workspace_bytes,
+    hf_window_advance,
     hf_select_k,
     hf_workspace_bytes,
     hf_block_select,

@@ -76,12 +76,13 @@ def load():
     lib.hf_state_fold_linear.argtypes = [CP, P, P, P, P]
     lib.hf_absorb_evicted.argtypes = [CP, P, P, P, I, P, P, P, SZ, P]
     lib.hf_absorb_workspace_bytes.argtypes = [CP, I, ctypes.POINTER(SZ)]
+    lib.hf_window_advance.argtypes = [CP, P, P, I, I, P, P, P, P, SZ, P]
     lib.hf_select_k.argtypes = [CP, I, ctypes.POINTER(I)]
     lib.hf_workspace_bytes.argtypes = [CP, I, I, ctypes.POINTER(SZ)]
     lib.hf_block_select.argtypes = [CP, P, I, P, I, P, P, P, SZ, P]
     lib.hf_block_select_cached.argtypes = [CP, P, I, P, I, I, P, P, P, SZ, P]
     lib.hf_hybrid_attn_fwd.argtypes = [CP, P, I, P, P, I, P, I, P, P, P, P, P, SZ, P]
-    for name in ("hf_state_bytes", "hf_state_init", "hf_state_fold_linear", "hf_absorb_evicted", "hf_absorb_workspace_bytes", "hf_select_k",
+    for name in ("hf_state_bytes", "hf_state_init", "hf_state_fold_linear", "hf_window_advance", "hf_absorb_evicted", "hf_absorb_workspace_bytes", "hf_select_k",
                  "hf_workspace_bytes",
                  "hf_block_select", "hf_block_select_cached", "hf_hybrid_attn_fwd"):
         getattr(lib, name).restype = ctypes.c_int
@@ -129,6 +130,21 @@ def hf_state_bytes(cfg: hf_config) -> int:
     out = ctypes.c_size_t(0)
     _check(load().hf_state_bytes(ctypes.byref(cfg), ctypes.byref(out)))
     return out.value
+
+
+def hf_window_advance(cfg: hf_config, K_win, V_win, n_evict: int, state, rope_cos=None, rope_sin=None,
+                      workspace=None) -> None:
+    """Absorb the oldest n_evict tokens of the window buffers into the state and move the rest to the front."""
+    B, H, d = cfg.batch, cfg.heads, cfg.head_dim
+    n_kv = K_win.shape[2]
+    ns = hf_state_bytes(cfg) // 4
+    tab = (int(n_evict), d // 2)
+    _check(load().hf_window_advance(
+        ctypes.byref(cfg), _dev(K_win, "K_win", _tdtype(cfg), (B, H, n_kv, d)),
+        _dev(V_win, "V_win", _tdtype(cfg), (B, H, n_kv, d)), n_kv, int(n_evict),
+        _dev(state, "state", torch.float32, (ns,)), _dev(rope_cos, "rope_cos", torch.float32, tab),
+        _dev(rope_sin, "rope_sin", torch.float32, tab), _dev(workspace, "workspace", torch.uint8),
+        0 if workspace is None else workspace.numel(), _stream()))
 
 
 def hf_select_k(cfg: hf_config, n_kv: int) -> int:

@@ -159,8 +159,37 @@ int hf_absorb_evicted(const hf_config* cfg, void* state, const void* K_ev, const
     set_error("workspace is not 256-byte aligned");
     return HF_ERR_ALIGN;
   }
-  return launch_absorb(*cfg, static_cast<float*>(state), K_ev, V_ev, n_tokens, rope_cos, rope_sin, workspace,
-                       workspace ? workspace_bytes : 0, static_cast<hipStream_t>(stream));
+  return launch_absorb(*cfg, static_cast<float*>(state), K_ev, V_ev, n_tokens, n_tokens, rope_cos, rope_sin,
+                       workspace, workspace ? workspace_bytes : 0, static_cast<hipStream_t>(stream));
+}
+
+int hf_window_advance(const hf_config* cfg, void* K_win, void* V_win, int32_t n_kv, int32_t n_evict, void* state,
+                      const float* rope_cos, const float* rope_sin, void* workspace, size_t workspace_bytes,
+                      void* stream) {
+  HF_TRY(check_cfg(cfg));
+  HF_TRY(check_ptr(K_win, "K_win", true));
+  HF_TRY(check_ptr(V_win, "V_win", true));
+  HF_TRY(check_ptr(state, "state", true));
+  HF_TRY(check_tokens(n_kv, "n_kv"));
+  HF_TRY(check_tokens(n_evict, "n_evict"));
+  if (n_evict > n_kv) { set_error("n_evict=%d exceeds the %d tokens of the window", n_evict, n_kv); return HF_ERR_SHAPE; }
+  if ((rope_cos == nullptr) != (rope_sin == nullptr)) {
+    set_error("rope_cos and rope_sin must both be given or both be NULL");
+    return HF_ERR_NULL;
+  }
+  HF_TRY(check_ptr(rope_cos, "rope_cos", false));
+  HF_TRY(check_ptr(rope_sin, "rope_sin", false));
+  if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 255u)) {
+    set_error("workspace is not 256-byte aligned");
+    return HF_ERR_ALIGN;
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // the oldest n_evict tokens of every head (heads are n_kv tokens apart) go into the state ...
+  HF_TRY(launch_absorb(*cfg, static_cast<float*>(state), K_win, V_win, n_evict, n_kv, rope_cos, rope_sin, workspace,
+                       workspace ? workspace_bytes : 0, s));
+  // ... and the rest of the window moves to the front
+  if (n_evict == n_kv) return HF_OK;
+  return launch_window_shift(*cfg, K_win, V_win, n_kv, n_evict, s);
 }
 
 int hf_select_k(const hf_config* cfg, int32_t n_kv, int32_t* k_out) {

@@ -79,8 +79,8 @@ int launch_fold_linear(const hf_config& c, const float* state_in, const float* W
 // Tokens are staged TT at a time in LDS as fp32 (rotated phi(k) and v).
 template <typename T, int D>
 __global__ __launch_bounds__(256) void absorb_fma_kernel(float* __restrict__ state, const T* __restrict__ K,
-                                                         const T* __restrict__ V, int n, int tokens_per_slice,
-                                                         const float* __restrict__ cosv,
+                                                         const T* __restrict__ V, int n, int head_stride,
+                                                         int tokens_per_slice, const float* __restrict__ cosv,
                                                          const float* __restrict__ sinv, int phi_kind, int BH) {
   constexpr int E = D / 16;
   constexpr int TT = 32;
@@ -92,8 +92,8 @@ __global__ __launch_bounds__(256) void absorb_fma_kernel(float* __restrict__ sta
   if (t0 >= t1) return;
   const int tid = threadIdx.x;
   const int ti = tid / 16, tj = tid % 16;
-  const T* Kh = K + (size_t)bh * n * D;
-  const T* Vh = V + (size_t)bh * n * D;
+  const T* Kh = K + (size_t)bh * head_stride * D;  // head_stride tokens between heads (= n when packed)
+  const T* Vh = V + (size_t)bh * head_stride * D;
   float acc[E][E];
 #pragma unroll
   for (int a = 0; a < E; ++a)
@@ -150,7 +150,7 @@ __global__ __launch_bounds__(256) void absorb_fma_kernel(float* __restrict__ sta
 
 template <typename T, int D>
 static int launch_absorb_fma(const hf_config& c, float* state, const void* K, const void* V, int n,
-                             const float* cosv, const float* sinv, hipStream_t s) {
+                             int head_stride, const float* cosv, const float* sinv, hipStream_t s) {
   const int BH = c.batch * c.heads;
   // aim at ~4 workgroups per compute unit, at least 64 tokens per slice
   int slices = (1024 + BH - 1) / BH;
@@ -159,11 +159,11 @@ static int launch_absorb_fma(const hf_config& c, float* state, const void* K, co
   per = (per + 31) / 32 * 32;
   slices = (n + per - 1) / per;
   hipLaunchKernelGGL((absorb_fma_kernel<T, D>), dim3(slices, BH), dim3(256), 0, s, state,
-                     static_cast<const T*>(K), static_cast<const T*>(V), n, per, cosv, sinv, c.phi, BH);
+                     static_cast<const T*>(K), static_cast<const T*>(V), n, head_stride, per, cosv, sinv, c.phi, BH);
   return check_launch("hf_absorb_evicted");
 }
 
-int launch_absorb_mfma(const hf_config& c, float* state, const void* K, const void* V, int n,
+int launch_absorb_mfma(const hf_config& c, float* state, const void* K, const void* V, int n, int head_stride,
                        const float* cosv, const float* sinv, void* workspace, size_t workspace_bytes,
                        hipStream_t s);  // hf_state_mfma.hip
 size_t absorb_mfma_workspace_bytes(const hf_config& c, int n);
@@ -174,15 +174,47 @@ size_t absorb_workspace_bytes(const hf_config& c, int n) {
   return absorb_uses_mfma(c) ? absorb_mfma_workspace_bytes(c, n) : 0;
 }
 
-int launch_absorb(const hf_config& c, float* state, const void* K, const void* V, int n,
+int launch_absorb(const hf_config& c, float* state, const void* K, const void* V, int n, int head_stride,
                   const float* cosv, const float* sinv, void* workspace, size_t workspace_bytes,
                   hipStream_t s) {
   if (c.dtype == HF_F32) {
-    return c.head_dim == 128 ? launch_absorb_fma<float, 128>(c, state, K, V, n, cosv, sinv, s)
-                             : launch_absorb_fma<float, 64>(c, state, K, V, n, cosv, sinv, s);
+    return c.head_dim == 128 ? launch_absorb_fma<float, 128>(c, state, K, V, n, head_stride, cosv, sinv, s)
+                             : launch_absorb_fma<float, 64>(c, state, K, V, n, head_stride, cosv, sinv, s);
   }
-  if (absorb_uses_mfma(c)) return launch_absorb_mfma(c, state, K, V, n, cosv, sinv, workspace, workspace_bytes, s);
-  return launch_absorb_fma<bf16_t, 64>(c, state, K, V, n, cosv, sinv, s);
+  if (absorb_uses_mfma(c))
+    return launch_absorb_mfma(c, state, K, V, n, head_stride, cosv, sinv, workspace, workspace_bytes, s);
+  return launch_absorb_fma<bf16_t, 64>(c, state, K, V, n, head_stride, cosv, sinv, s);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Window compaction after an eviction: tokens [src, src + len) of every head move to [dst, dst + len)
+// in K_win and V_win (16-byte pieces; blockIdx.z picks K or V).  The caller issues non-overlapping
+// pieces in ascending order, so a launch never reads what it writes.
+__global__ __launch_bounds__(256) void window_shift_kernel(uint4* __restrict__ K, uint4* __restrict__ V,
+                                                           size_t head_stride16, size_t src16, size_t dst16,
+                                                           size_t len16) {
+  uint4* X = (blockIdx.z ? V : K) + (size_t)blockIdx.y * head_stride16;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < len16; i += (size_t)gridDim.x * 256)
+    X[dst16 + i] = X[src16 + i];
+}
+
+int launch_window_shift(const hf_config& c, void* K, void* V, int n_kv, int n_evict, hipStream_t s) {
+  const int BH = c.batch * c.heads;
+  const size_t row16 = (size_t)c.head_dim * (c.dtype == HF_BF16 ? 2 : 4) / 16;  // 16-byte pieces per token
+  const int keep = n_kv - n_evict;
+  // pieces of at most n_evict tokens: source [t + n_evict, ...) and destination [t, ...) never overlap
+  for (int t = 0; t < keep; t += n_evict) {
+    const int len = min(n_evict, keep - t);
+    const size_t len16 = (size_t)len * row16;
+    unsigned blocks = (unsigned)((len16 + 255) / 256);
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(window_shift_kernel, dim3(blocks, BH, 2), dim3(256), 0, s, static_cast<uint4*>(K),
+                       static_cast<uint4*>(V), (size_t)n_kv * row16, (size_t)(t + n_evict) * row16,
+                       (size_t)t * row16, len16);
+    const int rc = check_launch("hf_window_advance(shift)");
+    if (rc != HF_OK) return rc;
+  }
+  return HF_OK;
 }
 
 }  // namespace hf

@@ -64,7 +64,7 @@ __device__ __forceinline__ uint32_t relu_pk(uint32_t x) {
 template <bool kPlain>
 __global__ __launch_bounds__(NT, 1) void absorb_mfma_kernel(float* __restrict__ state, float* __restrict__ partials,
                                                              const bf16_t* __restrict__ K,
-                                                             const bf16_t* __restrict__ V, int n,
+                                                             const bf16_t* __restrict__ V, int n, int head_stride,
                                                              int tokens_per_slice, const float* __restrict__ cosv,
                                                              const float* __restrict__ sinv, int phi_kind, int BH,
                                                              int slices) {
@@ -87,8 +87,8 @@ __global__ __launch_bounds__(NT, 1) void absorb_mfma_kernel(float* __restrict__ 
   const int t0 = slice * tokens_per_slice;
   const int t1 = min(n, t0 + tokens_per_slice);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const bf16_t* Kh = K + (size_t)bh * n * D;
-  const bf16_t* Vh = V + (size_t)bh * n * D;
+  const bf16_t* Kh = K + (size_t)bh * head_stride * D;  // head_stride tokens between heads (= n when packed)
+  const bf16_t* Vh = V + (size_t)bh * head_stride * D;
   const int g = (lane & 7) + 8 * (lane >> 5);      // feature group: features 8g .. 8g+7
   const int tp0 = 4 * wave + ((lane >> 3) & 3);    // token pair of item 0; further items are TPI pairs apart
 
@@ -332,7 +332,7 @@ size_t absorb_mfma_workspace_bytes(const hf_config& c, int n) {
   return (size_t)c.batch * c.heads * slices * PART * sizeof(float);
 }
 
-int launch_absorb_mfma(const hf_config& c, float* state, const void* K, const void* V, int n,
+int launch_absorb_mfma(const hf_config& c, float* state, const void* K, const void* V, int n, int head_stride,
                        const float* cosv, const float* sinv, void* workspace, size_t workspace_bytes,
                        hipStream_t s) {
   const int BH = c.batch * c.heads;
@@ -346,10 +346,10 @@ int launch_absorb_mfma(const hf_config& c, float* state, const void* K, const vo
   const int heads_per_xcd = (BH + 7) / 8;
   const dim3 grid(use_ws ? BH * slices : 8 * heads_per_xcd * slices);
   if (plain) {
-    hipLaunchKernelGGL((absorb_mfma_kernel<true>), grid, dim3(NT), 0, s, state, partials, Kp, Vp, n, per, cosv,
+    hipLaunchKernelGGL((absorb_mfma_kernel<true>), grid, dim3(NT), 0, s, state, partials, Kp, Vp, n, head_stride, per, cosv,
                        sinv, c.phi, BH, slices);
   } else {
-    hipLaunchKernelGGL((absorb_mfma_kernel<false>), grid, dim3(NT), 0, s, state, partials, Kp, Vp, n, per, cosv,
+    hipLaunchKernelGGL((absorb_mfma_kernel<false>), grid, dim3(NT), 0, s, state, partials, Kp, Vp, n, head_stride, per, cosv,
                        sinv, c.phi, BH, slices);
   }
   const int rc = check_launch("hf_absorb_evicted");

@@ -105,6 +105,9 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_launch(lib):
     assert lib.hf_absorb_evicted(c, 4096, 4096, 4096, 0, None, None, None, 0, None) == -2
     assert lib.hf_absorb_evicted(c, 4096, 4096, 4096, 10, 4096, None, None, 0, None) == -1   # cos without sin
     assert lib.hf_absorb_evicted(c, 4096, 4096, 4096, 10, None, None, 4096 + 16, 1 << 20, None) == -4   # workspace alignment
+    assert lib.hf_window_advance(c, 4096, 8192, 200, 300, 1 << 20, None, None, None, 0, None) == -2   # evicts more than it holds
+    assert lib.hf_window_advance(c, 4096, None, 200, 100, 1 << 20, None, None, None, 0, None) == -1
+    assert lib.hf_window_advance(c, 4096, 8192, 200, 100, 1 << 20, 4096, None, None, 0, None) == -1  # cos without sin
     assert lib.hf_block_select(c, 4096, 100, 4096, 200, 4096, None, None, 0, None) == -5
     assert lib.hf_block_select(c, 4096, 100, 4096, 200, 4096, None, 4096 + 16, 1 << 30, None) == -4
     # reused pooled keys: whole blocks of the window only (200 tokens = 3 whole blocks of 64)

@@ -181,23 +181,27 @@ def test_streaming_200_chunks_state_drift_and_sampled_outputs():
     q_pool = [wl.randn((w.batch, w.heads, n_chunk, w.head_dim), 76_000 + i, w.scale, w.torch_dtype).to(DEV)
               for i in range(3)]
     errs_L, errs_z = [], []
+    # the window lives in one pair of device buffers [older chunk | current chunk], rolled by the library
+    Kw = torch.cat([pool_dev[win[0]][0], pool_dev[win[1]][0]], dim=2).contiguous()
+    Vw = torch.cat([pool_dev[win[0]][1], pool_dev[win[1]][1]], dim=2).contiguous()
     for c in range(1, n_chunks + 1):
-        Kw = torch.cat([pool_dev[win[0]][0], pool_dev[win[1]][0]], dim=2)
-        Vw = torch.cat([pool_dev[win[0]][1], pool_dev[win[1]][1]], dim=2)
         Q = wl.randn((w.batch, w.heads, n_chunk, w.head_dim), 77_000 + c, w.scale, w.torch_dtype) if c in sampled else None
         if Q is not None:
             L.attend(Q.to(DEV), Kw, Vw)
             torch.cuda.synchronize()
             Kc = torch.cat([pool[win[0]][0], pool[win[1]][0]], dim=2)
             Vc = torch.cat([pool[win[0]][1], pool[win[1]][1]], dim=2)
+            assert torch.equal(Kw.cpu(), Kc)                 # the rolled buffer holds exactly the window
             check_heads(w, cfg, L.k, Q, Kc, Vc, L.O, L.idx, states, [c % w.heads, (c + 5) % w.heads])
         else:
             L.attend(q_pool[c % 3], Kw, Vw)   # every chunk runs the hybrid attention; sampled ones are checked
-        # eviction of the oldest chunk into the state, then the window advances
-        L.absorb(*pool_dev[win[0]])
+        # eviction of the oldest chunk into the state and compaction of the window, then the next chunk arrives
+        hf.hf_window_advance(cfg, Kw, Vw, n_chunk, L.state, workspace=L.aws)
         k64, v64 = pool64[win[0]]
         states = [orc.state_absorb(Ls, zs, k64[h], v64[h]) for h, (Ls, zs) in enumerate(states)]
         win = [win[1], (win[1] + 1) % pool_size]
+        Kw[:, :, n_chunk:] = pool_dev[win[1]][0]
+        Vw[:, :, n_chunk:] = pool_dev[win[1]][1]
         torch.cuda.synchronize()
         Lg, zg = split_state(L.state, w.heads, w.head_dim)
         errs_L.append(rel_l2(Lg, np.stack([s[0] for s in states])))

@@ -222,6 +222,48 @@ def test_selection_with_reused_pooled_keys(name):
     assert np.array_equal(idx.cpu().numpy(), got_idx) and np.array_equal(scores.cpu().numpy(), got_sc)
 
 
+# ------------------------------------------------------------------------------- cache eviction
+@pytest.mark.parametrize("name,use_ws,rope", [("small_bf16", True, False), ("small_bf16", False, True),
+                                              ("tiny_f32", False, False), ("small_b128", True, True)])
+def test_window_advance_absorbs_the_oldest_chunk_and_compacts(name, use_ws, rope):
+    # three rolls of the window buffers: every roll pops one chunk into the state (oracle: direct sum over
+    # exactly those tokens), moves the rest to the front bit for bit, and leaves the freed tail to the caller
+    w = wl.get(name)
+    cfg = cfg_of(w)
+    d, n_kv, n_ev = w.head_dim, w.n_kv, w.n_q
+    assert n_kv - n_ev > n_ev                       # source and destination of the move overlap
+    _, K, V = wl.make_qkv(w)
+    Kd, Vd = K.to(DEV).clone(), V.to(DEV).clone()
+    Kc, Vc = K.clone(), V.clone()                   # host mirror of the window
+    st = new_state(cfg)
+    aws = absorb_ws(cfg, n_ev) if use_ws else None
+    states = [orc.state_zero(d) for _ in range(w.batch * w.heads)]
+    for roll in range(3):
+        tab = wl.rope_tables(n_ev, d, first_position=float(roll), tokens_per_position=w.tokens_per_frame) if rope \
+            else (None, None)
+        hf.hf_window_advance(cfg, Kd, Vd, n_ev, st, *(t.to(DEV) if t is not None else None for t in tab), workspace=aws)
+        torch.cuda.synchronize()
+        cos, sin = (None, None) if not rope else (wl.to_f64(tab[0]), wl.to_f64(tab[1]))
+        ke, ve = heads_of(Kc[:, :, :n_ev]), heads_of(Vc[:, :, :n_ev])
+        states = [orc.state_absorb(L, z, k_, v_, cfg.phi, cos, sin) for (L, z), k_, v_ in zip(states, ke, ve)]
+        Lg, zg = split_state(st, w.batch * w.heads, d)
+        bound = 5e-3 if (rope and w.dtype == "bf16" and d == 128) else 1e-5   # rotated keys rounded to bf16
+        assert rel_l2(Lg, np.stack([s_[0] for s_ in states])) <= bound
+        assert rel_l2(zg, np.stack([s_[1] for s_ in states])) <= 1e-5
+        # the window moved to the front, the tail untouched
+        Kc = torch.cat([Kc[:, :, n_ev:], Kc[:, :, n_kv - n_ev:]], dim=2)
+        Vc = torch.cat([Vc[:, :, n_ev:], Vc[:, :, n_kv - n_ev:]], dim=2)
+        assert torch.equal(Kd.cpu(), Kc) and torch.equal(Vd.cpu(), Vc)
+        # the caller writes the next chunk into the freed slots
+        Kn, Vn = wl.make_evicted(w, 40 + roll, n_ev)
+        Kd[:, :, n_kv - n_ev:] = Kn.to(DEV); Vd[:, :, n_kv - n_ev:] = Vn.to(DEV)
+        Kc[:, :, n_kv - n_ev:] = Kn; Vc[:, :, n_kv - n_ev:] = Vn
+    # evicting the whole window is allowed: nothing moves
+    hf.hf_window_advance(cfg, Kd, Vd, n_kv, st, workspace=None)
+    torch.cuda.synchronize()
+    assert torch.equal(Kd.cpu(), Kc)
+
+
 # ------------------------------------------------------------------------------- Linear of Eq. 3
 @pytest.mark.parametrize("name", ["small_bf16", "tiny_f32"])
 def test_linear_map_folded_into_the_state(name):
