@@ -380,7 +380,8 @@ def test_empty_state_gives_local_attention_only():
     assert torch.equal(a, b)
 
 
-@pytest.mark.parametrize("n_q,n_kv,b", [(1, 1, 64), (5, 70, 64), (64, 64, 64), (129, 257, 128), (33, 100, 16)])
+@pytest.mark.parametrize("n_q,n_kv,b", [(1, 1, 64), (5, 70, 64), (64, 64, 64), (129, 257, 128), (33, 100, 16),
+                                        (300, 1300, 256), (200, 1000, 192)])   # 192 / 256: wavefront-per-64-rows kernel
 def test_ragged_and_degenerate_sizes(n_q, n_kv, b):
     dtype = torch.bfloat16
     cfg = hf.make_config(1, 2, 128, "bf16", b, b, 0.5)
