@@ -117,17 +117,28 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
     for (int r = 0; r < 16; ++r) o[dt][r] = 0.0f;
   float m_ref = -INFINITY, l_run = 0.0f;
 
-  // ---- tile list: (selected block, 32-key part).  Tiles past the end of the list and
-  // out-of-range block indices give (0, 0): such a tile reads real rows and is masked entirely.
-  int cur_s = 0, cur_sub = 0;
-  auto next_tile = [&](int& start, int& valid) {
-    const int sc = min(cur_s, nsel - 1);
+  // ---- tile list: (selected block, 32-key part) -> (first key, number of real keys).  Tiles past
+  // the end of the list and out-of-range block indices give (0, 0): such a tile reads real rows and
+  // is masked entirely.  The descriptors are formed 64 tiles at a time, lane l holding tile 64 c + l,
+  // and handed out with one v_readlane per tile: the scalar bookkeeping (and the scalar load of the
+  // block index, whose wait would drain the LDS queue) stays out of the tile loop.
+  int d_tile = 0, tq = 0;  // first key (24 bits: the window has fewer than 2^23 keys) | real keys << 24
+  auto refill = [&](int t0) {
+    const int t = t0 + lane;
+    const int sel = t / subs, sub = t - sel * subs;
+    const int sc = min(sel, nsel - 1);
     const int jb = row_idx ? row_idx[sc] : sc;
-    const bool ok = (cur_s < nsel) && ((unsigned)jb < (unsigned)t_n);
-    const int st = jb * bkv + TK * cur_sub;
-    start = ok ? st : 0;
-    valid = ok ? max(0, min(TK, min(n_kv, (jb + 1) * bkv) - st)) : 0;
-    if (++cur_sub == subs) { cur_sub = 0; ++cur_s; }
+    const bool ok = (sel < nsel) && ((unsigned)jb < (unsigned)t_n);
+    const int st = jb * bkv + TK * sub;
+    d_tile = ok ? (st | (max(0, min(TK, min(n_kv, (jb + 1) * bkv) - st)) << 24)) : 0;
+  };
+  refill(0);
+  auto next_tile = [&](int& start, int& valid) {
+    if ((tq & 63) == 0 && tq > 0) refill(tq);  // uniform
+    const int d = __builtin_amdgcn_readlane(d_tile, tq & 63);
+    start = d & 0xffffff;
+    valid = d >> 24;
+    ++tq;
   };
 
   // ---- staging.  Loads go through buffer resources that end at the head's last key: rows past
@@ -213,10 +224,13 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
     f32x16 sacc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) sacc[r] = 0.0f;
+    uint32_t k_off = static_cast<uint32_t>(k_rd - sK);
+    // with the history epilogue compiled in, eight hoisted swizzled addresses cost spills inside this
+    // loop: there they are formed again for every tile (seven XORs)
+    if (kFused) asm volatile("" : "+v"(k_off));
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(
-          sK + par * KTILE + (static_cast<uint32_t>(k_rd - sK) ^ (32u * s)));
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(sK + par * KTILE + (k_off ^ (32u * s)));
       sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[s], sacc, 0, 0, 0);
     }
     // the first half of the V^T fragments is requested now: the reads complete under the softmax
