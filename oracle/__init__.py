@@ -20,3 +20,10 @@ from .hybrid_attention import (  # noqa: F401
     state_fold_linear,
     hybrid_attention,
 )
+from .rope import (  # noqa: F401
+    default_axis_pairs,
+    chunk_temporal_indices,
+    window_temporal_indices,
+    axis_frequencies,
+    rope_tables_3d,
+)

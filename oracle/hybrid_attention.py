@@ -224,9 +224,13 @@ def state_fold_linear(L, W) -> np.ndarray:
 def hybrid_attention(Q, K_win, V_win, state, b_q: int, b_kv: int, k: int,
                      phi_kind: int = PHI_RELU, cos_q=None, sin_q=None,
                      eps: float = 1e-6, z_scale: float = 1.0, scale=None,
-                     block_idx=None, W=None):
+                     block_idx=None, W=None, Q_hist=None):
     """The whole per-chunk path for one head: score, select, sparse attention,
     history readout, sum (Eq. 4, 5, 3, 6).
+
+    ``Q_hist``: the queries the history branch reads, when they differ from the ones of the
+    softmax branch (a model that rotates q for Eq. 4/5 while Eq. 3 applies phi to the
+    un-rotated q and rotates afterwards); ``None`` = the same ``Q``.
 
     ``state`` is ``(L, z)`` or ``None`` (no history yet: O_history = 0).  If
     ``block_idx`` is given it is used instead of the oracle's own selection (stage-wise
@@ -241,5 +245,5 @@ def hybrid_attention(Q, K_win, V_win, state, b_q: int, b_kv: int, k: int,
     if state is None:
         O_hist = np.zeros_like(O_local)
     else:
-        O_hist = history_readout(Q, state[0], state[1], phi_kind, cos_q, sin_q, eps, z_scale, W)
+        O_hist = history_readout(Q if Q_hist is None else Q_hist, state[0], state[1], phi_kind, cos_q, sin_q, eps, z_scale, W)
     return O_local + O_hist, O_local, O_hist, np.asarray(block_idx), gap
