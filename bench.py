@@ -230,6 +230,19 @@ def main():
     copy_ms, _ = time_calls(lambda s: cp_dst.copy_(cp_src[next(it) % nl]), a.steps)
     del cp_src, cp_dst
 
+    # preparation of Sec. 3.3 around the step, once per chunk and so outside the timed step: cos/sin tables of the
+    # window from its re-based frame indices, and the rotated copy of the window's keys that the softmax branch reads
+    rows, cols = wl.frame_grid(w)
+    pairs = (w.head_dim // 2 - 2 * (w.head_dim // 6), w.head_dim // 6, w.head_dim // 6)
+    win_idx = hf.hf_rope_window_indices(200, w.window_frames, 21)
+    kc = torch.empty((w.n_kv, w.head_dim // 2), dtype=torch.float32, device=dev)
+    ks = torch.empty_like(kc)
+    k_rot = torch.empty_like(sets[0]["K"])
+    tab_ms, _ = time_calls(lambda s: hf.hf_rope_tables(win_idx, rows, cols, pairs, kc, ks), a.steps)
+    ropek_ms, _ = time_calls(lambda s: hf.hf_rope_apply(cfg, s["K"], kc, ks, k_rot), a.steps)
+    rope_bytes = 2 * w.batch * w.heads * w.n_kv * w.head_dim * esz + 2 * kc.numel() * 4
+    del k_rot
+
     flops = float(np.mean([algorithmic_flops(s["idx"].cpu(), w) for s in sets]))
     dense_flops = 4.0 * w.head_dim * w.n_q * w.n_kv * w.heads * w.batch
     bh = w.batch * w.heads
@@ -264,15 +277,17 @@ def main():
                      "flops_per_launch": flops, "avg_ms": a4_ms, "min_ms": a4_min},
         "kernels_ms": {"block_select": sel_ms, "block_select_cached_half": selc_ms, "attn_fwd_total": fwd_ms, "sparse_flash_fwd": a4_ms,
                        "readout_combine_unfused": a5_ms, "fused_epilogue_extra": max(fwd_ms - a4_ms, 0.0), "absorb": abs_ms,
-                       "dense_window_fwd": dense_ms},
+                       "dense_window_fwd": dense_ms, "rope_tables_window": tab_ms, "rope_apply_k_window": ropek_ms},
         "hbm": {"absorb_GBs": absorb_bytes / (abs_ms * 1e-3) / 1e9,
                 "absorb_frac": absorb_bytes / (abs_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
                 "readout_GBs": (readout_bytes / (a5_ms * 1e-3) / 1e9) if a5_ms > 0 else None,
                 "readout_frac": (readout_bytes / (a5_ms * 1e-3) / 1e9 / PEAK_HBM_GBS) if a5_ms > 0 else None,
                 "select_GBs": select_bytes / (sel_ms * 1e-3) / 1e9,
+                "rope_apply_GBs": rope_bytes / (ropek_ms * 1e-3) / 1e9,
                 "device_copy_GBs": 2 * n_copy / (copy_ms * 1e-3) / 1e9,
                 "peak_GBs": PEAK_HBM_GBS,
-                "bytes": {"absorb": absorb_bytes, "readout": readout_bytes, "select": select_bytes}},
+                "bytes": {"absorb": absorb_bytes, "readout": readout_bytes, "select": select_bytes,
+                          "rope_apply": rope_bytes}},
     }
     if dense_ms is not None:
         out["dense"] = {"tflops": dense_flops / (dense_ms * 1e-3) / 1e12,

@@ -178,6 +178,53 @@ HF_API int hf_hybrid_attn_fwd(const hf_config* cfg, const void* Q, int32_t n_q,
                        const float* rope_cos_q, const float* rope_sin_q,
                        void* O, void* workspace, size_t workspace_bytes, void* stream);
 
+/* hf_hybrid_attn_fwd for a model that rotates q and k for the softmax branch as well (Sec. 3.3):
+ * Q_local (already rotated, e.g. by hf_rope_apply) feeds Eq. 5, Q_hist (un-rotated) feeds phi of
+ * Eq. 3, whose numerator is then rotated by rope_cos_q / rope_sin_q.  Both [B, H, n_q, d];
+ * Q_hist == Q_local or NULL is hf_hybrid_attn_fwd.  Everything else as there. */
+HF_API int hf_hybrid_attn_fwd_split(const hf_config* cfg, const void* Q_local, const void* Q_hist, int32_t n_q,
+                       const void* K_win, const void* V_win, int32_t n_kv,
+                       const int32_t* block_idx, int32_t k,
+                       const void* state_or_null,
+                       const float* rope_cos_q, const float* rope_sin_q,
+                       void* O, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- Relative RoPE (Sec. 3.3) ------------------------------------------------------------------ */
+#define HF_ROPE_MAX_FRAMES 64    /* frames one hf_rope_tables call covers */
+#define HF_ROPE_MAX_PAIRS 128    /* feature pairs (head_dim / 2) of a table row */
+
+/* Eq. 7 and the re-basing of the KV cache, host-only: temporal indices of the last n_frames latent
+ * frames up to and including the frame with running index i_newest (cached frames first, the
+ * current chunk last).  The newest frame takes min(i_newest, t0) (the index stops at the cap t0 of
+ * the pretrained model), every other frame keeps its offset to it:
+ *     idx_out[n_frames - 1 - delta] = min(i_newest, t0) - delta.
+ * idx_out: HOST int32 [n_frames], 1 <= n_frames. */
+HF_API int hf_rope_window_indices(int32_t i_newest, int32_t n_frames, int32_t t0, int32_t* idx_out);
+
+/* cos / sin tables of the three-axis rotary embedding for n_frames * height * width tokens ordered
+ * frame-major, then row, then column: of the pairs_t + pairs_h + pairs_w adjacent feature pairs of
+ * a token the first pairs_t turn by frame_idx[frame] * w, the next pairs_h by row * w, the last
+ * pairs_w by column * w radians, with w = theta^(-p / pairs_axis) for pair p of its axis.  The paper
+ * fixes only the temporal indices (Eq. 7; spatial coordinates unchanged); the split and theta are
+ * those of the pretrained model (head_dim 128: 22 + 21 + 21 pairs, theta 10000).
+ *   frame_idx  HOST int32 [n_frames] (copied into the launch), 1 <= n_frames <= HF_ROPE_MAX_FRAMES;
+ *              negative values allowed
+ *   temporal_only != 0: spatial angles are zero; such a table moves tokens that already carry
+ *              their rotation by frame_idx frames (re-basing cached keys by an offset)
+ *   cos_out, sin_out  out fp32 [n_frames * height * width, pairs_t + pairs_h + pairs_w]
+ * Angles and their sine / cosine are computed in fp64 and rounded once to fp32. */
+HF_API int hf_rope_tables(const int32_t* frame_idx, int32_t n_frames, int32_t height, int32_t width,
+                   int32_t pairs_t, int32_t pairs_h, int32_t pairs_w, double theta, int32_t temporal_only,
+                   float* cos_out, float* sin_out, void* stream);
+
+/* Rotation of adjacent feature pairs (2p, 2p+1) of every token by its own angle:
+ *     y[2p] = x[2p] cos - x[2p+1] sin,   y[2p+1] = x[2p] sin + x[2p+1] cos
+ * for X [B, H, n_tokens, d] of cfg->dtype with tables fp32 [n_tokens, d/2] shared by heads and
+ * batch; fp32 arithmetic, one rounding to cfg->dtype.  Y may be X (in place) but must not overlap
+ * it otherwise. */
+HF_API int hf_rope_apply(const hf_config* cfg, const void* X, int32_t n_tokens,
+                  const float* rope_cos, const float* rope_sin, void* Y, void* stream);
+
 /* Last error message of the calling thread (static storage, never NULL). */
 HF_API const char* hf_last_error(void);
 

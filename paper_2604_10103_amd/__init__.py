@@ -25,4 +25,7 @@ from .binding import (  # noqa: F401
     hf_block_select,
     hf_block_select_cached,
     hf_hybrid_attn_fwd,
+    hf_rope_window_indices,
+    hf_rope_tables,
+    hf_rope_apply,
 )

@@ -82,9 +82,14 @@ def load():
     lib.hf_block_select.argtypes = [CP, P, I, P, I, P, P, P, SZ, P]
     lib.hf_block_select_cached.argtypes = [CP, P, I, P, I, I, P, P, P, SZ, P]
     lib.hf_hybrid_attn_fwd.argtypes = [CP, P, I, P, P, I, P, I, P, P, P, P, P, SZ, P]
+    lib.hf_hybrid_attn_fwd_split.argtypes = [CP, P, P, I, P, P, I, P, I, P, P, P, P, P, SZ, P]
+    lib.hf_rope_window_indices.argtypes = [I, I, I, ctypes.POINTER(I)]
+    lib.hf_rope_tables.argtypes = [ctypes.POINTER(I), I, I, I, I, I, I, ctypes.c_double, I, P, P, P]
+    lib.hf_rope_apply.argtypes = [CP, P, I, P, P, P, P]
     for name in ("hf_state_bytes", "hf_state_init", "hf_state_fold_linear", "hf_window_advance", "hf_absorb_evicted", "hf_absorb_workspace_bytes", "hf_select_k",
                  "hf_workspace_bytes",
-                 "hf_block_select", "hf_block_select_cached", "hf_hybrid_attn_fwd"):
+                 "hf_block_select", "hf_block_select_cached", "hf_hybrid_attn_fwd", "hf_hybrid_attn_fwd_split",
+                 "hf_rope_window_indices", "hf_rope_tables", "hf_rope_apply"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -221,8 +226,9 @@ def hf_block_select_cached(cfg: hf_config, Q, K_win, n_cached_kv_blocks: int, bl
 
 
 def hf_hybrid_attn_fwd(cfg: hf_config, Q, K_win, V_win, block_idx, state, O, workspace=None,
-                       rope_cos_q=None, rope_sin_q=None) -> None:
-    """block_idx None = dense window attention; state None = no history term."""
+                       rope_cos_q=None, rope_sin_q=None, Q_hist=None) -> None:
+    """block_idx None = dense window attention; state None = no history term; Q_hist: the history branch's
+    queries when they are not Q (hf_hybrid_attn_fwd_split)."""
     B, H, d = cfg.batch, cfg.heads, cfg.head_dim
     n_q, n_kv = Q.shape[2], K_win.shape[2]
     t_m = _cdiv(n_q, cfg.block_q)
@@ -233,8 +239,10 @@ def hf_hybrid_attn_fwd(cfg: hf_config, Q, K_win, V_win, block_idx, state, O, wor
         k = block_idx.shape[3]
     tab = (n_q, d // 2)
     ns = hf_state_bytes(cfg) // 4
-    _check(load().hf_hybrid_attn_fwd(
-        ctypes.byref(cfg), _dev(Q, "Q", _tdtype(cfg), (B, H, n_q, d)), n_q,
+    split = () if Q_hist is None else (_dev(Q_hist, "Q_hist", _tdtype(cfg), (B, H, n_q, d)),)
+    entry = load().hf_hybrid_attn_fwd if Q_hist is None else load().hf_hybrid_attn_fwd_split
+    _check(entry(
+        ctypes.byref(cfg), _dev(Q, "Q", _tdtype(cfg), (B, H, n_q, d)), *split, n_q,
         _dev(K_win, "K_win", _tdtype(cfg), (B, H, n_kv, d)),
         _dev(V_win, "V_win", _tdtype(cfg), (B, H, n_kv, d)), n_kv,
         _dev(block_idx, "block_idx", torch.int32, (B, H, t_m, k)), k,
@@ -242,3 +250,32 @@ def hf_hybrid_attn_fwd(cfg: hf_config, Q, K_win, V_win, block_idx, state, O, wor
         _dev(rope_cos_q, "rope_cos_q", torch.float32, tab), _dev(rope_sin_q, "rope_sin_q", torch.float32, tab),
         _dev(O, "O", _tdtype(cfg), (B, H, n_q, d)),
         _dev(workspace, "workspace", torch.uint8), 0 if workspace is None else workspace.numel(), _stream()))
+
+
+def hf_rope_window_indices(i_newest: int, n_frames: int, t0: int) -> list:
+    """Eq. 7 with the cache re-based to the current chunk: temporal indices of the last n_frames frames."""
+    out = (ctypes.c_int32 * n_frames)()
+    _check(load().hf_rope_window_indices(int(i_newest), int(n_frames), int(t0), out))
+    return list(out)
+
+
+def hf_rope_tables(frame_idx, height: int, width: int, pairs, cos_out, sin_out, theta: float = 10000.0,
+                   temporal_only: bool = False) -> None:
+    """cos_out, sin_out: fp32 GPU tensors [len(frame_idx) * height * width, sum(pairs)]."""
+    nf = len(frame_idx)
+    arr = (ctypes.c_int32 * max(nf, 1))(*[int(x) for x in frame_idx])
+    shp = (nf * height * width, int(sum(pairs)))
+    _check(load().hf_rope_tables(arr, nf, int(height), int(width), int(pairs[0]), int(pairs[1]), int(pairs[2]),
+                                 float(theta), 1 if temporal_only else 0,
+                                 _dev(cos_out, "cos_out", torch.float32, shp),
+                                 _dev(sin_out, "sin_out", torch.float32, shp), _stream()))
+
+
+def hf_rope_apply(cfg: hf_config, X, rope_cos, rope_sin, Y) -> None:
+    """Y = X with adjacent feature pairs of every token turned by the tables [n, d/2]; Y may be X."""
+    B, H, d = cfg.batch, cfg.heads, cfg.head_dim
+    n = X.shape[2]
+    _check(load().hf_rope_apply(
+        ctypes.byref(cfg), _dev(X, "X", _tdtype(cfg), (B, H, n, d)), n,
+        _dev(rope_cos, "rope_cos", torch.float32, (n, d // 2)), _dev(rope_sin, "rope_sin", torch.float32, (n, d // 2)),
+        _dev(Y, "Y", _tdtype(cfg), (B, H, n, d)), _stream()))

@@ -28,6 +28,7 @@ SOURCES = [
     "hf_attn_w64.hip",
     "hf_readout.hip",
     "hf_readout_mfma.hip",
+    "hf_rope.hip",
 ]
 
 FLAGS = [

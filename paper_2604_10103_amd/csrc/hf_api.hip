@@ -259,8 +259,19 @@ int hf_hybrid_attn_fwd(const hf_config* cfg, const void* Q, int32_t n_q, const v
                        const void* V_win, int32_t n_kv, const int32_t* block_idx, int32_t k,
                        const void* state_or_null, const float* rope_cos_q, const float* rope_sin_q,
                        void* O, void* workspace, size_t workspace_bytes, void* stream) {
+  return hf_hybrid_attn_fwd_split(cfg, Q, Q, n_q, K_win, V_win, n_kv, block_idx, k, state_or_null, rope_cos_q,
+                                  rope_sin_q, O, workspace, workspace_bytes, stream);
+}
+
+int hf_hybrid_attn_fwd_split(const hf_config* cfg, const void* Q, const void* Q_hist, int32_t n_q,
+                             const void* K_win, const void* V_win, int32_t n_kv, const int32_t* block_idx,
+                             int32_t k, const void* state_or_null, const float* rope_cos_q,
+                             const float* rope_sin_q, void* O, void* workspace, size_t workspace_bytes,
+                             void* stream) {
   HF_TRY(check_cfg(cfg));
   HF_TRY(check_ptr(Q, "Q", true));
+  if (!Q_hist) Q_hist = Q;
+  HF_TRY(check_ptr(Q_hist, "Q_hist", true));
   HF_TRY(check_ptr(K_win, "K_win", true));
   HF_TRY(check_ptr(V_win, "V_win", true));
   HF_TRY(check_ptr(O, "O", true));
@@ -268,7 +279,7 @@ int hf_hybrid_attn_fwd(const hf_config* cfg, const void* Q, int32_t n_q, const v
   HF_TRY(check_ptr(state_or_null, "state", false));
   HF_TRY(check_tokens(n_q, "n_q"));
   HF_TRY(check_tokens(n_kv, "n_kv"));
-  if (O == Q || O == K_win || O == V_win) { set_error("O must not alias an input"); return HF_ERR_SHAPE; }
+  if (O == Q || O == Q_hist || O == K_win || O == V_win) { set_error("O must not alias an input"); return HF_ERR_SHAPE; }
   if ((rope_cos_q == nullptr) != (rope_sin_q == nullptr)) {
     set_error("rope_cos_q and rope_sin_q must both be given or both be NULL");
     return HF_ERR_NULL;
@@ -300,12 +311,59 @@ int hf_hybrid_attn_fwd(const hf_config* cfg, const void* Q, int32_t n_q, const v
     const size_t d = cfg->head_dim;
     HF_TRY(launch_state_planes(*cfg, st, planes, s));
     return launch_attn_mfma_fused(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, planes,
-                                  st + (size_t)cfg->batch * cfg->heads * d * d, rope_cos_q, rope_sin_q, O, s);
+                                  st + (size_t)cfg->batch * cfg->heads * d * d, rope_cos_q, rope_sin_q, Q_hist, O, s);
   }
   void* o_local = static_cast<char*>(workspace) + w.olocal;
   HF_TRY(launch_attn(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, o_local, s));
-  return launch_readout(*cfg, Q, n_q, o_local, static_cast<const float*>(state_or_null), rope_cos_q,
+  return launch_readout(*cfg, Q_hist, n_q, o_local, static_cast<const float*>(state_or_null), rope_cos_q,
                         rope_sin_q, static_cast<char*>(workspace) + w.planes, O, s);
+}
+
+int hf_rope_window_indices(int32_t i_newest, int32_t n_frames, int32_t t0, int32_t* idx_out) {
+  if (!idx_out) { set_error("idx_out is NULL"); return HF_ERR_NULL; }
+  if (n_frames < 1) { set_error("n_frames must be >= 1"); return HF_ERR_SHAPE; }
+  const int64_t newest = i_newest <= t0 ? i_newest : t0;
+  if (newest - (n_frames - 1) < INT32_MIN) { set_error("index out of range"); return HF_ERR_SHAPE; }
+  for (int32_t delta = 0; delta < n_frames; ++delta) idx_out[n_frames - 1 - delta] = (int32_t)(newest - delta);
+  return HF_OK;
+}
+
+int hf_rope_tables(const int32_t* frame_idx, int32_t n_frames, int32_t height, int32_t width, int32_t pairs_t,
+                   int32_t pairs_h, int32_t pairs_w, double theta, int32_t temporal_only, float* cos_out,
+                   float* sin_out, void* stream) {
+  if (!frame_idx) { set_error("frame_idx is NULL"); return HF_ERR_NULL; }
+  if (n_frames < 1 || n_frames > HF_ROPE_MAX_FRAMES) {
+    set_error("n_frames must be in [1, %d], got %d", HF_ROPE_MAX_FRAMES, n_frames); return HF_ERR_SHAPE;
+  }
+  if (height < 1 || width < 1 || (int64_t)n_frames * height * width > (1 << 24)) {
+    set_error("height and width must be >= 1 and n_frames*height*width <= 2^24"); return HF_ERR_SHAPE;
+  }
+  if (pairs_t < 0 || pairs_h < 0 || pairs_w < 0 || pairs_t + (int64_t)pairs_h + pairs_w < 1 ||
+      pairs_t + (int64_t)pairs_h + pairs_w > HF_ROPE_MAX_PAIRS) {
+    set_error("pairs_t + pairs_h + pairs_w must be in [1, %d]", HF_ROPE_MAX_PAIRS); return HF_ERR_SHAPE;
+  }
+  if (!(theta > 0.0) || !isfinite(theta)) { set_error("theta must be positive and finite"); return HF_ERR_SHAPE; }
+  HF_TRY(check_ptr(cos_out, "cos_out", true));
+  HF_TRY(check_ptr(sin_out, "sin_out", true));
+  return launch_rope_tables(frame_idx, n_frames, height, width, pairs_t, pairs_h, pairs_w, theta, temporal_only,
+                            cos_out, sin_out, static_cast<hipStream_t>(stream));
+}
+
+int hf_rope_apply(const hf_config* cfg, const void* X, int32_t n_tokens, const float* rope_cos,
+                  const float* rope_sin, void* Y, void* stream) {
+  HF_TRY(check_cfg(cfg));
+  HF_TRY(check_ptr(X, "X", true));
+  HF_TRY(check_ptr(Y, "Y", true));
+  HF_TRY(check_ptr(rope_cos, "rope_cos", true));
+  HF_TRY(check_ptr(rope_sin, "rope_sin", true));
+  HF_TRY(check_tokens(n_tokens, "n_tokens"));
+  if (X != Y) {
+    const size_t bytes = (size_t)cfg->batch * cfg->heads * n_tokens * cfg->head_dim * esize(cfg);
+    const char* a = static_cast<const char*>(X);
+    const char* b = static_cast<const char*>(Y);
+    if (a < b + bytes && b < a + bytes) { set_error("Y overlaps X without being X"); return HF_ERR_SHAPE; }
+  }
+  return launch_rope_apply(*cfg, X, n_tokens, rope_cos, rope_sin, Y, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

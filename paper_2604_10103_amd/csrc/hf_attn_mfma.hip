@@ -66,6 +66,7 @@ struct HistArgs {
   int phi_kind;          // feature map of the history branch
   const float* cosq;     // [n_q][d/2] rotation of phi(q) in the numerator, or NULL
   const float* sinq;
+  const bf16_t* q_hist;  // [BH][n_q][d] queries of the history branch when they are not Q, or NULL
 };
 
 // kFused: 0 = attention only, 1 = + history term for ReLU without rotation, 2 = + history term, general
@@ -348,6 +349,11 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
       // any feature map, optional rotation of adjacent feature pairs: phi in fp32, the denominator from
       // the unrotated phi(q), the rotated numerator operand rounded to bf16 (2^-9, like P)
       const size_t trow = (size_t)min(q_row, n_q - 1) * (D / 2) + 4 * h;
+      if (hist.q_hist) {
+        const bf16_t* qp = hist.q_hist + ((size_t)bh * n_q + min(q_row, n_q - 1)) * D + 8 * h;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qp + 16 * s);
+      }
 #pragma unroll
       for (int s = 0; s < 8; ++s) {
         float f[8];
@@ -457,11 +463,11 @@ static int launch_attn_mfma_impl(const hf_config& c, const void* Q, int n_q, con
   const bf16_t* kk = static_cast<const bf16_t*>(K);
   const bf16_t* v = static_cast<const bf16_t*>(V);
   bf16_t* o = static_cast<bf16_t*>(O);
-  const HistArgs h = hist ? *hist : HistArgs{nullptr, nullptr, 0.0f, 0.0f, 0, 0, nullptr, nullptr};
+  const HistArgs h = hist ? *hist : HistArgs{nullptr, nullptr, 0.0f, 0.0f, 0, 0, nullptr, nullptr, nullptr};
 #define HF_LAUNCH_ATTN(NWV, FUSED)                                                                              \
   hipLaunchKernelGGL((attn_mfma_kernel<NWV, FUSED>), grid, dim3(64 * NWV), 0, s, q, kk, v, idx, k, n_q, n_kv,   \
                      c.block_kv, t_m, t_n, per_xcd, (int)total, c_scale, h, o)
-  const int fused = !hist ? 0 : ((h.phi_kind == HF_PHI_RELU && h.cosq == nullptr) ? 1 : 2);
+  const int fused = !hist ? 0 : ((h.phi_kind == HF_PHI_RELU && h.cosq == nullptr && h.q_hist == nullptr) ? 1 : 2);
   if (c.block_q == 64) {
     if (fused == 0) HF_LAUNCH_ATTN(2, 0); else if (fused == 1) HF_LAUNCH_ATTN(2, 1); else HF_LAUNCH_ATTN(2, 2);
   } else {
@@ -481,13 +487,13 @@ bool attn_mfma_fused_supported(const hf_config& c) { return attn_mfma_supported(
 
 int launch_attn_mfma_fused(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
                            const int32_t* idx, int k, const void* planes, const float* zvec, const float* cosq,
-                           const float* sinq, void* O, hipStream_t s) {
+                           const float* sinq, const void* Q_hist, void* O, hipStream_t s) {
   // One bf16 plane of L (2^-9 per element, errors of the d terms of a readout average out) costs the
   // output nothing measurable next to the bf16 rounding of P and O; HF_FUSED_PLANES=2 in the
   // environment adds the low plane (development switch).
   const char* np = getenv("HF_FUSED_PLANES");
   const HistArgs h = {static_cast<const bf16_t*>(planes), zvec, c.eps, c.z_scale, (np && np[0] == '2') ? 2 : 1,
-                      c.phi, cosq, sinq};
+                      c.phi, cosq, sinq, Q_hist == Q ? nullptr : static_cast<const bf16_t*>(Q_hist)};
   return launch_attn_mfma_impl(c, Q, n_q, K, V, n_kv, idx, k, &h, O, s);
 }
 

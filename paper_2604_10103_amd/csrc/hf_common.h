@@ -99,6 +99,10 @@ int launch_state_planes(const hf_config& c, const float* state, void* planes, hi
 bool attn_mfma_fused_supported(const hf_config& c);
 int launch_attn_mfma_fused(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
                            const int32_t* idx, int k, const void* planes, const float* zvec, const float* cosq,
-                           const float* sinq, void* O, hipStream_t s);
+                           const float* sinq, const void* Q_hist, void* O, hipStream_t s);
+int launch_rope_tables(const int32_t* frame_idx, int n_frames, int height, int width, int pairs_t, int pairs_h,
+                       int pairs_w, double theta, int temporal_only, float* cosv, float* sinv, hipStream_t s);
+int launch_rope_apply(const hf_config& c, const void* X, int n, const float* cosv, const float* sinv, void* Y,
+                      hipStream_t s);
 
 }  // namespace hf

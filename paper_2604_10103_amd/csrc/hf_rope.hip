@@ -1,0 +1,114 @@
+// Relative, capped temporal RoPE (Sec. 3.3, Eq. 7): construction of the per-token cos/sin tables
+// from frame indices and the token grid, and rotation of a Q or K tensor by such tables.
+//
+// Both kernels are small and HBM-bound.  The rotation is a pass of its own, not folded into the
+// attention kernel's tile loads: that kernel is bound by its vector ALU work next to the matrix
+// cores, a rotated copy of the window's K costs one read and one write of it per chunk, and the
+// copy is then read by every denoising step of the chunk.
+#include <math.h>
+
+#include "hf_common.h"
+
+namespace hf {
+
+struct RopeSpec {
+  int frame_idx[HF_ROPE_MAX_FRAMES];
+  double omega[HF_ROPE_MAX_PAIRS];  // radians per position step of every feature pair
+};
+
+// one thread per (token, pair); angles and their sine / cosine in fp64, rounded once to fp32
+__global__ __launch_bounds__(256) void rope_tables_kernel(const RopeSpec spec, int n_tokens, int height, int width,
+                                                          int pairs_t, int pairs_h, int pairs_w, int temporal_only,
+                                                          float* __restrict__ cosv, float* __restrict__ sinv) {
+  const int P = pairs_t + pairs_h + pairs_w;
+  const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (e >= (long long)n_tokens * P) return;
+  const int tok = (int)(e / P), p = (int)(e - (long long)tok * P);
+  const int frame = tok / (height * width);
+  const int rem = tok - frame * height * width;
+  const int row = rem / width, col = rem - row * width;
+  int pos;
+  if (p < pairs_t) pos = spec.frame_idx[frame];
+  else if (temporal_only) pos = 0;
+  else pos = p < pairs_t + pairs_h ? row : col;
+  double sn, cs;
+  sincos((double)pos * spec.omega[p], &sn, &cs);
+  cosv[e] = (float)cs;
+  sinv[e] = (float)sn;
+}
+
+// 8 consecutive features (4 adjacent pairs) of one token per thread; fp32 arithmetic, one rounding to
+// the storage type.  X and Y may be the same buffer: a thread writes only what it has read.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void rope_apply_kernel(const T* __restrict__ X, int n_tokens,
+                                                         const float* __restrict__ cosv,
+                                                         const float* __restrict__ sinv, T* __restrict__ Y) {
+  constexpr int TPT = D / 8;         // threads per token
+  constexpr int TOK = 256 / TPT;     // tokens per workgroup
+  const int tok = blockIdx.x * TOK + threadIdx.x / TPT;
+  if (tok >= n_tokens) return;
+  const int g = threadIdx.x % TPT;
+  const size_t off = ((size_t)blockIdx.y * n_tokens + tok) * D + 8 * g;
+  float x[8];
+  load16B<T>(X + off, x);
+  if (Elem<T>::kPer16B == 4) load16B<T>(X + off + 4, x + 4);
+  const float4 c4 = *reinterpret_cast<const float4*>(cosv + (size_t)tok * (D / 2) + 4 * g);
+  const float4 s4 = *reinterpret_cast<const float4*>(sinv + (size_t)tok * (D / 2) + 4 * g);
+  const float cc[4] = {c4.x, c4.y, c4.z, c4.w}, ss[4] = {s4.x, s4.y, s4.z, s4.w};
+  float y[8];
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    y[2 * p] = x[2 * p] * cc[p] - x[2 * p + 1] * ss[p];
+    y[2 * p + 1] = x[2 * p] * ss[p] + x[2 * p + 1] * cc[p];
+  }
+  if (Elem<T>::kPer16B == 8) {
+    uint4 o;
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f32_to_bf16(y[2 * i]) | ((uint32_t)f32_to_bf16(y[2 * i + 1]) << 16);
+    o.x = w[0]; o.y = w[1]; o.z = w[2]; o.w = w[3];
+    *reinterpret_cast<uint4*>(Y + off) = o;
+  } else {
+    *reinterpret_cast<float4*>(Y + off) = make_float4(y[0], y[1], y[2], y[3]);
+    *reinterpret_cast<float4*>(Y + off + 4) = make_float4(y[4], y[5], y[6], y[7]);
+  }
+}
+
+int launch_rope_tables(const int32_t* frame_idx, int n_frames, int height, int width, int pairs_t, int pairs_h,
+                       int pairs_w, double theta, int temporal_only, float* cosv, float* sinv, hipStream_t s) {
+  RopeSpec spec;
+  for (int f = 0; f < HF_ROPE_MAX_FRAMES; ++f) spec.frame_idx[f] = f < n_frames ? frame_idx[f] : 0;
+  const int np[3] = {pairs_t, pairs_h, pairs_w};
+  int at = 0;
+  for (int a = 0; a < 3; ++a)
+    for (int p = 0; p < np[a]; ++p) spec.omega[at++] = pow(theta, -(double)p / (double)np[a]);
+  for (; at < HF_ROPE_MAX_PAIRS; ++at) spec.omega[at] = 0.0;
+  const long long n_tokens = (long long)n_frames * height * width;
+  const long long total = n_tokens * (pairs_t + pairs_h + pairs_w);
+  hipLaunchKernelGGL(rope_tables_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, spec,
+                     (int)n_tokens, height, width, pairs_t, pairs_h, pairs_w, temporal_only, cosv, sinv);
+  return check_launch("hf_rope_tables");
+}
+
+template <typename T>
+static int launch_rope_apply_t(const hf_config& c, const void* X, int n, const float* cosv, const float* sinv,
+                               void* Y, hipStream_t s) {
+  const int D = c.head_dim;
+  const int tok_per_wg = 256 / (D / 8);
+  const dim3 grid((n + tok_per_wg - 1) / tok_per_wg, c.batch * c.heads);
+  if (D == 128)
+    hipLaunchKernelGGL((rope_apply_kernel<T, 128>), grid, dim3(256), 0, s, static_cast<const T*>(X), n, cosv, sinv,
+                       static_cast<T*>(Y));
+  else
+    hipLaunchKernelGGL((rope_apply_kernel<T, 64>), grid, dim3(256), 0, s, static_cast<const T*>(X), n, cosv, sinv,
+                       static_cast<T*>(Y));
+  return check_launch("hf_rope_apply");
+}
+
+int launch_rope_apply(const hf_config& c, const void* X, int n, const float* cosv, const float* sinv, void* Y,
+                      hipStream_t s) {
+  return c.dtype == HF_BF16 ? launch_rope_apply_t<bf16_t>(c, X, n, cosv, sinv, Y, s)
+                            : launch_rope_apply_t<float>(c, X, n, cosv, sinv, Y, s);
+}
+
+}  // namespace hf

@@ -121,3 +121,35 @@ def test_null_and_misaligned_pointers_are_rejected_before_any_launch(lib):
     # state given but no workspace
     assert lib.hf_hybrid_attn_fwd(c, 4096, 100, 8192, 8192, 200, None, 0, 4096, None, None, 16384, None, 0, None) == -5
     assert b"workspace" in lib.hf_last_error()
+
+
+def test_rope_window_indices_follow_eq7(lib):
+    # host-only helper against the oracle's reading of Eq. 7 and of the re-based cache
+    for t0 in (5, 21):
+        for n in (1, 3, 6, 9, 30):
+            for i in (0, 2, 5, 20, 21, 22, 23, 1000):
+                assert hf.hf_rope_window_indices(i, n, t0) == orc.window_temporal_indices(i, n, t0).tolist()
+    assert hf.hf_rope_window_indices(30, 3, 21) == orc.chunk_temporal_indices(30, 3, 21).tolist()
+
+
+def test_rope_calls_reject_bad_arguments(lib):
+    cfg = hf.make_config(1, 2, 128, "bf16", 64, 64, 0.25)
+    c = ctypes.byref(cfg)
+    I = ctypes.c_int32
+    idx = (I * 70)(*range(70))
+    assert lib.hf_rope_window_indices(5, 0, 21, idx) == -2
+    assert lib.hf_rope_window_indices(5, 3, 21, None) == -1
+    assert lib.hf_rope_tables(None, 3, 4, 4, 22, 21, 21, 1e4, 0, 4096, 8192, None) == -1
+    assert lib.hf_rope_tables(idx, 65, 4, 4, 22, 21, 21, 1e4, 0, 4096, 8192, None) == -2     # too many frames
+    assert lib.hf_rope_tables(idx, 3, 4, 4, 64, 64, 1, 1e4, 0, 4096, 8192, None) == -2       # too many pairs
+    assert lib.hf_rope_tables(idx, 3, 0, 4, 22, 21, 21, 1e4, 0, 4096, 8192, None) == -2
+    assert lib.hf_rope_tables(idx, 3, 4, 4, 22, 21, 21, -1.0, 0, 4096, 8192, None) == -2
+    assert lib.hf_rope_tables(idx, 3, 4, 4, 22, 21, 21, 1e4, 0, None, 8192, None) == -1
+    assert lib.hf_rope_apply(c, 4096, 100, None, 4096, 1 << 20, None) == -1
+    assert lib.hf_rope_apply(c, 4096, 100, 4096, 4096, 4096 + 512, None) == -2              # partial overlap
+    assert lib.hf_rope_apply(c, 4096, 0, 4096, 4096, 1 << 20, None) == -2
+    # the split call checks the second query pointer like the first
+    assert lib.hf_hybrid_attn_fwd_split(c, 4096, 4100, 100, 8192, 8192, 200, None, 0, None, None, None, 16384,
+                                        None, 0, None) == -4
+    assert lib.hf_hybrid_attn_fwd_split(c, 4096, 16384, 100, 8192, 8192, 200, None, 0, None, None, None, 16384,
+                                        None, 0, None) == -2                                  # O aliases Q_hist

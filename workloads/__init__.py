@@ -12,5 +12,6 @@ from .configs import (  # noqa: F401
     make_qkv,
     make_evicted,
     rope_tables,
+    frame_grid,
     to_f64,
 )

@@ -124,6 +124,14 @@ def rope_tables(n_tokens: int, head_dim: int, first_position: float = 0.0,
     return cos, sin
 
 
+_FRAME_GRID = {64: (8, 8), 100: (10, 10), 200: (10, 20), 300: (15, 20), 1560: (30, 52), 3600: (45, 80)}
+
+
+def frame_grid(w: Workload):
+    """(rows, columns) of the latent token grid of one frame (832x480 -> 30 x 52 tokens)."""
+    return _FRAME_GRID[w.tokens_per_frame]
+
+
 def to_f64(t) -> np.ndarray:
     """Exact up-cast of a stored tensor (bf16/f32/int) to a float64 NumPy array on the host."""
     if t is None:
