@@ -76,6 +76,9 @@ typedef struct hf_config {
   float   eps;            /* added to the readout denominator (Eq. 3); e.g. 1e-6 */
   float   z_scale;        /* multiplies phi(q).z at readout; 1.0 = plain sum normaliser */
   float   softmax_scale;  /* 0 means 1/sqrt(head_dim) (Eq. 5) */
+  int32_t kv_capacity;    /* 0: the heads of K_win, V_win are packed, n_kv tokens apart.  > 0: they are the
+                             heads of a cache buffer [B, H, kv_capacity, d] whose first n_kv <= kv_capacity
+                             tokens are valid.  Applies to every K_win / V_win argument, to nothing else. */
 } hf_config;
 
 /* Size in bytes of the linear state: batch*heads*(d*d + d)*4.  Host-only. */
@@ -126,6 +129,45 @@ HF_API int hf_absorb_evicted(const hf_config* cfg, void* state,
 HF_API int hf_window_advance(const hf_config* cfg, void* K_win, void* V_win, int32_t n_kv, int32_t n_evict,
                       void* state, const float* rope_cos, const float* rope_sin,
                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* hf_window_advance for a cache that keeps sink frames: the first n_sink tokens of the window stay where
+ * they are, the n_evict tokens behind them are absorbed into the state, tokens [n_sink + n_evict, n_kv)
+ * move down to n_sink.  0 <= n_sink, 0 < n_evict <= n_kv - n_sink; the rest as hf_window_advance. */
+HF_API int hf_window_evict(const hf_config* cfg, void* K_win, void* V_win, int32_t n_kv, int32_t n_sink,
+                    int32_t n_evict, void* state, const float* rope_cos, const float* rope_sin,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bookkeeping of the rolling KV cache of the inference algorithm of the supplement, kept by the caller
+ * on the host; the cache buffers K_win, V_win [B, H, cfg->kv_capacity, d] are the caller's too. */
+typedef struct hf_window {
+  int32_t n_sink;     /* leading tokens that are never evicted (sink frames) */
+  int32_t n_tokens;   /* valid tokens now: sink, cached chunks and, once opened, the current chunk */
+} hf_window;
+
+/* Start of a chunk ("if KV cache is full: pop(0), update the linear state" followed by the append, done
+ * ahead of the chunk so that its own K, V have their slot during all of its denoising steps): if
+ * win->n_tokens + n_chunk exceeds cfg->kv_capacity, the overflow is evicted from behind the sink into the
+ * state (hf_window_evict; rope_*_ev are tables for exactly that many tokens or NULL, workspace as for
+ * hf_absorb_evicted).  Then the chunk's slot is reserved: *first_out = token offset at which the caller
+ * writes the chunk's K, V (before each hf_stream_step, and the clean ones after the last step),
+ * *n_evicted_out = tokens evicted (both HOST, may be NULL), and win->n_tokens grows by n_chunk.
+ * The overflow is max(0, win->n_tokens + n_chunk - cfg->kv_capacity): the caller can size the tables
+ * before the call. */
+HF_API int hf_stream_open_chunk(const hf_config* cfg, hf_window* win, int32_t n_chunk, void* K_win, void* V_win,
+                         void* state, const float* rope_cos_ev, const float* rope_sin_ev,
+                         void* workspace, size_t workspace_bytes,
+                         int32_t* first_out, int32_t* n_evicted_out, void* stream);
+
+/* One denoising step of the current chunk (the hybrid attention inside g_theta of the inference
+ * algorithm): hf_block_select_cached over the win->n_tokens valid tokens of the cache (on steps after the
+ * chunk's first, step_in_chunk > 0, the pooled keys of the whole blocks before the chunk's own n_q
+ * tokens are reused) followed by hf_hybrid_attn_fwd_split.  block_idx: scratch and output, int32
+ * [B, H, T_m, k] for this window length; workspace >= hf_workspace_bytes(cfg, n_q, win->n_tokens),
+ * the same buffer on every step of a chunk.  The other arguments as in those two calls. */
+HF_API int hf_stream_step(const hf_config* cfg, const hf_window* win, const void* Q, const void* Q_hist, int32_t n_q,
+                   const void* K_win, const void* V_win, int32_t step_in_chunk, int32_t* block_idx,
+                   const void* state_or_null, const float* rope_cos_q, const float* rope_sin_q,
+                   void* O, void* workspace, size_t workspace_bytes, void* stream);
 
 /* k of "sparse Top K" for a window of n_kv tokens (see keep_k / keep_ratio).  Host-only. */
 HF_API int hf_select_k(const hf_config* cfg, int32_t n_kv, int32_t* k_out);

@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     HF_PHI_ELU1,
     HFError,
     hf_config,
+    hf_window,
     make_config,
     load,
     lib_path,
@@ -28,4 +29,6 @@ from .binding import (  # noqa: F401
     hf_rope_window_indices,
     hf_rope_tables,
     hf_rope_apply,
+    hf_stream_open_chunk,
+    hf_stream_step,
 )

@@ -40,17 +40,22 @@ class hf_config(ctypes.Structure):
         ("eps", ctypes.c_float),
         ("z_scale", ctypes.c_float),
         ("softmax_scale", ctypes.c_float),
+        ("kv_capacity", ctypes.c_int32),
     ]
 
 
+class hf_window(ctypes.Structure):
+    _fields_ = [("n_sink", ctypes.c_int32), ("n_tokens", ctypes.c_int32)]
+
+
 def make_config(batch, heads, head_dim, dtype, block_q, block_kv, keep_ratio=1.0, keep_k=0,
-                phi=HF_PHI_RELU, eps=1e-6, z_scale=1.0, softmax_scale=0.0) -> hf_config:
+                phi=HF_PHI_RELU, eps=1e-6, z_scale=1.0, softmax_scale=0.0, kv_capacity=0) -> hf_config:
     if isinstance(dtype, str):
         dtype = {"bf16": HF_BF16, "f32": HF_F32}[dtype]
     elif isinstance(dtype, torch.dtype):
         dtype = {torch.bfloat16: HF_BF16, torch.float32: HF_F32}[dtype]
     return hf_config(batch, heads, head_dim, dtype, block_q, block_kv, keep_ratio, keep_k, phi, eps,
-                     z_scale, softmax_scale)
+                     z_scale, softmax_scale, kv_capacity)
 
 
 def lib_path() -> str:
@@ -77,6 +82,10 @@ def load():
     lib.hf_absorb_evicted.argtypes = [CP, P, P, P, I, P, P, P, SZ, P]
     lib.hf_absorb_workspace_bytes.argtypes = [CP, I, ctypes.POINTER(SZ)]
     lib.hf_window_advance.argtypes = [CP, P, P, I, I, P, P, P, P, SZ, P]
+    lib.hf_window_evict.argtypes = [CP, P, P, I, I, I, P, P, P, P, SZ, P]
+    WP = ctypes.POINTER(hf_window)
+    lib.hf_stream_open_chunk.argtypes = [CP, WP, I, P, P, P, P, P, P, SZ, ctypes.POINTER(I), ctypes.POINTER(I), P]
+    lib.hf_stream_step.argtypes = [CP, WP, P, P, I, P, P, I, P, P, P, P, P, P, SZ, P]
     lib.hf_select_k.argtypes = [CP, I, ctypes.POINTER(I)]
     lib.hf_workspace_bytes.argtypes = [CP, I, I, ctypes.POINTER(SZ)]
     lib.hf_block_select.argtypes = [CP, P, I, P, I, P, P, P, SZ, P]
@@ -89,7 +98,8 @@ def load():
     for name in ("hf_state_bytes", "hf_state_init", "hf_state_fold_linear", "hf_window_advance", "hf_absorb_evicted", "hf_absorb_workspace_bytes", "hf_select_k",
                  "hf_workspace_bytes",
                  "hf_block_select", "hf_block_select_cached", "hf_hybrid_attn_fwd", "hf_hybrid_attn_fwd_split",
-                 "hf_rope_window_indices", "hf_rope_tables", "hf_rope_apply"):
+                 "hf_rope_window_indices", "hf_rope_tables", "hf_rope_apply", "hf_window_evict", "hf_stream_open_chunk",
+                 "hf_stream_step"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -118,6 +128,19 @@ def _dev(t, name, dtype=None, shape=None):
     return t.data_ptr()
 
 
+def _kv_len(cfg: hf_config, K_win, n_kv):
+    """Valid tokens of a window tensor: its length when packed, the caller's n_kv in a cache buffer."""
+    if cfg.kv_capacity > 0:
+        if n_kv is None:
+            raise ValueError("n_kv must be given when cfg.kv_capacity is set")
+        if K_win.shape[2] != cfg.kv_capacity:
+            raise ValueError(f"K_win must hold kv_capacity={cfg.kv_capacity} tokens per head")
+        return int(n_kv)
+    if n_kv is not None and n_kv != K_win.shape[2]:
+        raise ValueError("n_kv differs from the packed window length")
+    return K_win.shape[2]
+
+
 def _tdtype(cfg: hf_config):
     return torch.bfloat16 if cfg.dtype == HF_BF16 else torch.float32
 
@@ -138,15 +161,16 @@ def hf_state_bytes(cfg: hf_config) -> int:
 
 
 def hf_window_advance(cfg: hf_config, K_win, V_win, n_evict: int, state, rope_cos=None, rope_sin=None,
-                      workspace=None) -> None:
-    """Absorb the oldest n_evict tokens of the window buffers into the state and move the rest to the front."""
+                      workspace=None, n_sink: int = 0, n_kv=None) -> None:
+    """Absorb the oldest n_evict tokens behind the first n_sink of the window buffers into the state and move
+    the rest down (hf_window_evict; n_sink = 0 is hf_window_advance)."""
     B, H, d = cfg.batch, cfg.heads, cfg.head_dim
-    n_kv = K_win.shape[2]
+    n_kv = _kv_len(cfg, K_win, n_kv)
     ns = hf_state_bytes(cfg) // 4
     tab = (int(n_evict), d // 2)
-    _check(load().hf_window_advance(
-        ctypes.byref(cfg), _dev(K_win, "K_win", _tdtype(cfg), (B, H, n_kv, d)),
-        _dev(V_win, "V_win", _tdtype(cfg), (B, H, n_kv, d)), n_kv, int(n_evict),
+    _check(load().hf_window_evict(
+        ctypes.byref(cfg), _dev(K_win, "K_win", _tdtype(cfg), (B, H, K_win.shape[2], d)),
+        _dev(V_win, "V_win", _tdtype(cfg), (B, H, K_win.shape[2], d)), n_kv, int(n_sink), int(n_evict),
         _dev(state, "state", torch.float32, (ns,)), _dev(rope_cos, "rope_cos", torch.float32, tab),
         _dev(rope_sin, "rope_sin", torch.float32, tab), _dev(workspace, "workspace", torch.uint8),
         0 if workspace is None else workspace.numel(), _stream()))
@@ -202,35 +226,35 @@ def hf_absorb_evicted(cfg: hf_config, state, K_ev, V_ev, rope_cos=None, rope_sin
         _dev(workspace, "workspace", torch.uint8), 0 if workspace is None else workspace.numel(), _stream()))
 
 
-def hf_block_select(cfg: hf_config, Q, K_win, block_idx, scores=None, workspace=None) -> None:
+def hf_block_select(cfg: hf_config, Q, K_win, block_idx, scores=None, workspace=None, n_kv=None) -> None:
     """block_idx: int32 [B,H,T_m,k] out; scores: optional fp32 [B,H,T_m,T_n] out; workspace: uint8 buffer."""
-    hf_block_select_cached(cfg, Q, K_win, 0, block_idx, scores, workspace, _entry="hf_block_select")
+    hf_block_select_cached(cfg, Q, K_win, 0, block_idx, scores, workspace, _entry="hf_block_select", n_kv=n_kv)
 
 
 def hf_block_select_cached(cfg: hf_config, Q, K_win, n_cached_kv_blocks: int, block_idx, scores=None,
-                           workspace=None, _entry="hf_block_select_cached") -> None:
+                           workspace=None, _entry="hf_block_select_cached", n_kv=None) -> None:
     """As hf_block_select; the pooled means of the first n_cached_kv_blocks KV blocks are reused from the
     previous call on the same workspace (the caller guarantees those tokens did not change)."""
     B, H, d = cfg.batch, cfg.heads, cfg.head_dim
-    n_q, n_kv = Q.shape[2], K_win.shape[2]
+    n_q, n_kv = Q.shape[2], _kv_len(cfg, K_win, n_kv)
     t_m, t_n = _cdiv(n_q, cfg.block_q), _cdiv(n_kv, cfg.block_kv)
     k = hf_select_k(cfg, n_kv)
     ws_ptr = _dev(workspace, "workspace", torch.uint8)
     extra = () if _entry == "hf_block_select" else (int(n_cached_kv_blocks),)
     _check(getattr(load(), _entry)(
         ctypes.byref(cfg), _dev(Q, "Q", _tdtype(cfg), (B, H, n_q, d)), n_q,
-        _dev(K_win, "K_win", _tdtype(cfg), (B, H, n_kv, d)), n_kv, *extra,
+        _dev(K_win, "K_win", _tdtype(cfg), (B, H, K_win.shape[2], d)), n_kv, *extra,
         _dev(block_idx, "block_idx", torch.int32, (B, H, t_m, k)),
         _dev(scores, "scores", torch.float32, (B, H, t_m, t_n)),
         ws_ptr, 0 if workspace is None else workspace.numel(), _stream()))
 
 
 def hf_hybrid_attn_fwd(cfg: hf_config, Q, K_win, V_win, block_idx, state, O, workspace=None,
-                       rope_cos_q=None, rope_sin_q=None, Q_hist=None) -> None:
+                       rope_cos_q=None, rope_sin_q=None, Q_hist=None, n_kv=None) -> None:
     """block_idx None = dense window attention; state None = no history term; Q_hist: the history branch's
     queries when they are not Q (hf_hybrid_attn_fwd_split)."""
     B, H, d = cfg.batch, cfg.heads, cfg.head_dim
-    n_q, n_kv = Q.shape[2], K_win.shape[2]
+    n_q, n_kv = Q.shape[2], _kv_len(cfg, K_win, n_kv)
     t_m = _cdiv(n_q, cfg.block_q)
     k = 0
     if block_idx is not None:
@@ -243,8 +267,8 @@ def hf_hybrid_attn_fwd(cfg: hf_config, Q, K_win, V_win, block_idx, state, O, wor
     entry = load().hf_hybrid_attn_fwd if Q_hist is None else load().hf_hybrid_attn_fwd_split
     _check(entry(
         ctypes.byref(cfg), _dev(Q, "Q", _tdtype(cfg), (B, H, n_q, d)), *split, n_q,
-        _dev(K_win, "K_win", _tdtype(cfg), (B, H, n_kv, d)),
-        _dev(V_win, "V_win", _tdtype(cfg), (B, H, n_kv, d)), n_kv,
+        _dev(K_win, "K_win", _tdtype(cfg), (B, H, K_win.shape[2], d)),
+        _dev(V_win, "V_win", _tdtype(cfg), (B, H, K_win.shape[2], d)), n_kv,
         _dev(block_idx, "block_idx", torch.int32, (B, H, t_m, k)), k,
         _dev(state, "state", torch.float32, (ns,)),
         _dev(rope_cos_q, "rope_cos_q", torch.float32, tab), _dev(rope_sin_q, "rope_sin_q", torch.float32, tab),
@@ -279,3 +303,42 @@ def hf_rope_apply(cfg: hf_config, X, rope_cos, rope_sin, Y) -> None:
         ctypes.byref(cfg), _dev(X, "X", _tdtype(cfg), (B, H, n, d)), n,
         _dev(rope_cos, "rope_cos", torch.float32, (n, d // 2)), _dev(rope_sin, "rope_sin", torch.float32, (n, d // 2)),
         _dev(Y, "Y", _tdtype(cfg), (B, H, n, d)), _stream()))
+
+
+def hf_stream_open_chunk(cfg: hf_config, win: hf_window, n_chunk: int, K_win, V_win, state, rope_cos_ev=None,
+                         rope_sin_ev=None, workspace=None):
+    """Evict what the next chunk of n_chunk tokens pushes out of the cache into the state and reserve the
+    chunk's slot; returns (token offset of the slot, tokens evicted) and updates ``win``."""
+    B, H, d = cfg.batch, cfg.heads, cfg.head_dim
+    cap = cfg.kv_capacity
+    over = max(0, win.n_tokens + int(n_chunk) - cap)
+    tab = (over, d // 2)
+    first, n_ev = ctypes.c_int32(-1), ctypes.c_int32(-1)
+    _check(load().hf_stream_open_chunk(
+        ctypes.byref(cfg), ctypes.byref(win), int(n_chunk), _dev(K_win, "K_win", _tdtype(cfg), (B, H, cap, d)),
+        _dev(V_win, "V_win", _tdtype(cfg), (B, H, cap, d)),
+        _dev(state, "state", torch.float32, (hf_state_bytes(cfg) // 4,)),
+        _dev(rope_cos_ev, "rope_cos_ev", torch.float32, tab), _dev(rope_sin_ev, "rope_sin_ev", torch.float32, tab),
+        _dev(workspace, "workspace", torch.uint8), 0 if workspace is None else workspace.numel(),
+        ctypes.byref(first), ctypes.byref(n_ev), _stream()))
+    return first.value, n_ev.value
+
+
+def hf_stream_step(cfg: hf_config, win: hf_window, Q, K_win, V_win, step_in_chunk: int, block_idx, state, O,
+                   workspace, rope_cos_q=None, rope_sin_q=None, Q_hist=None) -> None:
+    """Selection (pooled keys of the unchanged blocks reused after the chunk's first step) and hybrid attention
+    over the valid tokens of the cache."""
+    B, H, d = cfg.batch, cfg.heads, cfg.head_dim
+    cap, n_q = cfg.kv_capacity, Q.shape[2]
+    t_m = _cdiv(n_q, cfg.block_q)
+    k = hf_select_k(cfg, win.n_tokens)
+    tab = (n_q, d // 2)
+    _check(load().hf_stream_step(
+        ctypes.byref(cfg), ctypes.byref(win), _dev(Q, "Q", _tdtype(cfg), (B, H, n_q, d)),
+        _dev(Q_hist, "Q_hist", _tdtype(cfg), (B, H, n_q, d)), n_q,
+        _dev(K_win, "K_win", _tdtype(cfg), (B, H, cap, d)), _dev(V_win, "V_win", _tdtype(cfg), (B, H, cap, d)),
+        int(step_in_chunk), _dev(block_idx, "block_idx", torch.int32, (B, H, t_m, k)),
+        _dev(state, "state", torch.float32, (hf_state_bytes(cfg) // 4,)),
+        _dev(rope_cos_q, "rope_cos_q", torch.float32, tab), _dev(rope_sin_q, "rope_sin_q", torch.float32, tab),
+        _dev(O, "O", _tdtype(cfg), (B, H, n_q, d)), _dev(workspace, "workspace", torch.uint8),
+        0 if workspace is None else workspace.numel(), _stream()))

@@ -37,6 +37,7 @@ static int check_cfg(const hf_config* c) {
   if (c->block_q < 1 || c->block_kv < 1) { set_error("block sizes must be >= 1"); return HF_ERR_SHAPE; }
   if (c->block_q > 1024 || c->block_kv > 1024) { set_error("block sizes must be <= 1024"); return HF_ERR_SHAPE; }
   if (c->keep_k < 0) { set_error("keep_k must be >= 0"); return HF_ERR_SHAPE; }
+  if (c->kv_capacity < 0 || c->kv_capacity > (1 << 24)) { set_error("kv_capacity must be in [0, 2^24]"); return HF_ERR_SHAPE; }
   if (c->keep_k == 0 && !(c->keep_ratio > 0.0f && c->keep_ratio <= 1.0f)) {
     set_error("keep_ratio must be in (0, 1]"); return HF_ERR_SHAPE;
   }
@@ -59,6 +60,14 @@ static int check_ptr(const void* p, const char* name, bool required) {
 static int check_tokens(int32_t n, const char* name) {
   // 2^24 tokens keeps every element offset within one head below 2^31
   if (n < 1 || n > (1 << 24)) { set_error("%s must be in [1, 2^24], got %d", name, n); return HF_ERR_SHAPE; }
+  return HF_OK;
+}
+
+static int check_window_len(const hf_config* c, int32_t n_kv) {
+  if (c->kv_capacity > 0 && n_kv > c->kv_capacity) {
+    set_error("n_kv=%d exceeds kv_capacity=%d", n_kv, c->kv_capacity);
+    return HF_ERR_SHAPE;
+  }
   return HF_OK;
 }
 
@@ -166,13 +175,25 @@ int hf_absorb_evicted(const hf_config* cfg, void* state, const void* K_ev, const
 int hf_window_advance(const hf_config* cfg, void* K_win, void* V_win, int32_t n_kv, int32_t n_evict, void* state,
                       const float* rope_cos, const float* rope_sin, void* workspace, size_t workspace_bytes,
                       void* stream) {
+  return hf_window_evict(cfg, K_win, V_win, n_kv, 0, n_evict, state, rope_cos, rope_sin, workspace, workspace_bytes,
+                         stream);
+}
+
+int hf_window_evict(const hf_config* cfg, void* K_win, void* V_win, int32_t n_kv, int32_t n_sink, int32_t n_evict,
+                    void* state, const float* rope_cos, const float* rope_sin, void* workspace,
+                    size_t workspace_bytes, void* stream) {
   HF_TRY(check_cfg(cfg));
   HF_TRY(check_ptr(K_win, "K_win", true));
   HF_TRY(check_ptr(V_win, "V_win", true));
   HF_TRY(check_ptr(state, "state", true));
   HF_TRY(check_tokens(n_kv, "n_kv"));
   HF_TRY(check_tokens(n_evict, "n_evict"));
-  if (n_evict > n_kv) { set_error("n_evict=%d exceeds the %d tokens of the window", n_evict, n_kv); return HF_ERR_SHAPE; }
+  HF_TRY(check_window_len(cfg, n_kv));
+  if (n_sink < 0 || n_sink > n_kv) { set_error("n_sink=%d outside [0, n_kv]", n_sink); return HF_ERR_SHAPE; }
+  if (n_evict > n_kv - n_sink) {
+    set_error("n_evict=%d exceeds the %d tokens of the window behind its %d sink tokens", n_evict, n_kv - n_sink, n_sink);
+    return HF_ERR_SHAPE;
+  }
   if ((rope_cos == nullptr) != (rope_sin == nullptr)) {
     set_error("rope_cos and rope_sin must both be given or both be NULL");
     return HF_ERR_NULL;
@@ -184,12 +205,14 @@ int hf_window_advance(const hf_config* cfg, void* K_win, void* V_win, int32_t n_
     return HF_ERR_ALIGN;
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
-  // the oldest n_evict tokens of every head (heads are n_kv tokens apart) go into the state ...
-  HF_TRY(launch_absorb(*cfg, static_cast<float*>(state), K_win, V_win, n_evict, n_kv, rope_cos, rope_sin, workspace,
-                       workspace ? workspace_bytes : 0, s));
-  // ... and the rest of the window moves to the front
-  if (n_evict == n_kv) return HF_OK;
-  return launch_window_shift(*cfg, K_win, V_win, n_kv, n_evict, s);
+  // the oldest n_evict tokens behind the sink of every head go into the state ...
+  const size_t skip = (size_t)n_sink * cfg->head_dim * esize(cfg);
+  HF_TRY(launch_absorb(*cfg, static_cast<float*>(state), static_cast<char*>(K_win) + skip,
+                       static_cast<char*>(V_win) + skip, n_evict, kv_stride_of(*cfg, n_kv), rope_cos, rope_sin,
+                       workspace, workspace ? workspace_bytes : 0, s));
+  // ... and the rest of the window moves down to the sink
+  if (n_sink + n_evict == n_kv) return HF_OK;
+  return launch_window_shift(*cfg, K_win, V_win, n_kv, n_sink, n_evict, s);
 }
 
 int hf_select_k(const hf_config* cfg, int32_t n_kv, int32_t* k_out) {
@@ -229,6 +252,7 @@ int hf_block_select_cached(const hf_config* cfg, const void* Q, int32_t n_q, con
   HF_TRY(check_ptr(scores_or_null, "scores", false));
   HF_TRY(check_tokens(n_q, "n_q"));
   HF_TRY(check_tokens(n_kv, "n_kv"));
+  HF_TRY(check_window_len(cfg, n_kv));
   const int t_m = cdiv(n_q, cfg->block_q), t_n = cdiv(n_kv, cfg->block_kv);
   if (t_n > kMaxSelectBlocks) {
     set_error("window has %d KV blocks; the selection kernel ranks at most %d", t_n, kMaxSelectBlocks);
@@ -279,6 +303,7 @@ int hf_hybrid_attn_fwd_split(const hf_config* cfg, const void* Q, const void* Q_
   HF_TRY(check_ptr(state_or_null, "state", false));
   HF_TRY(check_tokens(n_q, "n_q"));
   HF_TRY(check_tokens(n_kv, "n_kv"));
+  HF_TRY(check_window_len(cfg, n_kv));
   if (O == Q || O == Q_hist || O == K_win || O == V_win) { set_error("O must not alias an input"); return HF_ERR_SHAPE; }
   if ((rope_cos_q == nullptr) != (rope_sin_q == nullptr)) {
     set_error("rope_cos_q and rope_sin_q must both be given or both be NULL");
@@ -317,6 +342,55 @@ int hf_hybrid_attn_fwd_split(const hf_config* cfg, const void* Q, const void* Q_
   HF_TRY(launch_attn(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, o_local, s));
   return launch_readout(*cfg, Q_hist, n_q, o_local, static_cast<const float*>(state_or_null), rope_cos_q,
                         rope_sin_q, static_cast<char*>(workspace) + w.planes, O, s);
+}
+
+int hf_stream_open_chunk(const hf_config* cfg, hf_window* win, int32_t n_chunk, void* K_win, void* V_win,
+                         void* state, const float* rope_cos_ev, const float* rope_sin_ev, void* workspace,
+                         size_t workspace_bytes, int32_t* first_out, int32_t* n_evicted_out, void* stream) {
+  HF_TRY(check_cfg(cfg));
+  if (!win) { set_error("win is NULL"); return HF_ERR_NULL; }
+  if (cfg->kv_capacity < 1) { set_error("a stream needs cfg->kv_capacity"); return HF_ERR_SHAPE; }
+  if (win->n_sink < 0 || win->n_tokens < win->n_sink || win->n_tokens > cfg->kv_capacity) {
+    set_error("window bookkeeping out of range: n_sink=%d n_tokens=%d capacity=%d", win->n_sink, win->n_tokens,
+              cfg->kv_capacity);
+    return HF_ERR_SHAPE;
+  }
+  HF_TRY(check_tokens(n_chunk, "n_chunk"));
+  if (n_chunk > cfg->kv_capacity - win->n_sink) {
+    set_error("a chunk of %d tokens does not fit behind %d sink tokens in %d", n_chunk, win->n_sink, cfg->kv_capacity);
+    return HF_ERR_SHAPE;
+  }
+  const int32_t over = win->n_tokens + n_chunk - cfg->kv_capacity;
+  if (over > 0) {
+    // "KV cache is full": pop the oldest tokens behind the sink and update the linear state with them
+    HF_TRY(hf_window_evict(cfg, K_win, V_win, win->n_tokens, win->n_sink, over, state, rope_cos_ev, rope_sin_ev,
+                           workspace, workspace_bytes, stream));
+    win->n_tokens -= over;
+  }
+  if (first_out) *first_out = win->n_tokens;
+  if (n_evicted_out) *n_evicted_out = over > 0 ? over : 0;
+  win->n_tokens += n_chunk;
+  return HF_OK;
+}
+
+int hf_stream_step(const hf_config* cfg, const hf_window* win, const void* Q, const void* Q_hist, int32_t n_q,
+                   const void* K_win, const void* V_win, int32_t step_in_chunk, int32_t* block_idx,
+                   const void* state_or_null, const float* rope_cos_q, const float* rope_sin_q, void* O,
+                   void* workspace, size_t workspace_bytes, void* stream) {
+  HF_TRY(check_cfg(cfg));
+  if (!win) { set_error("win is NULL"); return HF_ERR_NULL; }
+  if (win->n_tokens < n_q || n_q < 1) {
+    set_error("the window holds %d tokens, fewer than the chunk's %d", win->n_tokens, n_q);
+    return HF_ERR_SHAPE;
+  }
+  if (step_in_chunk < 0) { set_error("step_in_chunk must be >= 0"); return HF_ERR_SHAPE; }
+  const int32_t n_kv = win->n_tokens;
+  // the chunk's own keys are the last n_q tokens; whole blocks before them are as the chunk's first step left them
+  const int32_t reuse = step_in_chunk > 0 ? (n_kv - n_q) / cfg->block_kv : 0;
+  HF_TRY(hf_block_select_cached(cfg, Q, n_q, K_win, n_kv, reuse, block_idx, nullptr, workspace, workspace_bytes,
+                                stream));
+  return hf_hybrid_attn_fwd_split(cfg, Q, Q_hist, n_q, K_win, V_win, n_kv, block_idx, select_k_of(cfg, cdiv(n_kv, cfg->block_kv)),
+                                  state_or_null, rope_cos_q, rope_sin_q, O, workspace, workspace_bytes, stream);
 }
 
 int hf_rope_window_indices(int32_t i_newest, int32_t n_frames, int32_t t0, int32_t* idx_out) {

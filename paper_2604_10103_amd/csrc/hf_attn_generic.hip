@@ -18,16 +18,16 @@ template <typename T, int D, int R>
 __global__ __launch_bounds__(256) void attn_generic_kernel(const T* __restrict__ Q, const T* __restrict__ K,
                                                            const T* __restrict__ V,
                                                            const int32_t* __restrict__ idx, int k, int n_q,
-                                                           int n_kv, int bq, int bkv, int t_m, int t_n,
-                                                           float scale_log2e, T* __restrict__ O) {
+                                                           int n_kv, int kv_stride, int bq, int bkv, int t_m,
+                                                           int t_n, float scale_log2e, T* __restrict__ O) {
   constexpr int E = Elem<T>::kPer16B;
   constexpr int C = D / kWave;  // value features per lane
   __shared__ float sq[4][R][D];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int qb = blockIdx.x, bh = blockIdx.y;
   const T* Qh = Q + (size_t)bh * n_q * D;
-  const T* Kh = K + (size_t)bh * n_kv * D;
-  const T* Vh = V + (size_t)bh * n_kv * D;
+  const T* Kh = K + (size_t)bh * kv_stride * D;  // heads of a cache buffer are kv_stride tokens apart
+  const T* Vh = V + (size_t)bh * kv_stride * D;
   T* Oh = O + (size_t)bh * n_q * D;
   const int32_t* row_idx = idx ? idx + ((size_t)bh * t_m + qb) * k : nullptr;
   const int nsel = idx ? k : t_n;
@@ -125,7 +125,7 @@ int launch_attn_generic(const hf_config& c, const void* Q, int n_q, const void* 
   const dim3 grid(t_m, BH), block(256);
 #define HF_LAUNCH_GENERIC(T, DD)                                                                           \
   hipLaunchKernelGGL((attn_generic_kernel<T, DD, 4>), grid, block, 0, s, static_cast<const T*>(Q),         \
-                     static_cast<const T*>(K), static_cast<const T*>(V), idx, k, n_q, n_kv, c.block_q,     \
+                     static_cast<const T*>(K), static_cast<const T*>(V), idx, k, n_q, n_kv, kv_stride_of(c, n_kv), c.block_q, \
                      c.block_kv, t_m, t_n, sl2, static_cast<T*>(O_local))
   if (c.dtype == HF_F32) {
     if (c.head_dim == 128) HF_LAUNCH_GENERIC(float, 128); else HF_LAUNCH_GENERIC(float, 64);

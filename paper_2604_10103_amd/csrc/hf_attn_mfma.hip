@@ -73,8 +73,8 @@ struct HistArgs {
 template <int NW, int kFused>
 __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
-    const int32_t* __restrict__ idx, int k, int n_q, int n_kv, int bkv, int t_m, int t_n, int items_per_xcd,
-    int total_items, float c_scale, HistArgs hist, bf16_t* __restrict__ O) {
+    const int32_t* __restrict__ idx, int k, int n_q, int n_kv, int kv_stride, int bkv, int t_m, int t_n,
+    int items_per_xcd, int total_items, float c_scale, HistArgs hist, bf16_t* __restrict__ O) {
   constexpr int NT = 64 * NW;
   constexpr int BQ = 32 * NW;
   constexpr int CPT = (TK * D * 2 / 16) / NT;  // 16-byte chunks of a K tile per thread (4 or 2)
@@ -94,8 +94,8 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, h = lane >> 5;
   const bf16_t* Qh = Q + (size_t)bh * n_q * D;
-  const bf16_t* Kh = K + (size_t)bh * n_kv * D;
-  const bf16_t* Vh = V + (size_t)bh * n_kv * D;
+  const bf16_t* Kh = K + (size_t)bh * kv_stride * D;  // heads of a cache buffer are kv_stride tokens apart
+  const bf16_t* Vh = V + (size_t)bh * kv_stride * D;
   bf16_t* Oh = O + (size_t)bh * n_q * D;
   const int32_t* row_idx = idx ? idx + ((size_t)bh * t_m + qb) * k : nullptr;
   const int nsel = idx ? k : t_n;
@@ -466,7 +466,7 @@ static int launch_attn_mfma_impl(const hf_config& c, const void* Q, int n_q, con
   const HistArgs h = hist ? *hist : HistArgs{nullptr, nullptr, 0.0f, 0.0f, 0, 0, nullptr, nullptr, nullptr};
 #define HF_LAUNCH_ATTN(NWV, FUSED)                                                                              \
   hipLaunchKernelGGL((attn_mfma_kernel<NWV, FUSED>), grid, dim3(64 * NWV), 0, s, q, kk, v, idx, k, n_q, n_kv,   \
-                     c.block_kv, t_m, t_n, per_xcd, (int)total, c_scale, h, o)
+                     kv_stride_of(c, n_kv), c.block_kv, t_m, t_n, per_xcd, (int)total, c_scale, h, o)
   const int fused = !hist ? 0 : ((h.phi_kind == HF_PHI_RELU && h.cosq == nullptr && h.q_hist == nullptr) ? 1 : 2);
   if (c.block_q == 64) {
     if (fused == 0) HF_LAUNCH_ATTN(2, 0); else if (fused == 1) HF_LAUNCH_ATTN(2, 1); else HF_LAUNCH_ATTN(2, 2);

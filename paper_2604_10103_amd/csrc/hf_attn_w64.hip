@@ -45,7 +45,7 @@ struct Cursor {  // position in the list of 32-key tiles of this query block
 template <bool kDense>
 __global__ __launch_bounds__(64, 1) void attn_w64_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
-    const int32_t* __restrict__ idx, int k, int n_q, int n_kv, int bq, int bkv, int t_m, int t_n,
+    const int32_t* __restrict__ idx, int k, int n_q, int n_kv, int kv_stride, int bq, int bkv, int t_m, int t_n,
     int items_per_xcd, int total_items, float c_scale, bf16_t* __restrict__ O) {
   __shared__ __attribute__((aligned(16))) char sK[TK * KSTR];
   __shared__ __attribute__((aligned(16))) uint32_t sVt[D * VSTRD];
@@ -60,8 +60,8 @@ __global__ __launch_bounds__(64, 1) void attn_w64_kernel(
 
   const int lane = threadIdx.x, l32 = lane & 31, h = lane >> 5;
   const bf16_t* Qh = Q + (size_t)bh * n_q * D;
-  const bf16_t* Kh = K + (size_t)bh * n_kv * D;
-  const bf16_t* Vh = V + (size_t)bh * n_kv * D;
+  const bf16_t* Kh = K + (size_t)bh * kv_stride * D;
+  const bf16_t* Vh = V + (size_t)bh * kv_stride * D;
   bf16_t* Oh = O + (size_t)bh * n_q * D;
   const int32_t* row_idx = kDense ? nullptr : idx + ((size_t)bh * t_m + qb) * k;
   const int nsel = kDense ? t_n : k;
@@ -335,10 +335,10 @@ int launch_attn_w64(const hf_config& c, const void* Q, int n_q, const void* K, c
   const bf16_t* v = static_cast<const bf16_t*>(V);
   bf16_t* o = static_cast<bf16_t*>(O_local);
   if (idx)
-    hipLaunchKernelGGL((attn_w64_kernel<false>), grid, block, 0, s, q, kk, v, idx, k, n_q, n_kv, c.block_q,
+    hipLaunchKernelGGL((attn_w64_kernel<false>), grid, block, 0, s, q, kk, v, idx, k, n_q, n_kv, kv_stride_of(c, n_kv), c.block_q,
                        c.block_kv, t_m, t_n, per_xcd, (int)total, c_scale, o);
   else
-    hipLaunchKernelGGL((attn_w64_kernel<true>), grid, block, 0, s, q, kk, v, idx, k, n_q, n_kv, c.block_q,
+    hipLaunchKernelGGL((attn_w64_kernel<true>), grid, block, 0, s, q, kk, v, idx, k, n_q, n_kv, kv_stride_of(c, n_kv), c.block_q,
                        c.block_kv, t_m, t_n, per_xcd, (int)total, c_scale, o);
   return check_launch("hf_hybrid_attn_fwd(attention)");
 }

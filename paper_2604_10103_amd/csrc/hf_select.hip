@@ -19,8 +19,8 @@ namespace {
 // Pooled queries stay row-major, qbar[bh][t_m][D].
 template <typename T, int D>
 __global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ Q, int n_q, int bq, int t_m,
-                                                   const T* __restrict__ K, int n_kv, int bkv, int t_n,
-                                                   int kv_first, float* __restrict__ qbar,
+                                                   const T* __restrict__ K, int n_kv, int kv_stride, int bkv,
+                                                   int t_n, int kv_first, float* __restrict__ qbar,
                                                    float* __restrict__ kbar_t) {
   constexpr int E = Elem<T>::kPer16B;  // elements per 16-byte load
   constexpr int LPR = D / E;           // lanes covering one row
@@ -35,7 +35,7 @@ __global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ Q, int 
   const int n = is_q ? n_q : n_kv, b = is_q ? bq : bkv;
   const int r0 = blk * b, r1 = min(n, r0 + b);
   const int sub = lane / LPR, col = (lane % LPR) * E;
-  const T* base = X + (size_t)bh * n * D + col;
+  const T* base = X + (size_t)bh * (is_q ? n_q : kv_stride) * D + col;
   float acc[E];
 #pragma unroll
   for (int e = 0; e < E; ++e) acc[e] = 0.0f;
@@ -326,7 +326,7 @@ int launch_pool_both(const hf_config& c, const void* Q, int n_q, int t_m, const 
   const dim3 grid((t_m + t_n - kv_first + 3) / 4, BH), block(256);
 #define HF_LAUNCH_POOL(T, DD)                                                                                  \
   hipLaunchKernelGGL((pool_kernel<T, DD>), grid, block, 0, s, static_cast<const T*>(Q), n_q, c.block_q, t_m,   \
-                     static_cast<const T*>(K), n_kv, c.block_kv, t_n, kv_first, qbar, kbar_t)
+                     static_cast<const T*>(K), n_kv, kv_stride_of(c, n_kv), c.block_kv, t_n, kv_first, qbar, kbar_t)
   if (c.dtype == HF_BF16) {
     if (c.head_dim == 128) HF_LAUNCH_POOL(bf16_t, 128); else HF_LAUNCH_POOL(bf16_t, 64);
   } else {

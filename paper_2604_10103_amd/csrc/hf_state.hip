@@ -198,10 +198,10 @@ __global__ __launch_bounds__(256) void window_shift_kernel(uint4* __restrict__ K
     X[dst16 + i] = X[src16 + i];
 }
 
-int launch_window_shift(const hf_config& c, void* K, void* V, int n_kv, int n_evict, hipStream_t s) {
+int launch_window_shift(const hf_config& c, void* K, void* V, int n_kv, int first, int n_evict, hipStream_t s) {
   const int BH = c.batch * c.heads;
   const size_t row16 = (size_t)c.head_dim * (c.dtype == HF_BF16 ? 2 : 4) / 16;  // 16-byte pieces per token
-  const int keep = n_kv - n_evict;
+  const int keep = n_kv - first - n_evict;  // tokens behind the evicted run move down to `first`
   // pieces of at most n_evict tokens: source [t + n_evict, ...) and destination [t, ...) never overlap
   for (int t = 0; t < keep; t += n_evict) {
     const int len = min(n_evict, keep - t);
@@ -209,8 +209,8 @@ int launch_window_shift(const hf_config& c, void* K, void* V, int n_kv, int n_ev
     unsigned blocks = (unsigned)((len16 + 255) / 256);
     if (blocks > 1024) blocks = 1024;
     hipLaunchKernelGGL(window_shift_kernel, dim3(blocks, BH, 2), dim3(256), 0, s, static_cast<uint4*>(K),
-                       static_cast<uint4*>(V), (size_t)n_kv * row16, (size_t)(t + n_evict) * row16,
-                       (size_t)t * row16, len16);
+                       static_cast<uint4*>(V), (size_t)kv_stride_of(c, n_kv) * row16,
+                       (size_t)(first + t + n_evict) * row16, (size_t)(first + t) * row16, len16);
     const int rc = check_launch("hf_window_advance(shift)");
     if (rc != HF_OK) return rc;
   }

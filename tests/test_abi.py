@@ -35,8 +35,10 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_config_struct_layout():
-    assert ctypes.sizeof(hf.hf_config) == 12 * 4
+    assert ctypes.sizeof(hf.hf_config) == 13 * 4
     assert hf.hf_config.keep_ratio.offset == 24 and hf.hf_config.softmax_scale.offset == 44
+    assert hf.hf_config.kv_capacity.offset == 48
+    assert ctypes.sizeof(hf.hf_window) == 8 and hf.hf_window.n_tokens.offset == 4
 
 
 def test_version_and_state_bytes(lib):
@@ -153,3 +155,38 @@ def test_rope_calls_reject_bad_arguments(lib):
                                         None, 0, None) == -4
     assert lib.hf_hybrid_attn_fwd_split(c, 4096, 16384, 100, 8192, 8192, 200, None, 0, None, None, None, 16384,
                                         None, 0, None) == -2                                  # O aliases Q_hist
+
+
+def test_cache_capacity_and_stream_bookkeeping_are_checked(lib):
+    cfg = hf.make_config(1, 2, 128, "bf16", 64, 64, 0.25, kv_capacity=300)
+    c = ctypes.byref(cfg)
+    # a window longer than the cache buffer
+    assert lib.hf_block_select(c, 4096, 100, 4096, 301, 4096, None, 4096, 1 << 30, None) == -2
+    assert b"kv_capacity" in lib.hf_last_error()
+    assert lib.hf_hybrid_attn_fwd(c, 4096, 100, 8192, 8192, 301, None, 0, None, None, None, 16384, None, 0, None) == -2
+    assert lib.hf_window_evict(c, 4096, 8192, 301, 0, 100, 1 << 20, None, None, None, 0, None) == -2
+    # eviction must stay behind the sink
+    assert lib.hf_window_evict(c, 4096, 8192, 300, 250, 100, 1 << 20, None, None, None, 0, None) == -2
+    assert lib.hf_window_evict(c, 4096, 8192, 300, -1, 100, 1 << 20, None, None, None, 0, None) == -2
+    # stream calls: bookkeeping out of range, chunk larger than the room behind the sink, no capacity at all
+    win = hf.hf_window(100, 50)
+    first = ctypes.c_int32(0)
+    assert lib.hf_stream_open_chunk(c, ctypes.byref(win), 100, 4096, 8192, 1 << 20, None, None, None, 0,
+                                    ctypes.byref(first), None, None) == -2
+    win = hf.hf_window(100, 100)
+    assert lib.hf_stream_open_chunk(c, ctypes.byref(win), 201, 4096, 8192, 1 << 20, None, None, None, 0,
+                                    ctypes.byref(first), None, None) == -2
+    assert lib.hf_stream_open_chunk(c, None, 100, 4096, 8192, 1 << 20, None, None, None, 0, None, None, None) == -1
+    packed = hf.make_config(1, 2, 128, "bf16", 64, 64, 0.25)
+    assert lib.hf_stream_open_chunk(ctypes.byref(packed), ctypes.byref(win), 100, 4096, 8192, 1 << 20, None, None,
+                                    None, 0, None, None, None) == -2
+    # a chunk that fits without eviction launches nothing: pure bookkeeping on the host
+    win = hf.hf_window(100, 100)
+    n_ev = ctypes.c_int32(-1)
+    assert lib.hf_stream_open_chunk(c, ctypes.byref(win), 150, 4096, 8192, 1 << 20, None, None, None, 0,
+                                    ctypes.byref(first), ctypes.byref(n_ev), None) == 0
+    assert (first.value, n_ev.value, win.n_tokens) == (100, 0, 250)
+    # a step on a window shorter than the chunk
+    win = hf.hf_window(0, 50)
+    assert lib.hf_stream_step(c, ctypes.byref(win), 4096, None, 100, 8192, 8192, 0, 4096, None, None, None, 16384,
+                              4096, 1 << 30, None) == -2
