@@ -27,3 +27,9 @@ from .rope import (  # noqa: F401
     axis_frequencies,
     rope_tables_3d,
 )
+from .backward import (  # noqa: F401
+    phi_prime,
+    sparse_attention_bwd,
+    history_readout_bwd,
+    hybrid_attention_bwd,
+)
