@@ -231,6 +231,36 @@ HF_API int hf_hybrid_attn_fwd_split(const hf_config* cfg, const void* Q_local, c
                        const float* rope_cos_q, const float* rope_sin_q,
                        void* O, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- Backward pass (training algorithm of the supplement) ------------------------------------------- */
+
+/* Bytes of scratch hf_hybrid_attn_bwd needs for these sizes.  Host-only. */
+HF_API int hf_bwd_workspace_bytes(const hf_config* cfg, int32_t n_q, int32_t n_kv, size_t* bytes_out);
+
+/* Gradients of O = O_local + O_hist (Eq. 5, 3, 6) for the step of the training algorithm that runs with
+ * gradients enabled.  That algorithm builds the KV cache and the linear state with gradients disabled, so
+ * the state, the index lists of the Top-K mask and the rotation tables are constants here; the
+ * differentiable inputs are the queries and the window's keys and values.  Needs only the forward call's
+ * inputs and dO: the row statistics of the softmax are recomputed.
+ *   Q, Q_hist, K_win, V_win, block_idx, k, state_or_null, rope_cos_q / rope_sin_q: exactly what the forward
+ *        call (hf_hybrid_attn_fwd_split) was given; Q_hist == Q or NULL means one tensor fed both branches
+ *   dO       [B, H, n_q, d] of cfg->dtype, gradient of the loss with respect to O        read-only
+ *   dQ       out [B, H, n_q, d]: gradient with respect to Q (the softmax branch, plus the history branch
+ *            when one tensor fed both)
+ *   dQ_hist  out [B, H, n_q, d]: gradient with respect to Q_hist; required when Q_hist is a tensor of its
+ *            own, must be NULL otherwise.  With state_or_null == NULL it is filled with zeros.
+ *   dK, dV   out, laid out like K_win, V_win (heads kv_capacity tokens apart if cfg->kv_capacity is set;
+ *            only the first n_kv tokens of a head are written): gradients with respect to every key and
+ *            value of the window; keys of blocks that no query block selected get zeros.
+ *   workspace >= hf_bwd_workspace_bytes(...) bytes, 256-byte aligned.
+ * fp32 arithmetic on the recomputed probabilities, one rounding to cfg->dtype per output element.
+ * Outputs must not alias inputs or each other. */
+HF_API int hf_hybrid_attn_bwd(const hf_config* cfg, const void* Q, const void* Q_hist, int32_t n_q,
+                       const void* K_win, const void* V_win, int32_t n_kv,
+                       const int32_t* block_idx, int32_t k, const void* state_or_null,
+                       const float* rope_cos_q, const float* rope_sin_q, const void* dO,
+                       void* dQ, void* dQ_hist, void* dK, void* dV,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- Relative RoPE (Sec. 3.3) ------------------------------------------------------------------ */
 #define HF_ROPE_MAX_FRAMES 64    /* frames one hf_rope_tables call covers */
 #define HF_ROPE_MAX_PAIRS 128    /* feature pairs (head_dim / 2) of a table row */

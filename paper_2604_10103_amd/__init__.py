@@ -31,4 +31,6 @@ from .binding import (  # noqa: F401
     hf_rope_apply,
     hf_stream_open_chunk,
     hf_stream_step,
+    hf_bwd_workspace_bytes,
+    hf_hybrid_attn_bwd,
 )

@@ -92,6 +92,8 @@ def load():
     lib.hf_block_select_cached.argtypes = [CP, P, I, P, I, I, P, P, P, SZ, P]
     lib.hf_hybrid_attn_fwd.argtypes = [CP, P, I, P, P, I, P, I, P, P, P, P, P, SZ, P]
     lib.hf_hybrid_attn_fwd_split.argtypes = [CP, P, P, I, P, P, I, P, I, P, P, P, P, P, SZ, P]
+    lib.hf_bwd_workspace_bytes.argtypes = [CP, I, I, ctypes.POINTER(SZ)]
+    lib.hf_hybrid_attn_bwd.argtypes = [CP, P, P, I, P, P, I, P, I, P, P, P, P, P, P, P, P, P, SZ, P]
     lib.hf_rope_window_indices.argtypes = [I, I, I, ctypes.POINTER(I)]
     lib.hf_rope_tables.argtypes = [ctypes.POINTER(I), I, I, I, I, I, I, ctypes.c_double, I, P, P, P]
     lib.hf_rope_apply.argtypes = [CP, P, I, P, P, P, P]
@@ -99,7 +101,7 @@ def load():
                  "hf_workspace_bytes",
                  "hf_block_select", "hf_block_select_cached", "hf_hybrid_attn_fwd", "hf_hybrid_attn_fwd_split",
                  "hf_rope_window_indices", "hf_rope_tables", "hf_rope_apply", "hf_window_evict", "hf_stream_open_chunk",
-                 "hf_stream_step"):
+                 "hf_stream_step", "hf_bwd_workspace_bytes", "hf_hybrid_attn_bwd"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -342,3 +344,32 @@ def hf_stream_step(cfg: hf_config, win: hf_window, Q, K_win, V_win, step_in_chun
         _dev(rope_cos_q, "rope_cos_q", torch.float32, tab), _dev(rope_sin_q, "rope_sin_q", torch.float32, tab),
         _dev(O, "O", _tdtype(cfg), (B, H, n_q, d)), _dev(workspace, "workspace", torch.uint8),
         0 if workspace is None else workspace.numel(), _stream()))
+
+
+def hf_bwd_workspace_bytes(cfg: hf_config, n_q: int, n_kv: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().hf_bwd_workspace_bytes(ctypes.byref(cfg), n_q, n_kv, ctypes.byref(out)))
+    return out.value
+
+
+def hf_hybrid_attn_bwd(cfg: hf_config, Q, K_win, V_win, block_idx, state, dO, dQ, dK, dV, workspace,
+                       rope_cos_q=None, rope_sin_q=None, Q_hist=None, dQ_hist=None, n_kv=None) -> None:
+    """Gradients of hf_hybrid_attn_fwd's output with respect to Q (and Q_hist), K_win, V_win for a fixed mask
+    and a constant state.  dK, dV are laid out like K_win, V_win."""
+    B, H, d = cfg.batch, cfg.heads, cfg.head_dim
+    n_q, n_kv = Q.shape[2], _kv_len(cfg, K_win, n_kv)
+    t_m = _cdiv(n_q, cfg.block_q)
+    k = 0
+    if block_idx is not None:
+        k = block_idx.shape[3]
+    tab = (n_q, d // 2)
+    qs, ks = (B, H, n_q, d), (B, H, K_win.shape[2], d)
+    _check(load().hf_hybrid_attn_bwd(
+        ctypes.byref(cfg), _dev(Q, "Q", _tdtype(cfg), qs), _dev(Q_hist, "Q_hist", _tdtype(cfg), qs), n_q,
+        _dev(K_win, "K_win", _tdtype(cfg), ks), _dev(V_win, "V_win", _tdtype(cfg), ks), n_kv,
+        _dev(block_idx, "block_idx", torch.int32, (B, H, t_m, k)), k,
+        _dev(state, "state", torch.float32, (hf_state_bytes(cfg) // 4,)),
+        _dev(rope_cos_q, "rope_cos_q", torch.float32, tab), _dev(rope_sin_q, "rope_sin_q", torch.float32, tab),
+        _dev(dO, "dO", _tdtype(cfg), qs), _dev(dQ, "dQ", _tdtype(cfg), qs), _dev(dQ_hist, "dQ_hist", _tdtype(cfg), qs),
+        _dev(dK, "dK", _tdtype(cfg), ks), _dev(dV, "dV", _tdtype(cfg), ks),
+        _dev(workspace, "workspace", torch.uint8), 0 if workspace is None else workspace.numel(), _stream()))

@@ -29,6 +29,7 @@ SOURCES = [
     "hf_readout.hip",
     "hf_readout_mfma.hip",
     "hf_rope.hip",
+    "hf_bwd.hip",
 ]
 
 FLAGS = [

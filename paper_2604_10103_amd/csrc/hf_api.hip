@@ -100,6 +100,23 @@ static WorkspaceLayout workspace_layout(const hf_config* c, int n_q, int n_kv) {
   return w;
 }
 
+struct BwdLayout {
+  size_t lse2, dvec, dqh32, inv_cnt, inv_list, total;  // byte offsets
+};
+
+static BwdLayout bwd_layout(const hf_config* c, int n_q, int n_kv) {
+  const size_t bh = (size_t)c->batch * c->heads, d = c->head_dim;
+  const size_t t_m = cdiv(n_q, c->block_q), t_n = cdiv(n_kv, c->block_kv);
+  BwdLayout w;
+  w.lse2 = 0;
+  w.dvec = align256(bh * n_q * 4);
+  w.dqh32 = w.dvec + align256(bh * n_q * 4);
+  w.inv_cnt = w.dqh32 + align256(bh * (size_t)n_q * d * 4);
+  w.inv_list = w.inv_cnt + align256(bh * t_n * 4);
+  w.total = w.inv_list + align256(bh * t_n * t_m * 4);
+  return w;
+}
+
 }  // namespace hf
 
 using namespace hf;
@@ -391,6 +408,95 @@ int hf_stream_step(const hf_config* cfg, const hf_window* win, const void* Q, co
                                 stream));
   return hf_hybrid_attn_fwd_split(cfg, Q, Q_hist, n_q, K_win, V_win, n_kv, block_idx, select_k_of(cfg, cdiv(n_kv, cfg->block_kv)),
                                   state_or_null, rope_cos_q, rope_sin_q, O, workspace, workspace_bytes, stream);
+}
+
+int hf_bwd_workspace_bytes(const hf_config* cfg, int32_t n_q, int32_t n_kv, size_t* bytes_out) {
+  HF_TRY(check_cfg(cfg));
+  if (!bytes_out) { set_error("bytes_out is NULL"); return HF_ERR_NULL; }
+  HF_TRY(check_tokens(n_q, "n_q"));
+  HF_TRY(check_tokens(n_kv, "n_kv"));
+  *bytes_out = bwd_layout(cfg, n_q, n_kv).total;
+  return HF_OK;
+}
+
+int hf_hybrid_attn_bwd(const hf_config* cfg, const void* Q, const void* Q_hist, int32_t n_q, const void* K_win,
+                       const void* V_win, int32_t n_kv, const int32_t* block_idx, int32_t k,
+                       const void* state_or_null, const float* rope_cos_q, const float* rope_sin_q, const void* dO,
+                       void* dQ, void* dQ_hist, void* dK, void* dV, void* workspace, size_t workspace_bytes,
+                       void* stream) {
+  HF_TRY(check_cfg(cfg));
+  HF_TRY(check_ptr(Q, "Q", true));
+  if (!Q_hist) Q_hist = Q;
+  HF_TRY(check_ptr(Q_hist, "Q_hist", true));
+  HF_TRY(check_ptr(K_win, "K_win", true));
+  HF_TRY(check_ptr(V_win, "V_win", true));
+  HF_TRY(check_ptr(dO, "dO", true));
+  HF_TRY(check_ptr(dQ, "dQ", true));
+  HF_TRY(check_ptr(dK, "dK", true));
+  HF_TRY(check_ptr(dV, "dV", true));
+  HF_TRY(check_ptr(block_idx, "block_idx", false));
+  HF_TRY(check_ptr(state_or_null, "state", false));
+  HF_TRY(check_tokens(n_q, "n_q"));
+  HF_TRY(check_tokens(n_kv, "n_kv"));
+  HF_TRY(check_window_len(cfg, n_kv));
+  const bool split = Q_hist != Q;
+  if (split && !dQ_hist) { set_error("dQ_hist is required when Q_hist is a tensor of its own"); return HF_ERR_NULL; }
+  if (!split && dQ_hist) { set_error("dQ_hist must be NULL when one tensor feeds both branches"); return HF_ERR_SHAPE; }
+  HF_TRY(check_ptr(dQ_hist, "dQ_hist", false));
+  const void* ins[] = {Q, Q_hist, K_win, V_win, dO};
+  void* outs[] = {dQ, dK, dV, dQ_hist};
+  for (int a = 0; a < 4; ++a) {
+    if (!outs[a]) continue;
+    for (const void* in : ins)
+      if (outs[a] == in) { set_error("an output aliases an input"); return HF_ERR_SHAPE; }
+    for (int b = a + 1; b < 4; ++b)
+      if (outs[a] == outs[b]) { set_error("two outputs alias"); return HF_ERR_SHAPE; }
+  }
+  if ((rope_cos_q == nullptr) != (rope_sin_q == nullptr)) {
+    set_error("rope_cos_q and rope_sin_q must both be given or both be NULL");
+    return HF_ERR_NULL;
+  }
+  HF_TRY(check_ptr(rope_cos_q, "rope_cos_q", false));
+  HF_TRY(check_ptr(rope_sin_q, "rope_sin_q", false));
+  const int t_m = cdiv(n_q, cfg->block_q), t_n = cdiv(n_kv, cfg->block_kv);
+  if (block_idx) {
+    if (k < 1 || k > t_n) { set_error("k=%d must be in [1, %d]", k, t_n); return HF_ERR_SHAPE; }
+  } else {
+    k = t_n;
+  }
+  const BwdLayout w = bwd_layout(cfg, n_q, n_kv);
+  if (!workspace || workspace_bytes < w.total) {
+    set_error("workspace of %zu bytes needed, %zu given", w.total, workspace ? workspace_bytes : (size_t)0);
+    return HF_ERR_WORKSPACE;
+  }
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) { set_error("workspace is not 256-byte aligned"); return HF_ERR_ALIGN; }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  char* ws = static_cast<char*>(workspace);
+  float* lse2 = reinterpret_cast<float*>(ws + w.lse2);
+  float* dvec = reinterpret_cast<float*>(ws + w.dvec);
+  float* dqh32 = reinterpret_cast<float*>(ws + w.dqh32);
+  int32_t* inv_cnt = block_idx ? reinterpret_cast<int32_t*>(ws + w.inv_cnt) : nullptr;
+  int32_t* inv_list = block_idx ? reinterpret_cast<int32_t*>(ws + w.inv_list) : nullptr;
+  const float* st = static_cast<const float*>(state_or_null);
+
+  // history branch first: its gradient either is an output of its own or joins dQ before dQ's one rounding
+  const float* add_to_dq = nullptr;
+  if (st) {
+    if (split) {
+      HF_TRY(launch_bwd_hist_generic(*cfg, Q_hist, dO, st, n_q, rope_cos_q, rope_sin_q, dQ_hist, false, s));
+    } else {
+      HF_TRY(launch_bwd_hist_generic(*cfg, Q_hist, dO, st, n_q, rope_cos_q, rope_sin_q, dqh32, true, s));
+      add_to_dq = dqh32;
+    }
+  } else if (split) {
+    const size_t bytes = (size_t)cfg->batch * cfg->heads * n_q * cfg->head_dim * esize(cfg);
+    HF_TRY(launch_fill_zero(static_cast<float*>(dQ_hist), bytes / 4, s));
+  }
+  // row statistics of the softmax and D = dO . O_local (unrounded) from a recomputed forward pass
+  HF_TRY(launch_attn_generic(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, nullptr, s, lse2, dO, dvec));
+  if (block_idx) HF_TRY(launch_invert_index(*cfg, block_idx, k, t_m, t_n, inv_cnt, inv_list, s));
+  return launch_bwd_generic(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, dO, lse2, dvec, inv_cnt, inv_list,
+                            add_to_dq, dQ, dK, dV, s);
 }
 
 int hf_rope_window_indices(int32_t i_newest, int32_t n_frames, int32_t t0, int32_t* idx_out) {

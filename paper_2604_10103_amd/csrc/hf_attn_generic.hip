@@ -19,7 +19,9 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const T* __restrict__
                                                            const T* __restrict__ V,
                                                            const int32_t* __restrict__ idx, int k, int n_q,
                                                            int n_kv, int kv_stride, int bq, int bkv, int t_m,
-                                                           int t_n, float scale_log2e, T* __restrict__ O) {
+                                                           int t_n, float scale_log2e, T* __restrict__ O,
+                                                           float* __restrict__ lse2, const T* __restrict__ dO,
+                                                           float* __restrict__ Dv) {
   constexpr int E = Elem<T>::kPer16B;
   constexpr int C = D / kWave;  // value features per lane
   __shared__ float sq[4][R][D];
@@ -101,6 +103,26 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const T* __restrict__
         }
       }
     }
+    if (lse2) {
+      // statistics for the backward pass instead of the output: log2 of the sum of 2^(scaled logit), and
+      // D = dO . O_local from the unrounded output (uniform branch: every lane of the wavefront takes it)
+#pragma unroll
+      for (int rr = 0; rr < R; ++rr) {
+        const int row = min(r0 + rr, n_q - 1);
+        const float inv = 1.0f / l[rr];
+        float acc = 0.0f;
+#pragma unroll
+        for (int e = 0; e < C; ++e)
+          acc = fmaf(o[rr][e] * inv, Elem<T>::load(dO + ((size_t)bh * n_q + row) * D + lane * C + e), acc);
+        acc = wave_sum(acc);
+        if (lane == 0 && r0 + rr < q_end) {
+          lse2[(size_t)bh * n_q + row] = m[rr] + log2f(l[rr]);
+          Dv[(size_t)bh * n_q + row] = acc;
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+      continue;
+    }
 #pragma unroll
     for (int rr = 0; rr < R; ++rr) {
       const int row = r0 + rr;
@@ -117,7 +139,8 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const T* __restrict__
 }  // namespace
 
 int launch_attn_generic(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
-                        const int32_t* idx, int k, void* O_local, hipStream_t s) {
+                        const int32_t* idx, int k, void* O_local, hipStream_t s, float* lse2, const void* dO,
+                        float* Dv) {
   const int BH = c.batch * c.heads;
   const int t_m = (n_q + c.block_q - 1) / c.block_q, t_n = (n_kv + c.block_kv - 1) / c.block_kv;
   const float scale = c.softmax_scale > 0.0f ? c.softmax_scale : 1.0f / sqrtf((float)c.head_dim);
@@ -126,7 +149,7 @@ int launch_attn_generic(const hf_config& c, const void* Q, int n_q, const void* 
 #define HF_LAUNCH_GENERIC(T, DD)                                                                           \
   hipLaunchKernelGGL((attn_generic_kernel<T, DD, 4>), grid, block, 0, s, static_cast<const T*>(Q),         \
                      static_cast<const T*>(K), static_cast<const T*>(V), idx, k, n_q, n_kv, kv_stride_of(c, n_kv), c.block_q, \
-                     c.block_kv, t_m, t_n, sl2, static_cast<T*>(O_local))
+                     c.block_kv, t_m, t_n, sl2, static_cast<T*>(O_local), lse2, static_cast<const T*>(dO), Dv)
   if (c.dtype == HF_F32) {
     if (c.head_dim == 128) HF_LAUNCH_GENERIC(float, 128); else HF_LAUNCH_GENERIC(float, 64);
   } else {
@@ -155,7 +178,7 @@ int launch_attn(const hf_config& c, const void* Q, int n_q, const void* K, const
   const bool want_w64 = pick && pick[0] == 'w';
   if (attn_mfma_supported(c) && !want_w64) return launch_attn_mfma(c, Q, n_q, K, V, n_kv, idx, k, O_local, s);
   if (attn_w64_supported(c)) return launch_attn_w64(c, Q, n_q, K, V, n_kv, idx, k, O_local, s);
-  return launch_attn_generic(c, Q, n_q, K, V, n_kv, idx, k, O_local, s);
+  return launch_attn_generic(c, Q, n_q, K, V, n_kv, idx, k, O_local, s, nullptr, nullptr, nullptr);
 }
 
 }  // namespace hf

@@ -103,6 +103,18 @@ bool attn_mfma_fused_supported(const hf_config& c);
 int launch_attn_mfma_fused(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
                            const int32_t* idx, int k, const void* planes, const float* zvec, const float* cosq,
                            const float* sinq, const void* Q_hist, void* O, hipStream_t s);
+// backward pass (training algorithm): lse2 = per-row log2 of the softmax denominator in the scaled-logit domain
+int launch_attn_generic(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
+                        const int32_t* idx, int k, void* O_local, hipStream_t s, float* lse2, const void* dO,
+                        float* Dv);  // lse2 given: writes lse2 and Dv = dO . O_local instead of O_local
+int launch_invert_index(const hf_config& c, const int32_t* idx, int k, int t_m, int t_n, int32_t* inv_cnt,
+                        int32_t* inv_list, hipStream_t s);
+int launch_bwd_generic(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
+                       const int32_t* idx, int k, const void* dO, const float* lse2, const float* Dv,
+                       const int32_t* inv_cnt, const int32_t* inv_list, const float* dqh32, void* dQ, void* dK,
+                       void* dV, hipStream_t s);
+int launch_bwd_hist_generic(const hf_config& c, const void* Q_hist, const void* dO, const float* state, int n_q,
+                            const float* cosq, const float* sinq, void* out, bool out_f32, hipStream_t s);
 int launch_rope_tables(const int32_t* frame_idx, int n_frames, int height, int width, int pairs_t, int pairs_h,
                        int pairs_w, double theta, int temporal_only, float* cosv, float* sinv, hipStream_t s);
 int launch_rope_apply(const hf_config& c, const void* X, int n, const float* cosv, const float* sinv, void* Y,

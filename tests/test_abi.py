@@ -190,3 +190,25 @@ def test_cache_capacity_and_stream_bookkeeping_are_checked(lib):
     win = hf.hf_window(0, 50)
     assert lib.hf_stream_step(c, ctypes.byref(win), 4096, None, 100, 8192, 8192, 0, 4096, None, None, None, 16384,
                               4096, 1 << 30, None) == -2
+
+
+def test_backward_call_rejects_bad_arguments(lib):
+    cfg = hf.make_config(1, 2, 128, "bf16", 64, 64, 0.25)
+    c = ctypes.byref(cfg)
+    a = [4096 * i for i in range(1, 12)]          # distinct aligned fake addresses; nothing is launched on an error
+    Q, K, V, dO, dQ, dK, dV, dQh, Qh, ws = a[:10]
+    ok_tail = (ws << 8, 1 << 40, None)
+    # Q_hist of its own needs dQ_hist; a single query tensor must not get one
+    assert lib.hf_hybrid_attn_bwd(c, Q, Qh, 100, K, V, 200, None, 0, None, None, None, dO, dQ, None, dK, dV, *ok_tail) == -1
+    assert lib.hf_hybrid_attn_bwd(c, Q, None, 100, K, V, 200, None, 0, None, None, None, dO, dQ, dQh, dK, dV, *ok_tail) == -2
+    # outputs aliasing inputs or each other
+    assert lib.hf_hybrid_attn_bwd(c, Q, None, 100, K, V, 200, None, 0, None, None, None, dO, Q, None, dK, dV, *ok_tail) == -2
+    assert lib.hf_hybrid_attn_bwd(c, Q, None, 100, K, V, 200, None, 0, None, None, None, dO, dQ, None, dK, dK, *ok_tail) == -2
+    # missing gradient input, k out of range, workspace too small
+    assert lib.hf_hybrid_attn_bwd(c, Q, None, 100, K, V, 200, None, 0, None, None, None, None, dQ, None, dK, dV, *ok_tail) == -1
+    assert lib.hf_hybrid_attn_bwd(c, Q, None, 100, K, V, 200, 4096 * 20, 9, None, None, None, dO, dQ, None, dK, dV, *ok_tail) == -2
+    assert lib.hf_hybrid_attn_bwd(c, Q, None, 100, K, V, 200, None, 0, None, None, None, dO, dQ, None, dK, dV, ws << 8, 16, None) == -5
+    n = ctypes.c_size_t(0)
+    assert lib.hf_bwd_workspace_bytes(c, 100, 200, ctypes.byref(n)) == 0
+    # two row statistics per query row, the fp32 history gradient, the inverse index lists (counts + T_n x T_m entries)
+    assert n.value >= 2 * 2 * 100 * 4 + 2 * 100 * 128 * 4 + 2 * 4 * 4 + 2 * 4 * 2 * 4

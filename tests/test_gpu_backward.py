@@ -1,0 +1,153 @@
+"""GPU parity of the backward pass (training algorithm of the supplement) against the fp64 oracle's gradients:
+dQ, dK, dV of the block-sparse attention for the library's own index lists, the history branch's query gradient,
+split queries, the dense window, a cache buffer with spare capacity.
+
+Bounds.  fp32 storage: rel-L2 <= 5e-5 (fp32 exp2 and accumulation; dS = P (dP - D) subtracts two O(1) numbers, which
+costs a few units over the forward's 1e-5).  bf16 storage: rel-L2 <= 1e-2 and max-abs <= 2e-2 of the largest
+gradient magnitude, the forward's bounds (inputs are exact in both; the output rounding alone is 2^-9)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+import paper_2604_10103_amd as hf
+import workloads as wl
+from parity import heads_of, max_abs, oracle_state, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def cfg_of(w, **kw):
+    args = dict(batch=w.batch, heads=w.heads, head_dim=w.head_dim, dtype=w.dtype, block_q=w.block,
+                block_kv=w.block, keep_ratio=w.keep_ratio)
+    args.update(kw)
+    return hf.make_config(**args)
+
+
+def bounds(w):
+    return (1e-2, 2e-2) if w.dtype == "bf16" else (5e-5, 1e-4)
+
+
+def check(name, got, ref, w):
+    rl, ma = bounds(w)
+    scale = max(np.abs(ref).max(), 1e-30)
+    e1, e2 = rel_l2(got, ref), max_abs(got, ref) / scale
+    assert e1 <= rl and e2 <= ma, (name, e1, e2)
+    return e1
+
+
+def make_state(cfg, w, phi, rope):
+    st = torch.empty(hf.hf_state_bytes(cfg) // 4, dtype=torch.float32, device=DEV)
+    hf.hf_state_init(cfg, st)
+    Ks, Vs, tabs = [], [], []
+    for c in range(w.evicted_frames):
+        K, V = wl.make_evicted(w, c, w.tokens_per_frame)
+        tab = wl.rope_tables(w.tokens_per_frame, w.head_dim, first_position=float(c)) if rope else (None, None)
+        Ks.append(K); Vs.append(V); tabs.append(tab)
+        hf.hf_absorb_evicted(cfg, st, K.to(DEV), V.to(DEV), *(None if t is None else t.to(DEV) for t in tab))
+    return st, oracle_state(Ks, Vs, w.head_dim, phi, tabs if rope else None)
+
+
+def run_bwd(cfg, w, Q, K, V, idx, st, dO, tables=None, Q_hist=None, n_kv=None):
+    dQ = torch.full(Q.shape, float("nan"), dtype=Q.dtype, device=DEV)
+    dK = torch.full(K.shape, float("nan"), dtype=K.dtype, device=DEV)
+    dV = torch.full(K.shape, float("nan"), dtype=K.dtype, device=DEV)
+    dQh = torch.full(Q.shape, float("nan"), dtype=Q.dtype, device=DEV) if Q_hist is not None else None
+    nkv = K.shape[2] if n_kv is None else n_kv
+    ws = torch.empty(hf.hf_bwd_workspace_bytes(cfg, Q.shape[2], nkv), dtype=torch.uint8, device=DEV)
+    cos, sin = (None, None) if tables is None else (tables[0].to(DEV), tables[1].to(DEV))
+    hf.hf_hybrid_attn_bwd(cfg, Q.to(DEV), K.to(DEV), V.to(DEV), idx, st, dO.to(DEV), dQ, dK, dV, ws, cos, sin,
+                          None if Q_hist is None else Q_hist.to(DEV), dQh, n_kv=n_kv)
+    torch.cuda.synchronize()
+    return dQ, dK, dV, dQh
+
+
+def select(cfg, w, Q, K):
+    k = hf.hf_select_k(cfg, w.n_kv)
+    idx = torch.full((w.batch, w.heads, w.t_m, k), -1, dtype=torch.int32, device=DEV)
+    ws = torch.empty(hf.hf_workspace_bytes(cfg, w.n_q, w.n_kv), dtype=torch.uint8, device=DEV)
+    hf.hf_block_select(cfg, Q.to(DEV), K.to(DEV), idx, None, ws)
+    torch.cuda.synchronize()
+    return idx, k
+
+
+@pytest.mark.parametrize("name,phi,rope", [("tiny_f32", hf.HF_PHI_RELU, False), ("tiny_f32", hf.HF_PHI_ELU1, True),
+                                           ("small_f32_d128", hf.HF_PHI_RELU, True), ("small_bf16", hf.HF_PHI_RELU, False),
+                                           ("small_bf16", hf.HF_PHI_ELU1, True), ("small_b128", hf.HF_PHI_RELU, False)])
+def test_gradients_of_the_whole_path_match_oracle(name, phi, rope):
+    w = wl.get(name)
+    cfg = cfg_of(w, phi=phi)
+    st, ref_states = make_state(cfg, w, phi, rope)
+    Q, K, V = wl.make_qkv(w, q_gain=2.0)
+    dO = wl.randn(Q.shape, 91_000 + w.cfg, 1.0, w.torch_dtype)
+    qtab = wl.rope_tables(w.n_q, w.head_dim, first_position=float(w.evicted_frames + 2),
+                          tokens_per_position=w.tokens_per_frame) if rope else None
+    idx, k = select(cfg, w, Q, K)
+    dQ, dK, dV, _ = run_bwd(cfg, w, Q, K, V, idx, st, dO, qtab)
+    idxc = idx.cpu().numpy()
+    cq = None if qtab is None else wl.to_f64(qtab[0])
+    sq = None if qtab is None else wl.to_f64(qtab[1])
+    gq, gk, gv = wl.to_f64(dQ), wl.to_f64(dK), wl.to_f64(dV)
+    for h, (q, kk, v, g) in enumerate(zip(heads_of(Q), heads_of(K), heads_of(V), heads_of(dO))):
+        rql, rqh, rk, rv = orc.hybrid_attention_bwd(q, kk, v, ref_states[h], w.block, w.block, idxc[0, h], g, phi,
+                                                    cq, sq, cfg.eps, cfg.z_scale)
+        assert np.abs(rqh).max() > 1e-3 * np.abs(rql).max()        # the history branch's share is really there
+        check("dQ", gq[0, h], rql + rqh, w)
+        check("dK", gk[0, h], rk, w)
+        check("dV", gv[0, h], rv, w)
+        # blocks nobody selected: exact zeros
+        unused = sorted(set(range(w.t_n)) - set(idxc[0, h].ravel().tolist()))
+        for j in unused:
+            assert not gk[0, h, j * w.block:(j + 1) * w.block].any() and not gv[0, h, j * w.block:(j + 1) * w.block].any()
+
+
+@pytest.mark.parametrize("name", ["tiny_f32", "small_bf16"])
+def test_split_queries_no_state_and_dense_window(name):
+    w = wl.get(name)
+    cfg = cfg_of(w)
+    st, ref_states = make_state(cfg, w, hf.HF_PHI_RELU, False)
+    Q, K, V = wl.make_qkv(w)
+    Qh = wl.randn(Q.shape, 92_000 + w.cfg, w.scale, w.torch_dtype)
+    dO = wl.randn(Q.shape, 93_000 + w.cfg, 1.0, w.torch_dtype)
+    idx, k = select(cfg, w, Q, K)
+    idxc = idx.cpu().numpy()
+    # split queries: the two gradients go to the two tensors
+    dQ, dK, dV, dQh = run_bwd(cfg, w, Q, K, V, idx, st, dO, Q_hist=Qh)
+    for h, (q, qh, kk, v, g) in enumerate(zip(heads_of(Q), heads_of(Qh), heads_of(K), heads_of(V), heads_of(dO))):
+        rql, rqh, rk, rv = orc.hybrid_attention_bwd(q, kk, v, ref_states[h], w.block, w.block, idxc[0, h], g,
+                                                    eps=cfg.eps, z_scale=cfg.z_scale, Q_hist=qh)
+        check("dQ", wl.to_f64(dQ)[0, h], rql, w)
+        check("dQ_hist", wl.to_f64(dQh)[0, h], rqh, w)
+        check("dK", wl.to_f64(dK)[0, h], rk, w)
+    # no state: dQ_hist is zero, dQ is the softmax branch alone
+    dQ0, _, _, dQh0 = run_bwd(cfg, w, Q, K, V, idx, None, dO, Q_hist=Qh)
+    assert not dQh0.float().abs().max().item()
+    assert torch.equal(dQ0, dQ)
+    # dense window: no index list
+    dQd, dKd, dVd, _ = run_bwd(cfg, w, Q, K, V, None, None, dO)
+    all_blocks = np.tile(np.arange(w.t_n), (w.t_m, 1))
+    for h, (q, kk, v, g) in enumerate(zip(heads_of(Q), heads_of(K), heads_of(V), heads_of(dO))):
+        rq, rk, rv = orc.sparse_attention_bwd(q, kk, v, all_blocks, w.block, w.block, g)
+        check("dQ dense", wl.to_f64(dQd)[0, h], rq, w)
+        check("dK dense", wl.to_f64(dKd)[0, h], rk, w)
+        check("dV dense", wl.to_f64(dVd)[0, h], rv, w)
+
+
+def test_gradients_in_a_cache_buffer_layout():
+    w = wl.get("small_bf16")
+    cap = w.n_kv + 70
+    packed, cached = cfg_of(w), cfg_of(w, kv_capacity=cap)
+    Q, K, V = wl.make_qkv(w)
+    dO = wl.randn(Q.shape, 94_000, 1.0, w.torch_dtype)
+    idx, k = select(packed, w, Q, K)
+    Kc = torch.zeros((w.batch, w.heads, cap, w.head_dim), dtype=K.dtype)
+    Vc = torch.zeros_like(Kc)
+    Kc[:, :, :w.n_kv] = K
+    Vc[:, :, :w.n_kv] = V
+    a = run_bwd(packed, w, Q, K, V, idx, None, dO)
+    b = run_bwd(cached, w, Q, Kc, Vc, idx, None, dO, n_kv=w.n_kv)
+    assert torch.equal(a[0], b[0])
+    assert torch.equal(a[1], b[1][:, :, :w.n_kv]) and torch.equal(a[2], b[2][:, :, :w.n_kv])
+    assert b[1][:, :, w.n_kv:].isnan().all()          # nothing behind the valid tokens is written
