@@ -30,6 +30,7 @@ SOURCES = [
     "hf_readout_mfma.hip",
     "hf_rope.hip",
     "hf_bwd.hip",
+    "hf_bwd_mfma.hip",
 ]
 
 FLAGS = [

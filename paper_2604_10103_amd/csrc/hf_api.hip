@@ -493,8 +493,14 @@ int hf_hybrid_attn_bwd(const hf_config* cfg, const void* Q, const void* Q_hist, 
     HF_TRY(launch_fill_zero(static_cast<float*>(dQ_hist), bytes / 4, s));
   }
   // row statistics of the softmax and D = dO . O_local (unrounded) from a recomputed forward pass
-  HF_TRY(launch_attn_generic(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, nullptr, s, lse2, dO, dvec));
+  const char* pick = getenv("HF_BWD_KERNEL");   // development switch: "g" forces the fp32-arithmetic kernels
+  const bool mfma = bwd_mfma_supported(*cfg) && !(pick && pick[0] == 'g');
+  if (mfma) HF_TRY(launch_attn_mfma_stats(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, dO, lse2, dvec, s));
+  else HF_TRY(launch_attn_generic(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, nullptr, s, lse2, dO, dvec));
   if (block_idx) HF_TRY(launch_invert_index(*cfg, block_idx, k, t_m, t_n, inv_cnt, inv_list, s));
+  if (mfma)
+    return launch_bwd_mfma(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, dO, lse2, dvec, inv_cnt, inv_list,
+                           add_to_dq, dQ, dK, dV, s);
   return launch_bwd_generic(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, dO, lse2, dvec, inv_cnt, inv_list,
                             add_to_dq, dQ, dK, dV, s);
 }

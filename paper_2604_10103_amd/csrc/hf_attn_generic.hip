@@ -116,7 +116,7 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const T* __restrict__
           acc = fmaf(o[rr][e] * inv, Elem<T>::load(dO + ((size_t)bh * n_q + row) * D + lane * C + e), acc);
         acc = wave_sum(acc);
         if (lane == 0 && r0 + rr < q_end) {
-          lse2[(size_t)bh * n_q + row] = m[rr] + log2f(l[rr]);
+          lse2[(size_t)bh * n_q + row] = l[rr] > 0.0f ? m[rr] + log2f(l[rr]) : INFINITY;  // no real key: P = 0
           Dv[(size_t)bh * n_q + row] = acc;
         }
       }

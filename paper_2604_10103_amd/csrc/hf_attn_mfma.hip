@@ -67,9 +67,14 @@ struct HistArgs {
   const float* cosq;     // [n_q][d/2] rotation of phi(q) in the numerator, or NULL
   const float* sinq;
   const bf16_t* q_hist;  // [BH][n_q][d] queries of the history branch when they are not Q, or NULL
+  // kFused == 3 (row statistics for the backward pass instead of the output):
+  const bf16_t* d_out;   // [BH][n_q][d] gradient of the output
+  float* lse2;           // [BH][n_q] log2 of the softmax denominator in the scaled-logit domain
+  float* dvec;           // [BH][n_q] d_out . O_local
 };
 
-// kFused: 0 = attention only, 1 = + history term for ReLU without rotation, 2 = + history term, general
+// kFused: 0 = attention only, 1 = + history term for ReLU without rotation, 2 = + history term, general,
+// 3 = no output: the row statistics the backward pass needs
 template <int NW, int kFused>
 __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
@@ -325,6 +330,30 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[dt][r] *= inv;
 
+  if (kFused == 3) {
+    // ---- backward-pass statistics: lse2 = m + log2(l) and D = dO . O_local, O_local still unrounded
+    const bf16_t* gp = hist.d_out + ((size_t)bh * n_q + min(q_row, n_q - 1)) * D + 4 * h;
+    float acc = 0.0f;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        const uint2 w = *reinterpret_cast<const uint2*>(gp + 32 * dt + 8 * rq);
+        acc = fmaf(o[dt][4 * rq], __uint_as_float(w.x << 16), acc);
+        acc = fmaf(o[dt][4 * rq + 1], __uint_as_float(w.x & 0xffff0000u), acc);
+        acc = fmaf(o[dt][4 * rq + 2], __uint_as_float(w.y << 16), acc);
+        acc = fmaf(o[dt][4 * rq + 3], __uint_as_float(w.y & 0xffff0000u), acc);
+      }
+    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc), __float_as_uint(acc), false, false);
+    acc = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+    if (h == 0 && q_row < n_q) {
+      // a row without a single real key keeps probability zero everywhere
+      hist.lse2[(size_t)bh * n_q + q_row] = l_tot > 0.0f ? m_ref + __log2f(l_tot) : INFINITY;
+      hist.dvec[(size_t)bh * n_q + q_row] = acc;
+    }
+    return;
+  }
+
   if (kFused) {
     // ---- O += R(phi(q)) L / (z_scale phi(q).z + eps) (Eq. 3, 6): the query fragments already in
     // registers become the B operand of O_hist^T = Lt x R(phi(Q))^T; the A operand comes from the
@@ -463,15 +492,15 @@ static int launch_attn_mfma_impl(const hf_config& c, const void* Q, int n_q, con
   const bf16_t* kk = static_cast<const bf16_t*>(K);
   const bf16_t* v = static_cast<const bf16_t*>(V);
   bf16_t* o = static_cast<bf16_t*>(O);
-  const HistArgs h = hist ? *hist : HistArgs{nullptr, nullptr, 0.0f, 0.0f, 0, 0, nullptr, nullptr, nullptr};
+  const HistArgs h = hist ? *hist : HistArgs{nullptr, nullptr, 0.0f, 0.0f, 0, 0, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
 #define HF_LAUNCH_ATTN(NWV, FUSED)                                                                              \
   hipLaunchKernelGGL((attn_mfma_kernel<NWV, FUSED>), grid, dim3(64 * NWV), 0, s, q, kk, v, idx, k, n_q, n_kv,   \
                      kv_stride_of(c, n_kv), c.block_kv, t_m, t_n, per_xcd, (int)total, c_scale, h, o)
-  const int fused = !hist ? 0 : ((h.phi_kind == HF_PHI_RELU && h.cosq == nullptr && h.q_hist == nullptr) ? 1 : 2);
+  const int fused = !hist ? 0 : (h.lse2 ? 3 : ((h.phi_kind == HF_PHI_RELU && h.cosq == nullptr && h.q_hist == nullptr) ? 1 : 2));
   if (c.block_q == 64) {
-    if (fused == 0) HF_LAUNCH_ATTN(2, 0); else if (fused == 1) HF_LAUNCH_ATTN(2, 1); else HF_LAUNCH_ATTN(2, 2);
+    if (fused == 0) HF_LAUNCH_ATTN(2, 0); else if (fused == 1) HF_LAUNCH_ATTN(2, 1); else if (fused == 2) HF_LAUNCH_ATTN(2, 2); else HF_LAUNCH_ATTN(2, 3);
   } else {
-    if (fused == 0) HF_LAUNCH_ATTN(4, 0); else if (fused == 1) HF_LAUNCH_ATTN(4, 1); else HF_LAUNCH_ATTN(4, 2);
+    if (fused == 0) HF_LAUNCH_ATTN(4, 0); else if (fused == 1) HF_LAUNCH_ATTN(4, 1); else if (fused == 2) HF_LAUNCH_ATTN(4, 2); else HF_LAUNCH_ATTN(4, 3);
   }
 #undef HF_LAUNCH_ATTN
   return check_launch("hf_hybrid_attn_fwd(attention)");
@@ -493,8 +522,16 @@ int launch_attn_mfma_fused(const hf_config& c, const void* Q, int n_q, const voi
   // environment adds the low plane (development switch).
   const char* np = getenv("HF_FUSED_PLANES");
   const HistArgs h = {static_cast<const bf16_t*>(planes), zvec, c.eps, c.z_scale, (np && np[0] == '2') ? 2 : 1,
-                      c.phi, cosq, sinq, Q_hist == Q ? nullptr : static_cast<const bf16_t*>(Q_hist)};
+                      c.phi, cosq, sinq, Q_hist == Q ? nullptr : static_cast<const bf16_t*>(Q_hist), nullptr, nullptr, nullptr};
   return launch_attn_mfma_impl(c, Q, n_q, K, V, n_kv, idx, k, &h, O, s);
+}
+
+// the forward pass recomputed for the backward pass: row statistics out, no attention output
+int launch_attn_mfma_stats(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
+                           const int32_t* idx, int k, const void* dO, float* lse2, float* dvec, hipStream_t s) {
+  const HistArgs h = {nullptr, nullptr, 0.0f, 0.0f, 0, 0, nullptr, nullptr, nullptr, static_cast<const bf16_t*>(dO),
+                      lse2, dvec};
+  return launch_attn_mfma_impl(c, Q, n_q, K, V, n_kv, idx, k, &h, nullptr, s);
 }
 
 }  // namespace hf

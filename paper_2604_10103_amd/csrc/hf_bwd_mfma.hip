@@ -1,0 +1,397 @@
+// Backward pass of the block-sparse attention on the matrix cores (bf16, head_dim 128, block_q 64 or
+// 128; training algorithm of the supplement).  Two kernels, both built from 32x32x16 bf16 MFMAs on
+// transposed products, so that every statistic of a softmax row is private to a lane or comes from a
+// 32-entry table, and every accumulated gradient stays in registers until it is stored once:
+//
+//  dQ  (one workgroup per query block, one wavefront per 32 query rows, tiles of 32 keys)
+//      S^T  = K Q^T          dP^T = V dO^T            lane = query row, registers = keys
+//      dS^T = 2^(c S^T - lse2) * (dP^T - D)           -> bf16, B operand
+//      dQ^T += K^T dS^T                               A operand = K transposed in LDS
+//  dK, dV  (one workgroup per slab of a KV block, one wavefront per 32 keys, tiles of 32 query rows
+//      taken from the inverse index lists)
+//      S  = Q K^T            dP = dO V^T              lane = key, registers = query rows
+//      P  = 2^(c S - lse2),  dS = P * (dP - D)        -> bf16, B operands
+//      dV^T += dO^T P        dK^T += Q^T dS           A operands = dO, Q transposed in LDS
+//
+// A tile of 32 tokens x 128 features is fetched once from HBM (buffer loads that return zero past the
+// end of the head) in the lane mapping of the transposing store and written to LDS twice: row-major
+// with XOR-swizzled 16-byte units (A operand with tokens as rows) and transposed with token pairs in
+// MFMA order (A operand with features as rows).  The LDS layouts are those of the forward kernel.
+#include <math.h>
+
+#include "hf_common.h"
+
+namespace hf {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr int D = 128;
+constexpr int TT = 32;       // tokens per tile
+constexpr int RSTR = 256;    // bytes per token row of a row-major tile
+constexpr int TSTR = 40;     // dwords per feature row of a transposed tile (16 token pairs, rotated within 32)
+constexpr int RTILE = TT * RSTR;
+constexpr int TTILE = D * TSTR * 4;
+constexpr int OSTR = 272;    // bytes per token row of a staged output
+
+// lane mapping of the transposing fetch: a half-wavefront covers 8 feature groups x 4 token pairs
+struct Stager {
+  int wave, vgrp, sub4, tok_lane, rot;
+  __device__ explicit Stager(int tid) {
+    const int lane = tid & 63;
+    wave = tid >> 6;
+    vgrp = (lane & 7) + 8 * (lane >> 5);
+    sub4 = (lane >> 3) & 3;
+    tok_lane = 8 * (sub4 >> 1) + 2 * (sub4 & 1);
+    rot = 4 * (vgrp & 7);
+  }
+  // item cb in [0, 4): tokens 16 (cb >> 1) + 4 (cb & 1) + tok_lane and the next one
+  __device__ int token(int cb) const { return 16 * (cb >> 1) + 4 * (cb & 1) + tok_lane; }
+};
+
+// fetch: IPT items of (two token rows x one 16-byte feature group) per thread
+template <int NT>
+__device__ __forceinline__ void tile_fetch(const Stager& st, __amdgpu_buffer_rsrc_t rsrc, int first_token,
+                                           u32x4 (&reg)[512 / NT]) {
+  constexpr int IPT = 256 / NT;
+#pragma unroll
+  for (int j = 0; j < IPT; ++j) {
+    const int off = (first_token + st.token(st.wave * IPT + j)) * (D * 2) + st.vgrp * 16;
+    reg[2 * j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 0);
+    reg[2 * j + 1] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off + D * 2, 0, 0);
+  }
+}
+
+template <int NT>
+__device__ __forceinline__ void tile_store_rows(const Stager& st, const u32x4 (&reg)[512 / NT], char* sX) {
+  constexpr int IPT = 256 / NT;
+#pragma unroll
+  for (int j = 0; j < IPT; ++j) {
+    const int t0 = st.token(st.wave * IPT + j);
+    *reinterpret_cast<u32x4*>(sX + t0 * RSTR + ((st.vgrp ^ (t0 & 15)) * 16)) = reg[2 * j];
+    *reinterpret_cast<u32x4*>(sX + (t0 + 1) * RSTR + ((st.vgrp ^ ((t0 + 1) & 15)) * 16)) = reg[2 * j + 1];
+  }
+}
+
+template <int NT>
+__device__ __forceinline__ void tile_store_transposed(const Stager& st, const u32x4 (&reg)[512 / NT],
+                                                      uint32_t* sXt) {
+  constexpr int IPT = 256 / NT;
+#pragma unroll
+  for (int j = 0; j < IPT; ++j) {
+    const int col = (4 * (st.wave * IPT + j) + st.sub4 + st.rot) & 31;
+    const u32x4 a = reg[2 * j], b = reg[2 * j + 1];  // tokens t and t + 1
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const int f = 8 * st.vgrp + 2 * p;
+      sXt[f * TSTR + col] = __builtin_amdgcn_perm(b[p], a[p], 0x05040100u);
+      sXt[(f + 1) * TSTR + col] = __builtin_amdgcn_perm(b[p], a[p], 0x07060302u);
+    }
+  }
+}
+
+// A operand, tokens as rows: row l32, features 16 s + 8 h .. + 8
+__device__ __forceinline__ bf16x8 rows_frag(const char* sX, int l32, int h, int s) {
+  return *reinterpret_cast<const bf16x8*>(sX + l32 * RSTR + (((2 * s + h) ^ (l32 & 15)) * 16));
+}
+// A operand, features as rows: feature 32 dt + l32, tokens of MFMA step t2 (16 tokens), half h
+__device__ __forceinline__ bf16x8 transposed_frag(const uint32_t* sXt, int l32, int h, int dt, int t2) {
+  const int rot = 4 * ((4 * dt + (l32 >> 3)) & 7);
+  return *reinterpret_cast<const bf16x8*>(&sXt[(32 * dt + l32) * TSTR + ((8 * t2 + 4 * h + rot) & 31)]);
+}
+
+// this lane's token row as B-operand fragments (features 16 s + 8 h .. + 8), zero past the end
+__device__ __forceinline__ void row_frags(__amdgpu_buffer_rsrc_t rsrc, int row, int h, bf16x8 (&f)[8]) {
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, row * (D * 2) + 16 * h + 32 * s, 0, 0);
+    f[s] = __builtin_bit_cast(bf16x8, v);
+  }
+}
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc_of(const bf16_t* p, int rows) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(p), 0, rows * (D * 2), 0x00020000);
+}
+
+// C-layout accumulators (feature 32 dt + 8 (r >> 2) + 4 h + (r & 3), token l32) -> bf16 rows in LDS
+__device__ __forceinline__ void stage_rows(char* stage, int row, int h, const f32x16 (&acc)[4], float mul) {
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int rq = 0; rq < 4; ++rq) {
+      uint2 w;
+      w.x = (uint32_t)f32_to_bf16(acc[dt][4 * rq] * mul) | ((uint32_t)f32_to_bf16(acc[dt][4 * rq + 1] * mul) << 16);
+      w.y = (uint32_t)f32_to_bf16(acc[dt][4 * rq + 2] * mul) | ((uint32_t)f32_to_bf16(acc[dt][4 * rq + 3] * mul) << 16);
+      *reinterpret_cast<uint2*>(stage + row * OSTR + (32 * dt + 8 * rq + 4 * h) * 2) = w;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------- dQ
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void bwd_dq_mfma_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+    const bf16_t* __restrict__ dO, const int32_t* __restrict__ idx, int k, int n_q, int n_kv, int kv_stride, int bkv,
+    int t_m, int t_n, float c_scale, float scale, const float* __restrict__ lse2, const float* __restrict__ Dv,
+    const float* __restrict__ dqh32, bf16_t* __restrict__ dQ) {
+  constexpr int NT = 64 * NW;
+  constexpr int BQ = 32 * NW;
+  __shared__ __attribute__((aligned(16))) char smem[2 * RTILE + TTILE];
+  char* const sK = smem;
+  char* const sV = smem + RTILE;
+  uint32_t* const sKt = reinterpret_cast<uint32_t*>(smem + 2 * RTILE);
+  static_assert(BQ * OSTR <= 2 * RTILE + TTILE, "staged output must fit");
+
+  const int qb = blockIdx.x, bh = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, h = lane >> 5;
+  const Stager st(tid);
+  const __amdgpu_buffer_rsrc_t q_rsrc = rsrc_of(Q + (size_t)bh * n_q * D, n_q);
+  const __amdgpu_buffer_rsrc_t do_rsrc = rsrc_of(dO + (size_t)bh * n_q * D, n_q);
+  const __amdgpu_buffer_rsrc_t k_rsrc = rsrc_of(K + (size_t)bh * kv_stride * D, n_kv);
+  const __amdgpu_buffer_rsrc_t v_rsrc = rsrc_of(V + (size_t)bh * kv_stride * D, n_kv);
+  const int32_t* row_idx = idx ? idx + ((size_t)bh * t_m + qb) * k : nullptr;
+  const int nsel = idx ? k : t_n;
+  const int subs = (bkv + TT - 1) / TT;
+
+  const int q_row = qb * BQ + 32 * wave + l32;   // rows past n_q read zeros and are not stored
+  bf16x8 qf[8], dof[8];
+  row_frags(q_rsrc, q_row, h, qf);
+  row_frags(do_rsrc, q_row, h, dof);
+  const size_t stat = (size_t)bh * n_q + min(q_row, n_q - 1);
+  const float lse = lse2[stat], dvec = Dv[stat];
+
+  f32x16 dq[4];
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dq[dt][r] = 0.0f;
+
+  for (int sel = 0; sel < nsel; ++sel) {
+    const int jb = row_idx ? row_idx[sel] : sel;
+    if ((unsigned)jb >= (unsigned)t_n) continue;   // uniform over the workgroup
+    const int blk_end = min(n_kv, (jb + 1) * bkv);
+    for (int sub = 0; sub < subs; ++sub) {
+      const int start = jb * bkv + TT * sub;
+      const int valid = min(TT, blk_end - start);
+      if (valid <= 0) break;
+      u32x4 kreg[512 / NT], vreg[512 / NT];
+      tile_fetch<NT>(st, k_rsrc, start, kreg);
+      tile_fetch<NT>(st, v_rsrc, start, vreg);
+      __syncthreads();   // the previous tile is consumed
+      tile_store_rows<NT>(st, kreg, sK);
+      tile_store_transposed<NT>(st, kreg, sKt);
+      tile_store_rows<NT>(st, vreg, sV);
+      __syncthreads();
+
+      f32x16 sacc, dpacc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sacc[r] = 0.0f; dpacc[r] = 0.0f; }
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(sK, l32, h, s), qf[s], sacc, 0, 0, 0);
+        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(sV, l32, h, s), dof[s], dpacc, 0, 0, 0);
+      }
+      bf16x8 dsf[2];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = 8 * (r >> 2) + 4 * h + (r & 3);
+        const float p = key < valid ? __builtin_amdgcn_exp2f(fmaf(sacc[r], c_scale, -lse)) : 0.0f;
+        dsf[r >> 3][r & 7] = static_cast<__bf16>(p * (dpacc[r] - dvec));
+      }
+#pragma unroll
+      for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+          dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(transposed_frag(sKt, l32, h, dt, t2), dsf[t2], dq[dt], 0, 0, 0);
+    }
+  }
+
+  // the history branch's share joins before the one rounding
+  if (dqh32 && q_row < n_q) {
+    const float* g = dqh32 + ((size_t)bh * n_q + q_row) * D;
+    const float inv = 1.0f / scale;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        const float4 a = *reinterpret_cast<const float4*>(g + 32 * dt + 8 * rq + 4 * h);
+        dq[dt][4 * rq] += a.x * inv;
+        dq[dt][4 * rq + 1] += a.y * inv;
+        dq[dt][4 * rq + 2] += a.z * inv;
+        dq[dt][4 * rq + 3] += a.w * inv;
+      }
+  }
+  __syncthreads();
+  stage_rows(smem, 32 * wave + l32, h, dq, scale);
+  __syncthreads();
+  bf16_t* dQh = dQ + (size_t)bh * n_q * D;
+#pragma unroll
+  for (int i = 0; i < (BQ * 16) / NT; ++i) {
+    const int c = tid + NT * i, row = c >> 4, col = c & 15;
+    if (qb * BQ + row < n_q)
+      *reinterpret_cast<uint4*>(dQh + (size_t)(qb * BQ + row) * D + col * 8) =
+          *reinterpret_cast<const uint4*>(smem + row * OSTR + col * 16);
+  }
+}
+
+// ------------------------------------------------------------------------------------------ dK, dV
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void bwd_dkv_mfma_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+    const bf16_t* __restrict__ dO, const int32_t* __restrict__ inv_cnt, const int32_t* __restrict__ inv_list,
+    int n_q, int n_kv, int kv_stride, int bq, int bkv, int t_m, int t_n, int slabs, float c_scale, float scale,
+    const float* __restrict__ lse2, const float* __restrict__ Dv, bf16_t* __restrict__ dK, bf16_t* __restrict__ dV) {
+  constexpr int NT = 64 * NW;
+  __shared__ __attribute__((aligned(16))) char smem[2 * RTILE + 2 * TTILE + 256];
+  char* const sQ = smem;
+  char* const sdO = smem + RTILE;
+  uint32_t* const sQt = reinterpret_cast<uint32_t*>(smem + 2 * RTILE);
+  uint32_t* const sdOt = reinterpret_cast<uint32_t*>(smem + 2 * RTILE + TTILE);
+  float* const sStat = reinterpret_cast<float*>(smem + 2 * RTILE + 2 * TTILE);   // lse2[32], D[32]
+  static_assert(32 * NW * OSTR <= 2 * RTILE + 2 * TTILE, "staged output must fit");
+
+  const int jb = blockIdx.x / slabs, slab = blockIdx.x - jb * slabs, bh = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, h = lane >> 5;
+  const Stager st(tid);
+  const __amdgpu_buffer_rsrc_t q_rsrc = rsrc_of(Q + (size_t)bh * n_q * D, n_q);
+  const __amdgpu_buffer_rsrc_t do_rsrc = rsrc_of(dO + (size_t)bh * n_q * D, n_q);
+  const __amdgpu_buffer_rsrc_t k_rsrc = rsrc_of(K + (size_t)bh * kv_stride * D, n_kv);
+  const __amdgpu_buffer_rsrc_t v_rsrc = rsrc_of(V + (size_t)bh * kv_stride * D, n_kv);
+  const float* lseh = lse2 + (size_t)bh * n_q;
+  const float* Dvh = Dv + (size_t)bh * n_q;
+  const int n_lists = inv_cnt ? inv_cnt[(size_t)bh * t_n + jb] : t_m;   // no lists: every query block (dense)
+  const int32_t* list = inv_list ? inv_list + ((size_t)bh * t_n + jb) * t_m : nullptr;
+
+  // this wavefront's 32 keys; a wavefront past the block's end carries no real key
+  const int blk_end = min(n_kv, (jb + 1) * bkv);
+  const int key0 = jb * bkv + 32 * (slab * NW + wave);
+  const int kvalid = min(32, blk_end - key0);          // may be <= 0
+  bf16x8 kf[8], vf[8];
+  row_frags(k_rsrc, key0 + l32, h, kf);
+  row_frags(v_rsrc, key0 + l32, h, vf);
+  const bool key_ok = l32 < kvalid;
+
+  f32x16 dk[4], dv[4];
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { dk[dt][r] = 0.0f; dv[dt][r] = 0.0f; }
+
+  const int qtiles = bq / TT;
+  for (int t = 0; t < n_lists; ++t) {
+    const int qb = list ? list[t] : t;
+    for (int qt = 0; qt < qtiles; ++qt) {
+      const int row0 = qb * bq + TT * qt;
+      if (row0 >= n_q) break;   // uniform
+      u32x4 qreg[512 / NT], dreg[512 / NT];
+      tile_fetch<NT>(st, q_rsrc, row0, qreg);
+      tile_fetch<NT>(st, do_rsrc, row0, dreg);
+      float stat = 0.0f;
+      if (tid < 64) {
+        const int row = min(row0 + (tid & 31), n_q - 1);
+        stat = tid < 32 ? lseh[row] : Dvh[row];
+      }
+      __syncthreads();   // the previous tile is consumed
+      tile_store_rows<NT>(st, qreg, sQ);
+      tile_store_transposed<NT>(st, qreg, sQt);
+      tile_store_rows<NT>(st, dreg, sdO);
+      tile_store_transposed<NT>(st, dreg, sdOt);
+      if (tid < 64) sStat[tid] = stat;
+      __syncthreads();
+
+      f32x16 sacc, dpacc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sacc[r] = 0.0f; dpacc[r] = 0.0f; }
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(sQ, l32, h, s), kf[s], sacc, 0, 0, 0);
+        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(sdO, l32, h, s), vf[s], dpacc, 0, 0, 0);
+      }
+      bf16x8 pf[2], dsf[2];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const float4 l4 = *reinterpret_cast<const float4*>(sStat + 8 * g + 4 * h);
+        const float4 d4 = *reinterpret_cast<const float4*>(sStat + 32 + 8 * g + 4 * h);
+        const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, ds[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int r = 4 * g + i;
+          const int row = row0 + 8 * g + 4 * h + i;
+          const float p = (key_ok && row < n_q) ? __builtin_amdgcn_exp2f(fmaf(sacc[r], c_scale, -ls[i])) : 0.0f;
+          pf[r >> 3][r & 7] = static_cast<__bf16>(p);
+          dsf[r >> 3][r & 7] = static_cast<__bf16>(p * (dpacc[r] - ds[i]));
+        }
+      }
+#pragma unroll
+      for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
+          dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(transposed_frag(sdOt, l32, h, dt, t2), pf[t2], dv[dt], 0, 0, 0);
+          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(transposed_frag(sQt, l32, h, dt, t2), dsf[t2], dk[dt], 0, 0, 0);
+        }
+    }
+  }
+
+  // transpose through LDS and store the rows of real keys, dK first, then dV
+  const int first_key = jb * bkv + 32 * slab * NW;
+  for (int which = 0; which < 2; ++which) {
+    __syncthreads();
+    stage_rows(smem, 32 * wave + l32, h, which ? dv : dk, which ? 1.0f : scale);
+    __syncthreads();
+    bf16_t* out = (which ? dV : dK) + (size_t)bh * kv_stride * D;
+#pragma unroll
+    for (int i = 0; i < (32 * NW * 16) / NT; ++i) {
+      const int c = tid + NT * i, row = c >> 4, col = c & 15;
+      if (first_key + row < blk_end)
+        *reinterpret_cast<uint4*>(out + (size_t)(first_key + row) * D + col * 8) =
+            *reinterpret_cast<const uint4*>(smem + row * OSTR + col * 16);
+    }
+  }
+}
+
+}  // namespace
+
+bool bwd_mfma_supported(const hf_config& c) {
+  return c.dtype == HF_BF16 && c.head_dim == 128 && (c.block_q == 64 || c.block_q == 128);
+}
+
+int launch_bwd_mfma(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
+                    const int32_t* idx, int k, const void* dO, const float* lse2, const float* Dv,
+                    const int32_t* inv_cnt, const int32_t* inv_list, const float* dqh32, void* dQ, void* dK,
+                    void* dV, hipStream_t s) {
+  if (n_kv >= (1 << 23) || n_q >= (1 << 23)) { set_error("more than 2^23 tokens"); return HF_ERR_SHAPE; }
+  const int BH = c.batch * c.heads;
+  const int t_m = (n_q + c.block_q - 1) / c.block_q, t_n = (n_kv + c.block_kv - 1) / c.block_kv;
+  const float scale = c.softmax_scale > 0.0f ? c.softmax_scale : 1.0f / sqrtf((float)c.head_dim);
+  const float c_scale = scale * 1.4426950408889634f;
+  const int kvs = kv_stride_of(c, n_kv);
+  const bf16_t* q = static_cast<const bf16_t*>(Q);
+  const bf16_t* kk = static_cast<const bf16_t*>(K);
+  const bf16_t* v = static_cast<const bf16_t*>(V);
+  const bf16_t* g = static_cast<const bf16_t*>(dO);
+#define HF_LAUNCH_DQ(NWV)                                                                                      \
+  hipLaunchKernelGGL((bwd_dq_mfma_kernel<NWV>), dim3(t_m, BH), dim3(64 * NWV), 0, s, q, kk, v, g, idx, k, n_q, \
+                     n_kv, kvs, c.block_kv, t_m, t_n, c_scale, scale, lse2, Dv, dqh32, static_cast<bf16_t*>(dQ))
+  if (c.block_q == 64) HF_LAUNCH_DQ(2); else HF_LAUNCH_DQ(4);
+#undef HF_LAUNCH_DQ
+  int rc = check_launch("hf_hybrid_attn_bwd(dQ)");
+  if (rc != HF_OK) return rc;
+  // wavefronts of 32 keys: 1, 2 or 4 per workgroup, as many workgroups (slabs) per KV block as it takes
+  const int subs = (c.block_kv + 31) / 32;
+  const int nw = subs >= 4 ? 4 : (subs >= 2 ? 2 : 1);
+  const int slabs = (subs + nw - 1) / nw;
+  if ((long long)t_n * slabs > 0x7fffffffll) { set_error("too many KV slabs"); return HF_ERR_SHAPE; }
+#define HF_LAUNCH_DKV(NWV)                                                                                       \
+  hipLaunchKernelGGL((bwd_dkv_mfma_kernel<NWV>), dim3(t_n * slabs, BH), dim3(64 * NWV), 0, s, q, kk, v, g, inv_cnt, \
+                     inv_list, n_q, n_kv, kvs, c.block_q, c.block_kv, t_m, t_n, slabs, c_scale, scale, lse2, Dv,    \
+                     static_cast<bf16_t*>(dK), static_cast<bf16_t*>(dV))
+  if (nw == 4) HF_LAUNCH_DKV(4); else if (nw == 2) HF_LAUNCH_DKV(2); else HF_LAUNCH_DKV(1);
+#undef HF_LAUNCH_DKV
+  return check_launch("hf_hybrid_attn_bwd(dK, dV)");
+}
+
+}  // namespace hf

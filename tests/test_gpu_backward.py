@@ -5,6 +5,8 @@ split queries, the dense window, a cache buffer with spare capacity.
 Bounds.  fp32 storage: rel-L2 <= 5e-5 (fp32 exp2 and accumulation; dS = P (dP - D) subtracts two O(1) numbers, which
 costs a few units over the forward's 1e-5).  bf16 storage: rel-L2 <= 1e-2 and max-abs <= 2e-2 of the largest
 gradient magnitude, the forward's bounds (inputs are exact in both; the output rounding alone is 2^-9)."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -151,3 +153,35 @@ def test_gradients_in_a_cache_buffer_layout():
     assert torch.equal(a[0], b[0])
     assert torch.equal(a[1], b[1][:, :, :w.n_kv]) and torch.equal(a[2], b[2][:, :, :w.n_kv])
     assert b[1][:, :, w.n_kv:].isnan().all()          # nothing behind the valid tokens is written
+
+
+@pytest.mark.parametrize("name,block_kv,force_generic", [("small_bf16", 64, True), ("small_bf16", 100, False),
+                                                         ("small_bf16", 32, False), ("small_b128", 200, False)])
+def test_bf16_kernel_choices_and_key_blocks_that_are_no_multiple_of_a_tile(name, block_kv, force_generic):
+    """bf16 through the fp32-arithmetic kernels as well, and KV blocks whose length is not a multiple of the
+    32-key tile of the matrix-core kernels (a tile then ends inside the next block and must be cut)."""
+    w = wl.get(name)
+    cfg = cfg_of(w, block_kv=block_kv)
+    st, ref_states = make_state(cfg, w, hf.HF_PHI_RELU, False)
+    Q, K, V = wl.make_qkv(w, q_gain=1.5)
+    dO = wl.randn(Q.shape, 95_000 + block_kv, 1.0, w.torch_dtype)
+    k = hf.hf_select_k(cfg, w.n_kv)
+    t_n = -(-w.n_kv // block_kv)
+    idx = torch.full((w.batch, w.heads, w.t_m, k), -1, dtype=torch.int32, device=DEV)
+    ws = torch.empty(hf.hf_workspace_bytes(cfg, w.n_q, w.n_kv), dtype=torch.uint8, device=DEV)
+    hf.hf_block_select(cfg, Q.to(DEV), K.to(DEV), idx, None, ws)
+    torch.cuda.synchronize()
+    if force_generic:
+        os.environ["HF_BWD_KERNEL"] = "g"
+    try:
+        dQ, dK, dV, _ = run_bwd(cfg, w, Q, K, V, idx, st, dO)
+    finally:
+        os.environ.pop("HF_BWD_KERNEL", None)
+    idxc = idx.cpu().numpy()
+    assert idxc.max() < t_n
+    for h, (q, kk, v, g) in enumerate(zip(heads_of(Q), heads_of(K), heads_of(V), heads_of(dO))):
+        rql, rqh, rk, rv = orc.hybrid_attention_bwd(q, kk, v, ref_states[h], w.block, block_kv, idxc[0, h], g,
+                                                    eps=cfg.eps, z_scale=cfg.z_scale)
+        check("dQ", wl.to_f64(dQ)[0, h], rql + rqh, w)
+        check("dK", wl.to_f64(dK)[0, h], rk, w)
+        check("dV", wl.to_f64(dV)[0, h], rv, w)
