@@ -43,6 +43,7 @@ def parse():
                    help="rotate phi(k) / phi(q) of the history branch with synthetic per-token tables (default: none)")
     p.add_argument("--no-dense", action="store_true",
                    help="skip the dense comparator launches (they share the sparse kernel's name in a profile)")
+    p.add_argument("--no-backward", action="store_true", help="skip the timing of the backward pass (training step)")
     p.add_argument("--eager", action="store_true",
                    help="time eager single-stream launches instead of one captured HIP graph per step")
     p.add_argument("--cpu-heads", type=int, default=0, help="heads per layer the oracle is timed on (0 = all)")
@@ -243,6 +244,17 @@ def main():
     rope_bytes = 2 * w.batch * w.heads * w.n_kv * w.head_dim * esz + 2 * kc.numel() * 4
     del k_rot
 
+    # the training algorithm's gradient step (outside the timed step, which is the inference path): dQ, dK, dV of
+    # one layer call, row statistics recomputed
+    bwd_ms = None
+    if not a.no_backward:
+        bws = torch.empty(hf.hf_bwd_workspace_bytes(cfg, w.n_q, w.n_kv), dtype=torch.uint8, device=dev)
+        dO = wl.randn(sets[0]["Q"].shape, 96_000, 1.0, w.torch_dtype).to(dev)
+        dQ, dK, dV = torch.empty_like(sets[0]["Q"]), torch.empty_like(sets[0]["K"]), torch.empty_like(sets[0]["V"])
+        bwd_ms, _ = time_calls(lambda s: hf.hf_hybrid_attn_bwd(cfg, s["Q"], s["K"], s["V"], s["idx"], s["st"], dO, dQ, dK,
+                                                               dV, bws), max(3, min(a.steps, 12)))
+        del bws, dO, dQ, dK, dV
+
     flops = float(np.mean([algorithmic_flops(s["idx"].cpu(), w) for s in sets]))
     dense_flops = 4.0 * w.head_dim * w.n_q * w.n_kv * w.heads * w.batch
     bh = w.batch * w.heads
@@ -289,6 +301,10 @@ def main():
                 "bytes": {"absorb": absorb_bytes, "readout": readout_bytes, "select": select_bytes,
                           "rope_apply": rope_bytes}},
     }
+    if bwd_ms is not None:
+        # five products of the forward's size (S, dP, dV, dK, dQ) count; the recomputation does not
+        out["backward"] = {"ms": bwd_ms, "tflops": 2.5 * flops / (bwd_ms * 1e-3) / 1e12,
+                           "frac_of_bf16_peak": 2.5 * flops / (bwd_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
     if dense_ms is not None:
         out["dense"] = {"tflops": dense_flops / (dense_ms * 1e-3) / 1e12,
                         "speedup_sparse_incl_select": dense_ms / (sel_ms + a4_ms),

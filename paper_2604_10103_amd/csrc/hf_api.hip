@@ -101,7 +101,7 @@ static WorkspaceLayout workspace_layout(const hf_config* c, int n_q, int n_kv) {
 }
 
 struct BwdLayout {
-  size_t lse2, dvec, dqh32, inv_cnt, inv_list, total;  // byte offsets
+  size_t lse2, dvec, dqh32, inv_cnt, inv_list, planes, total;  // byte offsets
 };
 
 static BwdLayout bwd_layout(const hf_config* c, int n_q, int n_kv) {
@@ -113,7 +113,8 @@ static BwdLayout bwd_layout(const hf_config* c, int n_q, int n_kv) {
   w.dqh32 = w.dvec + align256(bh * n_q * 4);
   w.inv_cnt = w.dqh32 + align256(bh * (size_t)n_q * d * 4);
   w.inv_list = w.inv_cnt + align256(bh * t_n * 4);
-  w.total = w.inv_list + align256(bh * t_n * t_m * 4);
+  w.planes = w.inv_list + align256(bh * t_n * t_m * 4);
+  w.total = w.planes + align256(bwd_planes_bytes(*c));
   return w;
 }
 
@@ -479,6 +480,20 @@ int hf_hybrid_attn_bwd(const hf_config* cfg, const void* Q, const void* Q_hist, 
   int32_t* inv_list = block_idx ? reinterpret_cast<int32_t*>(ws + w.inv_list) : nullptr;
   const float* st = static_cast<const float*>(state_or_null);
 
+  const char* pick = getenv("HF_BWD_KERNEL");   // development switch: "g" forces the fp32-arithmetic kernels
+  const bool mfma = bwd_mfma_supported(*cfg) && !(pick && pick[0] == 'g');
+  if (split && !st) {
+    const size_t bytes = (size_t)cfg->batch * cfg->heads * n_q * cfg->head_dim * esize(cfg);
+    HF_TRY(launch_fill_zero(static_cast<float*>(dQ_hist), bytes / 4, s));
+  }
+  if (block_idx) HF_TRY(launch_invert_index(*cfg, block_idx, k, t_m, t_n, inv_cnt, inv_list, s));
+  if (mfma) {
+    // row statistics of the softmax and D = dO . O_local (unrounded) from a recomputed forward pass; the history
+    // branch rides in the dQ kernel's epilogue
+    HF_TRY(launch_attn_mfma_stats(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, dO, lse2, dvec, s));
+    return launch_bwd_mfma(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, dO, lse2, dvec, inv_cnt, inv_list, st,
+                           rope_cos_q, rope_sin_q, Q_hist, ws + w.planes, dQ, dQ_hist, dK, dV, s);
+  }
   // history branch first: its gradient either is an output of its own or joins dQ before dQ's one rounding
   const float* add_to_dq = nullptr;
   if (st) {
@@ -488,19 +503,8 @@ int hf_hybrid_attn_bwd(const hf_config* cfg, const void* Q, const void* Q_hist, 
       HF_TRY(launch_bwd_hist_generic(*cfg, Q_hist, dO, st, n_q, rope_cos_q, rope_sin_q, dqh32, true, s));
       add_to_dq = dqh32;
     }
-  } else if (split) {
-    const size_t bytes = (size_t)cfg->batch * cfg->heads * n_q * cfg->head_dim * esize(cfg);
-    HF_TRY(launch_fill_zero(static_cast<float*>(dQ_hist), bytes / 4, s));
   }
-  // row statistics of the softmax and D = dO . O_local (unrounded) from a recomputed forward pass
-  const char* pick = getenv("HF_BWD_KERNEL");   // development switch: "g" forces the fp32-arithmetic kernels
-  const bool mfma = bwd_mfma_supported(*cfg) && !(pick && pick[0] == 'g');
-  if (mfma) HF_TRY(launch_attn_mfma_stats(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, dO, lse2, dvec, s));
-  else HF_TRY(launch_attn_generic(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, nullptr, s, lse2, dO, dvec));
-  if (block_idx) HF_TRY(launch_invert_index(*cfg, block_idx, k, t_m, t_n, inv_cnt, inv_list, s));
-  if (mfma)
-    return launch_bwd_mfma(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, dO, lse2, dvec, inv_cnt, inv_list,
-                           add_to_dq, dQ, dK, dV, s);
+  HF_TRY(launch_attn_generic(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, nullptr, s, lse2, dO, dvec));
   return launch_bwd_generic(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, dO, lse2, dvec, inv_cnt, inv_list,
                             add_to_dq, dQ, dK, dV, s);
 }

@@ -18,22 +18,28 @@
 namespace hf {
 namespace {
 
-// ---- inverse of the index lists: for every KV block the query blocks whose row holds it ------------
+// ---- inverse of the index lists: for every KV block the query blocks whose row holds it, ascending ----
+// One wavefront per (head, KV block): lane = query block, 64 at a time; a ballot and a prefix count compact
+// the hits in order.
 __global__ __launch_bounds__(256) void invert_index_kernel(const int32_t* __restrict__ idx, int k, int t_m, int t_n,
                                                            int32_t* __restrict__ inv_cnt,
                                                            int32_t* __restrict__ inv_list) {
-  const int bh = blockIdx.x;
+  const int lane = threadIdx.x & 63;
+  const int j = blockIdx.x * 4 + (threadIdx.x >> 6), bh = blockIdx.y;
+  if (j >= t_n) return;
   const int32_t* rows = idx + (size_t)bh * t_m * k;
-  for (int j = threadIdx.x; j < t_n; j += 256) {
-    int32_t* out = inv_list + ((size_t)bh * t_n + j) * t_m;
-    int cnt = 0;
-    for (int i = 0; i < t_m; ++i) {
-      bool hit = false;
-      for (int s = 0; s < k; ++s) hit |= rows[(size_t)i * k + s] == j;
-      if (hit) out[cnt++] = i;   // by contract a row lists a block at most once
-    }
-    inv_cnt[(size_t)bh * t_n + j] = cnt;
+  int32_t* out = inv_list + ((size_t)bh * t_n + j) * t_m;
+  int cnt = 0;
+  for (int i0 = 0; i0 < t_m; i0 += kWave) {
+    const int i = i0 + lane;
+    bool hit = false;
+    if (i < t_m)
+      for (int s = 0; s < k; ++s) hit |= rows[(size_t)i * k + s] == j;   // by contract a row lists a block at most once
+    const unsigned long long mask = __ballot(hit);
+    if (hit) out[cnt + __popcll(mask & ((1ull << lane) - 1ull))] = i;
+    cnt += __popcll(mask);
   }
+  if (lane == 0) inv_cnt[(size_t)bh * t_n + j] = cnt;
 }
 
 // ---- dQ: R query rows per wavefront, lanes = keys for the dot products, lanes = features for dQ ------
@@ -346,8 +352,8 @@ __global__ __launch_bounds__(256) void bwd_hist_generic_kernel(const T* __restri
 
 int launch_invert_index(const hf_config& c, const int32_t* idx, int k, int t_m, int t_n, int32_t* inv_cnt,
                         int32_t* inv_list, hipStream_t s) {
-  hipLaunchKernelGGL(invert_index_kernel, dim3(c.batch * c.heads), dim3(256), 0, s, idx, k, t_m, t_n, inv_cnt,
-                     inv_list);
+  hipLaunchKernelGGL(invert_index_kernel, dim3((t_n + 3) / 4, c.batch * c.heads), dim3(256), 0, s, idx, k, t_m, t_n,
+                     inv_cnt, inv_list);
   return check_launch("hf_hybrid_attn_bwd(inverse lists)");
 }
 

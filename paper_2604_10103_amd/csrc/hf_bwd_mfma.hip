@@ -129,16 +129,55 @@ __device__ __forceinline__ void stage_rows(char* stage, int row, int h, const f3
     }
 }
 
+// History branch (Eq. 3) in the dQ kernel's epilogue: with f = phi(q), r = R f, den = z_scale f.z + eps
+//     num^T = Lt r^T            (first plane:  Lt[j][i] = bf16(L[i][j]), rows = value features)
+//     dden  = -(dO . num) / den^2
+//     t^T   = L (dO / den)^T    (second plane: bf16(L[i][j]), rows = key features)
+//     dq    = (R^T t + z_scale dden z) * phi'(q)
+// Both products have the query fragments' layout on the B side (lane = query row), so the result lands
+// in the accumulator layout of dQ and joins it before the one rounding (kHist 1) or is stored as the
+// gradient of a query tensor of its own (kHist 2).
+struct BwdHist {
+  const bf16_t* planes;   // [BH][2][d][d]
+  const float* zvec;      // [BH][d]
+  const float* cosq;      // [n_q][d/2] or NULL
+  const float* sinq;
+  const bf16_t* q_hist;   // [BH][n_q][d] queries of the history branch (kHist 2)
+  bf16_t* dq_hist;        // [BH][n_q][d] their gradient (kHist 2)
+  float eps, z_scale;
+  int phi_kind;
+};
+constexpr int PSTR = 272;   // bytes per row of a staged state plane (256 + 16)
+
+// fp32 state -> the two bf16 planes of the backward pass: Lt (transposed) and L
+__global__ __launch_bounds__(256) void state_planes_bwd_kernel(const float* __restrict__ state,
+                                                               bf16_t* __restrict__ planes) {
+  __shared__ float tile[32][33];
+  const int bh = blockIdx.z, i0 = blockIdx.y * 32, j0 = blockIdx.x * 32;
+  const float* L = state + (size_t)bh * D * D;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+  bf16_t* lt = planes + (size_t)bh * 2 * D * D;
+  bf16_t* ln = lt + D * D;
+  for (int r = ty; r < 32; r += 8) {
+    const float v = L[(size_t)(i0 + r) * D + j0 + tx];
+    tile[r][tx] = v;
+    ln[(size_t)(i0 + r) * D + j0 + tx] = f32_to_bf16(v);
+  }
+  __syncthreads();
+  for (int r = ty; r < 32; r += 8) lt[(size_t)(j0 + r) * D + i0 + tx] = f32_to_bf16(tile[tx][r]);
+}
+
 // ---------------------------------------------------------------------------------------------- dQ
-template <int NW>
+template <int NW, int kHist>
 __global__ __launch_bounds__(64 * NW) void bwd_dq_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const int32_t* __restrict__ idx, int k, int n_q, int n_kv, int kv_stride, int bkv,
     int t_m, int t_n, float c_scale, float scale, const float* __restrict__ lse2, const float* __restrict__ Dv,
-    const float* __restrict__ dqh32, bf16_t* __restrict__ dQ) {
+    BwdHist hist, bf16_t* __restrict__ dQ) {
   constexpr int NT = 64 * NW;
   constexpr int BQ = 32 * NW;
   __shared__ __attribute__((aligned(16))) char smem[2 * RTILE + TTILE];
+  static_assert(D * PSTR <= 2 * RTILE + TTILE, "a state plane must fit in the tiles' space");
   char* const sK = smem;
   char* const sV = smem + RTILE;
   uint32_t* const sKt = reinterpret_cast<uint32_t*>(smem + 2 * RTILE);
@@ -209,31 +248,145 @@ __global__ __launch_bounds__(64 * NW) void bwd_dq_mfma_kernel(
     }
   }
 
-  // the history branch's share joins before the one rounding
-  if (dqh32 && q_row < n_q) {
-    const float* g = dqh32 + ((size_t)bh * n_q + q_row) * D;
-    const float inv = 1.0f / scale;
+  f32x16 acc[4];   // history branch: num^T, then t^T, then the gradient itself
+  if (kHist) {
+    bf16x8 hq[8];
+    if (kHist == 2) {
+      row_frags(rsrc_of(hist.q_hist + (size_t)bh * n_q * D, n_q), q_row, h, hq);
+    } else {
+#pragma unroll
+      for (int s = 0; s < 8; ++s) hq[s] = qf[s];
+    }
+    const int crow = min(q_row, n_q - 1);
+    const float* zv = hist.zvec + (size_t)bh * D;
+    // f = phi(q), den = z_scale f.z + eps, r = R f as bf16 fragments
+    bf16x8 rf[8];
+    float den = 0.0f;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      float f[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) f[e] = phi_apply(static_cast<float>(hq[s][e]), hist.phi_kind);
+      const float4 z0 = *reinterpret_cast<const float4*>(zv + 16 * s + 8 * h);
+      const float4 z1 = *reinterpret_cast<const float4*>(zv + 16 * s + 8 * h + 4);
+      den += f[0] * z0.x + f[1] * z0.y + f[2] * z0.z + f[3] * z0.w + f[4] * z1.x + f[5] * z1.y + f[6] * z1.z +
+             f[7] * z1.w;
+      if (hist.cosq) {
+        const size_t tp = (size_t)crow * (D / 2) + 8 * s + 4 * h;
+        const float4 c4 = *reinterpret_cast<const float4*>(hist.cosq + tp);
+        const float4 s4 = *reinterpret_cast<const float4*>(hist.sinq + tp);
+        const float cc[4] = {c4.x, c4.y, c4.z, c4.w}, ss[4] = {s4.x, s4.y, s4.z, s4.w};
+#pragma unroll
+        for (int p2 = 0; p2 < 4; ++p2) {
+          const float a = f[2 * p2], b = f[2 * p2 + 1];
+          f[2 * p2] = a * cc[p2] - b * ss[p2];
+          f[2 * p2 + 1] = a * ss[p2] + b * cc[p2];
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) rf[s][e] = static_cast<__bf16>(f[e]);
+    }
+    {
+      const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(den), __float_as_uint(den), false, false);
+      den = hist.z_scale * (__uint_as_float(sw[0]) + __uint_as_float(sw[1])) + hist.eps;
+    }
+    const float inv_den = 1.0f / den;
+
+    constexpr int PCH = (D * D * 2 / 16) / NT;   // 16-byte chunks of one plane per thread
+    const u32x4* gp = reinterpret_cast<const u32x4*>(hist.planes + (size_t)bh * 2 * D * D);
+    float dden = 0.0f;
+    bf16x8 dn[8];
+    for (int plane = 0; plane < 2; ++plane) {
+      u32x4 preg[PCH];
+#pragma unroll
+      for (int i = 0; i < PCH; ++i) preg[i] = gp[plane * (D * D * 2 / 16) + tid + NT * i];
+      __syncthreads();   // the tiles, or the previous plane, are consumed
+#pragma unroll
+      for (int i = 0; i < PCH; ++i) {
+        const int c = tid + NT * i;
+        *reinterpret_cast<u32x4*>(smem + (c >> 4) * PSTR + (c & 15) * 16) = preg[i];
+      }
+      __syncthreads();
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[dt][r] = 0.0f;
+#pragma unroll
+      for (int s = 0; s < 8; ++s)
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
+          const bf16x8 a = *reinterpret_cast<const bf16x8*>(smem + (32 * dt + l32) * PSTR + 16 * h + 32 * s);
+          acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, plane ? dn[s] : rf[s], acc[dt], 0, 0, 0);
+        }
+      if (plane == 0) {
+        // dden = -(dO . num) / den^2 ; dnum = dO / den as the next B operand
+        const bf16_t* gq = dO + ((size_t)bh * n_q + crow) * D + 4 * h;
+        float gn = 0.0f;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+          for (int rq = 0; rq < 4; ++rq) {
+            const uint2 w = *reinterpret_cast<const uint2*>(gq + 32 * dt + 8 * rq);
+            gn = fmaf(acc[dt][4 * rq], __uint_as_float(w.x << 16), gn);
+            gn = fmaf(acc[dt][4 * rq + 1], __uint_as_float(w.x & 0xffff0000u), gn);
+            gn = fmaf(acc[dt][4 * rq + 2], __uint_as_float(w.y << 16), gn);
+            gn = fmaf(acc[dt][4 * rq + 3], __uint_as_float(w.y & 0xffff0000u), gn);
+          }
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(gn), __float_as_uint(gn), false, false);
+        dden = -(__uint_as_float(sw[0]) + __uint_as_float(sw[1])) * inv_den * inv_den;
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) dn[s][e] = static_cast<__bf16>(static_cast<float>(dof[s][e]) * inv_den);
+      }
+    }
+    // back through the rotation, the denominator's share, phi'
+    const bf16_t* qsrc = (kHist == 2 ? hist.q_hist : Q) + ((size_t)bh * n_q + crow) * D + 4 * h;
+    const float zd = hist.z_scale * dden;
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
       for (int rq = 0; rq < 4; ++rq) {
-        const float4 a = *reinterpret_cast<const float4*>(g + 32 * dt + 8 * rq + 4 * h);
-        dq[dt][4 * rq] += a.x * inv;
-        dq[dt][4 * rq + 1] += a.y * inv;
-        dq[dt][4 * rq + 2] += a.z * inv;
-        dq[dt][4 * rq + 3] += a.w * inv;
+        const int f0 = 32 * dt + 8 * rq + 4 * h;
+        float t[4] = {acc[dt][4 * rq], acc[dt][4 * rq + 1], acc[dt][4 * rq + 2], acc[dt][4 * rq + 3]};
+        if (hist.cosq) {
+          const float2 c2 = *reinterpret_cast<const float2*>(hist.cosq + (size_t)crow * (D / 2) + f0 / 2);
+          const float2 s2 = *reinterpret_cast<const float2*>(hist.sinq + (size_t)crow * (D / 2) + f0 / 2);
+          const float a0 = t[0], b0 = t[1], a1 = t[2], b1 = t[3];
+          t[0] = a0 * c2.x + b0 * s2.x;
+          t[1] = -a0 * s2.x + b0 * c2.x;
+          t[2] = a1 * c2.y + b1 * s2.y;
+          t[3] = -a1 * s2.y + b1 * c2.y;
+        }
+        const float4 z4 = *reinterpret_cast<const float4*>(zv + f0);
+        const float zz[4] = {z4.x, z4.y, z4.z, z4.w};
+        const uint2 w = *reinterpret_cast<const uint2*>(qsrc + 32 * dt + 8 * rq);
+        const float qv[4] = {__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xffff0000u),
+                             __uint_as_float(w.y << 16), __uint_as_float(w.y & 0xffff0000u)};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float dphi = hist.phi_kind == HF_PHI_RELU ? (qv[i] > 0.0f ? 1.0f : 0.0f)
+                                                          : (qv[i] > 0.0f ? 1.0f : __expf(qv[i]));
+          const float g = (t[i] + zd * zz[i]) * dphi;
+          if (kHist == 1) dq[dt][4 * rq + i] = fmaf(dq[dt][4 * rq + i], scale, g);
+          else acc[dt][4 * rq + i] = g;
+        }
       }
   }
-  __syncthreads();
-  stage_rows(smem, 32 * wave + l32, h, dq, scale);
-  __syncthreads();
   bf16_t* dQh = dQ + (size_t)bh * n_q * D;
+  for (int which = 0; which < (kHist == 2 ? 2 : 1); ++which) {
+    __syncthreads();
+    if (which == 0) stage_rows(smem, 32 * wave + l32, h, dq, kHist == 1 ? 1.0f : scale);
+    else stage_rows(smem, 32 * wave + l32, h, acc, 1.0f);
+    __syncthreads();
+    bf16_t* out = which ? hist.dq_hist + (size_t)bh * n_q * D : dQh;
 #pragma unroll
-  for (int i = 0; i < (BQ * 16) / NT; ++i) {
-    const int c = tid + NT * i, row = c >> 4, col = c & 15;
-    if (qb * BQ + row < n_q)
-      *reinterpret_cast<uint4*>(dQh + (size_t)(qb * BQ + row) * D + col * 8) =
-          *reinterpret_cast<const uint4*>(smem + row * OSTR + col * 16);
+    for (int i = 0; i < (BQ * 16) / NT; ++i) {
+      const int c = tid + NT * i, row = c >> 4, col = c & 15;
+      if (qb * BQ + row < n_q)
+        *reinterpret_cast<uint4*>(out + (size_t)(qb * BQ + row) * D + col * 8) =
+            *reinterpret_cast<const uint4*>(smem + row * OSTR + col * 16);
+    }
   }
 }
 
@@ -359,9 +512,15 @@ bool bwd_mfma_supported(const hf_config& c) {
   return c.dtype == HF_BF16 && c.head_dim == 128 && (c.block_q == 64 || c.block_q == 128);
 }
 
+size_t bwd_planes_bytes(const hf_config& c) {
+  return bwd_mfma_supported(c) ? (size_t)c.batch * c.heads * 2 * D * D * sizeof(bf16_t) : 0;
+}
+
+// state == NULL: no history branch.  Q_hist != Q: its gradient goes to dQ_hist, else it joins dQ.
 int launch_bwd_mfma(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
                     const int32_t* idx, int k, const void* dO, const float* lse2, const float* Dv,
-                    const int32_t* inv_cnt, const int32_t* inv_list, const float* dqh32, void* dQ, void* dK,
+                    const int32_t* inv_cnt, const int32_t* inv_list, const float* state, const float* cosq,
+                    const float* sinq, const void* Q_hist, void* planes, void* dQ, void* dQ_hist, void* dK,
                     void* dV, hipStream_t s) {
   if (n_kv >= (1 << 23) || n_q >= (1 << 23)) { set_error("more than 2^23 tokens"); return HF_ERR_SHAPE; }
   const int BH = c.batch * c.heads;
@@ -373,10 +532,29 @@ int launch_bwd_mfma(const hf_config& c, const void* Q, int n_q, const void* K, c
   const bf16_t* kk = static_cast<const bf16_t*>(K);
   const bf16_t* v = static_cast<const bf16_t*>(V);
   const bf16_t* g = static_cast<const bf16_t*>(dO);
-#define HF_LAUNCH_DQ(NWV)                                                                                      \
-  hipLaunchKernelGGL((bwd_dq_mfma_kernel<NWV>), dim3(t_m, BH), dim3(64 * NWV), 0, s, q, kk, v, g, idx, k, n_q, \
-                     n_kv, kvs, c.block_kv, t_m, t_n, c_scale, scale, lse2, Dv, dqh32, static_cast<bf16_t*>(dQ))
-  if (c.block_q == 64) HF_LAUNCH_DQ(2); else HF_LAUNCH_DQ(4);
+  const int hist_mode = !state ? 0 : (Q_hist != Q ? 2 : 1);
+  BwdHist hist = {};
+  if (hist_mode) {
+    hipLaunchKernelGGL(state_planes_bwd_kernel, dim3(D / 32, D / 32, BH), dim3(256), 0, s, state,
+                       static_cast<bf16_t*>(planes));
+    hist.planes = static_cast<const bf16_t*>(planes);
+    hist.zvec = state + (size_t)BH * D * D;
+    hist.cosq = cosq;
+    hist.sinq = sinq;
+    hist.q_hist = static_cast<const bf16_t*>(Q_hist);
+    hist.dq_hist = static_cast<bf16_t*>(dQ_hist);
+    hist.eps = c.eps;
+    hist.z_scale = c.z_scale;
+    hist.phi_kind = c.phi;
+  }
+#define HF_LAUNCH_DQ(NWV, HM)                                                                                      \
+  hipLaunchKernelGGL((bwd_dq_mfma_kernel<NWV, HM>), dim3(t_m, BH), dim3(64 * NWV), 0, s, q, kk, v, g, idx, k, n_q, \
+                     n_kv, kvs, c.block_kv, t_m, t_n, c_scale, scale, lse2, Dv, hist, static_cast<bf16_t*>(dQ))
+  if (c.block_q == 64) {
+    if (hist_mode == 0) HF_LAUNCH_DQ(2, 0); else if (hist_mode == 1) HF_LAUNCH_DQ(2, 1); else HF_LAUNCH_DQ(2, 2);
+  } else {
+    if (hist_mode == 0) HF_LAUNCH_DQ(4, 0); else if (hist_mode == 1) HF_LAUNCH_DQ(4, 1); else HF_LAUNCH_DQ(4, 2);
+  }
 #undef HF_LAUNCH_DQ
   int rc = check_launch("hf_hybrid_attn_bwd(dQ)");
   if (rc != HF_OK) return rc;

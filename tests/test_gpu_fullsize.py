@@ -235,3 +235,31 @@ def test_layer_stack_with_frozen_cache_and_state():
             torch.cuda.synchronize()
             check_heads(w, cfg, L.k, Q, K, V, L.O, L.idx, states, heads if step in (0, 3) else heads[:1])
         assert torch.equal(L.state, state_before)      # attention never touches the state
+
+
+@pytest.mark.parametrize("name,heads", [("step_832x480", (0, 7)), ("large_1280x720", (33,))])
+def test_backward_at_full_size_sampled_heads(name, heads):
+    """Gradients of one layer call at the benchmark's shapes against the oracle on sampled heads (the training
+    algorithm's step with gradients enabled; state constant, mask fixed)."""
+    w = wl.get(name)
+    cfg = cfg_of(w)
+    L = Layer(cfg, w)
+    Ke, Ve = cached((name, "ev0"), lambda: wl.make_evicted(w, 0))
+    L.absorb(Ke.to(DEV), Ve.to(DEV))
+    Q, K, V = cached((name, "qkv"), lambda: wl.make_qkv(w))
+    dO = wl.randn(Q.shape, 96_000 + w.cfg, 1.0, w.torch_dtype)
+    Qd, Kd, Vd = Q.to(DEV), K.to(DEV), V.to(DEV)
+    hf.hf_block_select(cfg, Qd, Kd, L.idx, None, L.ws)
+    dQ, dK, dV = torch.empty_like(Qd), torch.empty_like(Kd), torch.empty_like(Vd)
+    ws = torch.empty(hf.hf_bwd_workspace_bytes(cfg, w.n_q, w.n_kv), dtype=torch.uint8, device=DEV)
+    hf.hf_hybrid_attn_bwd(cfg, Qd, Kd, Vd, L.idx, L.state, dO.to(DEV), dQ, dK, dV, ws)
+    torch.cuda.synchronize()
+    idxc = L.idx.cpu().numpy()
+    for h in heads:
+        st = orc.state_absorb(*orc.state_zero(w.head_dim), wl.to_f64(Ke[0, h]), wl.to_f64(Ve[0, h]))
+        rql, rqh, rk, rv = orc.hybrid_attention_bwd(wl.to_f64(Q[0, h]), wl.to_f64(K[0, h]), wl.to_f64(V[0, h]), st,
+                                                    w.block, w.block, idxc[0, h], wl.to_f64(dO[0, h]), eps=cfg.eps)
+        for nm, got, ref in (("dQ", dQ, rql + rqh), ("dK", dK, rk), ("dV", dV, rv)):
+            g = wl.to_f64(got[0, h])
+            assert rel_l2(g, ref) <= BF16_REL_L2, (nm, h, rel_l2(g, ref))
+            assert max_abs(g, ref) <= BF16_MAX_ABS * max(np.abs(ref).max(), 1e-30)
