@@ -7,8 +7,8 @@
 //      S^T  = K Q^T          dP^T = V dO^T            lane = query row, registers = keys
 //      dS^T = 2^(c S^T - lse2) * (dP^T - D)           -> bf16, B operand
 //      dQ^T += K^T dS^T                               A operand = K transposed in LDS
-//  dK, dV  (one workgroup per slab of a KV block, one wavefront per 32 keys, tiles of 32 query rows
-//      taken from the inverse index lists)
+//  dK, dV  (one workgroup per 64 keys of a KV block, a wavefront per 32 keys x 64 features, tiles of 32
+//      query rows taken from the inverse index lists)
 //      S  = Q K^T            dP = dO V^T              lane = key, registers = query rows
 //      P  = 2^(c S - lse2),  dS = P * (dP - D)        -> bf16, B operands
 //      dV^T += dO^T P        dK^T += Q^T dS           A operands = dO, Q transposed in LDS
@@ -169,7 +169,7 @@ __global__ __launch_bounds__(256) void state_planes_bwd_kernel(const float* __re
 
 // ---------------------------------------------------------------------------------------------- dQ
 template <int NW, int kHist>
-__global__ __launch_bounds__(64 * NW) void bwd_dq_mfma_kernel(
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2))) void bwd_dq_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const int32_t* __restrict__ idx, int k, int n_q, int n_kv, int kv_stride, int bkv,
     int t_m, int t_n, float c_scale, float scale, const float* __restrict__ lse2, const float* __restrict__ Dv,
@@ -237,7 +237,8 @@ __global__ __launch_bounds__(64 * NW) void bwd_dq_mfma_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int key = 8 * (r >> 2) + 4 * h + (r & 3);
-        const float p = key < valid ? __builtin_amdgcn_exp2f(fmaf(sacc[r], c_scale, -lse)) : 0.0f;
+        const uint32_t keep = key < valid ? 0xffffffffu : 0u;   // bit mask: a select would become a branch per element
+        const float p = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(sacc[r], c_scale, -lse))) & keep);
         dsf[r >> 3][r & 7] = static_cast<__bf16>(p * (dpacc[r] - dvec));
       }
 #pragma unroll
@@ -391,23 +392,27 @@ __global__ __launch_bounds__(64 * NW) void bwd_dq_mfma_kernel(
 }
 
 // ------------------------------------------------------------------------------------------ dK, dV
-template <int NW>
-__global__ __launch_bounds__(64 * NW) void bwd_dkv_mfma_kernel(
+// One workgroup per slab of 64 keys of a KV block, four wavefronts: wavefront (kw, dh) owns the 32 keys of
+// half kw and the 64 features of half dh of dK and dV.  Both feature halves of a key group form S and dP
+// (16 MFMAs each, done twice) and then only their own 8 + 8 accumulating MFMAs: 64 accumulator registers
+// per wavefront instead of 128, which is what lets two wavefronts share a SIMD.
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void bwd_dkv_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const int32_t* __restrict__ inv_cnt, const int32_t* __restrict__ inv_list,
     int n_q, int n_kv, int kv_stride, int bq, int bkv, int t_m, int t_n, int slabs, float c_scale, float scale,
     const float* __restrict__ lse2, const float* __restrict__ Dv, bf16_t* __restrict__ dK, bf16_t* __restrict__ dV) {
-  constexpr int NT = 64 * NW;
+  constexpr int NT = 256;
   __shared__ __attribute__((aligned(16))) char smem[2 * RTILE + 2 * TTILE + 256];
   char* const sQ = smem;
   char* const sdO = smem + RTILE;
   uint32_t* const sQt = reinterpret_cast<uint32_t*>(smem + 2 * RTILE);
   uint32_t* const sdOt = reinterpret_cast<uint32_t*>(smem + 2 * RTILE + TTILE);
   float* const sStat = reinterpret_cast<float*>(smem + 2 * RTILE + 2 * TTILE);   // lse2[32], D[32]
-  static_assert(32 * NW * OSTR <= 2 * RTILE + 2 * TTILE, "staged output must fit");
+  static_assert(64 * OSTR <= 2 * RTILE + 2 * TTILE, "staged output must fit");
 
   const int jb = blockIdx.x / slabs, slab = blockIdx.x - jb * slabs, bh = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int kw = wave & 1, dh = wave >> 1;
   const int l32 = lane & 31, h = lane >> 5;
   const Stager st(tid);
   const __amdgpu_buffer_rsrc_t q_rsrc = rsrc_of(Q + (size_t)bh * n_q * D, n_q);
@@ -421,41 +426,53 @@ __global__ __launch_bounds__(64 * NW) void bwd_dkv_mfma_kernel(
 
   // this wavefront's 32 keys; a wavefront past the block's end carries no real key
   const int blk_end = min(n_kv, (jb + 1) * bkv);
-  const int key0 = jb * bkv + 32 * (slab * NW + wave);
+  const int first_key = jb * bkv + 64 * slab;
+  const int key0 = first_key + 32 * kw;
   const int kvalid = min(32, blk_end - key0);          // may be <= 0
   bf16x8 kf[8], vf[8];
   row_frags(k_rsrc, key0 + l32, h, kf);
   row_frags(v_rsrc, key0 + l32, h, vf);
-  const bool key_ok = l32 < kvalid;
+  const uint32_t kmask = l32 < kvalid ? 0xffffffffu : 0u;   // lanes of keys that do not exist contribute nothing
 
-  f32x16 dk[4], dv[4];
+  f32x16 dk[2], dv[2];   // features 64 dh + 32 a + ...
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
+  for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { dk[dt][r] = 0.0f; dv[dt][r] = 0.0f; }
+    for (int r = 0; r < 16; ++r) { dk[a][r] = 0.0f; dv[a][r] = 0.0f; }
 
+  // tiles of 32 query rows of the listed query blocks; the fetch of tile n + 1 (and of its row statistics) is
+  // in flight while tile n is consumed.  A tile past n_q reads zeros and is masked.
   const int qtiles = bq / TT;
-  for (int t = 0; t < n_lists; ++t) {
-    const int qb = list ? list[t] : t;
-    for (int qt = 0; qt < qtiles; ++qt) {
-      const int row0 = qb * bq + TT * qt;
-      if (row0 >= n_q) break;   // uniform
-      u32x4 qreg[512 / NT], dreg[512 / NT];
-      tile_fetch<NT>(st, q_rsrc, row0, qreg);
-      tile_fetch<NT>(st, do_rsrc, row0, dreg);
-      float stat = 0.0f;
-      if (tid < 64) {
-        const int row = min(row0 + (tid & 31), n_q - 1);
-        stat = tid < 32 ? lseh[row] : Dvh[row];
-      }
-      __syncthreads();   // the previous tile is consumed
-      tile_store_rows<NT>(st, qreg, sQ);
-      tile_store_transposed<NT>(st, qreg, sQt);
-      tile_store_rows<NT>(st, dreg, sdO);
-      tile_store_transposed<NT>(st, dreg, sdOt);
-      if (tid < 64) sStat[tid] = stat;
-      __syncthreads();
-
+  const int ntiles = n_lists * qtiles;
+  auto tile_row0 = [&](int n) {   // uniform over the workgroup
+    if (n >= ntiles) return 0;
+    const int t = n / qtiles;
+    return (list ? list[t] : t) * bq + TT * (n - t * qtiles);
+  };
+  auto stat_fetch = [&](int r0) {
+    if (tid >= 64) return 0.0f;
+    const int row = min(r0 + (tid & 31), n_q - 1);
+    return tid < 32 ? lseh[row] : Dvh[row];
+  };
+  int row0_next = tile_row0(0);
+  u32x4 qreg[2], dreg[2];
+  tile_fetch<NT>(st, q_rsrc, row0_next, qreg);
+  tile_fetch<NT>(st, do_rsrc, row0_next, dreg);
+  float stat = stat_fetch(row0_next);
+  for (int n = 0; n < ntiles; ++n) {
+    const int row0 = row0_next;
+    __syncthreads();   // the previous tile is consumed
+    tile_store_rows<NT>(st, qreg, sQ);
+    tile_store_transposed<NT>(st, qreg, sQt);
+    tile_store_rows<NT>(st, dreg, sdO);
+    tile_store_transposed<NT>(st, dreg, sdOt);
+    if (tid < 64) sStat[tid] = stat;
+    __syncthreads();
+    row0_next = tile_row0(n + 1);
+    tile_fetch<NT>(st, q_rsrc, row0_next, qreg);
+    tile_fetch<NT>(st, do_rsrc, row0_next, dreg);
+    stat = stat_fetch(row0_next);
+    {
       f32x16 sacc, dpacc;
 #pragma unroll
       for (int r = 0; r < 16; ++r) { sacc[r] = 0.0f; dpacc[r] = 0.0f; }
@@ -473,8 +490,9 @@ __global__ __launch_bounds__(64 * NW) void bwd_dkv_mfma_kernel(
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int r = 4 * g + i;
-          const int row = row0 + 8 * g + 4 * h + i;
-          const float p = (key_ok && row < n_q) ? __builtin_amdgcn_exp2f(fmaf(sacc[r], c_scale, -ls[i])) : 0.0f;
+          // masked by bit operations: a select around the exponential would become a branch per element
+          const uint32_t keep = (row0 + 8 * g + 4 * h + i < n_q) ? kmask : 0u;
+          const float p = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(sacc[r], c_scale, -ls[i]))) & keep);
           pf[r >> 3][r & 7] = static_cast<__bf16>(p);
           dsf[r >> 3][r & 7] = static_cast<__bf16>(p * (dpacc[r] - ds[i]));
         }
@@ -482,22 +500,31 @@ __global__ __launch_bounds__(64 * NW) void bwd_dkv_mfma_kernel(
 #pragma unroll
       for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt) {
-          dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(transposed_frag(sdOt, l32, h, dt, t2), pf[t2], dv[dt], 0, 0, 0);
-          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(transposed_frag(sQt, l32, h, dt, t2), dsf[t2], dk[dt], 0, 0, 0);
+        for (int a = 0; a < 2; ++a) {
+          dv[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(transposed_frag(sdOt, l32, h, 2 * dh + a, t2), pf[t2], dv[a], 0, 0, 0);
+          dk[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(transposed_frag(sQt, l32, h, 2 * dh + a, t2), dsf[t2], dk[a], 0, 0, 0);
         }
     }
   }
 
   // transpose through LDS and store the rows of real keys, dK first, then dV
-  const int first_key = jb * bkv + 32 * slab * NW;
   for (int which = 0; which < 2; ++which) {
     __syncthreads();
-    stage_rows(smem, 32 * wave + l32, h, which ? dv : dk, which ? 1.0f : scale);
+    const float mul = which ? 1.0f : scale;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        const f32x16& x = which ? dv[a] : dk[a];
+        uint2 w;
+        w.x = (uint32_t)f32_to_bf16(x[4 * rq] * mul) | ((uint32_t)f32_to_bf16(x[4 * rq + 1] * mul) << 16);
+        w.y = (uint32_t)f32_to_bf16(x[4 * rq + 2] * mul) | ((uint32_t)f32_to_bf16(x[4 * rq + 3] * mul) << 16);
+        *reinterpret_cast<uint2*>(smem + (32 * kw + l32) * OSTR + (64 * dh + 32 * a + 8 * rq + 4 * h) * 2) = w;
+      }
     __syncthreads();
     bf16_t* out = (which ? dV : dK) + (size_t)bh * kv_stride * D;
 #pragma unroll
-    for (int i = 0; i < (32 * NW * 16) / NT; ++i) {
+    for (int i = 0; i < (64 * 16) / NT; ++i) {
       const int c = tid + NT * i, row = c >> 4, col = c & 15;
       if (first_key + row < blk_end)
         *reinterpret_cast<uint4*>(out + (size_t)(first_key + row) * D + col * 8) =
@@ -558,17 +585,11 @@ int launch_bwd_mfma(const hf_config& c, const void* Q, int n_q, const void* K, c
 #undef HF_LAUNCH_DQ
   int rc = check_launch("hf_hybrid_attn_bwd(dQ)");
   if (rc != HF_OK) return rc;
-  // wavefronts of 32 keys: 1, 2 or 4 per workgroup, as many workgroups (slabs) per KV block as it takes
-  const int subs = (c.block_kv + 31) / 32;
-  const int nw = subs >= 4 ? 4 : (subs >= 2 ? 2 : 1);
-  const int slabs = (subs + nw - 1) / nw;
+  const int slabs = (c.block_kv + 63) / 64;   // 64 keys per workgroup
   if ((long long)t_n * slabs > 0x7fffffffll) { set_error("too many KV slabs"); return HF_ERR_SHAPE; }
-#define HF_LAUNCH_DKV(NWV)                                                                                       \
-  hipLaunchKernelGGL((bwd_dkv_mfma_kernel<NWV>), dim3(t_n * slabs, BH), dim3(64 * NWV), 0, s, q, kk, v, g, inv_cnt, \
-                     inv_list, n_q, n_kv, kvs, c.block_q, c.block_kv, t_m, t_n, slabs, c_scale, scale, lse2, Dv,    \
-                     static_cast<bf16_t*>(dK), static_cast<bf16_t*>(dV))
-  if (nw == 4) HF_LAUNCH_DKV(4); else if (nw == 2) HF_LAUNCH_DKV(2); else HF_LAUNCH_DKV(1);
-#undef HF_LAUNCH_DKV
+  hipLaunchKernelGGL(bwd_dkv_mfma_kernel, dim3(t_n * slabs, BH), dim3(256), 0, s, q, kk, v, g, inv_cnt, inv_list, n_q,
+                     n_kv, kvs, c.block_q, c.block_kv, t_m, t_n, slabs, c_scale, scale, lse2, Dv,
+                     static_cast<bf16_t*>(dK), static_cast<bf16_t*>(dV));
   return check_launch("hf_hybrid_attn_bwd(dK, dV)");
 }
 
