@@ -172,8 +172,8 @@ template <int NW, int kHist>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2))) void bwd_dq_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const int32_t* __restrict__ idx, int k, int n_q, int n_kv, int kv_stride, int bkv,
-    int t_m, int t_n, float c_scale, float scale, const float* __restrict__ lse2, const float* __restrict__ Dv,
-    BwdHist hist, bf16_t* __restrict__ dQ) {
+    int t_m, int t_n, int items_per_xcd, int total_items, float c_scale, float scale,
+    const float* __restrict__ lse2, const float* __restrict__ Dv, BwdHist hist, bf16_t* __restrict__ dQ) {
   constexpr int NT = 64 * NW;
   constexpr int BQ = 32 * NW;
   __shared__ __attribute__((aligned(16))) char smem[2 * RTILE + TTILE];
@@ -183,7 +183,12 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
   uint32_t* const sKt = reinterpret_cast<uint32_t*>(smem + 2 * RTILE);
   static_assert(BQ * OSTR <= 2 * RTILE + TTILE, "staged output must fit");
 
-  const int qb = blockIdx.x, bh = blockIdx.y;
+  // consecutive workgroup ids go to consecutive XCDs: every XCD gets one contiguous run of (head, query
+  // block) items, so that its L2 holds the keys and values of few heads
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int item = xcd * items_per_xcd + slot;
+  if (slot >= items_per_xcd || item >= total_items) return;
+  const int bh = item / t_m, qb = item - bh * t_m;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, h = lane >> 5;
   const Stager st(tid);
@@ -399,8 +404,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void bwd_dkv_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const int32_t* __restrict__ inv_cnt, const int32_t* __restrict__ inv_list,
-    int n_q, int n_kv, int kv_stride, int bq, int bkv, int t_m, int t_n, int slabs, float c_scale, float scale,
-    const float* __restrict__ lse2, const float* __restrict__ Dv, bf16_t* __restrict__ dK, bf16_t* __restrict__ dV) {
+    int n_q, int n_kv, int kv_stride, int bq, int bkv, int t_m, int t_n, int slabs, int items_per_xcd,
+    int total_items, float c_scale, float scale, const float* __restrict__ lse2, const float* __restrict__ Dv,
+    bf16_t* __restrict__ dK, bf16_t* __restrict__ dV) {
   constexpr int NT = 256;
   __shared__ __attribute__((aligned(16))) char smem[2 * RTILE + 2 * TTILE + 256];
   char* const sQ = smem;
@@ -410,7 +416,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   float* const sStat = reinterpret_cast<float*>(smem + 2 * RTILE + 2 * TTILE);   // lse2[32], D[32]
   static_assert(64 * OSTR <= 2 * RTILE + 2 * TTILE, "staged output must fit");
 
-  const int jb = blockIdx.x / slabs, slab = blockIdx.x - jb * slabs, bh = blockIdx.y;
+  // XCD-aware placement as in the dQ kernel: an XCD's L2 then holds the queries and output gradients of few heads
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int item = xcd * items_per_xcd + slot;
+  if (slot >= items_per_xcd || item >= total_items) return;
+  const int bh = item / (t_n * slabs);
+  const int rest = item - bh * (t_n * slabs);
+  const int jb = rest / slabs, slab = rest - jb * slabs;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int kw = wave & 1, dh = wave >> 1;
   const int l32 = lane & 31, h = lane >> 5;
@@ -574,9 +586,13 @@ int launch_bwd_mfma(const hf_config& c, const void* Q, int n_q, const void* K, c
     hist.z_scale = c.z_scale;
     hist.phi_kind = c.phi;
   }
+  const long long q_items = (long long)BH * t_m;
+  if (q_items > (1ll << 30)) { set_error("too many query blocks"); return HF_ERR_SHAPE; }
+  const int q_per_xcd = (int)((q_items + 7) / 8);
 #define HF_LAUNCH_DQ(NWV, HM)                                                                                      \
-  hipLaunchKernelGGL((bwd_dq_mfma_kernel<NWV, HM>), dim3(t_m, BH), dim3(64 * NWV), 0, s, q, kk, v, g, idx, k, n_q, \
-                     n_kv, kvs, c.block_kv, t_m, t_n, c_scale, scale, lse2, Dv, hist, static_cast<bf16_t*>(dQ))
+  hipLaunchKernelGGL((bwd_dq_mfma_kernel<NWV, HM>), dim3(8 * q_per_xcd), dim3(64 * NWV), 0, s, q, kk, v, g, idx, k, \
+                     n_q, n_kv, kvs, c.block_kv, t_m, t_n, q_per_xcd, (int)q_items, c_scale, scale, lse2, Dv, hist,   \
+                     static_cast<bf16_t*>(dQ))
   if (c.block_q == 64) {
     if (hist_mode == 0) HF_LAUNCH_DQ(2, 0); else if (hist_mode == 1) HF_LAUNCH_DQ(2, 1); else HF_LAUNCH_DQ(2, 2);
   } else {
@@ -586,10 +602,12 @@ int launch_bwd_mfma(const hf_config& c, const void* Q, int n_q, const void* K, c
   int rc = check_launch("hf_hybrid_attn_bwd(dQ)");
   if (rc != HF_OK) return rc;
   const int slabs = (c.block_kv + 63) / 64;   // 64 keys per workgroup
-  if ((long long)t_n * slabs > 0x7fffffffll) { set_error("too many KV slabs"); return HF_ERR_SHAPE; }
-  hipLaunchKernelGGL(bwd_dkv_mfma_kernel, dim3(t_n * slabs, BH), dim3(256), 0, s, q, kk, v, g, inv_cnt, inv_list, n_q,
-                     n_kv, kvs, c.block_q, c.block_kv, t_m, t_n, slabs, c_scale, scale, lse2, Dv,
-                     static_cast<bf16_t*>(dK), static_cast<bf16_t*>(dV));
+  const long long kv_items = (long long)BH * t_n * slabs;
+  if (kv_items > (1ll << 30)) { set_error("too many KV slabs"); return HF_ERR_SHAPE; }
+  const int kv_per_xcd = (int)((kv_items + 7) / 8);
+  hipLaunchKernelGGL(bwd_dkv_mfma_kernel, dim3(8 * kv_per_xcd), dim3(256), 0, s, q, kk, v, g, inv_cnt, inv_list, n_q,
+                     n_kv, kvs, c.block_q, c.block_kv, t_m, t_n, slabs, kv_per_xcd, (int)kv_items, c_scale, scale, lse2,
+                     Dv, static_cast<bf16_t*>(dK), static_cast<bf16_t*>(dV));
   return check_launch("hf_hybrid_attn_bwd(dK, dV)");
 }
 
