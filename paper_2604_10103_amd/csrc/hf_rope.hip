@@ -37,40 +37,46 @@ __global__ __launch_bounds__(256) void rope_tables_kernel(const RopeSpec spec, i
   sinv[e] = (float)sn;
 }
 
-// 8 consecutive features (4 adjacent pairs) of one token per thread; fp32 arithmetic, one rounding to
-// the storage type.  X and Y may be the same buffer: a thread writes only what it has read.
+// 8 consecutive features (4 adjacent pairs) of one token per thread, for every head in turn: the thread's
+// slice of the tables is read once and stays in registers (a table row is shared by all heads; read per head
+// it would cross HBM once per head, the table being larger than an XCD's L2).  fp32 arithmetic, one rounding
+// to the storage type.  X and Y may be the same buffer: a thread writes only what it has read.
 template <typename T, int D>
-__global__ __launch_bounds__(256) void rope_apply_kernel(const T* __restrict__ X, int n_tokens,
+__global__ __launch_bounds__(256) void rope_apply_kernel(const T* X, int n_tokens, int BH,
                                                          const float* __restrict__ cosv,
-                                                         const float* __restrict__ sinv, T* __restrict__ Y) {
+                                                         const float* __restrict__ sinv, T* Y) {
   constexpr int TPT = D / 8;         // threads per token
   constexpr int TOK = 256 / TPT;     // tokens per workgroup
   const int tok = blockIdx.x * TOK + threadIdx.x / TPT;
   if (tok >= n_tokens) return;
   const int g = threadIdx.x % TPT;
-  const size_t off = ((size_t)blockIdx.y * n_tokens + tok) * D + 8 * g;
-  float x[8];
-  load16B<T>(X + off, x);
-  if (Elem<T>::kPer16B == 4) load16B<T>(X + off + 4, x + 4);
   const float4 c4 = *reinterpret_cast<const float4*>(cosv + (size_t)tok * (D / 2) + 4 * g);
   const float4 s4 = *reinterpret_cast<const float4*>(sinv + (size_t)tok * (D / 2) + 4 * g);
   const float cc[4] = {c4.x, c4.y, c4.z, c4.w}, ss[4] = {s4.x, s4.y, s4.z, s4.w};
-  float y[8];
+  const int bh0 = blockIdx.y, bh_step = gridDim.y;
+#pragma unroll 4
+  for (int bh = bh0; bh < BH; bh += bh_step) {
+    const size_t off = ((size_t)bh * n_tokens + tok) * D + 8 * g;
+    float x[8];
+    load16B<T>(X + off, x);
+    if (Elem<T>::kPer16B == 4) load16B<T>(X + off + 4, x + 4);
+    float y[8];
 #pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    y[2 * p] = x[2 * p] * cc[p] - x[2 * p + 1] * ss[p];
-    y[2 * p + 1] = x[2 * p] * ss[p] + x[2 * p + 1] * cc[p];
-  }
-  if (Elem<T>::kPer16B == 8) {
-    uint4 o;
-    uint32_t w[4];
+    for (int p = 0; p < 4; ++p) {
+      y[2 * p] = x[2 * p] * cc[p] - x[2 * p + 1] * ss[p];
+      y[2 * p + 1] = x[2 * p] * ss[p] + x[2 * p + 1] * cc[p];
+    }
+    if (Elem<T>::kPer16B == 8) {
+      uint4 o;
+      uint32_t w[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f32_to_bf16(y[2 * i]) | ((uint32_t)f32_to_bf16(y[2 * i + 1]) << 16);
-    o.x = w[0]; o.y = w[1]; o.z = w[2]; o.w = w[3];
-    *reinterpret_cast<uint4*>(Y + off) = o;
-  } else {
-    *reinterpret_cast<float4*>(Y + off) = make_float4(y[0], y[1], y[2], y[3]);
-    *reinterpret_cast<float4*>(Y + off + 4) = make_float4(y[4], y[5], y[6], y[7]);
+      for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f32_to_bf16(y[2 * i]) | ((uint32_t)f32_to_bf16(y[2 * i + 1]) << 16);
+      o.x = w[0]; o.y = w[1]; o.z = w[2]; o.w = w[3];
+      *reinterpret_cast<uint4*>(Y + off) = o;
+    } else {
+      *reinterpret_cast<float4*>(Y + off) = make_float4(y[0], y[1], y[2], y[3]);
+      *reinterpret_cast<float4*>(Y + off + 4) = make_float4(y[4], y[5], y[6], y[7]);
+    }
   }
 }
 
@@ -95,12 +101,18 @@ static int launch_rope_apply_t(const hf_config& c, const void* X, int n, const f
                                void* Y, hipStream_t s) {
   const int D = c.head_dim;
   const int tok_per_wg = 256 / (D / 8);
-  const dim3 grid((n + tok_per_wg - 1) / tok_per_wg, c.batch * c.heads);
+  const int BH = c.batch * c.heads;
+  const int chunks = (n + tok_per_wg - 1) / tok_per_wg;
+  // heads are split over grid.y only as far as it takes to fill the chip (about 2000 workgroups)
+  int ysplit = (2048 + chunks - 1) / chunks;
+  if (ysplit > BH) ysplit = BH;
+  if (ysplit < 1) ysplit = 1;
+  const dim3 grid(chunks, ysplit);
   if (D == 128)
-    hipLaunchKernelGGL((rope_apply_kernel<T, 128>), grid, dim3(256), 0, s, static_cast<const T*>(X), n, cosv, sinv,
+    hipLaunchKernelGGL((rope_apply_kernel<T, 128>), grid, dim3(256), 0, s, static_cast<const T*>(X), n, BH, cosv, sinv,
                        static_cast<T*>(Y));
   else
-    hipLaunchKernelGGL((rope_apply_kernel<T, 64>), grid, dim3(256), 0, s, static_cast<const T*>(X), n, cosv, sinv,
+    hipLaunchKernelGGL((rope_apply_kernel<T, 64>), grid, dim3(256), 0, s, static_cast<const T*>(X), n, BH, cosv, sinv,
                        static_cast<T*>(Y));
   return check_launch("hf_rope_apply");
 }
