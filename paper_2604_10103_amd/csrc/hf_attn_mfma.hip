@@ -11,16 +11,20 @@
 // and row sum are in-lane reductions plus one exchange with lane^32, the rescale factor is a
 // per-lane scalar, and the exp'd accumulators of S^T are, after rounding to bf16, already the
 // B operand of the second product.  The k index of that MFMA is thereby bound to the order in
-// which a lane holds keys, so V is transposed on its way into LDS with the key pairs stored in
-// that order: a V^T fragment is one conflict-free 16-byte read.
+// which a lane holds keys: 16 t2 + 8 x + 4 (lane / 32) + 0..3.
+//
+// Staging.  K and V tiles go global -> LDS directly (buffer loads with the LDS bit: 16 bytes per lane,
+// 1 KB = 4 key rows per instruction, no staging registers, no LDS stores), row-major with the 16-byte
+// units of a row permuted (K: u ^ (row & 15), V: u ^ 2 (row & 7)) by choosing which global unit a lane
+// fetches.  A K fragment is one 16-byte read; a V^T fragment is two transposing 8-byte reads
+// (ds_read_b64_tr_b16: a 16-lane group fetches 4 key rows x 16 features and every lane receives the
+// four keys of its own feature), which is exactly the key order above.  Both patterns are conflict free.
+// LDS holds two K tiles and two V tiles; one workgroup barrier per tile, placed behind the S^T products,
+// whose K fragments were read into registers during the previous tile's softmax: see tile_step.
 //
 // What bounds this kernel at block_q 64: the matrix work and the vector work of the softmax do not
-// overlap on a SIMD of this chip (together about two thirds of the run time), and every query
-// block stages its own 8 KB of K and 8 KB of V per 32 keys through the CU's vector-memory path
-// (64 B/clk) and LDS (128 B per cycle for stores), whose queues delay the operand reads.  LDS holds two tiles
-// (ping-pong): while tile t is consumed, tile t+1 moves registers -> LDS and tiles t+2, t+3 are on
-// their way global -> registers (buffer loads, no branches); one workgroup barrier per tile.
-// The V^T fragments of a tile are requested before its softmax so that their LDS latency is hidden.
+// overlap on a SIMD of this chip; with no loads, no exponentials and no barrier the loop still takes
+// twice the time of its MFMAs.
 #include <stdlib.h>
 
 #include "hf_common.h"
@@ -36,7 +40,6 @@ namespace {
 constexpr int D = 128;
 constexpr int TK = 32;      // keys per tile
 constexpr int KSTR = 256;   // bytes per key row of a K tile in LDS; 16-byte units XOR-swizzled by (row & 15)
-constexpr int VSTRD = 48;   // dwords per feature row of the V^T image: 2 tiles x 16 key pairs + 16
 constexpr int PSTR = 272;   // bytes per row of a staged state plane (256 + 16)
 constexpr int OSTR = 272;   // bytes per query row of the staged output
 constexpr int KTILE = TK * KSTR;
@@ -82,12 +85,11 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
     int items_per_xcd, int total_items, float c_scale, HistArgs hist, bf16_t* __restrict__ O) {
   constexpr int NT = 64 * NW;
   constexpr int BQ = 32 * NW;
-  constexpr int CPT = (TK * D * 2 / 16) / NT;  // 16-byte chunks of a K tile per thread (4 or 2)
-  constexpr int IPT = CPT / 2;                 // (key pair, feature group) items of a V tile per thread
-  __shared__ __attribute__((aligned(16))) char smem[2 * KTILE + D * VSTRD * 4];
-  char* const sK = smem;                                                   // two K tiles
-  uint32_t* const sVt = reinterpret_cast<uint32_t*>(smem + 2 * KTILE);     // V^T, both tiles side by side
-  static_assert(BQ * OSTR <= 2 * KTILE + D * VSTRD * 4, "staged output must fit in the tiles");
+  constexpr int CPT = (TK * D * 2 / 16) / NT;  // 1 KB pieces (4 key rows) of a tile per wavefront (4 or 2)
+  __shared__ __attribute__((aligned(16))) char smem[5 * KTILE];
+  char* const sK = smem;                // two K tiles
+  char* const sV = smem + 2 * KTILE;    // two V tiles (the fifth tile's space only serves the epilogue)
+  static_assert(BQ * OSTR <= 5 * KTILE, "staged output must fit in the tiles");
 
   // consecutive workgroup ids go to consecutive XCDs: give every XCD one contiguous run of
   // (head, query block) items so that its L2 sees few heads
@@ -96,7 +98,8 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
   if (slot >= items_per_xcd || item >= total_items) return;
   const int bh = item / t_m, qb = item % t_m;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: keeps LDS slot arithmetic on the scalar unit
   const int l32 = lane & 31, h = lane >> 5;
   const bf16_t* Qh = Q + (size_t)bh * n_q * D;
   const bf16_t* Kh = K + (size_t)bh * kv_stride * D;  // heads of a cache buffer are kv_stride tokens apart
@@ -147,110 +150,119 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
     ++tq;
   };
 
-  // ---- staging.  Loads go through buffer resources that end at the head's last key: rows past
-  // n_kv (the only rows of a tile that can be missing) read as zero without a branch; every
-  // offset sits in the vector operand, which is what the hardware range check looks at.
-  const __amdgpu_buffer_rsrc_t k_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(Kh), 0, n_kv * (D * 2), 0x00020000);
-  const __amdgpu_buffer_rsrc_t v_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(Vh), 0, n_kv * (D * 2), 0x00020000);
-  const int grp = tid & 15;                                  // 16-byte feature group
-  const int k_ld_off = (tid >> 4) * (D * 2) + grp * 16;      // K: row (tid>>4) + (NT/16) i
-  // V: a half-wavefront covers 8 feature groups x 4 adjacent key pairs, so that its 32 transposing
-  // dword stores fall into 32 different banks
-  const int vgrp = (lane & 7) + 8 * (lane >> 5);             // 16-byte feature group of the V rows
-  const int sub4 = (lane >> 3) & 3;                          // which of 4 adjacent key pairs
-  const int v_key_lane = 8 * (sub4 >> 1) + 2 * (sub4 & 1);
-  auto gload = [&](int start, u32x4 (&kreg)[CPT], u32x4 (&vreg)[CPT]) {
-    const int kb = k_ld_off + start * (D * 2);
+  // ---- staging: K and V tiles go global -> LDS directly (16 bytes per lane, 1 KB = 4 key rows per
+  // instruction), row-major with swizzled 16-byte units: K unit u of row r sits at u ^ (r & 15), V unit u
+  // at u ^ 2 (r & 7).  Rows past n_kv read as zero (range check on the vector offset).
+  // K has three slots, V two: in iteration t, V of tile t+1 and then K of tile t+2 are requested.
+  typedef int i32x4 __attribute__((ext_vector_type(4)));
+  const uint64_t kbase = reinterpret_cast<uint64_t>(Kh), vbase = reinterpret_cast<uint64_t>(Vh);
+  const i32x4 k_desc = {(int)(uint32_t)kbase, (int)(uint32_t)(kbase >> 32), n_kv * (D * 2), 0x00020000};
+  const i32x4 v_desc = {(int)(uint32_t)vbase, (int)(uint32_t)(vbase >> 32), n_kv * (D * 2), 0x00020000};
+  const uint32_t sK_lds = (uint32_t)(uintptr_t)sK, sV_lds = (uint32_t)(uintptr_t)sV;
+  int k_lane_off[CPT], v_lane_off[CPT];
 #pragma unroll
-    for (int i = 0; i < CPT; ++i) kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, kb + i * (NT / 16) * (D * 2), 0, 0);
+  for (int j = 0; j < CPT; ++j) {
+    const int r = 4 * (wave + NW * j) + (lane >> 4), u = lane & 15;
+    k_lane_off[j] = r * (D * 2) + ((u ^ (r & 15)) * 16);
+    v_lane_off[j] = r * (D * 2) + ((u ^ (2 * (r & 7))) * 16);
+  }
+  // the tile's first key moves into the descriptor (base and size, scalar arithmetic): the per-lane offsets
+  // stay constant and the range check still ends at the head's last key
+  auto dma_tile = [&](const i32x4& desc, uint32_t lds_slot, int start_v, const int (&lane_off)[CPT]) {
+    const int start = __builtin_amdgcn_readfirstlane(start_v);   // uniform already; this pins it to a scalar register
+    // a tile that starts at or past the head's end (an empty part of a short block) gets a descriptor of
+    // size zero: every load of it returns zero and nothing outside the head is touched
+    const int skip = start * (D * 2), left = desc.z - skip;
+    const uint64_t base = (((uint64_t)(uint32_t)desc.y << 32) | (uint32_t)desc.x) + (uint64_t)(uint32_t)(left > 0 ? skip : 0);
+    const i32x4 d2 = {(int)(uint32_t)base, (int)(uint32_t)(base >> 32), left > 0 ? left : 0, desc.w};
 #pragma unroll
-    for (int j = 0; j < IPT; ++j) {
-      const int cb = wave * IPT + j;  // = 2 t2 + hh
-      const int key = 16 * (cb >> 1) + 4 * (cb & 1) + v_key_lane;
-      const int vb = (start + key) * (D * 2) + vgrp * 16;
-      vreg[2 * j] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, vb, 0, 0);
-      vreg[2 * j + 1] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, vb + D * 2, 0, 0);
-    }
-  };
-  // V^T image: row = feature, dword column = 16 (tile parity) + key pair in MFMA order
-  // (8 t2 + 4 hh + 2 x + y), rotated by 4 dwords per 8 features.  LDS serves dword stores 32 lanes
-  // at a time from 32 banks and 16-byte reads from 64 banks in lane groups it picks by one of the
-  // lane bits 2..4: with 48-dword rows and this rotation both the stores and the operand reads
-  // are conflict free (measured with SQ_LDS_BANK_CONFLICT on the exact address patterns).
-  const int vt_rot = 4 * (vgrp & 7);
-  auto lstore = [&](int par, const u32x4 (&kreg)[CPT], const u32x4 (&vreg)[CPT]) {
-#pragma unroll
-    for (int i = 0; i < CPT; ++i) {
-      const int row = (tid >> 4) + (NT / 16) * i;
-      *reinterpret_cast<u32x4*>(sK + par * KTILE + row * KSTR + ((grp ^ (row & 15)) * 16)) = kreg[i];
-    }
-#pragma unroll
-    for (int j = 0; j < IPT; ++j) {
-      const int col = (16 * par + 4 * (wave * IPT + j) + sub4 + vt_rot) & 31;
-      const u32x4 a = vreg[2 * j], b = vreg[2 * j + 1];  // rows key and key + 1
-#pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        const int f = 8 * vgrp + 2 * p;
-        sVt[f * VSTRD + col] = __builtin_amdgcn_perm(b[p], a[p], 0x05040100u);        // feature f: (key, key + 1)
-        sVt[(f + 1) * VSTRD + col] = __builtin_amdgcn_perm(b[p], a[p], 0x07060302u);  // feature f + 1
-      }
+    for (int j = 0; j < CPT; ++j) {
+      const uint32_t dst = lds_slot + 4 * (wave + NW * j) * KSTR;
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                   :: "s"(dst), "v"(lane_off[j]), "s"(d2) : "memory", "m0");
     }
   };
 
   // per-lane LDS read offsets
   // K operand of step s: unit (2 s + h) ^ (row & 15) of row l32, i.e. byte k_rd ^ (32 s)
-  const char* k_rd = sK + l32 * KSTR + 16 * (h ^ (l32 & 1)) + 32 * ((l32 & 15) >> 1);  // + par KTILE
-  int v_row[4], v_rot[4];
+  const uint32_t k_rd = l32 * KSTR + 16 * (h ^ (l32 & 1)) + 32 * ((l32 & 15) >> 1);
+  // V operand (feature 32 dt + l32, keys 16 t2 + 8 x + 4 h .. + 4) by transposing reads: a 16-lane group
+  // fetches 4 key rows x 16 features as 16 chunks of 8 bytes, lane j the chunk (key j / 4, features 4 (j % 4));
+  // each lane receives the four keys of its own feature column
+  const int j16 = lane & 15, grp16 = lane >> 4;
+  const int key_l = 4 * h + (j16 >> 2);                                  // key within the group of 8, = key & 7
+  const int w_l = (2 * (grp16 & 1) + ((j16 & 3) >> 1)) ^ (2 * key_l);     // swizzled unit for dt = 0
+  const uint32_t v_rd = key_l * KSTR + w_l * 16 + 8 * (j16 & 1);         // ^ (64 dt), + 4096 t2 + 2048 x
+
+  // ---- prologue: K and V of tile 0 and K of tile 1 land, the K fragments of tile 0 are read into registers
+  typedef short s16x4 __attribute__((ext_vector_type(4)));
+  uint32_t k_addr[8], v_addr[4];
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt) {
-    v_row[dt] = (32 * dt + l32) * VSTRD;
-    v_rot[dt] = 4 * ((4 * dt + (l32 >> 3)) & 7) + 4 * h;
-  }
-
-  // ---- prologue: tile 0 in LDS, tiles 1 and 2 on their way in two sets of staging registers.
-  // Two tiles in flight per workgroup cover the global-load latency (one iteration is shorter
-  // than a trip to HBM).
-  u32x4 kregA[CPT], vregA[CPT], kregB[CPT], vregB[CPT];
-  int start_t, valid0, valid1, valid2;
-  next_tile(start_t, valid0);
-  gload(start_t, kregA, vregA);
-  lstore(0, kregA, vregA);
-  next_tile(start_t, valid1);
-  gload(start_t, kregA, vregA);   // tile 1
-  next_tile(start_t, valid2);
-  gload(start_t, kregB, vregB);   // tile 2
+  for (int s = 0; s < 8; ++s) k_addr[s] = k_rd ^ (32u * s);
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt) v_addr[dt] = v_rd ^ (64u * dt);
+  // The tile slots start out as zeros: a key row past the head's end is never written by the loads below (or
+  // is written as zero), and whatever a slot holds there is multiplied by a probability of zero, so it must be
+  // a finite number, which leftovers of another kernel in LDS need not be.
+  for (int c = tid; c < 4 * KTILE / 16; c += NT) reinterpret_cast<u32x4*>(smem)[c] = u32x4{0u, 0u, 0u, 0u};
   __syncthreads();
+  int start_a, start_b, valid0, valid1, valid2;   // starts of tiles t+1, t+2
+  {
+    int st0;
+    next_tile(st0, valid0);
+    dma_tile(k_desc, sK_lds, st0, k_lane_off);
+    dma_tile(v_desc, sV_lds, st0, v_lane_off);
+    next_tile(start_a, valid1);
+    dma_tile(k_desc, sK_lds + KTILE, start_a, k_lane_off);
+    next_tile(start_b, valid2);
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  bf16x8 kf[8];   // K operand fragments of the tile whose scores come next
+#pragma unroll
+  for (int s = 0; s < 8; ++s) kf[s] = *reinterpret_cast<const bf16x8*>(sK + k_addr[s]);
 
-  // One tile: consume LDS half `par`, move tile t+1 (staging set `kr`, `vr`) to the other half,
-  // refill that set with tile t+3.  One barrier per tile.
-  auto tile_step = [&](const int par, const int valid_cur, int& valid_new, u32x4 (&kr)[CPT], u32x4 (&vr)[CPT]) {
+  int va = valid0, vb = valid1, vc = valid2;  // real keys of tiles t, t+1, t+2
+  // One tile (par = t mod 2, a literal at every call site).  The scores of tile t are formed from fragments
+  // already in registers; the one barrier of the iteration follows them.  Behind it every wavefront is done
+  // with K slot par (fragments of tile t were read during tile t-1) and with V half par^1 (tile t-1), so K of
+  // tile t+2 and V of tile t+1 are requested into them; K of tile t+1 and V of tile t have landed (requested
+  // behind the previous barrier, awaited before this one) and their fragments are read while the softmax runs.
+  auto tile_step = [&](const int par) {
+    const int valid_cur = va;
     // ---- S^T = K Q^T : 32 keys, 8 steps over d
     f32x16 sacc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) sacc[r] = 0.0f;
-    uint32_t k_off = static_cast<uint32_t>(k_rd - sK);
-    // with the history epilogue compiled in, eight hoisted swizzled addresses cost spills inside this
-    // loop: there they are formed again for every tile (seven XORs)
-    if (kFused) asm volatile("" : "+v"(k_off));
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(sK + par * KTILE + (k_off ^ (32u * s)));
-      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[s], sacc, 0, 0, 0);
-    }
-    // the first half of the V^T fragments is requested now: the reads complete under the softmax
-    // (the barrier keeps the compiler from sinking them down to their use)
-    bf16x8 vf[4];
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-      vf[dt] = *reinterpret_cast<const bf16x8*>(&sVt[v_row[dt] + ((16 * par + v_rot[dt]) & 31)]);
-    __builtin_amdgcn_sched_barrier(0);
+    for (int s = 0; s < 8; ++s) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[s], sacc, 0, 0, 0);
 
-    // ---- tile t+1: registers -> the other LDS half; tile t+3: global -> the same registers
-    lstore(par ^ 1, kr, vr);
-    next_tile(start_t, valid_new);
-    gload(start_t, kr, vr);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's parts of K of tile t+1 and V of tile t
+    __syncthreads();
+
+    dma_tile(k_desc, sK_lds + par * KTILE, start_b, k_lane_off);           // K of tile t+2
+    dma_tile(v_desc, sV_lds + (par ^ 1) * KTILE, start_a, v_lane_off);     // V of tile t+1
+    start_a = start_b;
+    int vnew;
+    next_tile(start_b, vnew);
+
+    // V fragments of tile t and K fragments of tile t+1: the reads complete under the softmax
+    auto v_frag = [&](int dt, int t2) {
+      const char* p = sV + v_addr[dt] + par * KTILE + 4096 * t2;
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p + 2048));
+      typedef short s16x8 __attribute__((ext_vector_type(8)));
+      const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      return __builtin_bit_cast(bf16x8, both);
+    };
+    bf16x8 vf[4], vg[4];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) vf[dt] = v_frag(dt, 0);
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) vg[dt] = v_frag(dt, 1);
+#pragma unroll
+    for (int s = 0; s < 8; ++s) kf[s] = *reinterpret_cast<const bf16x8*>(sK + k_addr[s] + (par ^ 1) * KTILE);
+    __builtin_amdgcn_sched_barrier(0);
 
     if (valid_cur < TK) {  // keys that do not exist never contribute
 #pragma unroll
@@ -295,29 +307,20 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
 
     // ---- O^T += V^T P^T : 2 steps of 16 keys, 4 tiles of 32 features
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt) {
-      const bf16x8 a = vf[dt];
-      vf[dt] = *reinterpret_cast<const bf16x8*>(&sVt[v_row[dt] + ((16 * par + 8 + v_rot[dt]) & 31)]);
-      o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[0], o[dt], 0, 0, 0);
-    }
+    for (int dt = 0; dt < 4; ++dt) o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt], pf[0], o[dt], 0, 0, 0);
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt) o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt], pf[1], o[dt], 0, 0, 0);
-
-    __syncthreads();  // tile t is consumed everywhere, tile t+1 is complete in LDS
+    for (int dt = 0; dt < 4; ++dt) o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vg[dt], pf[1], o[dt], 0, 0, 0);
+    va = vb;
+    vb = vc;
+    vc = vnew;
   };
-
-  // tiles in pairs so that the staging sets alternate with compile-time names; a surplus tile
-  // of an odd list is empty (fully masked) and changes nothing
-  int va = valid0, vb = valid1, vc = valid2;  // real keys of tiles t, t+1, t+2
   for (int t = 0; t < ntiles; t += 2) {
-    int vd, ve;
-    tile_step(0, va, vd, kregA, vregA);  // consumes tile t,   stores t+1 (set A), fetches t+3 into A
-    tile_step(1, vb, ve, kregB, vregB);  // consumes tile t+1, stores t+2 (set B), fetches t+4 into B
-    va = vc;
-    vb = vd;
-    vc = ve;
+    tile_step(0);
+    if (t + 1 >= ntiles) break;
+    tile_step(1);
   }
-
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing may land in LDS after the tiles' space is reused
+  __syncthreads();
   // ---- normalise, transpose through LDS (the tiles are dead now) and store coalesced rows
   float l_tot;
   {
@@ -419,7 +422,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[dt][r] *= den_eps;
     constexpr int PCH = (D * D * 2 / 16) / NT;  // 16-byte chunks of one plane per thread
-    static_assert(D * PSTR <= 2 * KTILE + D * VSTRD * 4, "a state plane must fit in the tiles' space");
+    static_assert(D * PSTR <= 5 * KTILE, "a state plane must fit in the tiles' space");
     const u32x4* gp = reinterpret_cast<const u32x4*>(hist.planes + (size_t)bh * 2 * D * D);
     for (int plane = 0; plane < hist.n_planes; ++plane) {  // each plane goes through LDS once per workgroup
       u32x4 preg[PCH];
