@@ -13,10 +13,10 @@
 //      P  = 2^(c S - lse2),  dS = P * (dP - D)        -> bf16, B operands
 //      dV^T += dO^T P        dK^T += Q^T dS           A operands = dO, Q transposed in LDS
 //
-// A tile of 32 tokens x 128 features is fetched once from HBM (buffer loads that return zero past the
-// end of the head) in the lane mapping of the transposing store and written to LDS twice: row-major
-// with XOR-swizzled 16-byte units (A operand with tokens as rows) and transposed with token pairs in
-// MFMA order (A operand with features as rows).  The LDS layouts are those of the forward kernel.
+// A tile of 32 tokens x 128 features goes global -> LDS directly (buffer loads with the LDS bit; rows past the
+// end of the head arrive as zeros), row-major with swizzled 16-byte units, and serves both kinds of A operand:
+// tokens as rows by 16-byte reads, features as rows by gfx950's transposing reads (ds_read_b64_tr_b16).
+// No staging registers, no LDS stores, no transposing permutes; two slots per tensor, one barrier per tile.
 #include <math.h>
 
 #include "hf_common.h"
@@ -32,75 +32,81 @@ namespace {
 constexpr int D = 128;
 constexpr int TT = 32;       // tokens per tile
 constexpr int RSTR = 256;    // bytes per token row of a row-major tile
-constexpr int TSTR = 40;     // dwords per feature row of a transposed tile (16 token pairs, rotated within 32)
 constexpr int RTILE = TT * RSTR;
-constexpr int TTILE = D * TSTR * 4;
 constexpr int OSTR = 272;    // bytes per token row of a staged output
 
-// lane mapping of the transposing fetch: a half-wavefront covers 8 feature groups x 4 token pairs
-struct Stager {
-  int wave, vgrp, sub4, tok_lane, rot;
-  __device__ explicit Stager(int tid) {
-    const int lane = tid & 63;
-    wave = tid >> 6;
-    vgrp = (lane & 7) + 8 * (lane >> 5);
-    sub4 = (lane >> 3) & 3;
-    tok_lane = 8 * (sub4 >> 1) + 2 * (sub4 & 1);
-    rot = 4 * (vgrp & 7);
-  }
-  // item cb in [0, 4): tokens 16 (cb >> 1) + 4 (cb & 1) + tok_lane and the next one
-  __device__ int token(int cb) const { return 16 * (cb >> 1) + 4 * (cb & 1) + tok_lane; }
-};
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-// fetch: IPT items of (two token rows x one 16-byte feature group) per thread
-template <int NT>
-__device__ __forceinline__ void tile_fetch(const Stager& st, __amdgpu_buffer_rsrc_t rsrc, int first_token,
-                                           u32x4 (&reg)[512 / NT]) {
-  constexpr int IPT = 256 / NT;
-#pragma unroll
-  for (int j = 0; j < IPT; ++j) {
-    const int off = (first_token + st.token(st.wave * IPT + j)) * (D * 2) + st.vgrp * 16;
-    reg[2 * j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 0);
-    reg[2 * j + 1] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off + D * 2, 0, 0);
-  }
+// A 32-token tile sits in LDS row-major, 256 B per token, the 16-byte units of a row permuted:
+// unit u of row r is stored at u ^ swz(r), swz(r) = 2 (r & 7) | ((r >> 3) & 1).  With it both access
+// patterns below are free of bank conflicts: 16-byte reads of one unit from 16 consecutive rows (16 different
+// units) and the transposing reads of two units from 4 consecutive rows (8 different units).
+__device__ __forceinline__ int swz(int r) { return ((r & 7) << 1) | ((r >> 3) & 1); }
+
+// buffer descriptor of [rows x 128] bf16 at p (range check ends at the last row)
+__device__ __forceinline__ i32x4 desc_of(const bf16_t* p, int rows) {
+  const uint64_t a = reinterpret_cast<uint64_t>(p);
+  return i32x4{(int)(uint32_t)a, (int)(uint32_t)(a >> 32), rows * (D * 2), 0x00020000};
 }
 
-template <int NT>
-__device__ __forceinline__ void tile_store_rows(const Stager& st, const u32x4 (&reg)[512 / NT], char* sX) {
-  constexpr int IPT = 256 / NT;
+// Per-wavefront constants of the tile transfer global -> LDS (buffer loads with the LDS bit, 16 bytes per
+// lane, 1 KB = 4 token rows per instruction): a lane's place in LDS is fixed, the swizzle is done by
+// choosing which global unit it fetches.
+template <int NWAVES>
+struct TileDma {
+  static constexpr int CPT = 8 / NWAVES;   // 1 KB pieces per wavefront
+  int lane_off[CPT];
+  int wave;
+  __device__ TileDma(int wave_, int lane) : wave(wave_) {
 #pragma unroll
-  for (int j = 0; j < IPT; ++j) {
-    const int t0 = st.token(st.wave * IPT + j);
-    *reinterpret_cast<u32x4*>(sX + t0 * RSTR + ((st.vgrp ^ (t0 & 15)) * 16)) = reg[2 * j];
-    *reinterpret_cast<u32x4*>(sX + (t0 + 1) * RSTR + ((st.vgrp ^ ((t0 + 1) & 15)) * 16)) = reg[2 * j + 1];
-  }
-}
-
-template <int NT>
-__device__ __forceinline__ void tile_store_transposed(const Stager& st, const u32x4 (&reg)[512 / NT],
-                                                      uint32_t* sXt) {
-  constexpr int IPT = 256 / NT;
-#pragma unroll
-  for (int j = 0; j < IPT; ++j) {
-    const int col = (4 * (st.wave * IPT + j) + st.sub4 + st.rot) & 31;
-    const u32x4 a = reg[2 * j], b = reg[2 * j + 1];  // tokens t and t + 1
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const int f = 8 * st.vgrp + 2 * p;
-      sXt[f * TSTR + col] = __builtin_amdgcn_perm(b[p], a[p], 0x05040100u);
-      sXt[(f + 1) * TSTR + col] = __builtin_amdgcn_perm(b[p], a[p], 0x07060302u);
+    for (int j = 0; j < CPT; ++j) {
+      const int r = 4 * (wave + NWAVES * j) + (lane >> 4), u = lane & 15;
+      lane_off[j] = r * (D * 2) + ((u ^ swz(r)) * 16);
     }
   }
-}
+  // rows [first, first + 32) of the tensor behind desc -> LDS at byte address lds; rows past the end (or a
+  // tile that starts past it) arrive as zeros.  Completion is counted by vmcnt.
+  __device__ __forceinline__ void fetch(const i32x4& desc, uint32_t lds, int first_v) const {
+    const int first = __builtin_amdgcn_readfirstlane(first_v);
+    const int skip = first * (D * 2), left = desc.z - skip;
+    const uint64_t base = (((uint64_t)(uint32_t)desc.y << 32) | (uint32_t)desc.x) + (uint64_t)(uint32_t)(left > 0 ? skip : 0);
+    const i32x4 d2 = {(int)(uint32_t)base, (int)(uint32_t)(base >> 32), left > 0 ? left : 0, desc.w};
+#pragma unroll
+    for (int j = 0; j < CPT; ++j) {
+      const uint32_t dst = lds + 4 * (wave + NWAVES * j) * RSTR;
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                   :: "s"(dst), "v"(lane_off[j]), "s"(d2) : "memory", "m0");
+    }
+  }
+};
 
-// A operand, tokens as rows: row l32, features 16 s + 8 h .. + 8
-__device__ __forceinline__ bf16x8 rows_frag(const char* sX, int l32, int h, int s) {
-  return *reinterpret_cast<const bf16x8*>(sX + l32 * RSTR + (((2 * s + h) ^ (l32 & 15)) * 16));
+// A operand, tokens as rows: row l32, features 16 s + 8 h .. + 8: byte rows_base(l32, h) ^ (32 s)
+__device__ __forceinline__ uint32_t rows_base(int l32, int h) {
+  const int w = swz(l32);
+  return l32 * RSTR + 16 * (h ^ (w & 1)) + 32 * (w >> 1);
 }
-// A operand, features as rows: feature 32 dt + l32, tokens of MFMA step t2 (16 tokens), half h
-__device__ __forceinline__ bf16x8 transposed_frag(const uint32_t* sXt, int l32, int h, int dt, int t2) {
-  const int rot = 4 * ((4 * dt + (l32 >> 3)) & 7);
-  return *reinterpret_cast<const bf16x8*>(&sXt[(32 * dt + l32) * TSTR + ((8 * t2 + 4 * h + rot) & 31)]);
+__device__ __forceinline__ bf16x8 rows_frag(const char* sX, uint32_t base, int s) {
+  return *reinterpret_cast<const bf16x8*>(sX + (base ^ (32u * s)));
+}
+// A operand, features as rows: feature 32 ft + l32, tokens 16 t2 + 8 x + 4 h .. + 4 for x = 0, 1, by two
+// transposing reads (a 16-lane group fetches 4 token rows x 16 features as 16 chunks of 8 bytes, lane j the
+// chunk (row j / 4, features 4 (j % 4)); every lane receives the four tokens of its own feature):
+// byte (tr_base(lane) ^ (64 ft) ^ (16 x)) + 4096 t2 + 2048 x
+__device__ __forceinline__ uint32_t tr_base(int lane) {
+  const int j = lane & 15, g = lane >> 4, h = lane >> 5;
+  const int key_l = 4 * h + (j >> 2);
+  const int c = (2 * (g & 1) + ((j & 3) >> 1)) ^ (2 * key_l);
+  return key_l * RSTR + 16 * c + 8 * (j & 1);
+}
+__device__ __forceinline__ bf16x8 transposed_frag(const char* sX, uint32_t base, int ft, int t2) {
+  const char* p0 = sX + (base ^ (64u * ft)) + 4096 * t2;
+  const char* p1 = sX + (base ^ (64u * ft) ^ 16u) + 4096 * t2 + 2048;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p1));
+  const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8, both);
 }
 
 // this lane's token row as B-operand fragments (features 16 s + 8 h .. + 8), zero past the end
@@ -176,12 +182,11 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const float* __restrict__ lse2, const float* __restrict__ Dv, BwdHist hist, bf16_t* __restrict__ dQ) {
   constexpr int NT = 64 * NW;
   constexpr int BQ = 32 * NW;
-  __shared__ __attribute__((aligned(16))) char smem[2 * RTILE + TTILE];
-  static_assert(D * PSTR <= 2 * RTILE + TTILE, "a state plane must fit in the tiles' space");
+  __shared__ __attribute__((aligned(16))) char smem[5 * RTILE];   // K x 2, V x 2; all of it for a state plane later
+  static_assert(D * PSTR <= 5 * RTILE, "a state plane must fit in the tiles' space");
   char* const sK = smem;
-  char* const sV = smem + RTILE;
-  uint32_t* const sKt = reinterpret_cast<uint32_t*>(smem + 2 * RTILE);
-  static_assert(BQ * OSTR <= 2 * RTILE + TTILE, "staged output must fit");
+  char* const sV = smem + 2 * RTILE;
+  static_assert(BQ * OSTR <= 5 * RTILE, "staged output must fit");
 
   // consecutive workgroup ids go to consecutive XCDs: every XCD gets one contiguous run of (head, query
   // block) items, so that its L2 holds the keys and values of few heads
@@ -189,13 +194,16 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int item = xcd * items_per_xcd + slot;
   if (slot >= items_per_xcd || item >= total_items) return;
   const int bh = item / t_m, qb = item - bh * t_m;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, h = lane >> 5;
-  const Stager st(tid);
+  const TileDma<NW> dma(wave, lane);
   const __amdgpu_buffer_rsrc_t q_rsrc = rsrc_of(Q + (size_t)bh * n_q * D, n_q);
   const __amdgpu_buffer_rsrc_t do_rsrc = rsrc_of(dO + (size_t)bh * n_q * D, n_q);
-  const __amdgpu_buffer_rsrc_t k_rsrc = rsrc_of(K + (size_t)bh * kv_stride * D, n_kv);
-  const __amdgpu_buffer_rsrc_t v_rsrc = rsrc_of(V + (size_t)bh * kv_stride * D, n_kv);
+  const i32x4 k_desc = desc_of(K + (size_t)bh * kv_stride * D, n_kv);
+  const i32x4 v_desc = desc_of(V + (size_t)bh * kv_stride * D, n_kv);
+  const uint32_t sK_lds = (uint32_t)(uintptr_t)sK, sV_lds = (uint32_t)(uintptr_t)sV;
+  const uint32_t rb = rows_base(l32, h), tb = tr_base(lane);
   const int32_t* row_idx = idx ? idx + ((size_t)bh * t_m + qb) * k : nullptr;
   const int nsel = idx ? k : t_n;
   const int subs = (bkv + TT - 1) / TT;
@@ -213,46 +221,73 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
     for (int r = 0; r < 16; ++r) dq[dt][r] = 0.0f;
 
-  for (int sel = 0; sel < nsel; ++sel) {
+  // tile list: (selected block, 32-key part) -> (first key, real keys); a part past the end of a short block
+  // or an out-of-range block index gives (0, 0) and is skipped.  K and V of tile t + 1 are on their way into
+  // the other pair of slots while tile t is consumed; one barrier per tile.
+  const int ntiles = nsel * subs;
+  auto tile_desc = [&](int t, int& start, int& valid) {   // uniform over the workgroup
+    start = 0;
+    valid = 0;
+    if (t >= ntiles) return;
+    const int sel = t / subs, sub = t - sel * subs;
     const int jb = row_idx ? row_idx[sel] : sel;
-    if ((unsigned)jb >= (unsigned)t_n) continue;   // uniform over the workgroup
-    const int blk_end = min(n_kv, (jb + 1) * bkv);
-    for (int sub = 0; sub < subs; ++sub) {
-      const int start = jb * bkv + TT * sub;
-      const int valid = min(TT, blk_end - start);
-      if (valid <= 0) break;
-      u32x4 kreg[512 / NT], vreg[512 / NT];
-      tile_fetch<NT>(st, k_rsrc, start, kreg);
-      tile_fetch<NT>(st, v_rsrc, start, vreg);
-      __syncthreads();   // the previous tile is consumed
-      tile_store_rows<NT>(st, kreg, sK);
-      tile_store_transposed<NT>(st, kreg, sKt);
-      tile_store_rows<NT>(st, vreg, sV);
-      __syncthreads();
-
-      f32x16 sacc, dpacc;
+    if ((unsigned)jb >= (unsigned)t_n) return;
+    const int first = jb * bkv + TT * sub;
+    const int n = min(TT, min(n_kv, (jb + 1) * bkv) - first);
+    if (n > 0) { start = first; valid = n; }
+  };
+  for (int c = tid; c < 4 * RTILE / 16; c += NT) reinterpret_cast<u32x4*>(smem)[c] = u32x4{0u, 0u, 0u, 0u};
+  __syncthreads();   // rows past a head's end are never written: they must hold finite numbers
+  int start, valid;
+  tile_desc(0, start, valid);
+  dma.fetch(k_desc, sK_lds, start);
+  dma.fetch(v_desc, sV_lds, start);
+  auto tile_step = [&](const int t, const int par) {
+    const int valid_cur = valid;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's parts of tile t
+    __syncthreads();                                   // tile t complete, tile t - 1 consumed by everybody
+    tile_desc(t + 1, start, valid);
+    dma.fetch(k_desc, sK_lds + (par ^ 1) * RTILE, start);
+    dma.fetch(v_desc, sV_lds + (par ^ 1) * RTILE, start);
+    if (valid_cur == 0) return;
+    const char* tK = sK + par * RTILE;
+    const char* tV = sV + par * RTILE;
+    f32x16 sacc, dpacc;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { sacc[r] = 0.0f; dpacc[r] = 0.0f; }
+    for (int r = 0; r < 16; ++r) { sacc[r] = 0.0f; dpacc[r] = 0.0f; }
 #pragma unroll
-      for (int s = 0; s < 8; ++s) {
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(sK, l32, h, s), qf[s], sacc, 0, 0, 0);
-        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(sV, l32, h, s), dof[s], dpacc, 0, 0, 0);
-      }
-      bf16x8 dsf[2];
+    for (int s = 0; s < 8; ++s) {
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(tK, rb, s), qf[s], sacc, 0, 0, 0);
+      dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(tV, rb, s), dof[s], dpacc, 0, 0, 0);
+    }
+    bf16x8 dsf[2];
+    if (valid_cur == TT) {   // uniform
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        dsf[r >> 3][r & 7] = static_cast<__bf16>(__builtin_amdgcn_exp2f(fmaf(sacc[r], c_scale, -lse)) * (dpacc[r] - dvec));
+    } else {
+      // a tile cut short by its block's or the head's end: masked by bit operations (a select around the
+      // exponential would become a branch per element)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int key = 8 * (r >> 2) + 4 * h + (r & 3);
-        const uint32_t keep = key < valid ? 0xffffffffu : 0u;   // bit mask: a select would become a branch per element
+        const uint32_t keep = key < valid_cur ? 0xffffffffu : 0u;
         const float p = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(sacc[r], c_scale, -lse))) & keep);
         dsf[r >> 3][r & 7] = static_cast<__bf16>(p * (dpacc[r] - dvec));
       }
-#pragma unroll
-      for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
-          dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(transposed_frag(sKt, l32, h, dt, t2), dsf[t2], dq[dt], 0, 0, 0);
     }
+#pragma unroll
+    for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+        dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(transposed_frag(tK, tb, dt, t2), dsf[t2], dq[dt], 0, 0, 0);
+  };
+  for (int t = 0; t < ntiles; t += 2) {
+    tile_step(t, 0);
+    if (t + 1 >= ntiles) break;
+    tile_step(t + 1, 1);
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing may land in LDS once the tiles' space is reused
 
   f32x16 acc[4];   // history branch: num^T, then t^T, then the gradient itself
   if (kHist) {
@@ -408,13 +443,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     int total_items, float c_scale, float scale, const float* __restrict__ lse2, const float* __restrict__ Dv,
     bf16_t* __restrict__ dK, bf16_t* __restrict__ dV) {
   constexpr int NT = 256;
-  __shared__ __attribute__((aligned(16))) char smem[2 * RTILE + 2 * TTILE + 256];
+  __shared__ __attribute__((aligned(16))) char smem[4 * RTILE + 512];   // Q x 2, dO x 2, row statistics x 2
   char* const sQ = smem;
-  char* const sdO = smem + RTILE;
-  uint32_t* const sQt = reinterpret_cast<uint32_t*>(smem + 2 * RTILE);
-  uint32_t* const sdOt = reinterpret_cast<uint32_t*>(smem + 2 * RTILE + TTILE);
-  float* const sStat = reinterpret_cast<float*>(smem + 2 * RTILE + 2 * TTILE);   // lse2[32], D[32]
-  static_assert(64 * OSTR <= 2 * RTILE + 2 * TTILE, "staged output must fit");
+  char* const sdO = smem + 2 * RTILE;
+  float* const sStat = reinterpret_cast<float*>(smem + 4 * RTILE);   // per slot: lse2[32], D[32]
+  static_assert(64 * OSTR <= 4 * RTILE, "staged output must fit");
 
   // XCD-aware placement as in the dQ kernel: an XCD's L2 then holds the queries and output gradients of few heads
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -423,12 +456,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int bh = item / (t_n * slabs);
   const int rest = item - bh * (t_n * slabs);
   const int jb = rest / slabs, slab = rest - jb * slabs;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int kw = wave & 1, dh = wave >> 1;
   const int l32 = lane & 31, h = lane >> 5;
-  const Stager st(tid);
-  const __amdgpu_buffer_rsrc_t q_rsrc = rsrc_of(Q + (size_t)bh * n_q * D, n_q);
-  const __amdgpu_buffer_rsrc_t do_rsrc = rsrc_of(dO + (size_t)bh * n_q * D, n_q);
+  const TileDma<4> dma(wave, lane);
+  const i32x4 q_desc = desc_of(Q + (size_t)bh * n_q * D, n_q);
+  const i32x4 do_desc = desc_of(dO + (size_t)bh * n_q * D, n_q);
+  const uint32_t sQ_lds = (uint32_t)(uintptr_t)sQ, sdO_lds = (uint32_t)(uintptr_t)sdO;
+  const uint32_t rb = rows_base(l32, h), tb = tr_base(lane);
   const __amdgpu_buffer_rsrc_t k_rsrc = rsrc_of(K + (size_t)bh * kv_stride * D, n_kv);
   const __amdgpu_buffer_rsrc_t v_rsrc = rsrc_of(V + (size_t)bh * kv_stride * D, n_kv);
   const float* lseh = lse2 + (size_t)bh * n_q;
@@ -452,8 +488,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
     for (int r = 0; r < 16; ++r) { dk[a][r] = 0.0f; dv[a][r] = 0.0f; }
 
-  // tiles of 32 query rows of the listed query blocks; the fetch of tile n + 1 (and of its row statistics) is
-  // in flight while tile n is consumed.  A tile past n_q reads zeros and is masked.
+  // tiles of 32 query rows of the listed query blocks: Q and dO of tile n + 1 (and their row statistics) are
+  // on their way into the other slots while tile n is consumed; one barrier per tile.  A tile past n_q reads
+  // zeros and is masked.
   const int qtiles = bq / TT;
   const int ntiles = n_lists * qtiles;
   auto tile_row0 = [&](int n) {   // uniform over the workgroup
@@ -466,58 +503,66 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int row = min(r0 + (tid & 31), n_q - 1);
     return tid < 32 ? lseh[row] : Dvh[row];
   };
+  for (int c = tid; c < 4 * RTILE / 16; c += NT) reinterpret_cast<u32x4*>(smem)[c] = u32x4{0u, 0u, 0u, 0u};
+  __syncthreads();   // rows past n_q are never written: they must hold finite numbers
   int row0_next = tile_row0(0);
-  u32x4 qreg[2], dreg[2];
-  tile_fetch<NT>(st, q_rsrc, row0_next, qreg);
-  tile_fetch<NT>(st, do_rsrc, row0_next, dreg);
+  dma.fetch(q_desc, sQ_lds, row0_next);
+  dma.fetch(do_desc, sdO_lds, row0_next);
   float stat = stat_fetch(row0_next);
-  for (int n = 0; n < ntiles; ++n) {
+  auto tile_step = [&](const int n, const int par) {
     const int row0 = row0_next;
-    __syncthreads();   // the previous tile is consumed
-    tile_store_rows<NT>(st, qreg, sQ);
-    tile_store_transposed<NT>(st, qreg, sQt);
-    tile_store_rows<NT>(st, dreg, sdO);
-    tile_store_transposed<NT>(st, dreg, sdOt);
-    if (tid < 64) sStat[tid] = stat;
-    __syncthreads();
+    if (tid < 64) sStat[64 * par + tid] = stat;          // this slot's statistics were last read two tiles ago
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's parts of tile n
+    __syncthreads();                                   // tile n complete, tile n - 1 consumed by everybody
     row0_next = tile_row0(n + 1);
-    tile_fetch<NT>(st, q_rsrc, row0_next, qreg);
-    tile_fetch<NT>(st, do_rsrc, row0_next, dreg);
+    dma.fetch(q_desc, sQ_lds + (par ^ 1) * RTILE, row0_next);
+    dma.fetch(do_desc, sdO_lds + (par ^ 1) * RTILE, row0_next);
     stat = stat_fetch(row0_next);
-    {
-      f32x16 sacc, dpacc;
+    const char* tQ = sQ + par * RTILE;
+    const char* tdO = sdO + par * RTILE;
+    const float* tS = sStat + 64 * par;
+    f32x16 sacc, dpacc;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { sacc[r] = 0.0f; dpacc[r] = 0.0f; }
+    for (int r = 0; r < 16; ++r) { sacc[r] = 0.0f; dpacc[r] = 0.0f; }
 #pragma unroll
-      for (int s = 0; s < 8; ++s) {
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(sQ, l32, h, s), kf[s], sacc, 0, 0, 0);
-        dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(sdO, l32, h, s), vf[s], dpacc, 0, 0, 0);
-      }
-      bf16x8 pf[2], dsf[2];
+    for (int s = 0; s < 8; ++s) {
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(tQ, rb, s), kf[s], sacc, 0, 0, 0);
+      dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(tdO, rb, s), vf[s], dpacc, 0, 0, 0);
+    }
+    bf16x8 pf[2], dsf[2];
+    // probabilities masked by bit operations (a select around the exponential would become a branch per element):
+    // lanes of keys that do not exist, and, in the one tile that crosses n_q, rows that do not exist
+    auto probs = [&](const bool ragged) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const float4 l4 = *reinterpret_cast<const float4*>(sStat + 8 * g + 4 * h);
-        const float4 d4 = *reinterpret_cast<const float4*>(sStat + 32 + 8 * g + 4 * h);
+        const float4 l4 = *reinterpret_cast<const float4*>(tS + 8 * g + 4 * h);
+        const float4 d4 = *reinterpret_cast<const float4*>(tS + 32 + 8 * g + 4 * h);
         const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, ds[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int r = 4 * g + i;
-          // masked by bit operations: a select around the exponential would become a branch per element
-          const uint32_t keep = (row0 + 8 * g + 4 * h + i < n_q) ? kmask : 0u;
+          const uint32_t keep = (!ragged || row0 + 8 * g + 4 * h + i < n_q) ? kmask : 0u;
           const float p = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(sacc[r], c_scale, -ls[i]))) & keep);
           pf[r >> 3][r & 7] = static_cast<__bf16>(p);
           dsf[r >> 3][r & 7] = static_cast<__bf16>(p * (dpacc[r] - ds[i]));
         }
       }
+    };
+    if (row0 + TT <= n_q) probs(false); else probs(true);   // uniform
 #pragma unroll
-      for (int t2 = 0; t2 < 2; ++t2)
+    for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
-        for (int a = 0; a < 2; ++a) {
-          dv[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(transposed_frag(sdOt, l32, h, 2 * dh + a, t2), pf[t2], dv[a], 0, 0, 0);
-          dk[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(transposed_frag(sQt, l32, h, 2 * dh + a, t2), dsf[t2], dk[a], 0, 0, 0);
-        }
-    }
+      for (int a = 0; a < 2; ++a) {
+        dv[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(transposed_frag(tdO, tb, 2 * dh + a, t2), pf[t2], dv[a], 0, 0, 0);
+        dk[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(transposed_frag(tQ, tb, 2 * dh + a, t2), dsf[t2], dk[a], 0, 0, 0);
+      }
+  };
+  for (int n = 0; n < ntiles; n += 2) {
+    tile_step(n, 0);
+    if (n + 1 >= ntiles) break;
+    tile_step(n + 1, 1);
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing may land in LDS once the tiles' space is reused
 
   // transpose through LDS and store the rows of real keys, dK first, then dV
   for (int which = 0; which < 2; ++which) {
