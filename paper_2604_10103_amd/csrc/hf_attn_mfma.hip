@@ -19,7 +19,8 @@
 // fetches.  A K fragment is one 16-byte read; a V^T fragment is two transposing 8-byte reads
 // (ds_read_b64_tr_b16: a 16-lane group fetches 4 key rows x 16 features and every lane receives the
 // four keys of its own feature), which is exactly the key order above.  Both patterns are conflict free.
-// LDS holds two K tiles and two V tiles; one workgroup barrier per tile, placed behind the S^T products,
+// LDS holds three K tiles (requested two tiles ahead) and two V tiles (one ahead); one workgroup barrier per
+// tile, placed behind the S^T products,
 // whose K fragments were read into registers during the previous tile's softmax: see tile_step.
 //
 // What bounds this kernel at block_q 64: the matrix work and the vector work of the softmax do not
@@ -87,8 +88,8 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
   constexpr int BQ = 32 * NW;
   constexpr int CPT = (TK * D * 2 / 16) / NT;  // 1 KB pieces (4 key rows) of a tile per wavefront (4 or 2)
   __shared__ __attribute__((aligned(16))) char smem[5 * KTILE];
-  char* const sK = smem;                // two K tiles
-  char* const sV = smem + 2 * KTILE;    // two V tiles (the fifth tile's space only serves the epilogue)
+  char* const sK = smem;                // three K tiles (requested two tiles ahead)
+  char* const sV = smem + 3 * KTILE;    // two V tiles (requested one tile ahead)
   static_assert(BQ * OSTR <= 5 * KTILE, "staged output must fit in the tiles");
 
   // consecutive workgroup ids go to consecutive XCDs: give every XCD one contiguous run of
@@ -204,9 +205,9 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
   // The tile slots start out as zeros: a key row past the head's end is never written by the loads below (or
   // is written as zero), and whatever a slot holds there is multiplied by a probability of zero, so it must be
   // a finite number, which leftovers of another kernel in LDS need not be.
-  for (int c = tid; c < 4 * KTILE / 16; c += NT) reinterpret_cast<u32x4*>(smem)[c] = u32x4{0u, 0u, 0u, 0u};
+  for (int c = tid; c < 5 * KTILE / 16; c += NT) reinterpret_cast<u32x4*>(smem)[c] = u32x4{0u, 0u, 0u, 0u};
   __syncthreads();
-  int start_a, start_b, valid0, valid1, valid2;   // starts of tiles t+1, t+2
+  int start_a, start_b, start_c, valid0, valid1, valid2, valid3;   // starts of tiles t+1, t+2, t+3
   {
     int st0;
     next_tile(st0, valid0);
@@ -215,20 +216,22 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
     next_tile(start_a, valid1);
     dma_tile(k_desc, sK_lds + KTILE, start_a, k_lane_off);
     next_tile(start_b, valid2);
+    dma_tile(k_desc, sK_lds + 2 * KTILE, start_b, k_lane_off);
+    next_tile(start_c, valid3);
   }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * CPT) : "memory");   // K and V of tile 0 (K of tiles 1, 2 may fly)
   __syncthreads();
   bf16x8 kf[8];   // K operand fragments of the tile whose scores come next
 #pragma unroll
   for (int s = 0; s < 8; ++s) kf[s] = *reinterpret_cast<const bf16x8*>(sK + k_addr[s]);
 
-  int va = valid0, vb = valid1, vc = valid2;  // real keys of tiles t, t+1, t+2
-  // One tile (par = t mod 2, a literal at every call site).  The scores of tile t are formed from fragments
-  // already in registers; the one barrier of the iteration follows them.  Behind it every wavefront is done
-  // with K slot par (fragments of tile t were read during tile t-1) and with V half par^1 (tile t-1), so K of
-  // tile t+2 and V of tile t+1 are requested into them; K of tile t+1 and V of tile t have landed (requested
-  // behind the previous barrier, awaited before this one) and their fragments are read while the softmax runs.
-  auto tile_step = [&](const int par) {
+  int va = valid0, vb = valid1, vc = valid2, vd = valid3;  // real keys of tiles t .. t+3
+  // One tile (kslot = t mod 3, par = t mod 2, literals at every call site).  The scores of tile t are formed from
+  // fragments already in registers; the one barrier of the iteration follows them.  Behind it every wavefront is
+  // done with K slot kslot (fragments of tile t were read during tile t-1) and with V half par^1 (tile t-1), so V
+  // of tile t+1 and K of tile t+3 are requested into them; K of tile t+1 and V of tile t have landed (awaited
+  // before the barrier) and their fragments are read while the softmax runs.
+  auto tile_step = [&](const int kslot, const int par) {
     const int valid_cur = va;
     // ---- S^T = K Q^T : 32 keys, 8 steps over d
     f32x16 sacc;
@@ -237,14 +240,16 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
 #pragma unroll
     for (int s = 0; s < 8; ++s) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[s], sacc, 0, 0, 0);
 
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's parts of K of tile t+1 and V of tile t
+    // this wavefront's parts of K of tile t+1 and V of tile t have landed; K of tile t+2, requested last, may fly
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(CPT) : "memory");
     __syncthreads();
 
-    dma_tile(k_desc, sK_lds + par * KTILE, start_b, k_lane_off);           // K of tile t+2
     dma_tile(v_desc, sV_lds + (par ^ 1) * KTILE, start_a, v_lane_off);     // V of tile t+1
+    dma_tile(k_desc, sK_lds + kslot * KTILE, start_c, k_lane_off);         // K of tile t+3 into the slot of tile t
     start_a = start_b;
+    start_b = start_c;
     int vnew;
-    next_tile(start_b, vnew);
+    next_tile(start_c, vnew);
 
     // V fragments of tile t and K fragments of tile t+1: the reads complete under the softmax
     auto v_frag = [&](int dt, int t2) {
@@ -261,7 +266,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) vg[dt] = v_frag(dt, 1);
 #pragma unroll
-    for (int s = 0; s < 8; ++s) kf[s] = *reinterpret_cast<const bf16x8*>(sK + k_addr[s] + (par ^ 1) * KTILE);
+    for (int s = 0; s < 8; ++s) kf[s] = *reinterpret_cast<const bf16x8*>(sK + k_addr[s] + ((kslot + 1) % 3) * KTILE);
     __builtin_amdgcn_sched_barrier(0);
 
     if (valid_cur < TK) {  // keys that do not exist never contribute
@@ -312,12 +317,22 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
     for (int dt = 0; dt < 4; ++dt) o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vg[dt], pf[1], o[dt], 0, 0, 0);
     va = vb;
     vb = vc;
-    vc = vnew;
+    vc = vd;
+    vd = vnew;
   };
-  for (int t = 0; t < ntiles; t += 2) {
-    tile_step(0);
+  // six tiles per trip: every (t mod 3, t mod 2) pair once, so that all slot offsets are immediates
+  for (int t = 0; t < ntiles; t += 6) {
+    tile_step(0, 0);
     if (t + 1 >= ntiles) break;
-    tile_step(1);
+    tile_step(1, 1);
+    if (t + 2 >= ntiles) break;
+    tile_step(2, 0);
+    if (t + 3 >= ntiles) break;
+    tile_step(0, 1);
+    if (t + 4 >= ntiles) break;
+    tile_step(1, 0);
+    if (t + 5 >= ntiles) break;
+    tile_step(2, 1);
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing may land in LDS after the tiles' space is reused
   __syncthreads();
