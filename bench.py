@@ -27,7 +27,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM-side bytes per launch of the sparse flash forward from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
 # (profiles/bench_step_832x480_hbm_traffic.txt: read 93.1 MB + written 15.3 MB, scaled by a 256 MiB copy)
-MEASURED_TRAFFIC_BYTES = {"step_832x480": 108.4e6}
+MEASURED_TRAFFIC_BYTES = {"step_832x480": 110.3e6}
 
 
 def parse():
