@@ -19,6 +19,7 @@
 // fetches.  A K fragment is one 16-byte read; a V^T fragment is two transposing 8-byte reads
 // (ds_read_b64_tr_b16: a 16-lane group fetches 4 key rows x 16 features and every lane receives the
 // four keys of its own feature), which is exactly the key order above.  Both patterns are conflict free.
+// Key rows past the head's end are written as zeros (a load past the descriptor's end stores zero).
 // LDS holds three K tiles (requested two tiles ahead) and two V tiles (one ahead); one workgroup barrier per
 // tile, placed behind the S^T products,
 // whose K fragments were read into registers during the previous tile's softmax: see tile_step.
@@ -202,11 +203,6 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
   for (int s = 0; s < 8; ++s) k_addr[s] = k_rd ^ (32u * s);
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt) v_addr[dt] = v_rd ^ (64u * dt);
-  // The tile slots start out as zeros: a key row past the head's end is never written by the loads below (or
-  // is written as zero), and whatever a slot holds there is multiplied by a probability of zero, so it must be
-  // a finite number, which leftovers of another kernel in LDS need not be.
-  for (int c = tid; c < 5 * KTILE / 16; c += NT) reinterpret_cast<u32x4*>(smem)[c] = u32x4{0u, 0u, 0u, 0u};
-  __syncthreads();
   int start_a, start_b, start_c, valid0, valid1, valid2, valid3;   // starts of tiles t+1, t+2, t+3
   {
     int st0;

@@ -67,7 +67,8 @@ struct TileDma {
     }
   }
   // rows [first, first + 32) of the tensor behind desc -> LDS at byte address lds; rows past the end (or a
-  // tile that starts past it) arrive as zeros.  Completion is counted by vmcnt.
+  // tile that starts past it) arrive as zeros (a load past the descriptor's end stores zero in LDS).  Completion
+  // is counted by vmcnt.
   __device__ __forceinline__ void fetch(const i32x4& desc, uint32_t lds, int first_v) const {
     const int first = __builtin_amdgcn_readfirstlane(first_v);
     const int skip = first * (D * 2), left = desc.z - skip;
@@ -236,8 +237,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int n = min(TT, min(n_kv, (jb + 1) * bkv) - first);
     if (n > 0) { start = first; valid = n; }
   };
-  for (int c = tid; c < 4 * RTILE / 16; c += NT) reinterpret_cast<u32x4*>(smem)[c] = u32x4{0u, 0u, 0u, 0u};
-  __syncthreads();   // rows past a head's end are never written: they must hold finite numbers
   int start, valid;
   tile_desc(0, start, valid);
   dma.fetch(k_desc, sK_lds, start);
@@ -503,8 +502,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int row = min(r0 + (tid & 31), n_q - 1);
     return tid < 32 ? lseh[row] : Dvh[row];
   };
-  for (int c = tid; c < 4 * RTILE / 16; c += NT) reinterpret_cast<u32x4*>(smem)[c] = u32x4{0u, 0u, 0u, 0u};
-  __syncthreads();   // rows past n_q are never written: they must hold finite numbers
   int row0_next = tile_row0(0);
   dma.fetch(q_desc, sQ_lds, row0_next);
   dma.fetch(do_desc, sdO_lds, row0_next);

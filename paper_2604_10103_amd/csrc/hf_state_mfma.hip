@@ -269,6 +269,123 @@ __global__ __launch_bounds__(NT, 1) void absorb_mfma_kernel(float* __restrict__ 
   }
 }
 
+// ---- the same update with tiles streamed global -> LDS directly (plain case: ReLU, no rotation, partials) ----
+// A workgroup requests a whole run of 9 tiles of 32 tokens (K and V, 144 KB: one workgroup per CU) before it
+// touches the first: buffer loads with the LDS bit, 16 bytes per lane, no staging registers, no LDS stores;
+// tokens past the slice's end arrive as zeros (descriptor range), which ReLU and the products leave at zero.
+// Tiles are row-major with swizzled 16-byte units; both MFMA operands want tokens as the contraction index,
+// i.e. features as rows, and come from gfx950's transposing LDS reads (ds_read_b64_tr_b16: a 16-lane group
+// fetches 4 token rows x 16 features, every lane receives the four tokens of its own feature).
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+constexpr int TT = 32;               // tokens per tile
+constexpr int RTILE = TT * D * 2;    // bytes of one tile of one tensor
+constexpr int RUN_TILES = 9;         // tiles requested up front
+constexpr int DMA_LDS = RUN_TILES * 2 * RTILE + D * 4;
+
+__device__ __forceinline__ int swz(int r) { return ((r & 7) << 1) | ((r >> 3) & 1); }
+
+__device__ __forceinline__ bf16x8 tr_frag(const char* tile, uint32_t base, int ft, int t2) {
+  const char* p0 = tile + (base ^ (64u * ft)) + 4096 * t2;
+  const char* p1 = tile + (base ^ (64u * ft) ^ 16u) + 4096 * t2 + 2048;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p1));
+  const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8, both);
+}
+
+__global__ __launch_bounds__(NT, 1) void absorb_dma_kernel(float* __restrict__ partials, const bf16_t* __restrict__ K,
+                                                           const bf16_t* __restrict__ V, int n, int head_stride,
+                                                           int tokens_per_slice, int slices) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];   // RUN_TILES x (K tile, V tile), then z
+  float* const zs = reinterpret_cast<float*>(smem + RUN_TILES * 2 * RTILE);
+  const int bh = blockIdx.x / slices, slice = blockIdx.x - bh * slices;
+  const int t0 = slice * tokens_per_slice;
+  const int t1 = min(n, t0 + tokens_per_slice);
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, h = lane >> 5;
+
+  // transfer: wavefront w moves token rows 4 w .. 4 w + 3 of every tile (1 KB per instruction)
+  const int row = 4 * wave + (lane >> 4);
+  const int lane_off = row * (D * 2) + (((lane & 15) ^ swz(row)) * 16);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)smem + 4 * wave * (D * 2);
+  auto fetch = [&](const bf16_t* base_ptr, uint32_t dst, int first) {   // rows [first, first + 32), zeros from t1 on
+    const uint64_t a = reinterpret_cast<uint64_t>(base_ptr + (size_t)bh * head_stride * D) + (uint64_t)first * (D * 2);
+    const int left = (t1 - first) * (D * 2);
+    const i32x4 desc = {(int)(uint32_t)a, (int)(uint32_t)(a >> 32), left > 0 ? left : 0, 0x00020000};
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(dst), "v"(lane_off), "s"(desc) : "memory", "m0");
+  };
+  // operand addresses of a lane inside a tile (see tr_frag)
+  uint32_t tb;
+  {
+    const int j = lane & 15, g = lane >> 4;
+    const int key_l = 4 * h + (j >> 2);
+    const int c = (2 * (g & 1) + ((j & 3) >> 1)) ^ (2 * key_l);
+    tb = key_l * (D * 2) + 16 * c + 8 * (j & 1);
+  }
+
+  const int mi0 = wave >> 1, nj0 = 2 * (wave & 1);   // this wavefront's key-feature tile and its two value-feature tiles
+  f32x16 acc[2];
+#pragma unroll
+  for (int b = 0; b < 2; ++b)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[b][r] = 0.0f;
+  float zacc = 0.0f;   // sum over tokens of phi(k) for key feature 32 mi0 + l32 (this lane's half of the tokens)
+
+  typedef short s16x8v __attribute__((ext_vector_type(8)));
+  const s16x8v zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+  auto consume = [&](const int c) {
+    const char* tK = smem + c * 2 * RTILE;
+    const char* tV = tK + RTILE;
+#pragma unroll
+    for (int t2 = 0; t2 < 2; ++t2) {
+      // ReLU of bf16 values as a packed signed-integer max with zero
+      const bf16x8 af = __builtin_bit_cast(
+          bf16x8, __builtin_elementwise_max(__builtin_bit_cast(s16x8v, tr_frag(tK, tb, mi0, t2)), zero8));
+#pragma unroll
+      for (int e = 0; e < 8; ++e) zacc += static_cast<float>(af[e]);
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(tV, tb, nj0 + b, t2), af, acc[b], 0, 0, 0);  // L^T tile
+    }
+  };
+
+  for (int run0 = t0; run0 < t1; run0 += RUN_TILES * TT) {
+    if (run0 > t0) __syncthreads();   // the previous run is consumed
+    // every wavefront issues the same 2 x RUN_TILES requests (tiles past the end have an empty descriptor), so
+    // that the number still in flight when tile c is needed is a constant
+#pragma unroll
+    for (int c = 0; c < RUN_TILES; ++c) {
+      fetch(K, lds0 + c * 2 * RTILE, run0 + c * TT);
+      fetch(V, lds0 + c * 2 * RTILE + RTILE, run0 + c * TT);
+    }
+#pragma unroll
+    for (int c = 0; c < RUN_TILES; ++c) {
+      asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * (RUN_TILES - 1 - c)) : "memory");
+      __syncthreads();   // every wavefront's rows of tile c have landed
+      if (run0 + c * TT < t1) consume(c);   // uniform
+    }
+  }
+
+  // ---- hand the partial over: plain coalesced stores (16 contiguous bytes of a row of L per register group)
+  float* L = partials + ((size_t)bh * slices + slice) * PART;
+#pragma unroll
+  for (int b = 0; b < 2; ++b)
+#pragma unroll
+    for (int rq = 0; rq < 4; ++rq) {
+      const int i = 32 * mi0 + l32;
+      const int j = 32 * (nj0 + b) + 8 * rq + 4 * h;
+      *reinterpret_cast<float4*>(L + i * D + j) =
+          make_float4(acc[b][4 * rq], acc[b][4 * rq + 1], acc[b][4 * rq + 2], acc[b][4 * rq + 3]);
+    }
+  zacc += __shfl_xor(zacc, 32, kWave);   // the two halves of the tokens
+  if ((wave & 1) == 0 && h == 0) L[D * D + 32 * mi0 + l32] = zacc;   // one of the two wavefronts of a key tile
+  (void)zs;
+}
+
 // state += sum over slices of the partials; one thread per 4 consecutive floats of a partial
 __global__ __launch_bounds__(256) void absorb_reduce_kernel(float* __restrict__ state,
                                                             const float* __restrict__ partials, int slices,
@@ -306,10 +423,17 @@ int env_int(const char* name, int dflt) {
 }
 
 // slice length (a multiple of the 64-token chunk) and slice count for n tokens
-void slice_plan(int BH, int n, bool with_workspace, int& per, int& slices) {
+// dma: the plan of absorb_dma_kernel, whose run is RUN_TILES tiles of 32 tokens
+void slice_plan(int BH, int n, bool with_workspace, bool dma, int& per, int& slices) {
   const int forced = env_int("HF_ABSORB_SLICE_TOKENS", 0);  // development override
   if (forced > 0) {
     per = (forced + CH - 1) / CH * CH;
+  } else if (with_workspace && dma) {
+    // one run (288 tokens) per workgroup, one workgroup per CU; longer slices only for very long inputs
+    const int run = RUN_TILES * TT;
+    const int max_slices = (1024 + BH - 1) / BH;
+    per = run;
+    if ((n + per - 1) / per > max_slices) per = ((n + max_slices - 1) / max_slices + run - 1) / run * run;
   } else if (with_workspace) {
     // one run (320 tokens) per workgroup until there are ~4 workgroups per compute unit, then longer slices
     const int max_slices = (1024 + BH - 1) / BH;
@@ -327,9 +451,10 @@ void slice_plan(int BH, int n, bool with_workspace, int& per, int& slices) {
 }  // namespace
 
 size_t absorb_mfma_workspace_bytes(const hf_config& c, int n) {
-  int per, slices;
-  slice_plan(c.batch * c.heads, n, true, per, slices);
-  return (size_t)c.batch * c.heads * slices * PART * sizeof(float);
+  int per, slices, per2, slices2;   // whichever kernel runs: the larger of the two plans
+  slice_plan(c.batch * c.heads, n, true, false, per, slices);
+  slice_plan(c.batch * c.heads, n, true, true, per2, slices2);
+  return (size_t)c.batch * c.heads * (slices > slices2 ? slices : slices2) * PART * sizeof(float);
 }
 
 int launch_absorb_mfma(const hf_config& c, float* state, const void* K, const void* V, int n, int head_stride,
@@ -337,12 +462,33 @@ int launch_absorb_mfma(const hf_config& c, float* state, const void* K, const vo
                        hipStream_t s) {
   const int BH = c.batch * c.heads;
   const bool use_ws = workspace != nullptr && workspace_bytes >= absorb_mfma_workspace_bytes(c, n);
-  int per, slices;
-  slice_plan(BH, n, use_ws, per, slices);
-  float* partials = use_ws ? static_cast<float*>(workspace) : nullptr;
   const bool plain = (c.phi == HF_PHI_RELU) && cosv == nullptr;
+  const char* old = getenv("HF_ABSORB_KERNEL");   // development switch: "r" keeps the register-staged kernel
+  const bool dma = plain && use_ws && !(old && old[0] == 'r');
+  int per, slices;
+  slice_plan(BH, n, use_ws, dma, per, slices);
+  float* partials = use_ws ? static_cast<float*>(workspace) : nullptr;
   const bf16_t* Kp = static_cast<const bf16_t*>(K);
   const bf16_t* Vp = static_cast<const bf16_t*>(V);
+  if (dma) {
+    static bool ready = false;
+    if (!ready) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(absorb_dma_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, DMA_LDS) != hipSuccess) {
+        (void)hipGetLastError();
+        set_error("cannot reserve %d bytes of LDS for the absorb kernel", DMA_LDS);
+        return HF_ERR_HIP;
+      }
+      ready = true;
+    }
+    hipLaunchKernelGGL(absorb_dma_kernel, dim3(BH * slices), dim3(NT), DMA_LDS, s, partials, Kp, Vp, n, head_stride, per,
+                       slices);
+    const int rc2 = check_launch("hf_absorb_evicted");
+    if (rc2 != HF_OK) return rc2;
+    hipLaunchKernelGGL(absorb_reduce_kernel, dim3((PART / 4 + 255) / 256, BH), dim3(256), 0, s, state, partials,
+                       slices, BH);
+    return check_launch("hf_absorb_evicted(reduce)");
+  }
   const int heads_per_xcd = (BH + 7) / 8;
   const dim3 grid(use_ws ? BH * slices : 8 * heads_per_xcd * slices);
   if (plain) {
