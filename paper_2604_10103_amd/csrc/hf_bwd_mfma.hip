@@ -154,7 +154,6 @@ struct BwdHist {
   float eps, z_scale;
   int phi_kind;
 };
-constexpr int PSTR = 272;   // bytes per row of a staged state plane (256 + 16)
 
 // fp32 state -> the two bf16 planes of the backward pass: Lt (transposed) and L
 __global__ __launch_bounds__(256) void state_planes_bwd_kernel(const float* __restrict__ state,
@@ -184,7 +183,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
   constexpr int NT = 64 * NW;
   constexpr int BQ = 32 * NW;
   __shared__ __attribute__((aligned(16))) char smem[5 * RTILE];   // K x 2, V x 2; all of it for a state plane later
-  static_assert(D * PSTR <= 5 * RTILE, "a state plane must fit in the tiles' space");
+  static_assert(4 * RTILE <= 5 * RTILE, "a state plane (four pieces of 32 rows) must fit in the tiles' space");
   char* const sK = smem;
   char* const sV = smem + 2 * RTILE;
   static_assert(BQ * OSTR <= 5 * RTILE, "staged output must fit");
@@ -300,8 +299,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int crow = min(q_row, n_q - 1);
     const float* zv = hist.zvec + (size_t)bh * D;
     // f = phi(q), den = z_scale f.z + eps, r = R f as bf16 fragments
-    bf16x8 rf[8];
-    float den = 0.0f;
+    float den = 0.0f;   // (R f is written back into hq, dO / den into dof: the epilogue must not need more registers)
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
       float f[8];
@@ -324,7 +322,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
         }
       }
 #pragma unroll
-      for (int e = 0; e < 8; ++e) rf[s][e] = static_cast<__bf16>(f[e]);
+      for (int e = 0; e < 8; ++e) hq[s][e] = static_cast<__bf16>(f[e]);
     }
     {
       const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(den), __float_as_uint(den), false, false);
@@ -332,20 +330,19 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
     const float inv_den = 1.0f / den;
 
-    constexpr int PCH = (D * D * 2 / 16) / NT;   // 16-byte chunks of one plane per thread
-    const u32x4* gp = reinterpret_cast<const u32x4*>(hist.planes + (size_t)bh * 2 * D * D);
+    // a plane goes global -> LDS like the tiles (four pieces of 32 rows, no registers in between)
     float dden = 0.0f;
-    bf16x8 dn[8];
-    for (int plane = 0; plane < 2; ++plane) {
-      u32x4 preg[PCH];
 #pragma unroll
-      for (int i = 0; i < PCH; ++i) preg[i] = gp[plane * (D * D * 2 / 16) + tid + NT * i];
+    for (int s = 0; s < 8; ++s)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dof[s][e] = static_cast<__bf16>(static_cast<float>(dof[s][e]) * inv_den);   // dnum
+    const uint32_t smem_lds = (uint32_t)(uintptr_t)smem;
+    for (int plane = 0; plane < 2; ++plane) {
+      const i32x4 p_desc = desc_of(hist.planes + ((size_t)bh * 2 + plane) * D * D, D);
       __syncthreads();   // the tiles, or the previous plane, are consumed
 #pragma unroll
-      for (int i = 0; i < PCH; ++i) {
-        const int c = tid + NT * i;
-        *reinterpret_cast<u32x4*>(smem + (c >> 4) * PSTR + (c & 15) * 16) = preg[i];
-      }
+      for (int part = 0; part < 4; ++part) dma.fetch(p_desc, smem_lds + part * RTILE, 32 * part);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __syncthreads();
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt)
@@ -355,11 +352,11 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
       for (int s = 0; s < 8; ++s)
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(smem + (32 * dt + l32) * PSTR + 16 * h + 32 * s);
-          acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, plane ? dn[s] : rf[s], acc[dt], 0, 0, 0);
+          acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(smem + dt * RTILE, rb, s), plane ? dof[s] : hq[s],
+                                                            acc[dt], 0, 0, 0);
         }
       if (plane == 0) {
-        // dden = -(dO . num) / den^2 ; dnum = dO / den as the next B operand
+        // dden = -(dO . num) / den^2
         const bf16_t* gq = dO + ((size_t)bh * n_q + crow) * D + 4 * h;
         float gn = 0.0f;
 #pragma unroll
@@ -374,10 +371,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
           }
         const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(gn), __float_as_uint(gn), false, false);
         dden = -(__uint_as_float(sw[0]) + __uint_as_float(sw[1])) * inv_den * inv_den;
-#pragma unroll
-        for (int s = 0; s < 8; ++s)
-#pragma unroll
-          for (int e = 0; e < 8; ++e) dn[s][e] = static_cast<__bf16>(static_cast<float>(dof[s][e]) * inv_den);
       }
     }
     // back through the rotation, the denominator's share, phi'
