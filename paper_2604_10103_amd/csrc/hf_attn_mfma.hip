@@ -15,7 +15,7 @@
 //
 // Staging.  K and V tiles go global -> LDS directly (buffer loads with the LDS bit: 16 bytes per lane,
 // 1 KB = 4 key rows per instruction, no staging registers, no LDS stores), row-major with the 16-byte
-// units of a row permuted (K: u ^ (row & 15), V: u ^ 2 (row & 7)) by choosing which global unit a lane
+// units of a row permuted (K: u ^ (row & 15), V: u ^ (4 (row & 3) | (row >> 2 & 3))) by choosing which global unit a lane
 // fetches.  A K fragment is one 16-byte read; a V^T fragment is two transposing 8-byte reads
 // (ds_read_b64_tr_b16: a 16-lane group fetches 4 key rows x 16 features and every lane receives the
 // four keys of its own feature), which is exactly the key order above.  Both patterns are conflict free.
@@ -166,7 +166,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
   for (int j = 0; j < CPT; ++j) {
     const int r = 4 * (wave + NW * j) + (lane >> 4), u = lane & 15;
     k_lane_off[j] = r * (D * 2) + ((u ^ (r & 15)) * 16);
-    v_lane_off[j] = r * (D * 2) + ((u ^ (2 * (r & 7))) * 16);
+    v_lane_off[j] = r * (D * 2) + ((u ^ (((r & 3) << 2) | ((r >> 2) & 3))) * 16);
   }
   // the tile's first key moves into the descriptor (base and size, scalar arithmetic): the per-lane offsets
   // stay constant and the range check still ends at the head's last key
@@ -193,16 +193,21 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
   // each lane receives the four keys of its own feature column
   const int j16 = lane & 15, grp16 = lane >> 4;
   const int key_l = 4 * h + (j16 >> 2);                                  // key within the group of 8, = key & 7
-  const int w_l = (2 * (grp16 & 1) + ((j16 & 3) >> 1)) ^ (2 * key_l);     // swizzled unit for dt = 0
-  const uint32_t v_rd = key_l * KSTR + w_l * 16 + 8 * (j16 & 1);         // ^ (64 dt), + 4096 t2 + 2048 x
+  // unit u of key row r sits at u ^ (4 (r & 3) | (r >> 2 & 3)): the 32 lanes of two groups then touch 4 rows x 4
+  // units = 16 different units.  For the row 16 t2 + 8 x + key_l that is 4 (key_l & 3) | 2 x | h.
+  const int w_l = (4 * (key_l & 3)) | ((2 * (grp16 & 1) + ((j16 & 3) >> 1)) ^ h);   // swizzled unit for dt = 0, x = 0
+  const uint32_t v_rd = key_l * KSTR + w_l * 16 + 8 * (j16 & 1);   // ^ (64 dt) ^ (32 x), + 4096 t2 + 2048 x
 
   // ---- prologue: K and V of tile 0 and K of tile 1 land, the K fragments of tile 0 are read into registers
   typedef short s16x4 __attribute__((ext_vector_type(4)));
-  uint32_t k_addr[8], v_addr[4];
+  uint32_t k_addr[8], v_addr[4][2];
 #pragma unroll
   for (int s = 0; s < 8; ++s) k_addr[s] = k_rd ^ (32u * s);
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt) v_addr[dt] = v_rd ^ (64u * dt);
+  for (int dt = 0; dt < 4; ++dt) {
+    v_addr[dt][0] = v_rd ^ (64u * dt);
+    v_addr[dt][1] = v_rd ^ (64u * dt) ^ 32u;
+  }
   int start_a, start_b, start_c, valid0, valid1, valid2, valid3;   // starts of tiles t+1, t+2, t+3
   {
     int st0;
@@ -249,9 +254,10 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
 
     // V fragments of tile t and K fragments of tile t+1: the reads complete under the softmax
     auto v_frag = [&](int dt, int t2) {
-      const char* p = sV + v_addr[dt] + par * KTILE + 4096 * t2;
+      const char* p = sV + v_addr[dt][0] + par * KTILE + 4096 * t2;
+      const char* q = sV + v_addr[dt][1] + par * KTILE + 4096 * t2 + 2048;
       const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p));
-      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p + 2048));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(q));
       typedef short s16x8 __attribute__((ext_vector_type(8)));
       const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
       return __builtin_bit_cast(bf16x8, both);

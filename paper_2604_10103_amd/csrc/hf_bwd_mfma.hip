@@ -40,10 +40,10 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
 // A 32-token tile sits in LDS row-major, 256 B per token, the 16-byte units of a row permuted:
-// unit u of row r is stored at u ^ swz(r), swz(r) = 2 (r & 7) | ((r >> 3) & 1).  With it both access
-// patterns below are free of bank conflicts: 16-byte reads of one unit from 16 consecutive rows (16 different
-// units) and the transposing reads of two units from 4 consecutive rows (8 different units).
-__device__ __forceinline__ int swz(int r) { return ((r & 7) << 1) | ((r >> 3) & 1); }
+// unit u of row r is stored at u ^ swz(r), swz(r) = 4 (r & 3) | (r >> 2 & 3).  With it both access patterns
+// below are free of bank conflicts: 16-byte reads of one unit from 16 consecutive rows (16 different units)
+// and the transposing reads, whose 32 lanes of two groups touch 4 consecutive rows x 4 units (16 different units).
+__device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
 
 // buffer descriptor of [rows x 128] bf16 at p (range check ends at the last row)
 __device__ __forceinline__ i32x4 desc_of(const bf16_t* p, int rows) {
@@ -94,16 +94,16 @@ __device__ __forceinline__ bf16x8 rows_frag(const char* sX, uint32_t base, int s
 // A operand, features as rows: feature 32 ft + l32, tokens 16 t2 + 8 x + 4 h .. + 4 for x = 0, 1, by two
 // transposing reads (a 16-lane group fetches 4 token rows x 16 features as 16 chunks of 8 bytes, lane j the
 // chunk (row j / 4, features 4 (j % 4)); every lane receives the four tokens of its own feature):
-// byte (tr_base(lane) ^ (64 ft) ^ (16 x)) + 4096 t2 + 2048 x
+// byte (tr_base(lane) ^ (64 ft) ^ (32 x)) + 4096 t2 + 2048 x   (row 16 t2 + 8 x + key_l: swz = 4 (key_l & 3) | 2 x | h)
 __device__ __forceinline__ uint32_t tr_base(int lane) {
   const int j = lane & 15, g = lane >> 4, h = lane >> 5;
   const int key_l = 4 * h + (j >> 2);
-  const int c = (2 * (g & 1) + ((j & 3) >> 1)) ^ (2 * key_l);
+  const int c = (4 * (key_l & 3)) | ((2 * (g & 1) + ((j & 3) >> 1)) ^ h);
   return key_l * RSTR + 16 * c + 8 * (j & 1);
 }
 __device__ __forceinline__ bf16x8 transposed_frag(const char* sX, uint32_t base, int ft, int t2) {
   const char* p0 = sX + (base ^ (64u * ft)) + 4096 * t2;
-  const char* p1 = sX + (base ^ (64u * ft) ^ 16u) + 4096 * t2 + 2048;
+  const char* p1 = sX + (base ^ (64u * ft) ^ 32u) + 4096 * t2 + 2048;
   const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
   const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p1));
   const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};

@@ -284,11 +284,11 @@ constexpr int RTILE = TT * D * 2;    // bytes of one tile of one tensor
 constexpr int RUN_TILES = 9;         // tiles requested up front
 constexpr int DMA_LDS = RUN_TILES * 2 * RTILE + D * 4;
 
-__device__ __forceinline__ int swz(int r) { return ((r & 7) << 1) | ((r >> 3) & 1); }
+__device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }   // see hf_bwd_mfma.hip
 
 __device__ __forceinline__ bf16x8 tr_frag(const char* tile, uint32_t base, int ft, int t2) {
   const char* p0 = tile + (base ^ (64u * ft)) + 4096 * t2;
-  const char* p1 = tile + (base ^ (64u * ft) ^ 16u) + 4096 * t2 + 2048;
+  const char* p1 = tile + (base ^ (64u * ft) ^ 32u) + 4096 * t2 + 2048;
   const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
   const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p1));
   const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
@@ -323,7 +323,7 @@ __global__ __launch_bounds__(NT, 1) void absorb_dma_kernel(float* __restrict__ p
   {
     const int j = lane & 15, g = lane >> 4;
     const int key_l = 4 * h + (j >> 2);
-    const int c = (2 * (g & 1) + ((j & 3) >> 1)) ^ (2 * key_l);
+    const int c = (4 * (key_l & 3)) | ((2 * (g & 1) + ((j & 3) >> 1)) ^ h);
     tb = key_l * (D * 2) + 16 * c + 8 * (j & 1);
   }
 
