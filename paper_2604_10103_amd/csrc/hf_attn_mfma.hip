@@ -131,8 +131,8 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
   // ---- tile list: (selected block, 32-key part) -> (first key, number of real keys).  Tiles past
   // the end of the list and out-of-range block indices give (0, 0): such a tile reads real rows and
   // is masked entirely.  The descriptors are formed 64 tiles at a time, lane l holding tile 64 c + l,
-  // and handed out with one v_readlane per tile: the scalar bookkeeping (and the scalar load of the
-  // block index, whose wait would drain the LDS queue) stays out of the tile loop.
+  // and handed out with one v_readlane per tile: the bookkeeping and the load of the block index stay
+  // out of the tile loop.
   int d_tile = 0, tq = 0;  // first key (24 bits: the window has fewer than 2^23 keys) | real keys << 24
   auto refill = [&](int t0) {
     const int t = t0 + lane;
@@ -154,8 +154,8 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
 
   // ---- staging: K and V tiles go global -> LDS directly (16 bytes per lane, 1 KB = 4 key rows per
   // instruction), row-major with swizzled 16-byte units: K unit u of row r sits at u ^ (r & 15), V unit u
-  // at u ^ 2 (r & 7).  Rows past n_kv read as zero (range check on the vector offset).
-  // K has three slots, V two: in iteration t, V of tile t+1 and then K of tile t+2 are requested.
+  // at u ^ (4 (r & 3) | (r >> 2 & 3)).  Rows past n_kv arrive as zeros (range check of the descriptor).
+  // K has three slots, V two: in iteration t, V of tile t+1 and then K of tile t+3 are requested.
   typedef int i32x4 __attribute__((ext_vector_type(4)));
   const uint64_t kbase = reinterpret_cast<uint64_t>(Kh), vbase = reinterpret_cast<uint64_t>(Vh);
   const i32x4 k_desc = {(int)(uint32_t)kbase, (int)(uint32_t)(kbase >> 32), n_kv * (D * 2), 0x00020000};
@@ -198,7 +198,8 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
   const int w_l = (4 * (key_l & 3)) | ((2 * (grp16 & 1) + ((j16 & 3) >> 1)) ^ h);   // swizzled unit for dt = 0, x = 0
   const uint32_t v_rd = key_l * KSTR + w_l * 16 + 8 * (j16 & 1);   // ^ (64 dt) ^ (32 x), + 4096 t2 + 2048 x
 
-  // ---- prologue: K and V of tile 0 and K of tile 1 land, the K fragments of tile 0 are read into registers
+  // ---- prologue: K and V of tile 0 land (K of tiles 1 and 2 are on their way), the K fragments of tile 0 are
+  // read into registers
   typedef short s16x4 __attribute__((ext_vector_type(4)));
   uint32_t k_addr[8], v_addr[4][2];
 #pragma unroll

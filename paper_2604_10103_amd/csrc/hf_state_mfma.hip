@@ -282,7 +282,7 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 constexpr int TT = 32;               // tokens per tile
 constexpr int RTILE = TT * D * 2;    // bytes of one tile of one tensor
 constexpr int RUN_TILES = 9;         // tiles requested up front
-constexpr int DMA_LDS = RUN_TILES * 2 * RTILE + D * 4;
+constexpr int DMA_LDS = RUN_TILES * 2 * RTILE;
 
 __device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }   // see hf_bwd_mfma.hip
 
@@ -298,8 +298,7 @@ __device__ __forceinline__ bf16x8 tr_frag(const char* tile, uint32_t base, int f
 __global__ __launch_bounds__(NT, 1) void absorb_dma_kernel(float* __restrict__ partials, const bf16_t* __restrict__ K,
                                                            const bf16_t* __restrict__ V, int n, int head_stride,
                                                            int tokens_per_slice, int slices) {
-  extern __shared__ __attribute__((aligned(16))) char smem[];   // RUN_TILES x (K tile, V tile), then z
-  float* const zs = reinterpret_cast<float*>(smem + RUN_TILES * 2 * RTILE);
+  extern __shared__ __attribute__((aligned(16))) char smem[];   // RUN_TILES x (K tile, V tile)
   const int bh = blockIdx.x / slices, slice = blockIdx.x - bh * slices;
   const int t0 = slice * tokens_per_slice;
   const int t1 = min(n, t0 + tokens_per_slice);
@@ -383,7 +382,6 @@ __global__ __launch_bounds__(NT, 1) void absorb_dma_kernel(float* __restrict__ p
     }
   zacc += __shfl_xor(zacc, 32, kWave);   // the two halves of the tokens
   if ((wave & 1) == 0 && h == 0) L[D * D + 32 * mi0 + l32] = zacc;   // one of the two wavefronts of a key tile
-  (void)zs;
 }
 
 // state += sum over slices of the partials; one thread per 4 consecutive floats of a partial
