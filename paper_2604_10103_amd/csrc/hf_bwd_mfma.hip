@@ -110,6 +110,14 @@ __device__ __forceinline__ bf16x8 transposed_frag(const char* sX, uint32_t base,
   return __builtin_bit_cast(bf16x8, both);
 }
 
+// the same from two ready-made byte offsets (the two transposing reads of one fragment)
+__device__ __forceinline__ bf16x8 tr_frag(const char* sX, uint32_t off0, uint32_t off1) {
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(sX + off0));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(sX + off1));
+  const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8, both);
+}
+
 // this lane's token row as B-operand fragments (features 16 s + 8 h .. + 8), zero past the end
 __device__ __forceinline__ void row_frags(__amdgpu_buffer_rsrc_t rsrc, int row, int h, bf16x8 (&f)[8]) {
 #pragma unroll
@@ -428,6 +436,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 // half kw and the 64 features of half dh of dK and dV.  Both feature halves of a key group form S and dP
 // (16 MFMAs each, done twice) and then only their own 8 + 8 accumulating MFMAs: 64 accumulator registers
 // per wavefront instead of 128, which is what lets two wavefronts share a SIMD.
+constexpr int kDkvSlots = 4;   // tiles in LDS: one in use, three on their way
+constexpr int kDkvLds = kDkvSlots * (2 * RTILE + 512);
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void bwd_dkv_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const int32_t* __restrict__ inv_cnt, const int32_t* __restrict__ inv_list,
@@ -435,11 +445,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     int total_items, float c_scale, float scale, const float* __restrict__ lse2, const float* __restrict__ Dv,
     bf16_t* __restrict__ dK, bf16_t* __restrict__ dV) {
   constexpr int NT = 256;
-  __shared__ __attribute__((aligned(16))) char smem[4 * RTILE + 512];   // Q x 2, dO x 2, row statistics x 2
+  constexpr int NSLOT = kDkvSlots;
+  extern __shared__ __attribute__((aligned(16))) char smem[];   // kDkvLds bytes: Q, dO, row statistics per slot
   char* const sQ = smem;
-  char* const sdO = smem + 2 * RTILE;
-  float* const sStat = reinterpret_cast<float*>(smem + 4 * RTILE);   // per slot: lse2[32], D[32]
-  static_assert(64 * OSTR <= 4 * RTILE, "staged output must fit");
+  char* const sdO = smem + NSLOT * RTILE;
+  float* const sStat = reinterpret_cast<float*>(smem + 2 * NSLOT * RTILE);   // per slot: lse2[32] twice, D[32] twice
+  static_assert(64 * OSTR <= 2 * NSLOT * RTILE, "staged output must fit");
 
   // XCD-aware placement as in the dQ kernel: an XCD's L2 then holds the queries and output gradients of few heads
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -472,6 +483,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   bf16x8 kf[8], vf[8];
   row_frags(k_rsrc, key0 + l32, h, kf);
   row_frags(v_rsrc, key0 + l32, h, vf);
+  __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): from here on only the tile transfers are counted
+  // V enters negated: the dP accumulator starts at D and ends at D - dP, so that dS = (-P) (D - dP) costs one
+  // multiplication per element
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+    u32x4 w = __builtin_bit_cast(u32x4, vf[s]);
+    w ^= 0x80008000u;
+    vf[s] = __builtin_bit_cast(bf16x8, w);
+  }
   const uint32_t kmask = l32 < kvalid ? 0xffffffffu : 0u;   // lanes of keys that do not exist contribute nothing
 
   f32x16 dk[2], dv[2];   // features 64 dh + 32 a + ...
@@ -480,77 +500,132 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
     for (int r = 0; r < 16; ++r) { dk[a][r] = 0.0f; dv[a][r] = 0.0f; }
 
-  // tiles of 32 query rows of the listed query blocks: Q and dO of tile n + 1 (and their row statistics) are
-  // on their way into the other slots while tile n is consumed; one barrier per tile.  A tile past n_q reads
-  // zeros and is masked.
+  // tiles of 32 query rows of the listed query blocks.  The rows come from all over the head (whatever query
+  // blocks selected this KV block), so a tile is requested three tiles before its use: Q, dO and the row
+  // statistics of tiles n + 1 .. n + 3 are on their way into the other slots while tile n is consumed; one
+  // barrier per tile.  A tile past n_q reads zeros and is masked.
   const int qtiles = bq / TT;
   const int ntiles = n_lists * qtiles;
-  auto tile_row0 = [&](int n) {   // uniform over the workgroup
-    if (n >= ntiles) return 0;
-    const int t = n / qtiles;
-    return (list ? list[t] : t) * bq + TT * (n - t * qtiles);
+  // List entries are fetched with scalar loads issued one tile ahead of their use and awaited behind the next
+  // barrier (where no LDS read is in flight): a vector load inside the tile loop would have to be awaited together
+  // with every transfer in flight, they share one counter.
+  const int qshift = bq == 64 ? 1 : 2;   // tiles per query block = 2 or 4
+  auto entry_issue = [&](int n) {   // query block of tile n; valid after entry_wait
+    const int t = n >> qshift;
+    int e = t;
+    if (list) {
+      const int off = __builtin_amdgcn_readfirstlane(4 * min(t, max(n_lists - 1, 0)));
+      asm volatile("s_load_dword %0, %1, %2" : "=s"(e) : "s"(list), "s"(off) : "memory");
+    }
+    return e;
   };
-  auto stat_fetch = [&](int r0) {
-    if (tid >= 64) return 0.0f;
-    const int row = min(r0 + (tid & 31), n_q - 1);
-    return tid < 32 ? lseh[row] : Dvh[row];
+  auto entry_wait = [&](int& e) { asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(e) :: "memory"); };
+  auto tile_row0 = [&](int n, int e) {   // first row of tile n, a tile of query block e; uniform over the workgroup
+    return n < ntiles ? e * bq + TT * (n & (qtiles - 1)) : 0;
   };
-  int row0_next = tile_row0(0);
-  dma.fetch(q_desc, sQ_lds, row0_next);
-  dma.fetch(do_desc, sdO_lds, row0_next);
-  float stat = stat_fetch(row0_next);
+  // row statistics global -> LDS like the tiles (4 bytes per lane; both halves of a wavefront fetch the same 32
+  // rows).  Every wavefront issues them, so that all count the same number of transfers per tile.
+  const __amdgpu_buffer_rsrc_t lse_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(lseh), 0, n_q * 4, 0x00020000);
+  const __amdgpu_buffer_rsrc_t dv_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(Dvh), 0, n_q * 4, 0x00020000);
+  const uint32_t sStat_lds = (uint32_t)(uintptr_t)sStat;
+  auto fetch_tile = [&](const int slot_, const int r0_v) {
+    const int r0 = __builtin_amdgcn_readfirstlane(r0_v);
+    dma.fetch(q_desc, sQ_lds + slot_ * RTILE, r0);
+    dma.fetch(do_desc, sdO_lds + slot_ * RTILE, r0);
+    const int off = 4 * min(r0 + l32, n_q - 1);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
+                 :: "s"(sStat_lds + slot_ * 512), "v"(off), "s"(lse_rsrc) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
+                 :: "s"(sStat_lds + slot_ * 512 + 256), "v"(off), "s"(dv_rsrc) : "memory", "m0");
+  };
+  constexpr int kPerTile = 2 * TileDma<4>::CPT + 2;   // transfers a wavefront issues per tile
+  int e0 = entry_issue(0), e1 = entry_issue(1), e2 = entry_issue(2), e_next = entry_issue(3);
+  entry_wait(e0);
+  entry_wait(e1);
+  entry_wait(e2);
+  entry_wait(e_next);
+  int row0_a = tile_row0(0, e0), row0_b = tile_row0(1, e1), row0_c = tile_row0(2, e2);   // first rows of tiles n .. n + 2
+  fetch_tile(0, row0_a);
+  fetch_tile(1, row0_b);
+  fetch_tile(2, row0_c);
+  // tile n sits in slot n mod 4 = 2 half + par: par is a literal at the call sites (an immediate offset of the
+  // LDS reads), half flips every two tiles and lives in the tile read offsets themselves as bit 14 (with all four
+  // slot numbers as literals the loop body no longer fits the register file)
+  int half = 0;
+  uint32_t row_off[8], tr_off[2][2];
+#pragma unroll
+  for (int s = 0; s < 8; ++s) row_off[s] = rb ^ (32u * s);
+#pragma unroll
+  for (int a = 0; a < 2; ++a) {
+    tr_off[a][0] = tb ^ (64u * (2 * dh + a));
+    tr_off[a][1] = (tb ^ (64u * (2 * dh + a)) ^ 32u) + 2048;
+  }
+  const uint32_t stat_off = 16 * h;
+  static_assert(2 * RTILE == (1 << 14), "the half bit of the tile offsets");
   auto tile_step = [&](const int n, const int par) {
-    const int row0 = row0_next;
-    if (tid < 64) sStat[64 * par + tid] = stat;          // this slot's statistics were last read two tiles ago
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's parts of tile n
+    const int row0 = row0_a;
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * kPerTile) : "memory");   // this wavefront's parts of tile n
     __syncthreads();                                   // tile n complete, tile n - 1 consumed by everybody
-    row0_next = tile_row0(n + 1);
-    dma.fetch(q_desc, sQ_lds + (par ^ 1) * RTILE, row0_next);
-    dma.fetch(do_desc, sdO_lds + (par ^ 1) * RTILE, row0_next);
-    stat = stat_fetch(row0_next);
+    entry_wait(e_next);
+    const int row0_d = tile_row0(n + 3, e_next);
+    fetch_tile((2 * half + par + 3) & (NSLOT - 1), row0_d);
+    e_next = entry_issue(n + 4);
+    row0_a = row0_b;
+    row0_b = row0_c;
+    row0_c = row0_d;
     const char* tQ = sQ + par * RTILE;
     const char* tdO = sdO + par * RTILE;
-    const float* tS = sStat + 64 * par;
+    const char* tS = reinterpret_cast<const char*>(sStat) + 512 * par + 1024 * half + stat_off;
     f32x16 sacc, dpacc;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { sacc[r] = 0.0f; dpacc[r] = 0.0f; }
+    for (int r = 0; r < 16; ++r) sacc[r] = 0.0f;
+    float lsr[16];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const float4 l4 = *reinterpret_cast<const float4*>(tS + 32 * g);
+      const float4 d4 = *reinterpret_cast<const float4*>(tS + 256 + 32 * g);
+      lsr[4 * g] = l4.x; lsr[4 * g + 1] = l4.y; lsr[4 * g + 2] = l4.z; lsr[4 * g + 3] = l4.w;
+      dpacc[4 * g] = d4.x; dpacc[4 * g + 1] = d4.y; dpacc[4 * g + 2] = d4.z; dpacc[4 * g + 3] = d4.w;
+    }
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
-      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(tQ, rb, s), kf[s], sacc, 0, 0, 0);
-      dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(tdO, rb, s), vf[s], dpacc, 0, 0, 0);
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(tQ + row_off[s]), kf[s], sacc, 0, 0, 0);
+      dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(tdO + row_off[s]), vf[s], dpacc, 0, 0, 0);
     }
     bf16x8 pf[2], dsf[2];
-    // probabilities masked by bit operations (a select around the exponential would become a branch per element):
-    // lanes of keys that do not exist, and, in the one tile that crosses n_q, rows that do not exist
+    // P = 2^(c S - lse2) and dS = (-P) (D - dP).  In a ragged tile (keys that do not exist in this wavefront, or
+    // the tile that crosses n_q) the probabilities are masked by bit operations: a select around the exponential
+    // would become a branch per element.
     auto probs = [&](const bool ragged) {
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const float4 l4 = *reinterpret_cast<const float4*>(tS + 8 * g + 4 * h);
-        const float4 d4 = *reinterpret_cast<const float4*>(tS + 32 + 8 * g + 4 * h);
-        const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, ds[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int r = 4 * g + i;
-          const uint32_t keep = (!ragged || row0 + 8 * g + 4 * h + i < n_q) ? kmask : 0u;
-          const float p = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(sacc[r], c_scale, -ls[i]))) & keep);
-          pf[r >> 3][r & 7] = static_cast<__bf16>(p);
-          dsf[r >> 3][r & 7] = static_cast<__bf16>(p * (dpacc[r] - ds[i]));
+      for (int r = 0; r < 16; ++r) {
+        float p = __builtin_amdgcn_exp2f(fmaf(sacc[r], c_scale, -lsr[r]));
+        if (ragged) {
+          const uint32_t keep = (row0 + 8 * (r >> 2) + 4 * h + (r & 3) < n_q) ? kmask : 0u;
+          p = __uint_as_float(__float_as_uint(p) & keep);
         }
+        pf[r >> 3][r & 7] = static_cast<__bf16>(p);
+        dsf[r >> 3][r & 7] = static_cast<__bf16>(-p * dpacc[r]);
       }
     };
-    if (row0 + TT <= n_q) probs(false); else probs(true);   // uniform
+    if (row0 + TT <= n_q && kvalid >= 32) probs(false); else probs(true);   // uniform
 #pragma unroll
     for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
       for (int a = 0; a < 2; ++a) {
-        dv[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(transposed_frag(tdO, tb, 2 * dh + a, t2), pf[t2], dv[a], 0, 0, 0);
-        dk[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(transposed_frag(tQ, tb, 2 * dh + a, t2), dsf[t2], dk[a], 0, 0, 0);
+        dv[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(tdO + 4096 * t2, tr_off[a][0], tr_off[a][1]), pf[t2], dv[a], 0, 0, 0);
+        dk[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(tQ + 4096 * t2, tr_off[a][0], tr_off[a][1]), dsf[t2], dk[a], 0, 0, 0);
       }
   };
   for (int n = 0; n < ntiles; n += 2) {
     tile_step(n, 0);
     if (n + 1 >= ntiles) break;
     tile_step(n + 1, 1);
+    half ^= 1;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) row_off[s] ^= 1u << 14;
+#pragma unroll
+    for (int a = 0; a < 2; ++a) { tr_off[a][0] ^= 1u << 14; tr_off[a][1] ^= 1u << 14; }
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing may land in LDS once the tiles' space is reused
 
@@ -640,7 +715,17 @@ int launch_bwd_mfma(const hf_config& c, const void* Q, int n_q, const void* K, c
   const long long kv_items = (long long)BH * t_n * slabs;
   if (kv_items > (1ll << 30)) { set_error("too many KV slabs"); return HF_ERR_SHAPE; }
   const int kv_per_xcd = (int)((kv_items + 7) / 8);
-  hipLaunchKernelGGL(bwd_dkv_mfma_kernel, dim3(8 * kv_per_xcd), dim3(256), 0, s, q, kk, v, g, inv_cnt, inv_list, n_q,
+  static bool dkv_ready = false;
+  if (!dkv_ready) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dkv_mfma_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kDkvLds) != hipSuccess) {
+      (void)hipGetLastError();
+      set_error("cannot reserve %d bytes of LDS for the dK/dV kernel", kDkvLds);
+      return HF_ERR_HIP;
+    }
+    dkv_ready = true;
+  }
+  hipLaunchKernelGGL(bwd_dkv_mfma_kernel, dim3(8 * kv_per_xcd), dim3(256), kDkvLds, s, q, kk, v, g, inv_cnt, inv_list, n_q,
                      n_kv, kvs, c.block_q, c.block_kv, t_m, t_n, slabs, kv_per_xcd, (int)kv_items, c_scale, scale, lse2,
                      Dv, static_cast<bf16_t*>(dK), static_cast<bf16_t*>(dV));
   return check_launch("hf_hybrid_attn_bwd(dK, dV)");
