@@ -110,14 +110,6 @@ __device__ __forceinline__ bf16x8 transposed_frag(const char* sX, uint32_t base,
   return __builtin_bit_cast(bf16x8, both);
 }
 
-// the same from two ready-made byte offsets (the two transposing reads of one fragment)
-__device__ __forceinline__ bf16x8 tr_frag(const char* sX, uint32_t off0, uint32_t off1) {
-  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(sX + off0));
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(sX + off1));
-  const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-  return __builtin_bit_cast(bf16x8, both);
-}
-
 // this lane's token row as B-operand fragments (features 16 s + 8 h .. + 8), zero past the end
 __device__ __forceinline__ void row_frags(__amdgpu_buffer_rsrc_t rsrc, int row, int h, bf16x8 (&f)[8]) {
 #pragma unroll
@@ -432,19 +424,31 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 }
 
 // ------------------------------------------------------------------------------------------ dK, dV
-// One workgroup per slab of 64 keys of a KV block, four wavefronts: wavefront (kw, dh) owns the 32 keys of
-// half kw and the 64 features of half dh of dK and dV.  Both feature halves of a key group form S and dP
-// (16 MFMAs each, done twice) and then only their own 8 + 8 accumulating MFMAs: 64 accumulator registers
-// per wavefront instead of 128, which is what lets two wavefronts share a SIMD.
+// One workgroup per slab of 64 keys of a KV block, two wavefronts of 32 keys each; a wavefront owns all 128
+// features of dK and dV of its keys: 128 accumulator registers that only MFMAs touch until the end, which is what
+// the second half of the register file (one wavefront per SIMD: 512 registers) is for.  Per tile of 32 query rows
+// a wavefront issues 16 MFMAs for S and dP and 16 for dV and dK, nothing is computed twice.
+// acc += A B with the accumulator pinned to the accumulation half of the register file (the compiler, left to
+// itself, keeps such accumulators in ordinary registers and shuttles others through that half).  The compiler
+// counts no wait states for inline assembly, so they are provided here: A comes from LDS reads, which it awaits as
+// for any use; C is the same accumulator's previous value, eight MFMAs back; B is a vector ALU result, and an MFMA
+// may not read one in the two issue slots after it was written: kWait = true puts two idle slots first, for the
+// first reader of a B operand.  volatile keeps the MFMAs in program order, so that the first reader stays the first.
+template <bool kWait>
+__device__ __forceinline__ void mfma_acc(f32x16& acc, const bf16x8 a, const bf16x8 b) {
+  if (kWait) asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+  else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
 constexpr int kDkvSlots = 4;   // tiles in LDS: one in use, three on their way
 constexpr int kDkvLds = kDkvSlots * (2 * RTILE + 512);
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void bwd_dkv_mfma_kernel(
+__global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) void bwd_dkv_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const int32_t* __restrict__ inv_cnt, const int32_t* __restrict__ inv_list,
     int n_q, int n_kv, int kv_stride, int bq, int bkv, int t_m, int t_n, int slabs, int items_per_xcd,
     int total_items, float c_scale, float scale, const float* __restrict__ lse2, const float* __restrict__ Dv,
     bf16_t* __restrict__ dK, bf16_t* __restrict__ dV) {
-  constexpr int NT = 256;
+  constexpr int NT = 128;
   constexpr int NSLOT = kDkvSlots;
   extern __shared__ __attribute__((aligned(16))) char smem[];   // kDkvLds bytes: Q, dO, row statistics per slot
   char* const sQ = smem;
@@ -460,10 +464,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int rest = item - bh * (t_n * slabs);
   const int jb = rest / slabs, slab = rest - jb * slabs;
   const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int kw = wave & 1, dh = wave >> 1;
+  const int kw = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, h = lane >> 5;
-  const TileDma<4> dma(wave, lane);
+  const TileDma<2> dma(kw, lane);
   const i32x4 q_desc = desc_of(Q + (size_t)bh * n_q * D, n_q);
   const i32x4 do_desc = desc_of(dO + (size_t)bh * n_q * D, n_q);
   const uint32_t sQ_lds = (uint32_t)(uintptr_t)sQ, sdO_lds = (uint32_t)(uintptr_t)sdO;
@@ -475,11 +478,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   const int n_lists = inv_cnt ? inv_cnt[(size_t)bh * t_n + jb] : t_m;   // no lists: every query block (dense)
   const int32_t* list = inv_list ? inv_list + ((size_t)bh * t_n + jb) * t_m : nullptr;
 
-  // this wavefront's 32 keys; a wavefront past the block's end carries no real key
+  // this wavefront's 32 keys (keys past the block's end are computed along and never stored)
   const int blk_end = min(n_kv, (jb + 1) * bkv);
   const int first_key = jb * bkv + 64 * slab;
   const int key0 = first_key + 32 * kw;
-  const int kvalid = min(32, blk_end - key0);          // may be <= 0
   bf16x8 kf[8], vf[8];
   row_frags(k_rsrc, key0 + l32, h, kf);
   row_frags(v_rsrc, key0 + l32, h, vf);
@@ -492,18 +494,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     w ^= 0x80008000u;
     vf[s] = __builtin_bit_cast(bf16x8, w);
   }
-  const uint32_t kmask = l32 < kvalid ? 0xffffffffu : 0u;   // lanes of keys that do not exist contribute nothing
 
-  f32x16 dk[2], dv[2];   // features 64 dh + 32 a + ...
+  f32x16 dk[4], dv[4];
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < 4; ++a)
 #pragma unroll
     for (int r = 0; r < 16; ++r) { dk[a][r] = 0.0f; dv[a][r] = 0.0f; }
 
   // tiles of 32 query rows of the listed query blocks.  The rows come from all over the head (whatever query
   // blocks selected this KV block), so a tile is requested three tiles before its use: Q, dO and the row
   // statistics of tiles n + 1 .. n + 3 are on their way into the other slots while tile n is consumed; one
-  // barrier per tile.  A tile past n_q reads zeros and is masked.
+  // barrier per tile.  Rows past n_q, and whole tiles past the end of the list, read zeros.
   const int qtiles = bq / TT;
   const int ntiles = n_lists * qtiles;
   // List entries are fetched with scalar loads issued one tile ahead of their use and awaited behind the next
@@ -521,10 +522,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   };
   auto entry_wait = [&](int& e) { asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(e) :: "memory"); };
   auto tile_row0 = [&](int n, int e) {   // first row of tile n, a tile of query block e; uniform over the workgroup
-    return n < ntiles ? e * bq + TT * (n & (qtiles - 1)) : 0;
+    return n < ntiles ? e * bq + TT * (n & (qtiles - 1)) : n_q;   // a tile past the list lies past the head: zeros
   };
-  // row statistics global -> LDS like the tiles (4 bytes per lane; both halves of a wavefront fetch the same 32
-  // rows).  Every wavefront issues them, so that all count the same number of transfers per tile.
+  // row statistics global -> LDS like the tiles (4 bytes per lane; both halves of the wavefront fetch the same 32
+  // rows).  Both wavefronts issue them, so that they count the same number of transfers per tile.
   const __amdgpu_buffer_rsrc_t lse_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(lseh), 0, n_q * 4, 0x00020000);
   const __amdgpu_buffer_rsrc_t dv_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(Dvh), 0, n_q * 4, 0x00020000);
   const uint32_t sStat_lds = (uint32_t)(uintptr_t)sStat;
@@ -532,13 +533,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int r0 = __builtin_amdgcn_readfirstlane(r0_v);
     dma.fetch(q_desc, sQ_lds + slot_ * RTILE, r0);
     dma.fetch(do_desc, sdO_lds + slot_ * RTILE, r0);
-    const int off = 4 * min(r0 + l32, n_q - 1);
+    const int off = 4 * (r0 + l32);   // a row past n_q is past the descriptor's end: zero
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
                  :: "s"(sStat_lds + slot_ * 512), "v"(off), "s"(lse_rsrc) : "memory", "m0");
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
                  :: "s"(sStat_lds + slot_ * 512 + 256), "v"(off), "s"(dv_rsrc) : "memory", "m0");
   };
-  constexpr int kPerTile = 2 * TileDma<4>::CPT + 2;   // transfers a wavefront issues per tile
+  constexpr int kPerTile = 2 * TileDma<2>::CPT + 2;   // transfers a wavefront issues per tile
   int e0 = entry_issue(0), e1 = entry_issue(1), e2 = entry_issue(2), e_next = entry_issue(3);
   entry_wait(e0);
   entry_wait(e1);
@@ -548,101 +549,92 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   fetch_tile(0, row0_a);
   fetch_tile(1, row0_b);
   fetch_tile(2, row0_c);
-  // tile n sits in slot n mod 4 = 2 half + par: par is a literal at the call sites (an immediate offset of the
-  // LDS reads), half flips every two tiles and lives in the tile read offsets themselves as bit 14 (with all four
-  // slot numbers as literals the loop body no longer fits the register file)
-  int half = 0;
-  uint32_t row_off[8], tr_off[2][2];
-#pragma unroll
-  for (int s = 0; s < 8; ++s) row_off[s] = rb ^ (32u * s);
-#pragma unroll
-  for (int a = 0; a < 2; ++a) {
-    tr_off[a][0] = tb ^ (64u * (2 * dh + a));
-    tr_off[a][1] = (tb ^ (64u * (2 * dh + a)) ^ 32u) + 2048;
-  }
-  const uint32_t stat_off = 16 * h;
-  static_assert(2 * RTILE == (1 << 14), "the half bit of the tile offsets");
-  auto tile_step = [&](const int n, const int par) {
+  auto tile_step = [&](const int n, const int par) {   // par = n mod 4, a literal at the call sites
     const int row0 = row0_a;
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * kPerTile) : "memory");   // this wavefront's parts of tile n
-    __syncthreads();                                   // tile n complete, tile n - 1 consumed by everybody
+    __syncthreads();                                   // tile n complete, tile n - 1 consumed by both
     entry_wait(e_next);
     const int row0_d = tile_row0(n + 3, e_next);
-    fetch_tile((2 * half + par + 3) & (NSLOT - 1), row0_d);
+    fetch_tile((par + 3) % NSLOT, row0_d);
     e_next = entry_issue(n + 4);
     row0_a = row0_b;
     row0_b = row0_c;
     row0_c = row0_d;
     const char* tQ = sQ + par * RTILE;
     const char* tdO = sdO + par * RTILE;
-    const char* tS = reinterpret_cast<const char*>(sStat) + 512 * par + 1024 * half + stat_off;
+    const float* tS = sStat + 128 * par;
     f32x16 sacc, dpacc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) sacc[r] = 0.0f;
     float lsr[16];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-      const float4 l4 = *reinterpret_cast<const float4*>(tS + 32 * g);
-      const float4 d4 = *reinterpret_cast<const float4*>(tS + 256 + 32 * g);
+      const float4 l4 = *reinterpret_cast<const float4*>(tS + 8 * g + 4 * h);
+      const float4 d4 = *reinterpret_cast<const float4*>(tS + 64 + 8 * g + 4 * h);
       lsr[4 * g] = l4.x; lsr[4 * g + 1] = l4.y; lsr[4 * g + 2] = l4.z; lsr[4 * g + 3] = l4.w;
       dpacc[4 * g] = d4.x; dpacc[4 * g + 1] = d4.y; dpacc[4 * g + 2] = d4.z; dpacc[4 * g + 3] = d4.w;
     }
+    // all fragments of a phase are requested before its first MFMA (there are registers for it: one wavefront per
+    // SIMD), the transposed ones of the second phase before the vector work between the phases
+    bf16x8 qa[8], ga[8];
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
-      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(tQ + row_off[s]), kf[s], sacc, 0, 0, 0);
-      dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(tdO + row_off[s]), vf[s], dpacc, 0, 0, 0);
+      qa[s] = rows_frag(tQ, rb, s);
+      ga[s] = rows_frag(tdO, rb, s);
     }
-    bf16x8 pf[2], dsf[2];
-    // P = 2^(c S - lse2) and dS = (-P) (D - dP).  In a ragged tile (keys that do not exist in this wavefront, or
-    // the tile that crosses n_q) the probabilities are masked by bit operations: a select around the exponential
-    // would become a branch per element.
-    auto probs = [&](const bool ragged) {
+    __builtin_amdgcn_sched_barrier(0);   // (the scheduler would move each read next to its MFMA)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float p = __builtin_amdgcn_exp2f(fmaf(sacc[r], c_scale, -lsr[r]));
-        if (ragged) {
-          const uint32_t keep = (row0 + 8 * (r >> 2) + 4 * h + (r & 3) < n_q) ? kmask : 0u;
-          p = __uint_as_float(__float_as_uint(p) & keep);
-        }
-        pf[r >> 3][r & 7] = static_cast<__bf16>(p);
-        dsf[r >> 3][r & 7] = static_cast<__bf16>(-p * dpacc[r]);
-      }
-    };
-    if (row0 + TT <= n_q && kvalid >= 32) probs(false); else probs(true);   // uniform
+    for (int s = 0; s < 8; ++s) {
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[s], kf[s], sacc, 0, 0, 0);
+      dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga[s], vf[s], dpacc, 0, 0, 0);
+    }
+    bf16x8 qt[2][4], gt[2][4];
 #pragma unroll
     for (int t2 = 0; t2 < 2; ++t2)
 #pragma unroll
-      for (int a = 0; a < 2; ++a) {
-        dv[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(tdO + 4096 * t2, tr_off[a][0], tr_off[a][1]), pf[t2], dv[a], 0, 0, 0);
-        dk[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(tQ + 4096 * t2, tr_off[a][0], tr_off[a][1]), dsf[t2], dk[a], 0, 0, 0);
+      for (int ft = 0; ft < 4; ++ft) {
+        gt[t2][ft] = transposed_frag(tdO, tb, ft, t2);
+        qt[t2][ft] = transposed_frag(tQ, tb, ft, t2);
+      }
+    __builtin_amdgcn_sched_barrier(0);   // the reads above stay above the vector work below
+    bf16x8 pf[2], dsf[2];
+    // P = 2^(c S - lse2) and dS = (-P) (D - dP).  Nothing is masked: a query row that does not exist has zeros for
+    // Q, dO, lse2 and D in LDS (P = 1, dS = 0, and its columns of Q^T and dO^T are zero), and a key that does not
+    // exist owns a column of dK^T and dV^T that is never stored.
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float p = __builtin_amdgcn_exp2f(fmaf(sacc[r], c_scale, -lsr[r]));
+      pf[r >> 3][r & 7] = static_cast<__bf16>(p);
+      dsf[r >> 3][r & 7] = static_cast<__bf16>(-p * dpacc[r]);
+    }
+#pragma unroll
+    for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+      for (int ft = 0; ft < 4; ++ft) {
+        if (ft == 0) {   // first readers of pf[t2] and dsf[t2]
+          mfma_acc<true>(dv[ft], gt[t2][ft], pf[t2]);
+          mfma_acc<true>(dk[ft], qt[t2][ft], dsf[t2]);
+        } else {
+          mfma_acc<false>(dv[ft], gt[t2][ft], pf[t2]);
+          mfma_acc<false>(dk[ft], qt[t2][ft], dsf[t2]);
+        }
       }
   };
-  for (int n = 0; n < ntiles; n += 2) {
+  for (int n = 0; n < ntiles; n += 4) {   // slot numbers are literals
     tile_step(n, 0);
-    if (n + 1 >= ntiles) break;
     tile_step(n + 1, 1);
-    half ^= 1;
-#pragma unroll
-    for (int s = 0; s < 8; ++s) row_off[s] ^= 1u << 14;
-#pragma unroll
-    for (int a = 0; a < 2; ++a) { tr_off[a][0] ^= 1u << 14; tr_off[a][1] ^= 1u << 14; }
+    tile_step(n + 2, 2);
+    tile_step(n + 3, 3);
   }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing may land in LDS once the tiles' space is reused
+  // nothing may land in LDS once the tiles' space is reused; and the last accumulating MFMAs (inline assembly: the
+  // compiler does not count wait states for them) must have written their results before these are read
+  asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
 
   // transpose through LDS and store the rows of real keys, dK first, then dV
   for (int which = 0; which < 2; ++which) {
     __syncthreads();
-    const float mul = which ? 1.0f : scale;
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-      for (int rq = 0; rq < 4; ++rq) {
-        const f32x16& x = which ? dv[a] : dk[a];
-        uint2 w;
-        w.x = (uint32_t)f32_to_bf16(x[4 * rq] * mul) | ((uint32_t)f32_to_bf16(x[4 * rq + 1] * mul) << 16);
-        w.y = (uint32_t)f32_to_bf16(x[4 * rq + 2] * mul) | ((uint32_t)f32_to_bf16(x[4 * rq + 3] * mul) << 16);
-        *reinterpret_cast<uint2*>(smem + (32 * kw + l32) * OSTR + (64 * dh + 32 * a + 8 * rq + 4 * h) * 2) = w;
-      }
+    if (which == 0) stage_rows(smem, 32 * kw + l32, h, dk, scale);
+    else stage_rows(smem, 32 * kw + l32, h, dv, 1.0f);
     __syncthreads();
     bf16_t* out = (which ? dV : dK) + (size_t)bh * kv_stride * D;
 #pragma unroll
@@ -725,7 +717,7 @@ int launch_bwd_mfma(const hf_config& c, const void* Q, int n_q, const void* K, c
     }
     dkv_ready = true;
   }
-  hipLaunchKernelGGL(bwd_dkv_mfma_kernel, dim3(8 * kv_per_xcd), dim3(256), kDkvLds, s, q, kk, v, g, inv_cnt, inv_list, n_q,
+  hipLaunchKernelGGL(bwd_dkv_mfma_kernel, dim3(8 * kv_per_xcd), dim3(128), kDkvLds, s, q, kk, v, g, inv_cnt, inv_list, n_q,
                      n_kv, kvs, c.block_q, c.block_kv, t_m, t_n, slabs, kv_per_xcd, (int)kv_items, c_scale, scale, lse2,
                      Dv, static_cast<bf16_t*>(dK), static_cast<bf16_t*>(dV));
   return check_launch("hf_hybrid_attn_bwd(dK, dV)");
