@@ -253,7 +253,15 @@ def main():
         dQ, dK, dV = torch.empty_like(sets[0]["Q"]), torch.empty_like(sets[0]["K"]), torch.empty_like(sets[0]["V"])
         bwd_ms, _ = time_calls(lambda s: hf.hf_hybrid_attn_bwd(cfg, s["Q"], s["K"], s["V"], s["idx"], s["st"], dO, dQ, dK,
                                                                dV, bws), max(3, min(a.steps, 12)))
-        del bws, dO, dQ, dK, dV
+        # the same from the by-products of the saving forward: O_local and the softmax row statistic
+        Ol = torch.empty_like(sets[0]["Q"])
+        lse = torch.empty((w.batch * w.heads, w.n_q), dtype=torch.float32, device=dev)
+        fwd_save_ms, _ = time_calls(lambda s: hf.hf_hybrid_attn_fwd_save(cfg, s["Q"], s["K"], s["V"], s["idx"], s["st"],
+                                                                         s["O"], Ol, lse, s["ws"]), max(3, min(a.steps, 12)))
+        bwd_saved_ms, _ = time_calls(lambda s: hf.hf_hybrid_attn_bwd_saved(cfg, s["Q"], s["K"], s["V"], s["idx"], s["st"],
+                                                                           dO, Ol, lse, dQ, dK, dV, bws),
+                                     max(3, min(a.steps, 12)))
+        del bws, dO, dQ, dK, dV, Ol, lse
 
     flops = float(np.mean([algorithmic_flops(s["idx"].cpu(), w) for s in sets]))
     dense_flops = 4.0 * w.head_dim * w.n_q * w.n_kv * w.heads * w.batch
@@ -304,7 +312,10 @@ def main():
     if bwd_ms is not None:
         # five products of the forward's size (S, dP, dV, dK, dQ) count; the recomputation does not
         out["backward"] = {"ms": bwd_ms, "tflops": 2.5 * flops / (bwd_ms * 1e-3) / 1e12,
-                           "frac_of_bf16_peak": 2.5 * flops / (bwd_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+                           "frac_of_bf16_peak": 2.5 * flops / (bwd_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                           # training pair: the forward that also writes O_local and the row statistic, and the
+                           # backward pass that starts from them (2 algorithmic products less: no recomputed forward)
+                           "fwd_save_ms": fwd_save_ms, "saved_ms": bwd_saved_ms}
     if dense_ms is not None:
         out["dense"] = {"tflops": dense_flops / (dense_ms * 1e-3) / 1e12,
                         "speedup_sparse_incl_select": dense_ms / (sel_ms + a4_ms),

@@ -233,6 +233,23 @@ HF_API int hf_hybrid_attn_fwd_split(const hf_config* cfg, const void* Q_local, c
 
 /* ---- Backward pass (training algorithm of the supplement) ------------------------------------------- */
 
+/* hf_hybrid_attn_fwd_split as the training algorithm's forward pass of the one denoising step per chunk that
+ * carries gradients: the same O, plus two by-products that spare hf_hybrid_attn_bwd_saved the recomputed
+ * forward pass:
+ *   O_local_out  out [B, H, n_q, d] of cfg->dtype: the sparse branch's output alone (Eq. 5), rounded once
+ *                (equal to O when state_or_null is NULL)
+ *   lse2_out     out float [B*H, n_q]: log2 of the softmax denominator of every query row, logits scaled by
+ *                softmax_scale * log2(e); +inf for a row without a single real key
+ * Covers bf16, head_dim 128, block_q 64 or 128; HF_ERR_SHAPE for any other configuration (use
+ * hf_hybrid_attn_fwd_split and hf_hybrid_attn_bwd there).  Neither output may alias another argument. */
+HF_API int hf_hybrid_attn_fwd_save(const hf_config* cfg, const void* Q_local, const void* Q_hist, int32_t n_q,
+                       const void* K_win, const void* V_win, int32_t n_kv,
+                       const int32_t* block_idx, int32_t k,
+                       const void* state_or_null,
+                       const float* rope_cos_q, const float* rope_sin_q,
+                       void* O, void* O_local_out, float* lse2_out,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
 /* Bytes of scratch hf_hybrid_attn_bwd needs for these sizes.  Host-only. */
 HF_API int hf_bwd_workspace_bytes(const hf_config* cfg, int32_t n_q, int32_t n_kv, size_t* bytes_out);
 
@@ -258,6 +275,20 @@ HF_API int hf_hybrid_attn_bwd(const hf_config* cfg, const void* Q, const void* Q
                        const void* K_win, const void* V_win, int32_t n_kv,
                        const int32_t* block_idx, int32_t k, const void* state_or_null,
                        const float* rope_cos_q, const float* rope_sin_q, const void* dO,
+                       void* dQ, void* dQ_hist, void* dK, void* dV,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* hf_hybrid_attn_bwd from the by-products of hf_hybrid_attn_fwd_save instead of a recomputed forward pass:
+ *   O_local, lse2   exactly what that call wrote (for the same inputs, index lists and state)    read-only
+ * D = dO . O_local is formed from the once-rounded O_local (the recomputing call uses the unrounded one: the
+ * two calls agree to the rounding of O_local).  Same configurations as hf_hybrid_attn_fwd_save; everything
+ * else as hf_hybrid_attn_bwd, the same workspace size included. */
+HF_API int hf_hybrid_attn_bwd_saved(const hf_config* cfg, const void* Q, const void* Q_hist, int32_t n_q,
+                       const void* K_win, const void* V_win, int32_t n_kv,
+                       const int32_t* block_idx, int32_t k,
+                       const void* state_or_null,
+                       const float* rope_cos_q, const float* rope_sin_q,
+                       const void* dO, const void* O_local, const float* lse2,
                        void* dQ, void* dQ_hist, void* dK, void* dV,
                        void* workspace, size_t workspace_bytes, void* stream);
 

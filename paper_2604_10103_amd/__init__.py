@@ -33,4 +33,6 @@ from .binding import (  # noqa: F401
     hf_stream_step,
     hf_bwd_workspace_bytes,
     hf_hybrid_attn_bwd,
+    hf_hybrid_attn_bwd_saved,
+    hf_hybrid_attn_fwd_save,
 )

@@ -92,8 +92,10 @@ def load():
     lib.hf_block_select_cached.argtypes = [CP, P, I, P, I, I, P, P, P, SZ, P]
     lib.hf_hybrid_attn_fwd.argtypes = [CP, P, I, P, P, I, P, I, P, P, P, P, P, SZ, P]
     lib.hf_hybrid_attn_fwd_split.argtypes = [CP, P, P, I, P, P, I, P, I, P, P, P, P, P, SZ, P]
+    lib.hf_hybrid_attn_fwd_save.argtypes = [CP, P, P, I, P, P, I, P, I, P, P, P, P, P, P, P, SZ, P]
     lib.hf_bwd_workspace_bytes.argtypes = [CP, I, I, ctypes.POINTER(SZ)]
     lib.hf_hybrid_attn_bwd.argtypes = [CP, P, P, I, P, P, I, P, I, P, P, P, P, P, P, P, P, P, SZ, P]
+    lib.hf_hybrid_attn_bwd_saved.argtypes = [CP, P, P, I, P, P, I, P, I, P, P, P, P, P, P, P, P, P, P, P, SZ, P]
     lib.hf_rope_window_indices.argtypes = [I, I, I, ctypes.POINTER(I)]
     lib.hf_rope_tables.argtypes = [ctypes.POINTER(I), I, I, I, I, I, I, ctypes.c_double, I, P, P, P]
     lib.hf_rope_apply.argtypes = [CP, P, I, P, P, P, P]
@@ -278,6 +280,32 @@ def hf_hybrid_attn_fwd(cfg: hf_config, Q, K_win, V_win, block_idx, state, O, wor
         _dev(workspace, "workspace", torch.uint8), 0 if workspace is None else workspace.numel(), _stream()))
 
 
+def hf_hybrid_attn_fwd_save(cfg: hf_config, Q, K_win, V_win, block_idx, state, O, O_local_out, lse2_out, workspace=None,
+                            rope_cos_q=None, rope_sin_q=None, Q_hist=None, n_kv=None) -> None:
+    """hf_hybrid_attn_fwd that also writes O_local and the softmax row statistic lse2 [B*H, n_q] (fp32) for
+    hf_hybrid_attn_bwd_saved."""
+    B, H, d = cfg.batch, cfg.heads, cfg.head_dim
+    n_q, n_kv = Q.shape[2], _kv_len(cfg, K_win, n_kv)
+    t_m = _cdiv(n_q, cfg.block_q)
+    k = 0
+    if block_idx is not None:
+        if block_idx.dim() != 4:
+            raise ValueError("block_idx must be [B, H, T_m, k]")
+        k = block_idx.shape[3]
+    tab = (n_q, d // 2)
+    qs = (B, H, n_q, d)
+    _check(load().hf_hybrid_attn_fwd_save(
+        ctypes.byref(cfg), _dev(Q, "Q", _tdtype(cfg), qs), _dev(Q_hist, "Q_hist", _tdtype(cfg), qs), n_q,
+        _dev(K_win, "K_win", _tdtype(cfg), (B, H, K_win.shape[2], d)),
+        _dev(V_win, "V_win", _tdtype(cfg), (B, H, K_win.shape[2], d)), n_kv,
+        _dev(block_idx, "block_idx", torch.int32, (B, H, t_m, k)), k,
+        _dev(state, "state", torch.float32, (hf_state_bytes(cfg) // 4,)),
+        _dev(rope_cos_q, "rope_cos_q", torch.float32, tab), _dev(rope_sin_q, "rope_sin_q", torch.float32, tab),
+        _dev(O, "O", _tdtype(cfg), qs), _dev(O_local_out, "O_local_out", _tdtype(cfg), qs),
+        _dev(lse2_out, "lse2_out", torch.float32, (B * H, n_q)),
+        _dev(workspace, "workspace", torch.uint8), 0 if workspace is None else workspace.numel(), _stream()))
+
+
 def hf_rope_window_indices(i_newest: int, n_frames: int, t0: int) -> list:
     """Eq. 7 with the cache re-based to the current chunk: temporal indices of the last n_frames frames."""
     out = (ctypes.c_int32 * n_frames)()
@@ -371,5 +399,29 @@ def hf_hybrid_attn_bwd(cfg: hf_config, Q, K_win, V_win, block_idx, state, dO, dQ
         _dev(state, "state", torch.float32, (hf_state_bytes(cfg) // 4,)),
         _dev(rope_cos_q, "rope_cos_q", torch.float32, tab), _dev(rope_sin_q, "rope_sin_q", torch.float32, tab),
         _dev(dO, "dO", _tdtype(cfg), qs), _dev(dQ, "dQ", _tdtype(cfg), qs), _dev(dQ_hist, "dQ_hist", _tdtype(cfg), qs),
+        _dev(dK, "dK", _tdtype(cfg), ks), _dev(dV, "dV", _tdtype(cfg), ks),
+        _dev(workspace, "workspace", torch.uint8), 0 if workspace is None else workspace.numel(), _stream()))
+
+
+def hf_hybrid_attn_bwd_saved(cfg: hf_config, Q, K_win, V_win, block_idx, state, dO, O_local, lse2, dQ, dK, dV, workspace,
+                             rope_cos_q=None, rope_sin_q=None, Q_hist=None, dQ_hist=None, n_kv=None) -> None:
+    """hf_hybrid_attn_bwd from O_local and lse2 as hf_hybrid_attn_fwd_save wrote them (no recomputed forward)."""
+    B, H, d = cfg.batch, cfg.heads, cfg.head_dim
+    n_q, n_kv = Q.shape[2], _kv_len(cfg, K_win, n_kv)
+    t_m = _cdiv(n_q, cfg.block_q)
+    k = 0
+    if block_idx is not None:
+        k = block_idx.shape[3]
+    tab = (n_q, d // 2)
+    qs, ks = (B, H, n_q, d), (B, H, K_win.shape[2], d)
+    _check(load().hf_hybrid_attn_bwd_saved(
+        ctypes.byref(cfg), _dev(Q, "Q", _tdtype(cfg), qs), _dev(Q_hist, "Q_hist", _tdtype(cfg), qs), n_q,
+        _dev(K_win, "K_win", _tdtype(cfg), ks), _dev(V_win, "V_win", _tdtype(cfg), ks), n_kv,
+        _dev(block_idx, "block_idx", torch.int32, (B, H, t_m, k)), k,
+        _dev(state, "state", torch.float32, (hf_state_bytes(cfg) // 4,)),
+        _dev(rope_cos_q, "rope_cos_q", torch.float32, tab), _dev(rope_sin_q, "rope_sin_q", torch.float32, tab),
+        _dev(dO, "dO", _tdtype(cfg), qs), _dev(O_local, "O_local", _tdtype(cfg), qs),
+        _dev(lse2, "lse2", torch.float32, (B * H, n_q)),
+        _dev(dQ, "dQ", _tdtype(cfg), qs), _dev(dQ_hist, "dQ_hist", _tdtype(cfg), qs),
         _dev(dK, "dK", _tdtype(cfg), ks), _dev(dV, "dV", _tdtype(cfg), ks),
         _dev(workspace, "workspace", torch.uint8), 0 if workspace is None else workspace.numel(), _stream()))

@@ -305,12 +305,48 @@ int hf_hybrid_attn_fwd(const hf_config* cfg, const void* Q, int32_t n_q, const v
                                   rope_sin_q, O, workspace, workspace_bytes, stream);
 }
 
+// the forward call; save = the training forward, which also writes O_local and the softmax row statistic
+static int fwd_impl(const hf_config* cfg, const void* Q, const void* Q_hist, int32_t n_q, const void* K_win,
+                    const void* V_win, int32_t n_kv, const int32_t* block_idx, int32_t k, const void* state_or_null,
+                    const float* rope_cos_q, const float* rope_sin_q, void* O, bool save, void* O_local_out,
+                    float* lse2_out, void* workspace, size_t workspace_bytes, void* stream);
+
 int hf_hybrid_attn_fwd_split(const hf_config* cfg, const void* Q, const void* Q_hist, int32_t n_q,
                              const void* K_win, const void* V_win, int32_t n_kv, const int32_t* block_idx,
                              int32_t k, const void* state_or_null, const float* rope_cos_q,
                              const float* rope_sin_q, void* O, void* workspace, size_t workspace_bytes,
                              void* stream) {
+  return fwd_impl(cfg, Q, Q_hist, n_q, K_win, V_win, n_kv, block_idx, k, state_or_null, rope_cos_q, rope_sin_q, O,
+                  false, nullptr, nullptr, workspace, workspace_bytes, stream);
+}
+
+int hf_hybrid_attn_fwd_save(const hf_config* cfg, const void* Q, const void* Q_hist, int32_t n_q,
+                            const void* K_win, const void* V_win, int32_t n_kv, const int32_t* block_idx,
+                            int32_t k, const void* state_or_null, const float* rope_cos_q,
+                            const float* rope_sin_q, void* O, void* O_local_out, float* lse2_out, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+  return fwd_impl(cfg, Q, Q_hist, n_q, K_win, V_win, n_kv, block_idx, k, state_or_null, rope_cos_q, rope_sin_q, O,
+                  true, O_local_out, lse2_out, workspace, workspace_bytes, stream);
+}
+
+static int fwd_impl(const hf_config* cfg, const void* Q, const void* Q_hist, int32_t n_q, const void* K_win,
+                    const void* V_win, int32_t n_kv, const int32_t* block_idx, int32_t k, const void* state_or_null,
+                    const float* rope_cos_q, const float* rope_sin_q, void* O, bool save, void* O_local_out,
+                    float* lse2_out, void* workspace, size_t workspace_bytes, void* stream) {
   HF_TRY(check_cfg(cfg));
+  if (save) {
+    HF_TRY(check_ptr(O_local_out, "O_local_out", true));
+    HF_TRY(check_ptr(lse2_out, "lse2_out", true));
+    if (!attn_mfma_fused_supported(*cfg)) {
+      set_error("the saving forward covers bf16, head_dim 128, block_q 64 or 128 (hf_hybrid_attn_bwd recomputes instead)");
+      return HF_ERR_SHAPE;
+    }
+    if (O_local_out == O || O_local_out == Q || O_local_out == Q_hist || O_local_out == K_win || O_local_out == V_win ||
+        static_cast<void*>(lse2_out) == O || static_cast<void*>(lse2_out) == O_local_out) {
+      set_error("O_local_out / lse2_out alias another argument");
+      return HF_ERR_SHAPE;
+    }
+  }
   HF_TRY(check_ptr(Q, "Q", true));
   if (!Q_hist) Q_hist = Q;
   HF_TRY(check_ptr(Q_hist, "Q_hist", true));
@@ -338,7 +374,14 @@ int hf_hybrid_attn_fwd_split(const hf_config* cfg, const void* Q, const void* Q_
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (!state_or_null) {
     // no history yet: O = O_local, written directly
-    return launch_attn(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, O, s);
+    if (!save) return launch_attn(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, O, s);
+    HF_TRY(launch_attn_mfma_lse(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, O, lse2_out, s));
+    const size_t bytes = (size_t)cfg->batch * cfg->heads * n_q * cfg->head_dim * esize(cfg);
+    if (hipMemcpyAsync(O_local_out, O, bytes, hipMemcpyDeviceToDevice, s) != hipSuccess) {
+      set_error("copy of O into O_local_out: %s", hipGetErrorString(hipGetLastError()));
+      return HF_ERR_HIP;
+    }
+    return HF_OK;
   }
   const WorkspaceLayout w = workspace_layout(cfg, n_q, n_kv);
   if (!workspace || workspace_bytes < w.total) {
@@ -347,14 +390,15 @@ int hf_hybrid_attn_fwd_split(const hf_config* cfg, const void* Q, const void* Q_
   }
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) { set_error("workspace is not 256-byte aligned"); return HF_ERR_ALIGN; }
   const char* fuse_env = getenv("HF_FUSED_EPILOGUE");  // "0" keeps the two-kernel path (to time the readout alone)
-  if (attn_mfma_fused_supported(*cfg) && !(fuse_env && fuse_env[0] == '0')) {
+  if (attn_mfma_fused_supported(*cfg) && (save || !(fuse_env && fuse_env[0] == '0'))) {
     // MFMA shapes: the history term is added in the attention kernel's epilogue
     char* planes = static_cast<char*>(workspace) + w.planes;
     const float* st = static_cast<const float*>(state_or_null);
     const size_t d = cfg->head_dim;
     HF_TRY(launch_state_planes(*cfg, st, planes, s));
     return launch_attn_mfma_fused(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, planes,
-                                  st + (size_t)cfg->batch * cfg->heads * d * d, rope_cos_q, rope_sin_q, Q_hist, O, s);
+                                  st + (size_t)cfg->batch * cfg->heads * d * d, rope_cos_q, rope_sin_q, Q_hist, O, s,
+                                  save ? lse2_out : nullptr, save ? O_local_out : nullptr);
   }
   void* o_local = static_cast<char*>(workspace) + w.olocal;
   HF_TRY(launch_attn(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, o_local, s));
@@ -420,12 +464,46 @@ int hf_bwd_workspace_bytes(const hf_config* cfg, int32_t n_q, int32_t n_kv, size
   return HF_OK;
 }
 
+// the backward call; saved = O_local and lse2 of hf_hybrid_attn_fwd_save instead of a recomputed forward pass
+static int bwd_impl(const hf_config* cfg, const void* Q, const void* Q_hist, int32_t n_q, const void* K_win,
+                    const void* V_win, int32_t n_kv, const int32_t* block_idx, int32_t k, const void* state_or_null,
+                    const float* rope_cos_q, const float* rope_sin_q, const void* dO, bool saved, const void* O_local,
+                    const float* lse2_saved, void* dQ, void* dQ_hist, void* dK, void* dV, void* workspace,
+                    size_t workspace_bytes, void* stream);
+
 int hf_hybrid_attn_bwd(const hf_config* cfg, const void* Q, const void* Q_hist, int32_t n_q, const void* K_win,
                        const void* V_win, int32_t n_kv, const int32_t* block_idx, int32_t k,
                        const void* state_or_null, const float* rope_cos_q, const float* rope_sin_q, const void* dO,
                        void* dQ, void* dQ_hist, void* dK, void* dV, void* workspace, size_t workspace_bytes,
                        void* stream) {
+  return bwd_impl(cfg, Q, Q_hist, n_q, K_win, V_win, n_kv, block_idx, k, state_or_null, rope_cos_q, rope_sin_q, dO,
+                  false, nullptr, nullptr, dQ, dQ_hist, dK, dV, workspace, workspace_bytes, stream);
+}
+
+int hf_hybrid_attn_bwd_saved(const hf_config* cfg, const void* Q, const void* Q_hist, int32_t n_q,
+                             const void* K_win, const void* V_win, int32_t n_kv, const int32_t* block_idx,
+                             int32_t k, const void* state_or_null, const float* rope_cos_q,
+                             const float* rope_sin_q, const void* dO, const void* O_local, const float* lse2,
+                             void* dQ, void* dQ_hist, void* dK, void* dV, void* workspace, size_t workspace_bytes,
+                             void* stream) {
+  return bwd_impl(cfg, Q, Q_hist, n_q, K_win, V_win, n_kv, block_idx, k, state_or_null, rope_cos_q, rope_sin_q, dO,
+                  true, O_local, lse2, dQ, dQ_hist, dK, dV, workspace, workspace_bytes, stream);
+}
+
+static int bwd_impl(const hf_config* cfg, const void* Q, const void* Q_hist, int32_t n_q, const void* K_win,
+                    const void* V_win, int32_t n_kv, const int32_t* block_idx, int32_t k, const void* state_or_null,
+                    const float* rope_cos_q, const float* rope_sin_q, const void* dO, bool saved, const void* O_local,
+                    const float* lse2_saved, void* dQ, void* dQ_hist, void* dK, void* dV, void* workspace,
+                    size_t workspace_bytes, void* stream) {
   HF_TRY(check_cfg(cfg));
+  if (saved) {
+    HF_TRY(check_ptr(O_local, "O_local", true));
+    HF_TRY(check_ptr(lse2_saved, "lse2", true));
+    if (!bwd_mfma_supported(*cfg)) {
+      set_error("saved statistics cover bf16, head_dim 128, block_q 64 or 128 (hf_hybrid_attn_bwd recomputes instead)");
+      return HF_ERR_SHAPE;
+    }
+  }
   HF_TRY(check_ptr(Q, "Q", true));
   if (!Q_hist) Q_hist = Q;
   HF_TRY(check_ptr(Q_hist, "Q_hist", true));
@@ -444,7 +522,7 @@ int hf_hybrid_attn_bwd(const hf_config* cfg, const void* Q, const void* Q_hist, 
   if (split && !dQ_hist) { set_error("dQ_hist is required when Q_hist is a tensor of its own"); return HF_ERR_NULL; }
   if (!split && dQ_hist) { set_error("dQ_hist must be NULL when one tensor feeds both branches"); return HF_ERR_SHAPE; }
   HF_TRY(check_ptr(dQ_hist, "dQ_hist", false));
-  const void* ins[] = {Q, Q_hist, K_win, V_win, dO};
+  const void* ins[] = {Q, Q_hist, K_win, V_win, dO, O_local, lse2_saved};
   void* outs[] = {dQ, dK, dV, dQ_hist};
   for (int a = 0; a < 4; ++a) {
     if (!outs[a]) continue;
@@ -481,7 +559,7 @@ int hf_hybrid_attn_bwd(const hf_config* cfg, const void* Q, const void* Q_hist, 
   const float* st = static_cast<const float*>(state_or_null);
 
   const char* pick = getenv("HF_BWD_KERNEL");   // development switch: "g" forces the fp32-arithmetic kernels
-  const bool mfma = bwd_mfma_supported(*cfg) && !(pick && pick[0] == 'g');
+  const bool mfma = bwd_mfma_supported(*cfg) && (saved || !(pick && pick[0] == 'g'));
   if (split && !st) {
     const size_t bytes = (size_t)cfg->batch * cfg->heads * n_q * cfg->head_dim * esize(cfg);
     HF_TRY(launch_fill_zero(static_cast<float*>(dQ_hist), bytes / 4, s));
@@ -490,8 +568,15 @@ int hf_hybrid_attn_bwd(const hf_config* cfg, const void* Q, const void* Q_hist, 
   if (mfma) {
     // row statistics of the softmax and D = dO . O_local (unrounded) from a recomputed forward pass; the history
     // branch rides in the dQ kernel's epilogue
-    HF_TRY(launch_attn_mfma_stats(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, dO, lse2, dvec, s));
-    return launch_bwd_mfma(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, dO, lse2, dvec, inv_cnt, inv_list, st,
+    const float* lse2_in = lse2;
+    if (saved) {
+      // D = dO . O_local from the saved (once rounded) O_local; the row statistic as saved
+      HF_TRY(launch_row_dot(*cfg, dO, O_local, (long long)cfg->batch * cfg->heads * n_q, dvec, s));
+      lse2_in = lse2_saved;
+    } else {
+      HF_TRY(launch_attn_mfma_stats(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, dO, lse2, dvec, s));
+    }
+    return launch_bwd_mfma(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, dO, lse2_in, dvec, inv_cnt, inv_list, st,
                            rope_cos_q, rope_sin_q, Q_hist, ws + w.planes, dQ, dQ_hist, dK, dV, s);
   }
   // history branch first: its gradient either is an output of its own or joins dQ before dQ's one rounding

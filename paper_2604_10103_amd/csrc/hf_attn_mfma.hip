@@ -76,6 +76,9 @@ struct HistArgs {
   const bf16_t* d_out;   // [BH][n_q][d] gradient of the output
   float* lse2;           // [BH][n_q] log2 of the softmax denominator in the scaled-logit domain
   float* dvec;           // [BH][n_q] d_out . O_local
+  // by-products of an ordinary forward pass for the backward pass, each optional (kFused != 3):
+  float* lse2_out;       // [BH][n_q] the same row statistic
+  bf16_t* olocal_out;    // [BH][n_q][d] the sparse branch's output alone, rounded once
 };
 
 // kFused: 0 = attention only, 1 = + history term for ReLU without rotation, 2 = + history term, general,
@@ -351,6 +354,38 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[dt][r] *= inv;
 
+  // the accumulators as bf16 rows of a [n_q][d] head: transposed through LDS (whose tiles or planes are dead at
+  // every call), stored as coalesced rows; LDS may be reused after the barrier that follows the last call
+  auto store_rows = [&](bf16_t* dst_head) {
+    char* stage = smem;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        uint2 w;
+        w.x = (uint32_t)f32_to_bf16(o[dt][4 * rq]) | ((uint32_t)f32_to_bf16(o[dt][4 * rq + 1]) << 16);
+        w.y = (uint32_t)f32_to_bf16(o[dt][4 * rq + 2]) | ((uint32_t)f32_to_bf16(o[dt][4 * rq + 3]) << 16);
+        *reinterpret_cast<uint2*>(stage + (32 * wave + l32) * OSTR + (32 * dt + 8 * rq + 4 * h) * 2) = w;
+      }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < (BQ * 16) / NT; ++i) {
+      const int c = tid + NT * i, row = c >> 4, col = c & 15;
+      if (qb * BQ + row < n_q)
+        *reinterpret_cast<uint4*>(dst_head + (size_t)(qb * BQ + row) * D + col * 8) =
+            *reinterpret_cast<const uint4*>(stage + row * OSTR + col * 16);
+    }
+  };
+  if (kFused != 3) {
+    // ---- by-products for a later backward pass (training forward): the row statistic and O_local itself
+    if (hist.lse2_out && h == 0 && q_row < n_q)
+      hist.lse2_out[(size_t)bh * n_q + q_row] = l_tot > 0.0f ? m_ref + __log2f(l_tot) : INFINITY;
+    if (kFused != 0 && hist.olocal_out) {   // (without a history term O is O_local)
+      store_rows(hist.olocal_out + (size_t)bh * n_q * D);
+      __syncthreads();
+    }
+  }
+
   if (kFused == 3) {
     // ---- backward-pass statistics: lse2 = m + log2(l) and D = dO . O_local, O_local still unrounded
     const bf16_t* gp = hist.d_out + ((size_t)bh * n_q + min(q_row, n_q - 1)) * D + 4 * h;
@@ -469,24 +504,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
     __syncthreads();  // the plane's space becomes the output staging area
   }
 
-  char* stage = smem;
-#pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-    for (int rq = 0; rq < 4; ++rq) {
-      uint2 w;
-      w.x = (uint32_t)f32_to_bf16(o[dt][4 * rq]) | ((uint32_t)f32_to_bf16(o[dt][4 * rq + 1]) << 16);
-      w.y = (uint32_t)f32_to_bf16(o[dt][4 * rq + 2]) | ((uint32_t)f32_to_bf16(o[dt][4 * rq + 3]) << 16);
-      *reinterpret_cast<uint2*>(stage + (32 * wave + l32) * OSTR + (32 * dt + 8 * rq + 4 * h) * 2) = w;
-    }
-  __syncthreads();
-#pragma unroll
-  for (int i = 0; i < (BQ * 16) / NT; ++i) {
-    const int c = tid + NT * i, row = c >> 4, col = c & 15;
-    if (qb * BQ + row < n_q)
-      *reinterpret_cast<uint4*>(Oh + (size_t)(qb * BQ + row) * D + col * 8) =
-          *reinterpret_cast<const uint4*>(stage + row * OSTR + col * 16);
-  }
+  store_rows(Oh);
 }
 
 }  // namespace
@@ -513,11 +531,11 @@ static int launch_attn_mfma_impl(const hf_config& c, const void* Q, int n_q, con
   const bf16_t* kk = static_cast<const bf16_t*>(K);
   const bf16_t* v = static_cast<const bf16_t*>(V);
   bf16_t* o = static_cast<bf16_t*>(O);
-  const HistArgs h = hist ? *hist : HistArgs{nullptr, nullptr, 0.0f, 0.0f, 0, 0, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+  const HistArgs h = hist ? *hist : HistArgs{};
 #define HF_LAUNCH_ATTN(NWV, FUSED)                                                                              \
   hipLaunchKernelGGL((attn_mfma_kernel<NWV, FUSED>), grid, dim3(64 * NWV), 0, s, q, kk, v, idx, k, n_q, n_kv,   \
                      kv_stride_of(c, n_kv), c.block_kv, t_m, t_n, per_xcd, (int)total, c_scale, h, o)
-  const int fused = !hist ? 0 : (h.lse2 ? 3 : ((h.phi_kind == HF_PHI_RELU && h.cosq == nullptr && h.q_hist == nullptr) ? 1 : 2));
+  const int fused = !h.planes && !h.lse2 ? 0 : (h.lse2 ? 3 : ((h.phi_kind == HF_PHI_RELU && h.cosq == nullptr && h.q_hist == nullptr) ? 1 : 2));
   if (c.block_q == 64) {
     if (fused == 0) HF_LAUNCH_ATTN(2, 0); else if (fused == 1) HF_LAUNCH_ATTN(2, 1); else if (fused == 2) HF_LAUNCH_ATTN(2, 2); else HF_LAUNCH_ATTN(2, 3);
   } else {
@@ -532,18 +550,28 @@ int launch_attn_mfma(const hf_config& c, const void* Q, int n_q, const void* K, 
   return launch_attn_mfma_impl(c, Q, n_q, K, V, n_kv, idx, k, nullptr, O_local, s);
 }
 
+// the same with the row statistic of the softmax as a by-product (training forward without a history term)
+int launch_attn_mfma_lse(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
+                         const int32_t* idx, int k, void* O_local, float* lse2_out, hipStream_t s) {
+  HistArgs h = {};
+  h.lse2_out = lse2_out;
+  return launch_attn_mfma_impl(c, Q, n_q, K, V, n_kv, idx, k, &h, O_local, s);
+}
+
 // the history term rides in the attention epilogue (any feature map, with or without rotation)
 bool attn_mfma_fused_supported(const hf_config& c) { return attn_mfma_supported(c); }
 
 int launch_attn_mfma_fused(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
                            const int32_t* idx, int k, const void* planes, const float* zvec, const float* cosq,
-                           const float* sinq, const void* Q_hist, void* O, hipStream_t s) {
+                           const float* sinq, const void* Q_hist, void* O, hipStream_t s, float* lse2_out,
+                           void* olocal_out) {
   // One bf16 plane of L (2^-9 per element, errors of the d terms of a readout average out) costs the
   // output nothing measurable next to the bf16 rounding of P and O; HF_FUSED_PLANES=2 in the
   // environment adds the low plane (development switch).
   const char* np = getenv("HF_FUSED_PLANES");
   const HistArgs h = {static_cast<const bf16_t*>(planes), zvec, c.eps, c.z_scale, (np && np[0] == '2') ? 2 : 1,
-                      c.phi, cosq, sinq, Q_hist == Q ? nullptr : static_cast<const bf16_t*>(Q_hist), nullptr, nullptr, nullptr};
+                      c.phi, cosq, sinq, Q_hist == Q ? nullptr : static_cast<const bf16_t*>(Q_hist), nullptr, nullptr, nullptr,
+                      lse2_out, static_cast<bf16_t*>(olocal_out)};
   return launch_attn_mfma_impl(c, Q, n_q, K, V, n_kv, idx, k, &h, O, s);
 }
 
@@ -551,7 +579,7 @@ int launch_attn_mfma_fused(const hf_config& c, const void* Q, int n_q, const voi
 int launch_attn_mfma_stats(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
                            const int32_t* idx, int k, const void* dO, float* lse2, float* dvec, hipStream_t s) {
   const HistArgs h = {nullptr, nullptr, 0.0f, 0.0f, 0, 0, nullptr, nullptr, nullptr, static_cast<const bf16_t*>(dO),
-                      lse2, dvec};
+                      lse2, dvec, nullptr, nullptr};
   return launch_attn_mfma_impl(c, Q, n_q, K, V, n_kv, idx, k, &h, nullptr, s);
 }
 

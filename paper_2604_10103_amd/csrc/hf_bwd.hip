@@ -402,4 +402,34 @@ int launch_bwd_hist_generic(const hf_config& c, const void* Q_hist, const void* 
   return check_launch("hf_hybrid_attn_bwd(history)");
 }
 
+// out[row] = A[row] . B[row] over head_dim features (bf16 storage, fp32 arithmetic): D = dO . O_local from a
+// saved O_local.  16 lanes per row, 16 bytes per lane and tensor.
+__global__ __launch_bounds__(256) void row_dot_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
+                                                      long long rows, float* __restrict__ out) {
+  const long long row = (long long)blockIdx.x * 16 + (threadIdx.x >> 4);
+  const int part = threadIdx.x & 15;
+  float acc = 0.0f;
+  if (row < rows) {
+    const uint4 a = *reinterpret_cast<const uint4*>(A + row * 128 + part * 8);
+    const uint4 b = *reinterpret_cast<const uint4*>(B + row * 128 + part * 8);
+    const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      acc = fmaf(__uint_as_float(aw[i] << 16), __uint_as_float(bw[i] << 16), acc);
+      acc = fmaf(__uint_as_float(aw[i] & 0xffff0000u), __uint_as_float(bw[i] & 0xffff0000u), acc);
+    }
+  }
+#pragma unroll
+  for (int off = 8; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 16);
+  if (row < rows && part == 0) out[row] = acc;
+}
+
+int launch_row_dot(const hf_config& c, const void* A, const void* B, long long rows, float* out, hipStream_t s) {
+  if (c.dtype != HF_BF16 || c.head_dim != 128) { set_error("row dot: bf16, head_dim 128 only"); return HF_ERR_SHAPE; }
+  if (rows > (1ll << 34)) { set_error("too many rows"); return HF_ERR_SHAPE; }
+  hipLaunchKernelGGL(row_dot_kernel, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, s,
+                     static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(B), rows, out);
+  return check_launch("hf_hybrid_attn_bwd_saved(D)");
+}
+
 }  // namespace hf

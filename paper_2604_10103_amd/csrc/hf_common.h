@@ -102,13 +102,17 @@ int launch_state_planes(const hf_config& c, const float* state, void* planes, hi
 bool attn_mfma_fused_supported(const hf_config& c);
 int launch_attn_mfma_fused(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
                            const int32_t* idx, int k, const void* planes, const float* zvec, const float* cosq,
-                           const float* sinq, const void* Q_hist, void* O, hipStream_t s);
+                           const float* sinq, const void* Q_hist, void* O, hipStream_t s, float* lse2_out = nullptr,
+                           void* olocal_out = nullptr);   // by-products for hf_hybrid_attn_bwd_saved, each optional
+int launch_attn_mfma_lse(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
+                         const int32_t* idx, int k, void* O_local, float* lse2_out, hipStream_t s);
 // backward pass (training algorithm): lse2 = per-row log2 of the softmax denominator in the scaled-logit domain
 int launch_attn_generic(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
                         const int32_t* idx, int k, void* O_local, hipStream_t s, float* lse2, const void* dO,
                         float* Dv);  // lse2 given: writes lse2 and Dv = dO . O_local instead of O_local
 int launch_attn_mfma_stats(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
                            const int32_t* idx, int k, const void* dO, float* lse2, float* dvec, hipStream_t s);
+int launch_row_dot(const hf_config& c, const void* A, const void* B, long long rows, float* out, hipStream_t s);
 bool bwd_mfma_supported(const hf_config& c);
 size_t bwd_planes_bytes(const hf_config& c);
 int launch_bwd_mfma(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,

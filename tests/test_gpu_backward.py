@@ -277,3 +277,97 @@ def test_backward_seeded_random_shapes(seed):
             check("dQ", wl.to_f64(dQ)[b_, h_], rql + rqh, W)
         check("dK", wl.to_f64(dK)[b_, h_], rk, W)
         check("dV", wl.to_f64(dV)[b_, h_], rv, W)
+
+
+def run_fwd_save(cfg, Q, K, V, idx, st, tables=None, Q_hist=None):
+    n_q, n_kv = Q.shape[2], K.shape[2]
+    O = torch.full(Q.shape, float("nan"), dtype=Q.dtype, device=DEV)
+    Ol = torch.full(Q.shape, float("nan"), dtype=Q.dtype, device=DEV)
+    lse = torch.full((cfg.batch * cfg.heads, n_q), float("nan"), dtype=torch.float32, device=DEV)
+    ws = torch.empty(hf.hf_workspace_bytes(cfg, n_q, n_kv), dtype=torch.uint8, device=DEV)
+    cos, sin = (None, None) if tables is None else (tables[0].to(DEV), tables[1].to(DEV))
+    hf.hf_hybrid_attn_fwd_save(cfg, Q.to(DEV), K.to(DEV), V.to(DEV), idx, st, O, Ol, lse, ws, cos, sin,
+                               None if Q_hist is None else Q_hist.to(DEV))
+    torch.cuda.synchronize()
+    return O, Ol, lse
+
+
+def oracle_lse2(q, kk, idx_rows, block, scale):
+    """log2 of the softmax denominator of every query row over the keys of its selected blocks (Eq. 5), written out."""
+    out = np.empty(q.shape[0])
+    for i in range(q.shape[0]):
+        keys = np.concatenate([np.arange(j * block, min((j + 1) * block, kk.shape[0])) for j in idx_rows[i // block]])
+        s = (kk[keys] @ q[i]) * scale * np.log2(np.e)
+        out[i] = s.max() + np.log2(np.exp2(s - s.max()).sum())
+    return out
+
+
+@pytest.mark.parametrize("name,phi,rope,split,with_state", [("small_bf16", hf.HF_PHI_RELU, False, False, True),
+                                                            ("small_bf16", hf.HF_PHI_ELU1, True, True, True),
+                                                            ("small_b128", hf.HF_PHI_RELU, False, False, True),
+                                                            ("small_bf16", hf.HF_PHI_RELU, False, False, False)])
+def test_saving_forward_and_backward_from_saved_statistics(name, phi, rope, split, with_state):
+    """The training forward writes the same O as the plain forward plus O_local and the row statistic; the backward
+    pass fed with them meets the oracle to the same bounds as the recomputing one."""
+    w = wl.get(name)
+    cfg = cfg_of(w, phi=phi)
+    st, ref_states = make_state(cfg, w, phi, rope) if with_state else (None, [orc.state_zero(w.head_dim)] * w.heads)
+    Q, K, V = wl.make_qkv(w, q_gain=2.0)
+    Qh = wl.randn(Q.shape, 94_000 + w.cfg, w.scale, w.torch_dtype) if split else None
+    dO = wl.randn(Q.shape, 95_000 + w.cfg, 1.0, w.torch_dtype)
+    qtab = wl.rope_tables(w.n_q, w.head_dim, first_position=float(w.evicted_frames + 2),
+                          tokens_per_position=w.tokens_per_frame) if rope else None
+    idx, k = select(cfg, w, Q, K)
+    idxc = idx.cpu().numpy()
+    O, Ol, lse = run_fwd_save(cfg, Q, K, V, idx, st, qtab, Qh)
+    # the plain forward gives the same O, bit for bit
+    O2 = torch.empty_like(O)
+    ws = torch.empty(hf.hf_workspace_bytes(cfg, w.n_q, w.n_kv), dtype=torch.uint8, device=DEV)
+    cos, sin = (None, None) if qtab is None else (qtab[0].to(DEV), qtab[1].to(DEV))
+    hf.hf_hybrid_attn_fwd(cfg, Q.to(DEV), K.to(DEV), V.to(DEV), idx, st, O2, ws, cos, sin, None if Qh is None else Qh.to(DEV))
+    torch.cuda.synchronize()
+    assert torch.equal(O, O2)
+    scale = 1.0 / np.sqrt(w.head_dim)
+    lse_c = lse.cpu().numpy().astype(np.float64)
+    for h, (q, kk, v) in enumerate(zip(heads_of(Q), heads_of(K), heads_of(V))):
+        ref_l = orc.sparse_attention(q, kk, v, idxc[0, h], w.block, w.block)
+        check("O_local", wl.to_f64(Ol)[0, h], ref_l, w)
+        assert np.abs(lse_c[h] - oracle_lse2(q, kk, idxc[0, h], w.block, scale)).max() <= 2e-5 * max(1.0, np.abs(lse_c[h]).max())
+    if not with_state:
+        assert torch.equal(O, Ol)
+    # backward from the saved by-products
+    dQ = torch.full(Q.shape, float("nan"), dtype=Q.dtype, device=DEV)
+    dK, dV = torch.full(K.shape, float("nan"), dtype=K.dtype, device=DEV), torch.full(K.shape, float("nan"), dtype=K.dtype, device=DEV)
+    dQh = torch.full(Q.shape, float("nan"), dtype=Q.dtype, device=DEV) if split else None
+    bws = torch.empty(hf.hf_bwd_workspace_bytes(cfg, w.n_q, w.n_kv), dtype=torch.uint8, device=DEV)
+    hf.hf_hybrid_attn_bwd_saved(cfg, Q.to(DEV), K.to(DEV), V.to(DEV), idx, st, dO.to(DEV), Ol, lse, dQ, dK, dV, bws, cos, sin,
+                                None if Qh is None else Qh.to(DEV), dQh)
+    torch.cuda.synchronize()
+    cq = None if qtab is None else wl.to_f64(qtab[0])
+    sq = None if qtab is None else wl.to_f64(qtab[1])
+    for h, (q, kk, v, g) in enumerate(zip(heads_of(Q), heads_of(K), heads_of(V), heads_of(dO))):
+        qh = None if Qh is None else heads_of(Qh)[h]
+        rql, rqh, rk, rv = orc.hybrid_attention_bwd(q, kk, v, ref_states[h], w.block, w.block, idxc[0, h], g, phi,
+                                                    cq, sq, cfg.eps, cfg.z_scale, Q_hist=qh)
+        if split:
+            check("dQ", wl.to_f64(dQ)[0, h], rql, w)
+            check("dQ_hist", wl.to_f64(dQh)[0, h], rqh, w)
+        else:
+            check("dQ", wl.to_f64(dQ)[0, h], rql + (rqh if with_state else 0.0), w)
+        check("dK", wl.to_f64(dK)[0, h], rk, w)
+        check("dV", wl.to_f64(dV)[0, h], rv, w)
+
+
+def test_saving_entry_points_refuse_what_they_do_not_cover():
+    w = wl.get("tiny_f32")
+    cfg = cfg_of(w)
+    Q, K, V = wl.make_qkv(w)
+    idx, k = select(cfg, w, Q, K)
+    O, Ol = torch.empty_like(Q, device=DEV), torch.empty_like(Q, device=DEV)
+    lse = torch.empty((w.batch * w.heads, w.n_q), dtype=torch.float32, device=DEV)
+    with pytest.raises(hf.HFError, match="bf16"):
+        hf.hf_hybrid_attn_fwd_save(cfg, Q.to(DEV), K.to(DEV), V.to(DEV), idx, None, O, Ol, lse)
+    dQ, dK, dV = torch.empty_like(O), torch.empty_like(K, device=DEV), torch.empty_like(K, device=DEV)
+    bws = torch.empty(hf.hf_bwd_workspace_bytes(cfg, w.n_q, w.n_kv), dtype=torch.uint8, device=DEV)
+    with pytest.raises(hf.HFError, match="bf16"):
+        hf.hf_hybrid_attn_bwd_saved(cfg, Q.to(DEV), K.to(DEV), V.to(DEV), idx, None, O, Ol, lse, dQ, dK, dV, bws)

@@ -253,13 +253,20 @@ def test_backward_at_full_size_sampled_heads(name, heads):
     dQ, dK, dV = torch.empty_like(Qd), torch.empty_like(Kd), torch.empty_like(Vd)
     ws = torch.empty(hf.hf_bwd_workspace_bytes(cfg, w.n_q, w.n_kv), dtype=torch.uint8, device=DEV)
     hf.hf_hybrid_attn_bwd(cfg, Qd, Kd, Vd, L.idx, L.state, dO.to(DEV), dQ, dK, dV, ws)
+    # the same from the by-products of the saving forward (no recomputed forward pass)
+    O, Ol = torch.empty_like(Qd), torch.empty_like(Qd)
+    lse = torch.empty((w.batch * w.heads, w.n_q), dtype=torch.float32, device=DEV)
+    hf.hf_hybrid_attn_fwd_save(cfg, Qd, Kd, Vd, L.idx, L.state, O, Ol, lse, L.ws)
+    dQ2, dK2, dV2 = torch.empty_like(Qd), torch.empty_like(Kd), torch.empty_like(Vd)
+    hf.hf_hybrid_attn_bwd_saved(cfg, Qd, Kd, Vd, L.idx, L.state, dO.to(DEV), Ol, lse, dQ2, dK2, dV2, ws)
     torch.cuda.synchronize()
     idxc = L.idx.cpu().numpy()
     for h in heads:
         st = orc.state_absorb(*orc.state_zero(w.head_dim), wl.to_f64(Ke[0, h]), wl.to_f64(Ve[0, h]))
         rql, rqh, rk, rv = orc.hybrid_attention_bwd(wl.to_f64(Q[0, h]), wl.to_f64(K[0, h]), wl.to_f64(V[0, h]), st,
                                                     w.block, w.block, idxc[0, h], wl.to_f64(dO[0, h]), eps=cfg.eps)
-        for nm, got, ref in (("dQ", dQ, rql + rqh), ("dK", dK, rk), ("dV", dV, rv)):
+        for nm, got, ref in (("dQ", dQ, rql + rqh), ("dK", dK, rk), ("dV", dV, rv),
+                             ("dQ saved", dQ2, rql + rqh), ("dK saved", dK2, rk), ("dV saved", dV2, rv)):
             g = wl.to_f64(got[0, h])
             assert rel_l2(g, ref) <= BF16_REL_L2, (nm, h, rel_l2(g, ref))
             assert max_abs(g, ref) <= BF16_MAX_ABS * max(np.abs(ref).max(), 1e-30)
