@@ -7,16 +7,18 @@
 //      S^T  = K Q^T          dP^T = V dO^T            lane = query row, registers = keys
 //      dS^T = 2^(c S^T - lse2) * (dP^T - D)           -> bf16, B operand
 //      dQ^T += K^T dS^T                               A operand = K transposed in LDS
-//  dK, dV  (one workgroup per 64 keys of a KV block, a wavefront per 32 keys x 64 features, tiles of 32
-//      query rows taken from the inverse index lists)
-//      S  = Q K^T            dP = dO V^T              lane = key, registers = query rows
-//      P  = 2^(c S - lse2),  dS = P * (dP - D)        -> bf16, B operands
+//  dK, dV  (one workgroup per 64 keys of a KV block, a wavefront per 32 keys x 128 features, one wavefront per
+//      SIMD with the 128 accumulators in the accumulation half of the register file, tiles of 32 query rows
+//      taken from the inverse index lists)
+//      S  = Q K^T            D - dP = D + dO (-V)^T   lane = key, registers = query rows
+//      P  = 2^(c S - lse2),  dS = (-P) (D - dP)       -> bf16, B operands
 //      dV^T += dO^T P        dK^T += Q^T dS           A operands = dO, Q transposed in LDS
 //
 // A tile of 32 tokens x 128 features goes global -> LDS directly (buffer loads with the LDS bit; rows past the
 // end of the head arrive as zeros), row-major with swizzled 16-byte units, and serves both kinds of A operand:
 // tokens as rows by 16-byte reads, features as rows by gfx950's transposing reads (ds_read_b64_tr_b16).
-// No staging registers, no LDS stores, no transposing permutes; two slots per tensor, one barrier per tile.
+// No staging registers, no LDS stores, no transposing permutes; one barrier per tile; two slots per tensor in
+// the dQ kernel (a tile requested one tile ahead), four in the dK/dV kernel (three ahead).
 #include <math.h>
 
 #include "hf_common.h"
@@ -424,10 +426,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 }
 
 // ------------------------------------------------------------------------------------------ dK, dV
-// One workgroup per slab of 64 keys of a KV block, two wavefronts of 32 keys each; a wavefront owns all 128
-// features of dK and dV of its keys: 128 accumulator registers that only MFMAs touch until the end, which is what
-// the second half of the register file (one wavefront per SIMD: 512 registers) is for.  Per tile of 32 query rows
-// a wavefront issues 16 MFMAs for S and dP and 16 for dV and dK, nothing is computed twice.
 // acc += A B with the accumulator pinned to the accumulation half of the register file (the compiler, left to
 // itself, keeps such accumulators in ordinary registers and shuttles others through that half).  The compiler
 // counts no wait states for inline assembly, so they are provided here: A comes from LDS reads, which it awaits as
@@ -440,6 +438,10 @@ __device__ __forceinline__ void mfma_acc(f32x16& acc, const bf16x8 a, const bf16
   else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
 
+// One workgroup per slab of 64 keys of a KV block, two wavefronts of 32 keys each; a wavefront owns all 128
+// features of dK and dV of its keys: 128 accumulator registers that only MFMAs touch until the end, which is what
+// the second half of the register file (one wavefront per SIMD: 512 registers) is for.  Per tile of 32 query rows
+// a wavefront issues 16 MFMAs for S and dP and 16 for dV and dK, nothing is computed twice.
 constexpr int kDkvSlots = 4;   // tiles in LDS: one in use, three on their way
 constexpr int kDkvLds = kDkvSlots * (2 * RTILE + 512);
 __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) void bwd_dkv_mfma_kernel(
@@ -628,7 +630,10 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   }
   // nothing may land in LDS once the tiles' space is reused; and the last accumulating MFMAs (inline assembly: the
   // compiler does not count wait states for them) must have written their results before these are read
-  asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+  // (the idle slots name the accumulators as operands, or the compiler moves the reads above them)
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  asm volatile("s_nop 15\n\ts_nop 15" : "+a"(dk[0]), "+a"(dk[1]), "+a"(dk[2]), "+a"(dk[3]), "+a"(dv[0]), "+a"(dv[1]),
+               "+a"(dv[2]), "+a"(dv[3]));
 
   // transpose through LDS and store the rows of real keys, dK first, then dV
   for (int which = 0; which < 2; ++which) {
