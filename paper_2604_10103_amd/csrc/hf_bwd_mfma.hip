@@ -72,16 +72,22 @@ struct TileDma {
   // tile that starts past it) arrive as zeros (a load past the descriptor's end stores zero in LDS).  Completion
   // is counted by vmcnt.
   __device__ __forceinline__ void fetch(const i32x4& desc, uint32_t lds, int first_v) const {
+    const i32x4 d2 = moved(desc, first_v);
+#pragma unroll
+    for (int j = 0; j < CPT; ++j) piece(d2, lds, j);
+  }
+  // the same in two steps, for a caller that spreads the pieces between other instructions: the descriptor moved
+  // to the tile's first row, then piece j of this wavefront
+  __device__ __forceinline__ i32x4 moved(const i32x4& desc, int first_v) const {
     const int first = __builtin_amdgcn_readfirstlane(first_v);
     const int skip = first * (D * 2), left = desc.z - skip;
     const uint64_t base = (((uint64_t)(uint32_t)desc.y << 32) | (uint32_t)desc.x) + (uint64_t)(uint32_t)(left > 0 ? skip : 0);
-    const i32x4 d2 = {(int)(uint32_t)base, (int)(uint32_t)(base >> 32), left > 0 ? left : 0, desc.w};
-#pragma unroll
-    for (int j = 0; j < CPT; ++j) {
-      const uint32_t dst = lds + 4 * (wave + NWAVES * j) * RSTR;
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                   :: "s"(dst), "v"(lane_off[j]), "s"(d2) : "memory", "m0");
-    }
+    return i32x4{(int)(uint32_t)base, (int)(uint32_t)(base >> 32), left > 0 ? left : 0, desc.w};
+  }
+  __device__ __forceinline__ void piece(const i32x4& d2, uint32_t lds, int j) const {
+    const uint32_t dst = lds + 4 * (wave + NWAVES * j) * RSTR;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(dst), "v"(lane_off[j]), "s"(d2) : "memory", "m0");
   }
 };
 
@@ -531,15 +537,21 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const __amdgpu_buffer_rsrc_t lse_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(lseh), 0, n_q * 4, 0x00020000);
   const __amdgpu_buffer_rsrc_t dv_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(Dvh), 0, n_q * 4, 0x00020000);
   const uint32_t sStat_lds = (uint32_t)(uintptr_t)sStat;
+  auto stat_fetch = [&](const int slot_, const int r0, const int which) {   // which: 0 = lse2, 1 = D
+    const int off = 4 * (r0 + l32);   // a row past n_q is past the descriptor's end: zero
+    if (which == 0)
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
+                   :: "s"(sStat_lds + slot_ * 512), "v"(off), "s"(lse_rsrc) : "memory", "m0");
+    else
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
+                   :: "s"(sStat_lds + slot_ * 512 + 256), "v"(off), "s"(dv_rsrc) : "memory", "m0");
+  };
   auto fetch_tile = [&](const int slot_, const int r0_v) {
     const int r0 = __builtin_amdgcn_readfirstlane(r0_v);
     dma.fetch(q_desc, sQ_lds + slot_ * RTILE, r0);
     dma.fetch(do_desc, sdO_lds + slot_ * RTILE, r0);
-    const int off = 4 * (r0 + l32);   // a row past n_q is past the descriptor's end: zero
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
-                 :: "s"(sStat_lds + slot_ * 512), "v"(off), "s"(lse_rsrc) : "memory", "m0");
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
-                 :: "s"(sStat_lds + slot_ * 512 + 256), "v"(off), "s"(dv_rsrc) : "memory", "m0");
+    stat_fetch(slot_, r0, 0);
+    stat_fetch(slot_, r0, 1);
   };
   constexpr int kPerTile = 2 * TileDma<2>::CPT + 2;   // transfers a wavefront issues per tile
   int e0 = entry_issue(0), e1 = entry_issue(1), e2 = entry_issue(2), e_next = entry_issue(3);
@@ -552,12 +564,10 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   fetch_tile(1, row0_b);
   fetch_tile(2, row0_c);
   auto tile_step = [&](const int n, const int par) {   // par = n mod 4, a literal at the call sites
-    const int row0 = row0_a;
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * kPerTile) : "memory");   // this wavefront's parts of tile n
     __syncthreads();                                   // tile n complete, tile n - 1 consumed by both
     entry_wait(e_next);
     const int row0_d = tile_row0(n + 3, e_next);
-    fetch_tile((par + 3) % NSLOT, row0_d);
     e_next = entry_issue(n + 4);
     row0_a = row0_b;
     row0_b = row0_c;
@@ -565,6 +575,9 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const char* tQ = sQ + par * RTILE;
     const char* tdO = sdO + par * RTILE;
     const float* tS = sStat + 128 * par;
+    // All fragments of a phase are requested before its first MFMA (there are registers for it: one wavefront per
+    // SIMD).  While the first ones travel, and then between the MFMAs (each keeps the matrix pipe busy for some
+    // thirty cycles in which this wavefront may issue other instructions), tile n + 3 is requested piece by piece.
     f32x16 sacc, dpacc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) sacc[r] = 0.0f;
@@ -576,8 +589,6 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       lsr[4 * g] = l4.x; lsr[4 * g + 1] = l4.y; lsr[4 * g + 2] = l4.z; lsr[4 * g + 3] = l4.w;
       dpacc[4 * g] = d4.x; dpacc[4 * g + 1] = d4.y; dpacc[4 * g + 2] = d4.z; dpacc[4 * g + 3] = d4.w;
     }
-    // all fragments of a phase are requested before its first MFMA (there are registers for it: one wavefront per
-    // SIMD), the transposed ones of the second phase before the vector work between the phases
     bf16x8 qa[8], ga[8];
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
@@ -585,10 +596,21 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       ga[s] = rows_frag(tdO, rb, s);
     }
     __builtin_amdgcn_sched_barrier(0);   // (the scheduler would move each read next to its MFMA)
+    const int slot_ = (par + 3) % NSLOT;
+    const int r0 = __builtin_amdgcn_readfirstlane(row0_d);
+    const i32x4 dq_ = dma.moved(q_desc, r0), dg_ = dma.moved(do_desc, r0);
+    static_assert(TileDma<2>::CPT == 4, "the spreading below assumes four pieces per tensor");
+    dma.piece(dq_, sQ_lds + slot_ * RTILE, 0);
+    dma.piece(dq_, sQ_lds + slot_ * RTILE, 1);
+    dma.piece(dq_, sQ_lds + slot_ * RTILE, 2);
+    dma.piece(dq_, sQ_lds + slot_ * RTILE, 3);
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
       sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[s], kf[s], sacc, 0, 0, 0);
       dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga[s], vf[s], dpacc, 0, 0, 0);
+      if (s < 4) dma.piece(dg_, sdO_lds + slot_ * RTILE, s);
+      if (s == 4) stat_fetch(slot_, r0, 0);
+      if (s == 5) stat_fetch(slot_, r0, 1);
     }
     bf16x8 qt[2][4], gt[2][4];
 #pragma unroll
