@@ -234,8 +234,8 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
   // One tile (kslot = t mod 3, par = t mod 2, literals at every call site).  The scores of tile t are formed from
   // fragments already in registers; the one barrier of the iteration follows them.  Behind it every wavefront is
   // done with K slot kslot (fragments of tile t were read during tile t-1) and with V half par^1 (tile t-1), so V
-  // of tile t+1 and K of tile t+3 are requested into them; K of tile t+1 and V of tile t have landed (awaited
-  // before the barrier) and their fragments are read while the softmax runs.
+  // of tile t+1 (at once) and K of tile t+3 (between the P.V products) are requested into them; K of tile t+1 and
+  // V of tile t have landed (awaited before the barrier) and their fragments are read while the softmax runs.
   auto tile_step = [&](const int kslot, const int par) {
     const int valid_cur = va;
     // ---- S^T = K Q^T : 32 keys, 8 steps over d
@@ -250,7 +250,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
     __syncthreads();
 
     dma_tile(v_desc, sV_lds + (par ^ 1) * KTILE, start_a, v_lane_off);     // V of tile t+1
-    dma_tile(k_desc, sK_lds + kslot * KTILE, start_c, k_lane_off);         // K of tile t+3 into the slot of tile t
+    const int start_k = start_c;   // K of tile t+3 is requested further down
     start_a = start_b;
     start_b = start_c;
     int vnew;
@@ -319,6 +319,10 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
     // ---- O^T += V^T P^T : 2 steps of 16 keys, 4 tiles of 32 features
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[dt], pf[0], o[dt], 0, 0, 0);
+    // K of tile t+3 into the slot of tile t, here rather than with V behind the barrier: eight transfers in a row
+    // from every wavefront of the CU at once queue up at the memory pipeline, and a wavefront that cannot issue
+    // its transfer cannot issue anything else (1.2 % of the kernel's time)
+    dma_tile(k_desc, sK_lds + kslot * KTILE, start_k, k_lane_off);
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt) o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vg[dt], pf[1], o[dt], 0, 0, 0);
     va = vb;
