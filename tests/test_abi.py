@@ -212,3 +212,30 @@ def test_backward_call_rejects_bad_arguments(lib):
     assert lib.hf_bwd_workspace_bytes(c, 100, 200, ctypes.byref(n)) == 0
     # two row statistics per query row, the fp32 history gradient, the inverse index lists (counts + T_n x T_m entries)
     assert n.value >= 2 * 2 * 100 * 4 + 2 * 100 * 128 * 4 + 2 * 4 * 4 + 2 * 4 * 2 * 4
+
+
+def test_saving_forward_and_saved_backward_reject_bad_arguments(lib):
+    cfg = hf.make_config(1, 2, 128, "bf16", 64, 64, 0.25)
+    c = ctypes.byref(cfg)
+    a = [4096 * i for i in range(1, 14)]          # distinct aligned fake addresses; nothing is launched on an error
+    Q, K, V, dO, dQ, dK, dV, O, Ol, lse, ws = a[:11]
+    ok_tail = (ws << 8, 1 << 40, None)
+    # both by-products are required and must be buffers of their own
+    assert lib.hf_hybrid_attn_fwd_save(c, Q, None, 100, K, V, 200, None, 0, None, None, None, O, None, lse, *ok_tail) == -1
+    assert lib.hf_hybrid_attn_fwd_save(c, Q, None, 100, K, V, 200, None, 0, None, None, None, O, Ol, None, *ok_tail) == -1
+    assert lib.hf_hybrid_attn_fwd_save(c, Q, None, 100, K, V, 200, None, 0, None, None, None, O, O, lse, *ok_tail) == -2
+    assert lib.hf_hybrid_attn_fwd_save(c, Q, None, 100, K, V, 200, None, 0, None, None, None, O, Ol, Ol, *ok_tail) == -2
+    assert lib.hf_hybrid_attn_bwd_saved(c, Q, None, 100, K, V, 200, None, 0, None, None, None, dO, None, lse, dQ, None, dK,
+                                        dV, *ok_tail) == -1
+    assert lib.hf_hybrid_attn_bwd_saved(c, Q, None, 100, K, V, 200, None, 0, None, None, None, dO, Ol, None, dQ, None, dK,
+                                        dV, *ok_tail) == -1
+    assert lib.hf_hybrid_attn_bwd_saved(c, Q, None, 100, K, V, 200, None, 0, None, None, None, dO, Ol, lse, Ol, None, dK,
+                                        dV, *ok_tail) == -2          # an output over a saved input
+    # configurations outside the matrix-core path have no saving pair
+    for other in (hf.make_config(1, 2, 128, "f32", 64, 64, 0.25), hf.make_config(1, 2, 64, "bf16", 64, 64, 0.25),
+                  hf.make_config(1, 2, 128, "bf16", 32, 64, 0.25)):
+        co = ctypes.byref(other)
+        assert lib.hf_hybrid_attn_fwd_save(co, Q, None, 100, K, V, 200, None, 0, None, None, None, O, Ol, lse, *ok_tail) == -2
+        assert lib.hf_hybrid_attn_bwd_saved(co, Q, None, 100, K, V, 200, None, 0, None, None, None, dO, Ol, lse, dQ, None,
+                                            dK, dV, *ok_tail) == -2
+        assert b"hf_hybrid_attn_bwd" in lib.hf_last_error() or b"recomput" in lib.hf_last_error()
