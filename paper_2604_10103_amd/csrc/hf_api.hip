@@ -101,7 +101,7 @@ static WorkspaceLayout workspace_layout(const hf_config* c, int n_q, int n_kv) {
 }
 
 struct BwdLayout {
-  size_t lse2, dvec, dqh32, inv_cnt, inv_list, planes, total;  // byte offsets
+  size_t lse2, dvec, dqh32, inv_cnt, inv_list, order, planes, total;  // byte offsets
 };
 
 static BwdLayout bwd_layout(const hf_config* c, int n_q, int n_kv) {
@@ -113,7 +113,8 @@ static BwdLayout bwd_layout(const hf_config* c, int n_q, int n_kv) {
   w.dqh32 = w.dvec + align256(bh * n_q * 4);
   w.inv_cnt = w.dqh32 + align256(bh * (size_t)n_q * d * 4);
   w.inv_list = w.inv_cnt + align256(bh * t_n * 4);
-  w.planes = w.inv_list + align256(bh * t_n * t_m * 4);
+  w.order = w.inv_list + align256(bh * t_n * t_m * 4);   // launch order of the dK/dV workgroups (64 keys each)
+  w.planes = w.order + align256(bh * t_n * cdiv(c->block_kv, 64) * 4);
   w.total = w.planes + align256(bwd_planes_bytes(*c));
   return w;
 }
@@ -576,8 +577,9 @@ static int bwd_impl(const hf_config* cfg, const void* Q, const void* Q_hist, int
     } else {
       HF_TRY(launch_attn_mfma_stats(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, dO, lse2, dvec, s));
     }
-    return launch_bwd_mfma(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, dO, lse2_in, dvec, inv_cnt, inv_list, st,
-                           rope_cos_q, rope_sin_q, Q_hist, ws + w.planes, dQ, dQ_hist, dK, dV, s);
+    return launch_bwd_mfma(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, dO, lse2_in, dvec, inv_cnt, inv_list,
+                           reinterpret_cast<int32_t*>(ws + w.order), st, rope_cos_q, rope_sin_q, Q_hist, ws + w.planes,
+                           dQ, dQ_hist, dK, dV, s);
   }
   // history branch first: its gradient either is an output of its own or joins dQ before dQ's one rounding
   const float* add_to_dq = nullptr;

@@ -38,6 +38,7 @@ constexpr int RTILE = TT * RSTR;
 constexpr int OSTR = 272;    // bytes per token row of a staged output
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
@@ -83,6 +84,14 @@ struct TileDma {
     const int skip = first * (D * 2), left = desc.z - skip;
     const uint64_t base = (((uint64_t)(uint32_t)desc.y << 32) | (uint32_t)desc.x) + (uint64_t)(uint32_t)(left > 0 ? skip : 0);
     return i32x4{(int)(uint32_t)base, (int)(uint32_t)(base >> 32), left > 0 ? left : 0, desc.w};
+  }
+  // the same without moving the descriptor: voff = lane_off[j] + 256 first (rows past the end lie past the
+  // descriptor's range either way)
+  __device__ __forceinline__ int offset_of(int j, int first_bytes) const { return lane_off[j] + first_bytes; }
+  __device__ __forceinline__ uint32_t place_of(uint32_t lds, int j) const { return lds + 4 * (wave + NWAVES * j) * RSTR; }
+  __device__ __forceinline__ void piece_at(const i32x4& desc, uint32_t lds, int j, int voff) const {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(place_of(lds, j)), "v"(voff), "s"(desc) : "memory", "m0");
   }
   __device__ __forceinline__ void piece(const i32x4& d2, uint32_t lds, int j) const {
     const uint32_t dst = lds + 4 * (wave + NWAVES * j) * RSTR;
@@ -444,6 +453,47 @@ __device__ __forceinline__ void mfma_acc(f32x16& acc, const bf16x8 a, const bf16
   else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
 
+// Launch order of the dK/dV workgroups.  A workgroup's time is proportional to the length of its KV block's list
+// of query blocks, and the lists differ (top-k selection: a binomial spread around t_m k / t_n), while a GPU takes
+// workgroups in index order as slots free up.  Longest first within every XCD's share of the items leaves the short
+// ones to fill the end: order[first item of the share + rank] = item, rank by (list length descending, item
+// ascending), found by counting.  One workgroup per share; the share's keys sit in LDS.
+constexpr int kOrderMax = 8192;   // items per share this kernel takes (32 KB of LDS)
+__global__ __launch_bounds__(1024) void dkv_order_kernel(const int32_t* __restrict__ inv_cnt, int slabs,
+                                                          int items_per_xcd, int total_items,
+                                                          int32_t* __restrict__ order) {
+  __shared__ int32_t key[kOrderMax];
+  const int first = blockIdx.x * items_per_xcd;
+  const int n = max(0, min(items_per_xcd, total_items - first));
+  for (int j = threadIdx.x; j < n; j += 1024) key[j] = inv_cnt[(first + j) / slabs];
+  __syncthreads();
+  // a wavefront per item: its lanes share the comparisons, a ballot counts them
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  for (int j = wave; j < n; j += 16) {
+    const int mine = key[j];
+    int rank = 0;
+    for (int i0 = 0; i0 < n; i0 += 64) {
+      const int i = i0 + lane;
+      const int other = i < n ? key[i] : -1;   // (a list length is never negative)
+      rank += __builtin_popcountll(__ballot(other > mine || (other == mine && i < j)));
+    }
+    if (lane == 0) order[first + rank] = first + j;
+  }
+}
+
+// The same with a 1 KB transfer global -> LDS behind it (LDS address through m0, written in front of the MFMA).
+__device__ __forceinline__ void mfma_acc_piece(f32x16& acc, const bf16x8 a, const bf16x8 b, const bool wait,
+                                               const uint32_t lds, const int voff, const i32x4& desc) {
+  if (wait)
+    asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\t"
+                 "buffer_load_dwordx4 %4, %5, 0 offen lds"
+                 : "+a"(acc) : "v"(a), "v"(b), "s"(lds), "v"(voff), "s"(desc) : "memory", "m0");
+  else
+    asm volatile("s_mov_b32 m0, %3\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\t"
+                 "buffer_load_dwordx4 %4, %5, 0 offen lds"
+                 : "+a"(acc) : "v"(a), "v"(b), "s"(lds), "v"(voff), "s"(desc) : "memory", "m0");
+}
+
 // One workgroup per slab of 64 keys of a KV block, two wavefronts of 32 keys each; a wavefront owns all 128
 // features of dK and dV of its keys: 128 accumulator registers that only MFMAs touch until the end, which is what
 // the second half of the register file (one wavefront per SIMD: 512 registers) is for.  Per tile of 32 query rows
@@ -454,8 +504,8 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const int32_t* __restrict__ inv_cnt, const int32_t* __restrict__ inv_list,
     int n_q, int n_kv, int kv_stride, int bq, int bkv, int t_m, int t_n, int slabs, int items_per_xcd,
-    int total_items, float c_scale, float scale, const float* __restrict__ lse2, const float* __restrict__ Dv,
-    bf16_t* __restrict__ dK, bf16_t* __restrict__ dV) {
+    int total_items, const int32_t* __restrict__ order, float c_scale, float scale,
+    const float* __restrict__ lse2, const float* __restrict__ Dv, bf16_t* __restrict__ dK, bf16_t* __restrict__ dV) {
   constexpr int NT = 128;
   constexpr int NSLOT = kDkvSlots;
   extern __shared__ __attribute__((aligned(16))) char smem[];   // kDkvLds bytes: Q, dO, row statistics per slot
@@ -466,8 +516,9 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
   // XCD-aware placement as in the dQ kernel: an XCD's L2 then holds the queries and output gradients of few heads
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int item = xcd * items_per_xcd + slot;
-  if (slot >= items_per_xcd || item >= total_items) return;
+  const int place = xcd * items_per_xcd + slot;   // the slot-th workgroup of this XCD's share, longest lists first
+  if (slot >= items_per_xcd || place >= total_items) return;
+  const int item = order ? order[place] : place;
   const int bh = item / (t_n * slabs);
   const int rest = item - bh * (t_n * slabs);
   const int jb = rest / slabs, slab = rest - jb * slabs;
@@ -490,18 +541,10 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const int blk_end = min(n_kv, (jb + 1) * bkv);
   const int first_key = jb * bkv + 64 * slab;
   const int key0 = first_key + 32 * kw;
+  // (requested now, used after the first tiles have been requested: the latencies overlap)
   bf16x8 kf[8], vf[8];
   row_frags(k_rsrc, key0 + l32, h, kf);
   row_frags(v_rsrc, key0 + l32, h, vf);
-  __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): from here on only the tile transfers are counted
-  // V enters negated: the dP accumulator starts at D and ends at D - dP, so that dS = (-P) (D - dP) costs one
-  // multiplication per element
-#pragma unroll
-  for (int s = 0; s < 8; ++s) {
-    u32x4 w = __builtin_bit_cast(u32x4, vf[s]);
-    w ^= 0x80008000u;
-    vf[s] = __builtin_bit_cast(bf16x8, w);
-  }
 
   f32x16 dk[4], dv[4];
 #pragma unroll
@@ -523,7 +566,8 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const int t = n >> qshift;
     int e = t;
     if (list) {
-      const int off = __builtin_amdgcn_readfirstlane(4 * min(t, max(n_lists - 1, 0)));
+      // (an entry past the list's end is never used, so the load need not wait for the list's length)
+      const int off = __builtin_amdgcn_readfirstlane(4 * min(t, t_m - 1));
       asm volatile("s_load_dword %0, %1, %2" : "=s"(e) : "s"(list), "s"(off) : "memory");
     }
     return e;
@@ -548,110 +592,182 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   };
   auto fetch_tile = [&](const int slot_, const int r0_v) {
     const int r0 = __builtin_amdgcn_readfirstlane(r0_v);
-    dma.fetch(q_desc, sQ_lds + slot_ * RTILE, r0);
-    dma.fetch(do_desc, sdO_lds + slot_ * RTILE, r0);
+#pragma unroll
+    for (int j = 0; j < TileDma<2>::CPT; ++j) dma.piece_at(q_desc, sQ_lds + slot_ * RTILE, j, dma.offset_of(j, r0 * (D * 2)));
+#pragma unroll
+    for (int j = 0; j < TileDma<2>::CPT; ++j) dma.piece_at(do_desc, sdO_lds + slot_ * RTILE, j, dma.offset_of(j, r0 * (D * 2)));
     stat_fetch(slot_, r0, 0);
     stat_fetch(slot_, r0, 1);
   };
   constexpr int kPerTile = 2 * TileDma<2>::CPT + 2;   // transfers a wavefront issues per tile
-  int e0 = entry_issue(0), e1 = entry_issue(1), e2 = entry_issue(2), e_next = entry_issue(3);
+  int e0 = entry_issue(0), e1 = entry_issue(1), e2 = entry_issue(2), e3 = entry_issue(3), e_next = entry_issue(4);
   entry_wait(e0);
   entry_wait(e1);
   entry_wait(e2);
+  entry_wait(e3);
   entry_wait(e_next);
-  int row0_a = tile_row0(0, e0), row0_b = tile_row0(1, e1), row0_c = tile_row0(2, e2);   // first rows of tiles n .. n + 2
-  fetch_tile(0, row0_a);
-  fetch_tile(1, row0_b);
-  fetch_tile(2, row0_c);
-  auto tile_step = [&](const int n, const int par) {   // par = n mod 4, a literal at the call sites
-    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * kPerTile) : "memory");   // this wavefront's parts of tile n
-    __syncthreads();                                   // tile n complete, tile n - 1 consumed by both
-    entry_wait(e_next);
-    const int row0_d = tile_row0(n + 3, e_next);
-    e_next = entry_issue(n + 4);
-    row0_a = row0_b;
-    row0_b = row0_c;
-    row0_c = row0_d;
+  fetch_tile(0, tile_row0(0, e0));
+  fetch_tile(1, tile_row0(1, e1));
+  fetch_tile(2, tile_row0(2, e2));
+  fetch_tile(3, tile_row0(3, e3));
+  // K and V of this wavefront's keys (requested before the tiles: complete once at most the tiles are in flight).
+  // V enters negated: the dP accumulator starts at D and ends at D - dP, so that dS = (-P) (D - dP) costs one
+  // multiplication per element.
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(4 * kPerTile) : "memory");
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+    u32x4 w = __builtin_bit_cast(u32x4, vf[s]);
+    w ^= 0x80008000u;
+    vf[s] = __builtin_bit_cast(bf16x8, w);
+  }
+  // from here on they live in the accumulation half of the register file (every use below asks for them there;
+  // defined there, they are not copied before each use)
+#pragma unroll
+  for (int s = 0; s < 8; ++s) asm volatile("" : "+a"(kf[s]), "+a"(vf[s]));
+  // All MFMAs of the loop are inline assembly.  The loop-invariant B operands (K and -V of this wavefront's keys) and
+  // the accumulators sit in the accumulation half of the register file; S and D - dP come out in ordinary registers,
+  // and their first reader is vector work a whole phase (16 MFMAs) later.
+  auto mfma_zero = [&](f32x16& acc, const bf16x8 a, const bf16x8& b) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "a"(b));
+  };
+  auto mfma_more = [&](f32x16& acc, const bf16x8 a, const bf16x8& b) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b));
+  };
+  // A wavefront alone on its SIMD issues in order, one instruction per four cycles, and an MFMA keeps the matrix
+  // pipeline busy for 32: everything that is not an MFMA (56 LDS reads, 10 transfers, ~70 vector instructions per
+  // tile, about as many issue cycles as the 32 MFMAs take to execute) has to sit BETWEEN MFMAs or the pipeline
+  // idles.  Hence a loop pipelined over three tiles, the source order below being the issue order (a fence after
+  // every group).  Trip n:
+  //   phase one   S and D - dP of tile n + 1 (16 MFMAs; its rows were read in the trip before) next to P and dS of
+  //               tile n (vector work on the previous trip's S and D - dP) and the transposing reads of tile n;
+  //   barrier     tile n + 2 has landed, tile n's slot is free: tile n + 4 requested into it;
+  //   phase two   tile n into dV and dK (16 MFMAs) next to the reads of tile n + 2's rows and D, tile n + 1's
+  //               row statistic, and the requests.
+  f32x16 s0, p0, s1, p1;   // S and D - dP, two generations
+  bf16x8 qa[8], ga[8];     // rows of the tile whose scores come next
+  float lsr[16];           // row statistic of the tile whose probabilities come next
+  auto d_read = [&](const int par, const int g, f32x16& dpacc) {   // rows 8 g + 4 h .. + 4 of D
+    const float4 d4 = *reinterpret_cast<const float4*>(sStat + 128 * par + 64 + 8 * g + 4 * h);
+    dpacc[4 * g] = d4.x; dpacc[4 * g + 1] = d4.y; dpacc[4 * g + 2] = d4.z; dpacc[4 * g + 3] = d4.w;
+  };
+  auto lse_read = [&](const int par, const int g) {
+    const float4 l4 = *reinterpret_cast<const float4*>(sStat + 128 * par + 8 * g + 4 * h);
+    lsr[4 * g] = l4.x; lsr[4 * g + 1] = l4.y; lsr[4 * g + 2] = l4.z; lsr[4 * g + 3] = l4.w;
+  };
+  auto rows_read = [&](const int par, const int s) {
+    qa[s] = rows_frag(sQ + par * RTILE, rb, s);
+    ga[s] = rows_frag(sdO + par * RTILE, rb, s);
+  };
+  // prologue: S and D - dP of tile 0; rows and D of tile 1, row statistic of tile 0
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(3 * kPerTile) : "memory");   // tile 0
+  __syncthreads();
+#pragma unroll
+  for (int g = 0; g < 4; ++g) d_read(0, g, p0);
+#pragma unroll
+  for (int s = 0; s < 8; ++s) rows_read(0, s);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+    if (s == 0) mfma_zero(s0, qa[0], kf[0]);
+    else mfma_more(s0, qa[s], kf[s]);
+    mfma_more(p0, ga[s], vf[s]);
+  }
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * kPerTile) : "memory");   // tile 1
+  __syncthreads();
+#pragma unroll
+  for (int g = 0; g < 4; ++g) { d_read(1, g, p1); lse_read(0, g); }
+#pragma unroll
+  for (int s = 0; s < 8; ++s) rows_read(1, s);
+  __builtin_amdgcn_sched_barrier(0);
+
+  auto tile_step = [&](const int n, const int par, f32x16& sc, f32x16& dp, f32x16& sn, f32x16& dn) {
+    // par = n mod 4 (a literal at the call sites): the slot of tile n.  sc, dp: S and D - dP of tile n;
+    // sn, dn: those of tile n + 1, dn holding D so far.
     const char* tQ = sQ + par * RTILE;
     const char* tdO = sdO + par * RTILE;
-    const float* tS = sStat + 128 * par;
-    // All fragments of a phase are requested before its first MFMA (there are registers for it: one wavefront per
-    // SIMD).  While the first ones travel, and then between the MFMAs (each keeps the matrix pipe busy for some
-    // thirty cycles in which this wavefront may issue other instructions), tile n + 3 is requested piece by piece.
-    f32x16 sacc, dpacc;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) sacc[r] = 0.0f;
-    float lsr[16];
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const float4 l4 = *reinterpret_cast<const float4*>(tS + 8 * g + 4 * h);
-      const float4 d4 = *reinterpret_cast<const float4*>(tS + 64 + 8 * g + 4 * h);
-      lsr[4 * g] = l4.x; lsr[4 * g + 1] = l4.y; lsr[4 * g + 2] = l4.z; lsr[4 * g + 3] = l4.w;
-      dpacc[4 * g] = d4.x; dpacc[4 * g + 1] = d4.y; dpacc[4 * g + 2] = d4.z; dpacc[4 * g + 3] = d4.w;
-    }
-    bf16x8 qa[8], ga[8];
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      qa[s] = rows_frag(tQ, rb, s);
-      ga[s] = rows_frag(tdO, rb, s);
-    }
-    __builtin_amdgcn_sched_barrier(0);   // (the scheduler would move each read next to its MFMA)
-    const int slot_ = (par + 3) % NSLOT;
-    const int r0 = __builtin_amdgcn_readfirstlane(row0_d);
-    const i32x4 dq_ = dma.moved(q_desc, r0), dg_ = dma.moved(do_desc, r0);
-    static_assert(TileDma<2>::CPT == 4, "the spreading below assumes four pieces per tensor");
-    dma.piece(dq_, sQ_lds + slot_ * RTILE, 0);
-    dma.piece(dq_, sQ_lds + slot_ * RTILE, 1);
-    dma.piece(dq_, sQ_lds + slot_ * RTILE, 2);
-    dma.piece(dq_, sQ_lds + slot_ * RTILE, 3);
+    // ---- phase one.  P = 2^(c S - lse2) and dS = (-P) (D - dP).  Nothing is masked: a query row that does not
+    // exist has zeros for Q, dO, lse2 and D in LDS (P = 1, dS = 0, and its columns of Q^T and dO^T are zero), and a
+    // key that does not exist owns a column of dK^T and dV^T that is never stored.
+    bf16x8 trf[16];         // transposed fragments of tile n in the order of their use: 8 t2 + 2 ft + (0: dO^T, 1: Q^T)
+    u32x4 pfw[2], dsw[2];   // P and dS, two bf16 per word
+    auto tr_read = [&](const int f) {
+      trf[f] = transposed_frag((f & 1) ? tQ : tdO, tb, (f >> 1) & 3, f >> 3);
+    };
+    // rows 2 s and 2 s + 1 of this lane's P and dS, in two halves.  (The empty statements that name the results keep
+    // the vector work where it is written: without them the compiler collects all of it behind the phase's MFMAs.)
+    float pe, dse;
+    auto rows_even = [&](const int s) {
+      pe = __builtin_amdgcn_exp2f(fmaf(sc[2 * s], c_scale, -lsr[2 * s]));
+      dse = -pe * dp[2 * s];
+      asm volatile("" : "+v"(pe), "+v"(dse));
+    };
+    auto rows_odd = [&](const int s) {
+      const float po = __builtin_amdgcn_exp2f(fmaf(sc[2 * s + 1], c_scale, -lsr[2 * s + 1]));
+      const bf16x2 pw = {static_cast<__bf16>(pe), static_cast<__bf16>(po)};
+      const bf16x2 dw = {static_cast<__bf16>(dse), static_cast<__bf16>(-po * dp[2 * s + 1])};
+      uint32_t pwi = __builtin_bit_cast(uint32_t, pw), dwi = __builtin_bit_cast(uint32_t, dw);
+      asm volatile("" : "+v"(pwi), "+v"(dwi));
+      pfw[s >> 2][s & 3] = pwi;
+      dsw[s >> 2][s & 3] = dwi;
+    };
+    // The vector work of the first 16 tokens sits in the first half of phase one, that of the other 16 in the first
+    // half of phase two; the halves without it carry more of the reads and the requests.
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
-      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[s], kf[s], sacc, 0, 0, 0);
-      dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga[s], vf[s], dpacc, 0, 0, 0);
-      if (s < 4) dma.piece(dg_, sdO_lds + slot_ * RTILE, s);
-      if (s == 4) stat_fetch(slot_, r0, 0);
-      if (s == 5) stat_fetch(slot_, r0, 1);
+      if (s == 0) mfma_zero(sn, qa[0], kf[0]);
+      else mfma_more(sn, qa[s], kf[s]);
+      if (s < 4) { tr_read(s); rows_even(s); }
+      else { tr_read(3 * s - 8); tr_read(3 * s - 7); }
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_more(dn, ga[s], vf[s]);
+      if (s < 4) rows_odd(s);
+      else tr_read(3 * s - 6);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    bf16x8 qt[2][4], gt[2][4];
+    // ---- tile n + 2 visible, tile n's slot free (every transposing read of it has returned)
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(kPerTile) : "memory");   // this wavefront's parts of tile n + 2
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __syncthreads();
+    entry_wait(e_next);
+    const int r0 = __builtin_amdgcn_readfirstlane(tile_row0(n + 4, e_next));
+    e_next = entry_issue(n + 5);
+    static_assert(TileDma<2>::CPT == 4, "four pieces per tensor");
+    // ---- phase two: tile n into the accumulators; dp (spent) takes D of tile n + 2
+    const int p2 = (par + 2) % NSLOT, p1n = (par + 1) % NSLOT;
 #pragma unroll
-    for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-      for (int ft = 0; ft < 4; ++ft) {
-        gt[t2][ft] = transposed_frag(tdO, tb, ft, t2);
-        qt[t2][ft] = transposed_frag(tQ, tb, ft, t2);
+    for (int u = 0; u < 8; ++u) {   // u = 4 t2 + ft
+      const int t2 = u >> 2, ft = u & 3;
+      const bf16x8 pf = __builtin_bit_cast(bf16x8, pfw[t2]), dsf = __builtin_bit_cast(bf16x8, dsw[t2]);
+      // (in the second half an MFMA and a piece of tile n + 4 share a statement: the MFMA is the wait state that the
+      // transfer needs behind the write of m0)
+      const int voff = u >= 4 ? dma.offset_of(u - 4, r0 * (D * 2)) : 0;
+      if (u == 0) mfma_acc<true>(dv[ft], trf[2 * u], pf);   // first reader of pf
+      else if (u < 4) mfma_acc<false>(dv[ft], trf[2 * u], pf);
+      else mfma_acc_piece(dv[ft], trf[2 * u], pf, u == 4, dma.place_of(sQ_lds + par * RTILE, u - 4), voff, q_desc);
+      qa[u] = rows_frag(sQ + p2 * RTILE, rb, u);
+      if (u < 4) rows_even(4 + u);
+      __builtin_amdgcn_sched_barrier(0);
+      if (u == 0) mfma_acc<true>(dk[ft], trf[2 * u + 1], dsf);
+      else if (u < 4) mfma_acc<false>(dk[ft], trf[2 * u + 1], dsf);
+      else mfma_acc_piece(dk[ft], trf[2 * u + 1], dsf, u == 4, dma.place_of(sdO_lds + par * RTILE, u - 4), voff, do_desc);
+      ga[u] = rows_frag(sdO + p2 * RTILE, rb, u);
+      if (u < 4) {
+        rows_odd(4 + u);
+      } else {
+        d_read(p2, u - 4, dp);
+        lse_read(p1n, u - 4);
+        if (u == 5) stat_fetch(par, r0, 0);
+        if (u == 6) stat_fetch(par, r0, 1);
       }
-    __builtin_amdgcn_sched_barrier(0);   // the reads above stay above the vector work below
-    bf16x8 pf[2], dsf[2];
-    // P = 2^(c S - lse2) and dS = (-P) (D - dP).  Nothing is masked: a query row that does not exist has zeros for
-    // Q, dO, lse2 and D in LDS (P = 1, dS = 0, and its columns of Q^T and dO^T are zero), and a key that does not
-    // exist owns a column of dK^T and dV^T that is never stored.
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const float p = __builtin_amdgcn_exp2f(fmaf(sacc[r], c_scale, -lsr[r]));
-      pf[r >> 3][r & 7] = static_cast<__bf16>(p);
-      dsf[r >> 3][r & 7] = static_cast<__bf16>(-p * dpacc[r]);
+      __builtin_amdgcn_sched_barrier(0);
     }
-#pragma unroll
-    for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-      for (int ft = 0; ft < 4; ++ft) {
-        if (ft == 0) {   // first readers of pf[t2] and dsf[t2]
-          mfma_acc<true>(dv[ft], gt[t2][ft], pf[t2]);
-          mfma_acc<true>(dk[ft], qt[t2][ft], dsf[t2]);
-        } else {
-          mfma_acc<false>(dv[ft], gt[t2][ft], pf[t2]);
-          mfma_acc<false>(dk[ft], qt[t2][ft], dsf[t2]);
-        }
-      }
   };
-  for (int n = 0; n < ntiles; n += 4) {   // slot numbers are literals
-    tile_step(n, 0);
-    tile_step(n + 1, 1);
-    tile_step(n + 2, 2);
-    tile_step(n + 3, 3);
+  for (int n = 0; n < ntiles; n += 4) {   // slot numbers are literals; tiles past the list are zeros
+    tile_step(n, 0, s0, p0, s1, p1);
+    tile_step(n + 1, 1, s1, p1, s0, p0);
+    tile_step(n + 2, 2, s0, p0, s1, p1);
+    tile_step(n + 3, 3, s1, p1, s0, p0);
   }
-  // nothing may land in LDS once the tiles' space is reused; and the last accumulating MFMAs (inline assembly: the
-  // compiler does not count wait states for them) must have written their results before these are read
   // (the idle slots name the accumulators as operands, or the compiler moves the reads above them)
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   asm volatile("s_nop 15\n\ts_nop 15" : "+a"(dk[0]), "+a"(dk[1]), "+a"(dk[2]), "+a"(dk[3]), "+a"(dv[0]), "+a"(dv[1]),
@@ -687,9 +803,9 @@ size_t bwd_planes_bytes(const hf_config& c) {
 // state == NULL: no history branch.  Q_hist != Q: its gradient goes to dQ_hist, else it joins dQ.
 int launch_bwd_mfma(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
                     const int32_t* idx, int k, const void* dO, const float* lse2, const float* Dv,
-                    const int32_t* inv_cnt, const int32_t* inv_list, const float* state, const float* cosq,
-                    const float* sinq, const void* Q_hist, void* planes, void* dQ, void* dQ_hist, void* dK,
-                    void* dV, hipStream_t s) {
+                    const int32_t* inv_cnt, const int32_t* inv_list, int32_t* dkv_order, const float* state,
+                    const float* cosq, const float* sinq, const void* Q_hist, void* planes, void* dQ, void* dQ_hist,
+                    void* dK, void* dV, hipStream_t s) {
   if (n_kv >= (1 << 23) || n_q >= (1 << 23)) { set_error("more than 2^23 tokens"); return HF_ERR_SHAPE; }
   const int BH = c.batch * c.heads;
   const int t_m = (n_q + c.block_q - 1) / c.block_q, t_n = (n_kv + c.block_kv - 1) / c.block_kv;
@@ -744,9 +860,14 @@ int launch_bwd_mfma(const hf_config& c, const void* Q, int n_q, const void* K, c
     }
     dkv_ready = true;
   }
+  const int32_t* order = nullptr;   // equal lists (dense), or a share too long for the ordering kernel: index order
+  if (inv_cnt && dkv_order && kv_per_xcd <= kOrderMax) {
+    hipLaunchKernelGGL(dkv_order_kernel, dim3(8), dim3(1024), 0, s, inv_cnt, slabs, kv_per_xcd, (int)kv_items, dkv_order);
+    order = dkv_order;
+  }
   hipLaunchKernelGGL(bwd_dkv_mfma_kernel, dim3(8 * kv_per_xcd), dim3(128), kDkvLds, s, q, kk, v, g, inv_cnt, inv_list, n_q,
-                     n_kv, kvs, c.block_q, c.block_kv, t_m, t_n, slabs, kv_per_xcd, (int)kv_items, c_scale, scale, lse2,
-                     Dv, static_cast<bf16_t*>(dK), static_cast<bf16_t*>(dV));
+                     n_kv, kvs, c.block_q, c.block_kv, t_m, t_n, slabs, kv_per_xcd, (int)kv_items, order, c_scale, scale,
+                     lse2, Dv, static_cast<bf16_t*>(dK), static_cast<bf16_t*>(dV));
   return check_launch("hf_hybrid_attn_bwd(dK, dV)");
 }
 

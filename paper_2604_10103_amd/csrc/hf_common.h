@@ -117,9 +117,9 @@ bool bwd_mfma_supported(const hf_config& c);
 size_t bwd_planes_bytes(const hf_config& c);
 int launch_bwd_mfma(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
                     const int32_t* idx, int k, const void* dO, const float* lse2, const float* Dv,
-                    const int32_t* inv_cnt, const int32_t* inv_list, const float* state, const float* cosq,
-                    const float* sinq, const void* Q_hist, void* planes, void* dQ, void* dQ_hist, void* dK,
-                    void* dV, hipStream_t s);
+                    const int32_t* inv_cnt, const int32_t* inv_list, int32_t* dkv_order, const float* state,
+                    const float* cosq, const float* sinq, const void* Q_hist, void* planes, void* dQ, void* dQ_hist,
+                    void* dK, void* dV, hipStream_t s);
 int launch_invert_index(const hf_config& c, const int32_t* idx, int k, int t_m, int t_n, int32_t* inv_cnt,
                         int32_t* inv_list, hipStream_t s);
 int launch_bwd_generic(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
