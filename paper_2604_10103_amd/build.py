@@ -54,9 +54,6 @@ FLAGS = [
 # flight ahead of the MFMAs of the flash-attention loops (the default one serialises them)
 EXTRA_FLAGS = {
     "hf_attn_w64.hip": ["-mllvm", "-amdgpu-sched-strategy=iterative-ilp"],
-    # the dK/dV kernel runs one wavefront per SIMD and keeps its 128 accumulators in the accumulation half of
-    # the register file by hand; every other MFMA result stays in ordinary registers, where the vector ALU reads it
-    "hf_bwd_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
 }
 
 

@@ -113,8 +113,8 @@ static BwdLayout bwd_layout(const hf_config* c, int n_q, int n_kv) {
   w.dqh32 = w.dvec + align256(bh * n_q * 4);
   w.inv_cnt = w.dqh32 + align256(bh * (size_t)n_q * d * 4);
   w.inv_list = w.inv_cnt + align256(bh * t_n * 4);
-  w.order = w.inv_list + align256(bh * t_n * t_m * 4);   // launch order of the dK/dV workgroups (64 keys each)
-  w.planes = w.order + align256(bh * t_n * cdiv(c->block_kv, 64) * 4);
+  w.order = w.inv_list + align256(bh * t_n * t_m * 4);   // launch order of the dK/dV workgroups (64 keys each):
+  w.planes = w.order + align256(bh * t_n * cdiv(c->block_kv, 64) * 8 * 4);   // records of 8 words
   w.total = w.planes + align256(bwd_planes_bytes(*c));
   return w;
 }

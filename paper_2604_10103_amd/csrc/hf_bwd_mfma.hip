@@ -18,7 +18,8 @@
 // end of the head arrive as zeros), row-major with swizzled 16-byte units, and serves both kinds of A operand:
 // tokens as rows by 16-byte reads, features as rows by gfx950's transposing reads (ds_read_b64_tr_b16).
 // No staging registers, no LDS stores, no transposing permutes; one barrier per tile; two slots per tensor in
-// the dQ kernel (a tile requested one tile ahead), four in the dK/dV kernel (three ahead).
+// the dQ kernel (a tile requested one tile ahead), four in the dK/dV kernel, whose loop is pipelined over three
+// tiles (workgroups launched longest list first: dkv_order_kernel).
 #include <math.h>
 
 #include "hf_common.h"
@@ -456,28 +457,57 @@ __device__ __forceinline__ void mfma_acc(f32x16& acc, const bf16x8 a, const bf16
 // Launch order of the dK/dV workgroups.  A workgroup's time is proportional to the length of its KV block's list
 // of query blocks, and the lists differ (top-k selection: a binomial spread around t_m k / t_n), while a GPU takes
 // workgroups in index order as slots free up.  Longest first within every XCD's share of the items leaves the short
-// ones to fill the end: order[first item of the share + rank] = item, rank by (list length descending, item
-// ascending), found by counting.  One workgroup per share; the share's keys sit in LDS.
-constexpr int kOrderMax = 8192;   // items per share this kernel takes (32 KB of LDS)
-__global__ __launch_bounds__(1024) void dkv_order_kernel(const int32_t* __restrict__ inv_cnt, int slabs,
+// ones to fill the end.  The kernel writes one record of 8 words per place: the item that runs there (rank by list
+// length descending, item ascending, found by counting), the length of its list and the list's first three entries,
+// so that a workgroup has all it needs for its first tiles after ONE dependent load (a workgroup is alone on its
+// two SIMDs: every round trip to memory before its first MFMA is idle time).
+// One workgroup per share; the share's keys sit in LDS.
+constexpr int kOrderMax = 4096;   // items per share this kernel takes (4 per thread, 2 x 16 KB of LDS)
+constexpr int kOrderRec = 8;      // words per record
+__global__ __launch_bounds__(1024) void dkv_order_kernel(const int32_t* __restrict__ inv_cnt,
+                                                          const int32_t* __restrict__ inv_list, int t_m, int slabs,
                                                           int items_per_xcd, int total_items,
                                                           int32_t* __restrict__ order) {
-  __shared__ int32_t key[kOrderMax];
+  __shared__ int32_t key[kOrderMax], rank[kOrderMax];
   const int first = blockIdx.x * items_per_xcd;
   const int n = max(0, min(items_per_xcd, total_items - first));
-  for (int j = threadIdx.x; j < n; j += 1024) key[j] = inv_cnt[(first + j) / slabs];
-  __syncthreads();
-  // a wavefront per item: its lanes share the comparisons, a ballot counts them
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  for (int j = wave; j < n; j += 16) {
-    const int mine = key[j];
-    int rank = 0;
-    for (int i0 = 0; i0 < n; i0 += 64) {
-      const int i = i0 + lane;
-      const int other = i < n ? key[i] : -1;   // (a list length is never negative)
-      rank += __builtin_popcountll(__ballot(other > mine || (other == mine && i < j)));
+  // a thread per item: list length and first entries, all loads in flight together
+  int4 head[kOrderMax / 1024];
+#pragma unroll
+  for (int q = 0; q < kOrderMax / 1024; ++q) {
+    const int j = threadIdx.x + 1024 * q;
+    if (j < n) {
+      const int kvb = (first + j) / slabs;
+      const int32_t* list = inv_list + (size_t)kvb * t_m;
+      head[q] = int4{inv_cnt[kvb], list[0], list[min(1, t_m - 1)], list[min(2, t_m - 1)]};
+      key[j] = head[q].x;
+      rank[j] = 0;
     }
-    if (lane == 0) order[first + rank] = first + j;
+  }
+  __syncthreads();
+  // the n x n comparisons spread over all threads: `per` threads share an item, each takes every per-th key and
+  // adds its count to the item's rank
+  int per = 1;
+  while (per < 64 && 2 * per * n <= 1024) per *= 2;
+  const int sub = threadIdx.x & (per - 1);
+  for (int j = threadIdx.x / per; j < n; j += 1024 / per) {
+    const int mine = key[j];
+    int before = 0;
+    for (int i = sub; i < n; i += per) {
+      const int other = key[i];
+      before += (other > mine || (other == mine && i < j)) ? 1 : 0;
+    }
+    atomicAdd(&rank[j], before);
+  }
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < kOrderMax / 1024; ++q) {
+    const int j = threadIdx.x + 1024 * q;
+    if (j < n) {
+      int4* rec = reinterpret_cast<int4*>(order + (size_t)(first + rank[j]) * kOrderRec);
+      rec[0] = int4{first + j, head[q].x, head[q].y, head[q].z};
+      rec[1] = int4{head[q].w, 0, 0, 0};
+    }
   }
 }
 
@@ -518,7 +548,9 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   const int place = xcd * items_per_xcd + slot;   // the slot-th workgroup of this XCD's share, longest lists first
   if (slot >= items_per_xcd || place >= total_items) return;
-  const int item = order ? order[place] : place;
+  // the record of this place: item, list length, first three list entries (no record: index order, entries loaded)
+  const int32_t* rec = order ? order + (size_t)place * kOrderRec : nullptr;
+  const int item = rec ? rec[0] : place;
   const int bh = item / (t_n * slabs);
   const int rest = item - bh * (t_n * slabs);
   const int jb = rest / slabs, slab = rest - jb * slabs;
@@ -534,7 +566,7 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   const __amdgpu_buffer_rsrc_t v_rsrc = rsrc_of(V + (size_t)bh * kv_stride * D, n_kv);
   const float* lseh = lse2 + (size_t)bh * n_q;
   const float* Dvh = Dv + (size_t)bh * n_q;
-  const int n_lists = inv_cnt ? inv_cnt[(size_t)bh * t_n + jb] : t_m;   // no lists: every query block (dense)
+  const int n_lists = rec ? rec[1] : inv_cnt ? inv_cnt[(size_t)bh * t_n + jb] : t_m;   // no lists: every query block (dense)
   const int32_t* list = inv_list ? inv_list + ((size_t)bh * t_n + jb) * t_m : nullptr;
 
   // this wavefront's 32 keys (keys past the block's end are computed along and never stored)
@@ -553,9 +585,8 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     for (int r = 0; r < 16; ++r) { dk[a][r] = 0.0f; dv[a][r] = 0.0f; }
 
   // tiles of 32 query rows of the listed query blocks.  The rows come from all over the head (whatever query
-  // blocks selected this KV block), so a tile is requested three tiles before its use: Q, dO and the row
-  // statistics of tiles n + 1 .. n + 3 are on their way into the other slots while tile n is consumed; one
-  // barrier per tile.  Rows past n_q, and whole tiles past the end of the list, read zeros.
+  // blocks selected this KV block), so a tile is requested two trips of the loop before its first use, into one of
+  // four slots (Q, dO and the row statistics).  Rows past n_q, and whole tiles past the end of the list, read zeros.
   const int qtiles = bq / TT;
   const int ntiles = n_lists * qtiles;
   // List entries are fetched with scalar loads issued one tile ahead of their use and awaited behind the next
@@ -600,12 +631,22 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     stat_fetch(slot_, r0, 1);
   };
   constexpr int kPerTile = 2 * TileDma<2>::CPT + 2;   // transfers a wavefront issues per tile
-  int e0 = entry_issue(0), e1 = entry_issue(1), e2 = entry_issue(2), e3 = entry_issue(3), e_next = entry_issue(4);
-  entry_wait(e0);
-  entry_wait(e1);
-  entry_wait(e2);
-  entry_wait(e3);
-  entry_wait(e_next);
+  int e0, e1, e2, e3, e_next;   // entries of tiles 0 .. 4
+  if (rec) {
+    const int r0 = rec[2], r1 = rec[3], r2 = rec[4];
+    e0 = r0;
+    e1 = r0;
+    e2 = qshift == 1 ? r1 : r0;
+    e3 = e2;
+    e_next = qshift == 1 ? r2 : r1;
+  } else {
+    e0 = entry_issue(0), e1 = entry_issue(1), e2 = entry_issue(2), e3 = entry_issue(3), e_next = entry_issue(4);
+    entry_wait(e0);
+    entry_wait(e1);
+    entry_wait(e2);
+    entry_wait(e3);
+    entry_wait(e_next);
+  }
   fetch_tile(0, tile_row0(0, e0));
   fetch_tile(1, tile_row0(1, e1));
   fetch_tile(2, tile_row0(2, e2));
@@ -862,7 +903,8 @@ int launch_bwd_mfma(const hf_config& c, const void* Q, int n_q, const void* K, c
   }
   const int32_t* order = nullptr;   // equal lists (dense), or a share too long for the ordering kernel: index order
   if (inv_cnt && dkv_order && kv_per_xcd <= kOrderMax) {
-    hipLaunchKernelGGL(dkv_order_kernel, dim3(8), dim3(1024), 0, s, inv_cnt, slabs, kv_per_xcd, (int)kv_items, dkv_order);
+    hipLaunchKernelGGL(dkv_order_kernel, dim3(8), dim3(1024), 0, s, inv_cnt, inv_list, t_m, slabs, kv_per_xcd,
+                       (int)kv_items, dkv_order);
     order = dkv_order;
   }
   hipLaunchKernelGGL(bwd_dkv_mfma_kernel, dim3(8 * kv_per_xcd), dim3(128), kDkvLds, s, q, kk, v, g, inv_cnt, inv_list, n_q,
