@@ -4,9 +4,9 @@
 // 32-entry table, and every accumulated gradient stays in registers until it is stored once:
 //
 //  dQ  (one workgroup per query block, one wavefront per 32 query rows, tiles of 32 keys)
-//      S^T  = K Q^T          dP^T = V dO^T            lane = query row, registers = keys
-//      dS^T = 2^(c S^T - lse2) * (dP^T - D)           -> bf16, B operand
-//      dQ^T += K^T dS^T                               A operand = K transposed in LDS
+//      S^T  = K Q^T          D - dP^T = D + V (-dO)^T  lane = query row, registers = keys
+//      dS^T = (-2^(c S^T - lse2)) (D - dP^T)           -> bf16, B operand
+//      dQ^T += K^T dS^T                                A operand = K transposed in LDS
 //  dK, dV  (one workgroup per 64 keys of a KV block, a wavefront per 32 keys x 128 features, one wavefront per
 //      SIMD with the 128 accumulators in the accumulation half of the register file, tiles of 32 query rows
 //      taken from the inverse index lists)
@@ -17,9 +17,10 @@
 // A tile of 32 tokens x 128 features goes global -> LDS directly (buffer loads with the LDS bit; rows past the
 // end of the head arrive as zeros), row-major with swizzled 16-byte units, and serves both kinds of A operand:
 // tokens as rows by 16-byte reads, features as rows by gfx950's transposing reads (ds_read_b64_tr_b16).
-// No staging registers, no LDS stores, no transposing permutes; one barrier per tile; two slots per tensor in
-// the dQ kernel (a tile requested one tile ahead), four in the dK/dV kernel, whose loop is pipelined over three
-// tiles (workgroups launched longest list first: dkv_order_kernel).
+// No staging registers, no LDS stores, no transposing permutes; one barrier per tile.  Both kernels run one
+// wavefront per SIMD with their accumulators and loop-invariant operands in the accumulation half of the register
+// file, all MFMAs of their loops as inline assembly, four tile slots and a loop pipelined over three tiles; the
+// dK/dV workgroups are launched longest list first (dkv_order_kernel).
 #include <math.h>
 
 #include "hf_common.h"
@@ -191,20 +192,65 @@ __global__ __launch_bounds__(256) void state_planes_bwd_kernel(const float* __re
   for (int r = ty; r < 32; r += 8) lt[(size_t)(j0 + r) * D + i0 + tx] = f32_to_bf16(tile[tx][r]);
 }
 
+// acc += A B with the accumulator pinned to the accumulation half of the register file (the compiler, left to
+// itself, keeps such accumulators in ordinary registers and shuttles others through that half).  The compiler
+// counts no wait states for inline assembly, so they are provided here: A comes from LDS reads, which it awaits as
+// for any use; C is the same accumulator's previous value, eight MFMAs back; B is a vector ALU result, and an MFMA
+// may not read one in the two issue slots after it was written: kWait = true puts two idle slots first, for the
+// first reader of a B operand.  volatile keeps the MFMAs in program order, so that the first reader stays the first.
+template <bool kWait>
+__device__ __forceinline__ void mfma_acc(f32x16& acc, const bf16x8 a, const bf16x8 b) {
+  if (kWait) asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+  else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
+// Scores-type products of the two pipelined kernels: the loop-invariant B operand sits in the accumulation half of
+// the register file, the result in ordinary registers (its first reader is vector work a phase of MFMAs later).
+__device__ __forceinline__ void mfma_zero(f32x16& acc, const bf16x8 a, const bf16x8& b) {   // acc = A B
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "a"(b));
+}
+__device__ __forceinline__ void mfma_from(f32x16& acc, const bf16x8 a, const bf16x8& b, const f32x16& c) {   // = A B + C
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(acc) : "v"(a), "a"(b), "v"(c));
+}
+__device__ __forceinline__ void mfma_more(f32x16& acc, const bf16x8 a, const bf16x8& b) {   // acc += A B
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b));
+}
+// acc += A B, accumulator in the accumulation half, with a 1 KB transfer global -> LDS behind it (LDS address through
+// m0, written in front of the MFMA, which is the wait state that the transfer needs behind that write)
+__device__ __forceinline__ void mfma_acc_piece(f32x16& acc, const bf16x8 a, const bf16x8 b, const bool wait,
+                                               const uint32_t lds, const int voff, const i32x4& desc) {
+  if (wait)
+    asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\t"
+                 "buffer_load_dwordx4 %4, %5, 0 offen lds"
+                 : "+a"(acc) : "v"(a), "v"(b), "s"(lds), "v"(voff), "s"(desc) : "memory", "m0");
+  else
+    asm volatile("s_mov_b32 m0, %3\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\t"
+                 "buffer_load_dwordx4 %4, %5, 0 offen lds"
+                 : "+a"(acc) : "v"(a), "v"(b), "s"(lds), "v"(voff), "s"(desc) : "memory", "m0");
+}
+
 // ---------------------------------------------------------------------------------------------- dQ
-template <int NW, int kHist>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2))) void bwd_dq_mfma_kernel(
+// One workgroup per query block, a wavefront per 32 query rows, one wavefront per SIMD: the 64 accumulators of
+// dQ^T and the loop-invariant Q and -dO fragments sit in the accumulation half of the register file; only MFMAs
+// touch the accumulators inside the loop, whose body has no vector branch (see the dK/dV kernel below for why).
+// kRagged: block_kv is no multiple of 32, so that the last part of a block is cut short and its missing keys have
+// to be masked (they are keys of the next block).
+constexpr int kDqSlots = 4;   // tiles in LDS: K and V each
+constexpr int kDqLds = kDqSlots * 2 * RTILE;
+template <int NW, int kHist, bool kRagged>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, 1))) void bwd_dq_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const bf16_t* __restrict__ dO, const int32_t* __restrict__ idx, int k, int n_q, int n_kv, int kv_stride, int bkv,
     int t_m, int t_n, int items_per_xcd, int total_items, float c_scale, float scale,
     const float* __restrict__ lse2, const float* __restrict__ Dv, BwdHist hist, bf16_t* __restrict__ dQ) {
   constexpr int NT = 64 * NW;
   constexpr int BQ = 32 * NW;
-  __shared__ __attribute__((aligned(16))) char smem[5 * RTILE];   // K x 2, V x 2; all of it for a state plane later
-  static_assert(4 * RTILE <= 5 * RTILE, "a state plane (four pieces of 32 rows) must fit in the tiles' space");
+  constexpr int NSLOT = kDqSlots;
+  extern __shared__ __attribute__((aligned(16))) char smem[];   // kDqLds bytes: K and V per slot; a state plane later
+  static_assert(4 * RTILE <= kDqLds, "a state plane (four pieces of 32 rows) must fit in the tiles' space");
   char* const sK = smem;
-  char* const sV = smem + 2 * RTILE;
-  static_assert(BQ * OSTR <= 5 * RTILE, "staged output must fit");
+  char* const sV = smem + NSLOT * RTILE;
+  static_assert(BQ * OSTR <= kDqLds, "staged output must fit");
 
   // consecutive workgroup ids go to consecutive XCDs: every XCD gets one contiguous run of (head, query
   // block) items, so that its L2 holds the keys and values of few heads
@@ -232,78 +278,195 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
   row_frags(do_rsrc, q_row, h, dof);
   const size_t stat = (size_t)bh * n_q + min(q_row, n_q - 1);
   const float lse = lse2[stat], dvec = Dv[stat];
+  // (requested now, used after the first tiles have been requested: the latencies overlap)
+  f32x16 dq[4], dinit;
 
-  f32x16 dq[4];
-#pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) dq[dt][r] = 0.0f;
-
-  // tile list: (selected block, 32-key part) -> (first key, real keys); a part past the end of a short block
-  // or an out-of-range block index gives (0, 0) and is skipped.  K and V of tile t + 1 are on their way into
-  // the other pair of slots while tile t is consumed; one barrier per tile.
+  // Tile list: (selected block, 32-key part) -> first key.  A tile past the end of the list, an out-of-range block
+  // index or an empty part of a short block starts at n_kv: past the head's end, where the transfers deliver
+  // zeros, and zeros for K contribute nothing to dQ whatever P is.  Block indices come by scalar loads one tile
+  // ahead of their use, awaited behind the next barrier (a vector load in the loop would share the transfers'
+  // counter and drain them); the counters (sel, sub) of the next tile to look up advance without a branch.
   const int ntiles = nsel * subs;
-  auto tile_desc = [&](int t, int& start, int& valid) {   // uniform over the workgroup
-    start = 0;
-    valid = 0;
-    if (t >= ntiles) return;
-    const int sel = t / subs, sub = t - sel * subs;
-    const int jb = row_idx ? row_idx[sel] : sel;
-    if ((unsigned)jb >= (unsigned)t_n) return;
-    const int first = jb * bkv + TT * sub;
-    const int n = min(TT, min(n_kv, (jb + 1) * bkv) - first);
-    if (n > 0) { start = first; valid = n; }
+  const int32_t* list_base = row_idx ? row_idx : reinterpret_cast<const int32_t*>(Q);   // dense: any readable word
+  int sel_n = 0, sub_n = 0;
+  auto entry_issue_at = [&](const int sel) {
+    int jb;
+    const int off = __builtin_amdgcn_readfirstlane(row_idx ? 4 * min(sel, nsel - 1) : 0);
+    asm volatile("s_load_dword %0, %1, %2" : "=s"(jb) : "s"(list_base), "s"(off) : "memory");
+    return jb;
   };
-  int start, valid;
-  tile_desc(0, start, valid);
-  dma.fetch(k_desc, sK_lds, start);
-  dma.fetch(v_desc, sV_lds, start);
-  auto tile_step = [&](const int t, const int par) {
-    const int valid_cur = valid;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's parts of tile t
-    __syncthreads();                                   // tile t complete, tile t - 1 consumed by everybody
-    tile_desc(t + 1, start, valid);
-    dma.fetch(k_desc, sK_lds + (par ^ 1) * RTILE, start);
-    dma.fetch(v_desc, sV_lds + (par ^ 1) * RTILE, start);
-    if (valid_cur == 0) return;
-    const char* tK = sK + par * RTILE;
-    const char* tV = sV + par * RTILE;
-    f32x16 sacc, dpacc;
+  auto entry_issue = [&]() { return entry_issue_at(sel_n); };
+  auto entry_wait = [&](int& e) { asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(e) :: "memory"); };
+  // first key and number of real keys of the tile (sel_n, sub_n) whose block index was loaded; then step on
+  auto tile_of = [&](int jb_loaded, int& start, int& valid) {
+    const int jb = row_idx ? jb_loaded : sel_n;
+    const int first = jb * bkv + TT * sub_n;
+    const int n = min(TT, min(n_kv, (jb + 1) * bkv) - first);
+    const bool ok = sel_n < nsel && (unsigned)jb < (unsigned)t_n && n > 0;
+    start = ok ? first : n_kv;
+    valid = ok ? n : 0;
+    const bool wrap = sub_n + 1 == subs;
+    sub_n = wrap ? 0 : sub_n + 1;
+    sel_n += wrap ? 1 : 0;
+  };
+  constexpr int CPT = TileDma<NW>::CPT;
+  constexpr int kPerTile = 2 * CPT;   // transfers a wavefront issues per tile
+  auto fetch_tile = [&](const int slot_, const int start_v) {
+    const int first = __builtin_amdgcn_readfirstlane(start_v) * (D * 2);
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { sacc[r] = 0.0f; dpacc[r] = 0.0f; }
+    for (int j = 0; j < CPT; ++j) dma.piece_at(k_desc, sK_lds + slot_ * RTILE, j, dma.offset_of(j, first));
+#pragma unroll
+    for (int j = 0; j < CPT; ++j) dma.piece_at(v_desc, sV_lds + slot_ * RTILE, j, dma.offset_of(j, first));
+  };
+  int v1, v2, v3, e_next;   // real keys of tiles n + 1 .. n + 3
+  {
+    // the block indices of tiles 0 .. 3 in one round trip (tile t belongs to selection t / subs)
+    int st, v0;
+    int e0 = entry_issue_at(0), e1 = entry_issue_at(1 / subs), e2 = entry_issue_at(2 / subs), e3 = entry_issue_at(3 / subs);
+    entry_wait(e0);
+    entry_wait(e1);
+    entry_wait(e2);
+    entry_wait(e3);
+    tile_of(e0, st, v0); fetch_tile(0, st);
+    tile_of(e1, st, v1); fetch_tile(1, st);
+    tile_of(e2, st, v2); fetch_tile(2, st);
+    tile_of(e3, st, v3); fetch_tile(3, st);
+    e_next = entry_issue();
+    v1 = kRagged ? v1 : TT;   // (only the ragged instance looks at them)
+    (void)v0;
+    // Q, dO and the row statistics were requested before the tiles: complete once at most the tiles are in flight
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(4 * kPerTile) : "memory");
+    // dO enters negated: the dP accumulator starts at D and ends at D - dP, so that dS = (-P) (D - dP) costs one
+    // multiplication per element (the history branch below turns the sign back)
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
-      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(tK, rb, s), qf[s], sacc, 0, 0, 0);
-      dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(tV, rb, s), dof[s], dpacc, 0, 0, 0);
+      u32x4 w = __builtin_bit_cast(u32x4, dof[s]);
+      w ^= 0x80008000u;
+      dof[s] = __builtin_bit_cast(bf16x8, w);
     }
-    bf16x8 dsf[2];
-    if (valid_cur == TT) {   // uniform
+    // inside the loop Q and -dO of this wavefront's rows live in the accumulation half of the register file
 #pragma unroll
-      for (int r = 0; r < 16; ++r)
-        dsf[r >> 3][r & 7] = static_cast<__bf16>(__builtin_amdgcn_exp2f(fmaf(sacc[r], c_scale, -lse)) * (dpacc[r] - dvec));
-    } else {
-      // a tile cut short by its block's or the head's end: masked by bit operations (a select around the
-      // exponential would become a branch per element)
+    for (int s = 0; s < 8; ++s) asm volatile("" : "+a"(qf[s]), "+a"(dof[s]));
+    // (dinit: the dP accumulator's start)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = 8 * (r >> 2) + 4 * h + (r & 3);
-        const uint32_t keep = key < valid_cur ? 0xffffffffu : 0u;
-        const float p = __uint_as_float(__float_as_uint(__builtin_amdgcn_exp2f(fmaf(sacc[r], c_scale, -lse))) & keep);
-        dsf[r >> 3][r & 7] = static_cast<__bf16>(p * (dpacc[r] - dvec));
+    for (int r = 0; r < 16; ++r) dinit[r] = dvec;
+
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dq[dt][r] = 0.0f;
+
+    // The loop is pipelined over three tiles like the dK/dV kernel's (see there): a trip forms S^T and D - dP^T of
+    // tile n + 1 next to dS^T of tile n and the transposing reads of its keys, passes the barrier (tile n + 2 has
+    // landed, tile n's slot is free) and accumulates tile n into dQ^T next to the row reads of tile n + 2 and the
+    // requests for tile n + 4.  Source order is issue order.
+    f32x16 s0, p0, s1, p1;   // S^T and D - dP^T, two generations
+    bf16x8 ka[8], va_[8];    // rows of the tile whose scores come next
+    auto rows_read = [&](const int par, const int s) {
+      ka[s] = rows_frag(sK + par * RTILE, rb, s);
+      va_[s] = rows_frag(sV + par * RTILE, rb, s);
+    };
+    // a key that the part of a short block does not have starts at -inf: its probability is zero
+    auto scores = [&](const int s, const int valid, f32x16& sacc) {
+      if (s == 0 && kRagged) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[r] = (8 * (r >> 2) + 4 * h + (r & 3) >= valid) ? -INFINITY : 0.0f;
+        asm volatile("s_nop 1" : "+v"(sacc));   // (vector results, read by an MFMA the compiler does not know)
       }
+      if (s == 0 && !kRagged) mfma_zero(sacc, ka[0], qf[0]);
+      else mfma_more(sacc, ka[s], qf[s]);
+    };
+    auto grads = [&](const int s, f32x16& dpacc) {
+      if (s == 0) mfma_from(dpacc, va_[0], dof[0], dinit);
+      else mfma_more(dpacc, va_[s], dof[s]);
+    };
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(3 * kPerTile) : "memory");   // tile 0
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < 8; ++s) rows_read(0, s);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int s = 0; s < 8; ++s) { scores(s, kRagged ? v0 : TT, s0); grads(s, p0); }
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * kPerTile) : "memory");   // tile 1
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < 8; ++s) rows_read(1, s);
+    __builtin_amdgcn_sched_barrier(0);
+
+    auto tile_step = [&](const int par, f32x16& sc, f32x16& dp, f32x16& sn, f32x16& dn) {
+      // par = n mod 4 (a literal at the call sites): the slot of tile n.  sc, dp belong to tile n, sn, dn to n + 1.
+      const char* tK = sK + par * RTILE;
+      bf16x8 kt[8];          // K^T of tile n: 4 t2 + dt
+      u32x4 dsw[2];          // dS^T, two bf16 per word
+      float dse;
+      // dS^T = (-P) (D - dP) with P = 2^(c S^T - lse2), clamped to [0, 1] (an output modifier of the exponential: a
+      // real key's probability is there anyway, and a row of zeros standing in for a key past the head's end must
+      // not reach infinity, 0 * inf would follow).  The empty statements that name the results keep the vector work
+      // between the MFMAs where it is written.
+      auto ds_even = [&](const int s) {
+        dse = -__builtin_amdgcn_fmed3f(__builtin_amdgcn_exp2f(fmaf(sc[2 * s], c_scale, -lse)), 0.0f, 1.0f) * dp[2 * s];
+        asm volatile("" : "+v"(dse));
+      };
+      auto ds_odd = [&](const int s) {
+        const float dso =
+            -__builtin_amdgcn_fmed3f(__builtin_amdgcn_exp2f(fmaf(sc[2 * s + 1], c_scale, -lse)), 0.0f, 1.0f) * dp[2 * s + 1];
+        const bf16x2 dw = {static_cast<__bf16>(dse), static_cast<__bf16>(dso)};
+        uint32_t dwi = __builtin_bit_cast(uint32_t, dw);
+        asm volatile("" : "+v"(dwi));
+        dsw[s >> 2][s & 3] = dwi;
+      };
+      // ---- phase one
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        scores(s, v1, sn);
+        kt[s] = transposed_frag(tK, tb, s & 3, s >> 2);
+        ds_even(s);
+        __builtin_amdgcn_sched_barrier(0);
+        grads(s, dn);
+        ds_odd(s);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // ---- tile n + 2 visible, tile n's slot free (every transposing read of it has returned)
+      asm volatile("s_waitcnt vmcnt(%0)" :: "n"(kPerTile) : "memory");   // this wavefront's parts of tile n + 2
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      __syncthreads();
+      entry_wait(e_next);
+      int st4, v4;
+      tile_of(e_next, st4, v4);
+      e_next = entry_issue();
+      const int first = __builtin_amdgcn_readfirstlane(st4) * (D * 2);
+      v1 = v2; v2 = v3; v3 = v4;
+      // ---- phase two: tile n into the accumulators
+      const int p2 = (par + 2) % NSLOT;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {   // u = 4 t2 + dt
+        const int dt = u & 3;
+        const bf16x8 dsf = __builtin_bit_cast(bf16x8, dsw[u >> 2]);
+        if (u < 2 * CPT) {   // a piece of tile n + 4 rides along: K first, then V
+          const int j = u % CPT;
+          const int voff = dma.offset_of(j, first);
+          if (u < CPT) mfma_acc_piece(dq[dt], kt[u], dsf, dt == 0, dma.place_of(sK_lds + par * RTILE, j), voff, k_desc);
+          else mfma_acc_piece(dq[dt], kt[u], dsf, dt == 0, dma.place_of(sV_lds + par * RTILE, j), voff, v_desc);
+        } else {
+          if (dt == 0) mfma_acc<true>(dq[dt], kt[u], dsf);
+          else mfma_acc<false>(dq[dt], kt[u], dsf);
+        }
+        rows_read(p2, u);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    for (int n = 0; n < ntiles; n += 4) {   // slot numbers are literals; tiles past the list are zeros
+      tile_step(0, s0, p0, s1, p1);
+      tile_step(1, s1, p1, s0, p0);
+      tile_step(2, s0, p0, s1, p1);
+      tile_step(3, s1, p1, s0, p0);
     }
-#pragma unroll
-    for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
-        dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(transposed_frag(tK, tb, dt, t2), dsf[t2], dq[dt], 0, 0, 0);
-  };
-  for (int t = 0; t < ntiles; t += 2) {
-    tile_step(t, 0);
-    if (t + 1 >= ntiles) break;
-    tile_step(t + 1, 1);
   }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing may land in LDS once the tiles' space is reused
+  // nothing may land in LDS once the tiles' space is reused; and the last accumulating MFMAs (inline assembly: the
+  // compiler does not count wait states for them) must have written their results before these are read: the idle
+  // slots name the accumulators as operands, or the compiler moves the reads above them
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  asm volatile("s_nop 15\n\ts_nop 15" : "+a"(dq[0]), "+a"(dq[1]), "+a"(dq[2]), "+a"(dq[3]));
 
   f32x16 acc[4];   // history branch: num^T, then t^T, then the gradient itself
   if (kHist) {
@@ -353,7 +516,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
     for (int s = 0; s < 8; ++s)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) dof[s][e] = static_cast<__bf16>(static_cast<float>(dof[s][e]) * inv_den);   // dnum
+      for (int e = 0; e < 8; ++e) dof[s][e] = static_cast<__bf16>(-static_cast<float>(dof[s][e]) * inv_den);   // dnum
     const uint32_t smem_lds = (uint32_t)(uintptr_t)smem;
     for (int plane = 0; plane < 2; ++plane) {
       const i32x4 p_desc = desc_of(hist.planes + ((size_t)bh * 2 + plane) * D * D, D);
@@ -442,18 +605,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 }
 
 // ------------------------------------------------------------------------------------------ dK, dV
-// acc += A B with the accumulator pinned to the accumulation half of the register file (the compiler, left to
-// itself, keeps such accumulators in ordinary registers and shuttles others through that half).  The compiler
-// counts no wait states for inline assembly, so they are provided here: A comes from LDS reads, which it awaits as
-// for any use; C is the same accumulator's previous value, eight MFMAs back; B is a vector ALU result, and an MFMA
-// may not read one in the two issue slots after it was written: kWait = true puts two idle slots first, for the
-// first reader of a B operand.  volatile keeps the MFMAs in program order, so that the first reader stays the first.
-template <bool kWait>
-__device__ __forceinline__ void mfma_acc(f32x16& acc, const bf16x8 a, const bf16x8 b) {
-  if (kWait) asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
-  else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
-}
-
 // Launch order of the dK/dV workgroups.  A workgroup's time is proportional to the length of its KV block's list
 // of query blocks, and the lists differ (top-k selection: a binomial spread around t_m k / t_n), while a GPU takes
 // workgroups in index order as slots free up.  Longest first within every XCD's share of the items leaves the short
@@ -509,19 +660,6 @@ __global__ __launch_bounds__(1024) void dkv_order_kernel(const int32_t* __restri
       rec[1] = int4{head[q].w, 0, 0, 0};
     }
   }
-}
-
-// The same with a 1 KB transfer global -> LDS behind it (LDS address through m0, written in front of the MFMA).
-__device__ __forceinline__ void mfma_acc_piece(f32x16& acc, const bf16x8 a, const bf16x8 b, const bool wait,
-                                               const uint32_t lds, const int voff, const i32x4& desc) {
-  if (wait)
-    asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\t"
-                 "buffer_load_dwordx4 %4, %5, 0 offen lds"
-                 : "+a"(acc) : "v"(a), "v"(b), "s"(lds), "v"(voff), "s"(desc) : "memory", "m0");
-  else
-    asm volatile("s_mov_b32 m0, %3\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0\n\t"
-                 "buffer_load_dwordx4 %4, %5, 0 offen lds"
-                 : "+a"(acc) : "v"(a), "v"(b), "s"(lds), "v"(voff), "s"(desc) : "memory", "m0");
 }
 
 // One workgroup per slab of 64 keys of a KV block, two wavefronts of 32 keys each; a wavefront owns all 128
@@ -668,12 +806,6 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
   // All MFMAs of the loop are inline assembly.  The loop-invariant B operands (K and -V of this wavefront's keys) and
   // the accumulators sit in the accumulation half of the register file; S and D - dP come out in ordinary registers,
   // and their first reader is vector work a whole phase (16 MFMAs) later.
-  auto mfma_zero = [&](f32x16& acc, const bf16x8 a, const bf16x8& b) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "a"(b));
-  };
-  auto mfma_more = [&](f32x16& acc, const bf16x8 a, const bf16x8& b) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b));
-  };
   // A wavefront alone on its SIMD issues in order, one instruction per four cycles, and an MFMA keeps the matrix
   // pipeline busy for 32: everything that is not an MFMA (56 LDS reads, 10 transfers, ~70 vector instructions per
   // tile, about as many issue cycles as the 32 MFMAs take to execute) has to sit BETWEEN MFMAs or the pipeline
@@ -875,16 +1007,31 @@ int launch_bwd_mfma(const hf_config& c, const void* Q, int n_q, const void* K, c
   const long long q_items = (long long)BH * t_m;
   if (q_items > (1ll << 30)) { set_error("too many query blocks"); return HF_ERR_SHAPE; }
   const int q_per_xcd = (int)((q_items + 7) / 8);
-#define HF_LAUNCH_DQ(NWV, HM)                                                                                      \
-  hipLaunchKernelGGL((bwd_dq_mfma_kernel<NWV, HM>), dim3(8 * q_per_xcd), dim3(64 * NWV), 0, s, q, kk, v, g, idx, k, \
-                     n_q, n_kv, kvs, c.block_kv, t_m, t_n, q_per_xcd, (int)q_items, c_scale, scale, lse2, Dv, hist,   \
-                     static_cast<bf16_t*>(dQ))
+  // more than 64 KB of LDS has to be granted per kernel instance, once
+#define HF_LAUNCH_DQ3(NWV, HM, RG)                                                                                  \
+  do {                                                                                                             \
+    static bool granted = false;                                                                                   \
+    if (!granted) {                                                                                                \
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dq_mfma_kernel<NWV, HM, RG>),                      \
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kDqLds) != hipSuccess) {                 \
+        (void)hipGetLastError();                                                                                   \
+        set_error("cannot reserve %d bytes of LDS for the dQ kernel", kDqLds);                                     \
+        return HF_ERR_HIP;                                                                                         \
+      }                                                                                                            \
+      granted = true;                                                                                              \
+    }                                                                                                              \
+    hipLaunchKernelGGL((bwd_dq_mfma_kernel<NWV, HM, RG>), dim3(8 * q_per_xcd), dim3(64 * NWV), kDqLds, s, q, kk, v, \
+                       g, idx, k, n_q, n_kv, kvs, c.block_kv, t_m, t_n, q_per_xcd, (int)q_items, c_scale, scale,    \
+                       lse2, Dv, hist, static_cast<bf16_t*>(dQ));                                                  \
+  } while (0)
+#define HF_LAUNCH_DQ(NWV, HM) do { if (c.block_kv % 32) HF_LAUNCH_DQ3(NWV, HM, true); else HF_LAUNCH_DQ3(NWV, HM, false); } while (0)
   if (c.block_q == 64) {
     if (hist_mode == 0) HF_LAUNCH_DQ(2, 0); else if (hist_mode == 1) HF_LAUNCH_DQ(2, 1); else HF_LAUNCH_DQ(2, 2);
   } else {
     if (hist_mode == 0) HF_LAUNCH_DQ(4, 0); else if (hist_mode == 1) HF_LAUNCH_DQ(4, 1); else HF_LAUNCH_DQ(4, 2);
   }
 #undef HF_LAUNCH_DQ
+#undef HF_LAUNCH_DQ3
   int rc = check_launch("hf_hybrid_attn_bwd(dQ)");
   if (rc != HF_OK) return rc;
   const int slabs = (c.block_kv + 63) / 64;   // 64 keys per workgroup
