@@ -22,6 +22,7 @@
 // file, all MFMAs of their loops as inline assembly, four tile slots and a loop pipelined over three tiles; the
 // dK/dV workgroups are launched longest list first (dkv_order_kernel).
 #include <math.h>
+#include <stdlib.h>
 
 #include "hf_common.h"
 
@@ -1049,7 +1050,8 @@ int launch_bwd_mfma(const hf_config& c, const void* Q, int n_q, const void* K, c
     dkv_ready = true;
   }
   const int32_t* order = nullptr;   // equal lists (dense), or a share too long for the ordering kernel: index order
-  if (inv_cnt && dkv_order && kv_per_xcd <= kOrderMax) {
+  const char* pick = getenv("HF_DKV_ORDER");   // development switch: "0" launches in index order
+  if (inv_cnt && dkv_order && kv_per_xcd <= kOrderMax && !(pick && pick[0] == '0')) {
     hipLaunchKernelGGL(dkv_order_kernel, dim3(8), dim3(1024), 0, s, inv_cnt, inv_list, t_m, slabs, kv_per_xcd,
                        (int)kv_items, dkv_order);
     order = dkv_order;

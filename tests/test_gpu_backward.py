@@ -187,6 +187,28 @@ def test_bf16_kernel_choices_and_key_blocks_that_are_no_multiple_of_a_tile(name,
         check("dV", wl.to_f64(dV)[0, h], rv, w)
 
 
+@pytest.mark.parametrize("name", ["small_bf16", "small_b128", "step_832x480"])
+def test_launch_order_of_the_key_side_kernel_changes_no_bit(name):
+    """The dK/dV workgroups are launched longest list first, from records that also carry their first list
+    entries; in index order (development switch) every workgroup finds the same entries by itself.  A workgroup's
+    result does not depend on when it runs, so the two orders must agree bit for bit, and so must two runs."""
+    w = wl.get(name)
+    cfg = cfg_of(w)
+    Q, K, V = wl.make_qkv(w)
+    dO = wl.randn(Q.shape, 97_000, 1.0, w.torch_dtype)
+    idx, _ = select(cfg, w, Q, K)
+    a = run_bwd(cfg, w, Q, K, V, idx, None, dO)
+    b = run_bwd(cfg, w, Q, K, V, idx, None, dO)
+    os.environ["HF_DKV_ORDER"] = "0"
+    try:
+        c = run_bwd(cfg, w, Q, K, V, idx, None, dO)
+    finally:
+        os.environ.pop("HF_DKV_ORDER", None)
+    for x, y, z in zip(a[:3], b[:3], c[:3]):
+        assert torch.isfinite(x.float()).all()
+        assert torch.equal(x, y) and torch.equal(x, z)
+
+
 @pytest.mark.parametrize("n_q,n_kv,b", [(1, 1, 64), (5, 70, 64), (64, 64, 64), (129, 257, 128), (33, 100, 16),
                                         (200, 1000, 192)])
 def test_backward_ragged_and_degenerate_sizes(n_q, n_kv, b):
