@@ -456,9 +456,20 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, 1)))
         __builtin_amdgcn_sched_barrier(0);
       }
     };
-    for (int n = 0; n < ntiles; n += 4) {   // slot numbers are literals; tiles past the list are zeros
+    // slot numbers are literals, hence four trips per turn of the loop; the last one to three tiles take two or
+    // four more trips (a tile past the list is zeros)
+    const int whole = ntiles & ~3;
+    for (int n = 0; n < whole; n += 4) {
       tile_step(0, s0, p0, s1, p1);
       tile_step(1, s1, p1, s0, p0);
+      tile_step(2, s0, p0, s1, p1);
+      tile_step(3, s1, p1, s0, p0);
+    }
+    if (ntiles > whole) {
+      tile_step(0, s0, p0, s1, p1);
+      tile_step(1, s1, p1, s0, p0);
+    }
+    if (ntiles > whole + 2) {
       tile_step(2, s0, p0, s1, p1);
       tile_step(3, s1, p1, s0, p0);
     }
@@ -936,11 +947,22 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-  for (int n = 0; n < ntiles; n += 4) {   // slot numbers are literals; tiles past the list are zeros
+  // slot numbers are literals, hence four trips per turn of the loop; the last one to three tiles take two or four
+  // more trips (a tile past the list is zeros)
+  const int whole = ntiles & ~3;
+  for (int n = 0; n < whole; n += 4) {
     tile_step(n, 0, s0, p0, s1, p1);
     tile_step(n + 1, 1, s1, p1, s0, p0);
     tile_step(n + 2, 2, s0, p0, s1, p1);
     tile_step(n + 3, 3, s1, p1, s0, p0);
+  }
+  if (ntiles > whole) {
+    tile_step(whole, 0, s0, p0, s1, p1);
+    tile_step(whole + 1, 1, s1, p1, s0, p0);
+  }
+  if (ntiles > whole + 2) {
+    tile_step(whole + 2, 2, s0, p0, s1, p1);
+    tile_step(whole + 3, 3, s1, p1, s0, p0);
   }
   // (the idle slots name the accumulators as operands, or the compiler moves the reads above them)
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
