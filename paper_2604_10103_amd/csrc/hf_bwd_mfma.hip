@@ -482,6 +482,17 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, 1)))
 
   f32x16 acc[4];   // history branch: num^T, then t^T, then the gradient itself
   if (kHist) {
+    // both planes of the state go global -> LDS like the tiles (four pieces of 32 rows each, no registers in
+    // between) into the tiles' space, requested here so that they travel under the arithmetic below
+    static_assert(8 * RTILE <= kDqLds, "two state planes must fit in the tiles' space");
+    const uint32_t smem_lds = (uint32_t)(uintptr_t)smem;
+    __syncthreads();   // the tiles are consumed
+#pragma unroll
+    for (int plane = 0; plane < 2; ++plane) {
+      const i32x4 p_desc = desc_of(hist.planes + ((size_t)bh * 2 + plane) * D * D, D);
+#pragma unroll
+      for (int part = 0; part < 4; ++part) dma.fetch(p_desc, smem_lds + (4 * plane + part) * RTILE, 32 * part);
+    }
     bf16x8 hq[8];
     if (kHist == 2) {
       row_frags(rsrc_of(hist.q_hist + (size_t)bh * n_q * D, n_q), q_row, h, hq);
@@ -523,20 +534,15 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, 1)))
     }
     const float inv_den = 1.0f / den;
 
-    // a plane goes global -> LDS like the tiles (four pieces of 32 rows, no registers in between)
     float dden = 0.0f;
 #pragma unroll
     for (int s = 0; s < 8; ++s)
 #pragma unroll
       for (int e = 0; e < 8; ++e) dof[s][e] = static_cast<__bf16>(-static_cast<float>(dof[s][e]) * inv_den);   // dnum
-    const uint32_t smem_lds = (uint32_t)(uintptr_t)smem;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wavefront's pieces of both planes
+    __syncthreads();
     for (int plane = 0; plane < 2; ++plane) {
-      const i32x4 p_desc = desc_of(hist.planes + ((size_t)bh * 2 + plane) * D * D, D);
-      __syncthreads();   // the tiles, or the previous plane, are consumed
-#pragma unroll
-      for (int part = 0; part < 4; ++part) dma.fetch(p_desc, smem_lds + part * RTILE, 32 * part);
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      __syncthreads();
+      const char* sP = smem + 4 * plane * RTILE;
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
@@ -545,7 +551,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, 1)))
       for (int s = 0; s < 8; ++s)
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) {
-          acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(smem + dt * RTILE, rb, s), plane ? dof[s] : hq[s],
+          acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(sP + dt * RTILE, rb, s), plane ? dof[s] : hq[s],
                                                             acc[dt], 0, 0, 0);
         }
       if (plane == 0) {
