@@ -44,6 +44,9 @@ def parse():
     p.add_argument("--no-dense", action="store_true",
                    help="skip the dense comparator launches (they share the sparse kernel's name in a profile)")
     p.add_argument("--no-backward", action="store_true", help="skip the timing of the backward pass (training step)")
+    p.add_argument("--converted-planes", action="store_true",
+                   help="let every attention call convert the state to its bf16 planes (hf_hybrid_attn_fwd) instead "
+                        "of keeping them next to the state (hf_absorb_evicted_planes / hf_hybrid_attn_fwd_planes)")
     p.add_argument("--eager", action="store_true",
                    help="time eager single-stream launches instead of one captured HIP graph per step")
     p.add_argument("--cpu-heads", type=int, default=0, help="heads per layer the oracle is timed on (0 = all)")
@@ -97,6 +100,7 @@ def main():
     ws_bytes = hf.hf_workspace_bytes(cfg, w.n_q, w.n_kv)
     aws_bytes = hf.hf_absorb_workspace_bytes(cfg, w.n_q)
     aws = torch.empty(aws_bytes, dtype=torch.uint8, device=dev) if aws_bytes else None
+    keep_planes = (not a.converted_planes) and hf.hf_state_planes_bytes(cfg) > 0
     for l in range(nl):
         Q, K, V = wl.make_qkv(w, layer=l)
         Ke, Ve = wl.make_evicted(w, 100 + l)
@@ -104,8 +108,12 @@ def main():
         hf.hf_state_init(cfg, st)
         for (pk, pv) in prefill:
             hf.hf_absorb_evicted(cfg, st, pk, pv, workspace=aws)
+        planes = None
+        if keep_planes:   # the bf16 planes of the state, kept current by the absorb call from here on
+            planes = torch.empty(hf.hf_state_planes_bytes(cfg), dtype=torch.uint8, device=dev)
+            hf.hf_state_planes(cfg, st, planes)
         sets.append(dict(
-            Q=Q.to(dev), K=K.to(dev), V=V.to(dev), Ke=Ke.to(dev), Ve=Ve.to(dev), st=st,
+            Q=Q.to(dev), K=K.to(dev), V=V.to(dev), Ke=Ke.to(dev), Ve=Ve.to(dev), st=st, planes=planes,
             idx=torch.empty((w.batch, w.heads, w.t_m, k), dtype=torch.int32, device=dev),
             O=torch.empty(Q.shape, dtype=Q.dtype, device=dev),
             ws=torch.empty(ws_bytes, dtype=torch.uint8, device=dev), Qc=Q, Kc=K, Vc=V))
@@ -125,10 +133,16 @@ def main():
         hf.hf_block_select(cfg, s["Q"], s["K"], s["idx"], None, s["ws"])
         if events is not None:
             events[1].record()
-        hf.hf_hybrid_attn_fwd(cfg, s["Q"], s["K"], s["V"], s["idx"], s["st"], s["O"], s["ws"], rq[0], rq[1])
+        if keep_planes:
+            hf.hf_hybrid_attn_fwd_planes(cfg, s["Q"], s["K"], s["V"], s["idx"], s["st"], s["planes"], s["O"], rq[0], rq[1])
+        else:
+            hf.hf_hybrid_attn_fwd(cfg, s["Q"], s["K"], s["V"], s["idx"], s["st"], s["O"], s["ws"], rq[0], rq[1])
         if events is not None:
             events[2].record()
-        hf.hf_absorb_evicted(cfg, s["st"], s["Ke"], s["Ve"], re_[0], re_[1], workspace=aws)
+        if keep_planes:
+            hf.hf_absorb_evicted_planes(cfg, s["st"], s["Ke"], s["Ve"], s["planes"], re_[0], re_[1], workspace=aws)
+        else:
+            hf.hf_absorb_evicted(cfg, s["st"], s["Ke"], s["Ve"], re_[0], re_[1], workspace=aws)
         if events is not None:
             events[3].record()
 
@@ -290,7 +304,7 @@ def main():
         "config": {"workload": w.name, "batch": w.batch, "heads": w.heads, "head_dim": w.head_dim,
                    "n_q": w.n_q, "n_kv": w.n_kv, "block": w.block, "keep_ratio": keep, "k": k,
                    "t_n": w.t_n, "evicted_tokens_in_state": w.n_evicted, "rotated_layer_sets": nl,
-                   "history_rope": bool(a.rope)},
+                   "history_rope": bool(a.rope), "state_planes": "kept by the absorb call" if keep_planes else "converted per attention call"},
         "roofline": {"kernel": "sparse flash forward (Eq. 5)", "bound": "mfma", "achieved": a4_tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": a4_tflops / PEAK_BF16_TFLOPS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if a.keep_ratio is None else None,

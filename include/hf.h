@@ -119,6 +119,29 @@ HF_API int hf_absorb_evicted(const hf_config* cfg, void* state,
                       const float* rope_cos, const float* rope_sin,
                       void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- The state's bf16 planes, kept by the caller (bf16, head_dim 128, block_q 64 or 128 only) ----------
+ * The history term of Eq. 3 is evaluated on the matrix cores from two bf16 planes of L (high part and
+ * remainder, transposed).  hf_hybrid_attn_fwd derives them from the state on every call; the state changes
+ * only when tokens are absorbed (Eq. 2), so a caller may keep the planes next to the state instead:
+ * hf_absorb_evicted_planes writes them from the kernel that writes the state, hf_hybrid_attn_fwd_planes
+ * reads them.  Outputs are bit-identical to the ordinary calls.  The caller owns the buffer and the
+ * invariant: whatever else writes the state (hf_state_init, hf_state_fold_linear, hf_window_evict, a
+ * copy) must be followed by hf_state_planes before the planes are used again. */
+
+/* Bytes of the planes buffer (0 for configurations without this path).  Host-only. */
+HF_API int hf_state_planes_bytes(const hf_config* cfg, size_t* bytes_out);
+
+/* planes_out (device, 256-byte aligned, hf_state_planes_bytes bytes) = the planes of state (read-only). */
+HF_API int hf_state_planes(const hf_config* cfg, const void* state, void* planes_out, void* stream);
+
+/* hf_absorb_evicted (Eq. 2; every argument as there) that also writes the planes of the UPDATED state into
+ * planes_out.  With a workspace they leave the kernel that sums the slices; without, a conversion launch
+ * follows the atomics. */
+HF_API int hf_absorb_evicted_planes(const hf_config* cfg, void* state,
+                      const void* K_ev, const void* V_ev, int32_t n_tokens,
+                      const float* rope_cos, const float* rope_sin,
+                      void* workspace, size_t workspace_bytes, void* planes_out, void* stream);
+
 /* Cache eviction of the inference algorithm of the supplement ("pop(0)" of the KV cache followed by
  * the update of the linear state) on the window buffers themselves: the oldest n_evict tokens of
  * K_win, V_win [B, H, n_kv, d] are absorbed into the state exactly as hf_absorb_evicted does
@@ -230,6 +253,17 @@ HF_API int hf_hybrid_attn_fwd_split(const hf_config* cfg, const void* Q_local, c
                        const void* state_or_null,
                        const float* rope_cos_q, const float* rope_sin_q,
                        void* O, void* workspace, size_t workspace_bytes, void* stream);
+
+/* hf_hybrid_attn_fwd_split (Eq. 5 + Eq. 3 + Eq. 6; every argument as there, Q_hist NULL = Q_local) with the
+ * state's planes supplied by the caller (see hf_state_planes above): state must not be NULL, planes must
+ * be the planes of exactly this state; no workspace is needed.  HF_ERR_SHAPE for configurations without
+ * this path. */
+HF_API int hf_hybrid_attn_fwd_planes(const hf_config* cfg, const void* Q_local, const void* Q_hist, int32_t n_q,
+                       const void* K_win, const void* V_win, int32_t n_kv,
+                       const int32_t* block_idx, int32_t k,
+                       const void* state, const void* planes,
+                       const float* rope_cos_q, const float* rope_sin_q,
+                       void* O, void* stream);
 
 /* ---- Backward pass (training algorithm of the supplement) ------------------------------------------- */
 

@@ -81,6 +81,10 @@ def load():
     lib.hf_state_fold_linear.argtypes = [CP, P, P, P, P]
     lib.hf_absorb_evicted.argtypes = [CP, P, P, P, I, P, P, P, SZ, P]
     lib.hf_absorb_workspace_bytes.argtypes = [CP, I, ctypes.POINTER(SZ)]
+    lib.hf_state_planes_bytes.argtypes = [CP, ctypes.POINTER(SZ)]
+    lib.hf_state_planes.argtypes = [CP, P, P, P]
+    lib.hf_absorb_evicted_planes.argtypes = [CP, P, P, P, I, P, P, P, SZ, P, P]
+    lib.hf_hybrid_attn_fwd_planes.argtypes = [CP, P, P, I, P, P, I, P, I, P, P, P, P, P, P]
     lib.hf_window_advance.argtypes = [CP, P, P, I, I, P, P, P, P, SZ, P]
     lib.hf_window_evict.argtypes = [CP, P, P, I, I, I, P, P, P, P, SZ, P]
     WP = ctypes.POINTER(hf_window)
@@ -103,7 +107,8 @@ def load():
                  "hf_workspace_bytes",
                  "hf_block_select", "hf_block_select_cached", "hf_hybrid_attn_fwd", "hf_hybrid_attn_fwd_split",
                  "hf_rope_window_indices", "hf_rope_tables", "hf_rope_apply", "hf_window_evict", "hf_stream_open_chunk",
-                 "hf_stream_step", "hf_bwd_workspace_bytes", "hf_hybrid_attn_bwd"):
+                 "hf_stream_step", "hf_bwd_workspace_bytes", "hf_hybrid_attn_bwd", "hf_state_planes_bytes",
+                 "hf_state_planes", "hf_absorb_evicted_planes", "hf_hybrid_attn_fwd_planes"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -230,6 +235,38 @@ def hf_absorb_evicted(cfg: hf_config, state, K_ev, V_ev, rope_cos=None, rope_sin
         _dev(workspace, "workspace", torch.uint8), 0 if workspace is None else workspace.numel(), _stream()))
 
 
+def hf_state_planes_bytes(cfg: hf_config) -> int:
+    """Bytes of the caller-kept bf16 planes of the state (0: the configuration has no such path)."""
+    out = ctypes.c_size_t(0)
+    _check(load().hf_state_planes_bytes(ctypes.byref(cfg), ctypes.byref(out)))
+    return out.value
+
+
+def hf_state_planes(cfg: hf_config, state, planes_out) -> None:
+    """planes_out (uint8 GPU buffer of hf_state_planes_bytes(cfg) bytes) = the bf16 planes of state."""
+    n = hf_state_bytes(cfg) // 4
+    _check(load().hf_state_planes(ctypes.byref(cfg), _dev(state, "state", torch.float32, (n,)),
+                                  _dev(planes_out, "planes_out", torch.uint8), _stream()))
+
+
+def hf_absorb_evicted_planes(cfg: hf_config, state, K_ev, V_ev, planes_out, rope_cos=None, rope_sin=None,
+                             workspace=None) -> None:
+    """hf_absorb_evicted that also writes the planes of the updated state into planes_out."""
+    n = hf_state_bytes(cfg) // 4
+    B, H, d = cfg.batch, cfg.heads, cfg.head_dim
+    if K_ev.dim() != 4:
+        raise ValueError("K_ev must be [B, H, n, d]")
+    nt = K_ev.shape[2]
+    shp = (B, H, nt, d)
+    tab = (nt, d // 2)
+    _check(load().hf_absorb_evicted_planes(
+        ctypes.byref(cfg), _dev(state, "state", torch.float32, (n,)),
+        _dev(K_ev, "K_ev", _tdtype(cfg), shp), _dev(V_ev, "V_ev", _tdtype(cfg), shp), nt,
+        _dev(rope_cos, "rope_cos", torch.float32, tab), _dev(rope_sin, "rope_sin", torch.float32, tab),
+        _dev(workspace, "workspace", torch.uint8), 0 if workspace is None else workspace.numel(),
+        _dev(planes_out, "planes_out", torch.uint8), _stream()))
+
+
 def hf_block_select(cfg: hf_config, Q, K_win, block_idx, scores=None, workspace=None, n_kv=None) -> None:
     """block_idx: int32 [B,H,T_m,k] out; scores: optional fp32 [B,H,T_m,T_n] out; workspace: uint8 buffer."""
     hf_block_select_cached(cfg, Q, K_win, 0, block_idx, scores, workspace, _entry="hf_block_select", n_kv=n_kv)
@@ -278,6 +315,30 @@ def hf_hybrid_attn_fwd(cfg: hf_config, Q, K_win, V_win, block_idx, state, O, wor
         _dev(rope_cos_q, "rope_cos_q", torch.float32, tab), _dev(rope_sin_q, "rope_sin_q", torch.float32, tab),
         _dev(O, "O", _tdtype(cfg), (B, H, n_q, d)),
         _dev(workspace, "workspace", torch.uint8), 0 if workspace is None else workspace.numel(), _stream()))
+
+
+def hf_hybrid_attn_fwd_planes(cfg: hf_config, Q, K_win, V_win, block_idx, state, planes, O, rope_cos_q=None,
+                              rope_sin_q=None, Q_hist=None, n_kv=None) -> None:
+    """hf_hybrid_attn_fwd with the state's planes kept by the caller (hf_absorb_evicted_planes /
+    hf_state_planes): no workspace, no conversion launch."""
+    B, H, d = cfg.batch, cfg.heads, cfg.head_dim
+    n_q, n_kv = Q.shape[2], _kv_len(cfg, K_win, n_kv)
+    t_m = _cdiv(n_q, cfg.block_q)
+    k = 0
+    if block_idx is not None:
+        if block_idx.dim() != 4:
+            raise ValueError("block_idx must be [B, H, T_m, k]")
+        k = block_idx.shape[3]
+    tab = (n_q, d // 2)
+    qs = (B, H, n_q, d)
+    _check(load().hf_hybrid_attn_fwd_planes(
+        ctypes.byref(cfg), _dev(Q, "Q", _tdtype(cfg), qs), _dev(Q_hist, "Q_hist", _tdtype(cfg), qs), n_q,
+        _dev(K_win, "K_win", _tdtype(cfg), (B, H, K_win.shape[2], d)),
+        _dev(V_win, "V_win", _tdtype(cfg), (B, H, K_win.shape[2], d)), n_kv,
+        _dev(block_idx, "block_idx", torch.int32, (B, H, t_m, k)), k,
+        _dev(state, "state", torch.float32, (hf_state_bytes(cfg) // 4,)), _dev(planes, "planes", torch.uint8),
+        _dev(rope_cos_q, "rope_cos_q", torch.float32, tab), _dev(rope_sin_q, "rope_sin_q", torch.float32, tab),
+        _dev(O, "O", _tdtype(cfg), qs), _stream()))
 
 
 def hf_hybrid_attn_fwd_save(cfg: hf_config, Q, K_win, V_win, block_idx, state, O, O_local_out, lse2_out, workspace=None,

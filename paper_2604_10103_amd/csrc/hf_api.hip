@@ -169,9 +169,52 @@ int hf_absorb_workspace_bytes(const hf_config* cfg, int32_t n_tokens, size_t* by
   return HF_OK;
 }
 
+static int check_planes_cfg(const hf_config* cfg, const void* planes, const char* what) {
+  if (!attn_mfma_fused_supported(*cfg)) {
+    set_error("state planes exist for bf16, head_dim 128, block_q 64 or 128 only (elsewhere the attention call converts)");
+    return HF_ERR_SHAPE;
+  }
+  HF_TRY(check_ptr(planes, what, true));
+  if (reinterpret_cast<uintptr_t>(planes) & 255u) { set_error("%s is not 256-byte aligned", what); return HF_ERR_ALIGN; }
+  return HF_OK;
+}
+
+int hf_state_planes_bytes(const hf_config* cfg, size_t* bytes_out) {
+  HF_TRY(check_cfg(cfg));
+  if (!bytes_out) { set_error("bytes_out is NULL"); return HF_ERR_NULL; }
+  *bytes_out = attn_mfma_fused_supported(*cfg) ? readout_planes_bytes(*cfg) : 0;
+  return HF_OK;
+}
+
+int hf_state_planes(const hf_config* cfg, const void* state, void* planes_out, void* stream) {
+  HF_TRY(check_cfg(cfg));
+  HF_TRY(check_ptr(state, "state", true));
+  HF_TRY(check_planes_cfg(cfg, planes_out, "planes_out"));
+  return launch_state_planes(*cfg, static_cast<const float*>(state), planes_out, static_cast<hipStream_t>(stream));
+}
+
+static int absorb_impl(const hf_config* cfg, void* state, const void* K_ev, const void* V_ev, int32_t n_tokens,
+                       const float* rope_cos, const float* rope_sin, void* workspace, size_t workspace_bytes,
+                       void* planes_out, void* stream);
+
 int hf_absorb_evicted(const hf_config* cfg, void* state, const void* K_ev, const void* V_ev,
                       int32_t n_tokens, const float* rope_cos, const float* rope_sin, void* workspace,
                       size_t workspace_bytes, void* stream) {
+  return absorb_impl(cfg, state, K_ev, V_ev, n_tokens, rope_cos, rope_sin, workspace, workspace_bytes, nullptr, stream);
+}
+
+int hf_absorb_evicted_planes(const hf_config* cfg, void* state, const void* K_ev, const void* V_ev,
+                             int32_t n_tokens, const float* rope_cos, const float* rope_sin, void* workspace,
+                             size_t workspace_bytes, void* planes_out, void* stream) {
+  HF_TRY(check_cfg(cfg));
+  HF_TRY(check_planes_cfg(cfg, planes_out, "planes_out"));
+  if (planes_out == state || planes_out == workspace) { set_error("planes_out aliases another argument"); return HF_ERR_SHAPE; }
+  return absorb_impl(cfg, state, K_ev, V_ev, n_tokens, rope_cos, rope_sin, workspace, workspace_bytes, planes_out, stream);
+}
+
+static int absorb_impl(const hf_config* cfg, void* state, const void* K_ev, const void* V_ev, int32_t n_tokens,
+                       const float* rope_cos, const float* rope_sin, void* workspace, size_t workspace_bytes,
+                       void* planes_out, void* stream) {
   HF_TRY(check_cfg(cfg));
   HF_TRY(check_ptr(state, "state", true));
   HF_TRY(check_ptr(K_ev, "K_ev", true));
@@ -188,7 +231,7 @@ int hf_absorb_evicted(const hf_config* cfg, void* state, const void* K_ev, const
     return HF_ERR_ALIGN;
   }
   return launch_absorb(*cfg, static_cast<float*>(state), K_ev, V_ev, n_tokens, n_tokens, rope_cos, rope_sin,
-                       workspace, workspace ? workspace_bytes : 0, static_cast<hipStream_t>(stream));
+                       workspace, workspace ? workspace_bytes : 0, static_cast<hipStream_t>(stream), planes_out);
 }
 
 int hf_window_advance(const hf_config* cfg, void* K_win, void* V_win, int32_t n_kv, int32_t n_evict, void* state,
@@ -310,7 +353,8 @@ int hf_hybrid_attn_fwd(const hf_config* cfg, const void* Q, int32_t n_q, const v
 static int fwd_impl(const hf_config* cfg, const void* Q, const void* Q_hist, int32_t n_q, const void* K_win,
                     const void* V_win, int32_t n_kv, const int32_t* block_idx, int32_t k, const void* state_or_null,
                     const float* rope_cos_q, const float* rope_sin_q, void* O, bool save, void* O_local_out,
-                    float* lse2_out, void* workspace, size_t workspace_bytes, void* stream);
+                    float* lse2_out, void* workspace, size_t workspace_bytes, void* stream,
+                    const void* planes_in = nullptr);
 
 int hf_hybrid_attn_fwd_split(const hf_config* cfg, const void* Q, const void* Q_hist, int32_t n_q,
                              const void* K_win, const void* V_win, int32_t n_kv, const int32_t* block_idx,
@@ -319,6 +363,18 @@ int hf_hybrid_attn_fwd_split(const hf_config* cfg, const void* Q, const void* Q_
                              void* stream) {
   return fwd_impl(cfg, Q, Q_hist, n_q, K_win, V_win, n_kv, block_idx, k, state_or_null, rope_cos_q, rope_sin_q, O,
                   false, nullptr, nullptr, workspace, workspace_bytes, stream);
+}
+
+int hf_hybrid_attn_fwd_planes(const hf_config* cfg, const void* Q, const void* Q_hist, int32_t n_q,
+                              const void* K_win, const void* V_win, int32_t n_kv, const int32_t* block_idx,
+                              int32_t k, const void* state, const void* planes, const float* rope_cos_q,
+                              const float* rope_sin_q, void* O, void* stream) {
+  HF_TRY(check_cfg(cfg));
+  HF_TRY(check_ptr(state, "state", true));
+  HF_TRY(check_planes_cfg(cfg, planes, "planes"));
+  if (planes == O) { set_error("planes aliases O"); return HF_ERR_SHAPE; }
+  return fwd_impl(cfg, Q, Q_hist, n_q, K_win, V_win, n_kv, block_idx, k, state, rope_cos_q, rope_sin_q, O, false,
+                  nullptr, nullptr, nullptr, 0, stream, planes);
 }
 
 int hf_hybrid_attn_fwd_save(const hf_config* cfg, const void* Q, const void* Q_hist, int32_t n_q,
@@ -333,7 +389,7 @@ int hf_hybrid_attn_fwd_save(const hf_config* cfg, const void* Q, const void* Q_h
 static int fwd_impl(const hf_config* cfg, const void* Q, const void* Q_hist, int32_t n_q, const void* K_win,
                     const void* V_win, int32_t n_kv, const int32_t* block_idx, int32_t k, const void* state_or_null,
                     const float* rope_cos_q, const float* rope_sin_q, void* O, bool save, void* O_local_out,
-                    float* lse2_out, void* workspace, size_t workspace_bytes, void* stream) {
+                    float* lse2_out, void* workspace, size_t workspace_bytes, void* stream, const void* planes_in) {
   HF_TRY(check_cfg(cfg));
   if (save) {
     HF_TRY(check_ptr(O_local_out, "O_local_out", true));
@@ -383,6 +439,13 @@ static int fwd_impl(const hf_config* cfg, const void* Q, const void* Q_hist, int
       return HF_ERR_HIP;
     }
     return HF_OK;
+  }
+  if (planes_in) {
+    // the caller keeps the bf16 planes of the state (hf_absorb_evicted_planes): nothing to convert, no workspace
+    const float* st = static_cast<const float*>(state_or_null);
+    const size_t d = cfg->head_dim;
+    return launch_attn_mfma_fused(*cfg, Q, n_q, K_win, V_win, n_kv, block_idx, k, planes_in,
+                                  st + (size_t)cfg->batch * cfg->heads * d * d, rope_cos_q, rope_sin_q, Q_hist, O, s);
   }
   const WorkspaceLayout w = workspace_layout(cfg, n_q, n_kv);
   if (!workspace || workspace_bytes < w.total) {

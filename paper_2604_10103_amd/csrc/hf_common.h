@@ -85,7 +85,7 @@ int launch_fill_zero(float* p, size_t n, hipStream_t s);
 int launch_fold_linear(const hf_config& c, const float* state_in, const float* W, float* state_out, hipStream_t s);
 int launch_absorb(const hf_config& c, float* state, const void* K, const void* V, int n, int head_stride,
                   const float* cosv, const float* sinv, void* workspace, size_t workspace_bytes,
-                  hipStream_t s);
+                  hipStream_t s, void* planes_out = nullptr);
 int launch_window_shift(const hf_config& c, void* K, void* V, int n_kv, int first, int n_evict, hipStream_t s);
 size_t absorb_workspace_bytes(const hf_config& c, int n);
 int launch_pool_both(const hf_config& c, const void* Q, int n_q, int t_m, const void* K, int n_kv, int t_n,

@@ -165,7 +165,7 @@ static int launch_absorb_fma(const hf_config& c, float* state, const void* K, co
 
 int launch_absorb_mfma(const hf_config& c, float* state, const void* K, const void* V, int n, int head_stride,
                        const float* cosv, const float* sinv, void* workspace, size_t workspace_bytes,
-                       hipStream_t s);  // hf_state_mfma.hip
+                       hipStream_t s, void* planes_out);  // hf_state_mfma.hip
 size_t absorb_mfma_workspace_bytes(const hf_config& c, int n);
 
 static bool absorb_uses_mfma(const hf_config& c) { return c.dtype == HF_BF16 && c.head_dim == 128; }
@@ -174,15 +174,16 @@ size_t absorb_workspace_bytes(const hf_config& c, int n) {
   return absorb_uses_mfma(c) ? absorb_mfma_workspace_bytes(c, n) : 0;
 }
 
+// planes_out != NULL (bf16, head_dim 128 only; the caller checks): the bf16 planes of the updated state as well
 int launch_absorb(const hf_config& c, float* state, const void* K, const void* V, int n, int head_stride,
                   const float* cosv, const float* sinv, void* workspace, size_t workspace_bytes,
-                  hipStream_t s) {
+                  hipStream_t s, void* planes_out) {
   if (c.dtype == HF_F32) {
     return c.head_dim == 128 ? launch_absorb_fma<float, 128>(c, state, K, V, n, head_stride, cosv, sinv, s)
                              : launch_absorb_fma<float, 64>(c, state, K, V, n, head_stride, cosv, sinv, s);
   }
   if (absorb_uses_mfma(c))
-    return launch_absorb_mfma(c, state, K, V, n, head_stride, cosv, sinv, workspace, workspace_bytes, s);
+    return launch_absorb_mfma(c, state, K, V, n, head_stride, cosv, sinv, workspace, workspace_bytes, s, planes_out);
   return launch_absorb_fma<bf16_t, 64>(c, state, K, V, n, head_stride, cosv, sinv, s);
 }
 

@@ -384,13 +384,17 @@ __global__ __launch_bounds__(NT, 1) void absorb_dma_kernel(float* __restrict__ p
   if ((wave & 1) == 0 && h == 0) L[D * D + 32 * mi0 + l32] = zacc;   // one of the two wavefronts of a key tile
 }
 
-// state += sum over slices of the partials; one thread per 4 consecutive floats of a partial
+// state += sum over slices of the partials; one thread per 4 consecutive floats of a partial.
+// planes != NULL: the updated L also leaves as the two transposed bf16 planes (high part and remainder,
+// planes[bh][plane][j][i]) that the attention kernel's history epilogue multiplies with: the conversion rides
+// in the kernel that produces the state instead of running as a launch of its own before every attention call.
 __global__ __launch_bounds__(256) void absorb_reduce_kernel(float* __restrict__ state,
                                                             const float* __restrict__ partials, int slices,
-                                                            int BH) {
+                                                            int BH, bf16_t* __restrict__ planes) {
+  __shared__ float tile[8][D + 1];   // the block's 8 rows of L, for the transposed write
   const int e4 = blockIdx.x * 256 + threadIdx.x;  // float4 index inside a partial
   const int bh = blockIdx.y;
-  if (e4 >= PART / 4) return;
+  if (e4 >= PART / 4) return;   // (only in the block of z, which takes no part in the planes)
   const float4* p = reinterpret_cast<const float4*>(partials + (size_t)bh * slices * PART) + e4;
   float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
   int sl = 0;
@@ -411,6 +415,25 @@ __global__ __launch_bounds__(256) void absorb_reduce_kernel(float* __restrict__ 
   float4 cur = *reinterpret_cast<float4*>(dst);
   cur.x += s.x; cur.y += s.y; cur.z += s.z; cur.w += s.w;
   *reinterpret_cast<float4*>(dst) = cur;
+  if (planes == nullptr || e >= D * D) return;   // uniform over a block: a block holds 8 whole rows of L, or z
+  {
+    const int r = threadIdx.x >> 5, c0 = 4 * (threadIdx.x & 31);
+    tile[r][c0] = cur.x; tile[r][c0 + 1] = cur.y; tile[r][c0 + 2] = cur.z; tile[r][c0 + 3] = cur.w;
+  }
+  __syncthreads();
+  const int j = threadIdx.x & (D - 1), half = threadIdx.x >> 7;   // column j, rows 4 half .. + 4 of the block
+  const int i0 = 8 * blockIdx.x + 4 * half;
+  uint32_t hw[2], lw[2];
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const float v0 = tile[4 * half + 2 * q][j], v1 = tile[4 * half + 2 * q + 1][j];
+    const bf16_t h0 = f32_to_bf16(v0), h1 = f32_to_bf16(v1);
+    hw[q] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+    lw[q] = (uint32_t)f32_to_bf16(v0 - bf16_to_f32(h0)) | ((uint32_t)f32_to_bf16(v1 - bf16_to_f32(h1)) << 16);
+  }
+  bf16_t* hi = planes + (size_t)bh * 2 * D * D + (size_t)j * D + i0;
+  *reinterpret_cast<uint2*>(hi) = make_uint2(hw[0], hw[1]);
+  *reinterpret_cast<uint2*>(hi + D * D) = make_uint2(lw[0], lw[1]);
 }
 
 int env_int(const char* name, int dflt) {
@@ -457,8 +480,9 @@ size_t absorb_mfma_workspace_bytes(const hf_config& c, int n) {
 
 int launch_absorb_mfma(const hf_config& c, float* state, const void* K, const void* V, int n, int head_stride,
                        const float* cosv, const float* sinv, void* workspace, size_t workspace_bytes,
-                       hipStream_t s) {
+                       hipStream_t s, void* planes_out) {
   const int BH = c.batch * c.heads;
+  bf16_t* planes = static_cast<bf16_t*>(planes_out);   // NULL: the state alone
   const bool use_ws = workspace != nullptr && workspace_bytes >= absorb_mfma_workspace_bytes(c, n);
   const bool plain = (c.phi == HF_PHI_RELU) && cosv == nullptr;
   const char* old = getenv("HF_ABSORB_KERNEL");   // development switch: "r" keeps the register-staged kernel
@@ -484,7 +508,7 @@ int launch_absorb_mfma(const hf_config& c, float* state, const void* K, const vo
     const int rc2 = check_launch("hf_absorb_evicted");
     if (rc2 != HF_OK) return rc2;
     hipLaunchKernelGGL(absorb_reduce_kernel, dim3((PART / 4 + 255) / 256, BH), dim3(256), 0, s, state, partials,
-                       slices, BH);
+                       slices, BH, planes);
     return check_launch("hf_absorb_evicted(reduce)");
   }
   const int heads_per_xcd = (BH + 7) / 8;
@@ -497,9 +521,10 @@ int launch_absorb_mfma(const hf_config& c, float* state, const void* K, const vo
                        sinv, c.phi, BH, slices);
   }
   const int rc = check_launch("hf_absorb_evicted");
-  if (rc != HF_OK || !use_ws) return rc;
+  if (rc != HF_OK) return rc;
+  if (!use_ws) return planes ? launch_state_planes(c, state, planes, s) : HF_OK;   // (atomics: no reduce kernel)
   hipLaunchKernelGGL(absorb_reduce_kernel, dim3((PART / 4 + 255) / 256, BH), dim3(256), 0, s, state, partials,
-                     slices, BH);
+                     slices, BH, planes);
   return check_launch("hf_absorb_evicted(reduce)");
 }
 

@@ -239,3 +239,32 @@ def test_saving_forward_and_saved_backward_reject_bad_arguments(lib):
         assert lib.hf_hybrid_attn_bwd_saved(co, Q, None, 100, K, V, 200, None, 0, None, None, None, dO, Ol, lse, dQ, None,
                                             dK, dV, *ok_tail) == -2
         assert b"hf_hybrid_attn_bwd" in lib.hf_last_error() or b"recomput" in lib.hf_last_error()
+
+
+def test_kept_planes_entry_points_reject_bad_arguments():
+    """Argument checks of the calls that keep the state's bf16 planes with the caller (no GPU needed)."""
+    import ctypes
+    lib = hf.load()
+    cfg32 = hf.make_config(1, 2, 64, "f32", 16, 16, 0.25)
+    assert hf.hf_state_planes_bytes(cfg32) == 0
+    cfg = hf.make_config(1, 12, 128, "bf16", 64, 64, 0.25)
+    assert hf.hf_state_planes_bytes(cfg) == 12 * 2 * 128 * 128 * 2
+    out = ctypes.c_size_t(0)
+    assert lib.hf_state_planes_bytes(None, ctypes.byref(out)) != 0
+    assert lib.hf_state_planes_bytes(ctypes.byref(cfg), None) != 0
+    fake = ctypes.c_void_p(0x1000)
+    # unsupported configuration, NULL planes, misaligned planes
+    assert lib.hf_state_planes(ctypes.byref(cfg32), fake, fake, None) != 0
+    assert lib.hf_state_planes(ctypes.byref(cfg), fake, None, None) != 0
+    assert b"planes_out" in lib.hf_last_error()
+    assert lib.hf_state_planes(ctypes.byref(cfg), fake, ctypes.c_void_p(0x1010), None) != 0
+    assert b"aligned" in lib.hf_last_error()
+    assert lib.hf_absorb_evicted_planes(ctypes.byref(cfg), fake, fake, fake, 64, None, None, None, 0, None, None) != 0
+    assert lib.hf_absorb_evicted_planes(ctypes.byref(cfg), fake, fake, fake, 64, None, None, None, 0, fake, None) != 0
+    assert b"alias" in lib.hf_last_error()
+    assert lib.hf_hybrid_attn_fwd_planes(ctypes.byref(cfg), fake, None, 64, fake, fake, 64, None, 0, None, fake,
+                                         None, None, fake, None) != 0
+    assert b"state" in lib.hf_last_error()
+    assert lib.hf_hybrid_attn_fwd_planes(ctypes.byref(cfg32), fake, None, 64, fake, fake, 64, None, 0, fake, fake,
+                                         None, None, fake, None) != 0
+
