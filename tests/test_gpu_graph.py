@@ -1,4 +1,5 @@
-"""The whole step as a captured HIP graph, the way bench.py launches it, and a two-stream variant
+"""The whole step as a captured HIP graph (the ordinary calls, and the calls bench.py launches, which keep the
+state's bf16 planes with the caller), and a two-stream variant
 in which the evicted chunk is absorbed on a second stream while the blocks are selected.
 
 Every replay is compared with the same step run eagerly on one stream on buffers of its own;
@@ -30,6 +31,16 @@ class Buffers:
         self.st = torch.empty(hf.hf_state_bytes(cfg) // 4, dtype=torch.float32, device=DEV)
         hf.hf_state_init(cfg, self.st)
         hf.hf_absorb_evicted(cfg, self.st, self.Ke, self.Ve, workspace=self.aws)   # a non-empty history
+        nb = hf.hf_state_planes_bytes(cfg)
+        self.planes = torch.empty(nb, dtype=torch.uint8, device=DEV) if nb else None
+        if nb:
+            hf.hf_state_planes(cfg, self.st, self.planes)
+
+    def kept_planes_step(self):
+        """The step as bench.py launches it: the state's bf16 planes travel with the state."""
+        hf.hf_absorb_evicted_planes(self.cfg, self.st, self.Ke, self.Ve, self.planes, workspace=self.aws)
+        hf.hf_block_select(self.cfg, self.Q, self.K, self.idx, None, self.ws)
+        hf.hf_hybrid_attn_fwd_planes(self.cfg, self.Q, self.K, self.V, self.idx, self.st, self.planes, self.O)
 
     def eager_step(self):
         hf.hf_absorb_evicted(self.cfg, self.st, self.Ke, self.Ve, workspace=self.aws)
@@ -85,3 +96,32 @@ def test_captured_step_replays_match_eager(name, two_streams):
         else:
             torch.testing.assert_close(cap.O, ref.O, rtol=1e-4, atol=1e-5)
         assert torch.isfinite(cap.O.float()).all()
+
+
+@pytest.mark.parametrize("name", ["small_bf16", "step_832x480"])
+def test_captured_step_with_kept_planes_replays_match_eager(name):
+    """The same for the calls that keep the state's bf16 planes with the caller; the eager reference runs the
+    ordinary calls.  In the plain case with a workspace every sum has a fixed order: bit for bit."""
+    w = wl.get(name)
+    cfg = hf.make_config(batch=w.batch, heads=w.heads, head_dim=w.head_dim, dtype=w.dtype, block_q=w.block,
+                         block_kv=w.block, keep_ratio=w.keep_ratio)
+    Q, K, V = wl.make_qkv(w)
+    Ke, Ve = wl.make_evicted(w, 0)
+    ref = Buffers(cfg, w, Q, K, V, Ke, Ve)
+    cap = Buffers(cfg, w, Q, K, V, Ke, Ve)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        cap.kept_planes_step()
+    scratch = torch.zeros(1 << 20, device=DEV)
+    for rep in range(4):
+        ref.eager_step()
+        scratch.add_(1.0)        # the program's own eager work between replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(cap.idx, ref.idx), rep
+        assert torch.equal(cap.st, ref.st), rep
+        assert torch.equal(cap.O, ref.O), rep
+        assert torch.isfinite(cap.O.float()).all()
+
