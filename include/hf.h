@@ -184,9 +184,12 @@ HF_API int hf_stream_open_chunk(const hf_config* cfg, hf_window* win, int32_t n_
 /* One denoising step of the current chunk (the hybrid attention inside g_theta of the inference
  * algorithm): hf_block_select_cached over the win->n_tokens valid tokens of the cache (on steps after the
  * chunk's first, step_in_chunk > 0, the pooled keys of the whole blocks before the chunk's own n_q
- * tokens are reused) followed by hf_hybrid_attn_fwd_split.  block_idx: scratch and output, int32
- * [B, H, T_m, k] for this window length; workspace >= hf_workspace_bytes(cfg, n_q, win->n_tokens),
- * the same buffer on every step of a chunk.  The other arguments as in those two calls. */
+ * tokens are reused, and so are the bf16 planes of the state that the first step left in the workspace:
+ * the state must not change between the steps of a chunk, as in the inference algorithm, where it is
+ * updated only when a chunk opens) followed by hf_hybrid_attn_fwd_split.  block_idx: scratch and output,
+ * int32 [B, H, T_m, k] for this window length; workspace >= hf_workspace_bytes(cfg, n_q, win->n_tokens),
+ * the same buffer on every step of a chunk, written by nothing else in between.  The other arguments as
+ * in those two calls. */
 HF_API int hf_stream_step(const hf_config* cfg, const hf_window* win, const void* Q, const void* Q_hist, int32_t n_q,
                    const void* K_win, const void* V_win, int32_t step_in_chunk, int32_t* block_idx,
                    const void* state_or_null, const float* rope_cos_q, const float* rope_sin_q,

@@ -515,8 +515,17 @@ int hf_stream_step(const hf_config* cfg, const hf_window* win, const void* Q, co
   const int32_t reuse = step_in_chunk > 0 ? (n_kv - n_q) / cfg->block_kv : 0;
   HF_TRY(hf_block_select_cached(cfg, Q, n_q, K_win, n_kv, reuse, block_idx, nullptr, workspace, workspace_bytes,
                                 stream));
-  return hf_hybrid_attn_fwd_split(cfg, Q, Q_hist, n_q, K_win, V_win, n_kv, block_idx, select_k_of(cfg, cdiv(n_kv, cfg->block_kv)),
-                                  state_or_null, rope_cos_q, rope_sin_q, O, workspace, workspace_bytes, stream);
+  const int32_t k = select_k_of(cfg, cdiv(n_kv, cfg->block_kv));
+  const char* fuse_env = getenv("HF_FUSED_EPILOGUE");
+  if (step_in_chunk > 0 && state_or_null && attn_mfma_fused_supported(*cfg) && !(fuse_env && fuse_env[0] == '0')) {
+    // the state is frozen during a chunk's denoising steps: its bf16 planes are as the chunk's first step left them
+    // in this workspace (which hf_block_select_cached has just checked for size and alignment)
+    const WorkspaceLayout w = workspace_layout(cfg, n_q, n_kv);
+    return fwd_impl(cfg, Q, Q_hist, n_q, K_win, V_win, n_kv, block_idx, k, state_or_null, rope_cos_q, rope_sin_q, O,
+                    false, nullptr, nullptr, nullptr, 0, stream, static_cast<char*>(workspace) + w.planes);
+  }
+  return hf_hybrid_attn_fwd_split(cfg, Q, Q_hist, n_q, K_win, V_win, n_kv, block_idx, k, state_or_null, rope_cos_q,
+                                  rope_sin_q, O, workspace, workspace_bytes, stream);
 }
 
 int hf_bwd_workspace_bytes(const hf_config* cfg, int32_t n_q, int32_t n_kv, size_t* bytes_out) {
