@@ -42,6 +42,55 @@ __global__ __launch_bounds__(256) void invert_index_kernel(const int32_t* __rest
   if (lane == 0) inv_cnt[(size_t)bh * t_n + j] = cnt;
 }
 
+// The same lists by counting, one workgroup per head (used when a head's index rows and eight histograms fit in
+// LDS): the rows are copied to LDS once; wavefront w owns a contiguous run of query blocks and walks it in order,
+// first counting the hits per KV block, then, from the exclusive sums over the wavefronts, placing its query blocks
+// behind those of the wavefronts before it.  Lanes of a wavefront work on one row at a time, whose entries are
+// distinct by contract, so their counters are distinct: no atomics.  Ascending lists, as above.
+constexpr int kInvWaves = 8;
+__global__ __launch_bounds__(64 * kInvWaves) void invert_index_lds_kernel(const int32_t* __restrict__ idx, int k,
+                                                                          int t_m, int t_n,
+                                                                          int32_t* __restrict__ inv_cnt,
+                                                                          int32_t* __restrict__ inv_list) {
+  extern __shared__ int32_t inv_smem[];
+  int32_t* rows = inv_smem;              // [t_m][k]
+  int32_t* hist = inv_smem + t_m * k;    // [kInvWaves][t_n]
+  const int bh = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int32_t* src = idx + (size_t)bh * t_m * k;
+  for (int e = tid; e < t_m * k; e += 64 * kInvWaves) rows[e] = src[e];
+  for (int e = tid; e < kInvWaves * t_n; e += 64 * kInvWaves) hist[e] = 0;
+  __syncthreads();
+  const int seg = (t_m + kInvWaves - 1) / kInvWaves;
+  const int i_begin = min(w * seg, t_m), i_end = min(i_begin + seg, t_m);
+  int32_t* mine = hist + w * t_n;
+  for (int i = i_begin; i < i_end; ++i)
+    for (int s = lane; s < k; s += 64) {
+      const int j = rows[i * k + s];
+      if ((unsigned)j < (unsigned)t_n) mine[j] += 1;
+    }
+  __syncthreads();
+  for (int j = tid; j < t_n; j += 64 * kInvWaves) {
+    int base = 0;
+    for (int v = 0; v < kInvWaves; ++v) {
+      const int c = hist[v * t_n + j];
+      hist[v * t_n + j] = base;
+      base += c;
+    }
+    inv_cnt[(size_t)bh * t_n + j] = min(base, t_m);
+  }
+  __syncthreads();
+  int32_t* out = inv_list + (size_t)bh * t_n * t_m;
+  for (int i = i_begin; i < i_end; ++i)
+    for (int s = lane; s < k; s += 64) {
+      const int j = rows[i * k + s];
+      if ((unsigned)j < (unsigned)t_n) {
+        const int pos = mine[j];
+        mine[j] = pos + 1;
+        if (pos < t_m) out[(size_t)j * t_m + pos] = i;   // (a row that breaks the contract cannot write past a list)
+      }
+    }
+}
+
 // ---- dQ: R query rows per wavefront, lanes = keys for the dot products, lanes = features for dQ ------
 template <typename T, int D, int R>
 __global__ __launch_bounds__(256) void bwd_dq_generic_kernel(
@@ -352,6 +401,12 @@ __global__ __launch_bounds__(256) void bwd_hist_generic_kernel(const T* __restri
 
 int launch_invert_index(const hf_config& c, const int32_t* idx, int k, int t_m, int t_n, int32_t* inv_cnt,
                         int32_t* inv_list, hipStream_t s) {
+  const size_t lds = ((size_t)t_m * k + (size_t)kInvWaves * t_n) * sizeof(int32_t);
+  if (lds <= 48 * 1024) {
+    hipLaunchKernelGGL(invert_index_lds_kernel, dim3(c.batch * c.heads), dim3(64 * kInvWaves), lds, s, idx, k, t_m, t_n,
+                       inv_cnt, inv_list);
+    return check_launch("hf_hybrid_attn_bwd(inverse lists)");
+  }
   hipLaunchKernelGGL(invert_index_kernel, dim3((t_n + 3) / 4, c.batch * c.heads), dim3(256), 0, s, idx, k, t_m, t_n,
                      inv_cnt, inv_list);
   return check_launch("hf_hybrid_attn_bwd(inverse lists)");
