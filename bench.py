@@ -230,11 +230,11 @@ def main():
             max(3, min(a.steps, 10)))
     # the history readout as a kernel of its own (two-kernel path of hf_hybrid_attn_fwd) for its HBM roofline;
     # the default path adds the history term in the attention epilogue
-    os.environ["HF_FUSED_EPILOGUE"] = "0"
+    cfg_two = hf.make_config(w.batch, w.heads, w.head_dim, w.dtype, w.block, w.block, keep,
+                             flags=hf.HF_FLAG_READOUT_KERNEL)
     fwd2_ms, _ = time_calls(
-        lambda s: hf.hf_hybrid_attn_fwd(cfg, s["Q"], s["K"], s["V"], s["idx"], s["st"], s["O"], s["ws"], rq[0], rq[1]),
+        lambda s: hf.hf_hybrid_attn_fwd(cfg_two, s["Q"], s["K"], s["V"], s["idx"], s["st"], s["O"], s["ws"], rq[0], rq[1]),
         a.steps)
-    del os.environ["HF_FUSED_EPILOGUE"]
     a5_ms = max(fwd2_ms - a4_ms, 0.0)
 
     # practical HBM ceiling at this size: a plain device copy of the readout's byte count (read + written)

@@ -13,8 +13,8 @@
  *  - Every data pointer is a DEVICE pointer on the current HIP device unless it says
  *    "host".  `cfg`, `bytes_out`, `k_out` are HOST pointers.
  *  - The caller owns every buffer (inputs, outputs, state, workspace).  The library
- *    allocates nothing on the device and keeps no global state except a thread-local
- *    error string.
+ *    allocates nothing on the device, reads no environment variable and keeps no global
+ *    state except a thread-local error string and once-per-device kernel attributes.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every call
  *    only enqueues kernels on that stream: no call synchronises, none allocates.
  *  - Tensors are contiguous, head-major [batch, heads, tokens, head_dim] with head_dim
@@ -51,6 +51,20 @@ extern "C" {
 enum { HF_BF16 = 0, HF_F32 = 1 };            /* hf_config.dtype */
 enum { HF_PHI_RELU = 0, HF_PHI_ELU1 = 1 };   /* hf_config.phi: max(x,0) | elu(x)+1 */
 
+/* hf_config.flags: choices between kernels that compute the same thing.  0 is the fast default; the other
+ * settings exist so that every kernel can be reached, timed and checked through this interface (the library
+ * reads no environment variable). */
+enum {
+  HF_FLAG_READOUT_KERNEL = 1,      /* history term (Eq. 3, 6) by a readout kernel of its own behind the attention
+                                      kernel, instead of in that kernel's epilogue (bf16, head_dim 128, block_q
+                                      64 / 128; elsewhere that is the only path anyway) */
+  HF_FLAG_HISTORY_TWO_PLANES = 2,  /* the fused epilogue multiplies with both bf16 planes of L (high part and
+                                      remainder, ~2^-17 relative) instead of the high plane alone (2^-9) */
+  HF_FLAG_BWD_FP32_KERNELS = 4,    /* hf_hybrid_attn_bwd through the fp32-arithmetic kernels also where the
+                                      matrix-core kernels apply */
+  HF_FLAG_DKV_INDEX_ORDER = 8      /* dK / dV workgroups in index order instead of longest list first */
+};
+
 enum {
   HF_OK = 0,
   HF_ERR_NULL = -1,       /* a required pointer is NULL */
@@ -70,7 +84,8 @@ typedef struct hf_config {
   int32_t dtype;          /* HF_BF16 | HF_F32: storage type of Q, K, V, O */
   int32_t block_q;        /* b_q  >= 1 */
   int32_t block_kv;       /* b_kv >= 1 */
-  float   keep_ratio;     /* in (0, 1]; 1.0 keeps every block (dense window attention) */
+  float   keep_ratio;     /* in (0, 1]; 1.0 keeps every block (dense window attention).  Read to 7 significant
+                             decimal digits, so that 0.1f means 0.1 (and 0.1 * 10 blocks keeps 1, not 2) */
   int32_t keep_k;         /* > 0 overrides keep_ratio; 0: k = clamp(ceil(keep_ratio*T_n - 1e-9), 1, T_n) */
   int32_t phi;            /* HF_PHI_RELU (default) | HF_PHI_ELU1 */
   float   eps;            /* added to the readout denominator (Eq. 3); e.g. 1e-6 */
@@ -79,6 +94,7 @@ typedef struct hf_config {
   int32_t kv_capacity;    /* 0: the heads of K_win, V_win are packed, n_kv tokens apart.  > 0: they are the
                              heads of a cache buffer [B, H, kv_capacity, d] whose first n_kv <= kv_capacity
                              tokens are valid.  Applies to every K_win / V_win argument, to nothing else. */
+  int32_t flags;          /* bitwise OR of HF_FLAG_*; 0 = defaults */
 } hf_config;
 
 /* Size in bytes of the linear state: batch*heads*(d*d + d)*4.  Host-only. */

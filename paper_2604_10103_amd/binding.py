@@ -14,6 +14,7 @@ import torch
 
 HF_BF16, HF_F32 = 0, 1
 HF_PHI_RELU, HF_PHI_ELU1 = 0, 1
+HF_FLAG_READOUT_KERNEL, HF_FLAG_HISTORY_TWO_PLANES, HF_FLAG_BWD_FP32_KERNELS, HF_FLAG_DKV_INDEX_ORDER = 1, 2, 4, 8
 HF_OK = 0
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libhf.so")
@@ -41,6 +42,7 @@ class hf_config(ctypes.Structure):
         ("z_scale", ctypes.c_float),
         ("softmax_scale", ctypes.c_float),
         ("kv_capacity", ctypes.c_int32),
+        ("flags", ctypes.c_int32),
     ]
 
 
@@ -49,13 +51,13 @@ class hf_window(ctypes.Structure):
 
 
 def make_config(batch, heads, head_dim, dtype, block_q, block_kv, keep_ratio=1.0, keep_k=0,
-                phi=HF_PHI_RELU, eps=1e-6, z_scale=1.0, softmax_scale=0.0, kv_capacity=0) -> hf_config:
+                phi=HF_PHI_RELU, eps=1e-6, z_scale=1.0, softmax_scale=0.0, kv_capacity=0, flags=0) -> hf_config:
     if isinstance(dtype, str):
         dtype = {"bf16": HF_BF16, "f32": HF_F32}[dtype]
     elif isinstance(dtype, torch.dtype):
         dtype = {torch.bfloat16: HF_BF16, torch.float32: HF_F32}[dtype]
     return hf_config(batch, heads, head_dim, dtype, block_q, block_kv, keep_ratio, keep_k, phi, eps,
-                     z_scale, softmax_scale, kv_capacity)
+                     z_scale, softmax_scale, kv_capacity, flags)
 
 
 def lib_path() -> str:

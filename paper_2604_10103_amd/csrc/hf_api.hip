@@ -27,6 +27,20 @@ int check_launch(const char* what) {
   return HF_OK;
 }
 
+int grant_lds(LdsGrant& g, const void* kernel, int bytes, const char* what) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); dev = -1; }
+  const bool tracked = dev >= 0 && dev < LdsGrant::kDevices;
+  if (tracked && g.granted[dev].load(std::memory_order_acquire)) return HF_OK;
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    set_error("cannot reserve %d bytes of LDS for %s", bytes, what);
+    return HF_ERR_HIP;
+  }
+  if (tracked) g.granted[dev].store(1, std::memory_order_release);
+  return HF_OK;
+}
+
 static int check_cfg(const hf_config* c) {
   if (!c) { set_error("cfg is NULL"); return HF_ERR_NULL; }
   if (c->batch < 1 || c->heads < 1) { set_error("batch and heads must be >= 1"); return HF_ERR_SHAPE; }
@@ -40,6 +54,9 @@ static int check_cfg(const hf_config* c) {
   if (c->kv_capacity < 0 || c->kv_capacity > (1 << 24)) { set_error("kv_capacity must be in [0, 2^24]"); return HF_ERR_SHAPE; }
   if (c->keep_k == 0 && !(c->keep_ratio > 0.0f && c->keep_ratio <= 1.0f)) {
     set_error("keep_ratio must be in (0, 1]"); return HF_ERR_SHAPE;
+  }
+  if (c->flags & ~(HF_FLAG_READOUT_KERNEL | HF_FLAG_HISTORY_TWO_PLANES | HF_FLAG_BWD_FP32_KERNELS | HF_FLAG_DKV_INDEX_ORDER)) {
+    set_error("unknown bits in flags: 0x%x", (unsigned)c->flags); return HF_ERR_SHAPE;
   }
   if (!(c->eps >= 0.0f) || !isfinite(c->z_scale) || !(c->softmax_scale >= 0.0f)) {
     set_error("eps, z_scale or softmax_scale is invalid"); return HF_ERR_SHAPE;
@@ -75,7 +92,12 @@ static inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
 static int select_k_of(const hf_config* c, int t_n) {
   if (c->keep_k > 0) return c->keep_k;
-  int k = (int)ceil((double)c->keep_ratio * (double)t_n - 1e-9);
+  // keep_ratio is a float: its representation error (up to 6e-8 relative) would exceed the 1e-9 slack whenever
+  // ratio * T_n is an integer (0.1f * 10 = 1.0000000149).  The ratio is therefore read to 7 significant decimal
+  // digits, which recovers the decimal value the caller wrote.
+  char digits[32];
+  snprintf(digits, sizeof(digits), "%.7g", (double)c->keep_ratio);
+  int k = (int)ceil(strtod(digits, nullptr) * (double)t_n - 1e-9);
   if (k < 1) k = 1;
   if (k > t_n) k = t_n;
   return k;
@@ -453,8 +475,7 @@ static int fwd_impl(const hf_config* cfg, const void* Q, const void* Q_hist, int
     return HF_ERR_WORKSPACE;
   }
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) { set_error("workspace is not 256-byte aligned"); return HF_ERR_ALIGN; }
-  const char* fuse_env = getenv("HF_FUSED_EPILOGUE");  // "0" keeps the two-kernel path (to time the readout alone)
-  if (attn_mfma_fused_supported(*cfg) && (save || !(fuse_env && fuse_env[0] == '0'))) {
+  if (attn_mfma_fused_supported(*cfg) && (save || !(cfg->flags & HF_FLAG_READOUT_KERNEL))) {
     // MFMA shapes: the history term is added in the attention kernel's epilogue
     char* planes = static_cast<char*>(workspace) + w.planes;
     const float* st = static_cast<const float*>(state_or_null);
@@ -516,8 +537,7 @@ int hf_stream_step(const hf_config* cfg, const hf_window* win, const void* Q, co
   HF_TRY(hf_block_select_cached(cfg, Q, n_q, K_win, n_kv, reuse, block_idx, nullptr, workspace, workspace_bytes,
                                 stream));
   const int32_t k = select_k_of(cfg, cdiv(n_kv, cfg->block_kv));
-  const char* fuse_env = getenv("HF_FUSED_EPILOGUE");
-  if (step_in_chunk > 0 && state_or_null && attn_mfma_fused_supported(*cfg) && !(fuse_env && fuse_env[0] == '0')) {
+  if (step_in_chunk > 0 && state_or_null && attn_mfma_fused_supported(*cfg) && !(cfg->flags & HF_FLAG_READOUT_KERNEL)) {
     // the state is frozen during a chunk's denoising steps: its bf16 planes are as the chunk's first step left them
     // in this workspace (which hf_block_select_cached has just checked for size and alignment)
     const WorkspaceLayout w = workspace_layout(cfg, n_q, n_kv);
@@ -631,8 +651,7 @@ static int bwd_impl(const hf_config* cfg, const void* Q, const void* Q_hist, int
   int32_t* inv_list = block_idx ? reinterpret_cast<int32_t*>(ws + w.inv_list) : nullptr;
   const float* st = static_cast<const float*>(state_or_null);
 
-  const char* pick = getenv("HF_BWD_KERNEL");   // development switch: "g" forces the fp32-arithmetic kernels
-  const bool mfma = bwd_mfma_supported(*cfg) && (saved || !(pick && pick[0] == 'g'));
+  const bool mfma = bwd_mfma_supported(*cfg) && (saved || !(cfg->flags & HF_FLAG_BWD_FP32_KERNELS));
   if (split && !st) {
     const size_t bytes = (size_t)cfg->batch * cfg->heads * n_q * cfg->head_dim * esize(cfg);
     HF_TRY(launch_fill_zero(static_cast<float*>(dQ_hist), bytes / 4, s));

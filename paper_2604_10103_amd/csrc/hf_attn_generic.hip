@@ -109,7 +109,7 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const T* __restrict__
 #pragma unroll
       for (int rr = 0; rr < R; ++rr) {
         const int row = min(r0 + rr, n_q - 1);
-        const float inv = 1.0f / l[rr];
+        const float inv = l[rr] > 0.0f ? 1.0f / l[rr] : 0.0f;   // a row without a single real key: O_local = 0
         float acc = 0.0f;
 #pragma unroll
         for (int e = 0; e < C; ++e)
@@ -127,7 +127,7 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const T* __restrict__
     for (int rr = 0; rr < R; ++rr) {
       const int row = r0 + rr;
       if (row < q_end) {
-        const float inv = 1.0f / l[rr];
+        const float inv = l[rr] > 0.0f ? 1.0f / l[rr] : 0.0f;   // a row without a single real key: O_local = 0
 #pragma unroll
         for (int e = 0; e < C; ++e) Elem<T>::store(Oh + (size_t)row * D + lane * C + e, o[rr][e] * inv);
       }
@@ -174,9 +174,7 @@ int launch_attn(const hf_config& c, const void* Q, int n_q, const void* K, const
   }
   // bf16, head_dim 128: block_q 64 / 128 take the workgroup-per-query-block MFMA kernel, other
   // multiples of 64 the wavefront-per-64-rows MFMA kernel; everything else the fp32-arithmetic one
-  const char* pick = getenv("HF_ATTN_KERNEL");  // development switch: "w" forces the second kernel
-  const bool want_w64 = pick && pick[0] == 'w';
-  if (attn_mfma_supported(c) && !want_w64) return launch_attn_mfma(c, Q, n_q, K, V, n_kv, idx, k, O_local, s);
+  if (attn_mfma_supported(c)) return launch_attn_mfma(c, Q, n_q, K, V, n_kv, idx, k, O_local, s);
   if (attn_w64_supported(c)) return launch_attn_w64(c, Q, n_q, K, V, n_kv, idx, k, O_local, s);
   return launch_attn_generic(c, Q, n_q, K, V, n_kv, idx, k, O_local, s, nullptr, nullptr, nullptr);
 }

@@ -570,10 +570,8 @@ int launch_attn_mfma_fused(const hf_config& c, const void* Q, int n_q, const voi
                            const float* sinq, const void* Q_hist, void* O, hipStream_t s, float* lse2_out,
                            void* olocal_out) {
   // One bf16 plane of L (2^-9 per element, errors of the d terms of a readout average out) costs the
-  // output nothing measurable next to the bf16 rounding of P and O; HF_FUSED_PLANES=2 in the
-  // environment adds the low plane (development switch).
-  const char* np = getenv("HF_FUSED_PLANES");
-  const HistArgs h = {static_cast<const bf16_t*>(planes), zvec, c.eps, c.z_scale, (np && np[0] == '2') ? 2 : 1,
+  // output nothing measurable next to the bf16 rounding of P and O; HF_FLAG_HISTORY_TWO_PLANES adds the low plane.
+  const HistArgs h = {static_cast<const bf16_t*>(planes), zvec, c.eps, c.z_scale, (c.flags & HF_FLAG_HISTORY_TWO_PLANES) ? 2 : 1,
                       c.phi, cosq, sinq, Q_hist == Q ? nullptr : static_cast<const bf16_t*>(Q_hist), nullptr, nullptr, nullptr,
                       lse2_out, static_cast<bf16_t*>(olocal_out)};
   return launch_attn_mfma_impl(c, Q, n_q, K, V, n_kv, idx, k, &h, O, s);

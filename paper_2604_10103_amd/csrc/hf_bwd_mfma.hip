@@ -1039,16 +1039,10 @@ int launch_bwd_mfma(const hf_config& c, const void* Q, int n_q, const void* K, c
   // more than 64 KB of LDS has to be granted per kernel instance, once
 #define HF_LAUNCH_DQ3(NWV, HM, RG)                                                                                  \
   do {                                                                                                             \
-    static bool granted = false;                                                                                   \
-    if (!granted) {                                                                                                \
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dq_mfma_kernel<NWV, HM, RG>),                      \
-                              hipFuncAttributeMaxDynamicSharedMemorySize, kDqLds) != hipSuccess) {                 \
-        (void)hipGetLastError();                                                                                   \
-        set_error("cannot reserve %d bytes of LDS for the dQ kernel", kDqLds);                                     \
-        return HF_ERR_HIP;                                                                                         \
-      }                                                                                                            \
-      granted = true;                                                                                              \
-    }                                                                                                              \
+    static LdsGrant grant;                                                                                         \
+    const int rc_grant = grant_lds(grant, reinterpret_cast<const void*>(bwd_dq_mfma_kernel<NWV, HM, RG>), kDqLds,  \
+                                   "the dQ kernel");                                                               \
+    if (rc_grant != HF_OK) return rc_grant;                                                                        \
     hipLaunchKernelGGL((bwd_dq_mfma_kernel<NWV, HM, RG>), dim3(8 * q_per_xcd), dim3(64 * NWV), kDqLds, s, q, kk, v, \
                        g, idx, k, n_q, n_kv, kvs, c.block_kv, t_m, t_n, q_per_xcd, (int)q_items, c_scale, scale,    \
                        lse2, Dv, hist, static_cast<bf16_t*>(dQ));                                                  \
@@ -1067,19 +1061,11 @@ int launch_bwd_mfma(const hf_config& c, const void* Q, int n_q, const void* K, c
   const long long kv_items = (long long)BH * t_n * slabs;
   if (kv_items > (1ll << 30)) { set_error("too many KV slabs"); return HF_ERR_SHAPE; }
   const int kv_per_xcd = (int)((kv_items + 7) / 8);
-  static bool dkv_ready = false;
-  if (!dkv_ready) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(bwd_dkv_mfma_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, kDkvLds) != hipSuccess) {
-      (void)hipGetLastError();
-      set_error("cannot reserve %d bytes of LDS for the dK/dV kernel", kDkvLds);
-      return HF_ERR_HIP;
-    }
-    dkv_ready = true;
-  }
+  static LdsGrant dkv_grant;
+  const int rc_dkv = grant_lds(dkv_grant, reinterpret_cast<const void*>(bwd_dkv_mfma_kernel), kDkvLds, "the dK/dV kernel");
+  if (rc_dkv != HF_OK) return rc_dkv;
   const int32_t* order = nullptr;   // equal lists (dense), or a share too long for the ordering kernel: index order
-  const char* pick = getenv("HF_DKV_ORDER");   // development switch: "0" launches in index order
-  if (inv_cnt && dkv_order && kv_per_xcd <= kOrderMax && !(pick && pick[0] == '0')) {
+  if (inv_cnt && dkv_order && kv_per_xcd <= kOrderMax && !(c.flags & HF_FLAG_DKV_INDEX_ORDER)) {
     hipLaunchKernelGGL(dkv_order_kernel, dim3(8), dim3(1024), 0, s, inv_cnt, inv_list, t_m, slabs, kv_per_xcd,
                        (int)kv_items, dkv_order);
     order = dkv_order;

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "hf.h"
 
 namespace hf {
@@ -71,6 +73,14 @@ __device__ __forceinline__ float wave_sum(float v) {
 // ---- host side -------------------------------------------------------------------------
 void set_error(const char* fmt, ...);
 int check_launch(const char* what);
+
+// More than 64 KB of dynamic LDS has to be granted per kernel and device.  One object per kernel (static
+// storage, zero-initialised); the grant is idempotent, so threads that race here at worst both ask for it.
+struct LdsGrant {
+  static constexpr int kDevices = 64;
+  std::atomic<int> granted[kDevices];
+};
+int grant_lds(LdsGrant& g, const void* kernel, int bytes, const char* what);
 
 struct Dims {
   int B, H, D, BH;

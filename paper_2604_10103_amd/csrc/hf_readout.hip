@@ -108,15 +108,10 @@ static int launch_readout_fma(const hf_config& c, const void* Q, int n_q, const 
   const dim3 grid((n_q + rows_per_wg - 1) / rows_per_wg, BH), block(256);
   const size_t smem = (size_t)(D * D + D + 4 * R * 2 * D) * sizeof(float);
   auto kern = readout_fma_kernel<T, D, R>;
-  static bool attr_set = false;  // > 64 KB of dynamic LDS must be opted into once per kernel
-  if (!attr_set && smem > 64 * 1024) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)smem) != hipSuccess) {
-      (void)hipGetLastError();
-      set_error("cannot reserve %zu bytes of LDS for the readout kernel", smem);
-      return HF_ERR_HIP;
-    }
-    attr_set = true;
+  if (smem > 64 * 1024) {
+    static LdsGrant grant;   // (one per instantiation of this function template, i.e. per kernel)
+    const int rc = grant_lds(grant, reinterpret_cast<const void*>(kern), (int)smem, "the readout kernel");
+    if (rc != HF_OK) return rc;
   }
   hipLaunchKernelGGL(kern, grid, block, smem, s, static_cast<const T*>(Q), static_cast<const T*>(O_local), state,
                      cosq, sinq, n_q, rows_per_wg, c.phi, c.eps, c.z_scale, BH, static_cast<T*>(O));

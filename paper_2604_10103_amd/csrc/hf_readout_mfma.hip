@@ -198,16 +198,12 @@ int launch_readout_mfma(const hf_config& c, const void* Q, int n_q, const void* 
   const bf16_t* q = static_cast<const bf16_t*>(Q);
   const bf16_t* ol = static_cast<const bf16_t*>(O_local);
   bf16_t* o = static_cast<bf16_t*>(O);
-  static bool attr_set[2] = {false, false};
+  static LdsGrant grants[2];
   const void* fn = plain ? reinterpret_cast<const void*>(readout_mfma_kernel<true>)
                          : reinterpret_cast<const void*>(readout_mfma_kernel<false>);
-  if (!attr_set[plain]) {
-    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess) {
-      (void)hipGetLastError();
-      set_error("cannot reserve %zu bytes of LDS for the readout kernel", smem);
-      return HF_ERR_HIP;
-    }
-    attr_set[plain] = true;
+  {
+    const int rc = grant_lds(grants[plain], fn, (int)smem, "the readout kernel");
+    if (rc != HF_OK) return rc;
   }
   if (plain)
     hipLaunchKernelGGL((readout_mfma_kernel<true>), grid, block, smem, s, q, ol, pl, state, cosq, sinq, n_q, c.phi,

@@ -436,20 +436,10 @@ __global__ __launch_bounds__(256) void absorb_reduce_kernel(float* __restrict__ 
   *reinterpret_cast<uint2*>(hi + D * D) = make_uint2(lw[0], lw[1]);
 }
 
-int env_int(const char* name, int dflt) {
-  const char* v = getenv(name);
-  if (!v || !*v) return dflt;
-  const int x = atoi(v);
-  return x > 0 ? x : dflt;
-}
-
 // slice length (a multiple of the 64-token chunk) and slice count for n tokens
 // dma: the plan of absorb_dma_kernel, whose run is RUN_TILES tiles of 32 tokens
 void slice_plan(int BH, int n, bool with_workspace, bool dma, int& per, int& slices) {
-  const int forced = env_int("HF_ABSORB_SLICE_TOKENS", 0);  // development override
-  if (forced > 0) {
-    per = (forced + CH - 1) / CH * CH;
-  } else if (with_workspace && dma) {
+  if (with_workspace && dma) {
     // one run (288 tokens) per workgroup, one workgroup per CU; longer slices only for very long inputs
     const int run = RUN_TILES * TT;
     const int max_slices = (1024 + BH - 1) / BH;
@@ -485,24 +475,16 @@ int launch_absorb_mfma(const hf_config& c, float* state, const void* K, const vo
   bf16_t* planes = static_cast<bf16_t*>(planes_out);   // NULL: the state alone
   const bool use_ws = workspace != nullptr && workspace_bytes >= absorb_mfma_workspace_bytes(c, n);
   const bool plain = (c.phi == HF_PHI_RELU) && cosv == nullptr;
-  const char* old = getenv("HF_ABSORB_KERNEL");   // development switch: "r" keeps the register-staged kernel
-  const bool dma = plain && use_ws && !(old && old[0] == 'r');
+  const bool dma = plain && use_ws;
   int per, slices;
   slice_plan(BH, n, use_ws, dma, per, slices);
   float* partials = use_ws ? static_cast<float*>(workspace) : nullptr;
   const bf16_t* Kp = static_cast<const bf16_t*>(K);
   const bf16_t* Vp = static_cast<const bf16_t*>(V);
   if (dma) {
-    static bool ready = false;
-    if (!ready) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(absorb_dma_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, DMA_LDS) != hipSuccess) {
-        (void)hipGetLastError();
-        set_error("cannot reserve %d bytes of LDS for the absorb kernel", DMA_LDS);
-        return HF_ERR_HIP;
-      }
-      ready = true;
-    }
+    static LdsGrant grant;
+    const int rc_grant = grant_lds(grant, reinterpret_cast<const void*>(absorb_dma_kernel), DMA_LDS, "the absorb kernel");
+    if (rc_grant != HF_OK) return rc_grant;
     hipLaunchKernelGGL(absorb_dma_kernel, dim3(BH * slices), dim3(NT), DMA_LDS, s, partials, Kp, Vp, n, head_stride, per,
                        slices);
     const int rc2 = check_launch("hf_absorb_evicted");

@@ -35,10 +35,23 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_config_struct_layout():
-    assert ctypes.sizeof(hf.hf_config) == 13 * 4
+    assert ctypes.sizeof(hf.hf_config) == 14 * 4
+    assert hf.hf_config.flags.offset == 52
     assert hf.hf_config.keep_ratio.offset == 24 and hf.hf_config.softmax_scale.offset == 44
     assert hf.hf_config.kv_capacity.offset == 48
     assert ctypes.sizeof(hf.hf_window) == 8 and hf.hf_window.n_tokens.offset == 4
+
+
+def test_library_reads_no_environment_variable(lib):
+    """Kernel choices are hf_config.flags; nothing in the library's sources consults the process environment."""
+    csrc = os.path.join(ROOT, "paper_2604_10103_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        text = open(os.path.join(csrc, name)).read()
+        assert "getenv" not in text and "environ" not in text, name
+    cfg = hf.make_config(1, 1, 128, "bf16", 64, 64, 0.25, flags=1 << 20)
+    with pytest.raises(hf.HFError) as e:
+        hf.hf_state_bytes(cfg)
+    assert "flags" in str(e.value)
 
 
 def test_version_and_state_bytes(lib):
@@ -50,7 +63,10 @@ def test_version_and_state_bytes(lib):
 
 
 @pytest.mark.parametrize("ratio,n_kv,b", [(0.25, 256, 16), (0.25, 9360, 64), (0.125, 21600, 128), (0.25, 21600, 128),
-                                          (0.5, 21600, 128), (1.0, 21600, 128), (0.3, 500, 32), (1e-6, 100, 10)])
+                                          (0.5, 21600, 128), (1.0, 21600, 128), (0.3, 500, 32), (1e-6, 100, 10),
+                                          # ratio * T_n an integer with a ratio that float32 cannot hold exactly
+                                          (0.1, 100, 10), (0.2, 1500, 10), (0.3, 100, 10), (0.6, 50, 10),
+                                          (0.1, 1500, 10), (0.7, 100, 10), (0.9, 300, 10), (0.05, 2000, 10)])
 def test_select_k_matches_oracle(lib, ratio, n_kv, b):
     cfg = hf.make_config(1, 1, 128, "bf16", b, b, ratio)
     t_n = -(-n_kv // b)

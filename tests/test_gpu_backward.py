@@ -5,7 +5,6 @@ split queries, the dense window, a cache buffer with spare capacity.
 Bounds.  fp32 storage: rel-L2 <= 5e-5 (fp32 exp2 and accumulation; dS = P (dP - D) subtracts two O(1) numbers, which
 costs a few units over the forward's 1e-5).  bf16 storage: rel-L2 <= 1e-2 and max-abs <= 2e-2 of the largest
 gradient magnitude, the forward's bounds (inputs are exact in both; the output rounding alone is 2^-9)."""
-import os
 
 import numpy as np
 import pytest
@@ -172,11 +171,8 @@ def test_bf16_kernel_choices_and_key_blocks_that_are_no_multiple_of_a_tile(name,
     hf.hf_block_select(cfg, Q.to(DEV), K.to(DEV), idx, None, ws)
     torch.cuda.synchronize()
     if force_generic:
-        os.environ["HF_BWD_KERNEL"] = "g"
-    try:
-        dQ, dK, dV, _ = run_bwd(cfg, w, Q, K, V, idx, st, dO)
-    finally:
-        os.environ.pop("HF_BWD_KERNEL", None)
+        cfg.flags |= hf.HF_FLAG_BWD_FP32_KERNELS
+    dQ, dK, dV, _ = run_bwd(cfg, w, Q, K, V, idx, st, dO)
     idxc = idx.cpu().numpy()
     assert idxc.max() < t_n
     for h, (q, kk, v, g) in enumerate(zip(heads_of(Q), heads_of(K), heads_of(V), heads_of(dO))):
@@ -190,7 +186,7 @@ def test_bf16_kernel_choices_and_key_blocks_that_are_no_multiple_of_a_tile(name,
 @pytest.mark.parametrize("name", ["small_bf16", "small_b128", "step_832x480"])
 def test_launch_order_of_the_key_side_kernel_changes_no_bit(name):
     """The dK/dV workgroups are launched longest list first, from records that also carry their first list
-    entries; in index order (development switch) every workgroup finds the same entries by itself.  A workgroup's
+    entries; in index order (HF_FLAG_DKV_INDEX_ORDER) every workgroup finds the same entries by itself.  A workgroup's
     result does not depend on when it runs, so the two orders must agree bit for bit, and so must two runs."""
     w = wl.get(name)
     cfg = cfg_of(w)
@@ -199,11 +195,8 @@ def test_launch_order_of_the_key_side_kernel_changes_no_bit(name):
     idx, _ = select(cfg, w, Q, K)
     a = run_bwd(cfg, w, Q, K, V, idx, None, dO)
     b = run_bwd(cfg, w, Q, K, V, idx, None, dO)
-    os.environ["HF_DKV_ORDER"] = "0"
-    try:
-        c = run_bwd(cfg, w, Q, K, V, idx, None, dO)
-    finally:
-        os.environ.pop("HF_DKV_ORDER", None)
+    cfg.flags |= hf.HF_FLAG_DKV_INDEX_ORDER
+    c = run_bwd(cfg, w, Q, K, V, idx, None, dO)
     for x, y, z in zip(a[:3], b[:3], c[:3]):
         assert torch.isfinite(x.float()).all()
         assert torch.equal(x, y) and torch.equal(x, z)

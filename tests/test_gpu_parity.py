@@ -421,6 +421,28 @@ def test_out_of_range_block_index_is_ignored_not_read():
     assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("name", ["small_bf16", "tiny_f32", "small_f32_d128"])
+def test_query_block_with_no_valid_block_index_gives_zeros_on_every_kernel(name):
+    """A row of the index list that names no existing block selects no key: its softmax is empty and O_local is
+    defined as zero there (never NaN), by the matrix-core kernel and by the fp32-arithmetic kernel alike; the
+    other query blocks are not affected."""
+    w = wl.get(name)
+    cfg = cfg_of(w)
+    Q, K, V = wl.make_qkv(w)
+    idx, _, k = gpu_select(cfg, w, Q.to(DEV), K.to(DEV), want_scores=False)
+    bad = idx.clone()
+    bad[:, :, 1, :] = 1 << 20                       # query block 1 of every head: nothing but invalid indices
+    bad[:, 0, 0, :] = -7                            # and block 0 of head 0
+    a = run_hybrid(cfg, w, Q, K, V, idx, None)
+    b = run_hybrid(cfg, w, Q, K, V, bad, None)
+    assert torch.isfinite(b.float()).all()
+    rows1 = slice(w.block, min(2 * w.block, w.n_q))
+    assert (b[:, :, rows1] == 0).all() and (b[:, 0, : w.block] == 0).all()
+    keep = torch.ones(w.n_q, dtype=torch.bool, device=DEV)
+    keep[rows1] = False
+    assert torch.equal(a[:, 1:, keep], b[:, 1:, keep])
+
+
 # ------------------------------------------------------------------------------- batch > 1
 @pytest.mark.parametrize("name", ["small_bf16", "tiny_f32"])
 def test_batch_of_two_every_stage(name):
