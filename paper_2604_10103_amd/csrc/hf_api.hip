@@ -326,9 +326,10 @@ int hf_block_select(const hf_config* cfg, const void* Q, int32_t n_q, const void
                                 stream);
 }
 
-int hf_block_select_cached(const hf_config* cfg, const void* Q, int32_t n_q, const void* K_win, int32_t n_kv,
-                           int32_t n_cached_kv_blocks, int32_t* block_idx, float* scores_or_null, void* workspace,
-                           size_t workspace_bytes, void* stream) {
+// argument checks of the selection calls; k_out = blocks kept per row
+static int check_select_args(const hf_config* cfg, const void* Q, int32_t n_q, const void* K_win, int32_t n_kv,
+                             int32_t n_cached_kv_blocks, const int32_t* block_idx, const float* scores_or_null,
+                             int* k_out) {
   HF_TRY(check_cfg(cfg));
   HF_TRY(check_ptr(Q, "Q", true));
   HF_TRY(check_ptr(K_win, "K_win", true));
@@ -349,18 +350,35 @@ int hf_block_select_cached(const hf_config* cfg, const void* Q, int32_t n_q, con
   }
   const int k = select_k_of(cfg, t_n);
   if (k > t_n) { set_error("keep_k=%d exceeds the %d KV blocks of the window", k, t_n); return HF_ERR_SHAPE; }
+  (void)t_m;
+  *k_out = k;
+  return HF_OK;
+}
+
+// the two launches of a selection call; qbar / kbar = pooled means [BH, T_m, d] and (feature-group-major) [BH, d/4, T_n, 4]
+static int select_launches(const hf_config* cfg, const void* Q, int32_t n_q, const void* K_win, int32_t n_kv,
+                           int32_t n_cached_kv_blocks, int k, int32_t* block_idx, float* scores_or_null, float* qbar,
+                           float* kbar, hipStream_t s) {
+  const int t_m = cdiv(n_q, cfg->block_q), t_n = cdiv(n_kv, cfg->block_kv);
+  HF_TRY(launch_pool_both(*cfg, Q, n_q, t_m, K_win, n_kv, t_n, n_cached_kv_blocks, qbar, kbar, s));
+  return launch_score_select(*cfg, qbar, kbar, t_m, t_n, k, block_idx, scores_or_null, s);
+}
+
+int hf_block_select_cached(const hf_config* cfg, const void* Q, int32_t n_q, const void* K_win, int32_t n_kv,
+                           int32_t n_cached_kv_blocks, int32_t* block_idx, float* scores_or_null, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+  int k = 0;
+  HF_TRY(check_select_args(cfg, Q, n_q, K_win, n_kv, n_cached_kv_blocks, block_idx, scores_or_null, &k));
   const WorkspaceLayout w = workspace_layout(cfg, n_q, n_kv);
   if (!workspace || workspace_bytes < w.total) {
     set_error("workspace of %zu bytes needed, %zu given", w.total, workspace ? workspace_bytes : (size_t)0);
     return HF_ERR_WORKSPACE;
   }
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) { set_error("workspace is not 256-byte aligned"); return HF_ERR_ALIGN; }
-  hipStream_t s = static_cast<hipStream_t>(stream);
   char* ws = static_cast<char*>(workspace);
-  float* qbar = reinterpret_cast<float*>(ws + w.qbar);
-  float* kbar = reinterpret_cast<float*>(ws + w.kbar);
-  HF_TRY(launch_pool_both(*cfg, Q, n_q, t_m, K_win, n_kv, t_n, n_cached_kv_blocks, qbar, kbar, s));
-  return launch_score_select(*cfg, qbar, kbar, t_m, t_n, k, block_idx, scores_or_null, s);
+  return select_launches(cfg, Q, n_q, K_win, n_kv, n_cached_kv_blocks, k, block_idx, scores_or_null,
+                         reinterpret_cast<float*>(ws + w.qbar), reinterpret_cast<float*>(ws + w.kbar),
+                         static_cast<hipStream_t>(stream));
 }
 
 int hf_hybrid_attn_fwd(const hf_config* cfg, const void* Q, int32_t n_q, const void* K_win,
