@@ -244,6 +244,22 @@ HF_API int hf_block_select_cached(const hf_config* cfg, const void* Q, int32_t n
                     int32_t* block_idx, float* scores_or_null,
                     void* workspace, size_t workspace_bytes, void* stream);
 
+/* hf_block_select for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same outputs bit for bit; the
+ * pooled block means live in a buffer built into the library (HF_STATIC_SCRATCH_BYTES per GPU, held until the
+ * process ends) instead of a workspace.  The call allocates nothing and frees nothing.
+ *   - sizes whose pooled means, B*H*(T_m + T_n)*d*4 bytes (each part rounded up to 256), exceed the buffer
+ *     are refused with HF_ERR_WORKSPACE (use hf_block_select);
+ *   - every call on a GPU shares that GPU's buffer: calls that may overlap in time on one GPU (different
+ *     streams, different threads) race and must be ordered by the caller; calls on different GPUs do not
+ *     interact;
+ *   - the first call on a device looks the buffer's address up (no stream work; do it once outside a graph
+ *     capture). */
+#define HF_STATIC_SCRATCH_BYTES (8u << 20)
+HF_API int hf_block_select_static(const hf_config* cfg, const void* Q, int32_t n_q,
+                    const void* K_win, int32_t n_kv,
+                    int32_t* block_idx, float* scores_or_null, void* stream);
+
 /* Eq. 5 + Eq. 3 + Eq. 6 for one chunk:
  *   O_local = softmax over the keys of the selected blocks of (Q K^T * scale) times V
  *             (online softmax, fp32 statistics and accumulation);

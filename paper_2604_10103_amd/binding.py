@@ -96,6 +96,7 @@ def load():
     lib.hf_workspace_bytes.argtypes = [CP, I, I, ctypes.POINTER(SZ)]
     lib.hf_block_select.argtypes = [CP, P, I, P, I, P, P, P, SZ, P]
     lib.hf_block_select_cached.argtypes = [CP, P, I, P, I, I, P, P, P, SZ, P]
+    lib.hf_block_select_static.argtypes = [CP, P, I, P, I, P, P, P]
     lib.hf_hybrid_attn_fwd.argtypes = [CP, P, I, P, P, I, P, I, P, P, P, P, P, SZ, P]
     lib.hf_hybrid_attn_fwd_split.argtypes = [CP, P, P, I, P, P, I, P, I, P, P, P, P, P, SZ, P]
     lib.hf_hybrid_attn_fwd_save.argtypes = [CP, P, P, I, P, P, I, P, I, P, P, P, P, P, P, P, SZ, P]
@@ -107,7 +108,8 @@ def load():
     lib.hf_rope_apply.argtypes = [CP, P, I, P, P, P, P]
     for name in ("hf_state_bytes", "hf_state_init", "hf_state_fold_linear", "hf_window_advance", "hf_absorb_evicted", "hf_absorb_workspace_bytes", "hf_select_k",
                  "hf_workspace_bytes",
-                 "hf_block_select", "hf_block_select_cached", "hf_hybrid_attn_fwd", "hf_hybrid_attn_fwd_split",
+                 "hf_block_select", "hf_block_select_cached", "hf_block_select_static", "hf_hybrid_attn_fwd",
+                 "hf_hybrid_attn_fwd_split",
                  "hf_rope_window_indices", "hf_rope_tables", "hf_rope_apply", "hf_window_evict", "hf_stream_open_chunk",
                  "hf_stream_step", "hf_bwd_workspace_bytes", "hf_hybrid_attn_bwd", "hf_state_planes_bytes",
                  "hf_state_planes", "hf_absorb_evicted_planes", "hf_hybrid_attn_fwd_planes"):
@@ -272,6 +274,22 @@ def hf_absorb_evicted_planes(cfg: hf_config, state, K_ev, V_ev, planes_out, rope
 def hf_block_select(cfg: hf_config, Q, K_win, block_idx, scores=None, workspace=None, n_kv=None) -> None:
     """block_idx: int32 [B,H,T_m,k] out; scores: optional fp32 [B,H,T_m,T_n] out; workspace: uint8 buffer."""
     hf_block_select_cached(cfg, Q, K_win, 0, block_idx, scores, workspace, _entry="hf_block_select", n_kv=n_kv)
+
+
+HF_STATIC_SCRATCH_BYTES = 8 << 20
+
+
+def hf_block_select_static(cfg: hf_config, Q, K_win, block_idx, scores=None, n_kv=None) -> None:
+    """hf_block_select without a workspace: the pooled means live in the library's built-in per-GPU buffer."""
+    B, H, d = cfg.batch, cfg.heads, cfg.head_dim
+    n_q, n_kv = Q.shape[2], _kv_len(cfg, K_win, n_kv)
+    t_m, t_n = _cdiv(n_q, cfg.block_q), _cdiv(n_kv, cfg.block_kv)
+    k = hf_select_k(cfg, n_kv)
+    _check(load().hf_block_select_static(
+        ctypes.byref(cfg), _dev(Q, "Q", _tdtype(cfg), (B, H, n_q, d)), n_q,
+        _dev(K_win, "K_win", _tdtype(cfg), (B, H, K_win.shape[2], d)), n_kv,
+        _dev(block_idx, "block_idx", torch.int32, (B, H, t_m, k)),
+        _dev(scores, "scores", torch.float32, (B, H, t_m, t_n)), _stream()))
 
 
 def hf_block_select_cached(cfg: hf_config, Q, K_win, n_cached_kv_blocks: int, block_idx, scores=None,

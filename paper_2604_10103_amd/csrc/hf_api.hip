@@ -7,6 +7,11 @@
 
 #include "hf_common.h"
 
+// Scratch of hf_block_select_static (pooled block means), one copy per GPU the library runs on, held until the
+// process ends.  In host code this name is only a handle: the memory's device address comes from
+// hipGetSymbolAddress (static_scratch() below) and that pointer is what kernels and copies are given.
+static __device__ __align__(256) unsigned char scratch[HF_STATIC_SCRATCH_BYTES];
+
 namespace hf {
 
 static thread_local char g_err[512] = "";
@@ -379,6 +384,51 @@ int hf_block_select_cached(const hf_config* cfg, const void* Q, int32_t n_q, con
   return select_launches(cfg, Q, n_q, K_win, n_kv, n_cached_kv_blocks, k, block_idx, scores_or_null,
                          reinterpret_cast<float*>(ws + w.qbar), reinterpret_cast<float*>(ws + w.kbar),
                          static_cast<hipStream_t>(stream));
+}
+
+// device address of this GPU's copy of `scratch`, looked up once per device (each GPU holds its own copy at its
+// own address) with that device current
+static int static_scratch(unsigned char** ptr_out) {
+  constexpr int kDevices = 64;
+  static std::atomic<unsigned char*> known[kDevices];   // zero-initialised
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) {
+    set_error("hipGetDevice: %s", hipGetErrorString(hipGetLastError()));
+    return HF_ERR_HIP;
+  }
+  if (dev < 0 || dev >= kDevices) { set_error("device index %d outside [0, %d)", dev, kDevices); return HF_ERR_HIP; }
+  unsigned char* p = known[dev].load(std::memory_order_acquire);
+  if (!p) {
+    const hipError_t e = hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      (void)hipGetLastError();
+      set_error("hipGetSymbolAddress(scratch) on device %d: %s", dev, hipGetErrorString(e));
+      return HF_ERR_HIP;
+    }
+    known[dev].store(p, std::memory_order_release);   // racing threads look up the same address
+  }
+  *ptr_out = p;
+  return HF_OK;
+}
+
+int hf_block_select_static(const hf_config* cfg, const void* Q, int32_t n_q, const void* K_win, int32_t n_kv,
+                           int32_t* block_idx, float* scores_or_null, void* stream) {
+  int k = 0;
+  HF_TRY(check_select_args(cfg, Q, n_q, K_win, n_kv, 0, block_idx, scores_or_null, &k));
+  // the pooled means are all the selection kernels need of the workspace
+  const size_t bh = (size_t)cfg->batch * cfg->heads, d = cfg->head_dim;
+  const size_t qbar_bytes = align256(bh * cdiv(n_q, cfg->block_q) * d * 4);
+  const size_t kbar_bytes = align256(bh * cdiv(n_kv, cfg->block_kv) * d * 4);
+  if (qbar_bytes + kbar_bytes > (size_t)HF_STATIC_SCRATCH_BYTES) {
+    set_error("hf_block_select_static: these sizes need %zu bytes of scratch, the built-in buffer holds %zu "
+              "(use hf_block_select with a workspace)", qbar_bytes + kbar_bytes, (size_t)HF_STATIC_SCRATCH_BYTES);
+    return HF_ERR_WORKSPACE;
+  }
+  unsigned char* base = nullptr;
+  HF_TRY(static_scratch(&base));
+  // nothing has to start at zero: the pooling kernel writes every mean before the ranking kernel reads it
+  return select_launches(cfg, Q, n_q, K_win, n_kv, 0, k, block_idx, scores_or_null, reinterpret_cast<float*>(base),
+                         reinterpret_cast<float*>(base + qbar_bytes), static_cast<hipStream_t>(stream));
 }
 
 int hf_hybrid_attn_fwd(const hf_config* cfg, const void* Q, int32_t n_q, const void* K_win,
