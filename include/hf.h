@@ -127,9 +127,11 @@ HF_API int hf_absorb_workspace_bytes(const hf_config* cfg, int32_t n_tokens, siz
  * identity.  The state is updated in place (fp32 accumulation; concurrent calls on the same
  * state from different streams are allowed only if the caller orders them).
  * workspace: optional scratch of >= hf_absorb_workspace_bytes(...) bytes, 256-byte aligned;
- * with it the slices of one head are summed by a second small kernel (fast path), with NULL
- * (or too small a buffer) they are added to the state with float atomics.  Same result up to
- * fp32 summation order. */
+ * with it the partial sums of a head's token slices meet there and are added in a fixed order
+ * (fast path: one launch for bf16, head_dim 128, ReLU, no rotation; results do not vary from run
+ * to run), with NULL (or too small a buffer) they are added to the state with float atomics.
+ * Same result up to fp32 summation order.  The workspace needs no initialisation; two calls that
+ * may overlap in time must not share one. */
 HF_API int hf_absorb_evicted(const hf_config* cfg, void* state,
                       const void* K_ev, const void* V_ev, int32_t n_tokens,
                       const float* rope_cos, const float* rope_sin,

@@ -8,14 +8,19 @@
 // LDS read.
 //
 // The kernel is bound by the HBM read of K_ev and V_ev, which at this size (tens of MB) is a
-// latency problem: a workgroup requests ALL the tokens of its run (up to 320) before it touches
-// the first one, so that a whole run is in flight per compute unit.  The evicted tokens of one
-// head are cut into slices, one workgroup each.  Slice partials are combined either
-//   - through a caller workspace: plain coalesced stores of the d x d + d partial, then a small
-//     reduction kernel adds the slices to the state (the fast path), or
-//   - with device-scope float atomics straight into the state (no workspace; the L2 atomic units
-//     retire one dword per channel and clock, which costs more than the read itself).
+// latency problem.  Two kernels:
+//   - absorb_quad_kernel (ReLU, no rotation, caller workspace: the fast path, see there): tiles travel
+//     global -> LDS directly, operands by transposing LDS reads, ONE launch that also reduces;
+//   - absorb_mfma_kernel (any feature map, rotated keys, or no workspace): register-staged, described above; a
+//     workgroup requests ALL the tokens of its run (up to 320) before it touches the first one.  The evicted
+//     tokens of one head are cut into slices, one workgroup each; slice partials are combined through the
+//     workspace by a small reduction kernel, or, without workspace, with device-scope float atomics straight
+//     into the state (the L2 atomic units retire one dword per channel and clock, which costs more than the
+//     read itself).
 #include <stdlib.h>
+
+#include <atomic>
+#include <random>
 
 #include "hf_common.h"
 
@@ -269,119 +274,266 @@ __global__ __launch_bounds__(NT, 1) void absorb_mfma_kernel(float* __restrict__ 
   }
 }
 
-// ---- the same update with tiles streamed global -> LDS directly (plain case: ReLU, no rotation, partials) ----
-// A workgroup requests a whole run of 9 tiles of 32 tokens (K and V, 144 KB: one workgroup per CU) before it
-// touches the first: buffer loads with the LDS bit, 16 bytes per lane, no staging registers, no LDS stores;
-// tokens past the slice's end arrive as zeros (descriptor range), which ReLU and the products leave at zero.
-// Tiles are row-major with swizzled 16-byte units; both MFMA operands want tokens as the contraction index,
-// i.e. features as rows, and come from gfx950's transposing LDS reads (ds_read_b64_tr_b16: a 16-lane group
-// fetches 4 token rows x 16 features, every lane receives the four tokens of its own feature).
+// ---- the plain case (ReLU, no rotation, workspace given): ONE launch, partials of a few fat slices ---------------
+// Work item = (head, token slice, quadrant of L).  The evicted tokens of a head are cut into a FEW slices (about
+// 256 / (4 heads) of them), and the four workgroups of a (head, slice) share its tokens: each accumulates one
+// 64 x 64 quadrant L[64a .. , 64b ..] over the slice, reading the matching halves of the K and V rows.  The four
+// run on the same XCD, so the slice crosses HBM once and is served to the other three from that XCD's L2.  Few
+// slices keep the partials small (slices x state size, 3-4 MB at the 832x480 shape, where one workgroup per 288
+// tokens wrote 13 MB); many quadrant workgroups keep every compute unit streaming.
+//
+// Tiles of 32 tokens x 64 features (128-byte rows) travel global -> LDS directly (buffer loads with the LDS bit,
+// 16 bytes per lane, 1 KB = 8 token rows per instruction) through a ring of kRing tiles per tensor that is kept
+// full: tile c + kRing - 1 is requested as soon as tile c - 1 is consumed.  Both MFMA operands want tokens as
+// the contraction index, i.e. features as rows, and come from transposing LDS reads (ds_read_b64_tr_b16) of the
+// row-major tiles; 16-byte unit u of row r sits at u ^ (4 (r >> 1 & 1)), which spreads the 4 rows x 64 bytes a
+// half-wavefront reads over all 64 banks.  Tokens past the slice's end arrive as zeros (descriptor range).
+//
+// The slices of a quadrant meet in the workspace: every workgroup stores its 64 x 64 partial (coalesced, through
+// LDS), then takes a ticket from the quadrant's arrival counter; the workgroup that draws the last ticket adds
+// the partials IN SLICE ORDER to the state (so the sum does not depend on who came last), and writes the
+// quadrant of the readout's two transposed bf16 planes when asked.  No second launch, nothing waits for anyone.
+// The counter needs no initialisation: its upper 48 bits carry a tag that the host draws per call, and a counter
+// whose tag is not this call's counts from zero (the last workgroup also leaves the count at zero, so that a
+// launch replayed from a captured graph, tag and all, finds it ready).
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
-constexpr int TT = 32;               // tokens per tile
-constexpr int RTILE = TT * D * 2;    // bytes of one tile of one tensor
-constexpr int RUN_TILES = 9;         // tiles requested up front
-constexpr int DMA_LDS = RUN_TILES * 2 * RTILE;
+constexpr int QT = 32;                  // tokens per tile
+constexpr int QROW = 128;               // bytes per token row of a tile (64 features)
+constexpr int QTILE = QT * QROW;        // bytes of one tile of one tensor
+constexpr int QSLOT = 4 * QTILE;        // a ring slot: a pair of tiles (even, odd) of both tensors, 64 tokens
+constexpr int QNT = 512;                // threads per workgroup: two groups of four wavefronts (even / odd tiles),
+                                        // one 32 x 32 tile of the quadrant per wavefront
+constexpr int LSTR = 68;                // floats per row of the staged 64 x 64 block (16-byte aligned rows)
+constexpr int QUADS = 4;
 
-__device__ __forceinline__ int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }   // see hf_bwd_mfma.hip
-
-__device__ __forceinline__ bf16x8 tr_frag(const char* tile, uint32_t base, int ft, int t2) {
-  const char* p0 = tile + (base ^ (64u * ft)) + 4096 * t2;
-  const char* p1 = tile + (base ^ (64u * ft) ^ 32u) + 4096 * t2 + 2048;
+__device__ __forceinline__ bf16x8 tr_frag64(const char* tile, uint32_t base, int ft, int t2) {
+  const char* p0 = tile + (base ^ (64u * ft)) + 2048 * t2;
   const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p1));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 1024));
   const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
   return __builtin_bit_cast(bf16x8, both);
 }
 
-__global__ __launch_bounds__(NT, 1) void absorb_dma_kernel(float* __restrict__ partials, const bf16_t* __restrict__ K,
-                                                           const bf16_t* __restrict__ V, int n, int head_stride,
-                                                           int tokens_per_slice, int slices) {
-  extern __shared__ __attribute__((aligned(16))) char smem[];   // RUN_TILES x (K tile, V tile)
-  const int bh = blockIdx.x / slices, slice = blockIdx.x - bh * slices;
+template <int kRing>
+__global__ __launch_bounds__(QNT) void absorb_quad_kernel(float* __restrict__ state, bf16_t* __restrict__ planes,
+                                                          unsigned long long* __restrict__ counters,
+                                                          float* __restrict__ partials, const bf16_t* __restrict__ K,
+                                                          const bf16_t* __restrict__ V, int n, int head_stride,
+                                                          int tokens_per_slice, int slices, int BH,
+                                                          unsigned long long tag) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];   // kRing x 2 x (K tile, V tile); later the staged block
+  static_assert(kRing * QSLOT >= (64 * LSTR + 64) * 4, "the staged block must fit in the ring");
+  static_assert(2 * (kRing - 2) <= 63, "vmcnt holds six bits");
+  __shared__ int s_last;
+  // consecutive workgroup ids go to consecutive XCDs: the four quadrants of a (head, slice) share one
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int item = xcd + 8 * (slot >> 2), quad = slot & 3;
+  if (item >= BH * slices) return;
+  const int bh = item / slices, slice = item - bh * slices;
+  const int qa = quad >> 1, qb = quad & 1;   // key-feature half, value-feature half
   const int t0 = slice * tokens_per_slice;
   const int t1 = min(n, t0 + tokens_per_slice);
+  const int npairs = (t1 - t0 + 2 * QT - 1) / (2 * QT);
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // wavefronts 0-3 take the even tiles, 4-7 the odd ones; within a group one 32 x 32 tile of the quadrant each
+  const int grp = wave >> 2, wa = (wave >> 1) & 1, wb = wave & 1;
   const int l32 = lane & 31, h = lane >> 5;
 
-  // transfer: wavefront w moves token rows 4 w .. 4 w + 3 of every tile (1 KB per instruction)
-  const int row = 4 * wave + (lane >> 4);
-  const int lane_off = row * (D * 2) + (((lane & 15) ^ swz(row)) * 16);
-  const uint32_t lds0 = (uint32_t)(uintptr_t)smem + 4 * wave * (D * 2);
-  auto fetch = [&](const bf16_t* base_ptr, uint32_t dst, int first) {   // rows [first, first + 32), zeros from t1 on
-    const uint64_t a = reinterpret_cast<uint64_t>(base_ptr + (size_t)bh * head_stride * D) + (uint64_t)first * (D * 2);
+  // transfer: a wavefront moves token rows 8 (w & 3) .. + 7 of its own group's tile, lane l the physical unit
+  // l & 7 of row l >> 3
+  const int row = 8 * (wave & 3) + (lane >> 3);
+  const int unit = (lane & 7) ^ (4 * ((row >> 1) & 1));
+  const int k_off = row * (D * 2) + 128 * qa + 16 * unit;
+  const int v_off = row * (D * 2) + 128 * qb + 16 * unit;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)smem + grp * (2 * QTILE) + 1024 * (wave & 3);
+  const uint64_t kbase = reinterpret_cast<uint64_t>(K + (size_t)bh * head_stride * D);
+  const uint64_t vbase = reinterpret_cast<uint64_t>(V + (size_t)bh * head_stride * D);
+  auto fetch = [&](int c) {   // pair c of the slice into slot c mod kRing; rows past t1 (and whole tiles) as zeros
+    const int first = t0 + (2 * c + grp) * QT;
     const int left = (t1 - first) * (D * 2);
-    const i32x4 desc = {(int)(uint32_t)a, (int)(uint32_t)(a >> 32), left > 0 ? left : 0, 0x00020000};
+    const uint64_t ka = kbase + (uint64_t)(left > 0 ? first : 0) * (D * 2);
+    const uint64_t va = vbase + (uint64_t)(left > 0 ? first : 0) * (D * 2);
+    const i32x4 kd = {(int)(uint32_t)ka, (int)(uint32_t)(ka >> 32), left > 0 ? left : 0, 0x00020000};
+    const i32x4 vd = {(int)(uint32_t)va, (int)(uint32_t)(va >> 32), left > 0 ? left : 0, 0x00020000};
+    const uint32_t dst = lds0 + (uint32_t)(c % kRing) * QSLOT;
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                 :: "s"(dst), "v"(lane_off), "s"(desc) : "memory", "m0");
+                 :: "s"(dst), "v"(k_off), "s"(kd) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(dst + QTILE), "v"(v_off), "s"(vd) : "memory", "m0");
   };
-  // operand addresses of a lane inside a tile (see tr_frag)
+  // operand address of a lane inside a tile: the 16-lane group g reads 4 token rows x 16 features, lane j of it
+  // supplies the 8-byte chunk (row 4 h + j / 4, features 4 (j % 4) .. + 4) and receives feature 16 (g & 1) + j
   uint32_t tb;
   {
     const int j = lane & 15, g = lane >> 4;
     const int key_l = 4 * h + (j >> 2);
-    const int c = (4 * (key_l & 3)) | ((2 * (g & 1) + ((j & 3) >> 1)) ^ h);
-    tb = key_l * (D * 2) + 16 * c + 8 * (j & 1);
+    const int low2 = 2 * (g & 1) + ((j & 3) >> 1);
+    tb = key_l * QROW + 64 * ((key_l >> 1) & 1) + 16 * low2 + 8 * (j & 1);   // ^ 64 ft, + 1024 x + 2048 t2
   }
 
-  const int mi0 = wave >> 1, nj0 = 2 * (wave & 1);   // this wavefront's key-feature tile and its two value-feature tiles
-  f32x16 acc[2];
+  f32x16 acc;
 #pragma unroll
-  for (int b = 0; b < 2; ++b)
+  for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+  float zacc = 0.0f;   // sum over this lane's tokens of phi(k) for key feature 64 qa + 32 wa + l32
+  const s16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+  bf16x8 kf[2], vf[2];   // fragments of the tile read in the previous trip (zeros before the first)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[b][r] = 0.0f;
-  float zacc = 0.0f;   // sum over tokens of phi(k) for key feature 32 mi0 + l32 (this lane's half of the tokens)
-
-  typedef short s16x8v __attribute__((ext_vector_type(8)));
-  const s16x8v zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-  auto consume = [&](const int c) {
-    const char* tK = smem + c * 2 * RTILE;
-    const char* tV = tK + RTILE;
+  for (int t2 = 0; t2 < 2; ++t2) kf[t2] = vf[t2] = __builtin_bit_cast(bf16x8, zero8);
+  auto contract = [&]() {
 #pragma unroll
     for (int t2 = 0; t2 < 2; ++t2) {
       // ReLU of bf16 values as a packed signed-integer max with zero
-      const bf16x8 af = __builtin_bit_cast(
-          bf16x8, __builtin_elementwise_max(__builtin_bit_cast(s16x8v, tr_frag(tK, tb, mi0, t2)), zero8));
+      const bf16x8 a = __builtin_bit_cast(bf16x8, __builtin_elementwise_max(__builtin_bit_cast(s16x8, kf[t2]), zero8));
 #pragma unroll
-      for (int e = 0; e < 8; ++e) zacc += static_cast<float>(af[e]);
-#pragma unroll
-      for (int b = 0; b < 2; ++b)
-        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(tV, tb, nj0 + b, t2), af, acc[b], 0, 0, 0);  // L^T tile
+      for (int e = 0; e < 8; ++e) zacc += static_cast<float>(a[e]);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t2], a, acc, 0, 0, 0);   // L^T tile
     }
   };
 
-  for (int run0 = t0; run0 < t1; run0 += RUN_TILES * TT) {
-    if (run0 > t0) __syncthreads();   // the previous run is consumed
-    // every wavefront issues the same 2 x RUN_TILES requests (tiles past the end have an empty descriptor), so
-    // that the number still in flight when tile c is needed is a constant
+  // The quadrant's arrival counter has to carry this call's tag before anybody's ticket is drawn.  One lane looks
+  // at it now (the load is this wavefront's oldest request, so it has returned once at most the transfers issued
+  // behind it are in flight) and claims it if the tag is another call's; whether this exchange or another
+  // workgroup's wins does not matter.  Two round trips to memory, hidden behind the first tiles' latency.
+  unsigned long long* const ctr = counters + (size_t)bh * QUADS + quad;
+  const bool claimer = tid == QNT - 64;
+  unsigned long long seen = 0;
+  if (claimer) asm volatile("global_load_dwordx2 %0, %1, off sc1" : "=&v"(seen) : "v"(ctr) : "memory");
+  // every wavefront issues the same two requests per pair (tiles past the end have an empty descriptor), so the
+  // number in flight when a tile is needed is a constant
 #pragma unroll
-    for (int c = 0; c < RUN_TILES; ++c) {
-      fetch(K, lds0 + c * 2 * RTILE, run0 + c * TT);
-      fetch(V, lds0 + c * 2 * RTILE + RTILE, run0 + c * TT);
-    }
-#pragma unroll
-    for (int c = 0; c < RUN_TILES; ++c) {
-      asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * (RUN_TILES - 1 - c)) : "memory");
-      __syncthreads();   // every wavefront's rows of tile c have landed
-      if (run0 + c * TT < t1) consume(c);   // uniform
-    }
+  for (int c = 0; c < kRing - 1; ++c) fetch(c);
+  if (claimer) {
+    asm volatile("s_waitcnt vmcnt(%1)" : "+v"(seen) : "n"(2 * (kRing - 1)) : "memory");
+    if ((seen >> 16) != tag)
+      (void)__hip_atomic_compare_exchange_strong(ctr, &seen, tag << 16, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT);
   }
-
-  // ---- hand the partial over: plain coalesced stores (16 contiguous bytes of a row of L per register group)
-  float* L = partials + ((size_t)bh * slices + slice) * PART;
+  for (int c = 0; c < npairs; ++c) {
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * (kRing - 2)) : "memory");   // this wavefront's rows of pair c
+    __syncthreads();              // ... and everybody's; everybody has read pair c - 1
+    fetch(c + kRing - 1);         // into the slot of pair c - 1
+    const char* tK = smem + (c % kRing) * QSLOT + grp * (2 * QTILE);
+    bf16x8 nk[2], nv[2];
 #pragma unroll
-  for (int b = 0; b < 2; ++b)
+    for (int t2 = 0; t2 < 2; ++t2) {
+      nk[t2] = tr_frag64(tK, tb, wa, t2);
+      nv[t2] = tr_frag64(tK + QTILE, tb, wb, t2);
+    }
+    contract();   // the previous trip's tile, while this trip's reads are on their way
+#pragma unroll
+    for (int t2 = 0; t2 < 2; ++t2) { kf[t2] = nk[t2]; vf[t2] = nv[t2]; }
+  }
+  contract();
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing may land in LDS once the ring's space is reused
+  __syncthreads();
+
+  // ---- the quadrant's partial: both groups' tiles summed in LDS (a lane holds 4 x 4 consecutive value features
+  // of ONE key feature), then row pieces of 256 bytes into this slice's partial, which has the state's layout
+  float* tile = reinterpret_cast<float*>(smem);   // [64 key features][LSTR]
+  float* zs = tile + 64 * LSTR;                   // [64]
+  zacc += __shfl_xor(zacc, 32, kWave);   // the two halves of a tile's tokens
+  float* trow = tile + (32 * wa + l32) * LSTR + 32 * wb + 4 * h;
+  if (grp == 0) {
+#pragma unroll
+    for (int rq = 0; rq < 4; ++rq)
+      *reinterpret_cast<float4*>(trow + 8 * rq) = make_float4(acc[4 * rq], acc[4 * rq + 1], acc[4 * rq + 2], acc[4 * rq + 3]);
+    if (wb == 0 && h == 0) zs[32 * wa + l32] = zacc;
+  }
+  __syncthreads();
+  if (grp == 1) {
 #pragma unroll
     for (int rq = 0; rq < 4; ++rq) {
-      const int i = 32 * mi0 + l32;
-      const int j = 32 * (nj0 + b) + 8 * rq + 4 * h;
-      *reinterpret_cast<float4*>(L + i * D + j) =
-          make_float4(acc[b][4 * rq], acc[b][4 * rq + 1], acc[b][4 * rq + 2], acc[b][4 * rq + 3]);
+      float4 t = *reinterpret_cast<const float4*>(trow + 8 * rq);
+      t.x += acc[4 * rq]; t.y += acc[4 * rq + 1]; t.z += acc[4 * rq + 2]; t.w += acc[4 * rq + 3];
+      *reinterpret_cast<float4*>(trow + 8 * rq) = t;
     }
-  zacc += __shfl_xor(zacc, 32, kWave);   // the two halves of the tokens
-  if ((wave & 1) == 0 && h == 0) L[D * D + 32 * mi0 + l32] = zacc;   // one of the two wavefronts of a key tile
+    if (wb == 0 && h == 0) zs[32 * wa + l32] += zacc;
+  }
+  __syncthreads();
+  // Partials are exchanged between workgroups on different XCDs, whose L2 caches do not see each other's lines:
+  // they are written and read with device-scope accesses (they go through to memory; a device-scope FENCE would
+  // instead write back and invalidate the whole L2 of the XCD, per workgroup: measured 45-120 us per launch).
+  float* part = partials + ((size_t)bh * slices + slice) * PART;
+  const int er = tid >> 6, ec = tid & 63;   // a wavefront moves one 256-byte row piece; rows er + 8 p
+#pragma unroll
+  for (int p = 0; p < 8; ++p)
+    __hip_atomic_store(part + (64 * qa + er + 8 * p) * D + 64 * qb + ec, tile[(er + 8 * p) * LSTR + ec],
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (qb == 0 && tid < 64)
+    __hip_atomic_store(part + D * D + 64 * qa + tid, zs[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
+  // ---- arrival: every store above has been acknowledged before the workgroup draws its ticket
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (tid == 0) {   // (the claim above has long been carried out: the wait behind the loop covers it)
+    const unsigned long long before = __hip_atomic_fetch_add(ctr, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s_last = (int)(before & 0xffffull) + 1 == slices;
+    // the last one leaves the count at zero under this call's tag: a captured launch replays with the same tag
+    if (s_last) __hip_atomic_store(ctr, tag << 16, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  __syncthreads();
+  if (!s_last) return;
+
+  // ---- the last workgroup of the quadrant: state += partials in slice order; planes of the updated quadrant
+  // (these loads come from memory, not from L2: all eight of a thread for up to four slices are in flight at once)
+  const float* p0 = partials + (size_t)bh * slices * PART;
+  float* Lq = state + (size_t)bh * D * D;
+  // the slices are summed first and meet the state in ONE addition per call: over a long stream the state is much
+  // larger than a chunk's contribution, and every addition at its magnitude costs a rounding of its size
+  float sum[8], old[8];
+  const size_t at0 = (size_t)(64 * qa + er) * D + 64 * qb + ec;   // + 8 p rows
+#pragma unroll
+  for (int p = 0; p < 8; ++p) { old[p] = Lq[at0 + (size_t)8 * p * D]; sum[p] = 0.0f; }
+  const bool zrow = qb == 0 && tid < 64;
+  float* zq = state + (size_t)BH * D * D + (size_t)bh * D + 64 * qa + ec;
+  const float zold = zrow ? *zq : 0.0f;
+  float zsum = 0.0f;
+  constexpr int kBatch = 6;   // slices whose loads are in flight together (one round trip for the usual 4-6 slices)
+  for (int s0 = 0; s0 < slices; s0 += kBatch) {
+    float v[kBatch][8], zv[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const float* ps = p0 + (size_t)min(s0 + u, slices - 1) * PART;   // (past the last slice: re-read, not added)
+#pragma unroll
+      for (int p = 0; p < 8; ++p)
+        v[u][p] = __hip_atomic_load(ps + at0 + (size_t)8 * p * D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      zv[u] = zrow ? __hip_atomic_load(ps + D * D + 64 * qa + ec, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0f;
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u)
+      if (s0 + u < slices) {   // uniform; slice order
+#pragma unroll
+        for (int p = 0; p < 8; ++p) sum[p] += v[u][p];
+        zsum += zv[u];
+      }
+  }
+#pragma unroll
+  for (int p = 0; p < 8; ++p) sum[p] += old[p];
+  zsum += zold;
+#pragma unroll
+  for (int p = 0; p < 8; ++p) tile[(er + 8 * p) * LSTR + ec] = sum[p];
+  __syncthreads();   // (the planes' transposed reads; in front of the state's stores so that all stores leave together)
+#pragma unroll
+  for (int p = 0; p < 8; ++p) Lq[at0 + (size_t)8 * p * D] = sum[p];
+  if (zrow) *zq = zsum;
+  if (planes != nullptr) {
+    // planes[bh][plane][j][i]: thread (j, eighth) writes 8 consecutive key features i of value feature j
+    const int j = tid >> 3, i0 = 8 * (tid & 7);
+    uint32_t hw[4], lw[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float v0 = tile[(i0 + 2 * q) * LSTR + j], v1 = tile[(i0 + 2 * q + 1) * LSTR + j];
+      const bf16_t h0 = f32_to_bf16(v0), h1 = f32_to_bf16(v1);
+      hw[q] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+      lw[q] = (uint32_t)f32_to_bf16(v0 - bf16_to_f32(h0)) | ((uint32_t)f32_to_bf16(v1 - bf16_to_f32(h1)) << 16);
+    }
+    bf16_t* hi = planes + (size_t)bh * 2 * D * D + (size_t)(64 * qb + j) * D + 64 * qa + i0;
+    *reinterpret_cast<uint4*>(hi) = make_uint4(hw[0], hw[1], hw[2], hw[3]);
+    *reinterpret_cast<uint4*>(hi + D * D) = make_uint4(lw[0], lw[1], lw[2], lw[3]);
+  }
 }
 
 // state += sum over slices of the partials; one thread per 4 consecutive floats of a partial.
@@ -436,16 +588,9 @@ __global__ __launch_bounds__(256) void absorb_reduce_kernel(float* __restrict__ 
   *reinterpret_cast<uint2*>(hi + D * D) = make_uint2(lw[0], lw[1]);
 }
 
-// slice length (a multiple of the 64-token chunk) and slice count for n tokens
-// dma: the plan of absorb_dma_kernel, whose run is RUN_TILES tiles of 32 tokens
-void slice_plan(int BH, int n, bool with_workspace, bool dma, int& per, int& slices) {
-  if (with_workspace && dma) {
-    // one run (288 tokens) per workgroup, one workgroup per CU; longer slices only for very long inputs
-    const int run = RUN_TILES * TT;
-    const int max_slices = (1024 + BH - 1) / BH;
-    per = run;
-    if ((n + per - 1) / per > max_slices) per = ((n + max_slices - 1) / max_slices + run - 1) / run * run;
-  } else if (with_workspace) {
+// slice length (a multiple of the 64-token chunk) and slice count for n tokens: the register-staged kernel
+void slice_plan(int BH, int n, bool with_workspace, int& per, int& slices) {
+  if (with_workspace) {
     // one run (320 tokens) per workgroup until there are ~4 workgroups per compute unit, then longer slices
     const int max_slices = (1024 + BH - 1) / BH;
     per = RUN;
@@ -459,13 +604,75 @@ void slice_plan(int BH, int n, bool with_workspace, bool dma, int& per, int& sli
   slices = (n + per - 1) / per;
 }
 
+// the quadrant kernel: about one workgroup per compute unit (4 quadrants x BH heads x slices ~ 256), slices of whole tiles
+struct QuadPlan {
+  int per, slices;
+  size_t counters_bytes, total_bytes;
+};
+QuadPlan quad_plan(int BH, int n, int want_slices) {
+  const int tiles = (n + 2 * QT - 1) / (2 * QT);   // pairs of tiles
+  int sl = want_slices > 0 ? want_slices : (256 + 2 * BH) / (QUADS * BH);
+  if (sl < 1) sl = 1;
+  if (sl > tiles) sl = tiles;
+  if (sl > 4096) sl = 4096;   // the arrival counter holds 16 bits
+  QuadPlan p;
+  p.per = (tiles + sl - 1) / sl * (2 * QT);
+  p.slices = (n + p.per - 1) / p.per;
+  p.counters_bytes = ((size_t)BH * QUADS * sizeof(unsigned long long) + 255) & ~(size_t)255;
+  p.total_bytes = p.counters_bytes + (size_t)BH * p.slices * PART * sizeof(float);
+  return p;
+}
+
+// per-call tag of the arrival counters (48 bits): a process-wide sequence from a random start, so that neither
+// an earlier call's counters nor the uninitialised contents of a fresh workspace pass for this call's
+unsigned long long next_tag() {
+  static std::atomic<unsigned long long> seq{0};
+  unsigned long long cur = seq.load(std::memory_order_relaxed);
+  if (cur == 0) {
+    std::random_device rd;
+    unsigned long long start = (((unsigned long long)rd() << 32) ^ rd()) | 1ull;
+    seq.compare_exchange_strong(cur, start, std::memory_order_relaxed);   // (one thread's start wins)
+  }
+  return seq.fetch_add(1, std::memory_order_relaxed) & 0xffffffffffffull;
+}
+
 }  // namespace
 
 size_t absorb_mfma_workspace_bytes(const hf_config& c, int n) {
-  int per, slices, per2, slices2;   // whichever kernel runs: the larger of the two plans
-  slice_plan(c.batch * c.heads, n, true, false, per, slices);
-  slice_plan(c.batch * c.heads, n, true, true, per2, slices2);
-  return (size_t)c.batch * c.heads * (slices > slices2 ? slices : slices2) * PART * sizeof(float);
+  int per, slices;   // whichever kernel runs: the larger of the two plans
+  slice_plan(c.batch * c.heads, n, true, per, slices);
+  const size_t staged = (size_t)c.batch * c.heads * slices * PART * sizeof(float);
+  const size_t quad = quad_plan(c.batch * c.heads, n, 0).total_bytes;
+  return staged > quad ? staged : quad;
+}
+
+// ReLU without rotation, workspace given: one launch.  want_slices / ring: 0 = the plan's choice (other values:
+// tuning runs of a development harness)
+int launch_absorb_quad(const hf_config& c, float* state, const void* K, const void* V, int n, int head_stride,
+                       void* workspace, hipStream_t s, void* planes_out, int want_slices, int ring) {
+  const int BH = c.batch * c.heads;
+  const QuadPlan p = quad_plan(BH, n, want_slices);
+  const int items = BH * p.slices;
+  const dim3 grid(8 * QUADS * ((items + 7) / 8));
+  // four slots of 64 tokens (64 KB of LDS, three in flight per workgroup) measured as fast as eight and leave
+  // room for a second workgroup per compute unit
+  const bool deep = ring >= 8;
+  unsigned long long* counters = static_cast<unsigned long long*>(workspace);
+  float* partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + p.counters_bytes);
+  const unsigned long long tag = next_tag();
+#define HF_LAUNCH_QUAD(RING)                                                                                       \
+  do {                                                                                                             \
+    static LdsGrant grant;                                                                                         \
+    constexpr int lds = RING * QSLOT;                                                                              \
+    const int rc = grant_lds(grant, reinterpret_cast<const void*>(absorb_quad_kernel<RING>), lds, "the absorb kernel"); \
+    if (rc != HF_OK) return rc;                                                                                    \
+    hipLaunchKernelGGL((absorb_quad_kernel<RING>), grid, dim3(QNT), lds, s, state, static_cast<bf16_t*>(planes_out), \
+                       counters, partials, static_cast<const bf16_t*>(K), static_cast<const bf16_t*>(V), n,        \
+                       head_stride, p.per, p.slices, BH, tag);                                                              \
+  } while (0)
+  if (deep) HF_LAUNCH_QUAD(8); else HF_LAUNCH_QUAD(4);
+#undef HF_LAUNCH_QUAD
+  return check_launch("hf_absorb_evicted");
 }
 
 int launch_absorb_mfma(const hf_config& c, float* state, const void* K, const void* V, int n, int head_stride,
@@ -475,24 +682,12 @@ int launch_absorb_mfma(const hf_config& c, float* state, const void* K, const vo
   bf16_t* planes = static_cast<bf16_t*>(planes_out);   // NULL: the state alone
   const bool use_ws = workspace != nullptr && workspace_bytes >= absorb_mfma_workspace_bytes(c, n);
   const bool plain = (c.phi == HF_PHI_RELU) && cosv == nullptr;
-  const bool dma = plain && use_ws;
+  if (plain && use_ws) return launch_absorb_quad(c, state, K, V, n, head_stride, workspace, s, planes_out, 0, 0);
   int per, slices;
-  slice_plan(BH, n, use_ws, dma, per, slices);
+  slice_plan(BH, n, use_ws, per, slices);
   float* partials = use_ws ? static_cast<float*>(workspace) : nullptr;
   const bf16_t* Kp = static_cast<const bf16_t*>(K);
   const bf16_t* Vp = static_cast<const bf16_t*>(V);
-  if (dma) {
-    static LdsGrant grant;
-    const int rc_grant = grant_lds(grant, reinterpret_cast<const void*>(absorb_dma_kernel), DMA_LDS, "the absorb kernel");
-    if (rc_grant != HF_OK) return rc_grant;
-    hipLaunchKernelGGL(absorb_dma_kernel, dim3(BH * slices), dim3(NT), DMA_LDS, s, partials, Kp, Vp, n, head_stride, per,
-                       slices);
-    const int rc2 = check_launch("hf_absorb_evicted");
-    if (rc2 != HF_OK) return rc2;
-    hipLaunchKernelGGL(absorb_reduce_kernel, dim3((PART / 4 + 255) / 256, BH), dim3(256), 0, s, state, partials,
-                       slices, BH, planes);
-    return check_launch("hf_absorb_evicted(reduce)");
-  }
   const int heads_per_xcd = (BH + 7) / 8;
   const dim3 grid(use_ws ? BH * slices : 8 * heads_per_xcd * slices);
   if (plain) {
