@@ -95,6 +95,53 @@ def test_one_layer_step_832x480_all_heads():
     check_heads(w, cfg, L.k, Q, K, V, L.O, L.idx, states, range(w.heads))
 
 
+@pytest.mark.parametrize("flags,bound", [(0, 4e-3), (hf.HF_FLAG_HISTORY_TWO_PLANES, 4e-3), (hf.HF_FLAG_READOUT_KERNEL, 4e-3)])
+def test_history_term_alone_at_full_size(flags, bound):
+    """The history term (Eq. 3) on its own at the 832x480 shape, against the oracle's history_readout, per head.
+    (a) With V_win = 0 the sparse branch is exactly zero, so O IS the history term, rounded once to bf16: rel-L2
+    must stay within a few units of that rounding (2^-9 per element) whichever way the state enters the matrix
+    cores (one bf16 plane of L, two planes, or the stand-alone readout kernel).  (b) O - O_local of the saving
+    forward on the real V: both terms carry their own bf16 rounding, so the difference is noisier; it must still
+    meet the output bound of the path."""
+    w = wl.get("step_832x480")
+    cfg = cfg_of(w, flags=flags)
+    L = Layer(cfg, w)
+    Ks, Vs = [], []
+    for c in range(w.evicted_frames // w.chunk_frames):
+        K, V = wl.make_evicted(w, c)
+        Ks.append(K); Vs.append(V)
+        L.absorb(K.to(DEV), V.to(DEV))
+    states = oracle_state(Ks, Vs, w.head_dim)
+    Q, K, V = wl.make_qkv(w)
+    Qd, Kd, Vd = Q.to(DEV), K.to(DEV), V.to(DEV)
+    hf.hf_block_select(cfg, Qd, Kd, L.idx, None, L.ws)
+    # (a) the history term as the whole output
+    hf.hf_hybrid_attn_fwd(cfg, Qd, Kd, torch.zeros_like(Vd), L.idx, L.state, L.O, L.ws)
+    torch.cuda.synchronize()
+    Oa = wl.to_f64(L.O)
+    worst_a = 0.0
+    for h in range(w.heads):
+        ref = orc.history_readout(wl.to_f64(Q[0, h]), states[h][0], states[h][1], eps=cfg.eps, z_scale=cfg.z_scale)
+        assert np.abs(ref).mean() > 1e-3          # the term is not trivially small
+        worst_a = max(worst_a, rel_l2(Oa[0, h], ref))
+    print(f"history term alone, flags={flags}: worst rel-L2 over heads {worst_a:.3e}")
+    assert worst_a <= bound, worst_a
+    # (b) O - O_local of the saving forward (matrix-core path only)
+    if flags & hf.HF_FLAG_READOUT_KERNEL:
+        return
+    Ol = torch.empty_like(L.O)
+    lse = torch.empty((w.batch * w.heads, w.n_q), dtype=torch.float32, device=DEV)
+    hf.hf_hybrid_attn_fwd_save(cfg, Qd, Kd, Vd, L.idx, L.state, L.O, Ol, lse, L.ws)
+    torch.cuda.synchronize()
+    diff = wl.to_f64(L.O) - wl.to_f64(Ol)
+    worst_b = 0.0
+    for h in range(w.heads):
+        ref = orc.history_readout(wl.to_f64(Q[0, h]), states[h][0], states[h][1], eps=cfg.eps, z_scale=cfg.z_scale)
+        worst_b = max(worst_b, rel_l2(diff[0, h], ref))
+    print(f"O - O_local against the history term, flags={flags}: worst rel-L2 over heads {worst_b:.3e}")
+    assert worst_b <= BF16_REL_L2, worst_b
+
+
 def test_linear_map_folded_into_the_state_at_full_size():
     w = wl.get("step_832x480")
     cfg = cfg_of(w)
