@@ -25,9 +25,21 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
-# HBM-side bytes per launch of the sparse flash forward from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
-# (profiles/bench_step_832x480_hbm_traffic.txt: read 93.1 MB + written 15.3 MB, scaled by a 256 MiB copy)
-MEASURED_TRAFFIC_BYTES = {"step_832x480": 110.3e6}
+
+
+def profile_value(workload: str, kind: str, key: str):
+    """`key=value` line of profiles/bench_<workload>_<kind>.txt, as written by
+    `python -m paper_2604_10103_amd.profile_summary` from rocprofv3 runs of this file; None if there is no such
+    profile (the figure then stays out of the JSON line rather than being kept by hand)."""
+    path = os.path.join(ROOT, "profiles", f"bench_{workload}_{kind}.txt")
+    try:
+        for line in open(path):
+            if line.startswith(key + "="):
+                v = float(line.split("=", 1)[1])
+                return v if v == v else None
+    except (OSError, ValueError):
+        pass
+    return None
 
 
 def parse():
@@ -51,6 +63,8 @@ def parse():
                    help="time eager single-stream launches instead of one captured HIP graph per step")
     p.add_argument("--cpu-heads", type=int, default=0, help="heads per layer the oracle is timed on (0 = all)")
     p.add_argument("--cpu-layers", type=int, default=6, help="layer sets the oracle is timed on")
+    p.add_argument("--no-extras", action="store_true",
+                   help="skip the layer-stack run (30 layers x 4 steps) and the keep-ratio sweep at the large shape")
     p.add_argument("--calibration-copy-mib", type=int, default=0,
                    help="also run one plain device copy of this size (reference for HBM byte counters)")
     return p.parse_args()
@@ -64,6 +78,119 @@ def algorithmic_flops(idx_cpu, w):
     rows = np.minimum(b, w.n_q - np.arange(w.t_m) * b)                       # [T_m]
     keys = np.minimum(b, w.n_kv - idx * b).sum(axis=-1)                      # [B,H,T_m]
     return float(4.0 * w.head_dim * (keys * rows[None, None, :]).sum())
+
+
+def run_extras(hf, wl, torch, np, dev):
+    """Two further measurements, outside the timed step: the attention stack of one denoising pass (30 layers x 4
+    steps of the 832x480 layer call on 30 distinct layer sets, cached window half and state frozen across the
+    steps of a layer) and the keep-ratio sweep at the 1280x720 shape.  Inputs are drawn on the GPU from seeded
+    generators (no oracle runs on them; the parity tests cover these shapes with the CPU-seeded inputs)."""
+    out = {}
+
+    def gpu_randn(shape, seed, scale, dtype):
+        g = torch.Generator(device=dev).manual_seed(int(seed))
+        return (torch.randn(shape, generator=g, device=dev, dtype=torch.float32) * scale).to(dtype)
+
+    # ---- layer stack: 30 layers x 4 denoising steps = 120 select + attention calls
+    w = wl.get("step_832x480")
+    cfg = hf.make_config(w.batch, w.heads, w.head_dim, w.dtype, w.block, w.block, w.keep_ratio)
+    k = hf.hf_select_k(cfg, w.n_kv)
+    n_layers, n_steps = 30, 4
+    shape_q = (w.batch, w.heads, w.n_q, w.head_dim)
+    shape_kv = (w.batch, w.heads, w.n_kv, w.head_dim)
+    n_old = w.n_kv - w.n_q
+    aws = torch.empty(hf.hf_absorb_workspace_bytes(cfg, w.n_q), dtype=torch.uint8, device=dev)
+    layers = []
+    for l in range(n_layers):
+        K = gpu_randn(shape_kv, 40_000 + 100 * l + 1, w.scale, w.torch_dtype)
+        V = gpu_randn(shape_kv, 40_000 + 100 * l + 2, w.scale, w.torch_dtype)
+        st = torch.empty(hf.hf_state_bytes(cfg) // 4, dtype=torch.float32, device=dev)
+        hf.hf_state_init(cfg, st)
+        planes = torch.empty(hf.hf_state_planes_bytes(cfg), dtype=torch.uint8, device=dev)
+        hf.hf_absorb_evicted_planes(cfg, st, gpu_randn(shape_q, 45_000 + l, w.scale, w.torch_dtype),
+                                    gpu_randn(shape_q, 47_500 + l, w.scale, w.torch_dtype), planes, workspace=aws)
+        steps = []
+        for s in range(n_steps):   # per (layer, step): new queries and the chunk's own keys and values
+            steps.append((gpu_randn(shape_q, 40_000 + 100 * l + 10 * s, w.scale, w.torch_dtype),
+                          gpu_randn(shape_q, 40_000 + 100 * l + 10 * s + 3, w.scale, w.torch_dtype),
+                          gpu_randn(shape_q, 40_000 + 100 * l + 10 * s + 4, w.scale, w.torch_dtype)))
+        layers.append(dict(K=K, V=V, st=st, planes=planes, steps=steps,
+                           idx=torch.empty((w.batch, w.heads, w.t_m, k), dtype=torch.int32, device=dev),
+                           O=torch.empty(shape_q, dtype=w.torch_dtype, device=dev),
+                           ws=torch.empty(hf.hf_workspace_bytes(cfg, w.n_q, w.n_kv), dtype=torch.uint8, device=dev)))
+    reuse = n_old // w.block
+
+    def layer_call(L, s, events=None):
+        Q, Kc, Vc = L["steps"][s]
+        # the chunk's own K, V of this step take their place behind the cached half (the model's write, not timed)
+        L["K"][:, :, n_old:].copy_(Kc)
+        L["V"][:, :, n_old:].copy_(Vc)
+        if events is not None:
+            events[0].record()
+        # the pooled keys of the frozen half are reused after a layer's first step
+        hf.hf_block_select_cached(cfg, Q, L["K"], reuse if s > 0 else 0, L["idx"], None, L["ws"])
+        hf.hf_hybrid_attn_fwd_planes(cfg, Q, L["K"], L["V"], L["idx"], L["st"], L["planes"], L["O"])
+        if events is not None:
+            events[1].record()
+
+    for s in range(n_steps):          # warm-up pass (also leaves the pooled keys of every layer in its workspace)
+        for L in layers:
+            layer_call(L, s)
+    torch.cuda.synchronize()
+    evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in layers]
+           for _ in range(n_steps)]
+    for s in range(n_steps):
+        for i, L in enumerate(layers):
+            layer_call(L, s, evs[s][i])
+    torch.cuda.synchronize()
+    ts = np.array([[e[0].elapsed_time(e[1]) for e in row] for row in evs])   # [steps, layers] ms
+    out["stack_30x4"] = {
+        "workload": "30 layers x 4 denoising steps of the step_832x480 layer call (select + fused forward), 30 distinct "
+                    "layer sets (1.7 GB of K, V), cached window half and state frozen across a layer's steps",
+        "calls": int(ts.size), "total_ms": float(ts.sum()), "mean_ms": float(ts.mean()), "min_ms": float(ts.min()),
+        "max_ms": float(ts.max()), "first_step_mean_ms": float(ts[0].mean()), "later_steps_mean_ms": float(ts[1:].mean()),
+        "query_tokens_per_s": float(w.n_q * ts.size / (ts.sum() * 1e-3)), "timing": "HIP events around each call, eager launches"}
+    del layers
+
+    # ---- keep-ratio sweep at the 1280x720 shape
+    w = wl.get("large_1280x720")
+    shape_q = (w.batch, w.heads, w.n_q, w.head_dim)
+    shape_kv = (w.batch, w.heads, w.n_kv, w.head_dim)
+    sets = [(gpu_randn(shape_q, 50_000 + 10 * l, w.scale, w.torch_dtype), gpu_randn(shape_kv, 50_001 + 10 * l, w.scale, w.torch_dtype),
+             gpu_randn(shape_kv, 50_002 + 10 * l, w.scale, w.torch_dtype)) for l in range(2)]
+    O = torch.empty(shape_q, dtype=w.torch_dtype, device=dev)
+    sweep = []
+    for keep in (0.125, 0.25, 0.5, 1.0):
+        cfg = hf.make_config(w.batch, w.heads, w.head_dim, w.dtype, w.block, w.block, keep)
+        k = hf.hf_select_k(cfg, w.n_kv)
+        ws = torch.empty(hf.hf_workspace_bytes(cfg, w.n_q, w.n_kv), dtype=torch.uint8, device=dev)
+        idxs = [torch.empty((w.batch, w.heads, w.t_m, k), dtype=torch.int32, device=dev) for _ in sets]
+
+        def timed(fn, reps=3):
+            for i in range(len(sets)):
+                fn(i)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                for i in range(len(sets)):
+                    fn(i)
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / (reps * len(sets))
+
+        sel_ms = timed(lambda i: hf.hf_block_select(cfg, sets[i][0], sets[i][1], idxs[i], None, ws))
+        dense = keep >= 1.0
+        att_ms = timed(lambda i: hf.hf_hybrid_attn_fwd(cfg, sets[i][0], sets[i][1], sets[i][2], None if dense else idxs[i],
+                                                       None, O, ws))
+        fl = float(np.mean([algorithmic_flops(ix.cpu(), w) for ix in idxs]))
+        sweep.append({"keep_ratio": keep, "k": k, "select_ms": sel_ms, "sparse_flash_fwd_ms": att_ms,
+                      "tflops": fl / (att_ms * 1e-3) / 1e12, "frac_of_bf16_peak": fl / (att_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS})
+    base = sweep[-1]["sparse_flash_fwd_ms"]
+    for r in sweep:
+        r["speedup_over_dense_incl_select"] = base / (r["sparse_flash_fwd_ms"] + (0.0 if r["keep_ratio"] >= 1.0 else r["select_ms"]))
+    out["large_1280x720_keep_sweep"] = {"heads": w.heads, "n_q": w.n_q, "n_kv": w.n_kv, "block": w.block, "rows": sweep}
+    return out
 
 
 def main():
@@ -277,6 +404,23 @@ def main():
                                      max(3, min(a.steps, 12)))
         del bws, dO, dQ, dK, dV, Ol, lse
 
+    # ---- what the matrix cores sustain when they do nothing else: the MFMA of the attention kernels, two wavefronts
+    # per SIMD, non-trivial operands (a practical ceiling next to the nominal peak)
+    scratch4 = torch.zeros(4, dtype=torch.float32, device=dev)
+    probe_flops = hf.hf_probe_mfma_bf16(2000, scratch4)
+    torch.cuda.synchronize()
+    pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    pe[0].record()
+    for _ in range(3):
+        hf.hf_probe_mfma_bf16(2000, scratch4)
+    pe[1].record()
+    torch.cuda.synchronize()
+    mfma_ceiling_tflops = 3 * probe_flops / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e12
+
+    extras = {}
+    if not a.no_extras:
+        extras = run_extras(hf, wl, torch, np, dev)
+
     flops = float(np.mean([algorithmic_flops(s["idx"].cpu(), w) for s in sets]))
     dense_flops = 4.0 * w.head_dim * w.n_q * w.n_kv * w.heads * w.batch
     bh = w.batch * w.heads
@@ -307,8 +451,15 @@ def main():
                    "history_rope": bool(a.rope), "state_planes": "kept by the absorb call" if keep_planes else "converted per attention call"},
         "roofline": {"kernel": "sparse flash forward (Eq. 5)", "bound": "mfma", "achieved": a4_tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": a4_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if a.keep_ratio is None else None,
-                     "flops_per_launch": flops, "avg_ms": a4_ms, "min_ms": a4_min},
+                     # HBM-side bytes per launch (FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size) and the
+                     # kernel's average duration in the rocprofv3 trace, both read from profiles/ (null without)
+                     "traffic": profile_value(w.name, "hbm_traffic", "a4_hbm_bytes_per_launch") if a.keep_ratio is None else None,
+                     "flops_per_launch": flops, "avg_ms": a4_ms, "min_ms": a4_min,
+                     "avg_ms_timing": "HIP events around back-to-back launches over the rotated layer sets (gaps included)",
+                     "avg_ms_rocprofv3": (lambda v: None if v is None else v * 1e-3)(
+                         profile_value(w.name, "kernel_trace", "a4_avg_us") if a.keep_ratio is None else None),
+                     "mfma_issue_ceiling_tflops": mfma_ceiling_tflops,
+                     "frac_of_issue_ceiling": a4_tflops / mfma_ceiling_tflops},
         "kernels_ms": {"block_select": sel_ms, "block_select_cached_half": selc_ms, "attn_fwd_total": fwd_ms, "sparse_flash_fwd": a4_ms,
                        "readout_combine_unfused": a5_ms, "fused_epilogue_extra": max(fwd_ms - a4_ms, 0.0), "absorb": abs_ms,
                        "dense_window_fwd": dense_ms, "rope_tables_window": tab_ms, "rope_apply_k_window": ropek_ms},
@@ -330,6 +481,7 @@ def main():
                            # training pair: the forward that also writes O_local and the row statistic, and the
                            # backward pass that starts from them (2 algorithmic products less: no recomputed forward)
                            "fwd_save_ms": fwd_save_ms, "saved_ms": bwd_saved_ms}
+    out.update(extras)
     if dense_ms is not None:
         out["dense"] = {"tflops": dense_flops / (dense_ms * 1e-3) / 1e12,
                         "speedup_sparse_incl_select": dense_ms / (sel_ms + a4_ms),

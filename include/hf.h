@@ -399,6 +399,17 @@ HF_API int hf_rope_tables(const int32_t* frame_idx, int32_t n_frames, int32_t he
 HF_API int hf_rope_apply(const hf_config* cfg, const void* X, int32_t n_tokens,
                   const float* rope_cos, const float* rope_sin, void* Y, void* stream);
 
+/* ---- Measurement helper (no part of the method) ------------------------------------------------ */
+
+/* Enqueues a kernel in which 2048 wavefronts (two per SIMD of a 256-unit chip) each issue iters * 16 independent
+ * v_mfma_f32_32x32x16_bf16, the MFMA of the attention kernels, on non-trivial operands and nothing else:
+ * timed by the caller (events on `stream`), *flops_out / time is the rate the matrix cores sustain at the clock
+ * the chip holds under such a load, a practical ceiling to quote next to the nominal peak.
+ *   iters      in [1, 2^20]
+ *   scratch4   device, >= 4 bytes (never written in practice; keeps the products alive)
+ *   flops_out  HOST, may be NULL: floating-point operations of the launch */
+HF_API int hf_probe_mfma_bf16(int32_t iters, void* scratch4, double* flops_out, void* stream);
+
 /* Last error message of the calling thread (static storage, never NULL). */
 HF_API const char* hf_last_error(void);
 

@@ -106,13 +106,14 @@ def load():
     lib.hf_rope_window_indices.argtypes = [I, I, I, ctypes.POINTER(I)]
     lib.hf_rope_tables.argtypes = [ctypes.POINTER(I), I, I, I, I, I, I, ctypes.c_double, I, P, P, P]
     lib.hf_rope_apply.argtypes = [CP, P, I, P, P, P, P]
+    lib.hf_probe_mfma_bf16.argtypes = [I, P, ctypes.POINTER(ctypes.c_double), P]
     for name in ("hf_state_bytes", "hf_state_init", "hf_state_fold_linear", "hf_window_advance", "hf_absorb_evicted", "hf_absorb_workspace_bytes", "hf_select_k",
                  "hf_workspace_bytes",
                  "hf_block_select", "hf_block_select_cached", "hf_block_select_static", "hf_hybrid_attn_fwd",
                  "hf_hybrid_attn_fwd_split",
                  "hf_rope_window_indices", "hf_rope_tables", "hf_rope_apply", "hf_window_evict", "hf_stream_open_chunk",
                  "hf_stream_step", "hf_bwd_workspace_bytes", "hf_hybrid_attn_bwd", "hf_state_planes_bytes",
-                 "hf_state_planes", "hf_absorb_evicted_planes", "hf_hybrid_attn_fwd_planes"):
+                 "hf_state_planes", "hf_absorb_evicted_planes", "hf_hybrid_attn_fwd_planes", "hf_probe_mfma_bf16"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -385,6 +386,13 @@ def hf_hybrid_attn_fwd_save(cfg: hf_config, Q, K_win, V_win, block_idx, state, O
         _dev(O, "O", _tdtype(cfg), qs), _dev(O_local_out, "O_local_out", _tdtype(cfg), qs),
         _dev(lse2_out, "lse2_out", torch.float32, (B * H, n_q)),
         _dev(workspace, "workspace", torch.uint8), 0 if workspace is None else workspace.numel(), _stream()))
+
+
+def hf_probe_mfma_bf16(iters: int, scratch) -> float:
+    """Enqueue the MFMA issue-rate probe; returns the floating-point operations of the launch (time it with events)."""
+    flops = ctypes.c_double(0.0)
+    _check(load().hf_probe_mfma_bf16(int(iters), _dev(scratch, "scratch4", torch.float32), ctypes.byref(flops), _stream()))
+    return flops.value
 
 
 def hf_rope_window_indices(i_newest: int, n_frames: int, t0: int) -> list:

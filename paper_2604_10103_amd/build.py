@@ -31,6 +31,7 @@ SOURCES = [
     "hf_rope.hip",
     "hf_bwd.hip",
     "hf_bwd_mfma.hip",
+    "hf_probe.hip",
 ]
 
 FLAGS = [
