@@ -213,6 +213,43 @@ HF_API int hf_stream_step(const hf_config* cfg, const hf_window* win, const void
                    const void* state_or_null, const float* rope_cos_q, const float* rope_sin_q,
                    void* O, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- The same cache as a ring: eviction moves nothing -------------------------------------------------
+ * The cache buffers [B, H, cfg->kv_capacity, d] hold n_sink sink tokens in front and, behind them,
+ * (kv_capacity - n_sink) / n_chunk chunk slots of n_chunk tokens each, written round-robin.  "pop(0)" of the
+ * inference algorithm is then the slot about to be overwritten: hf_ring_open_chunk absorbs it into the linear
+ * state where it lies and hands the slot to the new chunk; no token of the cache is copied.
+ * The window that Eq. 4 and Eq. 5 see is the buffer in STORAGE order (sink, then the slots): softmax attention
+ * does not depend on the order of its keys, and the KV blocks of Eq. 4 are runs of block_kv tokens of the buffer,
+ * so that at most one block spans the seam between the newest and the oldest chunk (with the compacting cache
+ * above, blocks follow the temporal order instead).  Rotation tables are per token and therefore the caller's to
+ * lay out in storage order. */
+typedef struct hf_ring {
+  int32_t n_sink;      /* leading tokens that are never evicted */
+  int32_t n_chunk;     /* tokens per chunk slot; kv_capacity - n_sink must be a positive multiple of it */
+  int32_t n_filled;    /* slots that hold a chunk (the open one included); starts at 0 */
+  int32_t next_slot;   /* slot the next chunk goes to; starts at 0 */
+  int32_t cur_slot;    /* slot of the open chunk; starts at -1 */
+} hf_ring;
+
+/* Start of a chunk: if every slot is taken, the chunk in slot next_slot (the oldest) is absorbed into the state
+ * (Eq. 2; rope_*_ev: tables for its n_chunk tokens or both NULL; workspace as for hf_absorb_evicted) and
+ * *n_evicted_out = n_chunk, else 0.  *first_out = token offset of the slot: the caller writes the chunk's K, V
+ * there before each hf_ring_step (and the clean ones after the last).  Both outputs HOST, may be NULL. */
+HF_API int hf_ring_open_chunk(const hf_config* cfg, hf_ring* ring, void* K_cache, void* V_cache, void* state,
+                       const float* rope_cos_ev, const float* rope_sin_ev,
+                       void* workspace, size_t workspace_bytes,
+                       int32_t* first_out, int32_t* n_evicted_out, void* stream);
+
+/* One denoising step of the open chunk, as hf_stream_step: selection over the n_sink + n_filled * n_chunk valid
+ * tokens (after the chunk's first step only the KV blocks that touch the chunk's own slot are pooled again; the
+ * state's bf16 planes of the first step are reused) and hf_hybrid_attn_fwd_split.  Q, Q_hist: [B, H, n_chunk, d];
+ * block_idx: int32 [B, H, T_m, k] for that window length; workspace >= hf_workspace_bytes(cfg, n_chunk, n_kv),
+ * the same buffer on every step of a chunk. */
+HF_API int hf_ring_step(const hf_config* cfg, const hf_ring* ring, const void* Q, const void* Q_hist,
+                 const void* K_cache, const void* V_cache, int32_t step_in_chunk, int32_t* block_idx,
+                 const void* state_or_null, const float* rope_cos_q, const float* rope_sin_q,
+                 void* O, void* workspace, size_t workspace_bytes, void* stream);
+
 /* k of "sparse Top K" for a window of n_kv tokens (see keep_k / keep_ratio).  Host-only. */
 HF_API int hf_select_k(const hf_config* cfg, int32_t n_kv, int32_t* k_out);
 

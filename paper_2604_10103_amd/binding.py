@@ -50,6 +50,11 @@ class hf_window(ctypes.Structure):
     _fields_ = [("n_sink", ctypes.c_int32), ("n_tokens", ctypes.c_int32)]
 
 
+class hf_ring(ctypes.Structure):
+    _fields_ = [("n_sink", ctypes.c_int32), ("n_chunk", ctypes.c_int32), ("n_filled", ctypes.c_int32),
+                ("next_slot", ctypes.c_int32), ("cur_slot", ctypes.c_int32)]
+
+
 def make_config(batch, heads, head_dim, dtype, block_q, block_kv, keep_ratio=1.0, keep_k=0,
                 phi=HF_PHI_RELU, eps=1e-6, z_scale=1.0, softmax_scale=0.0, kv_capacity=0, flags=0) -> hf_config:
     if isinstance(dtype, str):
@@ -92,6 +97,9 @@ def load():
     WP = ctypes.POINTER(hf_window)
     lib.hf_stream_open_chunk.argtypes = [CP, WP, I, P, P, P, P, P, P, SZ, ctypes.POINTER(I), ctypes.POINTER(I), P]
     lib.hf_stream_step.argtypes = [CP, WP, P, P, I, P, P, I, P, P, P, P, P, P, SZ, P]
+    RP = ctypes.POINTER(hf_ring)
+    lib.hf_ring_open_chunk.argtypes = [CP, RP, P, P, P, P, P, P, SZ, ctypes.POINTER(I), ctypes.POINTER(I), P]
+    lib.hf_ring_step.argtypes = [CP, RP, P, P, P, P, I, P, P, P, P, P, P, SZ, P]
     lib.hf_select_k.argtypes = [CP, I, ctypes.POINTER(I)]
     lib.hf_workspace_bytes.argtypes = [CP, I, I, ctypes.POINTER(SZ)]
     lib.hf_block_select.argtypes = [CP, P, I, P, I, P, P, P, SZ, P]
@@ -113,7 +121,8 @@ def load():
                  "hf_hybrid_attn_fwd_split",
                  "hf_rope_window_indices", "hf_rope_tables", "hf_rope_apply", "hf_window_evict", "hf_stream_open_chunk",
                  "hf_stream_step", "hf_bwd_workspace_bytes", "hf_hybrid_attn_bwd", "hf_state_planes_bytes",
-                 "hf_state_planes", "hf_absorb_evicted_planes", "hf_hybrid_attn_fwd_planes", "hf_probe_mfma_bf16"):
+                 "hf_state_planes", "hf_absorb_evicted_planes", "hf_hybrid_attn_fwd_planes", "hf_probe_mfma_bf16",
+                 "hf_ring_open_chunk", "hf_ring_step"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -456,6 +465,48 @@ def hf_stream_step(cfg: hf_config, win: hf_window, Q, K_win, V_win, step_in_chun
         ctypes.byref(cfg), ctypes.byref(win), _dev(Q, "Q", _tdtype(cfg), (B, H, n_q, d)),
         _dev(Q_hist, "Q_hist", _tdtype(cfg), (B, H, n_q, d)), n_q,
         _dev(K_win, "K_win", _tdtype(cfg), (B, H, cap, d)), _dev(V_win, "V_win", _tdtype(cfg), (B, H, cap, d)),
+        int(step_in_chunk), _dev(block_idx, "block_idx", torch.int32, (B, H, t_m, k)),
+        _dev(state, "state", torch.float32, (hf_state_bytes(cfg) // 4,)),
+        _dev(rope_cos_q, "rope_cos_q", torch.float32, tab), _dev(rope_sin_q, "rope_sin_q", torch.float32, tab),
+        _dev(O, "O", _tdtype(cfg), (B, H, n_q, d)), _dev(workspace, "workspace", torch.uint8),
+        0 if workspace is None else workspace.numel(), _stream()))
+
+
+def make_ring(n_sink: int, n_chunk: int) -> hf_ring:
+    return hf_ring(int(n_sink), int(n_chunk), 0, 0, -1)
+
+
+def hf_ring_open_chunk(cfg: hf_config, ring: hf_ring, K_cache, V_cache, state, rope_cos_ev=None, rope_sin_ev=None,
+                       workspace=None):
+    """Hand the next chunk slot of the ring to a new chunk; the chunk it held (if any) goes into the state where it
+    lies.  Returns (token offset of the slot, tokens evicted) and updates ``ring``."""
+    B, H, d = cfg.batch, cfg.heads, cfg.head_dim
+    cap = cfg.kv_capacity
+    tab = (ring.n_chunk, d // 2)
+    first, n_ev = ctypes.c_int32(-1), ctypes.c_int32(-1)
+    _check(load().hf_ring_open_chunk(
+        ctypes.byref(cfg), ctypes.byref(ring), _dev(K_cache, "K_cache", _tdtype(cfg), (B, H, cap, d)),
+        _dev(V_cache, "V_cache", _tdtype(cfg), (B, H, cap, d)),
+        _dev(state, "state", torch.float32, (hf_state_bytes(cfg) // 4,)),
+        _dev(rope_cos_ev, "rope_cos_ev", torch.float32, tab), _dev(rope_sin_ev, "rope_sin_ev", torch.float32, tab),
+        _dev(workspace, "workspace", torch.uint8), 0 if workspace is None else workspace.numel(),
+        ctypes.byref(first), ctypes.byref(n_ev), _stream()))
+    return first.value, n_ev.value
+
+
+def hf_ring_step(cfg: hf_config, ring: hf_ring, Q, K_cache, V_cache, step_in_chunk: int, block_idx, state, O, workspace,
+                 rope_cos_q=None, rope_sin_q=None, Q_hist=None) -> None:
+    """Selection and hybrid attention of one denoising step over the ring's valid tokens, in storage order."""
+    B, H, d = cfg.batch, cfg.heads, cfg.head_dim
+    cap, n_q = cfg.kv_capacity, ring.n_chunk
+    n_kv = ring.n_sink + ring.n_filled * ring.n_chunk
+    t_m = _cdiv(n_q, cfg.block_q)
+    k = hf_select_k(cfg, n_kv)
+    tab = (n_q, d // 2)
+    _check(load().hf_ring_step(
+        ctypes.byref(cfg), ctypes.byref(ring), _dev(Q, "Q", _tdtype(cfg), (B, H, n_q, d)),
+        _dev(Q_hist, "Q_hist", _tdtype(cfg), (B, H, n_q, d)),
+        _dev(K_cache, "K_cache", _tdtype(cfg), (B, H, cap, d)), _dev(V_cache, "V_cache", _tdtype(cfg), (B, H, cap, d)),
         int(step_in_chunk), _dev(block_idx, "block_idx", torch.int32, (B, H, t_m, k)),
         _dev(state, "state", torch.float32, (hf_state_bytes(cfg) // 4,)),
         _dev(rope_cos_q, "rope_cos_q", torch.float32, tab), _dev(rope_sin_q, "rope_sin_q", torch.float32, tab),

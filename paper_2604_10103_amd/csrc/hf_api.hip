@@ -363,9 +363,9 @@ static int check_select_args(const hf_config* cfg, const void* Q, int32_t n_q, c
 // the two launches of a selection call; qbar / kbar = pooled means [BH, T_m, d] and (feature-group-major) [BH, d/4, T_n, 4]
 static int select_launches(const hf_config* cfg, const void* Q, int32_t n_q, const void* K_win, int32_t n_kv,
                            int32_t n_cached_kv_blocks, int k, int32_t* block_idx, float* scores_or_null, float* qbar,
-                           float* kbar, hipStream_t s) {
+                           float* kbar, hipStream_t s, int kv_end = -1) {
   const int t_m = cdiv(n_q, cfg->block_q), t_n = cdiv(n_kv, cfg->block_kv);
-  HF_TRY(launch_pool_both(*cfg, Q, n_q, t_m, K_win, n_kv, t_n, n_cached_kv_blocks, qbar, kbar, s));
+  HF_TRY(launch_pool_both(*cfg, Q, n_q, t_m, K_win, n_kv, t_n, n_cached_kv_blocks, kv_end < 0 ? t_n : kv_end, qbar, kbar, s));
   return launch_score_select(*cfg, qbar, kbar, t_m, t_n, k, block_idx, scores_or_null, s);
 }
 
@@ -613,6 +613,102 @@ int hf_stream_step(const hf_config* cfg, const hf_window* win, const void* Q, co
                     false, nullptr, nullptr, nullptr, 0, stream, static_cast<char*>(workspace) + w.planes);
   }
   return hf_hybrid_attn_fwd_split(cfg, Q, Q_hist, n_q, K_win, V_win, n_kv, block_idx, k, state_or_null, rope_cos_q,
+                                  rope_sin_q, O, workspace, workspace_bytes, stream);
+}
+
+static int check_ring(const hf_config* cfg, const hf_ring* r) {
+  if (!r) { set_error("ring is NULL"); return HF_ERR_NULL; }
+  if (cfg->kv_capacity < 1) { set_error("a ring needs cfg->kv_capacity"); return HF_ERR_SHAPE; }
+  if (r->n_sink < 0 || r->n_chunk < 1 || r->n_sink + r->n_chunk > cfg->kv_capacity ||
+      (cfg->kv_capacity - r->n_sink) % r->n_chunk != 0) {
+    set_error("ring: kv_capacity - n_sink = %d must be a positive multiple of n_chunk = %d", cfg->kv_capacity - r->n_sink,
+              r->n_chunk);
+    return HF_ERR_SHAPE;
+  }
+  const int slots = (cfg->kv_capacity - r->n_sink) / r->n_chunk;
+  if (r->n_filled < 0 || r->n_filled > slots || r->next_slot < 0 || r->next_slot >= slots || r->cur_slot < -1 ||
+      r->cur_slot >= slots || (r->n_filled < slots && r->next_slot != r->n_filled)) {
+    set_error("ring bookkeeping out of range: n_filled=%d next_slot=%d cur_slot=%d of %d slots", r->n_filled, r->next_slot,
+              r->cur_slot, slots);
+    return HF_ERR_SHAPE;
+  }
+  return HF_OK;
+}
+
+int hf_ring_open_chunk(const hf_config* cfg, hf_ring* ring, void* K_cache, void* V_cache, void* state,
+                       const float* rope_cos_ev, const float* rope_sin_ev, void* workspace, size_t workspace_bytes,
+                       int32_t* first_out, int32_t* n_evicted_out, void* stream) {
+  HF_TRY(check_cfg(cfg));
+  HF_TRY(check_ring(cfg, ring));
+  HF_TRY(check_ptr(K_cache, "K_cache", true));
+  HF_TRY(check_ptr(V_cache, "V_cache", true));
+  const int slots = (cfg->kv_capacity - ring->n_sink) / ring->n_chunk;
+  const int32_t first = ring->n_sink + ring->next_slot * ring->n_chunk;
+  int32_t evicted = 0;
+  if (ring->n_filled == slots) {
+    // "KV cache is full": the chunk in the slot about to be reused is the oldest; it goes into the linear state
+    // where it lies, and nothing else in the cache moves
+    HF_TRY(check_ptr(state, "state", true));
+    if ((rope_cos_ev == nullptr) != (rope_sin_ev == nullptr)) {
+      set_error("rope_cos_ev and rope_sin_ev must both be given or both be NULL");
+      return HF_ERR_NULL;
+    }
+    HF_TRY(check_ptr(rope_cos_ev, "rope_cos_ev", false));
+    HF_TRY(check_ptr(rope_sin_ev, "rope_sin_ev", false));
+    if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 255u)) {
+      set_error("workspace is not 256-byte aligned");
+      return HF_ERR_ALIGN;
+    }
+    const size_t skip = (size_t)first * cfg->head_dim * esize(cfg);
+    HF_TRY(launch_absorb(*cfg, static_cast<float*>(state), static_cast<char*>(K_cache) + skip,
+                         static_cast<char*>(V_cache) + skip, ring->n_chunk, cfg->kv_capacity, rope_cos_ev, rope_sin_ev,
+                         workspace, workspace ? workspace_bytes : 0, static_cast<hipStream_t>(stream)));
+    evicted = ring->n_chunk;
+  } else {
+    ring->n_filled += 1;
+  }
+  ring->cur_slot = ring->next_slot;
+  ring->next_slot = (ring->next_slot + 1) % slots;
+  if (first_out) *first_out = first;
+  if (n_evicted_out) *n_evicted_out = evicted;
+  return HF_OK;
+}
+
+int hf_ring_step(const hf_config* cfg, const hf_ring* ring, const void* Q, const void* Q_hist, const void* K_cache,
+                 const void* V_cache, int32_t step_in_chunk, int32_t* block_idx, const void* state_or_null,
+                 const float* rope_cos_q, const float* rope_sin_q, void* O, void* workspace, size_t workspace_bytes,
+                 void* stream) {
+  HF_TRY(check_cfg(cfg));
+  HF_TRY(check_ring(cfg, ring));
+  if (ring->cur_slot < 0) { set_error("no chunk is open (hf_ring_open_chunk first)"); return HF_ERR_SHAPE; }
+  if (step_in_chunk < 0) { set_error("step_in_chunk must be >= 0"); return HF_ERR_SHAPE; }
+  const int32_t n_q = ring->n_chunk, n_kv = ring->n_sink + ring->n_filled * ring->n_chunk;
+  int k = 0;
+  HF_TRY(check_select_args(cfg, Q, n_q, K_cache, n_kv, 0, block_idx, nullptr, &k));
+  const WorkspaceLayout w = workspace_layout(cfg, n_q, n_kv);
+  if (!workspace || workspace_bytes < w.total) {
+    set_error("workspace of %zu bytes needed, %zu given", w.total, workspace ? workspace_bytes : (size_t)0);
+    return HF_ERR_WORKSPACE;
+  }
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) { set_error("workspace is not 256-byte aligned"); return HF_ERR_ALIGN; }
+  // after the chunk's first step only the KV blocks that touch the chunk's own slot are pooled again
+  const int t_n = cdiv(n_kv, cfg->block_kv);
+  const int first = ring->n_sink + ring->cur_slot * ring->n_chunk;
+  int kv_first = 0, kv_end = t_n;
+  if (step_in_chunk > 0) {
+    kv_first = first / cfg->block_kv;
+    kv_end = cdiv(first + ring->n_chunk, cfg->block_kv);
+    if (kv_end > t_n) kv_end = t_n;
+  }
+  char* ws = static_cast<char*>(workspace);
+  HF_TRY(select_launches(cfg, Q, n_q, K_cache, n_kv, kv_first, k, block_idx, nullptr, reinterpret_cast<float*>(ws + w.qbar),
+                         reinterpret_cast<float*>(ws + w.kbar), static_cast<hipStream_t>(stream), kv_end));
+  if (step_in_chunk > 0 && state_or_null && attn_mfma_fused_supported(*cfg) && !(cfg->flags & HF_FLAG_READOUT_KERNEL)) {
+    // the state is frozen during a chunk's steps: its bf16 planes are as the chunk's first step left them here
+    return fwd_impl(cfg, Q, Q_hist, n_q, K_cache, V_cache, n_kv, block_idx, k, state_or_null, rope_cos_q, rope_sin_q, O,
+                    false, nullptr, nullptr, nullptr, 0, stream, ws + w.planes);
+  }
+  return hf_hybrid_attn_fwd_split(cfg, Q, Q_hist, n_q, K_cache, V_cache, n_kv, block_idx, k, state_or_null, rope_cos_q,
                                   rope_sin_q, O, workspace, workspace_bytes, stream);
 }
 

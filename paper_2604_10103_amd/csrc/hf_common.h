@@ -98,8 +98,9 @@ int launch_absorb(const hf_config& c, float* state, const void* K, const void* V
                   hipStream_t s, void* planes_out = nullptr);
 int launch_window_shift(const hf_config& c, void* K, void* V, int n_kv, int first, int n_evict, hipStream_t s);
 size_t absorb_workspace_bytes(const hf_config& c, int n);
+// pools every query block and the KV blocks [kv_first, kv_end); the other KV blocks keep what kbar_t holds
 int launch_pool_both(const hf_config& c, const void* Q, int n_q, int t_m, const void* K, int n_kv, int t_n,
-                     int kv_first, float* qbar, float* kbar_t, hipStream_t s);
+                     int kv_first, int kv_end, float* qbar, float* kbar_t, hipStream_t s);
 int launch_score_select(const hf_config& c, const float* qbar, const float* kbar_t, int t_m, int t_n,
                         int k, int32_t* idx, float* scores, hipStream_t s);
 int launch_attn(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,

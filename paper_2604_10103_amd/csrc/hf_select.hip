@@ -20,7 +20,7 @@ namespace {
 template <typename T, int D>
 __global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ Q, int n_q, int bq, int t_m,
                                                    const T* __restrict__ K, int n_kv, int kv_stride, int bkv,
-                                                   int t_n, int kv_first, float* __restrict__ qbar,
+                                                   int t_n, int kv_first, int kv_end, float* __restrict__ qbar,
                                                    float* __restrict__ kbar_t) {
   constexpr int E = Elem<T>::kPer16B;  // elements per 16-byte load
   constexpr int LPR = D / E;           // lanes covering one row
@@ -28,9 +28,9 @@ __global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ Q, int 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int blk = blockIdx.x * 4 + wave;
   const int bh = blockIdx.y;
-  if (blk >= t_m + t_n - kv_first) return;
+  if (blk >= t_m + kv_end - kv_first) return;
   const bool is_q = blk < t_m;
-  if (!is_q) blk += kv_first - t_m;  // KV blocks below kv_first keep the pooled means already stored
+  if (!is_q) blk += kv_first - t_m;  // KV blocks outside [kv_first, kv_end) keep the pooled means already stored
   const T* X = is_q ? Q : K;
   const int n = is_q ? n_q : n_kv, b = is_q ? bq : bkv;
   const int r0 = blk * b, r1 = min(n, r0 + b);
@@ -321,12 +321,12 @@ __global__ __launch_bounds__(512) void score_select3_kernel(const float* __restr
 }  // namespace
 
 int launch_pool_both(const hf_config& c, const void* Q, int n_q, int t_m, const void* K, int n_kv, int t_n,
-                     int kv_first, float* qbar, float* kbar_t, hipStream_t s) {
+                     int kv_first, int kv_end, float* qbar, float* kbar_t, hipStream_t s) {
   const int BH = c.batch * c.heads;
-  const dim3 grid((t_m + t_n - kv_first + 3) / 4, BH), block(256);
+  const dim3 grid((t_m + kv_end - kv_first + 3) / 4, BH), block(256);
 #define HF_LAUNCH_POOL(T, DD)                                                                                  \
   hipLaunchKernelGGL((pool_kernel<T, DD>), grid, block, 0, s, static_cast<const T*>(Q), n_q, c.block_q, t_m,   \
-                     static_cast<const T*>(K), n_kv, kv_stride_of(c, n_kv), c.block_kv, t_n, kv_first, qbar, kbar_t)
+                     static_cast<const T*>(K), n_kv, kv_stride_of(c, n_kv), c.block_kv, t_n, kv_first, kv_end, qbar, kbar_t)
   if (c.dtype == HF_BF16) {
     if (c.head_dim == 128) HF_LAUNCH_POOL(bf16_t, 128); else HF_LAUNCH_POOL(bf16_t, 64);
   } else {

@@ -134,3 +134,106 @@ def test_stream_with_sink_frames_matches_the_oracle_loop(name, sink_frames, rope
     Lg, zg = split_state(st, H, d)
     assert rel_l2(Lg, np.stack([s[0] for s in states])) <= (5e-3 if (rope and w.dtype == "bf16") else 1e-5)
     assert rel_l2(zg, np.stack([s[1] for s in states])) <= 1e-5
+
+
+@pytest.mark.parametrize("name,sink_frames,rope", [("small_bf16", 1, False), ("small_bf16", 0, True),
+                                                   ("tiny_f32", 2, False), ("small_b128", 1, True)])
+def test_ring_cache_evicts_without_moving_a_token_and_matches_the_oracle_loop(name, sink_frames, rope):
+    """The cache as a ring of chunk slots: opening a chunk absorbs the oldest chunk where it lies and changes no
+    other byte of the cache (nothing is copied).  The oracle keeps the cache as a list of chunks (pop(0) / append);
+    the window it is asked about is that list laid out in the ring's storage order, which is what the library
+    defines the blocks of Eq. 4 on (softmax attention itself does not depend on the order of its keys)."""
+    w = wl.get(name)
+    H, d, tpf = w.heads, w.head_dim, w.tokens_per_frame
+    n_chunk, n_sink, slots = w.n_q, sink_frames * tpf, 3
+    cap = n_sink + slots * n_chunk
+    cfg = cfg_of(w, kv_capacity=cap)
+    ring = hf.make_ring(n_sink, n_chunk)
+    Kc = torch.zeros((w.batch, H, cap, d), dtype=w.torch_dtype, device=DEV)
+    Vc = torch.zeros_like(Kc)
+    st = torch.empty(hf.hf_state_bytes(cfg) // 4, dtype=torch.float32, device=DEV)
+    hf.hf_state_init(cfg, st)
+    aws_n = hf.hf_absorb_workspace_bytes(cfg, n_chunk)
+    aws = torch.empty(aws_n, dtype=torch.uint8, device=DEV) if aws_n else None
+    ws = torch.empty(hf.hf_workspace_bytes(cfg, n_chunk, cap), dtype=torch.uint8, device=DEV)
+    O = torch.empty((w.batch, H, n_chunk, d), dtype=w.torch_dtype, device=DEV)
+
+    sinkK = [np.zeros((0, d)) for _ in range(H)]
+    sinkV = [np.zeros((0, d)) for _ in range(H)]
+    if n_sink:
+        Ks, Vs = wl.make_evicted(w, 900, n_sink)
+        Kc[:, :, :n_sink] = Ks.to(DEV)
+        Vc[:, :, :n_sink] = Vs.to(DEV)
+        sinkK = [wl.to_f64(Ks[0, h]) for h in range(H)]
+        sinkV = [wl.to_f64(Vs[0, h]) for h in range(H)]
+    chunks = []                       # oracle: list of (chunk number, K [H][n,d], V) oldest first
+    states = [orc.state_zero(d) for _ in range(H)]
+    rl, ma = (BF16_REL_L2, BF16_MAX_ABS) if w.dtype == "bf16" else (F32_REL_L2, 1e-4)
+    evictions = 0
+    for c in range(8):
+        before_K, before_V = Kc.clone(), Vc.clone()
+        full = len(chunks) == slots
+        tab_ev = wl.rope_tables(n_chunk, d, first_position=3.0 + c) if (rope and full) else (None, None)
+        first, n_ev = hf.hf_ring_open_chunk(cfg, ring, Kc, Vc, st, *(None if t is None else t.to(DEV) for t in tab_ev),
+                                            workspace=aws)
+        torch.cuda.synchronize()
+        assert first == n_sink + (c % slots) * n_chunk and n_ev == (n_chunk if full else 0)
+        # zero bytes copied: the cache is bit for bit what it was (the new chunk's slot still holds the old chunk)
+        assert torch.equal(Kc, before_K) and torch.equal(Vc, before_V)
+        if full:                      # pop(0): the oldest chunk goes into the linear state
+            _, ek, ev = chunks.pop(0)
+            for h in range(H):
+                states[h] = orc.state_absorb(*states[h], ek[h], ev[h], orc.PHI_RELU,
+                                             None if tab_ev[0] is None else wl.to_f64(tab_ev[0]),
+                                             None if tab_ev[1] is None else wl.to_f64(tab_ev[1]))
+            evictions += 1
+        n_kv = n_sink + ring.n_filled * n_chunk
+        k = hf.hf_select_k(cfg, n_kv)
+        t_m = -(-n_chunk // w.block)
+        idx = torch.full((w.batch, H, t_m, k), -1, dtype=torch.int32, device=DEV)
+        tab_q = wl.rope_tables(n_chunk, d, first_position=9.0) if rope else (None, None)
+        for step in range(3):
+            Kn, Vn = wl.make_evicted(w, 2000 + 10 * c + step, n_chunk)
+            Q = wl.randn((w.batch, H, n_chunk, d), 89_000 + 10 * c + step, w.scale, w.torch_dtype)
+            Kc[:, :, first:first + n_chunk] = Kn.to(DEV)
+            Vc[:, :, first:first + n_chunk] = Vn.to(DEV)
+            hf.hf_ring_step(cfg, ring, Q.to(DEV), Kc, Vc, step, idx, st, O, ws,
+                            *(None if t is None else t.to(DEV) for t in tab_q))
+            torch.cuda.synchronize()
+            Og, idxc = wl.to_f64(O), idx.cpu().numpy()
+            # the oracle's list, laid out in storage order: slot s holds the newest chunk with number = s mod slots
+            cur = (c, [wl.to_f64(Kn[0, h]) for h in range(H)], [wl.to_f64(Vn[0, h]) for h in range(H)])
+            by_slot = {num % slots: (kk, vv) for num, kk, vv in chunks + [cur]}
+            for h in range(H):
+                kk = np.concatenate([sinkK[h]] + [by_slot[s][0][h] for s in sorted(by_slot)])
+                vv = np.concatenate([sinkV[h]] + [by_slot[s][1][h] for s in sorted(by_slot)])
+                assert kk.shape[0] == n_kv
+                assert np.array_equal(wl.to_f64(Kc[0, h, :n_kv]), kk)          # the buffer IS that window
+                q = wl.to_f64(Q[0, h])
+                check_block_idx(idxc[0, h], orc.block_scores(q, kk, w.block, w.block), k)
+                ref = orc.hybrid_attention(q, kk, vv, states[h], w.block, w.block, k, orc.PHI_RELU,
+                                           None if tab_q[0] is None else wl.to_f64(tab_q[0]),
+                                           None if tab_q[1] is None else wl.to_f64(tab_q[1]),
+                                           cfg.eps, cfg.z_scale, block_idx=idxc[0, h])[0]
+                assert rel_l2(Og[0, h], ref) <= rl, (c, step, h, rel_l2(Og[0, h], ref))
+                assert max_abs(Og[0, h], ref) <= ma
+        chunks.append(cur)
+    assert evictions == 8 - slots
+    Lg, zg = split_state(st, H, d)
+    assert rel_l2(Lg, np.stack([s[0] for s in states])) <= (5e-3 if (rope and w.dtype == "bf16") else 1e-5)
+    assert rel_l2(zg, np.stack([s[1] for s in states])) <= 1e-5
+
+
+def test_ring_arguments_are_checked():
+    cfg = hf.make_config(1, 2, 128, "bf16", 64, 64, 0.25, kv_capacity=1000)
+    K = torch.zeros((1, 2, 1000, 128), dtype=torch.bfloat16, device=DEV)
+    st = torch.zeros(hf.hf_state_bytes(cfg) // 4, dtype=torch.float32, device=DEV)
+    with pytest.raises(hf.HFError) as e:                 # 1000 - 100 is no multiple of 400
+        hf.hf_ring_open_chunk(cfg, hf.make_ring(100, 400), K, K.clone(), st)
+    assert "multiple" in str(e.value)
+    ring = hf.make_ring(200, 400)
+    with pytest.raises(hf.HFError) as e:                 # no chunk open yet
+        hf.hf_ring_step(cfg, ring, K[:, :, :400].contiguous(), K, K, 0, torch.zeros((1, 2, 7, 1), dtype=torch.int32, device=DEV), st,
+                        torch.empty((1, 2, 400, 128), dtype=torch.bfloat16, device=DEV),
+                        torch.empty(1 << 20, dtype=torch.uint8, device=DEV))
+    assert "open" in str(e.value)

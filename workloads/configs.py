@@ -114,7 +114,10 @@ def rope_tables(n_tokens: int, head_dim: int, first_position: float = 0.0,
     """Synthetic per-token rotation tables cos, sin [n_tokens, d/2] in fp32.
 
     Token t sits at position first_position + t // tokens_per_position; pair i turns by
-    position * theta^(-2i/d).  These are caller-side inputs of the library, not part of it.
+    position * theta^(-2i/d).  INPUT GENERATION ONLY: these tables are data that a caller hands to the library
+    and to the oracle alike (like Q, K, V); neither side's rotary arithmetic lives here (the oracle's is
+    oracle/rope.py, pinned by its own tests; the library's is csrc/hf_rope.hip), and nothing of the method may be
+    added to this module.
     """
     pos = first_position + np.floor(np.arange(n_tokens, dtype=np.float64) / tokens_per_position)
     freq = theta ** (-2.0 * np.arange(head_dim // 2, dtype=np.float64) / head_dim)
