@@ -5,6 +5,8 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <random>
+
 #include "hf_common.h"
 
 // Scratch of hf_block_select_static (pooled block means), one copy per GPU the library runs on, held until the
@@ -44,6 +46,17 @@ int grant_lds(LdsGrant& g, const void* kernel, int bytes, const char* what) {
   }
   if (tracked) g.granted[dev].store(1, std::memory_order_release);
   return HF_OK;
+}
+
+unsigned long long next_call_tag() {
+  static std::atomic<unsigned long long> seq{0};
+  unsigned long long cur = seq.load(std::memory_order_relaxed);
+  if (cur == 0) {
+    std::random_device rd;
+    unsigned long long start = (((unsigned long long)rd() << 32) ^ rd()) | 1ull;
+    seq.compare_exchange_strong(cur, start, std::memory_order_relaxed);   // (one thread's start wins)
+  }
+  return seq.fetch_add(1, std::memory_order_relaxed) & 0xffffffffffffull;
 }
 
 static int check_cfg(const hf_config* c) {

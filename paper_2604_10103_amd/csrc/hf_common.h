@@ -82,6 +82,11 @@ struct LdsGrant {
 };
 int grant_lds(LdsGrant& g, const void* kernel, int bytes, const char* what);
 
+// Per-call tag (48 bits) of the arrival counters that kernels keep in caller workspaces: a process-wide sequence
+// from a random start, so that neither an earlier call's counters nor the uninitialised contents of a fresh
+// workspace pass for this call's.  A counter word is (tag << 16) | count.
+unsigned long long next_call_tag();
+
 struct Dims {
   int B, H, D, BH;
   int n_q, n_kv, bq, bkv, t_m, t_n;

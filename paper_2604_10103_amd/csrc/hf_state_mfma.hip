@@ -19,9 +19,6 @@
 //     read itself).
 #include <stdlib.h>
 
-#include <atomic>
-#include <random>
-
 #include "hf_common.h"
 
 namespace hf {
@@ -623,19 +620,6 @@ QuadPlan quad_plan(int BH, int n, int want_slices) {
   return p;
 }
 
-// per-call tag of the arrival counters (48 bits): a process-wide sequence from a random start, so that neither
-// an earlier call's counters nor the uninitialised contents of a fresh workspace pass for this call's
-unsigned long long next_tag() {
-  static std::atomic<unsigned long long> seq{0};
-  unsigned long long cur = seq.load(std::memory_order_relaxed);
-  if (cur == 0) {
-    std::random_device rd;
-    unsigned long long start = (((unsigned long long)rd() << 32) ^ rd()) | 1ull;
-    seq.compare_exchange_strong(cur, start, std::memory_order_relaxed);   // (one thread's start wins)
-  }
-  return seq.fetch_add(1, std::memory_order_relaxed) & 0xffffffffffffull;
-}
-
 }  // namespace
 
 size_t absorb_mfma_workspace_bytes(const hf_config& c, int n) {
@@ -659,7 +643,7 @@ int launch_absorb_quad(const hf_config& c, float* state, const void* K, const vo
   const bool deep = ring >= 8;
   unsigned long long* counters = static_cast<unsigned long long*>(workspace);
   float* partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + p.counters_bytes);
-  const unsigned long long tag = next_tag();
+  const unsigned long long tag = next_call_tag();
 #define HF_LAUNCH_QUAD(RING)                                                                                       \
   do {                                                                                                             \
     static LdsGrant grant;                                                                                         \
