@@ -2,10 +2,15 @@
 """Benchmark of the hybrid-attention hot path on one MI355X.
 
 A step is one pass of the whole path for one layer and one chunk of the 832x480 streaming
-workload: hf_block_select + hf_hybrid_attn_fwd (block-sparse flash forward, history readout,
-sum) + hf_absorb_evicted (one evicted chunk).  Inputs are seeded synthetic tensors already
-resident in HBM; several layers' worth of tensors are rotated so that consecutive steps do
-not find their inputs in the 256 MB Infinity Cache.
+workload: block selection (Eq. 4), block-sparse flash forward (Eq. 5), history readout and sum
+(Eq. 3, 6), and the state update for one evicted chunk (Eq. 2).  By default it runs as TWO
+launches: hf_pool_keys, then hf_step_fwd (every query block's workgroup selects its blocks
+itself, attends and adds the history term; workgroups of their own absorb the evicted chunk into
+the other of two state buffers, which becomes the state of the next step).  --separate-launches
+times the four launches of hf_block_select + hf_hybrid_attn_fwd_planes + hf_absorb_evicted_planes
+instead (also reported next to the default as ms_per_step_separate_launches).  Inputs are seeded
+synthetic tensors already resident in HBM; several layers' worth of tensors are rotated so that
+consecutive steps do not find their inputs in the 256 MB Infinity Cache.
 
 Prints ONE JSON line: metric = query tokens/s per layer, plus the roofline of the dominant
 kernel (the sparse flash forward, bf16 MFMA bound), HBM figures for absorb/readout, the
@@ -59,6 +64,9 @@ def parse():
     p.add_argument("--converted-planes", action="store_true",
                    help="let every attention call convert the state to its bf16 planes (hf_hybrid_attn_fwd) instead "
                         "of keeping them next to the state (hf_absorb_evicted_planes / hf_hybrid_attn_fwd_planes)")
+    p.add_argument("--separate-launches", action="store_true",
+                   help="the step as hf_block_select + hf_hybrid_attn_fwd_planes + hf_absorb_evicted_planes (four "
+                        "launches) instead of hf_pool_keys + hf_step_fwd (two)")
     p.add_argument("--eager", action="store_true",
                    help="time eager single-stream launches instead of one captured HIP graph per step")
     p.add_argument("--cpu-heads", type=int, default=0, help="heads per layer the oracle is timed on (0 = all)")
@@ -228,6 +236,8 @@ def main():
     aws_bytes = hf.hf_absorb_workspace_bytes(cfg, w.n_q)
     aws = torch.empty(aws_bytes, dtype=torch.uint8, device=dev) if aws_bytes else None
     keep_planes = (not a.converted_planes) and hf.hf_state_planes_bytes(cfg) > 0
+    # the two-launch step: bf16 / head_dim 128 shapes with kept planes, ReLU, no rotation of the absorbed keys
+    one_launch = keep_planes and not a.separate_launches and not a.rope
     for l in range(nl):
         Q, K, V = wl.make_qkv(w, layer=l)
         Ke, Ve = wl.make_evicted(w, 100 + l)
@@ -244,6 +254,11 @@ def main():
             idx=torch.empty((w.batch, w.heads, w.t_m, k), dtype=torch.int32, device=dev),
             O=torch.empty(Q.shape, dtype=Q.dtype, device=dev),
             ws=torch.empty(ws_bytes, dtype=torch.uint8, device=dev), Qc=Q, Kc=K, Vc=V))
+        if keep_planes and not a.rope:   # second state buffer, pooled keys and workspace of the two-launch step
+            sets[-1].update(
+                st2=torch.empty_like(st), planes2=torch.empty_like(planes), phase=0,
+                pooled=torch.empty(hf.hf_pooled_keys_bytes(cfg, w.n_kv), dtype=torch.uint8, device=dev),
+                sws=torch.empty(hf.hf_step_workspace_bytes(cfg, w.n_q, w.n_q), dtype=torch.uint8, device=dev))
     del prefill
     torch.cuda.synchronize()
 
@@ -254,7 +269,24 @@ def main():
         re_ = tuple(t.to(dev) for t in wl.rope_tables(w.n_q, w.head_dim, first_position=3.0,
                                                       tokens_per_position=w.tokens_per_frame))
 
-    def step(s, events=None):
+    def step_fused(s, events=None):
+        """hf_pool_keys + hf_step_fwd: the state alternates between the set's two buffers."""
+        ph = s["phase"]
+        st_in, pl_in = (s["st"], s["planes"]) if ph == 0 else (s["st2"], s["planes2"])
+        st_out, pl_out = (s["st2"], s["planes2"]) if ph == 0 else (s["st"], s["planes"])
+        if events is not None:
+            events[0].record()
+        hf.hf_pool_keys(cfg, s["K"], s["pooled"])
+        if events is not None:
+            events[1].record()
+        hf.hf_step_fwd(cfg, s["Q"], s["K"], s["V"], s["pooled"], st_in, pl_in, s["O"], s["idx"], s["Ke"], s["Ve"],
+                       st_out, pl_out, s["sws"])
+        if events is not None:
+            events[2].record()
+            events[3].record()
+        s["phase"] = 1 - ph
+
+    def step_separate(s, events=None):
         if events is not None:
             events[0].record()
         hf.hf_block_select(cfg, s["Q"], s["K"], s["idx"], None, s["ws"])
@@ -272,6 +304,8 @@ def main():
             hf.hf_absorb_evicted(cfg, s["st"], s["Ke"], s["Ve"], re_[0], re_[1], workspace=aws)
         if events is not None:
             events[3].record()
+
+    step = step_fused if one_launch else step_separate
 
     if a.calibration_copy_mib > 0:   # a copy of known size: what FETCH_SIZE / WRITE_SIZE read for it scales the rest
         src = torch.empty(a.calibration_copy_mib << 20, dtype=torch.uint8, device=dev)
@@ -294,6 +328,18 @@ def main():
         step(sets[i % nl], evs[i])
     torch.cuda.synchronize()
     wall_eager = time.perf_counter() - t0
+    step_calls_ms = None
+    if one_launch:
+        # per-call times of the two launches, then those of the separate calls (selection, attention with the
+        # history term, absorb) from eager steps of their own
+        step_calls_ms = {"pool_keys": float(np.mean([e[0].elapsed_time(e[1]) for e in evs])),
+                         "step_fwd": float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))}
+        for i in range(nl):
+            step_separate(sets[i % nl])
+        torch.cuda.synchronize()
+        for i in range(a.steps):
+            step_separate(sets[i % nl], evs[i])
+        torch.cuda.synchronize()
     sel_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in evs]))
     fwd_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in evs]))
     abs_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in evs]))
@@ -302,28 +348,45 @@ def main():
     # order, same stream as the eager step; what goes away is the host's launch gap between the six
     # kernels of a step).  One graph holds one pass over the rotated layer sets; a remainder of
     # steps runs from single-step graphs.
-    if a.eager:
-        wall, mode = wall_eager, "eager launches"
-    else:
+    def timed_graphs(step_fn, phases):
+        """`a.steps` steps of step_fn from captured graphs of one pass over the rotated sets each (`phases` of them,
+        replayed in turn: the two-launch step alternates its state buffers, so its second pass is a graph of its
+        own); a remainder of steps runs from single-step graphs.  Warm-up: whole passes."""
         def capture(group):
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g):
                 for s in group:
-                    step(s)
+                    step_fn(s)
             return g
-        g_all = capture(sets)
-        g_one = [capture([s]) for s in sets[:a.steps % nl]]
-        def run_steps(n):
-            for _ in range(n // nl):
-                g_all.replay()
-            for g in g_one[:n % nl]:
-                g.replay()
-        run_steps(max(a.warmup, nl))
+        torch.cuda.synchronize()
+        g_pass = [capture(sets) for _ in range(phases)]          # (capturing runs the host side: the phases advance)
+        n_pass, rem = a.steps // nl, a.steps % nl
+        # the remainder follows n_pass + warm-up passes: capture it in the phase the sets will have then
+        warm = -(-max(a.warmup, nl) // nl)
+        for _ in range((warm + n_pass) % phases):
+            for s in sets:
+                if "phase" in s:
+                    s["phase"] = 1 - s["phase"]
+        g_one = [capture([s]) for s in sets[:rem]]
+        for i in range(warm):
+            g_pass[i % phases].replay()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        run_steps(a.steps)
+        for i in range(n_pass):
+            g_pass[(warm + i) % phases].replay()
+        for g in g_one:
+            g.replay()
         torch.cuda.synchronize()
-        wall, mode = time.perf_counter() - t0, f"HIP graphs of {nl} steps"
+        return time.perf_counter() - t0
+
+    ms_separate = None
+    if a.eager:
+        wall, mode = wall_eager, "eager launches"
+    else:
+        wall = timed_graphs(step, 2 if one_launch else 1)
+        mode = f"HIP graphs of {nl} steps"
+        if one_launch:   # the four-launch step next to it, same sets, same way of launching
+            ms_separate = timed_graphs(step_separate, 1) * 1e3 / a.steps
     ms_per_step = wall * 1e3 / a.steps
 
     # ---- the sparse flash forward alone (no state => only that kernel runs), same inputs
@@ -344,6 +407,17 @@ def main():
         ts = [x.elapsed_time(y) / nl for x, y in ev]
         return float(np.mean(ts)), float(np.min(ts))
 
+    pool_ms = stepf_ms = selattn_ms = None
+    if "pooled" in sets[0]:
+        pool_ms, _ = time_calls(lambda s: hf.hf_pool_keys(cfg, s["K"], s["pooled"]), a.steps)
+        selattn_ms, _ = time_calls(lambda s: hf.hf_select_attn_fwd(cfg, s["Q"], s["K"], s["V"], s["pooled"], s["st"],
+                                                                   s["planes"], s["O"], s["idx"]), a.steps)
+        stepf_ms, _ = time_calls(lambda s: hf.hf_step_fwd(cfg, s["Q"], s["K"], s["V"], s["pooled"], s["st"], s["planes"],
+                                                          s["O"], s["idx"], s["Ke"], s["Ve"], s["st2"], s["planes2"],
+                                                          s["sws"]), a.steps)
+        for s in sets:   # (the state of the timed steps' last phase is the one the later measurements read)
+            if s["phase"]:
+                s["st"], s["st2"], s["planes"], s["planes2"], s["phase"] = s["st2"], s["st"], s["planes2"], s["planes"], 0
     a4_ms, a4_min = time_calls(
         lambda s: hf.hf_hybrid_attn_fwd(cfg, s["Q"], s["K"], s["V"], s["idx"], None, s["O"], s["ws"]), a.steps)
     # selection on the later denoising steps of a chunk: pooled keys of the unchanged older half reused
@@ -432,6 +506,10 @@ def main():
 
     out = {
         "metric": "hybrid-attn query tokens/s per layer (select + sparse flash fwd + readout + absorb)",
+        "step": ("hf_pool_keys + hf_step_fwd (2 launches: selection in the attention workgroups' prologue, absorb in "
+                 "workgroups of their own)") if one_launch else
+                "hf_block_select + hf_hybrid_attn_fwd + hf_absorb_evicted (4 launches)",
+        "ms_per_step_separate_launches": ms_separate,
         "value": w.n_q * w.batch / (ms_per_step * 1e-3),
         "unit": "query tokens/s",
         "n_gpus": 1,
@@ -462,7 +540,9 @@ def main():
                      "frac_of_issue_ceiling": a4_tflops / mfma_ceiling_tflops},
         "kernels_ms": {"block_select": sel_ms, "block_select_cached_half": selc_ms, "attn_fwd_total": fwd_ms, "sparse_flash_fwd": a4_ms,
                        "readout_combine_unfused": a5_ms, "fused_epilogue_extra": max(fwd_ms - a4_ms, 0.0), "absorb": abs_ms,
-                       "dense_window_fwd": dense_ms, "rope_tables_window": tab_ms, "rope_apply_k_window": ropek_ms},
+                       "dense_window_fwd": dense_ms, "rope_tables_window": tab_ms, "rope_apply_k_window": ropek_ms,
+                       "pool_keys": pool_ms, "select_attn_fwd": selattn_ms, "step_fwd": stepf_ms,
+                       "in_step_eager": step_calls_ms},
         "hbm": {"absorb_GBs": absorb_bytes / (abs_ms * 1e-3) / 1e9,
                 "absorb_frac": absorb_bytes / (abs_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
                 "readout_GBs": (readout_bytes / (a5_ms * 1e-3) / 1e9) if a5_ms > 0 else None,

@@ -339,6 +339,61 @@ HF_API int hf_hybrid_attn_fwd_planes(const hf_config* cfg, const void* Q_local, 
                        const float* rope_cos_q, const float* rope_sin_q,
                        void* O, void* stream);
 
+/* ---- Selection inside the attention launch (bf16, head_dim 128, block_q 64 or 128, T_n <= 1024) --------
+ * Eq. 4 scores a query block against the pooled keys of the whole window, but needs of Q only that block's own
+ * rows, which the attention workgroup of the block reads anyway.  So the Top-K of the "Hybrid Attention"
+ * algorithm can run in the prologue of that workgroup: hf_pool_keys pools K_win once (the only pass that has to
+ * finish before any block can choose), hf_select_attn_fwd does the rest in ONE launch: pooled query, Eq. 4,
+ * Top-K (ties to the lower index), Eq. 5 over the chosen blocks, Eq. 3 and Eq. 6 in the epilogue.  The scores
+ * and lists meet the same oracle bounds as hf_block_select's (fp32 sums in another order: not bit-identical to it).
+ *
+ * hf_pooled_keys_bytes: bytes of the pooled-key buffer for a window of n_kv tokens (host only).
+ * hf_pool_keys: pooled_K [B*H][d/4][T_n][4] fp32 (means over the real length of every KV block, 16-byte feature
+ *   groups outermost), 256-byte aligned, written for the KV blocks n_cached_kv_blocks .. T_n-1; the blocks before
+ *   keep what the buffer holds (the older part of the window does not change between the denoising steps of a
+ *   chunk; 0 <= n_cached_kv_blocks <= floor(n_kv / block_kv)).  Any dtype / head_dim the selection supports.
+ * hf_select_attn_fwd: arguments as hf_hybrid_attn_fwd_planes (Q_hist NULL = Q_local), except
+ *   pooled_K        from hf_pool_keys for exactly this K_win and n_kv
+ *   state_or_null   NULL: O = O_local and planes is ignored; else planes must be this state's planes
+ *   block_idx_out   out int32 [B, H, T_m, k], k = hf_select_k(cfg, n_kv): the list every query block chose,
+ *                   ascending (the kernel also reads it back)
+ *   scores_or_null  out fp32 [B, H, T_m, T_n] raw scores of Eq. 4, or NULL
+ * HF_ERR_SHAPE for configurations without this path (use hf_block_select + hf_hybrid_attn_fwd there). */
+HF_API int hf_pooled_keys_bytes(const hf_config* cfg, int32_t n_kv, size_t* bytes_out);
+HF_API int hf_pool_keys(const hf_config* cfg, const void* K_win, int32_t n_kv, int32_t n_cached_kv_blocks,
+                 void* pooled_K, void* stream);
+HF_API int hf_select_attn_fwd(const hf_config* cfg, const void* Q_local, const void* Q_hist, int32_t n_q,
+                       const void* K_win, const void* V_win, int32_t n_kv, const void* pooled_K,
+                       const void* state_or_null, const void* planes,
+                       const float* rope_cos_q, const float* rope_sin_q,
+                       void* O, int32_t* block_idx_out, float* scores_or_null, void* stream);
+
+/* ---- A whole step in one launch: hf_select_attn_fwd with Eq. 2 in workgroups of their own ------------
+ * The attending workgroups of one launch seldom fill every slot of the chip (888 workgroups on 1024 slots at the
+ * 832x480 shape) and the state update of Eq. 2 is independent of the attention that runs beside it if it goes to
+ * another buffer.  In the inference algorithm the chunk evicted NEXT is known during a chunk's last denoising step
+ * (the oldest chunk of the window): hf_step_fwd absorbs it while that step attends,
+ *     state_out = state_in + sum_t phi(k_t)^T v_t, sum_t phi(k_t)   over K_ev, V_ev        (Eq. 2)
+ *     planes_out = the bf16 planes of state_out (NULL: not written),
+ * and state_out / planes_out become the state of the next chunk's steps.  The attention reads state_in / planes
+ * exactly as hf_select_attn_fwd does (state_in NULL: O = O_local; the absorbed tokens then start from a zero
+ * state).  phi = ReLU and no rotation of the absorbed keys (else HF_ERR_SHAPE: use hf_absorb_evicted).
+ *   K_ev, V_ev   [B, H, ev_stride, d], the first n_ev tokens of every head are absorbed (ev_stride 0 = n_ev,
+ *                packed; a slice of the window cache itself may be passed with its head stride)
+ *   state_out, planes_out   must not overlap state_in / planes or any other argument
+ *   workspace    >= hf_step_workspace_bytes(cfg, n_q, n_ev) bytes, 256-byte aligned, no initialisation needed;
+ *                two launches that may overlap in time must not share one
+ * Every other argument as hf_select_attn_fwd. */
+HF_API int hf_step_workspace_bytes(const hf_config* cfg, int32_t n_q, int32_t n_ev, size_t* bytes_out);
+HF_API int hf_step_fwd(const hf_config* cfg, const void* Q_local, const void* Q_hist, int32_t n_q,
+                const void* K_win, const void* V_win, int32_t n_kv, const void* pooled_K,
+                const void* state_in, const void* planes,
+                const float* rope_cos_q, const float* rope_sin_q,
+                void* O, int32_t* block_idx_out, float* scores_or_null,
+                const void* K_ev, const void* V_ev, int32_t n_ev, int32_t ev_stride,
+                void* state_out, void* planes_out,
+                void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- Backward pass (training algorithm of the supplement) ------------------------------------------- */
 
 /* hf_hybrid_attn_fwd_split as the training algorithm's forward pass of the one denoising step per chunk that

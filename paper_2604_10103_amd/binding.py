@@ -105,6 +105,11 @@ def load():
     lib.hf_block_select.argtypes = [CP, P, I, P, I, P, P, P, SZ, P]
     lib.hf_block_select_cached.argtypes = [CP, P, I, P, I, I, P, P, P, SZ, P]
     lib.hf_block_select_static.argtypes = [CP, P, I, P, I, P, P, P]
+    lib.hf_pooled_keys_bytes.argtypes = [CP, I, ctypes.POINTER(ctypes.c_size_t)]
+    lib.hf_pool_keys.argtypes = [CP, P, I, I, P, P]
+    lib.hf_select_attn_fwd.argtypes = [CP, P, P, I, P, P, I, P, P, P, P, P, P, P, P, P]
+    lib.hf_step_workspace_bytes.argtypes = [CP, I, I, ctypes.POINTER(SZ)]
+    lib.hf_step_fwd.argtypes = [CP, P, P, I, P, P, I, P, P, P, P, P, P, P, P, P, P, I, I, P, P, P, SZ, P]
     lib.hf_hybrid_attn_fwd.argtypes = [CP, P, I, P, P, I, P, I, P, P, P, P, P, SZ, P]
     lib.hf_hybrid_attn_fwd_split.argtypes = [CP, P, P, I, P, P, I, P, I, P, P, P, P, P, SZ, P]
     lib.hf_hybrid_attn_fwd_save.argtypes = [CP, P, P, I, P, P, I, P, I, P, P, P, P, P, P, P, SZ, P]
@@ -122,7 +127,8 @@ def load():
                  "hf_rope_window_indices", "hf_rope_tables", "hf_rope_apply", "hf_window_evict", "hf_stream_open_chunk",
                  "hf_stream_step", "hf_bwd_workspace_bytes", "hf_hybrid_attn_bwd", "hf_state_planes_bytes",
                  "hf_state_planes", "hf_absorb_evicted_planes", "hf_hybrid_attn_fwd_planes", "hf_probe_mfma_bf16",
-                 "hf_ring_open_chunk", "hf_ring_step"):
+                 "hf_ring_open_chunk", "hf_ring_step", "hf_pooled_keys_bytes", "hf_pool_keys", "hf_select_attn_fwd",
+                 "hf_step_workspace_bytes", "hf_step_fwd"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -369,6 +375,85 @@ def hf_hybrid_attn_fwd_planes(cfg: hf_config, Q, K_win, V_win, block_idx, state,
         _dev(state, "state", torch.float32, (hf_state_bytes(cfg) // 4,)), _dev(planes, "planes", torch.uint8),
         _dev(rope_cos_q, "rope_cos_q", torch.float32, tab), _dev(rope_sin_q, "rope_sin_q", torch.float32, tab),
         _dev(O, "O", _tdtype(cfg), qs), _stream()))
+
+
+def hf_pooled_keys_bytes(cfg: hf_config, n_kv: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().hf_pooled_keys_bytes(ctypes.byref(cfg), n_kv, ctypes.byref(out)))
+    return out.value
+
+
+def hf_pool_keys(cfg: hf_config, K_win, pooled_K, n_cached_kv_blocks: int = 0, n_kv=None) -> None:
+    """Pooled keys of the window (Eq. 4's k-bar) for hf_select_attn_fwd; the first n_cached_kv_blocks keep their values."""
+    B, H, d = cfg.batch, cfg.heads, cfg.head_dim
+    n_kv = _kv_len(cfg, K_win, n_kv)
+    _check(load().hf_pool_keys(ctypes.byref(cfg), _dev(K_win, "K_win", _tdtype(cfg), (B, H, K_win.shape[2], d)), n_kv,
+                               n_cached_kv_blocks, _dev(pooled_K, "pooled_K", torch.uint8), _stream()))
+
+
+def hf_select_attn_fwd(cfg: hf_config, Q, K_win, V_win, pooled_K, state, planes, O, block_idx_out, scores=None,
+                       rope_cos_q=None, rope_sin_q=None, Q_hist=None, n_kv=None) -> None:
+    """Top-K selection (Eq. 4), sparse attention (Eq. 5) and history term (Eq. 3, 6) in one launch; the chosen
+    blocks are written to block_idx_out [B, H, T_m, k]."""
+    B, H, d = cfg.batch, cfg.heads, cfg.head_dim
+    n_q, n_kv = Q.shape[2], _kv_len(cfg, K_win, n_kv)
+    t_m, t_n = _cdiv(n_q, cfg.block_q), _cdiv(n_kv, cfg.block_kv)
+    if block_idx_out.dim() != 4:
+        raise ValueError("block_idx_out must be [B, H, T_m, k]")
+    k = block_idx_out.shape[3]
+    if k != hf_select_k(cfg, n_kv):
+        raise ValueError("block_idx_out must hold hf_select_k(cfg, n_kv) entries per row")
+    tab = (n_q, d // 2)
+    qs = (B, H, n_q, d)
+    _check(load().hf_select_attn_fwd(
+        ctypes.byref(cfg), _dev(Q, "Q", _tdtype(cfg), qs), _dev(Q_hist, "Q_hist", _tdtype(cfg), qs), n_q,
+        _dev(K_win, "K_win", _tdtype(cfg), (B, H, K_win.shape[2], d)),
+        _dev(V_win, "V_win", _tdtype(cfg), (B, H, K_win.shape[2], d)), n_kv,
+        _dev(pooled_K, "pooled_K", torch.uint8),
+        None if state is None else _dev(state, "state", torch.float32, (hf_state_bytes(cfg) // 4,)),
+        _dev(planes, "planes", torch.uint8),
+        _dev(rope_cos_q, "rope_cos_q", torch.float32, tab), _dev(rope_sin_q, "rope_sin_q", torch.float32, tab),
+        _dev(O, "O", _tdtype(cfg), qs), _dev(block_idx_out, "block_idx_out", torch.int32, (B, H, t_m, k)),
+        _dev(scores, "scores", torch.float32, (B, H, t_m, t_n)), _stream()))
+
+
+def hf_step_workspace_bytes(cfg: hf_config, n_q: int, n_ev: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().hf_step_workspace_bytes(ctypes.byref(cfg), n_q, n_ev, ctypes.byref(out)))
+    return out.value
+
+
+def hf_step_fwd(cfg: hf_config, Q, K_win, V_win, pooled_K, state_in, planes, O, block_idx_out, K_ev, V_ev, state_out,
+                planes_out, workspace, scores=None, rope_cos_q=None, rope_sin_q=None, Q_hist=None, n_kv=None,
+                n_ev=None) -> None:
+    """hf_select_attn_fwd with workgroups of their own that absorb K_ev, V_ev (Eq. 2) into state_out / planes_out
+    = state_in + their contribution, in the same launch.  n_ev: tokens of every head of K_ev to absorb (default:
+    all of its third dimension, which is also the head stride)."""
+    B, H, d = cfg.batch, cfg.heads, cfg.head_dim
+    n_q, n_kv = Q.shape[2], _kv_len(cfg, K_win, n_kv)
+    t_m, t_n = _cdiv(n_q, cfg.block_q), _cdiv(n_kv, cfg.block_kv)
+    if block_idx_out.dim() != 4:
+        raise ValueError("block_idx_out must be [B, H, T_m, k]")
+    k = block_idx_out.shape[3]
+    if k != hf_select_k(cfg, n_kv):
+        raise ValueError("block_idx_out must hold hf_select_k(cfg, n_kv) entries per row")
+    ev_stride = K_ev.shape[2]
+    n_ev = ev_stride if n_ev is None else int(n_ev)
+    tab = (n_q, d // 2)
+    qs = (B, H, n_q, d)
+    ns = hf_state_bytes(cfg) // 4
+    _check(load().hf_step_fwd(
+        ctypes.byref(cfg), _dev(Q, "Q", _tdtype(cfg), qs), _dev(Q_hist, "Q_hist", _tdtype(cfg), qs), n_q,
+        _dev(K_win, "K_win", _tdtype(cfg), (B, H, K_win.shape[2], d)),
+        _dev(V_win, "V_win", _tdtype(cfg), (B, H, K_win.shape[2], d)), n_kv,
+        _dev(pooled_K, "pooled_K", torch.uint8),
+        _dev(state_in, "state_in", torch.float32, (ns,)), _dev(planes, "planes", torch.uint8),
+        _dev(rope_cos_q, "rope_cos_q", torch.float32, tab), _dev(rope_sin_q, "rope_sin_q", torch.float32, tab),
+        _dev(O, "O", _tdtype(cfg), qs), _dev(block_idx_out, "block_idx_out", torch.int32, (B, H, t_m, k)),
+        _dev(scores, "scores", torch.float32, (B, H, t_m, t_n)),
+        _dev(K_ev, "K_ev", _tdtype(cfg), (B, H, ev_stride, d)), _dev(V_ev, "V_ev", _tdtype(cfg), (B, H, ev_stride, d)),
+        n_ev, ev_stride, _dev(state_out, "state_out", torch.float32, (ns,)), _dev(planes_out, "planes_out", torch.uint8),
+        _dev(workspace, "workspace", torch.uint8), 0 if workspace is None else workspace.numel(), _stream()))
 
 
 def hf_hybrid_attn_fwd_save(cfg: hf_config, Q, K_win, V_win, block_idx, state, O, O_local_out, lse2_out, workspace=None,

@@ -480,6 +480,158 @@ int hf_hybrid_attn_fwd_planes(const hf_config* cfg, const void* Q, const void* Q
                   nullptr, nullptr, nullptr, 0, stream, planes);
 }
 
+int hf_pooled_keys_bytes(const hf_config* cfg, int32_t n_kv, size_t* bytes_out) {
+  HF_TRY(check_cfg(cfg));
+  if (!bytes_out) { set_error("bytes_out is NULL"); return HF_ERR_NULL; }
+  HF_TRY(check_tokens(n_kv, "n_kv"));
+  *bytes_out = align256((size_t)cfg->batch * cfg->heads * cdiv(n_kv, cfg->block_kv) * cfg->head_dim * 4);
+  return HF_OK;
+}
+
+int hf_pool_keys(const hf_config* cfg, const void* K_win, int32_t n_kv, int32_t n_cached_kv_blocks, void* pooled_K,
+                 void* stream) {
+  HF_TRY(check_cfg(cfg));
+  HF_TRY(check_ptr(K_win, "K_win", true));
+  HF_TRY(check_ptr(pooled_K, "pooled_K", true));
+  HF_TRY(check_tokens(n_kv, "n_kv"));
+  HF_TRY(check_window_len(cfg, n_kv));
+  if (reinterpret_cast<uintptr_t>(pooled_K) & 255u) { set_error("pooled_K is not 256-byte aligned"); return HF_ERR_ALIGN; }
+  if (n_cached_kv_blocks < 0 || n_cached_kv_blocks > n_kv / cfg->block_kv) {
+    set_error("n_cached_kv_blocks=%d outside [0, %d] (whole KV blocks of the window)", n_cached_kv_blocks,
+              n_kv / cfg->block_kv);
+    return HF_ERR_SHAPE;
+  }
+  const int t_n = cdiv(n_kv, cfg->block_kv);
+  if (n_cached_kv_blocks == t_n) return HF_OK;   // nothing new to pool
+  // the pooling kernel with no query blocks: KV blocks [n_cached_kv_blocks, T_n)
+  return launch_pool_both(*cfg, nullptr, 0, 0, K_win, n_kv, t_n, n_cached_kv_blocks, t_n, nullptr,
+                          static_cast<float*>(pooled_K), static_cast<hipStream_t>(stream));
+}
+
+// the selecting launch; K_ev given: with workgroups that absorb those tokens into state_out / planes_out
+static int select_attn_impl(const hf_config* cfg, const void* Q, const void* Q_hist, int32_t n_q, const void* K_win,
+                            const void* V_win, int32_t n_kv, const void* pooled_K, const void* state_or_null,
+                            const void* planes, const float* rope_cos_q, const float* rope_sin_q, void* O,
+                            int32_t* block_idx_out, float* scores_or_null, const void* K_ev, const void* V_ev,
+                            int32_t n_ev, int32_t ev_stride, void* state_out, void* planes_out, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+  HF_TRY(check_cfg(cfg));
+  if (!attn_mfma_fused_supported(*cfg)) {
+    set_error("selection inside the attention launch covers bf16, head_dim 128, block_q 64 or 128 "
+              "(use hf_block_select + hf_hybrid_attn_fwd)");
+    return HF_ERR_SHAPE;
+  }
+  HF_TRY(check_ptr(Q, "Q", true));
+  if (!Q_hist) Q_hist = Q;
+  HF_TRY(check_ptr(K_win, "K_win", true));
+  HF_TRY(check_ptr(V_win, "V_win", true));
+  HF_TRY(check_ptr(pooled_K, "pooled_K", true));
+  HF_TRY(check_ptr(O, "O", true));
+  HF_TRY(check_ptr(block_idx_out, "block_idx_out", true));
+  HF_TRY(check_ptr(scores_or_null, "scores", false));
+  HF_TRY(check_tokens(n_q, "n_q"));
+  HF_TRY(check_tokens(n_kv, "n_kv"));
+  HF_TRY(check_window_len(cfg, n_kv));
+  if (reinterpret_cast<uintptr_t>(pooled_K) & 255u) { set_error("pooled_K is not 256-byte aligned"); return HF_ERR_ALIGN; }
+  if (O == Q || O == Q_hist || O == K_win || O == V_win || O == pooled_K || static_cast<void*>(block_idx_out) == O) {
+    set_error("O / block_idx_out alias another argument");
+    return HF_ERR_SHAPE;
+  }
+  if ((rope_cos_q == nullptr) != (rope_sin_q == nullptr)) {
+    set_error("rope_cos_q and rope_sin_q must both be given or both be NULL");
+    return HF_ERR_NULL;
+  }
+  const int t_n = cdiv(n_kv, cfg->block_kv);
+  if (t_n > kMaxFusedSelectBlocks) {
+    set_error("window has %d KV blocks; the attention kernel selects among at most %d (use hf_block_select)", t_n,
+              kMaxFusedSelectBlocks);
+    return HF_ERR_SHAPE;
+  }
+  const int k = select_k_of(cfg, t_n);
+  if (k > t_n) { set_error("keep_k=%d exceeds the %d KV blocks of the window", k, t_n); return HF_ERR_SHAPE; }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const float* kbar = static_cast<const float*>(pooled_K);
+  const float* st = static_cast<const float*>(state_or_null);
+  const size_t d = cfg->head_dim, bh = (size_t)cfg->batch * cfg->heads;
+  if (st) {
+    HF_TRY(check_planes_cfg(cfg, planes, "planes"));
+    if (planes == O) { set_error("planes aliases O"); return HF_ERR_SHAPE; }
+  }
+  if (!K_ev) {
+    if (!st) return launch_attn_mfma_select(*cfg, Q, n_q, K_win, V_win, n_kv, k, kbar, block_idx_out, scores_or_null, O, s);
+    return launch_attn_mfma_fused(*cfg, Q, n_q, K_win, V_win, n_kv, nullptr, k, planes, st + bh * d * d, rope_cos_q,
+                                  rope_sin_q, Q_hist, O, s, nullptr, nullptr, kbar, block_idx_out, scores_or_null);
+  }
+  // ---- with the absorbing workgroups
+  HF_TRY(check_ptr(V_ev, "V_ev", true));
+  HF_TRY(check_ptr(state_out, "state_out", true));
+  HF_TRY(check_tokens(n_ev, "n_ev"));
+  if (cfg->phi != HF_PHI_RELU) {
+    set_error("hf_step_fwd absorbs with phi = ReLU and no rotation only (use hf_absorb_evicted)");
+    return HF_ERR_SHAPE;
+  }
+  if (ev_stride == 0) ev_stride = n_ev;
+  if (ev_stride < n_ev) { set_error("ev_stride=%d is less than n_ev=%d", ev_stride, n_ev); return HF_ERR_SHAPE; }
+  if ((size_t)n_ev * d * 2 >= (1ull << 31)) { set_error("n_ev=%d tokens per head exceed the 2 GiB a descriptor spans", n_ev); return HF_ERR_SHAPE; }
+  if (planes_out) HF_TRY(check_planes_cfg(cfg, planes_out, "planes_out"));
+  const size_t state_bytes = bh * (d * d + d) * sizeof(float), planes_bytes = readout_planes_bytes(*cfg);
+  auto overlap = [](const void* a, size_t an, const void* b, size_t bn) {
+    const char* x = static_cast<const char*>(a);
+    const char* y = static_cast<const char*>(b);
+    return a && b && x < y + bn && y < x + an;
+  };
+  if (overlap(state_out, state_bytes, state_or_null, state_bytes) || overlap(planes_out, planes_bytes, planes, planes_bytes) ||
+      overlap(state_out, state_bytes, planes, planes_bytes) || overlap(planes_out, planes_bytes, state_or_null, state_bytes) ||
+      overlap(state_out, state_bytes, planes_out, planes_bytes) || state_out == O || planes_out == O ||
+      state_out == workspace || planes_out == workspace) {
+    set_error("state_out / planes_out overlap another argument (the attention of this launch still reads the old state)");
+    return HF_ERR_SHAPE;
+  }
+  const size_t need = step_absorb_workspace_bytes(*cfg, n_q, n_ev);
+  if (!workspace || workspace_bytes < need) {
+    set_error("workspace of %zu bytes needed, %zu given", need, workspace ? workspace_bytes : (size_t)0);
+    return HF_ERR_WORKSPACE;
+  }
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) { set_error("workspace is not 256-byte aligned"); return HF_ERR_ALIGN; }
+  const float* st_in = st;
+  if (!st_in) {
+    // no state yet: the absorbed tokens start from zero
+    HF_TRY(launch_fill_zero(static_cast<float*>(state_out), bh * (d * d + d), s));
+    st_in = static_cast<const float*>(state_out);   // (every element is read and written by the same thread)
+  }
+  return launch_attn_mfma_step(*cfg, Q, n_q, K_win, V_win, n_kv, k, kbar, block_idx_out, scores_or_null,
+                               st ? planes : nullptr, st ? st + bh * d * d : nullptr, rope_cos_q, rope_sin_q, Q_hist, O,
+                               K_ev, V_ev, n_ev, ev_stride, st_in, static_cast<float*>(state_out), planes_out, workspace, s);
+}
+
+int hf_select_attn_fwd(const hf_config* cfg, const void* Q, const void* Q_hist, int32_t n_q, const void* K_win,
+                       const void* V_win, int32_t n_kv, const void* pooled_K, const void* state_or_null,
+                       const void* planes, const float* rope_cos_q, const float* rope_sin_q, void* O,
+                       int32_t* block_idx_out, float* scores_or_null, void* stream) {
+  return select_attn_impl(cfg, Q, Q_hist, n_q, K_win, V_win, n_kv, pooled_K, state_or_null, planes, rope_cos_q, rope_sin_q,
+                          O, block_idx_out, scores_or_null, nullptr, nullptr, 0, 0, nullptr, nullptr, nullptr, 0, stream);
+}
+
+int hf_step_workspace_bytes(const hf_config* cfg, int32_t n_q, int32_t n_ev, size_t* bytes_out) {
+  HF_TRY(check_cfg(cfg));
+  if (!bytes_out) { set_error("bytes_out is NULL"); return HF_ERR_NULL; }
+  HF_TRY(check_tokens(n_q, "n_q"));
+  HF_TRY(check_tokens(n_ev, "n_ev"));
+  *bytes_out = attn_mfma_fused_supported(*cfg) ? step_absorb_workspace_bytes(*cfg, n_q, n_ev) : 0;
+  return HF_OK;
+}
+
+int hf_step_fwd(const hf_config* cfg, const void* Q, const void* Q_hist, int32_t n_q, const void* K_win,
+                const void* V_win, int32_t n_kv, const void* pooled_K, const void* state_in, const void* planes,
+                const float* rope_cos_q, const float* rope_sin_q, void* O, int32_t* block_idx_out,
+                float* scores_or_null, const void* K_ev, const void* V_ev, int32_t n_ev, int32_t ev_stride,
+                void* state_out, void* planes_out, void* workspace, size_t workspace_bytes, void* stream) {
+  HF_TRY(check_ptr(K_ev, "K_ev", true));
+  return select_attn_impl(cfg, Q, Q_hist, n_q, K_win, V_win, n_kv, pooled_K, state_in, planes, rope_cos_q, rope_sin_q, O,
+                          block_idx_out, scores_or_null, K_ev, V_ev, n_ev, ev_stride, state_out, planes_out, workspace,
+                          workspace_bytes, stream);
+}
+
 int hf_hybrid_attn_fwd_save(const hf_config* cfg, const void* Q, const void* Q_hist, int32_t n_q,
                             const void* K_win, const void* V_win, int32_t n_kv, const int32_t* block_idx,
                             int32_t k, const void* state_or_null, const float* rope_cos_q,

@@ -79,15 +79,435 @@ struct HistArgs {
   // by-products of an ordinary forward pass for the backward pass, each optional (kFused != 3):
   float* lse2_out;       // [BH][n_q] the same row statistic
   bf16_t* olocal_out;    // [BH][n_q][d] the sparse branch's output alone, rounded once
+  // kSel (the workgroup selects its own KV blocks, Eq. 4, before it attends to them):
+  const float* kbar_t;   // [BH][d/4][T_n][4] pooled keys, feature-group-major (pool kernel)
+  int32_t* idx_out;      // [BH][T_m][k] the ascending block list of every query block (also read back by the kernel)
+  float* scores_out;     // [BH][T_m][T_n] the scores A of Eq. 4, or NULL
 };
 
-// kFused: 0 = attention only, 1 = + history term for ReLU without rotation, 2 = + history term, general,
-// 3 = no output: the row statistics the backward pass needs
-template <int NW, int kFused>
+// ---- Eq. 4 and the Top-K of a query block inside the attention workgroup (kSel).
+// q-bar from the block's rows (they are read for the fragments anyway), A_j = q-bar . k-bar_j against the head's pooled
+// keys (wavefront w a slice of the head dimension, lane l the KV blocks l, l + 64, ...; partial sums meet in LDS in a
+// fixed order), rank by counting (strict comparison; the exact tie rule, lower index wins, only when a tie straddles
+// the k-th place), ascending list by ballot prefix sums.  The list is left in LDS at `sel` (k entries) and written to
+// idx_row.  All scratch lies in the tile space, which is not in use yet.  t_n <= kSelMaxBlocks.
+constexpr int kSelMaxBlocks = kMaxFusedSelectBlocks;
+
+template <int NW>
+__device__ __forceinline__ int* select_in_workgroup(char* smem, const bf16_t* Qh, int q0, int n_q, const float* kbar_head,
+                                                    int t_n, int k, int32_t* idx_row, float* scores_row) {
+  constexpr int NT = 64 * NW, BQ = 32 * NW, G = NT / 16, CW = D / 4 / NW;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int t_pad = (t_n + 3) & ~3;
+  float* qpart = reinterpret_cast<float*>(smem);      // [G][D] partial column sums
+  float* qbar = qpart + G * D;                          // [D]
+  float* part = qbar + D;                               // [NW][t_pad]
+  float* sc = part + NW * t_pad;                        // [t_pad]
+  int* sel = reinterpret_cast<int*>(sc + t_pad);        // [k]
+  int* wave_count = sel + t_n;                          // [2][NW]
+  const int rows = min(BQ, n_q - q0);
+  // the block's rows and, right behind them, the first pass of pooled keys: both are on their way while the
+  // pooled query is formed (the chain of this prologue is memory round trips, not arithmetic)
+  const int u16 = tid & 15, g = tid >> 4;
+  bf16x8 v[BQ / G];
+#pragma unroll
+  for (int i = 0; i < BQ / G; ++i)
+    v[i] = *reinterpret_cast<const bf16x8*>(Qh + (size_t)min(q0 + g + G * i, n_q - 1) * D + 8 * u16);
+  const float4* kt = reinterpret_cast<const float4*>(kbar_head) + (size_t)(wave * CW) * t_n;
+  constexpr int U = 48 / CW;   // KV blocks per lane and pass (3 or 6): 48 loads of 16 bytes in flight
+  float4 kv[U][CW];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int j = min(lane + 64 * u, t_n - 1);   // clamped: a valid address, the result is dropped
+#pragma unroll
+    for (int c = 0; c < CW; ++c) kv[u][c] = kt[(size_t)c * t_n + j];
+  }
+  {
+    // column sums of the thread's rows, two rows per instruction: (x_r, x_r') . (1, 1) + acc in fp32
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const bf16x2 one2 = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
+    const bf16x8 zero = {};
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
+#pragma unroll
+    for (int i = 0; i < BQ / G; i += 2) {
+      const bf16x8 r0 = (g + G * i < rows) ? v[i] : zero, r1 = (g + G * (i + 1) < rows) ? v[i + 1] : zero;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const bf16x2 pr = {r0[e], r1[e]};
+        acc[e] = __builtin_amdgcn_fdot2_f32_bf16(pr, one2, acc[e], false);
+      }
+    }
+    *reinterpret_cast<float4*>(qpart + g * D + 8 * u16) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    *reinterpret_cast<float4*>(qpart + g * D + 8 * u16 + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+  }
+  __syncthreads();
+  if (tid < D) {
+    float a = 0.0f;
+#pragma unroll
+    for (int gg = 0; gg < G; ++gg) a += qpart[gg * D + tid];
+    qbar[tid] = a * (1.0f / (float)rows);
+  }
+  if (tid < t_pad - t_n) sc[t_n + tid] = -INFINITY;   // padding never outranks a block
+  __syncthreads();
+
+  // ---- scores: wavefront w a slice of the head dimension, lane l the KV blocks l, l + 64, ...
+  const float4* q4 = reinterpret_cast<const float4*>(qbar) + wave * CW;
+  for (int j0 = lane; j0 < t_n; j0 += 64 * U) {
+    if (j0 != lane) {   // (uniform) windows of more than 64 U blocks: further passes
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int j = min(j0 + 64 * u, t_n - 1);
+#pragma unroll
+        for (int c = 0; c < CW; ++c) kv[u][c] = kt[(size_t)c * t_n + j];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float a0 = 0.0f, a1 = 0.0f;
+#pragma unroll
+      for (int c = 0; c < CW; c += 2) {
+        const float4 qa = q4[c], qb4 = q4[c + 1];
+        a0 = fmaf(qa.x, kv[u][c].x, a0); a0 = fmaf(qa.y, kv[u][c].y, a0);
+        a0 = fmaf(qa.z, kv[u][c].z, a0); a0 = fmaf(qa.w, kv[u][c].w, a0);
+        a1 = fmaf(qb4.x, kv[u][c + 1].x, a1); a1 = fmaf(qb4.y, kv[u][c + 1].y, a1);
+        a1 = fmaf(qb4.z, kv[u][c + 1].z, a1); a1 = fmaf(qb4.w, kv[u][c + 1].w, a1);
+      }
+      if (j0 + 64 * u < t_n) part[wave * t_pad + j0 + 64 * u] = a0 + a1;
+    }
+  }
+  __syncthreads();
+  for (int j = tid; j < t_n; j += NT) {
+    float a = part[j];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) a += part[w * t_pad + j];
+    sc[j] = a;
+    if (scores_row) scores_row[j] = a;
+  }
+  __syncthreads();
+
+  if (t_n <= 256) {
+    // ---- Top-K by the k-th largest key, found bit by bit (32 steps of a few comparisons and population counts, every
+    // wavefront for itself on the whole row: lane l holds the blocks l, l + 64, ...).  Keys order like the scores;
+    // kept: every block above the k-th key, and of the blocks equal to it the lowest indices (the tie rule).
+    uint32_t key[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int j = lane + 64 * e;
+      const uint32_t b = __float_as_uint(sc[min(j, t_pad - 1)] + 0.0f);   // (-0 counts as +0)
+      key[e] = j < t_n ? (b ^ ((b >> 31) ? 0xffffffffu : 0x80000000u)) : 0u;   // padding lies below every score
+    }
+    uint32_t kth = 0;
+    for (int bit = 31; bit >= 0; --bit) {
+      const uint32_t cand = kth | (1u << bit);
+      int cnt = 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) cnt += __popcll(__ballot(key[e] >= cand));
+      if (cnt >= k) kth = cand;   // uniform
+    }
+    int above = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) above += __popcll(__ballot(key[e] > kth));
+    const int ties_kept = k - above;
+    const unsigned long long below = (1ull << lane) - 1ull;
+    int base = 0, ties_seen = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int j = lane + 64 * e;
+      const bool eq = key[e] == kth;
+      const unsigned long long bal_eq = __ballot(eq);
+      const bool keep = key[e] > kth || (eq && ties_seen + __popcll(bal_eq & below) < ties_kept);
+      const unsigned long long bal = __ballot(keep);
+      const int pos = base + __popcll(bal & below);
+      if (keep && wave == 0) { sel[pos] = j; idx_row[pos] = j; }
+      base += __popcll(bal);
+      ties_seen += __popcll(bal_eq);
+    }
+    __syncthreads();
+    return sel;
+  }
+  // ---- rank and list (windows of more than 256 blocks), two blocks per thread and scan of the row (j and j + NT share every score they are
+  // compared with).  First pass: strict comparison only (blocks with equal scores share a rank), exact unless
+  // a tie straddles the k-th place, which shows as more than k blocks of rank < k; then the row is redone with the rule.
+  for (int pass = 0; pass < 2; ++pass) {
+    int base = 0;
+    for (int j0 = 0; j0 < t_n; j0 += 2 * NT) {   // uniform trip count: barriers inside
+      const int ja = j0 + tid, jb = ja + NT;
+      const float ma = ja < t_n ? sc[ja] : INFINITY, mb = jb < t_n ? sc[jb] : INFINITY;
+      int ra = 0, rb = 0;
+      if (pass == 0) {
+#pragma unroll 4
+        for (int o = 0; o < t_pad; o += 4) {
+          const float4 x = *reinterpret_cast<const float4*>(sc + o);
+          ra += (x.x > ma) ? 1 : 0; ra += (x.y > ma) ? 1 : 0; ra += (x.z > ma) ? 1 : 0; ra += (x.w > ma) ? 1 : 0;
+          rb += (x.x > mb) ? 1 : 0; rb += (x.y > mb) ? 1 : 0; rb += (x.z > mb) ? 1 : 0; rb += (x.w > mb) ? 1 : 0;
+        }
+      } else {
+        for (int o = 0; o < t_pad; o += 4) {
+          const float4 x = *reinterpret_cast<const float4*>(sc + o);
+          ra += (x.x > ma || (x.x == ma && o < ja)) ? 1 : 0;
+          ra += (x.y > ma || (x.y == ma && o + 1 < ja)) ? 1 : 0;
+          ra += (x.z > ma || (x.z == ma && o + 2 < ja)) ? 1 : 0;
+          ra += (x.w > ma || (x.w == ma && o + 3 < ja)) ? 1 : 0;
+          rb += (x.x > mb || (x.x == mb && o < jb)) ? 1 : 0;
+          rb += (x.y > mb || (x.y == mb && o + 1 < jb)) ? 1 : 0;
+          rb += (x.z > mb || (x.z == mb && o + 2 < jb)) ? 1 : 0;
+          rb += (x.w > mb || (x.w == mb && o + 3 < jb)) ? 1 : 0;
+        }
+      }
+      const bool keep_a = ja < t_n && ra < k, keep_b = jb < t_n && rb < k;
+      const unsigned long long bal_a = __ballot(keep_a), bal_b = __ballot(keep_b);
+      if (lane == 0) {
+        wave_count[wave] = __popcll(bal_a);
+        wave_count[NW + wave] = __popcll(bal_b);
+      }
+      __syncthreads();
+      const unsigned long long below = (1ull << lane) - 1ull;
+      int pos_a = base + __popcll(bal_a & below), pos_b = __popcll(bal_b & below), tot_a = 0, tot_b = 0;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        const int ca = wave_count[w], cb = wave_count[NW + w];
+        if (w < wave) { pos_a += ca; pos_b += cb; }
+        tot_a += ca;
+        tot_b += cb;
+      }
+      pos_b += base + tot_a;
+      if (keep_a && pos_a < k) { sel[pos_a] = ja; idx_row[pos_a] = ja; }
+      if (keep_b && pos_b < k) { sel[pos_b] = jb; idx_row[pos_b] = jb; }
+      base += tot_a + tot_b;
+      __syncthreads();
+    }
+    if (base == k) break;  // uniform over the workgroup
+  }
+  return sel;
+}
+
+// ---- Eq. 2 in workgroups of their own inside the attention launch (kSel instances; AbsorbArgs::role_blocks > 0).
+// A query block's workgroup occupies its compute-unit slot for the whole launch, and the launch seldom fills every
+// slot (888 workgroups on 1024 slots at the 832x480 shape): the first role_blocks workgroup ids therefore do not
+// attend.  Each takes one token slice of one head of the evicted chunk and accumulates that slice's 128 x 128
+// contribution  sum_t phi(k_t)^T v_t  (A operand phi(K)^T, B operand V, both by transposing reads of row-major
+// 16-token stages that travel global -> LDS directly, five stages in the tile space, four in flight) and  sum_t
+// phi(k_t)  (a B operand of ones), stores it as a partial, and the last workgroup of a head to arrive adds the
+// partials in slice order to state_in and writes state_out and its two bf16 planes.  state_out / planes_out are
+// other buffers than the ones the attending workgroups read: the chunk absorbed here is the one the NEXT chunk's
+// eviction removes, and nothing of this launch depends on it.  ReLU, no rotation.
+struct AbsorbArgs {
+  const bf16_t* K;         // [BH][stride][d] tokens to absorb (first n of every head)
+  const bf16_t* V;
+  int n, stride, slices, role_blocks, BH;
+  const float* state_in;   // L [BH][d][d] then z [BH][d]
+  float* state_out;
+  bf16_t* planes_out;      // [BH][2][d][d] or NULL
+  float* partials;         // [BH][slices][d*d + d]
+  unsigned long long* counters;   // [BH] arrival counters, (tag << 16) | count
+  unsigned long long tag;
+};
+
+template <int NW>
+__device__ __forceinline__ void absorb_role(char* smem, const AbsorbArgs& ab) {
+  constexpr int NT = 64 * NW;
+  constexpr int IB = 4 / NW;                 // 32-row blocks of key features per wavefront
+  constexpr int PARTB = 16 * KSTR;           // bytes of 16 tokens of K (or V)
+  constexpr int STAGE = 2 * PARTB;           // a stage: 16 tokens of K, then of V (8 KB)
+  constexpr int NSTG = 5;
+  constexpr int HP = (PARTB / 1024) / NW;    // 1 KB pieces (4 token rows) of a part per wavefront (2 or 1)
+  constexpr int PART = D * D + D;
+  typedef int i32x4 __attribute__((ext_vector_type(4)));
+  typedef short s16x4 __attribute__((ext_vector_type(4)));
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  int* const s_last = reinterpret_cast<int*>(smem);   // (the stages are dead when it is written)
+  const int wg = blockIdx.x;
+  if (wg >= ab.BH * ab.slices) return;      // (padding up to a multiple of eight workgroup ids)
+  const int bh = wg / ab.slices, slice = wg - bh * ab.slices;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, h = lane >> 5;
+  const int nst_total = (ab.n + 15) / 16;
+  const int st0 = (int)((long long)slice * nst_total / ab.slices);
+  const int nst = (int)((long long)(slice + 1) * nst_total / ab.slices) - st0;
+
+  const uint64_t kbase = reinterpret_cast<uint64_t>(ab.K + (size_t)bh * ab.stride * D);
+  const uint64_t vbase = reinterpret_cast<uint64_t>(ab.V + (size_t)bh * ab.stride * D);
+  const int head_bytes = ab.n * (D * 2);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+  int lane_off[HP];
+#pragma unroll
+  for (int j = 0; j < HP; ++j) {
+    const int r = 4 * (wave + NW * j) + (lane >> 4), u = lane & 15;
+    lane_off[j] = r * (D * 2) + ((u ^ (((r & 3) << 2) | ((r >> 2) & 3))) * 16);
+  }
+  // stage c of this slice (16 tokens from token 16 (st0 + c)) into slot c mod NSTG; stages past the slice's end
+  // get an empty descriptor (zeros, nothing read), so that every wavefront issues the same number of requests
+  auto fetch = [&](int c) {
+    const int start = __builtin_amdgcn_readfirstlane((st0 + c) * 16);
+    const int skip = start * (D * 2);
+    const int left = c < nst ? min(head_bytes - skip, 16 * D * 2) : 0;   // the slice's own tokens only
+    const uint32_t slot = lds0 + (uint32_t)(c % NSTG) * STAGE;
+#pragma unroll
+    for (int part = 0; part < 2; ++part) {
+      const uint64_t base = (part ? vbase : kbase) + (uint64_t)(uint32_t)(left > 0 ? skip : 0);
+      const i32x4 d2 = {(int)(uint32_t)base, (int)(uint32_t)(base >> 32), left > 0 ? left : 0, 0x00020000};
+#pragma unroll
+      for (int j = 0; j < HP; ++j) {
+        const uint32_t dst = slot + part * PARTB + 4 * (wave + NW * j) * KSTR;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                     :: "s"(dst), "v"(lane_off[j]), "s"(d2) : "memory", "m0");
+      }
+    }
+  };
+  // transposing reads of a 16-token part: feature 32 dt + l32 as the row, the lane's eight tokens as the k index
+  const int j16 = lane & 15, grp16 = lane >> 4;
+  const int key_l = 4 * h + (j16 >> 2);
+  const int w_l = (4 * (key_l & 3)) | ((2 * (grp16 & 1) + ((j16 & 3) >> 1)) ^ h);
+  const uint32_t rd = key_l * KSTR + w_l * 16 + 8 * (j16 & 1);
+  auto frag = [&](const char* part, int dt) {
+    const char* p = part + (rd ^ (64u * dt));
+    const char* q = part + ((rd ^ (64u * dt)) ^ 32u) + 2048;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(q));
+    const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return both;
+  };
+
+  // the head's arrival counter has to carry this call's tag before anybody's ticket is drawn: one lane looks at it
+  // now (its oldest request) and claims it if the tag is another call's
+  unsigned long long* const ctr = ab.counters + bh;
+  const bool claimer = tid == NT - 64;
+  unsigned long long seen = 0;
+  if (claimer) asm volatile("global_load_dwordx2 %0, %1, off sc1" : "=&v"(seen) : "v"(ctr) : "memory");
+#pragma unroll
+  for (int c = 0; c < NSTG - 1; ++c) fetch(c);
+  if (claimer) {
+    asm volatile("s_waitcnt vmcnt(%1)" : "+v"(seen) : "n"(2 * HP * (NSTG - 1)) : "memory");
+    if ((seen >> 16) != ab.tag)
+      (void)__hip_atomic_compare_exchange_strong(ctr, &seen, ab.tag << 16, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT);
+  }
+
+  f32x16 acc[IB][4], zacc[IB];
+#pragma unroll
+  for (int ib = 0; ib < IB; ++ib) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) zacc[ib][r] = 0.0f;
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[ib][jb][r] = 0.0f;
+  }
+  const s16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+  const s16x8 ones8 = {0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80, 0x3f80};   // bf16 1.0
+  for (int c = 0; c < nst; ++c) {
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(2 * HP * (NSTG - 2)) : "memory");   // this wavefront's rows of stage c
+    __syncthreads();             // ... and everybody's; everybody has read stage c - 1
+    fetch(c + NSTG - 1);         // into the slot of stage c - 1
+    const char* st = smem + (c % NSTG) * STAGE;
+    bf16x8 a[IB], b[4];
+#pragma unroll
+    for (int ib = 0; ib < IB; ++ib)   // phi = ReLU on bf16 values as a packed signed-integer max with zero
+      a[ib] = __builtin_bit_cast(bf16x8, __builtin_elementwise_max(frag(st, IB * wave + ib), zero8));
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb) b[jb] = __builtin_bit_cast(bf16x8, frag(st + PARTB, jb));
+#pragma unroll
+    for (int ib = 0; ib < IB; ++ib) {
+#pragma unroll
+      for (int jb = 0; jb < 4; ++jb) acc[ib][jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ib], b[jb], acc[ib][jb], 0, 0, 0);
+      zacc[ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ib], __builtin_bit_cast(bf16x8, ones8), zacc[ib], 0, 0, 0);
+    }
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // (requests past the slice's end were empty; the claim is done)
+
+  // ---- the slice's partial, in the state's layout.  Partials meet workgroups on other XCDs, whose L2 caches do not
+  // see each other's lines: device-scope stores and loads (through to memory), no fence.
+  float* part = ab.partials + ((size_t)bh * ab.slices + slice) * PART;
+#pragma unroll
+  for (int ib = 0; ib < IB; ++ib)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int i = 32 * (IB * wave + ib) + 8 * (r >> 2) + 4 * h + (r & 3);
+#pragma unroll
+      for (int jb = 0; jb < 4; ++jb)
+        __hip_atomic_store(part + i * D + 32 * jb + l32, acc[ib][jb][r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (l32 == 0) __hip_atomic_store(part + D * D + i, zacc[ib][r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  // ---- arrival: every store above has been acknowledged before the workgroup draws its ticket
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (tid == 0) {
+    const unsigned long long before = __hip_atomic_fetch_add(ctr, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *s_last = (int)(before & 0xffffull) + 1 == ab.slices;
+    // the last one leaves the count at zero under this call's tag: a captured launch replays with the same tag
+    if (*s_last) __hip_atomic_store(ctr, ab.tag << 16, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  __syncthreads();
+  if (!*s_last) return;
+
+  // ---- the head's last workgroup: state_out = state_in + (partials in slice order), one addition at the state's
+  // magnitude; a thread owns value feature j and a run of key features i, eight at a time, so that the planes
+  // [plane][j][i] leave as 16-byte pieces
+  constexpr int G = NT / D, RUN = D / G;
+  const int j = tid & (D - 1), i_begin = (tid / D) * RUN;
+  const float* p0 = ab.partials + (size_t)bh * ab.slices * PART;
+  const float* Lin = ab.state_in + (size_t)bh * D * D;
+  float* Lout = ab.state_out + (size_t)bh * D * D;
+  constexpr int KB = 8;   // slices whose loads are in flight together
+  for (int i0 = i_begin; i0 < i_begin + RUN; i0 += 8) {
+    float sum[8], old[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) { old[q] = Lin[(size_t)(i0 + q) * D + j]; sum[q] = 0.0f; }
+    for (int s0 = 0; s0 < ab.slices; s0 += KB) {
+      float v[KB][8];
+#pragma unroll
+      for (int u = 0; u < KB; ++u) {
+        const float* ps = p0 + (size_t)min(s0 + u, ab.slices - 1) * PART;   // (past the last slice: re-read, not added)
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+          v[u][q] = __hip_atomic_load(const_cast<float*>(ps) + (size_t)(i0 + q) * D + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+#pragma unroll
+      for (int u = 0; u < KB; ++u)
+        if (s0 + u < ab.slices) {   // uniform; slice order
+#pragma unroll
+          for (int q = 0; q < 8; ++q) sum[q] += v[u][q];
+        }
+    }
+    uint32_t hw[4], lw[4];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      sum[q] += old[q];
+      Lout[(size_t)(i0 + q) * D + j] = sum[q];
+    }
+    if (ab.planes_out) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float v0 = sum[2 * q], v1 = sum[2 * q + 1];
+        const bf16_t h0 = f32_to_bf16(v0), h1 = f32_to_bf16(v1);
+        hw[q] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+        lw[q] = (uint32_t)f32_to_bf16(v0 - bf16_to_f32(h0)) | ((uint32_t)f32_to_bf16(v1 - bf16_to_f32(h1)) << 16);
+      }
+      bf16_t* hi = ab.planes_out + (size_t)bh * 2 * D * D + (size_t)j * D + i0;
+      *reinterpret_cast<uint4*>(hi) = make_uint4(hw[0], hw[1], hw[2], hw[3]);
+      *reinterpret_cast<uint4*>(hi + D * D) = make_uint4(lw[0], lw[1], lw[2], lw[3]);
+    }
+  }
+  if (tid < D) {
+    float zsum = 0.0f;
+    for (int sl = 0; sl < ab.slices; ++sl)
+      zsum += __hip_atomic_load(const_cast<float*>(p0) + (size_t)sl * PART + D * D + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const size_t zat = (size_t)ab.BH * D * D + (size_t)bh * D + tid;
+    ab.state_out[zat] = zsum + ab.state_in[zat];
+  }
+}
+
+// kSel: 1 = the workgroup first selects its KV blocks itself (Eq. 4 from hist.kbar_t, list to hist.idx_out); the
+// first ab.role_blocks workgroup ids (a multiple of eight) absorb evicted tokens instead (absorb_role)
+template <int NW, int kFused, int kSel = 0>
 __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     const int32_t* __restrict__ idx, int k, int n_q, int n_kv, int kv_stride, int bkv, int t_m, int t_n,
-    int items_per_xcd, int total_items, float c_scale, HistArgs hist, bf16_t* __restrict__ O) {
+    int items_per_xcd, int total_items, float c_scale, HistArgs hist, AbsorbArgs ab, bf16_t* __restrict__ O) {
   constexpr int NT = 64 * NW;
   constexpr int BQ = 32 * NW;
   constexpr int CPT = (TK * D * 2 / 16) / NT;  // 1 KB pieces (4 key rows) of a tile per wavefront (4 or 2)
@@ -98,7 +518,12 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
 
   // consecutive workgroup ids go to consecutive XCDs: give every XCD one contiguous run of
   // (head, query block) items so that its L2 sees few heads
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  if (kSel && (int)blockIdx.x < ab.role_blocks) {
+    absorb_role<NW>(smem, ab);
+    return;
+  }
+  const int wgid = kSel ? (int)blockIdx.x - ab.role_blocks : (int)blockIdx.x;
+  const int xcd = wgid & 7, slot = wgid >> 3;
   const int item = xcd * items_per_xcd + slot;
   if (slot >= items_per_xcd || item >= total_items) return;
   const int bh = item / t_m, qb = item % t_m;
@@ -110,8 +535,13 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
   const bf16_t* Kh = K + (size_t)bh * kv_stride * D;  // heads of a cache buffer are kv_stride tokens apart
   const bf16_t* Vh = V + (size_t)bh * kv_stride * D;
   bf16_t* Oh = O + (size_t)bh * n_q * D;
-  const int32_t* row_idx = idx ? idx + ((size_t)bh * t_m + qb) * k : nullptr;
-  const int nsel = idx ? k : t_n;
+  const int32_t* row_idx = kSel ? hist.idx_out + ((size_t)bh * t_m + qb) * k : (idx ? idx + ((size_t)bh * t_m + qb) * k : nullptr);
+  const int nsel = (kSel || idx) ? k : t_n;
+  const int* sel_lds = nullptr;   // kSel: the list in LDS, valid until the first tile is requested
+  if (kSel)
+    sel_lds = select_in_workgroup<NW>(smem, Qh, qb * BQ, n_q, hist.kbar_t + (size_t)bh * (D / 4) * t_n * 4, t_n, k,
+                                      hist.idx_out + ((size_t)bh * t_m + qb) * k,
+                                      hist.scores_out ? hist.scores_out + ((size_t)bh * t_m + qb) * t_n : nullptr);
   const int subs = (bkv + TK - 1) / TK;
   const int ntiles = nsel * subs;
 
@@ -141,12 +571,17 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
     const int t = t0 + lane;
     const int sel = t / subs, sub = t - sel * subs;
     const int sc = min(sel, nsel - 1);
-    const int jb = row_idx ? row_idx[sc] : sc;
+    int jb;
+    if (kSel)   // the first 64 tiles from the list in LDS; later ones from the copy in memory, past this CU's L1
+      jb = t0 == 0 ? sel_lds[sc] : __hip_atomic_load(const_cast<int32_t*>(row_idx) + sc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else
+      jb = row_idx ? row_idx[sc] : sc;
     const bool ok = (sel < nsel) && ((unsigned)jb < (unsigned)t_n);
     const int st = jb * bkv + TK * sub;
     d_tile = ok ? (st | (max(0, min(TK, min(n_kv, (jb + 1) * bkv) - st)) << 24)) : 0;
   };
   refill(0);
+  if (kSel) __syncthreads();   // every wavefront has its descriptors before a tile lands on the list
   auto next_tile = [&](int& start, int& valid) {
     if ((tq & 63) == 0 && tq > 0) refill(tq);  // uniform
     const int d = __builtin_amdgcn_readlane(d_tile, tq & 63);
@@ -521,7 +956,8 @@ bool attn_mfma_supported(const hf_config& c) {
 constexpr int kMfmaMaxKeys = 1 << 23;
 
 static int launch_attn_mfma_impl(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
-                                 const int32_t* idx, int k, const HistArgs* hist, void* O, hipStream_t s) {
+                                 const int32_t* idx, int k, const HistArgs* hist, void* O, hipStream_t s,
+                                 const AbsorbArgs* absorb = nullptr) {
   if (n_kv >= kMfmaMaxKeys) { set_error("window longer than %d keys", kMfmaMaxKeys); return HF_ERR_SHAPE; }
   const int BH = c.batch * c.heads;
   const int t_m = (n_q + c.block_q - 1) / c.block_q, t_n = (n_kv + c.block_kv - 1) / c.block_kv;
@@ -530,22 +966,41 @@ static int launch_attn_mfma_impl(const hf_config& c, const void* Q, int n_q, con
   const int per_xcd = (int)((total + 7) / 8);
   const float scale = c.softmax_scale > 0.0f ? c.softmax_scale : 1.0f / sqrtf((float)c.head_dim);
   const float c_scale = scale * 1.4426950408889634f;
-  const dim3 grid(8 * per_xcd);
+  const AbsorbArgs ab = absorb ? *absorb : AbsorbArgs{};
+  const dim3 grid(8 * per_xcd + ab.role_blocks);
   const bf16_t* q = static_cast<const bf16_t*>(Q);
   const bf16_t* kk = static_cast<const bf16_t*>(K);
   const bf16_t* v = static_cast<const bf16_t*>(V);
   bf16_t* o = static_cast<bf16_t*>(O);
   const HistArgs h = hist ? *hist : HistArgs{};
-#define HF_LAUNCH_ATTN(NWV, FUSED)                                                                              \
-  hipLaunchKernelGGL((attn_mfma_kernel<NWV, FUSED>), grid, dim3(64 * NWV), 0, s, q, kk, v, idx, k, n_q, n_kv,   \
-                     kv_stride_of(c, n_kv), c.block_kv, t_m, t_n, per_xcd, (int)total, c_scale, h, o)
+#define HF_LAUNCH_ATTN_SEL(NWV, FUSED, SEL)                                                                      \
+  hipLaunchKernelGGL((attn_mfma_kernel<NWV, FUSED, SEL>), grid, dim3(64 * NWV), 0, s, q, kk, v, idx, k, n_q, n_kv, \
+                     kv_stride_of(c, n_kv), c.block_kv, t_m, t_n, per_xcd, (int)total, c_scale, h, ab, o)
+#define HF_LAUNCH_ATTN(NWV, FUSED) HF_LAUNCH_ATTN_SEL(NWV, FUSED, 0)
   const int fused = !h.planes && !h.lse2 ? 0 : (h.lse2 ? 3 : ((h.phi_kind == HF_PHI_RELU && h.cosq == nullptr && h.q_hist == nullptr) ? 1 : 2));
+  if (ab.role_blocks && !h.kbar_t) { set_error("absorbing workgroups ride only in the selecting launch"); return HF_ERR_SHAPE; }
+  if (h.kbar_t) {
+    // the workgroups select their KV blocks themselves
+    if (fused == 3 || idx || !h.idx_out) { set_error("in-kernel selection: bad operands"); return HF_ERR_SHAPE; }
+    if (t_n > kSelMaxBlocks) {
+      set_error("window has %d KV blocks; the attention kernel selects among at most %d (select with hf_block_select)", t_n,
+                kSelMaxBlocks);
+      return HF_ERR_SHAPE;
+    }
+    if (c.block_q == 64) {
+      if (fused == 0) HF_LAUNCH_ATTN_SEL(2, 0, 1); else if (fused == 1) HF_LAUNCH_ATTN_SEL(2, 1, 1); else HF_LAUNCH_ATTN_SEL(2, 2, 1);
+    } else {
+      if (fused == 0) HF_LAUNCH_ATTN_SEL(4, 0, 1); else if (fused == 1) HF_LAUNCH_ATTN_SEL(4, 1, 1); else HF_LAUNCH_ATTN_SEL(4, 2, 1);
+    }
+    return check_launch("hf_select_attn_fwd(attention)");
+  }
   if (c.block_q == 64) {
     if (fused == 0) HF_LAUNCH_ATTN(2, 0); else if (fused == 1) HF_LAUNCH_ATTN(2, 1); else if (fused == 2) HF_LAUNCH_ATTN(2, 2); else HF_LAUNCH_ATTN(2, 3);
   } else {
     if (fused == 0) HF_LAUNCH_ATTN(4, 0); else if (fused == 1) HF_LAUNCH_ATTN(4, 1); else if (fused == 2) HF_LAUNCH_ATTN(4, 2); else HF_LAUNCH_ATTN(4, 3);
   }
 #undef HF_LAUNCH_ATTN
+#undef HF_LAUNCH_ATTN_SEL
   return check_launch("hf_hybrid_attn_fwd(attention)");
 }
 
@@ -568,20 +1023,84 @@ bool attn_mfma_fused_supported(const hf_config& c) { return attn_mfma_supported(
 int launch_attn_mfma_fused(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
                            const int32_t* idx, int k, const void* planes, const float* zvec, const float* cosq,
                            const float* sinq, const void* Q_hist, void* O, hipStream_t s, float* lse2_out,
-                           void* olocal_out) {
+                           void* olocal_out, const float* kbar_t, int32_t* idx_out, float* scores_out) {
   // One bf16 plane of L (2^-9 per element, errors of the d terms of a readout average out) costs the
   // output nothing measurable next to the bf16 rounding of P and O; HF_FLAG_HISTORY_TWO_PLANES adds the low plane.
   const HistArgs h = {static_cast<const bf16_t*>(planes), zvec, c.eps, c.z_scale, (c.flags & HF_FLAG_HISTORY_TWO_PLANES) ? 2 : 1,
                       c.phi, cosq, sinq, Q_hist == Q ? nullptr : static_cast<const bf16_t*>(Q_hist), nullptr, nullptr, nullptr,
-                      lse2_out, static_cast<bf16_t*>(olocal_out)};
+                      lse2_out, static_cast<bf16_t*>(olocal_out), kbar_t, idx_out, scores_out};
   return launch_attn_mfma_impl(c, Q, n_q, K, V, n_kv, idx, k, &h, O, s);
+}
+
+// Workgroups that absorb next to the ones that attend: how many token slices per head, given what the attending
+// workgroups leave free of the chip's slots (256 compute units; 4 workgroups of two wavefronts or 2 of four each)
+int step_absorb_slices(const hf_config& c, int n_q, int n_ev) {
+  const int BH = c.batch * c.heads;
+  const long long attending = (long long)BH * ((n_q + c.block_q - 1) / c.block_q);
+  const long long slots = 256ll * (c.block_q == 64 ? 4 : 2);
+  long long room = slots - attending;          // a launch of several rounds has no room to speak of: few, long slices
+  int s = room >= BH ? (int)(room / BH) : 2;
+  if (s > 8) s = 8;
+  const int by_len = (n_ev + 255) / 256;       // a slice should hold some hundred tokens
+  if (s > by_len) s = by_len;
+  return s < 1 ? 1 : s;
+}
+
+size_t step_absorb_workspace_bytes(const hf_config& c, int n_q, int n_ev) {
+  const size_t BH = (size_t)c.batch * c.heads, d = c.head_dim;
+  const size_t counters = (BH * 8 + 255) & ~(size_t)255;
+  return counters + BH * step_absorb_slices(c, n_q, n_ev) * (d * d + d) * sizeof(float);
+}
+
+// selection, attention with the history term, and Eq. 2 for another chunk, in one launch
+int launch_attn_mfma_step(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv, int k,
+                          const float* kbar_t, int32_t* idx_out, float* scores_out, const void* planes,
+                          const float* zvec, const float* cosq, const float* sinq, const void* Q_hist, void* O,
+                          const void* K_ev, const void* V_ev, int n_ev, int ev_stride, const float* state_in,
+                          float* state_out, void* planes_out, void* workspace, hipStream_t s) {
+  const int BH = c.batch * c.heads;
+  AbsorbArgs ab = {};
+  ab.K = static_cast<const bf16_t*>(K_ev);
+  ab.V = static_cast<const bf16_t*>(V_ev);
+  ab.n = n_ev;
+  ab.stride = ev_stride;
+  ab.slices = step_absorb_slices(c, n_q, n_ev);
+  ab.role_blocks = (BH * ab.slices + 7) & ~7;
+  ab.BH = BH;
+  ab.state_in = state_in;
+  ab.state_out = state_out;
+  ab.planes_out = static_cast<bf16_t*>(planes_out);
+  ab.counters = static_cast<unsigned long long*>(workspace);
+  ab.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + (((size_t)BH * 8 + 255) & ~(size_t)255));
+  ab.tag = next_call_tag();
+  HistArgs h = {};
+  if (planes) {
+    h = HistArgs{static_cast<const bf16_t*>(planes), zvec, c.eps, c.z_scale, (c.flags & HF_FLAG_HISTORY_TWO_PLANES) ? 2 : 1,
+                 c.phi, cosq, sinq, Q_hist == Q ? nullptr : static_cast<const bf16_t*>(Q_hist), nullptr, nullptr, nullptr,
+                 nullptr, nullptr, kbar_t, idx_out, scores_out};
+  } else {
+    h.kbar_t = kbar_t;
+    h.idx_out = idx_out;
+    h.scores_out = scores_out;
+  }
+  return launch_attn_mfma_impl(c, Q, n_q, K, V, n_kv, nullptr, k, &h, O, s, &ab);
+}
+
+// selection (Eq. 4) and attention (Eq. 5) in one launch, no history term
+int launch_attn_mfma_select(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv, int k,
+                            const float* kbar_t, int32_t* idx_out, float* scores_out, void* O_local, hipStream_t s) {
+  HistArgs h = {};
+  h.kbar_t = kbar_t;
+  h.idx_out = idx_out;
+  h.scores_out = scores_out;
+  return launch_attn_mfma_impl(c, Q, n_q, K, V, n_kv, nullptr, k, &h, O_local, s);
 }
 
 // the forward pass recomputed for the backward pass: row statistics out, no attention output
 int launch_attn_mfma_stats(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
                            const int32_t* idx, int k, const void* dO, float* lse2, float* dvec, hipStream_t s) {
   const HistArgs h = {nullptr, nullptr, 0.0f, 0.0f, 0, 0, nullptr, nullptr, nullptr, static_cast<const bf16_t*>(dO),
-                      lse2, dvec, nullptr, nullptr};
+                      lse2, dvec, nullptr, nullptr, nullptr, nullptr, nullptr};
   return launch_attn_mfma_impl(c, Q, n_q, K, V, n_kv, idx, k, &h, nullptr, s);
 }
 

@@ -119,7 +119,20 @@ bool attn_mfma_fused_supported(const hf_config& c);
 int launch_attn_mfma_fused(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
                            const int32_t* idx, int k, const void* planes, const float* zvec, const float* cosq,
                            const float* sinq, const void* Q_hist, void* O, hipStream_t s, float* lse2_out = nullptr,
-                           void* olocal_out = nullptr);   // by-products for hf_hybrid_attn_bwd_saved, each optional
+                           void* olocal_out = nullptr,    // by-products for hf_hybrid_attn_bwd_saved, each optional
+                           const float* kbar_t = nullptr, int32_t* idx_out = nullptr, float* scores_out = nullptr);
+// kbar_t given (idx NULL): every workgroup selects its KV blocks itself (Eq. 4) and writes its list to idx_out
+int launch_attn_mfma_select(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv, int k,
+                            const float* kbar_t, int32_t* idx_out, float* scores_out, void* O_local, hipStream_t s);
+constexpr int kMaxFusedSelectBlocks = 1024;   // largest T_n the attention kernel ranks in its tile space
+// the selecting launch with workgroups of their own that absorb n_ev tokens of another chunk (Eq. 2; ReLU, no
+// rotation) into state_out / planes_out = state_in + their contribution; planes NULL: no history term in O
+size_t step_absorb_workspace_bytes(const hf_config& c, int n_q, int n_ev);
+int launch_attn_mfma_step(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv, int k,
+                          const float* kbar_t, int32_t* idx_out, float* scores_out, const void* planes,
+                          const float* zvec, const float* cosq, const float* sinq, const void* Q_hist, void* O,
+                          const void* K_ev, const void* V_ev, int n_ev, int ev_stride, const float* state_in,
+                          float* state_out, void* planes_out, void* workspace, hipStream_t s);
 int launch_attn_mfma_lse(const hf_config& c, const void* Q, int n_q, const void* K, const void* V, int n_kv,
                          const int32_t* idx, int k, void* O_local, float* lse2_out, hipStream_t s);
 // backward pass (training algorithm): lse2 = per-row log2 of the softmax denominator in the scaled-logit domain

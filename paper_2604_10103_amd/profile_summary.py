@@ -20,6 +20,7 @@ import argparse
 import collections
 import csv
 import glob
+import re
 import os
 import shutil
 import subprocess
@@ -91,9 +92,9 @@ def main():
         if is_attention(n) and (best is None or float(r["TotalDurationNs"]) > float(best["TotalDurationNs"])):
             best = r
     # bench.py's roofline times the launch without a history term (state = NULL): where the kernel has an instance
-    # of its own for that (last template argument 0), that instance is the one to compare with; the timed step's
+    # of its own for that (template arguments <.., 0, 0>: no history term, list given), that instance is the one to compare with; the timed step's
     # launches carry the history epilogue and are listed above as well
-    plain = [r for r in rows if is_attention(short(r["Name"])) and short(r["Name"]).endswith(", 0>")]
+    plain = [r for r in rows if re.search(r"attn_mfma_kernel<\d+, 0, 0>$", short(r["Name"]))]
     if plain:
         best = max(plain, key=lambda r: float(r["TotalDurationNs"]))
     lines += ["", f"a4_kernel={short(best['Name'])}", f"a4_avg_us={float(best['AverageNs']) / 1e3:.3f}"]
