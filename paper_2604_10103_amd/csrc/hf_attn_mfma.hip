@@ -452,44 +452,49 @@ __device__ __forceinline__ void absorb_role(char* smem, const AbsorbArgs& ab) {
   const float* p0 = ab.partials + (size_t)bh * ab.slices * PART;
   const float* Lin = ab.state_in + (size_t)bh * D * D;
   float* Lout = ab.state_out + (size_t)bh * D * D;
-  constexpr int KB = 8;   // slices whose loads are in flight together
-  for (int i0 = i_begin; i0 < i_begin + RUN; i0 += 8) {
-    float sum[8], old[8];
+  constexpr int KB = 8;    // slices whose loads are in flight together
+  constexpr int RB = 16;   // key features per trip: 16 x 8 loads of the partials in flight per thread (the trips are
+                           // round trips to memory, a handful of them is the whole tail of this role)
+  for (int i0 = i_begin; i0 < i_begin + RUN; i0 += RB) {
+    float sum[RB], old[RB];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) { old[q] = Lin[(size_t)(i0 + q) * D + j]; sum[q] = 0.0f; }
+    for (int q = 0; q < RB; ++q) { old[q] = Lin[(size_t)(i0 + q) * D + j]; sum[q] = 0.0f; }
     for (int s0 = 0; s0 < ab.slices; s0 += KB) {
-      float v[KB][8];
+      float v[KB][RB];
 #pragma unroll
       for (int u = 0; u < KB; ++u) {
         const float* ps = p0 + (size_t)min(s0 + u, ab.slices - 1) * PART;   // (past the last slice: re-read, not added)
 #pragma unroll
-        for (int q = 0; q < 8; ++q)
+        for (int q = 0; q < RB; ++q)
           v[u][q] = __hip_atomic_load(const_cast<float*>(ps) + (size_t)(i0 + q) * D + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
 #pragma unroll
       for (int u = 0; u < KB; ++u)
         if (s0 + u < ab.slices) {   // uniform; slice order
 #pragma unroll
-          for (int q = 0; q < 8; ++q) sum[q] += v[u][q];
+          for (int q = 0; q < RB; ++q) sum[q] += v[u][q];
         }
     }
-    uint32_t hw[4], lw[4];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
+    for (int q = 0; q < RB; ++q) {
       sum[q] += old[q];
       Lout[(size_t)(i0 + q) * D + j] = sum[q];
     }
     if (ab.planes_out) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const float v0 = sum[2 * q], v1 = sum[2 * q + 1];
-        const bf16_t h0 = f32_to_bf16(v0), h1 = f32_to_bf16(v1);
-        hw[q] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-        lw[q] = (uint32_t)f32_to_bf16(v0 - bf16_to_f32(h0)) | ((uint32_t)f32_to_bf16(v1 - bf16_to_f32(h1)) << 16);
+      for (int half = 0; half < RB / 8; ++half) {
+        uint32_t hw[4], lw[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const float v0 = sum[8 * half + 2 * q], v1 = sum[8 * half + 2 * q + 1];
+          const bf16_t h0 = f32_to_bf16(v0), h1 = f32_to_bf16(v1);
+          hw[q] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+          lw[q] = (uint32_t)f32_to_bf16(v0 - bf16_to_f32(h0)) | ((uint32_t)f32_to_bf16(v1 - bf16_to_f32(h1)) << 16);
+        }
+        bf16_t* hi = ab.planes_out + (size_t)bh * 2 * D * D + (size_t)j * D + i0 + 8 * half;
+        *reinterpret_cast<uint4*>(hi) = make_uint4(hw[0], hw[1], hw[2], hw[3]);
+        *reinterpret_cast<uint4*>(hi + D * D) = make_uint4(lw[0], lw[1], lw[2], lw[3]);
       }
-      bf16_t* hi = ab.planes_out + (size_t)bh * 2 * D * D + (size_t)j * D + i0;
-      *reinterpret_cast<uint4*>(hi) = make_uint4(hw[0], hw[1], hw[2], hw[3]);
-      *reinterpret_cast<uint4*>(hi + D * D) = make_uint4(lw[0], lw[1], lw[2], lw[3]);
     }
   }
   if (tid < D) {

@@ -284,3 +284,49 @@ def test_kept_planes_entry_points_reject_bad_arguments():
     assert lib.hf_hybrid_attn_fwd_planes(ctypes.byref(cfg32), fake, None, 64, fake, fake, 64, None, 0, fake, fake,
                                          None, None, fake, None) != 0
 
+
+
+def test_one_launch_entry_points_reject_bad_arguments(lib):
+    """hf_pool_keys / hf_select_attn_fwd / hf_step_fwd: sizes and argument checks on the host, nothing launched."""
+    class E:   # error codes of hf.h
+        HF_ERR_NULL, HF_ERR_SHAPE, HF_ERR_DTYPE, HF_ERR_ALIGN, HF_ERR_WORKSPACE = -1, -2, -3, -4, -5
+    cfg = hf.make_config(1, 12, 128, "bf16", 64, 64, 0.25)
+    cfg32 = hf.make_config(1, 2, 64, "f32", 16, 16, 0.25)
+    fake = ctypes.c_void_p(0x1000)
+    # pooled keys: B*H*T_n*d floats, rounded up to 256 bytes
+    assert hf.hf_pooled_keys_bytes(cfg, 9360) == 12 * 147 * 128 * 4
+    assert hf.hf_pooled_keys_bytes(cfg32, 100) == (2 * 7 * 64 * 4 + 255) // 256 * 256
+    # the step's workspace: counters + one partial of the state per (head, slice), at least one slice
+    part = (128 * 128 + 128) * 4
+    got = hf.hf_step_workspace_bytes(cfg, 4680, 4680)
+    assert got > 12 * part and (got - 256) % (12 * part) == 0 and 1 <= (got - 256) // (12 * part) <= 8
+    assert hf.hf_step_workspace_bytes(cfg32, 64, 64) == 0          # no such path for this configuration
+    assert lib.hf_pool_keys(ctypes.byref(cfg), None, 9360, 0, fake, None) == E.HF_ERR_NULL
+    assert lib.hf_pool_keys(ctypes.byref(cfg), fake, 9360, 0, ctypes.c_void_p(0x1010), None) == E.HF_ERR_ALIGN
+    assert lib.hf_pool_keys(ctypes.byref(cfg), fake, 9360, 147, fake, None) == E.HF_ERR_SHAPE   # whole blocks only: 146
+    # selection inside the attention launch: bf16 / head_dim 128 only, window of at most 1024 blocks, planes with a state
+    args = lambda c, n_kv=9360, pooled=fake, state=None, planes=None, idx=fake: (
+        ctypes.byref(c), fake, None, 4680, fake, fake, n_kv, pooled, state, planes, None, None, ctypes.c_void_p(0x2000),
+        idx, None, None)
+    assert lib.hf_select_attn_fwd(*args(cfg32)) == E.HF_ERR_SHAPE
+    assert lib.hf_select_attn_fwd(*args(cfg, pooled=None)) == E.HF_ERR_NULL
+    assert lib.hf_select_attn_fwd(*args(cfg, idx=None)) == E.HF_ERR_NULL
+    assert lib.hf_select_attn_fwd(*args(cfg, n_kv=64 * 1025)) == E.HF_ERR_SHAPE
+    assert lib.hf_select_attn_fwd(*args(cfg, state=fake, planes=None)) == E.HF_ERR_NULL
+    # the step: state_out is required and must not overlap what the attention reads; phi = ReLU only
+    st_in, st_out = ctypes.c_void_p(0x100000), ctypes.c_void_p(0x400000)
+    pl_in, pl_out = ctypes.c_void_p(0x800000), ctypes.c_void_p(0xC00000)
+    wsp = ctypes.c_void_p(0x1000000)
+    def step(c=cfg, K_ev=fake, V_ev=fake, n_ev=4680, stride=0, so=st_out, po=pl_out, ws=wsp, wb=1 << 30):
+        return lib.hf_step_fwd(ctypes.byref(c), fake, None, 4680, fake, fake, 9360, fake, st_in, pl_in, None, None,
+                               ctypes.c_void_p(0x2000), fake, None, K_ev, V_ev, n_ev, stride, so, po, ws, wb, None)
+    assert step(K_ev=None) == E.HF_ERR_NULL
+    assert step(V_ev=None) == E.HF_ERR_NULL
+    assert step(so=None) == E.HF_ERR_NULL
+    assert step(so=st_in) == E.HF_ERR_SHAPE
+    assert step(po=pl_in) == E.HF_ERR_SHAPE
+    assert step(so=ctypes.c_void_p(0x100000 + 4096)) == E.HF_ERR_SHAPE           # overlaps state_in
+    assert step(stride=100) == E.HF_ERR_SHAPE                                     # head stride below n_ev
+    assert step(wb=1024) == E.HF_ERR_WORKSPACE
+    assert step(ws=None) == E.HF_ERR_WORKSPACE
+    assert step(c=hf.make_config(1, 12, 128, "bf16", 64, 64, 0.25, phi=hf.HF_PHI_ELU1)) == E.HF_ERR_SHAPE
