@@ -204,7 +204,10 @@ HF_API int hf_stream_open_chunk(const hf_config* cfg, hf_window* win, int32_t n_
  * chunk's first, step_in_chunk > 0, the pooled keys of the whole blocks before the chunk's own n_q
  * tokens are reused, and so are the bf16 planes of the state that the first step left in the workspace:
  * the state must not change between the steps of a chunk, as in the inference algorithm, where it is
- * updated only when a chunk opens) followed by hf_hybrid_attn_fwd_split.  block_idx: scratch and output,
+ * updated only when a chunk opens) followed by hf_hybrid_attn_fwd_split.  Where the attention kernel can
+ * select for itself (bf16, head_dim 128, block_q 64 or 128, at most 1024 KV blocks, default flags) the step is
+ * hf_pool_keys over the blocks that changed plus ONE launch that selects, attends and adds the history term
+ * (hf_select_attn_fwd); same outputs to the same bounds.  block_idx: scratch and output,
  * int32 [B, H, T_m, k] for this window length; workspace >= hf_workspace_bytes(cfg, n_q, win->n_tokens),
  * the same buffer on every step of a chunk, written by nothing else in between.  The other arguments as
  * in those two calls. */

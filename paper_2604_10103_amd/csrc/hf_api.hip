@@ -753,6 +753,52 @@ int hf_stream_open_chunk(const hf_config* cfg, hf_window* win, int32_t n_chunk, 
   return HF_OK;
 }
 
+// One denoising step of a streaming driver where the attention kernel can select for itself (bf16, head_dim 128,
+// block_q 64 or 128, at most kMaxFusedSelectBlocks KV blocks, default flags): the KV blocks [kv_first, kv_end) are
+// pooled into the workspace (the others keep the means of the chunk's earlier steps), the state's planes are
+// converted on the chunk's first step and reused afterwards, and ONE launch selects, attends and adds the history
+// term.  Returns HF_OK with *done = false where this path does not apply (the caller takes the separate calls).
+static int step_one_launch(const hf_config* cfg, const void* Q, const void* Q_hist, int32_t n_q, const void* K,
+                           const void* V, int32_t n_kv, int kv_first, int kv_end, int32_t step_in_chunk,
+                           int32_t* block_idx, const void* state_or_null, const float* rope_cos_q,
+                           const float* rope_sin_q, void* O, void* workspace, size_t workspace_bytes, void* stream,
+                           bool* done) {
+  *done = false;
+  const int t_m = cdiv(n_q, cfg->block_q), t_n = cdiv(n_kv, cfg->block_kv);
+  (void)t_m;
+  if (!attn_mfma_fused_supported(*cfg) || (cfg->flags & HF_FLAG_READOUT_KERNEL) || t_n > kMaxFusedSelectBlocks) return HF_OK;
+  int k = 0;
+  HF_TRY(check_select_args(cfg, Q, n_q, K, n_kv, 0, block_idx, nullptr, &k));
+  HF_TRY(check_ptr(V, "V_win", true));
+  HF_TRY(check_ptr(O, "O", true));
+  if (!Q_hist) Q_hist = Q;
+  if (O == Q || O == Q_hist || O == K || O == V) { set_error("O must not alias an input"); return HF_ERR_SHAPE; }
+  if ((rope_cos_q == nullptr) != (rope_sin_q == nullptr)) {
+    set_error("rope_cos_q and rope_sin_q must both be given or both be NULL");
+    return HF_ERR_NULL;
+  }
+  const WorkspaceLayout w = workspace_layout(cfg, n_q, n_kv);
+  if (!workspace || workspace_bytes < w.total) {
+    set_error("workspace of %zu bytes needed, %zu given", w.total, workspace ? workspace_bytes : (size_t)0);
+    return HF_ERR_WORKSPACE;
+  }
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) { set_error("workspace is not 256-byte aligned"); return HF_ERR_ALIGN; }
+  char* ws = static_cast<char*>(workspace);
+  float* kbar = reinterpret_cast<float*>(ws + w.kbar);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (kv_end > kv_first)
+    HF_TRY(launch_pool_both(*cfg, nullptr, 0, 0, K, n_kv, t_n, kv_first, kv_end, nullptr, kbar, s));
+  *done = true;
+  if (!state_or_null) return launch_attn_mfma_select(*cfg, Q, n_q, K, V, n_kv, k, kbar, block_idx, nullptr, O, s);
+  const float* st = static_cast<const float*>(state_or_null);
+  const size_t d = cfg->head_dim;
+  // the state is frozen during a chunk's denoising steps: its planes are converted on the first and stay here
+  if (step_in_chunk == 0) HF_TRY(launch_state_planes(*cfg, st, ws + w.planes, s));
+  return launch_attn_mfma_fused(*cfg, Q, n_q, K, V, n_kv, nullptr, k, ws + w.planes,
+                                st + (size_t)cfg->batch * cfg->heads * d * d, rope_cos_q, rope_sin_q, Q_hist, O, s, nullptr,
+                                nullptr, kbar, block_idx, nullptr);
+}
+
 int hf_stream_step(const hf_config* cfg, const hf_window* win, const void* Q, const void* Q_hist, int32_t n_q,
                    const void* K_win, const void* V_win, int32_t step_in_chunk, int32_t* block_idx,
                    const void* state_or_null, const float* rope_cos_q, const float* rope_sin_q, void* O,
@@ -767,6 +813,12 @@ int hf_stream_step(const hf_config* cfg, const hf_window* win, const void* Q, co
   const int32_t n_kv = win->n_tokens;
   // the chunk's own keys are the last n_q tokens; whole blocks before them are as the chunk's first step left them
   const int32_t reuse = step_in_chunk > 0 ? (n_kv - n_q) / cfg->block_kv : 0;
+  HF_TRY(check_tokens(n_kv, "n_kv"));
+  HF_TRY(check_window_len(cfg, n_kv));
+  bool done = false;
+  HF_TRY(step_one_launch(cfg, Q, Q_hist, n_q, K_win, V_win, n_kv, reuse, cdiv(n_kv, cfg->block_kv), step_in_chunk, block_idx,
+                         state_or_null, rope_cos_q, rope_sin_q, O, workspace, workspace_bytes, stream, &done));
+  if (done) return HF_OK;
   HF_TRY(hf_block_select_cached(cfg, Q, n_q, K_win, n_kv, reuse, block_idx, nullptr, workspace, workspace_bytes,
                                 stream));
   const int32_t k = select_k_of(cfg, cdiv(n_kv, cfg->block_kv));
@@ -865,6 +917,10 @@ int hf_ring_step(const hf_config* cfg, const hf_ring* ring, const void* Q, const
     kv_end = cdiv(first + ring->n_chunk, cfg->block_kv);
     if (kv_end > t_n) kv_end = t_n;
   }
+  bool done = false;
+  HF_TRY(step_one_launch(cfg, Q, Q_hist, n_q, K_cache, V_cache, n_kv, kv_first, kv_end, step_in_chunk, block_idx,
+                         state_or_null, rope_cos_q, rope_sin_q, O, workspace, workspace_bytes, stream, &done));
+  if (done) return HF_OK;
   char* ws = static_cast<char*>(workspace);
   HF_TRY(select_launches(cfg, Q, n_q, K_cache, n_kv, kv_first, k, block_idx, nullptr, reinterpret_cast<float*>(ws + w.qbar),
                          reinterpret_cast<float*>(ws + w.kbar), static_cast<hipStream_t>(stream), kv_end));
