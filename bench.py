@@ -125,7 +125,7 @@ def run_extras(hf, wl, torch, np, dev):
         layers.append(dict(K=K, V=V, st=st, planes=planes, steps=steps,
                            idx=torch.empty((w.batch, w.heads, w.t_m, k), dtype=torch.int32, device=dev),
                            O=torch.empty(shape_q, dtype=w.torch_dtype, device=dev),
-                           ws=torch.empty(hf.hf_workspace_bytes(cfg, w.n_q, w.n_kv), dtype=torch.uint8, device=dev)))
+                           pooled=torch.empty(hf.hf_pooled_keys_bytes(cfg, w.n_kv), dtype=torch.uint8, device=dev)))
     reuse = n_old // w.block
 
     def layer_call(L, s, events=None):
@@ -135,9 +135,10 @@ def run_extras(hf, wl, torch, np, dev):
         L["V"][:, :, n_old:].copy_(Vc)
         if events is not None:
             events[0].record()
-        # the pooled keys of the frozen half are reused after a layer's first step
-        hf.hf_block_select_cached(cfg, Q, L["K"], reuse if s > 0 else 0, L["idx"], None, L["ws"])
-        hf.hf_hybrid_attn_fwd_planes(cfg, Q, L["K"], L["V"], L["idx"], L["st"], L["planes"], L["O"])
+        # the pooled keys of the frozen half are reused after a layer's first step; selection, attention and the
+        # history term are one launch
+        hf.hf_pool_keys(cfg, L["K"], L["pooled"], reuse if s > 0 else 0)
+        hf.hf_select_attn_fwd(cfg, Q, L["K"], L["V"], L["pooled"], L["st"], L["planes"], L["O"], L["idx"])
         if events is not None:
             events[1].record()
 
@@ -153,7 +154,7 @@ def run_extras(hf, wl, torch, np, dev):
     torch.cuda.synchronize()
     ts = np.array([[e[0].elapsed_time(e[1]) for e in row] for row in evs])   # [steps, layers] ms
     out["stack_30x4"] = {
-        "workload": "30 layers x 4 denoising steps of the step_832x480 layer call (select + fused forward), 30 distinct "
+        "workload": "30 layers x 4 denoising steps of the step_832x480 layer call (hf_pool_keys + hf_select_attn_fwd), 30 distinct "
                     "layer sets (1.7 GB of K, V), cached window half and state frozen across a layer's steps",
         "calls": int(ts.size), "total_ms": float(ts.sum()), "mean_ms": float(ts.mean()), "min_ms": float(ts.min()),
         "max_ms": float(ts.max()), "first_step_mean_ms": float(ts[0].mean()), "later_steps_mean_ms": float(ts[1:].mean()),
