@@ -125,3 +125,52 @@ def test_captured_step_with_kept_planes_replays_match_eager(name):
         assert torch.equal(cap.O, ref.O), rep
         assert torch.isfinite(cap.O.float()).all()
 
+
+
+@pytest.mark.parametrize("name", ["small_bf16", "step_832x480"])
+def test_captured_two_launch_step_replays_match_eager(name):
+    """hf_pool_keys + hf_step_fwd as a captured graph, one graph per direction of the state's two buffers (as bench.py
+    replays them).  Every replay carries the same counter tag; the last workgroup of a head leaves its arrival counter
+    at zero, so the replays count from zero again.  The eager reference makes the same calls on buffers of its own:
+    every sum has a fixed order, so state, planes, lists and outputs agree bit for bit."""
+    w = wl.get(name)
+    cfg = hf.make_config(batch=w.batch, heads=w.heads, head_dim=w.head_dim, dtype=w.dtype, block_q=w.block,
+                         block_kv=w.block, keep_ratio=w.keep_ratio)
+    Q, K, V = wl.make_qkv(w)
+    Ke, Ve = wl.make_evicted(w, 0)
+
+    class Two(Buffers):
+        def __init__(self):
+            super().__init__(cfg, w, Q, K, V, Ke, Ve)
+            self.st2, self.planes2 = torch.zeros_like(self.st), torch.zeros_like(self.planes)
+            self.pooled = torch.empty(hf.hf_pooled_keys_bytes(cfg, w.n_kv), dtype=torch.uint8, device=DEV)
+            self.sws = torch.empty(hf.hf_step_workspace_bytes(cfg, w.n_q, Ke.shape[2]), dtype=torch.uint8, device=DEV)
+
+        def step(self, phase):
+            a, b = ((self.st, self.planes), (self.st2, self.planes2))[::1 if phase == 0 else -1]
+            hf.hf_pool_keys(cfg, self.K, self.pooled)
+            hf.hf_step_fwd(cfg, self.Q, self.K, self.V, self.pooled, a[0], a[1], self.O, self.idx, self.Ke, self.Ve,
+                           b[0], b[1], self.sws)
+
+    ref, cap = Two(), Two()
+    torch.cuda.synchronize()
+    graphs = []
+    for phase in (0, 1):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            cap.step(phase)
+        graphs.append(g)
+    scratch = torch.zeros(1 << 20, device=DEV)
+    for rep in range(6):
+        ref.step(rep % 2)
+        scratch.add_(1.0)        # the program's own eager work between replays
+        torch.cuda.synchronize()
+        graphs[rep % 2].replay()
+        torch.cuda.synchronize()
+        assert torch.equal(cap.idx, ref.idx), rep
+        assert torch.equal(cap.O, ref.O), rep
+        for x, y in ((cap.st, ref.st), (cap.st2, ref.st2), (cap.planes, ref.planes), (cap.planes2, ref.planes2)):
+            assert torch.equal(x, y), rep
+        assert torch.isfinite(cap.O.float()).all()
+    # the state grew by one chunk per step: six absorbed chunks on top of the first
+    assert float(cap.st.abs().sum()) > 0 and not torch.equal(cap.st, cap.st2)
