@@ -458,6 +458,16 @@ def main():
     tab_ms, _ = time_calls(lambda s: hf.hf_rope_tables(win_idx, rows, cols, pairs, kc, ks), a.steps)
     ropek_ms, _ = time_calls(lambda s: hf.hf_rope_apply(cfg, s["K"], kc, ks, k_rot), a.steps)
     rope_bytes = 2 * w.batch * w.heads * w.n_kv * w.head_dim * esz + 2 * kc.numel() * 4
+    # per denoising step of a model that rotates its keys: the chunk's own keys rotated into the window and their
+    # KV blocks pooled in the same pass (no pooling launch on that step)
+    append_ms = None
+    if "pooled" in sets[0]:
+        n_old = w.n_kv - w.n_q
+        qc_tab, qs_tab = kc[n_old:].contiguous(), ks[n_old:].contiguous()
+        append_ms, _ = time_calls(lambda s: hf.hf_rope_append_keys(cfg, s["Q"], qc_tab, qs_tab, k_rot, n_old, s["pooled"]),
+                                  a.steps)   # (Q stands in for the chunk's new keys: same shape and type)
+        for s in sets:
+            hf.hf_pool_keys(cfg, s["K"], s["pooled"])
     del k_rot
 
     # the training algorithm's gradient step (outside the timed step, which is the inference path): dQ, dK, dV of
@@ -543,7 +553,7 @@ def main():
                        "readout_combine_unfused": a5_ms, "fused_epilogue_extra": max(fwd_ms - a4_ms, 0.0), "absorb": abs_ms,
                        "dense_window_fwd": dense_ms, "rope_tables_window": tab_ms, "rope_apply_k_window": ropek_ms,
                        "pool_keys": pool_ms, "select_attn_fwd": selattn_ms, "step_fwd": stepf_ms,
-                       "in_step_eager": step_calls_ms},
+                       "in_step_eager": step_calls_ms, "rope_append_keys_chunk": append_ms},
         "hbm": {"absorb_GBs": absorb_bytes / (abs_ms * 1e-3) / 1e9,
                 "absorb_frac": absorb_bytes / (abs_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
                 "readout_GBs": (readout_bytes / (a5_ms * 1e-3) / 1e9) if a5_ms > 0 else None,

@@ -494,6 +494,19 @@ HF_API int hf_rope_tables(const int32_t* frame_idx, int32_t n_frames, int32_t he
 HF_API int hf_rope_apply(const hf_config* cfg, const void* X, int32_t n_tokens,
                   const float* rope_cos, const float* rope_sin, void* Y, void* stream);
 
+/* The chunk's keys enter the window and are pooled in the pass that already reads them: K_new [B, H, n_new, d]
+ * (un-rotated, of cfg->dtype) is rotated like hf_rope_apply (tables fp32 [n_new, d/2] for exactly these tokens; both
+ * NULL: copied as it is) and written to tokens first .. first + n_new - 1 of every head of the window buffer K_win
+ * ([B, H, n_kv, d], or [B, H, cfg->kv_capacity, d] with n_kv valid tokens), and the pooled keys of hf_pool_keys are
+ * written for the KV blocks that those tokens touch, as means of the STORED values over each block's real length
+ * (tokens of such a block outside the new range are read from K_win as they stand).  Every other block of pooled_K
+ * keeps its value: with the cached part of the window pooled once per chunk, a denoising step needs no pooling
+ * launch (inference algorithm: only the chunk's own keys change between the steps of a chunk).
+ *   0 <= first, 1 <= n_new, first + n_new <= n_kv; K_new must not overlap K_win; pooled_K 256-byte aligned. */
+HF_API int hf_rope_append_keys(const hf_config* cfg, const void* K_new, int32_t n_new,
+                        const float* rope_cos, const float* rope_sin,
+                        void* K_win, int32_t first, int32_t n_kv, void* pooled_K, void* stream);
+
 /* ---- Measurement helper (no part of the method) ------------------------------------------------ */
 
 /* Enqueues a kernel in which 2048 wavefronts (two per SIMD of a 256-unit chip) each issue iters * 16 independent

@@ -119,6 +119,7 @@ def load():
     lib.hf_rope_window_indices.argtypes = [I, I, I, ctypes.POINTER(I)]
     lib.hf_rope_tables.argtypes = [ctypes.POINTER(I), I, I, I, I, I, I, ctypes.c_double, I, P, P, P]
     lib.hf_rope_apply.argtypes = [CP, P, I, P, P, P, P]
+    lib.hf_rope_append_keys.argtypes = [CP, P, I, P, P, P, I, I, P, P]
     lib.hf_probe_mfma_bf16.argtypes = [I, P, ctypes.POINTER(ctypes.c_double), P]
     for name in ("hf_state_bytes", "hf_state_init", "hf_state_fold_linear", "hf_window_advance", "hf_absorb_evicted", "hf_absorb_workspace_bytes", "hf_select_k",
                  "hf_workspace_bytes",
@@ -128,7 +129,7 @@ def load():
                  "hf_stream_step", "hf_bwd_workspace_bytes", "hf_hybrid_attn_bwd", "hf_state_planes_bytes",
                  "hf_state_planes", "hf_absorb_evicted_planes", "hf_hybrid_attn_fwd_planes", "hf_probe_mfma_bf16",
                  "hf_ring_open_chunk", "hf_ring_step", "hf_pooled_keys_bytes", "hf_pool_keys", "hf_select_attn_fwd",
-                 "hf_step_workspace_bytes", "hf_step_fwd"):
+                 "hf_step_workspace_bytes", "hf_step_fwd", "hf_rope_append_keys"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -506,6 +507,20 @@ def hf_rope_tables(frame_idx, height: int, width: int, pairs, cos_out, sin_out, 
                                  float(theta), 1 if temporal_only else 0,
                                  _dev(cos_out, "cos_out", torch.float32, shp),
                                  _dev(sin_out, "sin_out", torch.float32, shp), _stream()))
+
+
+def hf_rope_append_keys(cfg: hf_config, K_new, rope_cos, rope_sin, K_win, first: int, pooled_K, n_kv=None) -> None:
+    """K_new [B, H, n_new, d], rotated by its tables (None: copied), becomes tokens first .. first + n_new - 1 of the
+    window buffer K_win; the pooled keys of the KV blocks those tokens touch are rewritten in pooled_K."""
+    B, H, d = cfg.batch, cfg.heads, cfg.head_dim
+    n_new = K_new.shape[2]
+    n_kv = _kv_len(cfg, K_win, n_kv)
+    tab = (n_new, d // 2)
+    _check(load().hf_rope_append_keys(
+        ctypes.byref(cfg), _dev(K_new, "K_new", _tdtype(cfg), (B, H, n_new, d)), n_new,
+        _dev(rope_cos, "rope_cos", torch.float32, tab), _dev(rope_sin, "rope_sin", torch.float32, tab),
+        _dev(K_win, "K_win", _tdtype(cfg), (B, H, K_win.shape[2], d)), first, n_kv,
+        _dev(pooled_K, "pooled_K", torch.uint8), _stream()))
 
 
 def hf_rope_apply(cfg: hf_config, X, rope_cos, rope_sin, Y) -> None:

@@ -1102,6 +1102,37 @@ int hf_rope_tables(const int32_t* frame_idx, int32_t n_frames, int32_t height, i
                             cos_out, sin_out, static_cast<hipStream_t>(stream));
 }
 
+int hf_rope_append_keys(const hf_config* cfg, const void* K_new, int32_t n_new, const float* rope_cos,
+                        const float* rope_sin, void* K_win, int32_t first, int32_t n_kv, void* pooled_K, void* stream) {
+  HF_TRY(check_cfg(cfg));
+  HF_TRY(check_ptr(K_new, "K_new", true));
+  HF_TRY(check_ptr(K_win, "K_win", true));
+  HF_TRY(check_ptr(pooled_K, "pooled_K", true));
+  if ((rope_cos == nullptr) != (rope_sin == nullptr)) {
+    set_error("rope_cos and rope_sin must both be given or both be NULL");
+    return HF_ERR_NULL;
+  }
+  HF_TRY(check_ptr(rope_cos, "rope_cos", false));
+  HF_TRY(check_ptr(rope_sin, "rope_sin", false));
+  HF_TRY(check_tokens(n_new, "n_new"));
+  HF_TRY(check_tokens(n_kv, "n_kv"));
+  HF_TRY(check_window_len(cfg, n_kv));
+  if (first < 0 || (long long)first + n_new > n_kv) {
+    set_error("tokens %d .. %d lie outside the window of %d", first, first + n_new - 1, n_kv);
+    return HF_ERR_SHAPE;
+  }
+  if (reinterpret_cast<uintptr_t>(pooled_K) & 255u) { set_error("pooled_K is not 256-byte aligned"); return HF_ERR_ALIGN; }
+  const size_t bh = (size_t)cfg->batch * cfg->heads, row = (size_t)cfg->head_dim * esize(cfg);
+  const char* a = static_cast<const char*>(K_new);
+  const char* b = static_cast<const char*>(K_win);
+  if (a < b + bh * kv_stride_of(*cfg, n_kv) * row && b < a + bh * n_new * row) {
+    set_error("K_new overlaps K_win");
+    return HF_ERR_SHAPE;
+  }
+  return launch_rope_append_pool(*cfg, K_new, n_new, rope_cos, rope_sin, K_win, first, n_kv, static_cast<float*>(pooled_K),
+                                 static_cast<hipStream_t>(stream));
+}
+
 int hf_rope_apply(const hf_config* cfg, const void* X, int32_t n_tokens, const float* rope_cos,
                   const float* rope_sin, void* Y, void* stream) {
   HF_TRY(check_cfg(cfg));

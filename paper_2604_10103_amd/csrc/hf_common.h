@@ -161,5 +161,8 @@ int launch_rope_tables(const int32_t* frame_idx, int n_frames, int height, int w
                        int pairs_w, double theta, int temporal_only, float* cosv, float* sinv, hipStream_t s);
 int launch_rope_apply(const hf_config& c, const void* X, int n, const float* cosv, const float* sinv, void* Y,
                       hipStream_t s);
+// the chunk's new keys rotated (tables NULL: copied) into the window at token `first`, the KV blocks they touch pooled
+int launch_rope_append_pool(const hf_config& c, const void* X, int n_new, const float* cosv, const float* sinv, void* Kwin,
+                            int first, int n_kv, float* kbar_t, hipStream_t s);
 
 }  // namespace hf

@@ -80,6 +80,104 @@ __global__ __launch_bounds__(256) void rope_apply_kernel(const T* X, int n_token
   }
 }
 
+// The chunk's new keys take their place in the window buffer and the KV blocks they touch are pooled (Eq. 4's
+// k-bar) in the same pass: one workgroup per (KV block, head) walks the block's tokens, 8 features of a token per
+// thread; a token of the new range is read from X, rotated by its table row (fp32, one rounding to the storage type;
+// no tables: copied) and stored, any other token of the block is read from the window as it stands; the column sums
+// of the STORED values meet by lane exchanges and through LDS, and the mean over the block's real length goes to
+// kbar_t[bh][D/4][t_n][4].
+template <typename T, int D>
+__global__ __launch_bounds__(256) void rope_append_pool_kernel(const T* __restrict__ X, int n_new,
+                                                               const float* __restrict__ cosv,
+                                                               const float* __restrict__ sinv, T* Kwin, int kv_stride,
+                                                               int first, int n_kv, int bkv, int t_n, int blk0,
+                                                               float* __restrict__ kbar_t) {
+  constexpr int TPT = D / 8;         // threads per token
+  constexpr int TOK = 256 / TPT;     // tokens per pass of the workgroup
+  __shared__ float red[4][D];
+  const int blk = blk0 + blockIdx.x, bh = blockIdx.y;
+  const int t0 = blk * bkv, t1 = min(n_kv, t0 + bkv);
+  const int g = threadIdx.x % TPT, tl = threadIdx.x / TPT;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  float acc[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
+#pragma unroll 4
+  for (int t = t0 + tl; t < t1; t += TOK) {
+    T* dst = Kwin + ((size_t)bh * kv_stride + t) * D + 8 * g;
+    float x[8];
+    if (t >= first && t < first + n_new) {
+      const size_t src = ((size_t)bh * n_new + (t - first)) * D + 8 * g;
+      load16B<T>(X + src, x);
+      if (Elem<T>::kPer16B == 4) load16B<T>(X + src + 4, x + 4);
+      if (cosv != nullptr) {
+        const float4 c4 = *reinterpret_cast<const float4*>(cosv + (size_t)(t - first) * (D / 2) + 4 * g);
+        const float4 s4 = *reinterpret_cast<const float4*>(sinv + (size_t)(t - first) * (D / 2) + 4 * g);
+        const float cc[4] = {c4.x, c4.y, c4.z, c4.w}, ss[4] = {s4.x, s4.y, s4.z, s4.w};
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          const float a = x[2 * p], b = x[2 * p + 1];
+          x[2 * p] = a * cc[p] - b * ss[p];
+          x[2 * p + 1] = a * ss[p] + b * cc[p];
+        }
+      }
+      if (Elem<T>::kPer16B == 8) {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const bf16_t lo = f32_to_bf16(x[2 * i]), hi = f32_to_bf16(x[2 * i + 1]);
+          w[i] = (uint32_t)lo | ((uint32_t)hi << 16);
+          x[2 * i] = bf16_to_f32(lo);          // what is pooled is what is stored
+          x[2 * i + 1] = bf16_to_f32(hi);
+        }
+        *reinterpret_cast<uint4*>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
+      } else {
+        *reinterpret_cast<float4*>(dst) = make_float4(x[0], x[1], x[2], x[3]);
+        *reinterpret_cast<float4*>(dst + 4) = make_float4(x[4], x[5], x[6], x[7]);
+      }
+    } else {
+      load16B<T>(dst, x);
+      if (Elem<T>::kPer16B == 4) load16B<T>(dst + 4, x + 4);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] += x[e];
+  }
+  // lanes g, g + TPT, ... of a wavefront hold the same features of different tokens
+#pragma unroll
+  for (int o = TPT; o < kWave; o <<= 1)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] += __shfl_xor(acc[e], o, kWave);
+  if (lane < TPT) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) red[wave][8 * lane + e] = acc[e];
+  }
+  __syncthreads();
+  if (threadIdx.x < D) {
+    const int f = threadIdx.x;
+    const float sum = (red[0][f] + red[1][f]) + (red[2][f] + red[3][f]);
+    kbar_t[(((size_t)bh * (D / 4) + f / 4) * t_n + blk) * 4 + (f & 3)] = sum * (1.0f / (float)(t1 - t0));
+  }
+}
+
+int launch_rope_append_pool(const hf_config& c, const void* X, int n_new, const float* cosv, const float* sinv, void* Kwin,
+                            int first, int n_kv, float* kbar_t, hipStream_t s) {
+  const int BH = c.batch * c.heads;
+  const int t_n = (n_kv + c.block_kv - 1) / c.block_kv;
+  const int blk0 = first / c.block_kv, blk1 = (first + n_new + c.block_kv - 1) / c.block_kv;   // blocks the new tokens touch
+  const dim3 grid(blk1 - blk0, BH);
+  const int stride = kv_stride_of(c, n_kv);
+#define HF_LAUNCH_RAP(T, DD)                                                                                         \
+  hipLaunchKernelGGL((rope_append_pool_kernel<T, DD>), grid, dim3(256), 0, s, static_cast<const T*>(X), n_new, cosv, \
+                     sinv, static_cast<T*>(Kwin), stride, first, n_kv, c.block_kv, t_n, blk0, kbar_t)
+  if (c.dtype == HF_BF16) {
+    if (c.head_dim == 128) HF_LAUNCH_RAP(bf16_t, 128); else HF_LAUNCH_RAP(bf16_t, 64);
+  } else {
+    if (c.head_dim == 128) HF_LAUNCH_RAP(float, 128); else HF_LAUNCH_RAP(float, 64);
+  }
+#undef HF_LAUNCH_RAP
+  return check_launch("hf_rope_append_keys");
+}
+
 int launch_rope_tables(const int32_t* frame_idx, int n_frames, int height, int width, int pairs_t, int pairs_h,
                        int pairs_w, double theta, int temporal_only, float* cosv, float* sinv, hipStream_t s) {
   RopeSpec spec;

@@ -330,3 +330,16 @@ def test_one_launch_entry_points_reject_bad_arguments(lib):
     assert step(wb=1024) == E.HF_ERR_WORKSPACE
     assert step(ws=None) == E.HF_ERR_WORKSPACE
     assert step(c=hf.make_config(1, 12, 128, "bf16", 64, 64, 0.25, phi=hf.HF_PHI_ELU1)) == E.HF_ERR_SHAPE
+
+
+def test_rope_append_keys_rejects_bad_arguments(lib):
+    cfg = hf.make_config(1, 12, 128, "bf16", 64, 64, 0.25)
+    fake, win, pooled = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x10000000), ctypes.c_void_p(0x40000000)
+    call = lambda K_new=fake, n_new=4680, cos=fake, sin=fake, K_win=win, first=4680, n_kv=9360, pk=pooled: \
+        lib.hf_rope_append_keys(ctypes.byref(cfg), K_new, n_new, cos, sin, K_win, first, n_kv, pk, None)
+    assert call(K_new=None) == -1 and call(K_win=None) == -1 and call(pk=None) == -1
+    assert call(sin=None) == -1                              # one table without the other
+    assert call(first=4681) == -2 and call(first=-1) == -2   # the new tokens must lie inside the window
+    assert call(n_new=0) == -2
+    assert call(pk=ctypes.c_void_p(0x40000010)) == -4
+    assert call(K_new=ctypes.c_void_p(0x10000100)) == -2     # overlaps the window buffer

@@ -176,3 +176,66 @@ def test_rotated_local_branch_unrotated_history_branch(name, phi):
         wrong = orc.hybrid_attention(qr, kr, v, ref_states[h], w.block, w.block, k, phi, qc64, qs64, cfg.eps,
                                      cfg.z_scale, block_idx=idxc[0, h])[0]
         assert rel_l2(Og[0, h], wrong) > 2 * rel_l2(Og[0, h], ref)
+
+
+@pytest.mark.parametrize("name,rotate,capacity", [("small_bf16", True, 0), ("small_bf16", False, 0), ("small_bf16", True, 1200),
+                                                  ("tiny_f32", True, 0), ("small_b128", True, 0), ("small_f32_d128", True, 0)])
+def test_new_keys_are_rotated_into_the_window_and_pooled_in_one_pass(name, rotate, capacity):
+    """hf_rope_append_keys: the chunk's un-rotated keys become the last n_q tokens of the window buffer (rotated by
+    their tables) and the pooled keys of the KV blocks they touch are rewritten, the chunk's first block sharing
+    tokens with the cached part (first is not a multiple of the block size).  Expected: the oracle's rotation, rounded
+    to the storage type, laid behind the cached part, and the oracle's pooled means of that window."""
+    w = wl.get(name)
+    cfg = cfg_of(w, kv_capacity=capacity)
+    hh, ww = wl.frame_grid(w)
+    pairs = orc.default_axis_pairs(w.head_dim)
+    _, K, _ = wl.make_qkv(w)                      # the cached part: its first tokens, as they lie in the cache
+    first = w.n_kv - w.n_q
+    assert first % w.block != 0 or name == "tiny_f32"
+    K_new = wl.randn((w.batch, w.heads, w.n_q, w.head_dim), 99_000 + w.cfg, w.scale, w.torch_dtype)
+    frames = orc.window_temporal_indices(40, w.chunk_frames, T0)
+    cos, sin = (as_f32(t) for t in orc.rope_tables_3d(frames, hh, ww, pairs))
+    if rotate:
+        new_ref = torch.from_numpy(rotated_ref(K_new, wl.to_f64(cos), wl.to_f64(sin))).to(w.torch_dtype)
+    else:
+        new_ref = K_new
+    window_ref = torch.cat([K[:, :, :first], new_ref], dim=2)
+    cap = capacity or w.n_kv
+    Kwin = torch.full((w.batch, w.heads, cap, w.head_dim), float("nan"), dtype=w.torch_dtype, device=DEV)
+    Kwin[:, :, :first] = K[:, :, :first].to(DEV)
+    pooled = torch.empty(hf.hf_pooled_keys_bytes(cfg, w.n_kv), dtype=torch.uint8, device=DEV)
+    # the cached part is pooled once (its last, shared block from the stale tail: the append call rewrites it)
+    Kwin[:, :, first:w.n_kv] = 0
+    hf.hf_pool_keys(cfg, Kwin, pooled, n_kv=w.n_kv if capacity else None)
+    before = pooled.clone()
+    hf.hf_rope_append_keys(cfg, K_new.to(DEV), cos.to(DEV) if rotate else None, sin.to(DEV) if rotate else None, Kwin,
+                           first, pooled, n_kv=w.n_kv if capacity else None)
+    torch.cuda.synchronize()
+    got = Kwin[:, :, :w.n_kv].cpu()
+    assert torch.equal(got[:, :, :first], K[:, :, :first])                 # the cached part is untouched
+    if w.dtype == "bf16":
+        assert float((got == window_ref).float().mean()) > 0.999           # rare one-unit differences of the rotation
+        assert rel_l2(wl.to_f64(got), wl.to_f64(window_ref)) < 1e-3
+    else:
+        assert rel_l2(wl.to_f64(got), wl.to_f64(window_ref)) <= 1e-6
+    # pooled keys [B*H][d/4][T_n][4]: the touched blocks hold the means of the window, the others what they held
+    t_n, d = w.t_n, w.head_dim
+    pk = pooled.view(torch.float32)[: w.batch * w.heads * t_n * d].view(w.batch * w.heads, d // 4, t_n, 4)
+    pb = before.view(torch.float32)[: w.batch * w.heads * t_n * d].view(w.batch * w.heads, d // 4, t_n, 4)
+    pk = pk.permute(0, 2, 1, 3).reshape(w.batch * w.heads, t_n, d).cpu().double().numpy()
+    pb = pb.permute(0, 2, 1, 3).reshape(w.batch * w.heads, t_n, d).cpu().double().numpy()
+    b0 = first // w.block
+    assert np.array_equal(pk[:, :b0], pb[:, :b0])
+    for h, kk in enumerate(heads_of(window_ref)):
+        ref = orc.pool_blocks(kk, w.block)
+        diff = np.abs(pk[h, b0:] - ref[b0:])
+        # a one-unit difference of a rotated value (fewer than one in a thousand, above) moves the mean it enters
+        # by that unit over the block length; a mean gathers `block` values, so up to block/1000 of the means
+        assert diff.max() <= (1e-4 if w.dtype == "bf16" else 1e-6)
+        assert (diff <= 1e-6).mean() > 1.0 - w.block / 1000.0
+    # and the pooled keys are those of the stand-alone pooling of the buffer as it now stands, to fp32 summation order
+    again = torch.empty_like(pooled)
+    hf.hf_pool_keys(cfg, Kwin, again, n_kv=w.n_kv if capacity else None)
+    torch.cuda.synchronize()
+    pa = again.view(torch.float32)[: w.batch * w.heads * t_n * d]
+    torch.testing.assert_close(pooled.view(torch.float32)[: w.batch * w.heads * t_n * d], pa, rtol=0, atol=1e-6)
