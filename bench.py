@@ -50,8 +50,8 @@ def profile_value(workload: str, kind: str, key: str):
 def parse():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
-    p.add_argument("--steps", type=int, default=30)
-    p.add_argument("--warmup", type=int, default=6)
+    p.add_argument("--steps", type=int, default=300)
+    p.add_argument("--warmup", type=int, default=12)
     p.add_argument("--workload", default="step_832x480")
     p.add_argument("--layers", type=int, default=6, help="distinct layer tensor sets rotated through")
     p.add_argument("--keep-ratio", type=float, default=None)

@@ -114,14 +114,22 @@ __device__ __forceinline__ int* select_in_workgroup(char* smem, const bf16_t* Qh
 #pragma unroll
   for (int i = 0; i < BQ / G; ++i)
     v[i] = *reinterpret_cast<const bf16x8*>(Qh + (size_t)min(q0 + g + G * i, n_q - 1) * D + 8 * u16);
-  const float4* kt = reinterpret_cast<const float4*>(kbar_head) + (size_t)(wave * CW) * t_n;
+  // pooled keys through a buffer descriptor: one offset register per block, the feature group's offset is scalar
+  // (forty-eight 64-bit addresses would not fit next to the loads they feed)
+  const __amdgpu_buffer_rsrc_t krsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(kbar_head), 0, (D / 4) * t_n * 16, 0x00020000);
+  auto kload = [&](int j, int c) {
+    typedef unsigned int u32v4 __attribute__((vector_size(16)));
+    const u32v4 r = __builtin_amdgcn_raw_buffer_load_b128(krsrc, j * 16, (wave * CW + c) * t_n * 16, 0);
+    return make_float4(__uint_as_float(r[0]), __uint_as_float(r[1]), __uint_as_float(r[2]), __uint_as_float(r[3]));
+  };
   constexpr int U = 48 / CW;   // KV blocks per lane and pass (3 or 6): 48 loads of 16 bytes in flight
   float4 kv[U][CW];
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     const int j = min(lane + 64 * u, t_n - 1);   // clamped: a valid address, the result is dropped
 #pragma unroll
-    for (int c = 0; c < CW; ++c) kv[u][c] = kt[(size_t)c * t_n + j];
+    for (int c = 0; c < CW; ++c) kv[u][c] = kload(j, c);
   }
   {
     // column sums of the thread's rows, two rows per instruction: (x_r, x_r') . (1, 1) + acc in fp32
@@ -161,22 +169,27 @@ __device__ __forceinline__ int* select_in_workgroup(char* smem, const bf16_t* Qh
       for (int u = 0; u < U; ++u) {
         const int j = min(j0 + 64 * u, t_n - 1);
 #pragma unroll
-        for (int c = 0; c < CW; ++c) kv[u][c] = kt[(size_t)c * t_n + j];
+        for (int c = 0; c < CW; ++c) kv[u][c] = kload(j, c);
+      }
+    }
+    // (feature groups outermost: the pooled query passes through a few registers instead of staying in sixty-four)
+    float a0[U], a1[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) a0[u] = a1[u] = 0.0f;
+#pragma unroll
+    for (int c = 0; c < CW; c += 2) {
+      const float4 qa = q4[c], qb4 = q4[c + 1];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        a0[u] = fmaf(qa.x, kv[u][c].x, a0[u]); a0[u] = fmaf(qa.y, kv[u][c].y, a0[u]);
+        a0[u] = fmaf(qa.z, kv[u][c].z, a0[u]); a0[u] = fmaf(qa.w, kv[u][c].w, a0[u]);
+        a1[u] = fmaf(qb4.x, kv[u][c + 1].x, a1[u]); a1[u] = fmaf(qb4.y, kv[u][c + 1].y, a1[u]);
+        a1[u] = fmaf(qb4.z, kv[u][c + 1].z, a1[u]); a1[u] = fmaf(qb4.w, kv[u][c + 1].w, a1[u]);
       }
     }
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      float a0 = 0.0f, a1 = 0.0f;
-#pragma unroll
-      for (int c = 0; c < CW; c += 2) {
-        const float4 qa = q4[c], qb4 = q4[c + 1];
-        a0 = fmaf(qa.x, kv[u][c].x, a0); a0 = fmaf(qa.y, kv[u][c].y, a0);
-        a0 = fmaf(qa.z, kv[u][c].z, a0); a0 = fmaf(qa.w, kv[u][c].w, a0);
-        a1 = fmaf(qb4.x, kv[u][c + 1].x, a1); a1 = fmaf(qb4.y, kv[u][c + 1].y, a1);
-        a1 = fmaf(qb4.z, kv[u][c + 1].z, a1); a1 = fmaf(qb4.w, kv[u][c + 1].w, a1);
-      }
-      if (j0 + 64 * u < t_n) part[wave * t_pad + j0 + 64 * u] = a0 + a1;
-    }
+    for (int u = 0; u < U; ++u)
+      if (j0 + 64 * u < t_n) part[wave * t_pad + j0 + 64 * u] = a0[u] + a1[u];
   }
   __syncthreads();
   for (int j = tid; j < t_n; j += NT) {
