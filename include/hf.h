@@ -232,10 +232,12 @@ typedef struct hf_ring {
   int32_t n_filled;    /* slots that hold a chunk (the open one included); starts at 0 */
   int32_t next_slot;   /* slot the next chunk goes to; starts at 0 */
   int32_t cur_slot;    /* slot of the open chunk; starts at -1 */
+  int32_t absorbed_ahead;  /* set by hf_ring_last_step: the chunk in slot next_slot is in the state already; starts at 0 */
 } hf_ring;
 
 /* Start of a chunk: if every slot is taken, the chunk in slot next_slot (the oldest) is absorbed into the state
- * (Eq. 2; rope_*_ev: tables for its n_chunk tokens or both NULL; workspace as for hf_absorb_evicted) and
+ * (Eq. 2; rope_*_ev: tables for its n_chunk tokens or both NULL; workspace as for hf_absorb_evicted; nothing is
+ * absorbed if hf_ring_last_step has done so already, ring->absorbed_ahead, which is cleared) and
  * *n_evicted_out = n_chunk, else 0.  *first_out = token offset of the slot: the caller writes the chunk's K, V
  * there before each hf_ring_step (and the clean ones after the last).  Both outputs HOST, may be NULL. */
 HF_API int hf_ring_open_chunk(const hf_config* cfg, hf_ring* ring, void* K_cache, void* V_cache, void* state,
@@ -252,6 +254,28 @@ HF_API int hf_ring_step(const hf_config* cfg, const hf_ring* ring, const void* Q
                  const void* K_cache, const void* V_cache, int32_t step_in_chunk, int32_t* block_idx,
                  const void* state_or_null, const float* rope_cos_q, const float* rope_sin_q,
                  void* O, void* workspace, size_t workspace_bytes, void* stream);
+
+/* hf_ring_step for the LAST denoising step of the open chunk, together with the eviction that the next
+ * hf_ring_open_chunk would carry out: if every slot is taken, the oldest chunk (slot next_slot, whose keys and values
+ * are final) is absorbed into state_out = state + its contribution (Eq. 2) while this step still attends with
+ * `state`; ring->absorbed_ahead is set, *absorbed_out = 1, and the next hf_ring_open_chunk, which is to be given
+ * state_out as the state from then on, absorbs nothing.  While a slot is still free the next chunk evicts nothing:
+ * state_out is not written and *absorbed_out = 0 (the caller keeps `state`).
+ * Where hf_step_fwd applies (bf16, head_dim 128, block_q 64 or 128, ReLU, no rotation of the absorbed keys, default
+ * flags) the absorb runs in workgroups of the attention launch; elsewhere the state is copied and the chunk absorbed
+ * by launches of their own behind the step.  state_or_null NULL with a full ring: the chunk starts a state from zero.
+ *   state_out        fp32 state buffer, must not overlap `state` or any other argument
+ *   rope_*_ev        tables for the n_chunk absorbed tokens or both NULL (as hf_ring_open_chunk)
+ *   step_workspace   >= max(hf_step_workspace_bytes(cfg, n_chunk, n_chunk), hf_absorb_workspace_bytes(cfg, n_chunk))
+ *                    bytes, 256-byte aligned
+ *   absorbed_out     HOST, may be NULL
+ * Every other argument as hf_ring_step. */
+HF_API int hf_ring_last_step(const hf_config* cfg, hf_ring* ring, const void* Q, const void* Q_hist,
+                 const void* K_cache, const void* V_cache, int32_t step_in_chunk, int32_t* block_idx,
+                 const void* state_or_null, const float* rope_cos_q, const float* rope_sin_q,
+                 void* O, void* workspace, size_t workspace_bytes,
+                 void* state_out, const float* rope_cos_ev, const float* rope_sin_ev,
+                 void* step_workspace, size_t step_workspace_bytes, int32_t* absorbed_out, void* stream);
 
 /* k of "sparse Top K" for a window of n_kv tokens (see keep_k / keep_ratio).  Host-only. */
 HF_API int hf_select_k(const hf_config* cfg, int32_t n_kv, int32_t* k_out);

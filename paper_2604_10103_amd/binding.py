@@ -52,7 +52,7 @@ class hf_window(ctypes.Structure):
 
 class hf_ring(ctypes.Structure):
     _fields_ = [("n_sink", ctypes.c_int32), ("n_chunk", ctypes.c_int32), ("n_filled", ctypes.c_int32),
-                ("next_slot", ctypes.c_int32), ("cur_slot", ctypes.c_int32)]
+                ("next_slot", ctypes.c_int32), ("cur_slot", ctypes.c_int32), ("absorbed_ahead", ctypes.c_int32)]
 
 
 def make_config(batch, heads, head_dim, dtype, block_q, block_kv, keep_ratio=1.0, keep_k=0,
@@ -108,6 +108,8 @@ def load():
     lib.hf_pooled_keys_bytes.argtypes = [CP, I, ctypes.POINTER(ctypes.c_size_t)]
     lib.hf_pool_keys.argtypes = [CP, P, I, I, P, P]
     lib.hf_select_attn_fwd.argtypes = [CP, P, P, I, P, P, I, P, P, P, P, P, P, P, P, P]
+    lib.hf_ring_last_step.argtypes = [CP, ctypes.POINTER(hf_ring), P, P, P, P, I, P, P, P, P, P, P, SZ, P, P, P, P, SZ,
+                                      ctypes.POINTER(ctypes.c_int32), P]
     lib.hf_step_workspace_bytes.argtypes = [CP, I, I, ctypes.POINTER(SZ)]
     lib.hf_step_fwd.argtypes = [CP, P, P, I, P, P, I, P, P, P, P, P, P, P, P, P, P, I, I, P, P, P, SZ, P]
     lib.hf_hybrid_attn_fwd.argtypes = [CP, P, I, P, P, I, P, I, P, P, P, P, P, SZ, P]
@@ -129,7 +131,7 @@ def load():
                  "hf_stream_step", "hf_bwd_workspace_bytes", "hf_hybrid_attn_bwd", "hf_state_planes_bytes",
                  "hf_state_planes", "hf_absorb_evicted_planes", "hf_hybrid_attn_fwd_planes", "hf_probe_mfma_bf16",
                  "hf_ring_open_chunk", "hf_ring_step", "hf_pooled_keys_bytes", "hf_pool_keys", "hf_select_attn_fwd",
-                 "hf_step_workspace_bytes", "hf_step_fwd", "hf_rope_append_keys"):
+                 "hf_step_workspace_bytes", "hf_step_fwd", "hf_rope_append_keys", "hf_ring_last_step"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -573,7 +575,7 @@ def hf_stream_step(cfg: hf_config, win: hf_window, Q, K_win, V_win, step_in_chun
 
 
 def make_ring(n_sink: int, n_chunk: int) -> hf_ring:
-    return hf_ring(int(n_sink), int(n_chunk), 0, 0, -1)
+    return hf_ring(int(n_sink), int(n_chunk), 0, 0, -1, 0)
 
 
 def hf_ring_open_chunk(cfg: hf_config, ring: hf_ring, K_cache, V_cache, state, rope_cos_ev=None, rope_sin_ev=None,
@@ -592,6 +594,35 @@ def hf_ring_open_chunk(cfg: hf_config, ring: hf_ring, K_cache, V_cache, state, r
         _dev(workspace, "workspace", torch.uint8), 0 if workspace is None else workspace.numel(),
         ctypes.byref(first), ctypes.byref(n_ev), _stream()))
     return first.value, n_ev.value
+
+
+def hf_ring_last_step(cfg: hf_config, ring: hf_ring, Q, K_cache, V_cache, step_in_chunk: int, block_idx, state, O, workspace,
+                      state_out, step_workspace, rope_cos_q=None, rope_sin_q=None, Q_hist=None, rope_cos_ev=None,
+                      rope_sin_ev=None) -> bool:
+    """hf_ring_step for the chunk's last denoising step; if the next hf_ring_open_chunk would evict a chunk, that chunk
+    is absorbed now into state_out (= state + its contribution) and True is returned: state_out is the state from the
+    next chunk on."""
+    B, H, d = cfg.batch, cfg.heads, cfg.head_dim
+    cap, n_q = cfg.kv_capacity, ring.n_chunk
+    n_kv = ring.n_sink + ring.n_filled * ring.n_chunk
+    t_m = _cdiv(n_q, cfg.block_q)
+    k = hf_select_k(cfg, n_kv)
+    tab = (n_q, d // 2)
+    qs = (B, H, n_q, d)
+    ns = hf_state_bytes(cfg) // 4
+    done = ctypes.c_int32(0)
+    _check(load().hf_ring_last_step(
+        ctypes.byref(cfg), ctypes.byref(ring), _dev(Q, "Q", _tdtype(cfg), qs), _dev(Q_hist, "Q_hist", _tdtype(cfg), qs),
+        _dev(K_cache, "K_cache", _tdtype(cfg), (B, H, cap, d)), _dev(V_cache, "V_cache", _tdtype(cfg), (B, H, cap, d)),
+        step_in_chunk, _dev(block_idx, "block_idx", torch.int32, (B, H, t_m, k)),
+        None if state is None else _dev(state, "state", torch.float32, (ns,)),
+        _dev(rope_cos_q, "rope_cos_q", torch.float32, tab), _dev(rope_sin_q, "rope_sin_q", torch.float32, tab),
+        _dev(O, "O", _tdtype(cfg), qs), _dev(workspace, "workspace", torch.uint8), workspace.numel(),
+        _dev(state_out, "state_out", torch.float32, (ns,)),
+        _dev(rope_cos_ev, "rope_cos_ev", torch.float32, tab), _dev(rope_sin_ev, "rope_sin_ev", torch.float32, tab),
+        _dev(step_workspace, "step_workspace", torch.uint8), 0 if step_workspace is None else step_workspace.numel(),
+        ctypes.byref(done), _stream()))
+    return bool(done.value)
 
 
 def hf_ring_step(cfg: hf_config, ring: hf_ring, Q, K_cache, V_cache, step_in_chunk: int, block_idx, state, O, workspace,

@@ -844,7 +844,8 @@ static int check_ring(const hf_config* cfg, const hf_ring* r) {
   }
   const int slots = (cfg->kv_capacity - r->n_sink) / r->n_chunk;
   if (r->n_filled < 0 || r->n_filled > slots || r->next_slot < 0 || r->next_slot >= slots || r->cur_slot < -1 ||
-      r->cur_slot >= slots || (r->n_filled < slots && r->next_slot != r->n_filled)) {
+      r->cur_slot >= slots || (r->n_filled < slots && r->next_slot != r->n_filled) ||
+      (r->absorbed_ahead != 0 && r->absorbed_ahead != 1)) {
     set_error("ring bookkeeping out of range: n_filled=%d next_slot=%d cur_slot=%d of %d slots", r->n_filled, r->next_slot,
               r->cur_slot, slots);
     return HF_ERR_SHAPE;
@@ -862,7 +863,11 @@ int hf_ring_open_chunk(const hf_config* cfg, hf_ring* ring, void* K_cache, void*
   const int slots = (cfg->kv_capacity - ring->n_sink) / ring->n_chunk;
   const int32_t first = ring->n_sink + ring->next_slot * ring->n_chunk;
   int32_t evicted = 0;
-  if (ring->n_filled == slots) {
+  if (ring->n_filled == slots && ring->absorbed_ahead) {
+    // the last step of the chunk before has absorbed the slot's chunk already (hf_ring_last_step)
+    ring->absorbed_ahead = 0;
+    evicted = ring->n_chunk;
+  } else if (ring->n_filled == slots) {
     // "KV cache is full": the chunk in the slot about to be reused is the oldest; it goes into the linear state
     // where it lies, and nothing else in the cache moves
     HF_TRY(check_ptr(state, "state", true));
@@ -931,6 +936,100 @@ int hf_ring_step(const hf_config* cfg, const hf_ring* ring, const void* Q, const
   }
   return hf_hybrid_attn_fwd_split(cfg, Q, Q_hist, n_q, K_cache, V_cache, n_kv, block_idx, k, state_or_null, rope_cos_q,
                                   rope_sin_q, O, workspace, workspace_bytes, stream);
+}
+
+int hf_ring_last_step(const hf_config* cfg, hf_ring* ring, const void* Q, const void* Q_hist, const void* K_cache,
+                      const void* V_cache, int32_t step_in_chunk, int32_t* block_idx, const void* state_or_null,
+                      const float* rope_cos_q, const float* rope_sin_q, void* O, void* workspace, size_t workspace_bytes,
+                      void* state_out, const float* rope_cos_ev, const float* rope_sin_ev, void* step_workspace,
+                      size_t step_workspace_bytes, int32_t* absorbed_out, void* stream) {
+  HF_TRY(check_cfg(cfg));
+  HF_TRY(check_ring(cfg, ring));
+  if (ring->cur_slot < 0) { set_error("no chunk is open (hf_ring_open_chunk first)"); return HF_ERR_SHAPE; }
+  if (absorbed_out) *absorbed_out = 0;
+  const int slots = (cfg->kv_capacity - ring->n_sink) / ring->n_chunk;
+  if (ring->n_filled < slots || ring->absorbed_ahead) {
+    // a slot is still free (or the chunk is in the state already): the next chunk evicts nothing more
+    return hf_ring_step(cfg, ring, Q, Q_hist, K_cache, V_cache, step_in_chunk, block_idx, state_or_null, rope_cos_q,
+                        rope_sin_q, O, workspace, workspace_bytes, stream);
+  }
+  HF_TRY(check_ptr(state_out, "state_out", true));
+  HF_TRY(check_ptr(K_cache, "K_cache", true));
+  HF_TRY(check_ptr(V_cache, "V_cache", true));
+  if ((rope_cos_ev == nullptr) != (rope_sin_ev == nullptr)) {
+    set_error("rope_cos_ev and rope_sin_ev must both be given or both be NULL");
+    return HF_ERR_NULL;
+  }
+  if (step_workspace && (reinterpret_cast<uintptr_t>(step_workspace) & 255u)) {
+    set_error("step_workspace is not 256-byte aligned");
+    return HF_ERR_ALIGN;
+  }
+  const int32_t n_q = ring->n_chunk, n_kv = ring->n_sink + ring->n_filled * ring->n_chunk;
+  const size_t d = cfg->head_dim, bh = (size_t)cfg->batch * cfg->heads;
+  const size_t state_bytes = bh * (d * d + d) * sizeof(float);
+  {
+    const char* a = static_cast<const char*>(state_out);
+    const char* b = static_cast<const char*>(state_or_null);
+    if (b && a < b + state_bytes && b < a + state_bytes) { set_error("state_out overlaps state"); return HF_ERR_SHAPE; }
+  }
+  // the chunk that the next hf_ring_open_chunk evicts: slot next_slot, where it lies
+  const size_t skip = ((size_t)ring->n_sink + (size_t)ring->next_slot * ring->n_chunk) * d * esize(cfg);
+  const char* K_ev = static_cast<const char*>(K_cache) + skip;
+  const char* V_ev = static_cast<const char*>(V_cache) + skip;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int t_n = cdiv(n_kv, cfg->block_kv);
+  const bool fused = attn_mfma_fused_supported(*cfg) && !(cfg->flags & HF_FLAG_READOUT_KERNEL) && t_n <= kMaxFusedSelectBlocks &&
+                     cfg->phi == HF_PHI_RELU && !rope_cos_ev;
+  if (fused) {
+    // as step_one_launch (pool what changed, planes of the frozen state on the chunk's first step), then the
+    // launch that selects, attends, adds the history term and absorbs
+    int k = 0;
+    HF_TRY(check_select_args(cfg, Q, n_q, K_cache, n_kv, 0, block_idx, nullptr, &k));
+    const WorkspaceLayout w = workspace_layout(cfg, n_q, n_kv);
+    if (!workspace || workspace_bytes < w.total) {
+      set_error("workspace of %zu bytes needed, %zu given", w.total, workspace ? workspace_bytes : (size_t)0);
+      return HF_ERR_WORKSPACE;
+    }
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) { set_error("workspace is not 256-byte aligned"); return HF_ERR_ALIGN; }
+    char* ws = static_cast<char*>(workspace);
+    float* kbar = reinterpret_cast<float*>(ws + w.kbar);
+    const int first = ring->n_sink + ring->cur_slot * ring->n_chunk;
+    int kv_first = 0, kv_end = t_n;
+    if (step_in_chunk > 0) {
+      kv_first = first / cfg->block_kv;
+      kv_end = cdiv(first + ring->n_chunk, cfg->block_kv);
+      if (kv_end > t_n) kv_end = t_n;
+    }
+    // (argument checks of the fused call first: nothing is launched if it is going to refuse)
+    const size_t need = step_absorb_workspace_bytes(*cfg, n_q, ring->n_chunk);
+    if (!step_workspace || step_workspace_bytes < need) {
+      set_error("step_workspace of %zu bytes needed, %zu given", need, step_workspace ? step_workspace_bytes : (size_t)0);
+      return HF_ERR_WORKSPACE;
+    }
+    HF_TRY(launch_pool_both(*cfg, nullptr, 0, 0, K_cache, n_kv, t_n, kv_first, kv_end, nullptr, kbar, s));
+    if (state_or_null && step_in_chunk == 0)
+      HF_TRY(launch_state_planes(*cfg, static_cast<const float*>(state_or_null), ws + w.planes, s));
+    HF_TRY(select_attn_impl(cfg, Q, Q_hist, n_q, K_cache, V_cache, n_kv, kbar, state_or_null,
+                            state_or_null ? ws + w.planes : nullptr, rope_cos_q, rope_sin_q, O, block_idx, nullptr, K_ev, V_ev,
+                            ring->n_chunk, cfg->kv_capacity, state_out, nullptr, step_workspace, step_workspace_bytes, stream));
+  } else {
+    HF_TRY(hf_ring_step(cfg, ring, Q, Q_hist, K_cache, V_cache, step_in_chunk, block_idx, state_or_null, rope_cos_q,
+                        rope_sin_q, O, workspace, workspace_bytes, stream));
+    // the state is copied and the chunk absorbed into the copy, behind the step
+    if (state_or_null) {
+      if (hipMemcpyAsync(state_out, state_or_null, state_bytes, hipMemcpyDeviceToDevice, s) != hipSuccess) {
+        set_error("copy of the state: %s", hipGetErrorString(hipGetLastError()));
+        return HF_ERR_HIP;
+      }
+    } else {
+      HF_TRY(launch_fill_zero(static_cast<float*>(state_out), bh * (d * d + d), s));
+    }
+    HF_TRY(launch_absorb(*cfg, static_cast<float*>(state_out), K_ev, V_ev, ring->n_chunk, cfg->kv_capacity, rope_cos_ev,
+                         rope_sin_ev, step_workspace, step_workspace ? step_workspace_bytes : 0, s));
+  }
+  ring->absorbed_ahead = 1;
+  if (absorbed_out) *absorbed_out = 1;
+  return HF_OK;
 }
 
 int hf_bwd_workspace_bytes(const hf_config* cfg, int32_t n_q, int32_t n_kv, size_t* bytes_out) {

@@ -343,3 +343,17 @@ def test_rope_append_keys_rejects_bad_arguments(lib):
     assert call(n_new=0) == -2
     assert call(pk=ctypes.c_void_p(0x40000010)) == -4
     assert call(K_new=ctypes.c_void_p(0x10000100)) == -2     # overlaps the window buffer
+
+
+def test_ring_struct_layout_and_last_step_arguments(lib):
+    assert ctypes.sizeof(hf.hf_ring) == 6 * 4 and hf.hf_ring.absorbed_ahead.offset == 20
+    cfg = hf.make_config(1, 2, 128, "bf16", 64, 64, 0.25, kv_capacity=1400)
+    fake = ctypes.c_void_p(0x100000)
+    ring = hf.make_ring(200, 400)
+    args = lambda r, so=ctypes.c_void_p(0x900000): (ctypes.byref(cfg), ctypes.byref(r), fake, None, fake, fake, 2, fake, fake,
+                                                    None, None, fake, fake, 1 << 30, so, None, None, fake, 1 << 30, None, None)
+    assert lib.hf_ring_last_step(*args(ring)) == -2                 # no chunk is open
+    full = hf.hf_ring(200, 400, 3, 0, 2, 0)
+    assert lib.hf_ring_last_step(*args(full, so=None)) == -1        # a full ring needs somewhere to put the new state
+    assert lib.hf_ring_last_step(*args(full, so=fake)) == -2        # ... other than the state it reads
+    assert lib.hf_ring_last_step(*args(hf.hf_ring(200, 400, 3, 0, 2, 7))) == -2   # bookkeeping out of range

@@ -136,13 +136,19 @@ def test_stream_with_sink_frames_matches_the_oracle_loop(name, sink_frames, rope
     assert rel_l2(zg, np.stack([s[1] for s in states])) <= 1e-5
 
 
-@pytest.mark.parametrize("name,sink_frames,rope", [("small_bf16", 1, False), ("small_bf16", 0, True),
-                                                   ("tiny_f32", 2, False), ("small_b128", 1, True)])
-def test_ring_cache_evicts_without_moving_a_token_and_matches_the_oracle_loop(name, sink_frames, rope):
+@pytest.mark.parametrize("name,sink_frames,rope,ahead", [("small_bf16", 1, False, False), ("small_bf16", 0, True, False),
+                                                         ("tiny_f32", 2, False, False), ("small_b128", 1, True, False),
+                                                         ("small_bf16", 1, False, True), ("small_b128", 0, False, True),
+                                                         ("small_bf16", 0, True, True), ("tiny_f32", 1, False, True)])
+def test_ring_cache_evicts_without_moving_a_token_and_matches_the_oracle_loop(name, sink_frames, rope, ahead):
     """The cache as a ring of chunk slots: opening a chunk absorbs the oldest chunk where it lies and changes no
     other byte of the cache (nothing is copied).  The oracle keeps the cache as a list of chunks (pop(0) / append);
     the window it is asked about is that list laid out in the ring's storage order, which is what the library
-    defines the blocks of Eq. 4 on (softmax attention itself does not depend on the order of its keys)."""
+    defines the blocks of Eq. 4 on (softmax attention itself does not depend on the order of its keys).
+    ahead: the last denoising step of every chunk is hf_ring_last_step, which absorbs the chunk that the next
+    hf_ring_open_chunk would evict into a second state buffer while the step still attends with the old state (in
+    workgroups of the attention launch where that applies, by launches of their own for fp32 or rotated keys); the
+    oracle's loop keeps the literal order, and every output and the final state must still agree."""
     w = wl.get(name)
     H, d, tpf = w.heads, w.head_dim, w.tokens_per_frame
     n_chunk, n_sink, slots = w.n_q, sink_frames * tpf, 3
@@ -153,10 +159,13 @@ def test_ring_cache_evicts_without_moving_a_token_and_matches_the_oracle_loop(na
     Vc = torch.zeros_like(Kc)
     st = torch.empty(hf.hf_state_bytes(cfg) // 4, dtype=torch.float32, device=DEV)
     hf.hf_state_init(cfg, st)
+    st_other = torch.full_like(st, float("nan"))
     aws_n = hf.hf_absorb_workspace_bytes(cfg, n_chunk)
     aws = torch.empty(aws_n, dtype=torch.uint8, device=DEV) if aws_n else None
+    sws = torch.empty(max(hf.hf_step_workspace_bytes(cfg, n_chunk, n_chunk), aws_n, 256), dtype=torch.uint8, device=DEV)
     ws = torch.empty(hf.hf_workspace_bytes(cfg, n_chunk, cap), dtype=torch.uint8, device=DEV)
     O = torch.empty((w.batch, H, n_chunk, d), dtype=w.torch_dtype, device=DEV)
+    done_ahead = False
 
     sinkK = [np.zeros((0, d)) for _ in range(H)]
     sinkV = [np.zeros((0, d)) for _ in range(H)]
@@ -174,10 +183,13 @@ def test_ring_cache_evicts_without_moving_a_token_and_matches_the_oracle_loop(na
         before_K, before_V = Kc.clone(), Vc.clone()
         full = len(chunks) == slots
         tab_ev = wl.rope_tables(n_chunk, d, first_position=3.0 + c) if (rope and full) else (None, None)
+        st_before = st.clone()
         first, n_ev = hf.hf_ring_open_chunk(cfg, ring, Kc, Vc, st, *(None if t is None else t.to(DEV) for t in tab_ev),
                                             workspace=aws)
         torch.cuda.synchronize()
         assert first == n_sink + (c % slots) * n_chunk and n_ev == (n_chunk if full else 0)
+        if done_ahead:                # the chunk went into the state during the last step before: nothing was added now
+            assert torch.equal(st, st_before) and ring.absorbed_ahead == 0
         # zero bytes copied: the cache is bit for bit what it was (the new chunk's slot still holds the old chunk)
         assert torch.equal(Kc, before_K) and torch.equal(Vc, before_V)
         if full:                      # pop(0): the oldest chunk goes into the linear state
@@ -197,8 +209,20 @@ def test_ring_cache_evicts_without_moving_a_token_and_matches_the_oracle_loop(na
             Q = wl.randn((w.batch, H, n_chunk, d), 89_000 + 10 * c + step, w.scale, w.torch_dtype)
             Kc[:, :, first:first + n_chunk] = Kn.to(DEV)
             Vc[:, :, first:first + n_chunk] = Vn.to(DEV)
-            hf.hf_ring_step(cfg, ring, Q.to(DEV), Kc, Vc, step, idx, st, O, ws,
-                            *(None if t is None else t.to(DEV) for t in tab_q))
+            if ahead and step == 2:
+                # the chunk evicted next is absorbed now, with the tables the oracle's loop will use when it pops it
+                will_evict = len(chunks) + 1 > slots - 1 and len(chunks) == slots - 1
+                tab_nx = wl.rope_tables(n_chunk, d, first_position=3.0 + c + 1) if (rope and will_evict) else (None, None)
+                st_old = st.clone()
+                done_ahead = hf.hf_ring_last_step(cfg, ring, Q.to(DEV), Kc, Vc, step, idx, st, O, ws, st_other, sws,
+                                                  *(None if t is None else t.to(DEV) for t in tab_q),
+                                                  rope_cos_ev=None if tab_nx[0] is None else tab_nx[0].to(DEV),
+                                                  rope_sin_ev=None if tab_nx[1] is None else tab_nx[1].to(DEV))
+                torch.cuda.synchronize()
+                assert done_ahead == will_evict and torch.equal(st, st_old)      # this step read the old state
+            else:
+                hf.hf_ring_step(cfg, ring, Q.to(DEV), Kc, Vc, step, idx, st, O, ws,
+                                *(None if t is None else t.to(DEV) for t in tab_q))
             torch.cuda.synchronize()
             Og, idxc = wl.to_f64(O), idx.cpu().numpy()
             # the oracle's list, laid out in storage order: slot s holds the newest chunk with number = s mod slots
@@ -218,7 +242,16 @@ def test_ring_cache_evicts_without_moving_a_token_and_matches_the_oracle_loop(na
                 assert rel_l2(Og[0, h], ref) <= rl, (c, step, h, rel_l2(Og[0, h], ref))
                 assert max_abs(Og[0, h], ref) <= ma
         chunks.append(cur)
+        if done_ahead:                # the second buffer is the state from the next chunk on
+            st, st_other = st_other, st
     assert evictions == 8 - slots
+    if done_ahead:                    # the chunk absorbed ahead of an open that this loop no longer performs
+        _, ek, ev = chunks[0]
+        tab_nx = wl.rope_tables(n_chunk, d, first_position=3.0 + 8) if rope else (None, None)
+        for h in range(H):
+            states[h] = orc.state_absorb(*states[h], ek[h], ev[h], orc.PHI_RELU,
+                                         None if tab_nx[0] is None else wl.to_f64(tab_nx[0]),
+                                         None if tab_nx[1] is None else wl.to_f64(tab_nx[1]))
     Lg, zg = split_state(st, H, d)
     assert rel_l2(Lg, np.stack([s[0] for s in states])) <= (5e-3 if (rope and w.dtype == "bf16") else 1e-5)
     assert rel_l2(zg, np.stack([s[1] for s in states])) <= 1e-5
