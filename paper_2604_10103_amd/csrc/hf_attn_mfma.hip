@@ -42,7 +42,6 @@ namespace {
 constexpr int D = 128;
 constexpr int TK = 32;      // keys per tile
 constexpr int KSTR = 256;   // bytes per key row of a K tile in LDS; 16-byte units XOR-swizzled by (row & 15)
-constexpr int PSTR = 272;   // bytes per row of a staged state plane (256 + 16)
 constexpr int OSTR = 272;   // bytes per query row of the staged output
 constexpr int KTILE = TK * KSTR;
 constexpr float kRescaleThreshold = 8.0f;  // log2 units: rescale only when a row max grew by more than 2^8
@@ -871,6 +870,17 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
     // ---- O += R(phi(q)) L / (z_scale phi(q).z + eps) (Eq. 3, 6): the query fragments already in
     // registers become the B operand of O_hist^T = Lt x R(phi(Q))^T; the A operand comes from the
     // L2-resident plane(s) through LDS.
+    // The plane of the state is on its way before anything else: it travels global -> LDS like the tiles (four
+    // "tiles" of 32 value features x 128 key features in the K layout, so that an A fragment is the K fragment's
+    // read), under the arithmetic of the denominator.
+    const uint64_t plane_base = reinterpret_cast<uint64_t>(hist.planes + (size_t)bh * 2 * D * D);
+    auto dma_plane = [&](int plane) {
+      const uint64_t b = plane_base + (uint64_t)plane * (D * D * 2);
+      const i32x4 p_desc = {(int)(uint32_t)b, (int)(uint32_t)(b >> 32), D * D * 2, 0x00020000};
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt) dma_tile(p_desc, sK_lds + dt * KTILE, 32 * dt, k_lane_off);
+    };
+    dma_plane(0);
     const float* zv = hist.zvec + (size_t)bh * D + 8 * h;
     float den = 0.0f;
     if (kFused == 1) {
@@ -931,25 +941,19 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma_kernel(
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[dt][r] *= den_eps;
-    constexpr int PCH = (D * D * 2 / 16) / NT;  // 16-byte chunks of one plane per thread
-    static_assert(D * PSTR <= 5 * KTILE, "a state plane must fit in the tiles' space");
-    const u32x4* gp = reinterpret_cast<const u32x4*>(hist.planes + (size_t)bh * 2 * D * D);
+    static_assert(D * D * 2 <= 4 * KTILE, "a state plane must fit in the tiles' space");
     for (int plane = 0; plane < hist.n_planes; ++plane) {  // each plane goes through LDS once per workgroup
-      u32x4 preg[PCH];
-#pragma unroll
-      for (int i = 0; i < PCH; ++i) preg[i] = gp[plane * (D * D * 2 / 16) + tid + NT * i];
-      if (plane) __syncthreads();  // everybody is done with the previous plane
-#pragma unroll
-      for (int i = 0; i < PCH; ++i) {
-        const int c = tid + NT * i;
-        *reinterpret_cast<u32x4*>(smem + (c >> 4) * PSTR + (c & 15) * 16) = preg[i];
+      if (plane) {
+        __syncthreads();  // everybody is done with the previous plane
+        dma_plane(plane);
       }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __syncthreads();
 #pragma unroll
       for (int s = 0; s < 8; ++s)
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(smem + (32 * dt + l32) * PSTR + 16 * h + 32 * s);
+          const bf16x8 a = *reinterpret_cast<const bf16x8*>(sK + k_addr[s] + dt * KTILE);
           o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[s], o[dt], 0, 0, 0);
         }
     }
