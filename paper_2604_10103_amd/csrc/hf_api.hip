@@ -523,9 +523,12 @@ static int select_attn_impl(const hf_config* cfg, const void* Q, const void* Q_h
   }
   HF_TRY(check_ptr(Q, "Q", true));
   if (!Q_hist) Q_hist = Q;
+  HF_TRY(check_ptr(Q_hist, "Q_hist", true));
   HF_TRY(check_ptr(K_win, "K_win", true));
   HF_TRY(check_ptr(V_win, "V_win", true));
   HF_TRY(check_ptr(pooled_K, "pooled_K", true));
+  HF_TRY(check_ptr(rope_cos_q, "rope_cos_q", false));
+  HF_TRY(check_ptr(rope_sin_q, "rope_sin_q", false));
   HF_TRY(check_ptr(O, "O", true));
   HF_TRY(check_ptr(block_idx_out, "block_idx_out", true));
   HF_TRY(check_ptr(scores_or_null, "scores", false));

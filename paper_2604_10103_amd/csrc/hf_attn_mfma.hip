@@ -24,6 +24,10 @@
 // tile, placed behind the S^T products,
 // whose K fragments were read into registers during the previous tile's softmax: see tile_step.
 //
+// Two things ride in the same launch where the caller asks for them (the kSel instances): every workgroup selects its
+// own KV blocks first (Eq. 4 and the Top-K, select_in_workgroup), and workgroups of their own absorb another chunk's
+// tokens into a second state buffer (Eq. 2, absorb_role) in the slots that the attending workgroups leave free.
+//
 // What bounds this kernel at block_q 64: the matrix work and the vector work of the softmax do not
 // overlap on a SIMD of this chip; with no loads, no exponentials and no barrier the loop still takes
 // twice the time of its MFMAs.
