@@ -371,3 +371,70 @@ def test_step_832x480_state_and_output_twice():
     check_against_oracle(cfg, w, Q, K, V, O, idxc, None, k, states)
     ref = [orc.state_absorb(L, z, kk, vv) for (L, z), kk, vv in zip(states, heads_of(Ke), heads_of(Ve))]
     check_state(cfg, w, st_out, pl_out, ref)
+
+
+def test_streaming_200_chunks_through_the_two_launch_step():
+    """200 chunks at the 832x480 shape with the state carried by hf_step_fwd alone: every chunk's step attends with the
+    current state and absorbs the chunk that the next arrival evicts into the other of two state buffers, which then
+    swap.  The state is compared with the oracle's after every chunk (fp32 accumulation of exact bf16 products: far
+    below the bound and not growing with the stream); lists and outputs on sampled chunks."""
+    from parity import split_state
+    w = wl.get("step_832x480")
+    cfg = cfg_of(w)
+    n_chunk, n_chunks, pool_size = w.n_q, 200, 8
+    pool = [wl.make_evicted(w, 200 + i) for i in range(pool_size)]
+    pool_dev = [(k.to(DEV), v.to(DEV)) for k, v in pool]
+    pool64 = [([wl.to_f64(k[0, h]) for h in range(w.heads)], [wl.to_f64(v[0, h]) for h in range(w.heads)])
+              for k, v in pool]
+    win = [0, 1]                      # window = [older chunk | current chunk]
+    states = [orc.state_zero(w.head_dim) for _ in range(w.heads)]
+    st = [torch.empty(hf.hf_state_bytes(cfg) // 4, dtype=torch.float32, device=DEV) for _ in range(2)]
+    pl = [torch.empty(hf.hf_state_planes_bytes(cfg), dtype=torch.uint8, device=DEV) for _ in range(2)]
+    hf.hf_state_init(cfg, st[0])
+    hf.hf_state_planes(cfg, st[0], pl[0])
+    cur = 0
+    k = hf.hf_select_k(cfg, w.n_kv)
+    pooled = torch.empty(hf.hf_pooled_keys_bytes(cfg, w.n_kv), dtype=torch.uint8, device=DEV)
+    sws = torch.empty(hf.hf_step_workspace_bytes(cfg, n_chunk, n_chunk), dtype=torch.uint8, device=DEV)
+    idx = torch.empty((w.batch, w.heads, w.t_m, k), dtype=torch.int32, device=DEV)
+    O = torch.empty((w.batch, w.heads, n_chunk, w.head_dim), dtype=w.torch_dtype, device=DEV)
+    q_pool = [wl.randn(O.shape, 76_000 + i, w.scale, w.torch_dtype).to(DEV) for i in range(3)]
+    sampled = {1, 2, 50, 100, 200}
+    errs_L, errs_z = [], []
+    Kw = torch.cat([pool_dev[win[0]][0], pool_dev[win[1]][0]], dim=2).contiguous()
+    Vw = torch.cat([pool_dev[win[0]][1], pool_dev[win[1]][1]], dim=2).contiguous()
+    for c in range(1, n_chunks + 1):
+        Q = wl.randn(O.shape, 77_000 + c, w.scale, w.torch_dtype) if c in sampled else None
+        hf.hf_pool_keys(cfg, Kw, pooled)
+        # the older half of the window is what the next chunk's arrival evicts: absorbed beside this chunk's attention
+        Kev, Vev = pool_dev[win[0]]
+        hf.hf_step_fwd(cfg, q_pool[c % 3] if Q is None else Q.to(DEV), Kw, Vw, pooled, st[cur], pl[cur], O, idx, Kev, Vev,
+                       st[1 - cur], pl[1 - cur], sws)
+        torch.cuda.synchronize()
+        if Q is not None:
+            Kc = torch.cat([pool[win[0]][0], pool[win[1]][0]], dim=2)
+            Vc = torch.cat([pool[win[0]][1], pool[win[1]][1]], dim=2)
+            heads = [c % w.heads, (c + 5) % w.heads]
+            Og, idxc = wl.to_f64(O), idx.cpu().numpy()
+            for h in heads:
+                q, kk, v = wl.to_f64(Q[0, h]), wl.to_f64(Kc[0, h]), wl.to_f64(Vc[0, h])
+                check_block_idx(idxc[0, h], orc.block_scores(q, kk, w.block, w.block), k)
+                ref, *_ = orc.hybrid_attention(q, kk, v, states[h], w.block, w.block, k, eps=cfg.eps, block_idx=idxc[0, h])
+                assert rel_l2(Og[0, h], ref) <= BF16_REL_L2 and max_abs(Og[0, h], ref) <= BF16_MAX_ABS
+        k64, v64 = pool64[win[0]]
+        states = [orc.state_absorb(Ls, zs, k64[h], v64[h]) for h, (Ls, zs) in enumerate(states)]
+        cur = 1 - cur
+        win = [win[1], (win[1] + 1) % pool_size]
+        Kw[:, :, :n_chunk] = pool_dev[win[0]][0]
+        Vw[:, :, :n_chunk] = pool_dev[win[0]][1]
+        Kw[:, :, n_chunk:] = pool_dev[win[1]][0]
+        Vw[:, :, n_chunk:] = pool_dev[win[1]][1]
+        Lg, zg = split_state(st[cur], w.heads, w.head_dim)
+        errs_L.append(rel_l2(Lg, np.stack([s[0] for s in states])))
+        errs_z.append(rel_l2(zg, np.stack([s[1] for s in states])))
+    assert max(errs_L) <= 1e-5 and max(errs_z) <= 1e-5, (max(errs_L), max(errs_z))
+    assert errs_L[-1] <= 4 * max(errs_L[:20]) + 1e-7
+    ref_pl = torch.empty_like(pl[cur])
+    hf.hf_state_planes(cfg, st[cur], ref_pl)
+    torch.cuda.synchronize()
+    assert torch.equal(pl[cur], ref_pl)
