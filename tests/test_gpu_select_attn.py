@@ -438,3 +438,26 @@ def test_streaming_200_chunks_through_the_two_launch_step():
     hf.hf_state_planes(cfg, st[cur], ref_pl)
     torch.cuda.synchronize()
     assert torch.equal(pl[cur], ref_pl)
+
+
+def test_step_large_shape_head_subset():
+    """1280x720-like shape, three heads: four wavefronts per workgroup, the list read back from memory behind the first
+    64 tiles, and three frames (10 800 tokens per head) absorbed beside the attention."""
+    w = wl.get("large_1280x720")
+    heads = (0, 13, 39)
+    sub = dataclasses.replace(w, heads=len(heads))
+    cfg = cfg_of(sub)
+    Q, K, V = wl.make_qkv(w)
+    Q, K, V = (t[:, list(heads)].contiguous() for t in (Q, K, V))
+    Ke0, Ve0 = (t[:, list(heads)].contiguous() for t in wl.make_evicted(w, 0))
+    Ke1, Ve1 = (t[:, list(heads)].contiguous() for t in wl.make_evicted(w, 1))
+    st = torch.empty(hf.hf_state_bytes(cfg) // 4, dtype=torch.float32, device=DEV)
+    hf.hf_state_init(cfg, st)
+    planes = torch.empty(hf.hf_state_planes_bytes(cfg), dtype=torch.uint8, device=DEV)
+    hf.hf_absorb_evicted_planes(cfg, st, Ke0.to(DEV), Ve0.to(DEV), planes)
+    states = oracle_state([Ke0], [Ve0], w.head_dim)
+    O, idx, _, k, st_out, pl_out, _ = run_step(cfg, sub, Q, K, V, st, planes, Ke1, Ve1)
+    assert k == 43 and Ke1.shape[2] == 10800
+    check_against_oracle(cfg, sub, Q, K, V, O, idx, None, k, states)
+    ref = [orc.state_absorb(L, z, kk, vv) for (L, z), kk, vv in zip(states, heads_of(Ke1), heads_of(Ve1))]
+    check_state(cfg, sub, st_out, pl_out, ref)
