@@ -205,8 +205,8 @@ def run_extras(hf, wl, torch, np, dev):
 def main():
     a = parse()
     if a.gpus != 1:
-        print("bench.py measures one GPU only: this build has no multi-GPU path (heads shard "
-              "without exchange, see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py measures one GPU only: this build has no multi-GPU path (heads are independent in every "
+              "step and would shard without exchange); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch
