@@ -195,34 +195,44 @@ __device__ __forceinline__ int* select_in_workgroup(char* smem, const bf16_t* Qh
       if (j0 + 64 * u < t_n) part[wave * t_pad + j0 + 64 * u] = a0[u] + a1[u];
   }
   __syncthreads();
-  for (int j = tid; j < t_n; j += NT) {
-    float a = part[j];
-#pragma unroll
-    for (int w = 1; w < NW; ++w) a += part[w * t_pad + j];
-    sc[j] = a;
-    if (scores_row) scores_row[j] = a;
-  }
-  __syncthreads();
 
   if (t_n <= 256) {
-    // ---- Top-K by the k-th largest key, found bit by bit (32 steps of a few comparisons and population counts, every
-    // wavefront for itself on the whole row: lane l holds the blocks l, l + 64, ...).  Keys order like the scores;
-    // kept: every block above the k-th key, and of the blocks equal to it the lowest indices (the tie rule).
+    // ---- Top-K by the k-th largest key, found bit by bit (a few comparisons and population counts per step, every
+    // wavefront for itself on the whole row: lane l holds the blocks l, l + 64, ..., their scores summed from the
+    // wavefronts' parts in wavefront order).  Keys order like the scores; kept: every block above the k-th key, and
+    // of the blocks equal to it the lowest indices (the tie rule).
     uint32_t key[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const int j = lane + 64 * e;
-      const uint32_t b = __float_as_uint(sc[min(j, t_pad - 1)] + 0.0f);   // (-0 counts as +0)
+      const int j = lane + 64 * e, jc = min(j, t_n - 1);
+      float a = part[jc];
+#pragma unroll
+      for (int w = 1; w < NW; ++w) a += part[w * t_pad + jc];
+      if (scores_row && wave == 0 && j < t_n) scores_row[j] = a;
+      const uint32_t b = __float_as_uint(a + 0.0f);   // (-0 counts as +0)
       key[e] = j < t_n ? (b ^ ((b >> 31) ? 0xffffffffu : 0x80000000u)) : 0u;   // padding lies below every score
     }
+    // Two bits per step (the three candidates are counted side by side: the steps are a chain of latencies), and the
+    // search ends as soon as exactly k keys reach a candidate: they are the list, whatever the lower bits say.
     uint32_t kth = 0;
-    for (int bit = 31; bit >= 0; --bit) {
-      const uint32_t cand = kth | (1u << bit);
-      int cnt = 0;
+    bool cut = false;
+    for (int bit = 30; bit >= 0; bit -= 2) {
+      const uint32_t c1 = kth | (1u << bit), c2 = kth | (2u << bit), c3 = kth | (3u << bit);
+      int n1 = 0, n2 = 0, n3 = 0;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) cnt += __popcll(__ballot(key[e] >= cand));
-      if (cnt >= k) kth = cand;   // uniform
+      for (int e = 0; e < 4; ++e) {
+        n1 += __popcll(__ballot(key[e] >= c1));
+        n2 += __popcll(__ballot(key[e] >= c2));
+        n3 += __popcll(__ballot(key[e] >= c3));
+      }
+      int n;   // (all uniform)
+      if (n3 >= k) { kth = c3; n = n3; }
+      else if (n2 >= k) { kth = c2; n = n2; }
+      else if (n1 >= k) { kth = c1; n = n1; }
+      else continue;
+      if (n == k) { cut = true; break; }
     }
+    if (cut) --kth;   // kept: the keys above kth, i.e. the k that reach the candidate; none of them ties with the rest
     int above = 0;
 #pragma unroll
     for (int e = 0; e < 4; ++e) above += __popcll(__ballot(key[e] > kth));
@@ -244,6 +254,14 @@ __device__ __forceinline__ int* select_in_workgroup(char* smem, const bf16_t* Qh
     __syncthreads();
     return sel;
   }
+  for (int j = tid; j < t_n; j += NT) {
+    float a = part[j];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) a += part[w * t_pad + j];
+    sc[j] = a;
+    if (scores_row) scores_row[j] = a;
+  }
+  __syncthreads();
   // ---- rank and list (windows of more than 256 blocks), two blocks per thread and scan of the row (j and j + NT share every score they are
   // compared with).  First pass: strict comparison only (blocks with equal scores share a rank), exact unless
   // a tie straddles the k-th place, which shows as more than k blocks of rank < k; then the row is redone with the rule.
